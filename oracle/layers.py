@@ -1,0 +1,149 @@
+"""Layer definitions and their vector-Jacobian products, NumPy float64.
+
+Test infrastructure (see the package docstring).  These are the textbook
+definitions of the layers that the architectures named in the paper (Section 3:
+ResNet50; Section 4) are built from, written as their defining sums.  The paper
+only names the architectures; the layer conventions are the standard ones:
+
+  * activations are [B, H, W, C]; filters are [Cout, kh, kw, Cin];
+  * convolution is cross-correlation with zero padding;
+  * BatchNorm normalises with the biased batch variance over (B, H, W), eps 1e-5;
+  * ReLU'(0) = 0; max-pool routes the gradient to the first maximum in
+    row-major window order.
+"""
+import numpy as np
+
+BN_EPS = 1e-5
+
+
+def _out_size(n, k, stride, pad):
+    return (n + 2 * pad - k) // stride + 1
+
+
+# ---------------------------------------------------------------- convolution
+def conv2d_forward(x, w, bias, stride, pad):
+    """y[b,ho,wo,o] = bias[o] + sum_{r,s,c} x[b, ho*stride-pad+r, wo*stride-pad+s, c] * w[o,r,s,c]."""
+    B, H, W, Cin = x.shape
+    Cout, kh, kw, _ = w.shape
+    Ho, Wo = _out_size(H, kh, stride, pad), _out_size(W, kw, stride, pad)
+    xp = np.zeros((B, H + 2 * pad, W + 2 * pad, Cin))
+    xp[:, pad:pad + H, pad:pad + W, :] = x
+    y = np.zeros((B, Ho, Wo, Cout))
+    for r in range(kh):
+        for s in range(kw):
+            xs = xp[:, r:r + stride * (Ho - 1) + 1:stride, s:s + stride * (Wo - 1) + 1:stride, :]
+            y += xs.reshape(-1, Cin).dot(w[:, r, s, :].T).reshape(B, Ho, Wo, Cout)
+    if bias is not None:
+        y += bias
+    return y
+
+
+def conv2d_backward(x, w, dy, stride, pad, has_bias, need_dx=True):
+    """Return (dx, dw, dbias) of conv2d_forward for upstream gradient dy."""
+    B, H, W, Cin = x.shape
+    Cout, kh, kw, _ = w.shape
+    _, Ho, Wo, _ = dy.shape
+    xp = np.zeros((B, H + 2 * pad, W + 2 * pad, Cin))
+    xp[:, pad:pad + H, pad:pad + W, :] = x
+    dxp = np.zeros_like(xp)
+    dw = np.zeros_like(w)
+    dy2 = dy.reshape(-1, Cout)
+    for r in range(kh):
+        for s in range(kw):
+            sl = (slice(None), slice(r, r + stride * (Ho - 1) + 1, stride),
+                  slice(s, s + stride * (Wo - 1) + 1, stride), slice(None))
+            dw[:, r, s, :] = dy2.T.dot(xp[sl].reshape(-1, Cin))
+            if need_dx:
+                dxp[sl] += dy2.dot(w[:, r, s, :]).reshape(B, Ho, Wo, Cin)
+    dx = dxp[:, pad:pad + H, pad:pad + W, :].copy() if need_dx else None
+    db = dy2.sum(axis=0) if has_bias else None
+    return dx, dw, db
+
+
+# ------------------------------------------------------------------ BatchNorm
+def batchnorm_forward(x, gamma, beta):
+    """Training-mode BatchNorm over all axes but the last.  Returns (y, cache)."""
+    C = x.shape[-1]
+    x2 = x.reshape(-1, C)
+    mean = x2.mean(axis=0)
+    var = ((x2 - mean) ** 2).mean(axis=0)          # biased
+    invstd = 1.0 / np.sqrt(var + BN_EPS)
+    xhat = (x2 - mean) * invstd
+    y = (gamma * xhat + beta).reshape(x.shape)
+    return y, (xhat, invstd, mean, var)
+
+
+def batchnorm_backward(dy, gamma, cache):
+    """Return (dx, dgamma, dbeta)."""
+    xhat, invstd, _, _ = cache
+    C = dy.shape[-1]
+    dy2 = dy.reshape(-1, C)
+    M = dy2.shape[0]
+    dbeta = dy2.sum(axis=0)
+    dgamma = (dy2 * xhat).sum(axis=0)
+    dx = gamma * invstd * (dy2 - dbeta / M - xhat * dgamma / M)
+    return dx.reshape(dy.shape), dgamma, dbeta
+
+
+# ----------------------------------------------------------------------- glue
+def relu_forward(x):
+    return np.maximum(x, 0.0)
+
+
+def relu_backward(y, dy):
+    """y is the ReLU output; the derivative at 0 is 0."""
+    return dy * (y > 0.0)
+
+
+def maxpool_forward(x, k, stride, pad):
+    """Returns (y, argmax) with argmax the window tap index r*k+s of the first maximum."""
+    B, H, W, C = x.shape
+    Ho, Wo = _out_size(H, k, stride, pad), _out_size(W, k, stride, pad)
+    xp = np.full((B, H + 2 * pad, W + 2 * pad, C), -np.inf)
+    xp[:, pad:pad + H, pad:pad + W, :] = x
+    y = np.full((B, Ho, Wo, C), -np.inf)
+    arg = np.zeros((B, Ho, Wo, C), dtype=np.int64)
+    for r in range(k):
+        for s in range(k):
+            xs = xp[:, r:r + stride * (Ho - 1) + 1:stride, s:s + stride * (Wo - 1) + 1:stride, :]
+            better = xs > y                         # strict: first maximum wins
+            y = np.where(better, xs, y)
+            arg = np.where(better, r * k + s, arg)
+    return y, arg
+
+
+def maxpool_backward(x_shape, arg, dy, k, stride, pad):
+    B, H, W, C = x_shape
+    _, Ho, Wo, _ = dy.shape
+    dxp = np.zeros((B, H + 2 * pad, W + 2 * pad, C))
+    for r in range(k):
+        for s in range(k):
+            sl = (slice(None), slice(r, r + stride * (Ho - 1) + 1, stride),
+                  slice(s, s + stride * (Wo - 1) + 1, stride), slice(None))
+            dxp[sl] += dy * (arg == r * k + s)
+    return dxp[:, pad:pad + H, pad:pad + W, :].copy()
+
+
+def gap_forward(x):
+    """Global average pool [B,H,W,C] -> [B,C]."""
+    return x.mean(axis=(1, 2))
+
+
+def gap_backward(x_shape, dy):
+    B, H, W, C = x_shape
+    return np.broadcast_to(dy[:, None, None, :] / (H * W), x_shape).copy()
+
+
+def linear_forward(x, w, bias):
+    """y = x w^T + bias, w is [out, in]."""
+    y = x.dot(w.T)
+    if bias is not None:
+        y = y + bias
+    return y
+
+
+def linear_backward(x, w, dy, has_bias):
+    dx = dy.dot(w)
+    dw = dy.T.dot(x)
+    db = dy.sum(axis=0) if has_bias else None
+    return dx, dw, db

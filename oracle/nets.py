@@ -1,0 +1,216 @@
+"""Architectures as op lists, and a plain forward / backward interpreter.
+
+Test infrastructure (see the package docstring).  The paper names its
+architectures (Section 3: ResNet50 with 1000 classes, whose 32-bit size it
+gives as 8e8 bits) without defining them; these are the standard definitions:
+
+  tiny_cnn   conv3x3(3->16)+bias, ReLU, conv3x3(16->32)+bias, ReLU, global
+             average pool, linear(32->10)+bias; stride 1, zero padding 1.
+  resnet20   CIFAR-style: conv3x3(3->16)-BN-ReLU, 3 stages x 3 basic blocks
+             (widths 16/32/64, stride 2 entering stages 2 and 3, projection
+             shortcut = 1x1 stride-2 conv + BN where the width changes), global
+             average pool, linear(64->10)+bias.  Convs followed by BN carry no bias.
+  resnet50   7x7-s2-p3 stem (64) - BN - ReLU - 3x3-s2-p1 max-pool, bottleneck
+             stages 3/4/6/3 with widths 64/128/256/512 (x4 expansion), stride 2
+             on the 3x3 conv of the first block of stages 2-4, projection
+             shortcut in the first block of every stage, global average pool,
+             linear(2048->classes)+bias.
+
+An architecture is (param_table, ops).  param_table is an ordered list of
+(name, shape, kind, fan_in); ops is a list of dicts over integer tensor ids
+(tensor 0 is the input image batch, the last op writes the logits).
+"""
+import numpy as np
+from . import layers as L
+
+
+class Arch:
+    def __init__(self, name):
+        self.name = name
+        self.params = []      # (name, shape, kind, fan_in)
+        self.ops = []
+        self.n_tensors = 1    # tensor 0 = input
+
+    def _t(self):
+        self.n_tensors += 1
+        return self.n_tensors - 1
+
+    def _p(self, name, shape, kind, fan_in=0):
+        self.params.append((name, tuple(shape), kind, fan_in))
+        return name
+
+    def conv(self, x, name, cin, cout, k, stride, pad, bias):
+        w = self._p(name + ".w", (cout, k, k, cin), "conv_w", cin * k * k)
+        b = self._p(name + ".b", (cout,), "bias") if bias else None
+        y = self._t()
+        self.ops.append(dict(op="conv", x=x, y=y, w=w, b=b, stride=stride, pad=pad))
+        return y
+
+    def bn(self, x, name, c):
+        g = self._p(name + ".gamma", (c,), "bn_gamma")
+        b = self._p(name + ".beta", (c,), "bn_beta")
+        y = self._t()
+        self.ops.append(dict(op="bn", x=x, y=y, gamma=g, beta=b))
+        return y
+
+    def relu(self, x):
+        y = self._t()
+        self.ops.append(dict(op="relu", x=x, y=y))
+        return y
+
+    def add(self, a, b):
+        y = self._t()
+        self.ops.append(dict(op="add", a=a, b=b, y=y))
+        return y
+
+    def maxpool(self, x, k, stride, pad):
+        y = self._t()
+        self.ops.append(dict(op="maxpool", x=x, y=y, k=k, stride=stride, pad=pad))
+        return y
+
+    def gap(self, x):
+        y = self._t()
+        self.ops.append(dict(op="gap", x=x, y=y))
+        return y
+
+    def linear(self, x, name, fin, fout):
+        w = self._p(name + ".w", (fout, fin), "linear_w", fin)
+        b = self._p(name + ".b", (fout,), "bias")
+        y = self._t()
+        self.ops.append(dict(op="linear", x=x, y=y, w=w, b=b))
+        return y
+
+    def n_params(self):
+        return int(sum(int(np.prod(s)) for _, s, _, _ in self.params))
+
+
+def tiny_cnn(classes=10):
+    a = Arch("tiny_cnn")
+    t = a.conv(0, "conv1", 3, 16, 3, 1, 1, bias=True)
+    t = a.relu(t)
+    t = a.conv(t, "conv2", 16, 32, 3, 1, 1, bias=True)
+    t = a.relu(t)
+    t = a.gap(t)
+    a.linear(t, "fc", 32, classes)
+    return a
+
+
+def resnet20(classes=10, widths=(16, 32, 64), blocks=(3, 3, 3)):
+    a = Arch("resnet20")
+    t = a.conv(0, "stem.conv", 3, widths[0], 3, 1, 1, bias=False)
+    t = a.relu(a.bn(t, "stem.bn", widths[0]))
+    cin = widths[0]
+    for si, (wd, nb) in enumerate(zip(widths, blocks)):
+        for bi in range(nb):
+            stride = 2 if (si > 0 and bi == 0) else 1
+            p = "s%d.b%d" % (si + 1, bi)
+            u = a.conv(t, p + ".conv1", cin, wd, 3, stride, 1, bias=False)
+            u = a.relu(a.bn(u, p + ".bn1", wd))
+            u = a.conv(u, p + ".conv2", wd, wd, 3, 1, 1, bias=False)
+            u = a.bn(u, p + ".bn2", wd)
+            if stride != 1 or cin != wd:
+                sc = a.conv(t, p + ".down.conv", cin, wd, 1, stride, 0, bias=False)
+                sc = a.bn(sc, p + ".down.bn", wd)
+            else:
+                sc = t
+            t = a.relu(a.add(u, sc))
+            cin = wd
+    t = a.gap(t)
+    a.linear(t, "fc", cin, classes)
+    return a
+
+
+def resnet50(classes=1000, widths=(64, 128, 256, 512), blocks=(3, 4, 6, 3), stem=64):
+    a = Arch("resnet50")
+    t = a.conv(0, "stem.conv", 3, stem, 7, 2, 3, bias=False)
+    t = a.relu(a.bn(t, "stem.bn", stem))
+    t = a.maxpool(t, 3, 2, 1)
+    cin = stem
+    for si, (wd, nb) in enumerate(zip(widths, blocks)):
+        for bi in range(nb):
+            stride = 2 if (si > 0 and bi == 0) else 1
+            p = "s%d.b%d" % (si + 1, bi)
+            u = a.conv(t, p + ".conv1", cin, wd, 1, 1, 0, bias=False)
+            u = a.relu(a.bn(u, p + ".bn1", wd))
+            u = a.conv(u, p + ".conv2", wd, wd, 3, stride, 1, bias=False)
+            u = a.relu(a.bn(u, p + ".bn2", wd))
+            u = a.conv(u, p + ".conv3", wd, 4 * wd, 1, 1, 0, bias=False)
+            u = a.bn(u, p + ".bn3", 4 * wd)
+            if bi == 0:
+                sc = a.conv(t, p + ".down.conv", cin, 4 * wd, 1, stride, 0, bias=False)
+                sc = a.bn(sc, p + ".down.bn", 4 * wd)
+            else:
+                sc = t
+            t = a.relu(a.add(u, sc))
+            cin = 4 * wd
+    t = a.gap(t)
+    a.linear(t, "fc", cin, classes)
+    return a
+
+
+def forward(arch, params, x):
+    """Training-mode forward.  params: dict name -> float64 array.  Returns (logits, tape)."""
+    T = {0: np.asarray(x, dtype=np.float64)}
+    cache = {}
+    for i, o in enumerate(arch.ops):
+        k = o["op"]
+        if k == "conv":
+            b = params[o["b"]] if o["b"] else None
+            T[o["y"]] = L.conv2d_forward(T[o["x"]], params[o["w"]], b, o["stride"], o["pad"])
+        elif k == "bn":
+            T[o["y"]], cache[i] = L.batchnorm_forward(T[o["x"]], params[o["gamma"]], params[o["beta"]])
+        elif k == "relu":
+            T[o["y"]] = L.relu_forward(T[o["x"]])
+        elif k == "add":
+            T[o["y"]] = T[o["a"]] + T[o["b"]]
+        elif k == "maxpool":
+            T[o["y"]], cache[i] = L.maxpool_forward(T[o["x"]], o["k"], o["stride"], o["pad"])
+        elif k == "gap":
+            T[o["y"]] = L.gap_forward(T[o["x"]])
+        elif k == "linear":
+            T[o["y"]] = L.linear_forward(T[o["x"]], params[o["w"]], params[o["b"]])
+        else:
+            raise ValueError(k)
+    return T[arch.ops[-1]["y"]], (T, cache)
+
+
+def backward(arch, params, tape, dlogits):
+    """Gradient of the scalar loss with respect to every parameter, given d loss / d logits."""
+    T, cache = tape
+    G = {arch.ops[-1]["y"]: np.asarray(dlogits, dtype=np.float64)}
+    grads = {}
+
+    def acc(t, g):
+        if t == 0 or g is None:
+            return
+        G[t] = g if t not in G else G[t] + g
+
+    for i in reversed(range(len(arch.ops))):
+        o = arch.ops[i]
+        k = o["op"]
+        dy = G.pop(o["y"])
+        if k == "conv":
+            dx, dw, db = L.conv2d_backward(T[o["x"]], params[o["w"]], dy, o["stride"], o["pad"],
+                                           o["b"] is not None, need_dx=(o["x"] != 0))
+            grads[o["w"]] = dw
+            if o["b"]:
+                grads[o["b"]] = db
+            acc(o["x"], dx)
+        elif k == "bn":
+            dx, dg, db = L.batchnorm_backward(dy, params[o["gamma"]], cache[i])
+            grads[o["gamma"]], grads[o["beta"]] = dg, db
+            acc(o["x"], dx)
+        elif k == "relu":
+            acc(o["x"], L.relu_backward(T[o["y"]], dy))
+        elif k == "add":
+            acc(o["a"], dy)
+            acc(o["b"], dy)
+        elif k == "maxpool":
+            acc(o["x"], L.maxpool_backward(T[o["x"]].shape, cache[i], dy, o["k"], o["stride"], o["pad"]))
+        elif k == "gap":
+            acc(o["x"], L.gap_backward(T[o["x"]].shape, dy))
+        elif k == "linear":
+            dx, dw, db = L.linear_backward(T[o["x"]], params[o["w"]], dy, True)
+            grads[o["w"]], grads[o["b"]] = dw, db
+            acc(o["x"], dx)
+    return grads

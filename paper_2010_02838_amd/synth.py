@@ -1,0 +1,66 @@
+"""Seeded synthetic inputs: weights, images, labels, logits.
+
+This module only draws random numbers and rounds them; it contains none of the
+training step's arithmetic, so both the GPU library's callers and the CPU test
+oracle may be fed from it.  Everything comes from NumPy's PCG64 generator.
+
+Recipes (stand-ins for the image and translation datasets of the paper's
+experiments, whose shapes they keep: 32x32x3 / 10 classes, 224x224x3 / 1000
+classes, 32K-symbol vocabulary):
+  images   N(0,1) float32, NHWC
+  labels   uniform integer class ids
+  weights  He initialisation: N(0, 2/fan_in) for convolution and linear
+           weights (fan_in = Cin*kh*kw or in_features), BatchNorm scale 1,
+           BatchNorm shift and biases 0; `jitter` perturbs the scale/shift/bias
+           tensors so that tests exercise them
+  logits   N(0, sigma^2) float32
+"""
+import numpy as np
+
+
+def _rng(seed):
+    return np.random.Generator(np.random.PCG64(seed))
+
+
+def bf16_bits(x):
+    """float32 array -> uint16 array of bfloat16 bit patterns, round-to-nearest-even."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    r = ((u >> 16) & 1) + 0x7FFF
+    return ((u + r) >> 16).astype(np.uint16)
+
+
+def bf16_to_f32(bits):
+    return (np.asarray(bits, dtype=np.uint16).astype(np.uint32) << 16).view(np.float32)
+
+
+def round_bf16(x):
+    """Round a float32 array to the nearest bfloat16 value, returned as float32."""
+    return bf16_to_f32(bf16_bits(x)).reshape(np.shape(x))
+
+
+def he_init(param_table, seed, jitter=0.0):
+    """param_table: ordered (name, shape, kind, fan_in); returns the flat float32 vector."""
+    rng = _rng(seed)
+    parts = []
+    for _, shape, kind, fan_in in param_table:
+        n = int(np.prod(shape))
+        if kind in ("conv_w", "linear_w"):
+            a = rng.standard_normal(n) * np.sqrt(2.0 / fan_in)
+        elif kind == "bn_gamma":
+            a = 1.0 + jitter * rng.standard_normal(n)
+        else:
+            a = jitter * rng.standard_normal(n)
+        parts.append(a.astype(np.float32))
+    return np.concatenate(parts)
+
+
+def images(batch, h, w, c, seed):
+    return _rng(seed).standard_normal((batch, h, w, c)).astype(np.float32)
+
+
+def labels(n, classes, seed):
+    return _rng(seed).integers(0, classes, size=n).astype(np.int32)
+
+
+def logits(rows, cols, sigma, seed):
+    return (_rng(seed).standard_normal((rows, cols), dtype=np.float32) * np.float32(sigma))

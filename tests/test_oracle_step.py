@@ -1,0 +1,295 @@
+"""Pins for the oracle's layers, networks, optimiser and whole step.
+
+Brute force on tiny inputs, closed forms, invariants, finite differences, the
+model size the paper prints, and a cross-check of the hand-written VJPs against
+a library autograd (torch CPU float64) running the same op list.
+"""
+import itertools
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+from oracle import layers as L
+from oracle import nets, sgd
+from oracle.step import codistill_step, flatten, unflatten
+from paper_2010_02838_amd import synth
+
+
+# --------------------------------------------------------------- brute force
+@pytest.mark.parametrize("k,stride,pad", [(3, 1, 1), (3, 2, 1), (1, 1, 0), (1, 2, 0), (7, 2, 3)])
+def test_conv_forward_brute_force(k, stride, pad):
+    rng = np.random.default_rng(k * 10 + stride)
+    B, H, W, Cin, Cout = 2, 9, 8, 3, 4
+    x = rng.standard_normal((B, H, W, Cin))
+    w = rng.standard_normal((Cout, k, k, Cin))
+    b = rng.standard_normal(Cout)
+    y = L.conv2d_forward(x, w, b, stride, pad)
+    Ho, Wo = (H + 2 * pad - k) // stride + 1, (W + 2 * pad - k) // stride + 1
+    assert y.shape == (B, Ho, Wo, Cout)
+    ref = np.zeros_like(y)
+    for n, ho, wo, o in itertools.product(range(B), range(Ho), range(Wo), range(Cout)):
+        acc = b[o]
+        for r in range(k):
+            for s in range(k):
+                hi, wi = ho * stride - pad + r, wo * stride - pad + s
+                if 0 <= hi < H and 0 <= wi < W:
+                    for c in range(Cin):
+                        acc += x[n, hi, wi, c] * w[o, r, s, c]
+        ref[n, ho, wo, o] = acc
+    np.testing.assert_allclose(y, ref, atol=1e-12)
+
+
+@pytest.mark.parametrize("k,stride,pad", [(3, 1, 1), (3, 2, 1), (1, 2, 0), (7, 2, 3)])
+def test_conv_backward_is_adjoint(k, stride, pad):
+    # <dy, conv(x; w)> is bilinear: its derivatives are fixed by the forward map alone
+    rng = np.random.default_rng(k + stride)
+    x = rng.standard_normal((2, 9, 8, 3))
+    w = rng.standard_normal((4, k, k, 3))
+    y = L.conv2d_forward(x, w, None, stride, pad)
+    dy = rng.standard_normal(y.shape)
+    dx, dw, db = L.conv2d_backward(x, w, dy, stride, pad, True)
+    x2, w2 = rng.standard_normal(x.shape), rng.standard_normal(w.shape)
+    assert np.vdot(dx, x2) == pytest.approx(np.vdot(dy, L.conv2d_forward(x2, w, None, stride, pad)), rel=1e-11)
+    assert np.vdot(dw, w2) == pytest.approx(np.vdot(dy, L.conv2d_forward(x, w2, None, stride, pad)), rel=1e-11)
+    np.testing.assert_allclose(db, dy.sum(axis=(0, 1, 2)), atol=1e-12)
+
+
+def test_maxpool_brute_force_and_backward():
+    rng = np.random.default_rng(0)
+    x = rng.standard_normal((2, 7, 6, 3))
+    y, arg = L.maxpool_forward(x, 3, 2, 1)
+    B, Ho, Wo, C = y.shape
+    assert (Ho, Wo) == (4, 3)
+    dy = rng.standard_normal(y.shape)
+    dref = np.zeros_like(x)
+    for n, ho, wo, c in itertools.product(range(B), range(Ho), range(Wo), range(C)):
+        best, where = -np.inf, None
+        for r in range(3):
+            for s in range(3):
+                hi, wi = 2 * ho - 1 + r, 2 * wo - 1 + s
+                if 0 <= hi < 7 and 0 <= wi < 6 and x[n, hi, wi, c] > best:
+                    best, where = x[n, hi, wi, c], (hi, wi)
+        assert y[n, ho, wo, c] == best
+        dref[n, where[0], where[1], c] += dy[n, ho, wo, c]
+    np.testing.assert_allclose(L.maxpool_backward(x.shape, arg, dy, 3, 2, 1), dref, atol=1e-15)
+
+
+# ------------------------------------------------------------------ BatchNorm
+def test_batchnorm_invariants():
+    rng = np.random.default_rng(1)
+    x = rng.standard_normal((4, 5, 5, 6)) * 3 + 2
+    gamma, beta = rng.standard_normal(6), rng.standard_normal(6)
+    y, cache = L.batchnorm_forward(x, np.ones(6), np.zeros(6))
+    y2 = y.reshape(-1, 6)
+    var = x.reshape(-1, 6).var(axis=0)
+    np.testing.assert_allclose(y2.mean(axis=0), 0, atol=1e-14)
+    np.testing.assert_allclose(y2.var(axis=0), var / (var + 1e-5), rtol=1e-12)
+    yg, cache = L.batchnorm_forward(x, gamma, beta)
+    np.testing.assert_allclose(yg, gamma * y + beta, atol=1e-13)
+    dy = rng.standard_normal(x.shape)
+    dx, dg, db = L.batchnorm_backward(dy, gamma, cache)
+    np.testing.assert_allclose(dx.reshape(-1, 6).sum(axis=0), 0, atol=1e-12)       # sums to 0 per channel
+    # orthogonal to x-hat up to the eps in the denominator: sum dx*xhat = gamma*invstd*dgamma*eps/(var+eps)
+    invstd = 1 / np.sqrt(var + 1e-5)
+    np.testing.assert_allclose((dx * y).reshape(-1, 6).sum(axis=0), gamma * invstd * dg * 1e-5 / (var + 1e-5),
+                               atol=1e-12)
+    np.testing.assert_allclose(db, dy.reshape(-1, 6).sum(axis=0), atol=1e-12)
+
+
+def test_batchnorm_matches_library():
+    rng = np.random.default_rng(2)
+    x = rng.standard_normal((3, 4, 4, 5))
+    g, b = rng.standard_normal(5), rng.standard_normal(5)
+    dy = rng.standard_normal(x.shape)
+    xt = torch.tensor(x).permute(0, 3, 1, 2).requires_grad_(True)
+    gt, bt = torch.tensor(g, requires_grad=True), torch.tensor(b, requires_grad=True)
+    yt = F.batch_norm(xt, None, None, gt, bt, training=True, eps=1e-5)
+    yt.backward(torch.tensor(dy).permute(0, 3, 1, 2))
+    y, cache = L.batchnorm_forward(x, g, b)
+    dx, dg, db = L.batchnorm_backward(dy, g, cache)
+    np.testing.assert_allclose(y, yt.detach().permute(0, 2, 3, 1).numpy(), atol=1e-13)
+    np.testing.assert_allclose(dx, xt.grad.permute(0, 2, 3, 1).numpy(), atol=1e-13)
+    np.testing.assert_allclose(dg, gt.grad.numpy(), atol=1e-12)
+    np.testing.assert_allclose(db, bt.grad.numpy(), atol=1e-12)
+
+
+# ------------------------------------------------------------------------ SGD
+def test_sgd_closed_forms():
+    rng = np.random.default_rng(3)
+    w0, g = rng.standard_normal(50), rng.standard_normal(50)
+    lr, mu, lam = 0.1, 0.9, 0.01
+    w1, v1 = sgd.sgd_step(w0, np.zeros(50), g, lr, mu)
+    np.testing.assert_allclose(w1, w0 - lr * g, atol=1e-15)
+    w2, v2 = sgd.sgd_step(w1, v1, g, lr, mu)
+    np.testing.assert_allclose(w2, w1 - lr * (1 + mu) * g, atol=1e-15)
+    wd, _ = sgd.sgd_step(w0, np.zeros(50), g, lr, mu, weight_decay=lam)
+    np.testing.assert_allclose(wd, w0 - lr * (g + lam * w0), atol=1e-15)
+    wn, vn = sgd.sgd_step(w1, v1, g, lr, mu, nesterov=True)
+    np.testing.assert_allclose(wn, w1 - lr * (g + mu * (mu * g + g)), atol=1e-15)
+    # library cross-check over three steps
+    wt = torch.tensor(w0, requires_grad=True)
+    opt = torch.optim.SGD([wt], lr=lr, momentum=mu, weight_decay=lam)
+    w, v = w0, np.zeros(50)
+    for i in range(3):
+        gi = g * (i + 1)
+        wt.grad = torch.tensor(gi)
+        opt.step()
+        w, v = sgd.sgd_step(w, v, gi, lr, mu, weight_decay=lam)
+    np.testing.assert_allclose(w, wt.detach().numpy(), atol=1e-14)
+
+
+# --------------------------------------------------------------- architectures
+def test_parameter_counts():
+    # Section 3 gives the 32-bit ResNet50 as 8e8 bits and 1000 32-bit predictions as 3.2e4 bits
+    r50 = nets.resnet50()
+    assert r50.n_params() == 25557032
+    assert round(r50.n_params() * 32 / 1e8) == 8
+    assert r50.params[-1][1] == (1000,) and 1000 * 32 == 3.2e4
+    assert nets.tiny_cnn().n_params() == 5418
+    r20 = nets.resnet20()
+    assert r20.n_params() == 272474
+    assert sum(1 for o in r20.ops if o["op"] == "conv") == 21
+    assert sum(1 for o in r50.ops if o["op"] == "conv") == 53
+
+
+def _torch_forward(arch, params, x):
+    T = {0: x.permute(0, 3, 1, 2)}
+    for o in arch.ops:
+        k = o["op"]
+        if k == "conv":
+            b = params[o["b"]] if o["b"] else None
+            T[o["y"]] = F.conv2d(T[o["x"]], params[o["w"]].permute(0, 3, 1, 2), b, o["stride"], o["pad"])
+        elif k == "bn":
+            T[o["y"]] = F.batch_norm(T[o["x"]], None, None, params[o["gamma"]], params[o["beta"]], True, 0.1, 1e-5)
+        elif k == "relu":
+            T[o["y"]] = F.relu(T[o["x"]])
+        elif k == "add":
+            T[o["y"]] = T[o["a"]] + T[o["b"]]
+        elif k == "maxpool":
+            T[o["y"]] = F.max_pool2d(T[o["x"]], o["k"], o["stride"], o["pad"])
+        elif k == "gap":
+            T[o["y"]] = T[o["x"]].mean(dim=(2, 3))
+        elif k == "linear":
+            T[o["y"]] = F.linear(T[o["x"]], params[o["w"]], params[o["b"]])
+    return T[arch.ops[-1]["y"]]
+
+
+ARCHS = {
+    "tiny_cnn": (lambda: nets.tiny_cnn(), (8, 32, 32, 3), 10),
+    "resnet20_small": (lambda: nets.resnet20(classes=10, widths=(4, 8, 16), blocks=(2, 1, 1)), (6, 16, 16, 3), 10),
+    "resnet50_small": (lambda: nets.resnet50(classes=7, widths=(4, 8, 8, 16), blocks=(2, 1, 1, 1), stem=8), (4, 40, 40, 3), 7),
+}
+
+
+@pytest.mark.parametrize("name", list(ARCHS))
+@pytest.mark.parametrize("dist", ["mse", "kl"])
+def test_step_matches_library_autograd(name, dist):
+    mk, xs, classes = ARCHS[name]
+    arch = mk()
+    th = synth.he_init(arch.params, 1, jitter=0.1).astype(np.float64)
+    thp = synth.he_init(arch.params, 2, jitter=0.1).astype(np.float64)
+    x = synth.images(*xs, seed=0).astype(np.float64)
+    y = synth.labels(xs[0], classes, seed=3)
+    alpha, lr, mu, lam = 1.0, 0.1, 0.9, 1e-3
+    v0 = np.random.default_rng(5).standard_normal(th.size) * 0.01
+    out = codistill_step(arch, th, [thp], x, y, alpha, lr, mu, v=v0, weight_decay=lam, dist=dist)
+
+    tp = {k: torch.tensor(v, requires_grad=True) for k, v in unflatten(arch, th).items()}
+    tpp = {k: torch.tensor(v) for k, v in unflatten(arch, thp).items()}
+    xt = torch.tensor(x)
+    z = _torch_forward(arch, tp, xt)
+    with torch.no_grad():
+        zp = _torch_forward(arch, tpp, xt)
+    ce = F.cross_entropy(z, torch.tensor(y).long())
+    if dist == "mse":
+        d = F.mse_loss(z, zp)
+    else:
+        d = F.kl_div(torch.log_softmax(z, 1), torch.softmax(zp, 1), reduction="batchmean")
+    loss = ce + alpha * d
+    leaves = [tp[n] for n, _, _, _ in arch.params]
+    opt = torch.optim.SGD(leaves, lr=lr, momentum=mu, weight_decay=lam)
+    loss.backward()
+    off = 0
+    for p in leaves:                       # preload the momentum buffers with v0
+        opt.state[p]["momentum_buffer"] = torch.tensor(v0[off:off + p.numel()]).reshape(p.shape).clone()
+        off += p.numel()
+    g_ref = np.concatenate([p.grad.numpy().ravel() for p in leaves])
+    opt.step()
+    w_ref = np.concatenate([p.detach().numpy().ravel() for p in leaves])
+
+    np.testing.assert_allclose(out["logits"], z.detach().numpy(), atol=1e-11)
+    np.testing.assert_allclose(out["peer_logits"][0], zp.numpy(), atol=1e-11)
+    assert out["loss"][0] == pytest.approx(loss.item(), rel=1e-12)
+    assert out["loss"][1] == pytest.approx(ce.item(), rel=1e-12)
+    assert out["loss"][2] == pytest.approx(d.item(), rel=1e-11)
+    np.testing.assert_allclose(out["grad"], g_ref, atol=1e-10 * max(1.0, np.abs(g_ref).max()))
+    np.testing.assert_allclose(out["theta"], w_ref, atol=1e-11)
+
+
+@pytest.mark.parametrize("name", ["tiny_cnn", "resnet20_small", "resnet50_small"])
+def test_step_gradient_by_finite_differences(name):
+    mk, xs, classes = ARCHS[name]
+    arch = mk()
+    xs = (3, 12, 12, 3) if name != "resnet50_small" else (2, 36, 36, 3)
+    th = synth.he_init(arch.params, 1, jitter=0.1).astype(np.float64)
+    thp = synth.he_init(arch.params, 2, jitter=0.1).astype(np.float64)
+    x = synth.images(*xs, seed=0).astype(np.float64)
+    y = synth.labels(xs[0], classes, seed=3)
+
+    def loss_at(t):
+        return codistill_step(arch, t, [thp], x, y, 1.0, 0.0, 0.0)["loss"][0]
+
+    g = codistill_step(arch, th, [thp], x, y, 1.0, 0.0, 0.0)["grad"]
+    rng = np.random.default_rng(0)
+    h = 1e-5
+    # every tensor gets probed: one random coordinate each, plus a random direction
+    off = 0
+    for _, shape, _, _ in arch.params:
+        n = int(np.prod(shape))
+        i = off + int(rng.integers(0, n))
+        e = np.zeros_like(th)
+        e[i] = h
+        fd = (loss_at(th + e) - loss_at(th - e)) / (2 * h)
+        assert abs(fd - g[i]) <= 2e-6 * max(1.0, abs(g[i])), (shape, fd, g[i])
+        off += n
+    d = rng.standard_normal(th.size)
+    d /= np.linalg.norm(d)
+    fd = (loss_at(th + h * d) - loss_at(th - h * d)) / (2 * h)
+    assert fd == pytest.approx(float(g.dot(d)), rel=1e-6, abs=1e-8)
+
+
+def test_conv_before_batchnorm_scale_invariance():
+    # the loss does not change when a conv that feeds a BatchNorm is rescaled (up to the
+    # eps = 1e-5 in the BatchNorm denominator), so the gradient of its weights is
+    # orthogonal to the weights to about eps / var relative
+    arch = nets.resnet20(classes=10, widths=(4, 8, 16), blocks=(1, 1, 1))
+    th = synth.he_init(arch.params, 1, jitter=0.1).astype(np.float64)
+    thp = synth.he_init(arch.params, 2).astype(np.float64)
+    x = synth.images(4, 16, 16, 3, seed=0).astype(np.float64)
+    y = synth.labels(4, 10, seed=3)
+    out = codistill_step(arch, th, [thp], x, y, 1.0, 0.1, 0.9)
+    w = unflatten(arch, th)
+    for name, shape, kind, _ in arch.params:
+        if kind == "conv_w":
+            dot = np.vdot(w[name], out["grads"][name])
+            assert abs(dot) < 1e-4 * np.linalg.norm(w[name]) * np.linalg.norm(out["grads"][name])
+
+
+def test_peer_gets_no_gradient_and_plain_step():
+    # Section 3: backward only with respect to the local parameters; omitting D gives the supervised step
+    arch = nets.tiny_cnn()
+    th = synth.he_init(arch.params, 1).astype(np.float64)
+    thp = synth.he_init(arch.params, 2).astype(np.float64)
+    x = synth.images(4, 8, 8, 3, seed=0).astype(np.float64)
+    y = synth.labels(4, 10, seed=3)
+    a = codistill_step(arch, th, [thp], x, y, 0.0, 0.1, 0.9)
+    b = codistill_step(arch, th, [], x, y, 1.0, 0.1, 0.9)
+    np.testing.assert_array_equal(a["theta"], b["theta"])
+    c = codistill_step(arch, th, [th.copy()], x, y, 1.0, 0.1, 0.9)
+    np.testing.assert_array_equal(c["theta"], b["theta"])
+    assert c["loss"][2] == 0.0
+    # first step from v = 0: theta_1 = theta_0 - lr * g
+    np.testing.assert_allclose(b["theta"], th - 0.1 * b["grad"], atol=1e-15)
+    assert flatten(arch, unflatten(arch, th)).tolist() == th.tolist()
