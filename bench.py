@@ -1,0 +1,140 @@
+"""Throughput of one GPU's share of a codistillation step on one MI355X.
+
+A "step" is one pass of the whole hot path over one synthetic minibatch, inputs
+already resident in HBM: local forward (kept for backward), peer forward
+(nothing kept), codistillation loss + gradient, local backward, momentum-SGD.
+Workload: two ResNet-50 (bf16 compute, fp32 master weights), batch 256 of
+224x224x3 images ~ N(0,1), 1000 uniform classes, alpha = 1.
+
+Prints ONE JSON line.  `roofline` is for the dominant kernel (the bf16 MFMA
+implicit-GEMM convolution, all fprop and dgrad launches of a step): algorithmic
+flops / HIP-event time of those launches, measured in a second pass of the same
+steps with the library's per-launch event timer switched on.  `cpu_baseline` is
+the float64 NumPy oracle of the same step timed on the host on a small batch.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+
+def cpu_baseline(seconds_hint=20.0):
+    """Oracle step (ResNet-50, 224x224, batch 2) on the host cores: a baseline, not a target."""
+    import numpy as np
+    from oracle import nets
+    from oracle.step import codistill_step
+    from paper_2010_02838_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    arch = nets.resnet50()
+    batch = 2
+    th = synth.round_bf16(synth.he_init(arch.params, 1)).astype(np.float64)
+    thp = synth.round_bf16(synth.he_init(arch.params, 2)).astype(np.float64)
+    x = synth.round_bf16(synth.images(batch, 224, 224, 3, 0)).astype(np.float64)
+    y = synth.labels(batch, 1000, 3)
+    t0 = time.time()
+    codistill_step(arch, th, [thp], x, y, 1.0, 0.1, 0.9)
+    dt = time.time() - t0
+    return {"value": batch / dt, "unit": "samples/s", "cores": int(cores), "kind": "oracle",
+            "sample": "one float64 NumPy oracle step, ResNet-50 224x224, batch %d (%.1f s)" % (batch, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--batch", type=int, default=256)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU's share of the step: this build has no multi-GPU path, "
+                 "run it with --gpus 1")
+
+    import numpy as np
+    import torch
+    from paper_2010_02838_amd import binding as B
+    from paper_2010_02838_amd import synth
+    from paper_2010_02838_amd.runner import StepRunner, pack_flat, to_device
+
+    dev = "cuda:0"
+    batch, res, classes = args.batch, 224, 1000
+    arch = B.arch_preset(B.CD_ARCH_RESNET_BOTTLENECK)
+    model, peer = B.Model(arch, B.CD_BF16), B.Model(arch, B.CD_BF16)
+    table = model.param_table()
+    r = StepRunner(model, [peer], batch, dev)
+    r.load(pack_flat(model, synth.he_init(table, 1)), [pack_flat(peer, synth.he_init(table, 2))])
+    x = torch.empty(batch, res, res, 3, dtype=torch.bfloat16, device=dev)
+    for b0 in range(0, batch, 32):       # images ~ N(0,1), generated on the host in slices
+        n = min(32, batch - b0)
+        x[b0:b0 + n] = to_device(synth.images(n, res, res, 3, seed=100 + b0), torch.bfloat16, dev)
+    y = torch.from_numpy(synth.labels(batch, classes, seed=3)).to(dev)
+    alpha, lr, mu = 1.0, 0.1, 0.9
+
+    def step():
+        r.step(x, y, alpha, lr, mu)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    loss = r.loss.cpu().numpy()
+
+    # second pass: per-launch HIP events on the launch stream, per kernel class
+    B.profile_reset()
+    B.profile_enable(True)
+    psteps = max(1, min(args.steps, 5))
+    for _ in range(psteps):
+        step()
+    torch.cuda.synchronize()
+    prof = B.profile_collect()
+    B.profile_enable(False)
+    ig_ms = prof["conv_fprop"]["ms"] + prof["conv_dgrad"]["ms"]
+    ig_n = prof["conv_fprop"]["launches"] + prof["conv_dgrad"]["launches"]
+    ig_fl = prof["conv_fprop"]["flops"] + prof["conv_dgrad"]["flops"]
+    achieved = ig_fl / (ig_ms * 1e-3) / 1e12 if ig_ms > 0 else 0.0
+    roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                "kernel": "igemm_kernel (bf16 implicit-GEMM conv, fprop+dgrad launches)",
+                "launches_per_step": ig_n / psteps, "avg_launch_us": ig_ms / max(ig_n, 1) * 1e3}
+    classes_ms = {k: round(v["ms"] / psteps, 4) for k, v in prof.items()}
+    hbm = {}
+    for k in ("norm", "loss", "sgd"):
+        if prof[k]["ms"] > 0:
+            hbm[k] = {"GB/s": prof[k]["bytes"] / (prof[k]["ms"] * 1e-3) / 1e9}
+            hbm[k]["frac"] = hbm[k]["GB/s"] / PEAK_HBM_GBS
+
+    out = {
+        "metric": "codistill-step samples/sec on 1 MI355X (ResNet-50, 224^2, bs256)",
+        "value": batch / (ms_per_step * 1e-3), "unit": "samples/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "resnet50_codistill_step", "batch": batch, "resolution": res, "classes": classes,
+                   "models": "2 x ResNet-50 (local fwd+bwd+SGD, peer fwd)", "alpha": alpha,
+                   "distillation": "mse_logits", "lr": lr, "momentum": mu},
+        "loss": [float(v) for v in loss[:3]],
+        "roofline": roofline,
+        "kernel_class_ms_per_step": classes_ms,
+        "hbm_kernels": hbm,
+        "cpu_baseline": None if args.no_cpu_baseline else cpu_baseline(),
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,247 @@
+/*
+ * codistill.h - C ABI of the MI355X (gfx950) codistillation-step library.
+ *
+ * One GPU's share of one codistillation training step (paper, Algorithm 1, the
+ * per-model update, in the checkpoint-exchange implementation of Section 3):
+ *
+ *     z  = f_theta (x)     codistill_forward(local model, save_for_backward = 1)
+ *     z' = f_theta'(x)     codistill_forward(stale peer copy, save_for_backward = 0)
+ *     l  = L(y,z) + alpha * mean_j D(z, z'_j),  dz = dl/dz      codistill_loss_grad
+ *     g  = dl/dtheta       codistill_backward (local model only)
+ *     theta <- momentum-SGD(theta, g)                           codistill_sgd_step
+ *
+ * Conventions
+ *   - Every function returns CD_OK (0) or a negative CD_ERR_* code and never
+ *     throws or aborts; codistill_last_error() returns a thread-local message
+ *     for the last failing call on this thread.
+ *   - Unless marked "host", every data pointer is a DEVICE pointer owned by the
+ *     caller, 16-byte aligned.  The library does not allocate, free or retain
+ *     device memory; all temporary storage is the caller's workspace / scratch.
+ *   - Calls only enqueue kernels on the caller's stream (`stream` is a
+ *     hipStream_t passed as void*; NULL is the default stream) and never
+ *     synchronise.  Arguments are validated on the host before any launch; a
+ *     call that returns an error has launched nothing.
+ *   - Layouts: activations NHWC, filters [Cout][kh][kw][Cin], linear weights
+ *     [out][in], logits row-major [rows][cols].  bf16 is the upper half of an
+ *     IEEE float32, round-to-nearest-even.
+ */
+#ifndef CODISTILL_H
+#define CODISTILL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  CD_OK = 0,
+  CD_ERR_INVALID_ARG = -1,
+  CD_ERR_UNSUPPORTED = -2,
+  CD_ERR_WORKSPACE_TOO_SMALL = -3,
+  CD_ERR_HIP = -4
+};
+
+/* storage / compute type of a model: CD_F32 = fp32 everywhere; CD_BF16 = bf16
+ * weights and activations, fp32 accumulation, statistics, logits and gradients */
+enum { CD_F32 = 0, CD_BF16 = 1 };
+
+/* distillation term D.  CD_DIST_MSE_LOGITS: mean squared error between the raw,
+ * uncentred logits (paper, appendix "Implementation Details").  CD_DIST_KL:
+ * KL(softmax(z') || softmax(z)), the choice of the prior work cited in Section 2. */
+enum { CD_DIST_MSE_LOGITS = 0, CD_DIST_KL = 1 };
+/* normaliser of the squared error: all rows*cols elements, or rows only */
+enum { CD_MEAN_ALL = 0, CD_MEAN_ROWS = 1 };
+
+/* BatchNorm mode of a forward pass.  Only batch statistics are implemented. */
+enum { CD_BN_BATCH_STATS = 0, CD_BN_RUNNING = 1 };
+
+/* architecture families (the paper names ResNet50, Section 3; the others are
+ * the small workloads used to check the step) */
+enum {
+  CD_ARCH_TINY_CNN = 0,          /* conv3x3(3->16)+b, ReLU, conv3x3(16->32)+b, ReLU, GAP, linear */
+  CD_ARCH_RESNET_BASIC = 1,      /* CIFAR-style: 3x3 stem, basic blocks, projection shortcuts    */
+  CD_ARCH_RESNET_BOTTLENECK = 2  /* 7x7-s2 stem, 3x3-s2 max-pool, bottleneck blocks (x4)         */
+};
+
+#define CD_MAX_STAGES 4
+#define CD_NAME_LEN 48
+
+/* host struct.  Input images always have 3 channels. */
+typedef struct {
+  int32_t kind;                   /* CD_ARCH_*                                             */
+  int32_t classes;                /* width of the logits                                   */
+  int32_t in_h, in_w;             /* input resolution                                      */
+  int32_t n_stages;               /* residual families: 1..CD_MAX_STAGES; tiny CNN: unused */
+  int32_t widths[CD_MAX_STAGES];  /* stage widths (bottleneck: inner width, output is x4); */
+                                  /* tiny CNN: widths[0], widths[1] = the two conv widths  */
+  int32_t blocks[CD_MAX_STAGES];  /* blocks per stage                                      */
+  int32_t stem_width;             /* output channels of the stem convolution               */
+} cd_arch_desc;
+
+/* kind of a parameter tensor */
+enum { CD_P_CONV_W = 0, CD_P_BIAS = 1, CD_P_BN_GAMMA = 2, CD_P_BN_BETA = 3, CD_P_LINEAR_W = 4 };
+
+/* host struct describing one parameter tensor inside the flat buffers */
+typedef struct {
+  char name[CD_NAME_LEN];
+  int32_t kind;      /* CD_P_*                                                      */
+  int32_t ndim;      /* 1, 2 or 4                                                   */
+  int64_t shape[4];  /* conv [Cout,kh,kw,Cin]; linear [out,in]; others [C]          */
+  int64_t offset;    /* element offset in the flat parameter / gradient buffers     */
+  int64_t size;      /* number of elements                                          */
+  int64_t fan_in;    /* Cin*kh*kw or in_features; 0 for scale / shift / bias        */
+} cd_tensor_info;
+
+typedef struct cd_model cd_model; /* opaque host object */
+
+/* Fill *out with a preset: CD_ARCH_TINY_CNN (32x32, 10 classes), CD_ARCH_RESNET_BASIC
+ * (ResNet-20: 32x32, widths 16/32/64, 3 blocks each, 10 classes), CD_ARCH_RESNET_BOTTLENECK
+ * (ResNet-50: 224x224, widths 64..512, blocks 3/4/6/3, 1000 classes; Section 3). host. */
+int codistill_arch_preset(int kind, cd_arch_desc* out);
+
+/* Build the host-side description (op list, parameter table) of a model.
+ * dtype: CD_F32 or CD_BF16.  *out is owned by the caller until codistill_model_destroy. */
+int codistill_model_create(const cd_arch_desc* arch, int dtype, cd_model** out);
+void codistill_model_destroy(cd_model* m);
+
+/* number of parameter tensors and of parameter elements. host outputs. */
+int codistill_param_count(const cd_model* m, int64_t* n_tensors, int64_t* n_elements);
+/* describe parameter tensor idx (declaration order). host output. */
+int codistill_param_info(const cd_model* m, int64_t idx, cd_tensor_info* out);
+/* bytes of workspace a forward (and, with save_for_backward, the matching backward)
+ * needs for this batch size. host output. */
+int codistill_workspace_bytes(const cd_model* m, int64_t batch, int save_for_backward, size_t* bytes);
+
+/*
+ * z = f_params(x): training-mode forward pass (Algorithm 1: f_theta(x); Section 3: the
+ * device runs one forward for its own model and one per stale peer, on the same minibatch).
+ *   params      flat parameter buffer in the model's dtype (fp32 or bf16), declaration order
+ *   x           [batch][in_h][in_w][3] in the model's dtype
+ *   save_for_backward  1: keep in `workspace` what codistill_backward needs (local model);
+ *                      0: keep nothing (peer model; its logits are constants)
+ *   bn_mode     CD_BN_BATCH_STATS (CD_BN_RUNNING is rejected as unsupported)
+ *   bn_running  reserved, must be NULL
+ *   workspace   at least codistill_workspace_bytes(m, batch, save_for_backward) bytes; with
+ *               save_for_backward the same buffer must be handed, untouched, to codistill_backward
+ *   logits_out  [batch][classes] fp32
+ * Errors: NULL pointer, batch <= 0, unknown mode -> CD_ERR_INVALID_ARG; small workspace ->
+ * CD_ERR_WORKSPACE_TOO_SMALL; launch failure -> CD_ERR_HIP.
+ */
+int codistill_forward(const cd_model* m, const void* params, const void* x, int64_t batch,
+                      int save_for_backward, int bn_mode, float* bn_running,
+                      void* workspace, size_t workspace_bytes, float* logits_out, void* stream);
+
+/* host struct */
+typedef struct {
+  float alpha;            /* penalty coefficient alpha^k of Algorithm 1                        */
+  float label_smoothing;  /* in [0,1): target distribution (1-eps) onehot + eps/cols           */
+  int32_t dist_kind;      /* CD_DIST_*                                                         */
+  int32_t mse_reduction;  /* CD_MEAN_*; only read for CD_DIST_MSE_LOGITS                       */
+  int32_t ignore_index;   /* rows whose target equals this add nothing and get a zero gradient */
+  int32_t n_peers;        /* n-1 of Algorithm 1; 0 = no distillation term this iteration       */
+} cd_loss_cfg;
+
+#define CD_LOSS_MAX_PEERS 8
+
+/* bytes of scratch codistill_loss_grad needs for this row count. host output. */
+int codistill_loss_scratch_bytes(int64_t rows, int64_t cols, size_t* bytes);
+
+/*
+ * Codistillation loss and its gradient with respect to the local logits (Algorithm 1: the
+ * objective inside the gradient; Section 3: peers are constants, and the distillation term
+ * is left out on iterations without peer predictions):
+ *     task    = mean over valid rows of cross-entropy(q_row, softmax(z_row))
+ *     distill = mean over peers of D(z, z'_j), mean over valid rows (and columns for MSE/ALL)
+ *     total   = task + alpha * distill
+ *     dz      = d total / d z
+ *   z_local   [rows][cols] fp32
+ *   z_peers   HOST array of n_peers device pointers, each [rows][cols] fp32; may be NULL when
+ *             n_peers == 0
+ *   targets   [rows] int32 class ids.  A target equal to ignore_index skips the row; any other
+ *             target outside [0, cols) also skips the row and sets bit 0 of the status word
+ *   loss_out  device float[4]: total, task, distill, and the status word (as int32 bits)
+ *   dz_out    [rows][cols] fp32; may alias z_local
+ *   scratch   at least codistill_loss_scratch_bytes(rows, cols) bytes
+ * Supported: 1 <= cols <= 2^24, 1 <= rows <= 2^31-1, 0 <= n_peers <= CD_LOSS_MAX_PEERS.
+ * Errors: NULL required pointer, rows/cols out of range, unknown enum, n_peers out of range,
+ * label_smoothing outside [0,1), misaligned pointer -> CD_ERR_INVALID_ARG; small scratch ->
+ * CD_ERR_WORKSPACE_TOO_SMALL.
+ */
+int codistill_loss_grad(const float* z_local, const float* const* z_peers, const int32_t* targets,
+                        int64_t rows, int64_t cols, const cd_loss_cfg* cfg,
+                        float* loss_out, float* dz_out, void* scratch, size_t scratch_bytes,
+                        void* stream);
+
+/*
+ * Backward pass of the local model (Section 3: only with respect to the local parameters).
+ * Consumes the workspace written by codistill_forward(..., save_for_backward = 1, ...) with the
+ * same model, params, x and batch.
+ *   dlogits    [batch][classes] fp32, d loss / d logits
+ *   grads_out  flat fp32 gradient, same offsets as the parameter buffer; fully overwritten
+ */
+int codistill_backward(const cd_model* m, const void* params, const void* x, int64_t batch,
+                       void* workspace, size_t workspace_bytes, const float* dlogits,
+                       float* grads_out, void* stream);
+
+/*
+ * Momentum-SGD update, in place (Algorithm 1: theta <- theta - eta * gradient; momentum form of
+ * the large-minibatch recipe the paper follows, Section 4.1):
+ *     g = grad + weight_decay * w;  v = momentum * v + g;
+ *     w = w - lr * (nesterov ? g + momentum * v : v)
+ *   master_w, momentum_v  [n] fp32, updated in place;  grad [n] fp32, read only
+ *   lowp_w_out  [n] bf16 copy of the updated weights, or NULL
+ * The caller calls it once per group of tensors that share lr / weight_decay.
+ */
+int codistill_sgd_step(float* master_w, float* momentum_v, const float* grad, void* lowp_w_out,
+                       int64_t n, float lr, float momentum, float weight_decay, int nesterov,
+                       void* stream);
+
+/* ---- introspection ----------------------------------------------------------------------- */
+/* The fused op list and where each tensor lives inside a save_for_backward workspace, so that
+ * tools and tests can read intermediate activations and activation gradients after a forward /
+ * backward pair.  Tensor 0 is the input batch; the last op writes the logits (not in the workspace). */
+enum { CD_OP_CONV = 0, CD_OP_BN = 1, CD_OP_MAXPOOL = 2, CD_OP_GAP = 3, CD_OP_LINEAR = 4 };
+typedef struct {
+  int32_t kind;            /* CD_OP_*                                                           */
+  int32_t x, y;            /* input / output tensor ids                                         */
+  int32_t res;             /* CD_OP_BN: tensor added before the ReLU, else -1                   */
+  int32_t relu;            /* CD_OP_CONV (after the bias) and CD_OP_BN: ReLU fused into the op  */
+  int32_t param_w, param_b;/* parameter indices: weight + bias, or BN scale + shift; -1 if none */
+  int32_t k, stride, pad;  /* window of CD_OP_CONV / CD_OP_MAXPOOL                              */
+  int64_t stats_offset;    /* CD_OP_BN: byte offset of fp32 [4][C] = mean, invstd, scale, shift */
+} cd_op_info;
+typedef struct {
+  int32_t h, w, c;         /* per-sample shape; the tensor is [batch][h][w][c]                  */
+  int32_t is_f32;          /* 1 for the logits, else the model dtype                            */
+  int64_t act_offset;      /* byte offset of the activation in the workspace, -1 if not there   */
+  int64_t grad_offset;     /* byte offset of its gradient, -1 if not there                      */
+} cd_act_info;
+int codistill_graph_size(const cd_model* m, int64_t* n_ops, int64_t* n_tensors);
+int codistill_op_info(const cd_model* m, int64_t batch, int64_t idx, cd_op_info* out);
+int codistill_tensor_info(const cd_model* m, int64_t batch, int64_t idx, cd_act_info* out);
+
+/* ---- measurement aid -------------------------------------------------------------------- */
+/* kernel classes for the built-in timer */
+enum {
+  CD_K_CONV_FPROP = 0, CD_K_CONV_DGRAD = 1, CD_K_CONV_WGRAD = 2, CD_K_NORM = 3,
+  CD_K_GLUE = 4, CD_K_LINEAR = 5, CD_K_LOSS = 6, CD_K_SGD = 7, CD_K_COUNT = 8
+};
+/* When enabled, every launch is bracketed by HIP events on the launch stream and the events are
+ * kept in a host-side pool (created at enable time; no device memory).  host. */
+int codistill_profile_enable(int on);
+/* Synchronises the recorded events, adds the elapsed times to the per-class totals and clears the
+ * pool.  host. */
+int codistill_profile_collect(void);
+/* totals since the last reset: milliseconds, launches, algorithmic flops and bytes. host outputs. */
+int codistill_profile_get(int kernel_class, double* ms, int64_t* launches, double* flops, double* bytes);
+int codistill_profile_reset(void);
+
+const char* codistill_last_error(void);
+const char* codistill_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CODISTILL_H */

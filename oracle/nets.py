@@ -19,6 +19,17 @@ gives as 8e8 bits) without defining them; these are the standard definitions:
 An architecture is (param_table, ops).  param_table is an ordered list of
 (name, shape, kind, fan_in); ops is a list of dicts over integer tensor ids
 (tensor 0 is the input image batch, the last op writes the logits).
+
+Reduced-precision storage.  The workloads run "bf16 compute with fp32 master
+weights": arithmetic is exact here (float64), but `forward` takes an optional
+`store` function that is applied to every tensor such a pipeline writes to
+memory - the output of each convolution, of each BatchNorm group (BatchNorm,
+then the residual add and ReLU that follow it, if any), and of the pools; ops
+carry a `stored` flag saying whether their output is such a tensor.  With
+store = round-to-bf16 the result is what an exact-arithmetic bf16-storage
+pipeline computes; the tests use it to measure how much of a deviation from the
+float64 result is due to storage rounding alone.  store=None (the default) is
+the plain float64 definition.
 """
 import numpy as np
 from . import layers as L
@@ -43,41 +54,41 @@ class Arch:
         w = self._p(name + ".w", (cout, k, k, cin), "conv_w", cin * k * k)
         b = self._p(name + ".b", (cout,), "bias") if bias else None
         y = self._t()
-        self.ops.append(dict(op="conv", x=x, y=y, w=w, b=b, stride=stride, pad=pad))
+        self.ops.append(dict(op="conv", x=x, y=y, w=w, b=b, stride=stride, pad=pad, stored=True))
         return y
 
-    def bn(self, x, name, c):
+    def bn(self, x, name, c, stored=False):
         g = self._p(name + ".gamma", (c,), "bn_gamma")
         b = self._p(name + ".beta", (c,), "bn_beta")
         y = self._t()
-        self.ops.append(dict(op="bn", x=x, y=y, gamma=g, beta=b))
+        self.ops.append(dict(op="bn", x=x, y=y, gamma=g, beta=b, stored=stored))
         return y
 
     def relu(self, x):
         y = self._t()
-        self.ops.append(dict(op="relu", x=x, y=y))
+        self.ops.append(dict(op="relu", x=x, y=y, stored=True))
         return y
 
     def add(self, a, b):
         y = self._t()
-        self.ops.append(dict(op="add", a=a, b=b, y=y))
+        self.ops.append(dict(op="add", a=a, b=b, y=y, stored=False))
         return y
 
     def maxpool(self, x, k, stride, pad):
         y = self._t()
-        self.ops.append(dict(op="maxpool", x=x, y=y, k=k, stride=stride, pad=pad))
+        self.ops.append(dict(op="maxpool", x=x, y=y, k=k, stride=stride, pad=pad, stored=True))
         return y
 
     def gap(self, x):
         y = self._t()
-        self.ops.append(dict(op="gap", x=x, y=y))
+        self.ops.append(dict(op="gap", x=x, y=y, stored=True))
         return y
 
     def linear(self, x, name, fin, fout):
         w = self._p(name + ".w", (fout, fin), "linear_w", fin)
         b = self._p(name + ".b", (fout,), "bias")
         y = self._t()
-        self.ops.append(dict(op="linear", x=x, y=y, w=w, b=b))
+        self.ops.append(dict(op="linear", x=x, y=y, w=w, b=b, stored=False))
         return y
 
     def n_params(self):
@@ -110,7 +121,7 @@ def resnet20(classes=10, widths=(16, 32, 64), blocks=(3, 3, 3)):
             u = a.bn(u, p + ".bn2", wd)
             if stride != 1 or cin != wd:
                 sc = a.conv(t, p + ".down.conv", cin, wd, 1, stride, 0, bias=False)
-                sc = a.bn(sc, p + ".down.bn", wd)
+                sc = a.bn(sc, p + ".down.bn", wd, stored=True)
             else:
                 sc = t
             t = a.relu(a.add(u, sc))
@@ -138,7 +149,7 @@ def resnet50(classes=1000, widths=(64, 128, 256, 512), blocks=(3, 4, 6, 3), stem
             u = a.bn(u, p + ".bn3", 4 * wd)
             if bi == 0:
                 sc = a.conv(t, p + ".down.conv", cin, 4 * wd, 1, stride, 0, bias=False)
-                sc = a.bn(sc, p + ".down.bn", 4 * wd)
+                sc = a.bn(sc, p + ".down.bn", 4 * wd, stored=True)
             else:
                 sc = t
             t = a.relu(a.add(u, sc))
@@ -148,11 +159,14 @@ def resnet50(classes=1000, widths=(64, 128, 256, 512), blocks=(3, 4, 6, 3), stem
     return a
 
 
-def forward(arch, params, x):
-    """Training-mode forward.  params: dict name -> float64 array.  Returns (logits, tape)."""
+def forward(arch, params, x, store=None):
+    """Training-mode forward.  params: dict name -> float64 array.  Returns (logits, tape).
+    store: optional function applied to the tensors a reduced-precision pipeline keeps in memory."""
     T = {0: np.asarray(x, dtype=np.float64)}
     cache = {}
     for i, o in enumerate(arch.ops):
+        if i > 0 and store is not None and arch.ops[i - 1]["stored"]:
+            T[arch.ops[i - 1]["y"]] = store(T[arch.ops[i - 1]["y"]])
         k = o["op"]
         if k == "conv":
             b = params[o["b"]] if o["b"] else None

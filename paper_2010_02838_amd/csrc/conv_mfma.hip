@@ -1,0 +1,494 @@
+// bf16 implicit-GEMM convolution on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16), fp32
+// accumulation.  These are the contractions of the forward and backward passes of the paper's
+// networks (Section 3: ResNet50): fprop, dgrad and wgrad of every convolution.
+//
+//   fprop  y[m][n]  = sum_k im2col(x)[m][k] * w[n][k]          m = (b,ho,wo), k = (r,s,c)
+//   dgrad  dx[m][c] = sum_k gather(dy)[m][k] * wt[c][k]        m = (b,h,w),   k = (r,s,n)
+//   wgrad  dw[n][k] = sum_m dy[m][n] * im2col(x)[m][k]
+//
+// fprop and dgrad share one kernel: both operands are contiguous along the contraction index, so
+// a lane's 8-element MFMA operand is one 16-byte load.  Block = 4 waves; global -> registers ->
+// LDS (double buffered, 80-byte row pitch: conflict-free 16-byte reads) -> MFMA; the fp32 tile is
+// rounded to bf16, transposed through LDS and written as full 16-byte vectors along the channels.
+// The MFMA "A" operand is the filter tile and "B" the activation tile, so that a lane's 16
+// accumulators run along the output channels of one pixel.
+#include "kernels.h"
+
+namespace cd {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+constexpr int BK = 32;        // contraction elements per main-loop step
+constexpr int PITCH = BK + 8; // LDS row pitch in elements (80 bytes)
+
+struct IgemmArgs {
+  const bf16_t* src;  // gathered tensor [B][Hs][Ws][Cs]
+  const bf16_t* wt;   // [N][K]
+  bf16_t* dst;        // [M][N]
+  int64_t M;
+  int N, K;
+  int Hs, Ws, Cs, Hd, Wd, kh, kw, stride, pad;
+  int accumulate;
+  int ntiles;
+};
+
+// Blocks are handed to the 8 XCDs round-robin; renumber so that consecutive logical tiles (which
+// share activation rows and halos) run on the same XCD and meet in its L2.
+__device__ inline unsigned xcd_remap(unsigned bid, unsigned nblocks) {
+  const unsigned xcd = bid & 7u, idx = bid >> 3;
+  const unsigned per = nblocks >> 3, rem = nblocks & 7u;
+  return xcd * per + (xcd < rem ? xcd : rem) + idx;
+}
+
+__device__ inline uint32_t pack_bf16x2(float a, float b) {
+  return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
+}
+
+// MODE 0: fprop gather (hs = hd*stride - pad + r).  MODE 1: dgrad gather (hs = (hd + pad - r)/stride).
+template <int MODE, int BM, int BN, int WAVES_M, int WAVES_N>
+__global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
+  constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+  constexpr int TM = WM / 32, TN = WN / 32;
+  constexpr int AV = BM / 64;                  // activation vectors per thread per step
+  constexpr int BV = BN >= 64 ? BN / 64 : 1;   // filter vectors per thread per step
+  constexpr int MAIN_BYTES = 2 * (BM + BN) * PITCH * 2;
+  constexpr int EPITCH = WN + 8;
+  constexpr int EPI_BYTES = 4 * WM * EPITCH * 2;
+  constexpr int SMEM = MAIN_BYTES > EPI_BYTES ? MAIN_BYTES : EPI_BYTES;
+  __shared__ __attribute__((aligned(16))) char smem[SMEM];
+  bf16_t* As = reinterpret_cast<bf16_t*>(smem);                  // [2][BM][PITCH]
+  bf16_t* Bs = As + 2 * BM * PITCH;                              // [2][BN][PITCH]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm0 = (wave % WAVES_M) * WM, wn0 = (wave / WAVES_M) * WN;
+  const unsigned tile = xcd_remap(blockIdx.x, gridDim.x);
+  const int64_t m0 = (int64_t)(tile / a.ntiles) * BM;
+  const int n0 = (int)(tile % a.ntiles) * BN;
+
+  // ---- per-thread gather state -----------------------------------------------------------------
+  const int kvec = tid & 3, lrow = tid >> 2;   // this thread's 16-byte column and first row in a tile
+  int64_t pixbase[AV];
+  int h0[AV], w0[AV];
+  bool rowok[AV];
+#pragma unroll
+  for (int j = 0; j < AV; j++) {
+    const int64_t m = m0 + lrow + 64 * j;
+    rowok[j] = m < a.M;
+    const int64_t mm = rowok[j] ? m : 0;
+    const int wd = (int)(mm % a.Wd);
+    const int64_t q = mm / a.Wd;
+    const int hd = (int)(q % a.Hd);
+    pixbase[j] = (q / a.Hd) * a.Hs * a.Ws;
+    if (MODE == 0) { h0[j] = hd * a.stride - a.pad; w0[j] = wd * a.stride - a.pad; }
+    else { h0[j] = hd + a.pad; w0[j] = wd + a.pad; }
+  }
+  int kc, kr, ks;  // channel offset inside the tap, tap row, tap column of this thread's vector
+  {
+    const int k = kvec * 8;
+    const int tap = k / a.Cs;
+    kc = k - tap * a.Cs;
+    kr = tap / a.kw;
+    ks = tap - kr * a.kw;
+  }
+  const bf16_t* wrow[BV];
+  bool wok[BV];
+#pragma unroll
+  for (int j = 0; j < BV; j++) {
+    const int n = n0 + lrow + 64 * j;
+    wok[j] = (lrow + 64 * j) < BN && n < a.N;
+    wrow[j] = a.wt + (int64_t)(wok[j] ? n : 0) * a.K + kvec * 8;
+  }
+  const int sshift = a.stride == 2 ? 1 : 0;
+
+  uint4 ra[AV], rb[BV];
+  auto gload = [&](int kt) {
+    const bool kok = kr < a.kh;
+#pragma unroll
+    for (int j = 0; j < AV; j++) {
+      int hs, ws;
+      bool ok = rowok[j] && kok;
+      if (MODE == 0) {
+        hs = h0[j] + kr;
+        ws = w0[j] + ks;
+      } else {
+        const int hn = h0[j] - kr, wn = w0[j] - ks;
+        ok = ok && hn >= 0 && wn >= 0 && ((hn | wn) & (a.stride - 1)) == 0;
+        hs = hn >> sshift;
+        ws = wn >> sshift;
+      }
+      ok = ok && hs >= 0 && hs < a.Hs && ws >= 0 && ws < a.Ws;
+      ra[j] = make_uint4(0, 0, 0, 0);
+      if (ok) ra[j] = *reinterpret_cast<const uint4*>(a.src + (pixbase[j] + (int64_t)hs * a.Ws + ws) * a.Cs + kc);
+    }
+#pragma unroll
+    for (int j = 0; j < BV; j++) {
+      rb[j] = make_uint4(0, 0, 0, 0);
+      if (wok[j] && kok) rb[j] = *reinterpret_cast<const uint4*>(wrow[j] + (int64_t)kt * BK);
+    }
+    // advance this thread's (tap, channel) position by BK
+    kc += BK;
+    while (kc >= a.Cs) {
+      kc -= a.Cs;
+      if (++ks == a.kw) { ks = 0; ++kr; }
+    }
+  };
+  auto lstore = [&](int buf) {
+#pragma unroll
+    for (int j = 0; j < AV; j++)
+      *reinterpret_cast<uint4*>(As + ((buf * BM) + lrow + 64 * j) * PITCH + kvec * 8) = ra[j];
+#pragma unroll
+    for (int j = 0; j < BV; j++)
+      if ((lrow + 64 * j) < BN)
+        *reinterpret_cast<uint4*>(Bs + ((buf * BN) + lrow + 64 * j) * PITCH + kvec * 8) = rb[j];
+  };
+
+  f32x16_t acc[TN][TM];
+#pragma unroll
+  for (int i = 0; i < TN; i++)
+#pragma unroll
+    for (int j = 0; j < TM; j++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) acc[i][j][v] = 0.f;
+
+  const int KT = (a.K + BK - 1) / BK;
+  gload(0);
+  lstore(0);
+  __syncthreads();
+  const int frow = lane & 31, fk = (lane >> 5) * 8;
+  for (int kt = 0; kt < KT; kt++) {
+    const int cur = kt & 1;
+    if (kt + 1 < KT) gload(kt + 1);
+#pragma unroll
+    for (int kk = 0; kk < BK; kk += 16) {
+      bf16x8_t wf[TN], xf[TM];
+#pragma unroll
+      for (int i = 0; i < TN; i++)
+        wf[i] = *reinterpret_cast<const bf16x8_t*>(Bs + ((cur * BN) + wn0 + i * 32 + frow) * PITCH + kk + fk);
+#pragma unroll
+      for (int j = 0; j < TM; j++)
+        xf[j] = *reinterpret_cast<const bf16x8_t*>(As + ((cur * BM) + wm0 + j * 32 + frow) * PITCH + kk + fk);
+#pragma unroll
+      for (int i = 0; i < TN; i++)
+#pragma unroll
+        for (int j = 0; j < TM; j++)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], xf[j], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < KT) lstore(cur ^ 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue: fp32 -> bf16, transpose through LDS, 16-byte stores along the channels -------------
+  // accumulator layout: lane holds pixel column (lane % 32); register v holds channel
+  // 8*(v/4) + 4*(lane/32) + v%4 of the 32x32 tile
+  bf16_t* stage = reinterpret_cast<bf16_t*>(smem) + wave * WM * EPITCH;
+#pragma unroll
+  for (int i = 0; i < TN; i++)
+#pragma unroll
+    for (int j = 0; j < TM; j++)
+#pragma unroll
+      for (int g = 0; g < 4; g++) {
+        uint2 p;
+        p.x = pack_bf16x2(acc[i][j][4 * g + 0], acc[i][j][4 * g + 1]);
+        p.y = pack_bf16x2(acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+        *reinterpret_cast<uint2*>(stage + (j * 32 + frow) * EPITCH + i * 32 + 8 * g + 4 * (lane >> 5)) = p;
+      }
+  __syncthreads();
+  constexpr int LPR = WN / 8;        // lanes per output row
+  constexpr int RPP = 64 / LPR;      // rows per pass
+  const int er = lane / LPR, ec = (lane % LPR) * 8;
+#pragma unroll
+  for (int p = 0; p < WM / RPP; p++) {
+    const int row = p * RPP + er;
+    const int64_t m = m0 + wm0 + row;
+    const int n = n0 + wn0 + ec;
+    if (m < a.M && n < a.N) {
+      uint4 v = *reinterpret_cast<const uint4*>(stage + row * EPITCH + ec);
+      bf16_t* dp = a.dst + m * a.N + n;
+      if (a.accumulate) {
+        const uint4 o = *reinterpret_cast<const uint4*>(dp);
+        const uint32_t vv[4] = {v.x, v.y, v.z, v.w}, oo[4] = {o.x, o.y, o.z, o.w};
+        uint32_t r[4];
+#pragma unroll
+        for (int q = 0; q < 4; q++)
+          r[q] = pack_bf16x2(__uint_as_float(vv[q] << 16) + __uint_as_float(oo[q] << 16),
+                             __uint_as_float(vv[q] & 0xffff0000u) + __uint_as_float(oo[q] & 0xffff0000u));
+        v = make_uint4(r[0], r[1], r[2], r[3]);
+      }
+      *reinterpret_cast<uint4*>(dp) = v;
+    }
+  }
+}
+
+template <int MODE>
+static void launch_igemm(IgemmArgs a, hipStream_t s) {
+  if (a.N > 64) {
+    a.ntiles = (int)cdiv(a.N, 128);
+    const int64_t blocks = cdiv(a.M, 128) * a.ntiles;
+    hipLaunchKernelGGL((igemm_kernel<MODE, 128, 128, 2, 2>), dim3((unsigned)blocks), dim3(256), 0, s, a);
+  } else if (a.N > 32) {
+    a.ntiles = 1;
+    hipLaunchKernelGGL((igemm_kernel<MODE, 256, 64, 4, 1>), dim3((unsigned)cdiv(a.M, 256)), dim3(256), 0, s, a);
+  } else {
+    a.ntiles = 1;
+    hipLaunchKernelGGL((igemm_kernel<MODE, 256, 32, 4, 1>), dim3((unsigned)cdiv(a.M, 256)), dim3(256), 0, s, a);
+  }
+}
+
+bool conv_mfma_supported(const ConvGeom& g) {
+  return g.Cin % 8 == 0 && g.Cout % 8 == 0 && (g.stride == 1 || g.stride == 2) && g.kh == g.kw &&
+         g.B * g.H * g.W * (int64_t)g.Cin < (1LL << 40);
+}
+
+void conv_fprop_mfma(const bf16_t* x, const bf16_t* w, bf16_t* y, const ConvGeom& g, hipStream_t s) {
+  IgemmArgs a;
+  a.src = x; a.wt = w; a.dst = y;
+  a.M = g.M(); a.N = g.Cout; a.K = g.K();
+  a.Hs = g.H; a.Ws = g.W; a.Cs = g.Cin; a.Hd = g.Ho; a.Wd = g.Wo;
+  a.kh = g.kh; a.kw = g.kw; a.stride = g.stride; a.pad = g.pad;
+  a.accumulate = 0; a.ntiles = 1;
+  launch_igemm<0>(a, s);
+}
+
+void conv_dgrad_mfma(const bf16_t* dy, const bf16_t* wt, bf16_t* dx, const ConvGeom& g, bool accumulate,
+                     hipStream_t s) {
+  IgemmArgs a;
+  a.src = dy; a.wt = wt; a.dst = dx;
+  a.M = g.B * g.H * g.W; a.N = g.Cin; a.K = g.kh * g.kw * g.Cout;
+  a.Hs = g.Ho; a.Ws = g.Wo; a.Cs = g.Cout; a.Hd = g.H; a.Wd = g.W;
+  a.kh = g.kh; a.kw = g.kw; a.stride = g.stride; a.pad = g.pad;
+  a.accumulate = accumulate ? 1 : 0; a.ntiles = 1;
+  launch_igemm<1>(a, s);
+}
+
+// ---- wgrad ------------------------------------------------------------------------------------------
+// dw[n][k] = sum_m dy[m][n] * im2col(x)[m][k].  The contraction runs over pixels, which is the slow
+// axis of both operands in memory.  Tiles are staged in LDS as they lie in memory ([pixel][channel],
+// 16-byte vectors along the channels) and read back with the gfx950 LDS transpose load
+// (ds_read_b64_tr_b16): in every group of 16 lanes, lane i receives element (i & 3) of the four
+// 8-byte chunks addressed by lanes (i >> 2), 4 + (i >> 2), 8 + (i >> 2), 12 + (i >> 2).  Pointing
+// chunk 4e+q at pixel e, channels 4q..4q+3 therefore hands lane i four consecutive pixels of channel
+// i, which is the MFMA operand layout.  The pixel range is split over blockIdx.y; partial sums are
+// written per split and added by a second kernel in a fixed order.
+typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+#define CD_LDS __attribute__((address_space(3)))
+
+struct WgradArgs {
+  const bf16_t* x;   // [B][H][W][Cin]
+  const bf16_t* dy;  // [M][N]
+  float* out;        // [splits][N][K]
+  int64_t M, m_per_split;
+  int N, K;
+  int H, W, Cin, Ho, Wo, kh, kw, stride, pad;
+  int ktiles;
+};
+
+constexpr int WG_MS = 32;  // pixels per main-loop step
+
+template <int BN, int BKK>
+__global__ void __launch_bounds__(256) wgrad_kernel(WgradArgs a) {
+  constexpr int PN = BN + 32, PK = BKK + 32;   // pitches (elements): rows 16 banks apart, conflict-free reads
+  constexpr int NVR = BN / 8, KVR = BKK / 8;   // 16-byte vectors per tile row
+  constexpr int DV = WG_MS * NVR / 256, XV = WG_MS * KVR / 256;  // vectors per thread per step
+  constexpr int DROWS = 256 / NVR, XROWS = 256 / KVR;
+  constexpr int WNT = BN / 2, WKT = BKK / 2;   // wave tile (2 x 2 waves)
+  constexpr int TN = WNT / 32, TK = WKT / 32;
+  __shared__ __attribute__((aligned(16))) bf16_t Dy[2][WG_MS][PN];
+  __shared__ __attribute__((aligned(16))) bf16_t Xs[2][WG_MS][PK];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wn0 = (wave & 1) * WNT, wk0 = (wave >> 1) * WKT;
+  const int n0 = (blockIdx.x / a.ktiles) * BN, k0 = (blockIdx.x % a.ktiles) * BKK;
+  const int64_t mbeg = (int64_t)blockIdx.y * a.m_per_split;
+  const int64_t mend = mbeg + a.m_per_split < a.M ? mbeg + a.m_per_split : a.M;
+
+  // dy loader: fixed channel vector, DV rows
+  const int dnv = tid % NVR, drow = tid / NVR;
+  const bool dnok = n0 + dnv * 8 < a.N;
+  // x loader: fixed (tap, channel) vector, XV rows, pixel coordinates advanced incrementally
+  const int xkv = tid % KVR, xrow = tid / KVR;
+  const int k = k0 + xkv * 8;
+  const bool kok = k < a.K;
+  const int tap = kok ? k / a.Cin : 0;
+  const int kc = k - tap * a.Cin, kr = tap / a.kw, ks = tap - (tap / a.kw) * a.kw;
+  int pb[XV], ph[XV], pw[XV];
+#pragma unroll
+  for (int j = 0; j < XV; j++) {
+    const int64_t m = mbeg + xrow + XROWS * j;
+    pw[j] = (int)(m % a.Wo);
+    const int64_t q = m / a.Wo;
+    ph[j] = (int)(q % a.Ho);
+    pb[j] = (int)(q / a.Ho);
+  }
+
+  uint4 rd[DV], rx[XV];
+  auto gload = [&](int64_t ms) {
+#pragma unroll
+    for (int j = 0; j < DV; j++) {
+      const int64_t m = ms + drow + DROWS * j;
+      rd[j] = make_uint4(0, 0, 0, 0);
+      if (dnok && m < mend) rd[j] = *reinterpret_cast<const uint4*>(a.dy + m * a.N + n0 + dnv * 8);
+    }
+#pragma unroll
+    for (int j = 0; j < XV; j++) {
+      const int64_t m = ms + xrow + XROWS * j;
+      const int hi = ph[j] * a.stride - a.pad + kr, wi = pw[j] * a.stride - a.pad + ks;
+      rx[j] = make_uint4(0, 0, 0, 0);
+      if (kok && m < mend && hi >= 0 && hi < a.H && wi >= 0 && wi < a.W)
+        rx[j] = *reinterpret_cast<const uint4*>(a.x + (((int64_t)pb[j] * a.H + hi) * a.W + wi) * a.Cin + kc);
+      // next step: WG_MS pixels further
+      pw[j] += WG_MS;
+      while (pw[j] >= a.Wo) {
+        pw[j] -= a.Wo;
+        if (++ph[j] == a.Ho) { ph[j] = 0; ++pb[j]; }
+      }
+    }
+  };
+  auto lstore = [&](int buf) {
+#pragma unroll
+    for (int j = 0; j < DV; j++) *reinterpret_cast<uint4*>(&Dy[buf][drow + DROWS * j][dnv * 8]) = rd[j];
+#pragma unroll
+    for (int j = 0; j < XV; j++) *reinterpret_cast<uint4*>(&Xs[buf][xrow + XROWS * j][xkv * 8]) = rx[j];
+  };
+
+  f32x16_t acc[TN][TK];
+#pragma unroll
+  for (int i = 0; i < TN; i++)
+#pragma unroll
+    for (int j = 0; j < TK; j++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) acc[i][j][v] = 0.f;
+
+  // transpose-load addressing of this lane inside a 16-pixel x 32-channel fragment
+  const int grp = lane >> 4, li = lane & 15;
+  const int tr_m = 8 * (grp >> 1) + (li >> 2);      // pixel row (second load: +4)
+  const int tr_c = 16 * (grp & 1) + 4 * (li & 3);   // first of the 4 channels this lane points at
+
+  const int64_t steps = (mend - mbeg + WG_MS - 1) / WG_MS;
+  if (steps > 0) {
+    gload(mbeg);
+    lstore(0);
+  }
+  __syncthreads();
+  for (int64_t st = 0; st < steps; st++) {
+    const int cur = (int)(st & 1);
+    if (st + 1 < steps) gload(mbeg + (st + 1) * WG_MS);
+#pragma unroll
+    for (int ms = 0; ms < WG_MS; ms += 16) {
+      bf16x8_t df[TN], xf[TK];
+#pragma unroll
+      for (int i = 0; i < TN; i++) {
+        const bf16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+            (CD_LDS bf16x4_t*)(&Dy[cur][ms + tr_m][wn0 + i * 32 + tr_c]));
+        const bf16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+            (CD_LDS bf16x4_t*)(&Dy[cur][ms + tr_m + 4][wn0 + i * 32 + tr_c]));
+        df[i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      }
+#pragma unroll
+      for (int j = 0; j < TK; j++) {
+        const bf16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+            (CD_LDS bf16x4_t*)(&Xs[cur][ms + tr_m][wk0 + j * 32 + tr_c]));
+        const bf16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+            (CD_LDS bf16x4_t*)(&Xs[cur][ms + tr_m + 4][wk0 + j * 32 + tr_c]));
+        xf[j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      }
+#pragma unroll
+      for (int i = 0; i < TN; i++)
+#pragma unroll
+        for (int j = 0; j < TK; j++)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(df[i], xf[j], acc[i][j], 0, 0, 0);
+    }
+    if (st + 1 < steps) lstore(cur ^ 1);
+    __syncthreads();
+  }
+
+  float* out = a.out + (int64_t)blockIdx.y * a.N * a.K;
+#pragma unroll
+  for (int i = 0; i < TN; i++)
+#pragma unroll
+    for (int j = 0; j < TK; j++) {
+      const int kk = k0 + wk0 + j * 32 + (lane & 31);
+#pragma unroll
+      for (int v = 0; v < 16; v++) {
+        const int n = n0 + wn0 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        if (n < a.N && kk < a.K) out[(int64_t)n * a.K + kk] = acc[i][j][v];
+      }
+    }
+}
+
+__global__ void __launch_bounds__(256) wgrad_reduce_kernel(const float* __restrict__ part, float* __restrict__ out,
+                                                           int64_t n, int splits) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  float s = 0.f;
+  for (int j = 0; j < splits; j++) s += part[(int64_t)j * n + i];
+  out[i] = s;
+}
+
+void conv_wgrad_mfma(const bf16_t* x, const bf16_t* dy, float* dw, const ConvGeom& g, float* partials,
+                     size_t partials_bytes, hipStream_t s) {
+  WgradArgs a;
+  a.x = x; a.dy = dy;
+  a.M = g.M(); a.N = g.Cout; a.K = g.K();
+  a.H = g.H; a.W = g.W; a.Cin = g.Cin; a.Ho = g.Ho; a.Wo = g.Wo;
+  a.kh = g.kh; a.kw = g.kw; a.stride = g.stride; a.pad = g.pad;
+  const int bn = a.N > 64 ? 128 : 64, bk = a.K > 64 ? 128 : 64;
+  const int ntiles = (int)cdiv(a.N, bn);
+  a.ktiles = (int)cdiv(a.K, bk);
+  const int64_t tiles = (int64_t)ntiles * a.ktiles;
+  const int64_t nk = (int64_t)a.N * a.K;
+  int64_t splits = cdiv(1024, tiles);
+  const int64_t max_by_m = cdiv(a.M, 4 * WG_MS);
+  if (splits > max_by_m) splits = max_by_m;
+  const int64_t max_by_mem = (int64_t)(partials_bytes / (nk * sizeof(float)));
+  if (splits > max_by_mem) splits = max_by_mem;
+  if (splits < 1) splits = 1;
+  a.m_per_split = cdiv(cdiv(a.M, splits), WG_MS) * WG_MS;
+  splits = cdiv(a.M, a.m_per_split);
+  a.out = splits == 1 ? dw : partials;
+  dim3 grid((unsigned)tiles, (unsigned)splits);
+  if (bn == 128 && bk == 128) hipLaunchKernelGGL((wgrad_kernel<128, 128>), grid, dim3(256), 0, s, a);
+  else if (bn == 128) hipLaunchKernelGGL((wgrad_kernel<128, 64>), grid, dim3(256), 0, s, a);
+  else if (bk == 128) hipLaunchKernelGGL((wgrad_kernel<64, 128>), grid, dim3(256), 0, s, a);
+  else hipLaunchKernelGGL((wgrad_kernel<64, 64>), grid, dim3(256), 0, s, a);
+  if (splits > 1)
+    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)cdiv(nk, 256)), dim3(256), 0, s, partials, dw, nk,
+                       (int)splits);
+}
+
+// ---- layout helpers ---------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) pad_c3_to_c8_k(const bf16_t* __restrict__ in, bf16_t* __restrict__ out,
+                                                      int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  const uint32_t a = in[3 * i], b = in[3 * i + 1], c = in[3 * i + 2];
+  reinterpret_cast<uint4*>(out)[i] = make_uint4(a | (b << 16), c, 0u, 0u);
+}
+void pad_c3_to_c8(const bf16_t* in, bf16_t* out, int64_t n, hipStream_t s) {
+  hipLaunchKernelGGL(pad_c3_to_c8_k, dim3((unsigned)cdiv(n, 256)), dim3(256), 0, s, in, out, n);
+}
+__global__ void __launch_bounds__(256) unpad_c8_to_c3_k(const float* __restrict__ in, float* __restrict__ out,
+                                                        int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= 3 * n) return;
+  out[i] = in[(i / 3) * 8 + i % 3];
+}
+void unpad_c8_to_c3(const float* in, float* out, int64_t n, hipStream_t s) {
+  hipLaunchKernelGGL(unpad_c8_to_c3_k, dim3((unsigned)cdiv(3 * n, 256)), dim3(256), 0, s, in, out, n);
+}
+__global__ void __launch_bounds__(256) transpose_weight_k(const bf16_t* __restrict__ w, bf16_t* __restrict__ wt,
+                                                          int cout, int taps, int cin) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (int64_t)cout * taps * cin) return;
+  const int n = i % cout;
+  const int64_t q = i / cout;
+  const int tap = q % taps;
+  const int c = q / taps;
+  wt[i] = w[((int64_t)n * taps + tap) * cin + c];
+}
+void transpose_weight(const bf16_t* w, bf16_t* wt, int cout, int taps, int cin, hipStream_t s) {
+  const int64_t n = (int64_t)cout * taps * cin;
+  hipLaunchKernelGGL(transpose_weight_k, dim3((unsigned)cdiv(n, 256)), dim3(256), 0, s, w, wt, cout, taps, cin);
+}
+
+}  // namespace cd

@@ -1,0 +1,73 @@
+// Host launchers of the layer kernels.  `dtype` is CD_F32 or CD_BF16 and selects the storage type
+// of activations, activation gradients and parameters; statistics, logits and parameter gradients
+// are always fp32.  Nothing here allocates or synchronises.
+#pragma once
+#include "common.h"
+
+namespace cd {
+
+struct ConvGeom {
+  int64_t B;
+  int H, W, Cin, Ho, Wo, Cout, kh, kw, stride, pad;
+  __host__ __device__ int64_t M() const { return B * Ho * Wo; }
+  __host__ __device__ int K() const { return kh * kw * Cin; }
+};
+
+constexpr float kBnEps = 1e-5f;
+constexpr size_t kPartialsBytes = 128u << 20;  // reduction / split-K partials inside the workspace
+
+// ---- plain kernels: any shape, fp32 or bf16 storage, fp32 arithmetic ------------------------------
+void conv_fprop_simple(int dtype, const void* x, const void* w, const void* bias, void* y, const ConvGeom& g,
+                       bool relu, hipStream_t s);
+void conv_dgrad_simple(int dtype, const void* dy, const void* w, void* dx, const ConvGeom& g, bool accumulate,
+                       hipStream_t s);
+void conv_wgrad_simple(int dtype, const void* x, const void* dy, float* dw, const ConvGeom& g, hipStream_t s);
+void relu_bwd_inplace(int dtype, void* dy, const void* y, int64_t n, hipStream_t s);
+void colsum(int dtype, const void* a, int64_t M, int C, float* out, float* partials, hipStream_t s);
+
+// BatchNorm with batch statistics over M rows of C channels, y = relu?(gamma*xhat + beta + res?).
+// stats: [4][C] fp32 = mean, invstd, scale, shift (kept for the backward pass).
+void bn_forward(int dtype, const void* x, const void* gamma, const void* beta, const void* res, bool relu, void* y,
+                int64_t M, int C, float* stats, float* partials, hipStream_t s);
+// dz = dy * (relu ? y > 0 : 1); dgamma = sum dz*xhat; dbeta = sum dz;
+// dx = gamma*invstd*(dz - dbeta/M - xhat*dgamma/M); dres = dz.  coef: [3][C] fp32 scratch.
+void bn_backward(int dtype, const void* dy, const void* y, const void* x, const void* gamma, const float* stats,
+                 bool relu, void* dx, bool acc_dx, void* dres, bool acc_dres, float* dgamma, float* dbeta,
+                 float* coef, float* partials, int64_t M, int C, hipStream_t s);
+
+void maxpool_fwd(int dtype, const void* x, void* y, int64_t B, int H, int W, int C, int k, int stride, int pad,
+                 hipStream_t s);
+void maxpool_bwd(int dtype, const void* x, const void* dy, void* dx, bool accumulate, int64_t B, int H, int W, int C,
+                 int k, int stride, int pad, hipStream_t s);
+void gap_fwd(int dtype, const void* x, void* y, int64_t B, int HW, int C, hipStream_t s);
+void gap_bwd(int dtype, const void* dy, void* dx, bool accumulate, int64_t B, int HW, int C, hipStream_t s);
+void linear_fwd(int dtype, const void* x, const void* w, const void* b, float* y, int64_t B, int F, int C,
+                hipStream_t s);
+void linear_bwd(int dtype, const void* x, const void* w, const float* dy, void* dx, bool accumulate, float* dw,
+                float* db, int64_t B, int F, int C, hipStream_t s);
+
+struct Gap { int64_t off; int32_t len; };
+void zero_gaps(float* base, const Gap* gaps, int n, hipStream_t s);
+
+}  // namespace cd
+
+namespace cd {
+// ---- bf16 MFMA implicit-GEMM convolution (conv_mfma.hip) -----------------------------------------
+// All need the channel count of the gathered tensor to be a multiple of 8 (16-byte vectors).
+bool conv_mfma_supported(const ConvGeom& g);
+// y[M][Cout] = im2col(x)[M][K] * w[Cout][K]^T
+void conv_fprop_mfma(const bf16_t* x, const bf16_t* w, bf16_t* y, const ConvGeom& g, hipStream_t s);
+// dx[B*H*W][Cin] (+)= gather(dy)[.][kh*kw*Cout] * wt[Cin][kh*kw*Cout]^T, wt = weights re-laid-out by
+// transpose_weight
+void conv_dgrad_mfma(const bf16_t* dy, const bf16_t* wt, bf16_t* dx, const ConvGeom& g, bool accumulate,
+                     hipStream_t s);
+// dw[Cout][K] = dy[M][Cout]^T * im2col(x)[M][K], split over M with fp32 partials reduced in fixed order
+void conv_wgrad_mfma(const bf16_t* x, const bf16_t* dy, float* dw, const ConvGeom& g, float* partials,
+                     size_t partials_bytes, hipStream_t s);
+// [n][3] -> [n][8] zero padded (input images and the taps of a 3-channel filter)
+void pad_c3_to_c8(const bf16_t* in, bf16_t* out, int64_t n, hipStream_t s);
+// fp32 [n][8] -> [n][3]
+void unpad_c8_to_c3(const float* in, float* out, int64_t n, hipStream_t s);
+// w[Cout][taps][Cin] -> wt[Cin][taps][Cout]
+void transpose_weight(const bf16_t* w, bf16_t* wt, int cout, int taps, int cin, hipStream_t s);
+}  // namespace cd

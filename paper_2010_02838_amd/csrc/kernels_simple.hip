@@ -1,0 +1,303 @@
+// Plain layer kernels: one thread per output element, fp32 arithmetic, fp32 or bf16 storage.
+// They define the layers for any shape; the fp32 models run on them entirely, the bf16 models
+// use them for the small layers around the MFMA convolutions.
+#include "kernels.h"
+
+namespace cd {
+
+#define CD_DISPATCH_T(dtype, ...)                         \
+  do {                                                    \
+    if ((dtype) == CD_BF16) { typedef bf16_t T; __VA_ARGS__; } \
+    else { typedef float T; __VA_ARGS__; }                \
+  } while (0)
+
+static inline dim3 grid1d(int64_t n, int block = 256) { return dim3((unsigned)cdiv(n, block)); }
+
+// ------------------------------------------------------------------------------ convolution
+template <typename T>
+__global__ void __launch_bounds__(256) conv_fprop_simple_k(const T* __restrict__ x, const T* __restrict__ w,
+                                                           const T* __restrict__ bias, T* __restrict__ y, ConvGeom g,
+                                                           int relu) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= g.M() * g.Cout) return;
+  const int n = idx % g.Cout;
+  int64_t m = idx / g.Cout;
+  const int wo = m % g.Wo; m /= g.Wo;
+  const int ho = m % g.Ho;
+  const int64_t b = m / g.Ho;
+  float acc = bias ? Cvt<T>::ld(bias[n]) : 0.f;
+  for (int r = 0; r < g.kh; r++) {
+    const int hi = ho * g.stride - g.pad + r;
+    if (hi < 0 || hi >= g.H) continue;
+    for (int s = 0; s < g.kw; s++) {
+      const int wi = wo * g.stride - g.pad + s;
+      if (wi < 0 || wi >= g.W) continue;
+      const T* xp = x + ((b * g.H + hi) * g.W + wi) * g.Cin;
+      const T* wp = w + (((int64_t)n * g.kh + r) * g.kw + s) * g.Cin;
+      for (int c = 0; c < g.Cin; c++) acc += Cvt<T>::ld(xp[c]) * Cvt<T>::ld(wp[c]);
+    }
+  }
+  if (relu) acc = fmaxf(acc, 0.f);
+  y[idx] = Cvt<T>::st(acc);
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256) conv_dgrad_simple_k(const T* __restrict__ dy, const T* __restrict__ w,
+                                                           T* __restrict__ dx, ConvGeom g, int accumulate) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= g.B * g.H * g.W * g.Cin) return;
+  const int c = idx % g.Cin;
+  int64_t p = idx / g.Cin;
+  const int wi = p % g.W; p /= g.W;
+  const int hi = p % g.H;
+  const int64_t b = p / g.H;
+  float acc = 0.f;
+  for (int r = 0; r < g.kh; r++) {
+    const int hn = hi + g.pad - r;
+    if (hn < 0 || hn % g.stride) continue;
+    const int ho = hn / g.stride;
+    if (ho >= g.Ho) continue;
+    for (int s = 0; s < g.kw; s++) {
+      const int wn = wi + g.pad - s;
+      if (wn < 0 || wn % g.stride) continue;
+      const int wo = wn / g.stride;
+      if (wo >= g.Wo) continue;
+      const T* dp = dy + ((b * g.Ho + ho) * g.Wo + wo) * g.Cout;
+      const T* wp = w + ((int64_t)r * g.kw + s) * g.Cin + c;
+      const int64_t wstride = (int64_t)g.kh * g.kw * g.Cin;
+      for (int n = 0; n < g.Cout; n++) acc += Cvt<T>::ld(dp[n]) * Cvt<T>::ld(wp[n * wstride]);
+    }
+  }
+  if (accumulate) acc += Cvt<T>::ld(dx[idx]);
+  dx[idx] = Cvt<T>::st(acc);
+}
+
+// one block per weight element, threads stride over the B*Ho*Wo output positions
+template <typename T>
+__global__ void __launch_bounds__(256) conv_wgrad_simple_k(const T* __restrict__ x, const T* __restrict__ dy,
+                                                           float* __restrict__ dw, ConvGeom g) {
+  __shared__ float red[4];
+  int64_t e = blockIdx.x;
+  const int c = e % g.Cin; e /= g.Cin;
+  const int s = e % g.kw; e /= g.kw;
+  const int r = e % g.kh;
+  const int n = e / g.kh;
+  float acc = 0.f;
+  const int64_t M = g.M();
+  for (int64_t m = threadIdx.x; m < M; m += 256) {
+    int64_t q = m;
+    const int wo = q % g.Wo; q /= g.Wo;
+    const int ho = q % g.Ho;
+    const int64_t b = q / g.Ho;
+    const int hi = ho * g.stride - g.pad + r, wi = wo * g.stride - g.pad + s;
+    if (hi < 0 || hi >= g.H || wi < 0 || wi >= g.W) continue;
+    acc += Cvt<T>::ld(dy[m * g.Cout + n]) * Cvt<T>::ld(x[((b * g.H + hi) * g.W + wi) * g.Cin + c]);
+  }
+  acc = wave_sum(acc);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) dw[blockIdx.x] = red[0] + red[1] + red[2] + red[3];
+}
+
+void conv_fprop_simple(int dtype, const void* x, const void* w, const void* bias, void* y, const ConvGeom& g,
+                       bool relu, hipStream_t s) {
+  CD_DISPATCH_T(dtype, hipLaunchKernelGGL(conv_fprop_simple_k<T>, grid1d(g.M() * g.Cout), dim3(256), 0, s,
+                                          (const T*)x, (const T*)w, (const T*)bias, (T*)y, g, (int)relu));
+}
+void conv_dgrad_simple(int dtype, const void* dy, const void* w, void* dx, const ConvGeom& g, bool accumulate,
+                       hipStream_t s) {
+  CD_DISPATCH_T(dtype, hipLaunchKernelGGL(conv_dgrad_simple_k<T>, grid1d(g.B * g.H * g.W * g.Cin), dim3(256), 0, s,
+                                          (const T*)dy, (const T*)w, (T*)dx, g, (int)accumulate));
+}
+void conv_wgrad_simple(int dtype, const void* x, const void* dy, float* dw, const ConvGeom& g, hipStream_t s) {
+  const int64_t n = (int64_t)g.Cout * g.K();
+  CD_DISPATCH_T(dtype, hipLaunchKernelGGL(conv_wgrad_simple_k<T>, dim3((unsigned)n), dim3(256), 0, s, (const T*)x,
+                                          (const T*)dy, dw, g));
+}
+
+// ------------------------------------------------------------------------------------- glue
+template <typename T>
+__global__ void __launch_bounds__(256) relu_bwd_k(T* __restrict__ dy, const T* __restrict__ y, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n && !(Cvt<T>::ld(y[i]) > 0.f)) dy[i] = Cvt<T>::st(0.f);
+}
+void relu_bwd_inplace(int dtype, void* dy, const void* y, int64_t n, hipStream_t s) {
+  CD_DISPATCH_T(dtype, hipLaunchKernelGGL(relu_bwd_k<T>, grid1d(n), dim3(256), 0, s, (T*)dy, (const T*)y, n));
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256) maxpool_fwd_k(const T* __restrict__ x, T* __restrict__ y, int64_t B, int H,
+                                                     int W, int C, int Ho, int Wo, int k, int stride, int pad) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= B * Ho * Wo * C) return;
+  const int c = idx % C;
+  int64_t p = idx / C;
+  const int wo = p % Wo; p /= Wo;
+  const int ho = p % Ho;
+  const int64_t b = p / Ho;
+  float best = -INFINITY;
+  for (int r = 0; r < k; r++) {
+    const int hi = ho * stride - pad + r;
+    if (hi < 0 || hi >= H) continue;
+    for (int s = 0; s < k; s++) {
+      const int wi = wo * stride - pad + s;
+      if (wi < 0 || wi >= W) continue;
+      best = fmaxf(best, Cvt<T>::ld(x[((b * H + hi) * W + wi) * C + c]));
+    }
+  }
+  y[idx] = Cvt<T>::st(best);
+}
+
+// Gradient goes to the first maximum of each window in row-major tap order (recomputed here).
+template <typename T>
+__global__ void __launch_bounds__(256) maxpool_bwd_k(const T* __restrict__ x, const T* __restrict__ dy,
+                                                     T* __restrict__ dx, int accumulate, int64_t B, int H, int W,
+                                                     int C, int Ho, int Wo, int k, int stride, int pad) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= B * H * W * C) return;
+  const int c = idx % C;
+  int64_t p = idx / C;
+  const int wi = p % W; p /= W;
+  const int hi = p % H;
+  const int64_t b = p / H;
+  float acc = 0.f;
+  for (int ho = 0; ho < Ho; ho++) {
+    const int h0 = ho * stride - pad;
+    if (hi < h0 || hi >= h0 + k) continue;
+    for (int wo = 0; wo < Wo; wo++) {
+      const int w0 = wo * stride - pad;
+      if (wi < w0 || wi >= w0 + k) continue;
+      float best = -INFINITY;
+      int bh = -1, bw = -1;
+      for (int r = 0; r < k; r++) {
+        const int hh = h0 + r;
+        if (hh < 0 || hh >= H) continue;
+        for (int s = 0; s < k; s++) {
+          const int ww = w0 + s;
+          if (ww < 0 || ww >= W) continue;
+          const float v = Cvt<T>::ld(x[((b * H + hh) * W + ww) * C + c]);
+          if (v > best) { best = v; bh = hh; bw = ww; }
+        }
+      }
+      if (bh == hi && bw == wi) acc += Cvt<T>::ld(dy[((b * Ho + ho) * Wo + wo) * C + c]);
+    }
+  }
+  if (accumulate) acc += Cvt<T>::ld(dx[idx]);
+  dx[idx] = Cvt<T>::st(acc);
+}
+
+void maxpool_fwd(int dtype, const void* x, void* y, int64_t B, int H, int W, int C, int k, int stride, int pad,
+                 hipStream_t s) {
+  const int Ho = (H + 2 * pad - k) / stride + 1, Wo = (W + 2 * pad - k) / stride + 1;
+  CD_DISPATCH_T(dtype, hipLaunchKernelGGL(maxpool_fwd_k<T>, grid1d(B * Ho * Wo * C), dim3(256), 0, s, (const T*)x,
+                                          (T*)y, B, H, W, C, Ho, Wo, k, stride, pad));
+}
+void maxpool_bwd(int dtype, const void* x, const void* dy, void* dx, bool accumulate, int64_t B, int H, int W, int C,
+                 int k, int stride, int pad, hipStream_t s) {
+  const int Ho = (H + 2 * pad - k) / stride + 1, Wo = (W + 2 * pad - k) / stride + 1;
+  CD_DISPATCH_T(dtype, hipLaunchKernelGGL(maxpool_bwd_k<T>, grid1d(B * H * W * C), dim3(256), 0, s, (const T*)x,
+                                          (const T*)dy, (T*)dx, (int)accumulate, B, H, W, C, Ho, Wo, k, stride, pad));
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256) gap_fwd_k(const T* __restrict__ x, T* __restrict__ y, int64_t B, int HW, int C) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= B * C) return;
+  const int c = idx % C;
+  const int64_t b = idx / C;
+  float acc = 0.f;
+  for (int i = 0; i < HW; i++) acc += Cvt<T>::ld(x[(b * HW + i) * C + c]);
+  y[idx] = Cvt<T>::st(acc / (float)HW);
+}
+template <typename T>
+__global__ void __launch_bounds__(256) gap_bwd_k(const T* __restrict__ dy, T* __restrict__ dx, int accumulate,
+                                                 int64_t B, int HW, int C) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= B * HW * C) return;
+  const int c = idx % C;
+  const int64_t b = idx / ((int64_t)HW * C);
+  float v = Cvt<T>::ld(dy[b * C + c]) / (float)HW;
+  if (accumulate) v += Cvt<T>::ld(dx[idx]);
+  dx[idx] = Cvt<T>::st(v);
+}
+void gap_fwd(int dtype, const void* x, void* y, int64_t B, int HW, int C, hipStream_t s) {
+  CD_DISPATCH_T(dtype, hipLaunchKernelGGL(gap_fwd_k<T>, grid1d(B * C), dim3(256), 0, s, (const T*)x, (T*)y, B, HW, C));
+}
+void gap_bwd(int dtype, const void* dy, void* dx, bool accumulate, int64_t B, int HW, int C, hipStream_t s) {
+  CD_DISPATCH_T(dtype, hipLaunchKernelGGL(gap_bwd_k<T>, grid1d(B * HW * C), dim3(256), 0, s, (const T*)dy, (T*)dx,
+                                          (int)accumulate, B, HW, C));
+}
+
+// ----------------------------------------------------------------------------------- linear
+// one wave per output element: lanes stride over the F input features
+template <typename T>
+__global__ void __launch_bounds__(256) linear_fwd_k(const T* __restrict__ x, const T* __restrict__ w,
+                                                    const T* __restrict__ bias, float* __restrict__ y, int64_t B,
+                                                    int F, int C) {
+  const int64_t o = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (o >= B * C) return;
+  const int c = o % C;
+  const int64_t b = o / C;
+  float acc = 0.f;
+  for (int f = threadIdx.x & 63; f < F; f += 64) acc += Cvt<T>::ld(x[b * F + f]) * Cvt<T>::ld(w[(int64_t)c * F + f]);
+  acc = wave_sum(acc);
+  if ((threadIdx.x & 63) == 0) y[o] = acc + (bias ? Cvt<T>::ld(bias[c]) : 0.f);
+}
+template <typename T>
+__global__ void __launch_bounds__(256) linear_dx_k(const float* __restrict__ dy, const T* __restrict__ w,
+                                                   T* __restrict__ dx, int accumulate, int64_t B, int F, int C) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= B * F) return;
+  const int f = idx % F;
+  const int64_t b = idx / F;
+  float acc = 0.f;
+  for (int c = 0; c < C; c++) acc += dy[b * C + c] * Cvt<T>::ld(w[(int64_t)c * F + f]);
+  if (accumulate) acc += Cvt<T>::ld(dx[idx]);
+  dx[idx] = Cvt<T>::st(acc);
+}
+template <typename T>
+__global__ void __launch_bounds__(256) linear_dw_k(const float* __restrict__ dy, const T* __restrict__ x,
+                                                   float* __restrict__ dw, float* __restrict__ db, int64_t B, int F,
+                                                   int C) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (int64_t)C * (F + 1)) return;
+  const int f = idx % (F + 1);
+  const int c = idx / (F + 1);
+  float acc = 0.f;
+  if (f < F) {
+    for (int64_t b = 0; b < B; b++) acc += dy[b * C + c] * Cvt<T>::ld(x[b * F + f]);
+    dw[(int64_t)c * F + f] = acc;
+  } else {
+    for (int64_t b = 0; b < B; b++) acc += dy[b * C + c];
+    db[c] = acc;
+  }
+}
+void linear_fwd(int dtype, const void* x, const void* w, const void* b, float* y, int64_t B, int F, int C,
+                hipStream_t s) {
+  CD_DISPATCH_T(dtype, hipLaunchKernelGGL(linear_fwd_k<T>, grid1d(B * C, 4), dim3(256), 0, s, (const T*)x, (const T*)w,
+                                          (const T*)b, y, B, F, C));
+}
+void linear_bwd(int dtype, const void* x, const void* w, const float* dy, void* dx, bool accumulate, float* dw,
+                float* db, int64_t B, int F, int C, hipStream_t s) {
+  CD_DISPATCH_T(dtype, {
+    hipLaunchKernelGGL(linear_dx_k<T>, grid1d(B * F), dim3(256), 0, s, dy, (const T*)w, (T*)dx, (int)accumulate, B, F, C);
+    hipLaunchKernelGGL(linear_dw_k<T>, grid1d((int64_t)C * (F + 1)), dim3(256), 0, s, dy, (const T*)x, dw, db, B, F, C);
+  });
+}
+
+// ----------------------------------------------------------------------------- padding gaps
+struct GapList { Gap g[128]; int n; };
+__global__ void __launch_bounds__(64) zero_gaps_k(float* base, GapList l) {
+  const int i = blockIdx.x;
+  if (i < l.n && (int)threadIdx.x < l.g[i].len) base[l.g[i].off + threadIdx.x] = 0.f;
+}
+void zero_gaps(float* base, const Gap* gaps, int n, hipStream_t s) {
+  for (int i = 0; i < n; i += 128) {
+    GapList l;
+    l.n = n - i < 128 ? n - i : 128;
+    for (int j = 0; j < l.n; j++) l.g[j] = gaps[i + j];
+    hipLaunchKernelGGL(zero_gaps_k, dim3(l.n), dim3(64), 0, s, base, l);
+  }
+}
+
+}  // namespace cd

@@ -1,0 +1,373 @@
+// Fused codistillation loss: row-wise log-softmax, cross-entropy, distillation term and the
+// gradient with respect to the local logits, in one pass over HBM.
+//
+// Paper, Algorithm 1: the objective is L(y, z) + alpha * mean over peers of D(z, z').  D is the
+// mean squared error between raw logits (appendix "Implementation Details") or the KL divergence
+// of the prior work named in Section 2.  Peer logits are constants (Section 3).
+//
+// HBM-bound: each logit of z and z' is read once and each gradient element written once
+// (12 bytes per logit pair).  A row lives in registers between the reduction and the gradient:
+// one group of TPR threads owns one row, every thread holds V float4 of z and V float4 of z'.
+#include "common.h"
+#include <math.h>
+
+namespace cd {
+
+struct LossArgs {
+  const float* z;
+  const float* zp[CD_LOSS_MAX_PEERS];
+  const int32_t* targets;
+  float* dz;
+  int64_t rows, cols;
+  float alpha, eps;
+  int32_t dist, mse_reduction, ignore_index, n_peers;
+  int32_t* meta;    // [0] number of valid rows, [1] status bits
+  float* row_task;  // [rows]
+  float* row_dist;  // [rows] un-normalised per-row distillation sums (summed over peers)
+};
+
+// ---- step 1: count valid rows ---------------------------------------------------------------
+__global__ void __launch_bounds__(1024) loss_prep_kernel(LossArgs a) {
+  __shared__ int s_cnt[16], s_bad[16];
+  int cnt = 0, bad = 0;
+  for (int64_t r = threadIdx.x; r < a.rows; r += 1024) {
+    int t = a.targets[r];
+    if (t == a.ignore_index) continue;
+    if (t < 0 || t >= a.cols) bad = 1; else cnt++;
+  }
+  for (int o = 32; o > 0; o >>= 1) {
+    cnt += __shfl_xor(cnt, o, 64);
+    bad |= __shfl_xor(bad, o, 64);
+  }
+  if ((threadIdx.x & 63) == 0) { s_cnt[threadIdx.x >> 6] = cnt; s_bad[threadIdx.x >> 6] = bad; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int c = 0, b = 0;
+    for (int i = 0; i < 16; i++) { c += s_cnt[i]; b |= s_bad[i]; }
+    a.meta[0] = c;
+    a.meta[1] = b;
+  }
+}
+
+// Reduce NV values at once over a group of TPR threads (TPR = 64: one wave, no LDS; otherwise the
+// group is the whole block).  MAXMASK bit i set -> value i is reduced with max, else with sum.
+template <int TPR, int NV, unsigned MAXMASK>
+__device__ inline void group_reduce(float (&v)[NV], float* smem) {
+#pragma unroll
+  for (int i = 0; i < NV; i++) v[i] = ((MAXMASK >> i) & 1) ? wave_max(v[i]) : wave_sum(v[i]);
+  if (TPR > 64) {
+    constexpr int NW = TPR / 64;
+    const int w = threadIdx.x >> 6;
+    __syncthreads();  // smem may still be read from a previous call
+    if ((threadIdx.x & 63) == 0) {
+#pragma unroll
+      for (int i = 0; i < NV; i++) smem[i * NW + w] = v[i];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < NV; i++) {
+      float r = smem[i * NW];
+      for (int k = 1; k < NW; k++) r = ((MAXMASK >> i) & 1) ? fmaxf(r, smem[i * NW + k]) : r + smem[i * NW + k];
+      v[i] = r;
+    }
+  }
+}
+
+__device__ inline bool row_target(const LossArgs& a, int64_t row, int& t) {
+  t = a.targets[row];
+  return t != a.ignore_index && t >= 0 && t < a.cols;
+}
+
+// MODE: 0 = no peer, 1 = MSE between logits, 2 = KL(p'||p).  At most one peer.
+template <int TPR, int V, int MODE>
+__global__ void __launch_bounds__((TPR > 256 ? TPR : 256)) loss_row_kernel(LossArgs a) {
+  constexpr int BLOCK = TPR > 256 ? TPR : 256;
+  constexpr int RPB = BLOCK / TPR;
+  __shared__ float smem[5 * 16];
+  const int g = threadIdx.x / TPR;      // row group inside the block
+  const int lane = threadIdx.x % TPR;   // thread inside the group
+  const int64_t row = (int64_t)blockIdx.x * RPB + g;
+  if (RPB > 1 && row >= a.rows) return;  // only wave-sized groups can leave early (no barriers)
+  const int64_t cols = a.cols;
+  const float* __restrict__ zr = a.z + row * cols;
+  const float* __restrict__ pr = MODE ? a.zp[0] + row * cols : nullptr;
+  float* __restrict__ outr = a.dz + row * cols;
+  int t;
+  const bool valid = row_target(a, row, t);
+  const int nvalid = a.meta[0];
+
+  if (!valid) {  // uniform over the group
+#pragma unroll
+    for (int i = 0; i < V; i++) {
+      int64_t c = ((int64_t)i * TPR + lane) * 4;
+      if (c < cols) *reinterpret_cast<float4*>(outr + c) = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    if (lane == 0) { a.row_task[row] = 0.f; a.row_dist[row] = 0.f; }
+    return;
+  }
+
+  float4 x[V], y[V];
+  const float zt = zr[t];
+#pragma unroll
+  for (int i = 0; i < V; i++) {
+    int64_t c = ((int64_t)i * TPR + lane) * 4;
+    if (c < cols) {
+      x[i] = *reinterpret_cast<const float4*>(zr + c);
+      if (MODE) y[i] = *reinterpret_cast<const float4*>(pr + c);
+    } else {
+      x[i] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+      if (MODE) y[i] = x[i];
+    }
+  }
+  // row maxima
+  float mx[2] = {-INFINITY, -INFINITY};
+#pragma unroll
+  for (int i = 0; i < V; i++) {
+    mx[0] = fmaxf(mx[0], fmaxf(fmaxf(x[i].x, x[i].y), fmaxf(x[i].z, x[i].w)));
+    if (MODE == 2) mx[1] = fmaxf(mx[1], fmaxf(fmaxf(y[i].x, y[i].y), fmaxf(y[i].z, y[i].w)));
+  }
+  group_reduce<TPR, 2, 3u>(mx, smem);
+  const float m = mx[0], mp = mx[1];
+  // sums: [0] sum exp(z-m)  [1] sum z  [2] MSE: sum (z-z')^2 | KL: sum exp(z'-m')  [3] KL: sum exp(z'-m')(z'-z)
+  float s[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int i = 0; i < V; i++) {
+    int64_t c = ((int64_t)i * TPR + lane) * 4;
+    if (c < cols) {
+      const float xv[4] = {x[i].x, x[i].y, x[i].z, x[i].w};
+      const float yv[4] = {MODE ? y[i].x : 0.f, MODE ? y[i].y : 0.f, MODE ? y[i].z : 0.f, MODE ? y[i].w : 0.f};
+#pragma unroll
+      for (int k = 0; k < 4; k++) {
+        s[0] += __expf(xv[k] - m);
+        s[1] += xv[k];
+        if (MODE == 1) { float d = xv[k] - yv[k]; s[2] += d * d; }
+        if (MODE == 2) { float e = __expf(yv[k] - mp); s[2] += e; s[3] += e * (yv[k] - xv[k]); }
+      }
+    }
+  }
+  group_reduce<TPR, 4, 0u>(s, smem);
+  const float lse = m + logf(s[0]);
+  float lsep = 0.f;
+  if (MODE == 2) lsep = mp + logf(s[2]);
+  if (lane == 0) {
+    a.row_task[row] = lse - (1.f - a.eps) * zt - (a.eps / (float)cols) * s[1];
+    float d = 0.f;
+    if (MODE == 1) d = s[2];
+    if (MODE == 2) d = s[3] / s[2] - lsep + lse;
+    a.row_dist[row] = d;
+  }
+  // gradient
+  const float invn = 1.f / (float)nvalid;
+  const float epsc = a.eps / (float)cols;
+  float cm = 0.f;
+  if (MODE == 1) cm = a.alpha * 2.f * invn / (a.mse_reduction == CD_MEAN_ALL ? (float)cols : 1.f);
+  const float onehot = (1.f - a.eps) * invn;
+#pragma unroll
+  for (int i = 0; i < V; i++) {
+    int64_t c = ((int64_t)i * TPR + lane) * 4;
+    if (c < cols) {
+      const float xv[4] = {x[i].x, x[i].y, x[i].z, x[i].w};
+      const float yv[4] = {MODE ? y[i].x : 0.f, MODE ? y[i].y : 0.f, MODE ? y[i].z : 0.f, MODE ? y[i].w : 0.f};
+      float o[4];
+#pragma unroll
+      for (int k = 0; k < 4; k++) {
+        float p = __expf(xv[k] - lse);
+        float gk = (p - epsc) * invn;
+        if (MODE == 1) gk += cm * (xv[k] - yv[k]);
+        if (MODE == 2) gk += a.alpha * invn * (p - __expf(yv[k] - lsep));
+        if (c + k == t) gk -= onehot;
+        o[k] = gk;
+      }
+      *reinterpret_cast<float4*>(outr + c) = make_float4(o[0], o[1], o[2], o[3]);
+    }
+  }
+}
+
+// Any column count, any number of peers: one block per row, several passes over the row (later
+// passes hit in cache).  Scalar accesses, so rows need no alignment.
+__global__ void __launch_bounds__(256) loss_row_generic_kernel(LossArgs a) {
+  __shared__ float smem[5 * 4];
+  __shared__ float s_lsep[CD_LOSS_MAX_PEERS];
+  const int64_t row = blockIdx.x;
+  const int64_t cols = a.cols;
+  const float* zr = a.z + row * cols;
+  float* outr = a.dz + row * cols;
+  int t;
+  const bool valid = row_target(a, row, t);
+  const int nvalid = a.meta[0];
+  if (!valid) {
+    for (int64_t c = threadIdx.x; c < cols; c += 256) outr[c] = 0.f;
+    if (threadIdx.x == 0) { a.row_task[row] = 0.f; a.row_dist[row] = 0.f; }
+    return;
+  }
+  const float zt = zr[t];
+  float v1[1] = {-INFINITY};
+  for (int64_t c = threadIdx.x; c < cols; c += 256) v1[0] = fmaxf(v1[0], zr[c]);
+  group_reduce<256, 1, 1u>(v1, smem);
+  const float m = v1[0];
+  float v2[2] = {0.f, 0.f};
+  for (int64_t c = threadIdx.x; c < cols; c += 256) { float x = zr[c]; v2[0] += __expf(x - m); v2[1] += x; }
+  group_reduce<256, 2, 0u>(v2, smem);
+  const float lse = m + logf(v2[0]);
+  float dsum = 0.f;
+  for (int j = 0; j < a.n_peers; j++) {
+    const float* pr = a.zp[j] + row * cols;
+    if (a.dist == CD_DIST_MSE_LOGITS) {
+      float q[1] = {0.f};
+      for (int64_t c = threadIdx.x; c < cols; c += 256) { float d = zr[c] - pr[c]; q[0] += d * d; }
+      group_reduce<256, 1, 0u>(q, smem);
+      dsum += q[0];
+    } else {
+      float q[1] = {-INFINITY};
+      for (int64_t c = threadIdx.x; c < cols; c += 256) q[0] = fmaxf(q[0], pr[c]);
+      group_reduce<256, 1, 1u>(q, smem);
+      const float mp = q[0];
+      float w[2] = {0.f, 0.f};
+      for (int64_t c = threadIdx.x; c < cols; c += 256) {
+        float y = pr[c], e = __expf(y - mp);
+        w[0] += e;
+        w[1] += e * (y - zr[c]);
+      }
+      group_reduce<256, 2, 0u>(w, smem);
+      const float lsep = mp + logf(w[0]);
+      dsum += w[1] / w[0] - lsep + lse;
+      if (threadIdx.x == 0) s_lsep[j] = lsep;
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    a.row_task[row] = lse - (1.f - a.eps) * zt - (a.eps / (float)cols) * v2[1];
+    a.row_dist[row] = dsum;
+  }
+  const float invn = 1.f / (float)nvalid;
+  const float epsc = a.eps / (float)cols;
+  const float wj = a.n_peers > 0 ? 1.f / (float)a.n_peers : 0.f;
+  const float cm = a.alpha * wj * 2.f * invn / (a.mse_reduction == CD_MEAN_ALL ? (float)cols : 1.f);
+  const float ck = a.alpha * wj * invn;
+  for (int64_t c = threadIdx.x; c < cols; c += 256) {
+    const float x = zr[c];
+    const float p = __expf(x - lse);
+    float gk = (p - epsc) * invn;
+    for (int j = 0; j < a.n_peers; j++) {
+      const float y = a.zp[j][row * cols + c];
+      if (a.dist == CD_DIST_MSE_LOGITS) gk += cm * (x - y);
+      else gk += ck * (p - __expf(y - s_lsep[j]));
+    }
+    if (c == t) gk -= (1.f - a.eps) * invn;
+    outr[c] = gk;
+  }
+}
+
+// ---- step 3: deterministic sum of the per-row terms ------------------------------------------
+__global__ void __launch_bounds__(256) loss_finalize_kernel(LossArgs a, float* loss_out) {
+  __shared__ double s_t[256], s_d[256];
+  double st = 0.0, sd = 0.0;
+  for (int64_t r = threadIdx.x; r < a.rows; r += 256) { st += (double)a.row_task[r]; sd += (double)a.row_dist[r]; }
+  s_t[threadIdx.x] = st;
+  s_d[threadIdx.x] = sd;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if ((int)threadIdx.x < o) { s_t[threadIdx.x] += s_t[threadIdx.x + o]; s_d[threadIdx.x] += s_d[threadIdx.x + o]; }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    const int n = a.meta[0];
+    double task = 0.0, dist = 0.0;
+    if (n > 0) {
+      task = s_t[0] / n;
+      if (a.n_peers > 0) {
+        double denom = (double)n * a.n_peers;
+        if (a.dist == CD_DIST_MSE_LOGITS && a.mse_reduction == CD_MEAN_ALL) denom *= (double)a.cols;
+        dist = s_d[0] / denom;
+      }
+    }
+    loss_out[0] = (float)(task + (double)a.alpha * dist);
+    loss_out[1] = (float)task;
+    loss_out[2] = (float)dist;
+    reinterpret_cast<int32_t*>(loss_out)[3] = a.meta[1];
+  }
+}
+
+template <int TPR, int V>
+static void launch_rows(const LossArgs& a, int mode, hipStream_t s) {
+  constexpr int BLOCK = TPR > 256 ? TPR : 256;
+  constexpr int RPB = BLOCK / TPR;
+  dim3 grid((unsigned)cdiv(a.rows, RPB));
+  if (mode == 0) hipLaunchKernelGGL((loss_row_kernel<TPR, V, 0>), grid, dim3(BLOCK), 0, s, a);
+  else if (mode == 1) hipLaunchKernelGGL((loss_row_kernel<TPR, V, 1>), grid, dim3(BLOCK), 0, s, a);
+  else hipLaunchKernelGGL((loss_row_kernel<TPR, V, 2>), grid, dim3(BLOCK), 0, s, a);
+}
+
+}  // namespace cd
+
+using namespace cd;
+
+static size_t loss_scratch_need(int64_t rows) { return 16 + align_up((size_t)rows * 4, 16) * 2; }
+
+extern "C" int codistill_loss_scratch_bytes(int64_t rows, int64_t cols, size_t* bytes) {
+  CD_REQUIRE(bytes != nullptr, "loss_scratch_bytes: bytes is NULL");
+  CD_REQUIRE(rows >= 1 && rows <= 2147483647LL, "loss_scratch_bytes: rows=%lld out of range", (long long)rows);
+  CD_REQUIRE(cols >= 1 && cols <= (1LL << 24), "loss_scratch_bytes: cols=%lld out of range", (long long)cols);
+  *bytes = loss_scratch_need(rows);
+  return CD_OK;
+}
+
+extern "C" int codistill_loss_grad(const float* z_local, const float* const* z_peers, const int32_t* targets,
+                                   int64_t rows, int64_t cols, const cd_loss_cfg* cfg, float* loss_out,
+                                   float* dz_out, void* scratch, size_t scratch_bytes, void* stream) {
+  CD_REQUIRE(z_local && targets && cfg && loss_out && dz_out && scratch, "loss_grad: NULL pointer argument");
+  CD_REQUIRE(rows >= 1 && rows <= 2147483647LL, "loss_grad: rows=%lld out of range [1, 2^31-1]", (long long)rows);
+  CD_REQUIRE(cols >= 1 && cols <= (1LL << 24), "loss_grad: cols=%lld out of range [1, 2^24]", (long long)cols);
+  CD_REQUIRE(cfg->n_peers >= 0 && cfg->n_peers <= CD_LOSS_MAX_PEERS, "loss_grad: n_peers=%d out of range [0, %d]",
+             cfg->n_peers, CD_LOSS_MAX_PEERS);
+  CD_REQUIRE(cfg->dist_kind == CD_DIST_MSE_LOGITS || cfg->dist_kind == CD_DIST_KL, "loss_grad: unknown dist_kind %d",
+             cfg->dist_kind);
+  CD_REQUIRE(cfg->mse_reduction == CD_MEAN_ALL || cfg->mse_reduction == CD_MEAN_ROWS,
+             "loss_grad: unknown mse_reduction %d", cfg->mse_reduction);
+  CD_REQUIRE(cfg->label_smoothing >= 0.f && cfg->label_smoothing < 1.f, "loss_grad: label_smoothing %g outside [0,1)",
+             (double)cfg->label_smoothing);
+  CD_REQUIRE(cfg->alpha == cfg->alpha, "loss_grad: alpha is NaN");
+  CD_REQUIRE(cfg->n_peers == 0 || z_peers != nullptr, "loss_grad: z_peers is NULL with n_peers=%d", cfg->n_peers);
+  CD_REQUIRE(aligned16(z_local) && aligned16(dz_out) && aligned16(scratch) && aligned16(loss_out),
+             "loss_grad: pointers must be 16-byte aligned");
+  for (int j = 0; j < cfg->n_peers; j++)
+    CD_REQUIRE(z_peers[j] != nullptr && aligned16(z_peers[j]), "loss_grad: z_peers[%d] is NULL or misaligned", j);
+  if (scratch_bytes < loss_scratch_need(rows))
+    return set_error(CD_ERR_WORKSPACE_TOO_SMALL, "loss_grad: scratch %zu < %zu bytes", scratch_bytes,
+                     loss_scratch_need(rows));
+
+  LossArgs a;
+  a.z = z_local;
+  for (int j = 0; j < CD_LOSS_MAX_PEERS; j++) a.zp[j] = j < cfg->n_peers ? z_peers[j] : nullptr;
+  a.targets = targets;
+  a.dz = dz_out;
+  a.rows = rows;
+  a.cols = cols;
+  a.alpha = cfg->alpha;
+  a.eps = cfg->label_smoothing;
+  a.dist = cfg->dist_kind;
+  a.mse_reduction = cfg->mse_reduction;
+  a.ignore_index = cfg->ignore_index;
+  a.n_peers = cfg->n_peers;
+  char* sc = static_cast<char*>(scratch);
+  a.meta = reinterpret_cast<int32_t*>(sc);
+  a.row_task = reinterpret_cast<float*>(sc + 16);
+  a.row_dist = reinterpret_cast<float*>(sc + 16 + align_up((size_t)rows * 4, 16));
+  hipStream_t s = static_cast<hipStream_t>(stream);
+
+  const double bytes = (double)rows * cols * 4.0 * (2 + cfg->n_peers);
+  ProfScope prof(CD_K_LOSS, s, (double)rows * cols * 12.0, bytes);
+  hipLaunchKernelGGL(loss_prep_kernel, dim3(1), dim3(1024), 0, s, a);
+  const int mode = cfg->n_peers == 0 ? 0 : (cfg->dist_kind == CD_DIST_MSE_LOGITS ? 1 : 2);
+  const bool fast = cols % 4 == 0 && cols <= 32768 && cfg->n_peers <= 1;
+  if (!fast) {
+    hipLaunchKernelGGL(loss_row_generic_kernel, dim3((unsigned)rows), dim3(256), 0, s, a);
+  } else if (cols <= 256) launch_rows<64, 1>(a, mode, s);
+  else if (cols <= 1024) launch_rows<64, 4>(a, mode, s);
+  else if (cols <= 4096) launch_rows<256, 4>(a, mode, s);
+  else if (cols <= 8192) launch_rows<1024, 2>(a, mode, s);
+  else if (cols <= 16384) launch_rows<1024, 4>(a, mode, s);
+  else launch_rows<1024, 8>(a, mode, s);
+  hipLaunchKernelGGL(loss_finalize_kernel, dim3(1), dim3(256), 0, s, a, loss_out);
+  return check_launch("loss_grad");
+}

@@ -1,0 +1,69 @@
+// Host-side model description: parameter table, fused op list, workspace plan.
+#pragma once
+#include "common.h"
+#include <string>
+#include <vector>
+
+namespace cd {
+
+enum OpKind { OP_CONV, OP_BN, OP_MAXPOOL, OP_GAP, OP_LINEAR };
+
+struct TensorDesc {
+  int h = 1, w = 1, c = 1;  // per-sample shape; a [B, F] tensor has h = w = 1
+  bool f32 = false;         // logits are fp32 whatever the model dtype
+  int64_t per_sample() const { return (int64_t)h * w * c; }
+};
+
+struct Op {
+  OpKind kind;
+  int x = -1, y = -1;  // input / output tensor ids
+  int res = -1;        // OP_BN: tensor added before the ReLU (-1: none)
+  bool relu = false;   // OP_CONV (after the bias) and OP_BN
+  int pw = -1, pb = -1;  // parameter indices: conv/linear weight + bias, BN gamma + beta
+  int k = 1, stride = 1, pad = 0;
+  int bn_slot = -1;    // OP_BN: index into the per-BN statistics area
+};
+
+struct ParamDesc {
+  std::string name;
+  int kind;
+  int ndim;
+  int64_t shape[4];
+  int64_t offset, size, fan_in;
+};
+
+// Where everything lives inside the caller's workspace for one batch size.
+struct Plan {
+  int64_t batch = 0;
+  bool save = false;
+  std::vector<size_t> act;    // byte offset of every tensor's activation (tensor 0 unused)
+  std::vector<size_t> grad;   // byte offset of every tensor's gradient (save only)
+  size_t bn_stats = 0;        // per BN slot: mean[C], invstd[C], scale[C], shift[C] fp32
+  size_t bn_coef = 0;         // backward coefficients c1,c2,c3 [3][Cmax] fp32
+  size_t partials = 0;        // reduction partials / split-K partials
+  size_t partials_bytes = 0;
+  size_t xpack = 0;           // bf16 models: input packed to 8 channels
+  size_t wpack = 0;           // bf16 models: re-laid-out weights (stem padding, dgrad transposes)
+  size_t wpack_bytes = 0;
+  size_t total = 0;
+};
+
+}  // namespace cd
+
+struct cd_model {
+  cd_arch_desc arch;
+  int dtype;
+  std::vector<cd::TensorDesc> tensors;
+  std::vector<cd::Op> ops;
+  std::vector<cd::ParamDesc> params;
+  int64_t n_elements = 0;  // padded flat size
+  int n_bn = 0;
+  int64_t bn_c_total = 0;  // sum of BN channel counts
+  std::vector<int64_t> bn_off;  // per BN slot: channel offset into the statistics area
+  int max_c = 1;
+  size_t esize() const { return dtype == CD_BF16 ? 2 : 4; }
+};
+
+namespace cd {
+Plan make_plan(const cd_model* m, int64_t batch, bool save);
+}

@@ -1,0 +1,570 @@
+// Model description, workspace plan, and the forward / backward executors.
+//
+// Paper, Section 3 (checkpoint-exchange implementation of Algorithm 1): per step a device runs
+// one forward pass per model (its own, keeping what the backward pass needs, and each stale
+// peer's, keeping nothing) and one backward pass, with respect to its own parameters only.
+// The executors below enqueue exactly that on the caller's stream.
+#include "model.h"
+#include "kernels.h"
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+
+using namespace cd;
+
+// ------------------------------------------------------------------------------ construction
+namespace {
+
+struct Builder {
+  cd_model* m;
+  int add_tensor(int h, int w, int c, bool f32 = false) {
+    TensorDesc t;
+    t.h = h; t.w = w; t.c = c; t.f32 = f32;
+    m->tensors.push_back(t);
+    return (int)m->tensors.size() - 1;
+  }
+  int add_param(const std::string& name, int kind, int ndim, const int64_t* shape, int64_t fan_in) {
+    ParamDesc p;
+    p.name = name; p.kind = kind; p.ndim = ndim; p.fan_in = fan_in;
+    p.size = 1;
+    for (int i = 0; i < 4; i++) { p.shape[i] = i < ndim ? shape[i] : 1; p.size *= p.shape[i]; }
+    p.offset = m->n_elements;
+    m->n_elements += (p.size + 7) / 8 * 8;  // every tensor starts on a 16-byte (bf16) boundary
+    m->params.push_back(p);
+    return (int)m->params.size() - 1;
+  }
+  int conv_w(const std::string& n, int cin, int cout, int k) {
+    int64_t sh[4] = {cout, k, k, cin};
+    return add_param(n + ".w", CD_P_CONV_W, 4, sh, (int64_t)cin * k * k);
+  }
+  int vec(const std::string& n, int kind, int c) {
+    int64_t sh[1] = {c};
+    return add_param(n, kind, 1, sh, 0);
+  }
+  // ops
+  int conv(int x, int pw, int pb, int cout, int k, int stride, int pad, bool relu) {
+    const TensorDesc& tx = m->tensors[x];
+    Op o;
+    o.kind = OP_CONV; o.x = x; o.pw = pw; o.pb = pb; o.k = k; o.stride = stride; o.pad = pad; o.relu = relu;
+    o.y = add_tensor((tx.h + 2 * pad - k) / stride + 1, (tx.w + 2 * pad - k) / stride + 1, cout);
+    m->ops.push_back(o);
+    return o.y;
+  }
+  int bn(int x, int pg, int pb, int res, bool relu) {
+    const TensorDesc tx = m->tensors[x];
+    Op o;
+    o.kind = OP_BN; o.x = x; o.pw = pg; o.pb = pb; o.res = res; o.relu = relu;
+    o.bn_slot = m->n_bn++;
+    m->bn_off.push_back(m->bn_c_total);
+    m->bn_c_total += tx.c;
+    o.y = add_tensor(tx.h, tx.w, tx.c);
+    m->ops.push_back(o);
+    return o.y;
+  }
+  int maxpool(int x, int k, int stride, int pad) {
+    const TensorDesc tx = m->tensors[x];
+    Op o;
+    o.kind = OP_MAXPOOL; o.x = x; o.k = k; o.stride = stride; o.pad = pad;
+    o.y = add_tensor((tx.h + 2 * pad - k) / stride + 1, (tx.w + 2 * pad - k) / stride + 1, tx.c);
+    m->ops.push_back(o);
+    return o.y;
+  }
+  int gap(int x) {
+    const TensorDesc tx = m->tensors[x];
+    Op o;
+    o.kind = OP_GAP; o.x = x;
+    o.y = add_tensor(1, 1, tx.c);
+    m->ops.push_back(o);
+    return o.y;
+  }
+  int linear(int x, const std::string& n, int fin, int fout) {
+    int64_t sh[2] = {fout, fin};
+    Op o;
+    o.kind = OP_LINEAR; o.x = x;
+    o.pw = add_param(n + ".w", CD_P_LINEAR_W, 2, sh, fin);
+    o.pb = vec(n + ".b", CD_P_BIAS, fout);
+    o.y = add_tensor(1, 1, fout, true);
+    m->ops.push_back(o);
+    return o.y;
+  }
+};
+
+void build_tiny(Builder& b, const cd_arch_desc& a) {
+  const int c1 = a.widths[0], c2 = a.widths[1];
+  int w1 = b.conv_w("conv1", 3, c1, 3), b1 = b.vec("conv1.b", CD_P_BIAS, c1);
+  int t = b.conv(0, w1, b1, c1, 3, 1, 1, true);
+  int w2 = b.conv_w("conv2", c1, c2, 3), b2 = b.vec("conv2.b", CD_P_BIAS, c2);
+  t = b.conv(t, w2, b2, c2, 3, 1, 1, true);
+  t = b.gap(t);
+  b.linear(t, "fc", c2, a.classes);
+}
+
+struct BnP { int g, b; };
+BnP bn_params(Builder& b, const std::string& n, int c) {
+  BnP p;
+  p.g = b.vec(n + ".gamma", CD_P_BN_GAMMA, c);
+  p.b = b.vec(n + ".beta", CD_P_BN_BETA, c);
+  return p;
+}
+
+void build_resnet(Builder& b, const cd_arch_desc& a) {
+  const bool bott = a.kind == CD_ARCH_RESNET_BOTTLENECK;
+  char name[64];
+  int t, cin = a.stem_width;
+  {
+    int w = b.conv_w("stem.conv", 3, a.stem_width, bott ? 7 : 3);
+    BnP p = bn_params(b, "stem.bn", a.stem_width);
+    t = bott ? b.conv(0, w, -1, a.stem_width, 7, 2, 3, false) : b.conv(0, w, -1, a.stem_width, 3, 1, 1, false);
+    t = b.bn(t, p.g, p.b, -1, true);
+    if (bott) t = b.maxpool(t, 3, 2, 1);
+  }
+  for (int si = 0; si < a.n_stages; si++) {
+    const int wd = a.widths[si];
+    const int cout = bott ? 4 * wd : wd;
+    for (int bi = 0; bi < a.blocks[si]; bi++) {
+      const int stride = (si > 0 && bi == 0) ? 2 : 1;
+      snprintf(name, sizeof(name), "s%d.b%d", si + 1, bi);
+      const std::string p(name);
+      const bool proj = bott ? (bi == 0) : (stride != 1 || cin != wd);
+      // parameters in declaration order: the main path first, then the projection shortcut
+      int w1, w2, w3 = -1, wdn = -1;
+      BnP p1, p2, p3 = {-1, -1}, pdn = {-1, -1};
+      if (bott) {
+        w1 = b.conv_w(p + ".conv1", cin, wd, 1); p1 = bn_params(b, p + ".bn1", wd);
+        w2 = b.conv_w(p + ".conv2", wd, wd, 3);  p2 = bn_params(b, p + ".bn2", wd);
+        w3 = b.conv_w(p + ".conv3", wd, cout, 1); p3 = bn_params(b, p + ".bn3", cout);
+      } else {
+        w1 = b.conv_w(p + ".conv1", cin, wd, 3); p1 = bn_params(b, p + ".bn1", wd);
+        w2 = b.conv_w(p + ".conv2", wd, wd, 3);  p2 = bn_params(b, p + ".bn2", wd);
+      }
+      if (proj) { wdn = b.conv_w(p + ".down.conv", cin, cout, 1); pdn = bn_params(b, p + ".down.bn", cout); }
+      // ops: shortcut branch before the BatchNorm that adds it
+      int sc = t;
+      if (proj) {
+        sc = b.conv(t, wdn, -1, cout, 1, stride, 0, false);
+        sc = b.bn(sc, pdn.g, pdn.b, -1, false);
+      }
+      int u;
+      if (bott) {
+        u = b.conv(t, w1, -1, wd, 1, 1, 0, false);
+        u = b.bn(u, p1.g, p1.b, -1, true);
+        u = b.conv(u, w2, -1, wd, 3, stride, 1, false);
+        u = b.bn(u, p2.g, p2.b, -1, true);
+        u = b.conv(u, w3, -1, cout, 1, 1, 0, false);
+        t = b.bn(u, p3.g, p3.b, sc, true);
+      } else {
+        u = b.conv(t, w1, -1, wd, 3, stride, 1, false);
+        u = b.bn(u, p1.g, p1.b, -1, true);
+        u = b.conv(u, w2, -1, wd, 3, 1, 1, false);
+        t = b.bn(u, p2.g, p2.b, sc, true);
+      }
+      cin = cout;
+    }
+  }
+  t = b.gap(t);
+  b.linear(t, "fc", cin, a.classes);
+}
+
+// CODISTILL_FORCE_SIMPLE=1 routes every convolution to the plain kernels (debugging aid)
+bool force_simple() {
+  const char* e = getenv("CODISTILL_FORCE_SIMPLE");
+  return e && e[0] == '1';
+}
+
+ConvGeom conv_geom(const cd_model* m, const Op& o, int64_t B) {
+  const TensorDesc& tx = m->tensors[o.x];
+  const TensorDesc& ty = m->tensors[o.y];
+  ConvGeom g;
+  g.B = B; g.H = tx.h; g.W = tx.w; g.Cin = tx.c; g.Ho = ty.h; g.Wo = ty.w; g.Cout = ty.c;
+  g.kh = o.k; g.kw = o.k; g.stride = o.stride; g.pad = o.pad;
+  return g;
+}
+
+// bf16 convolutions run on the MFMA kernels; a 3-channel input is zero-padded to 8 channels
+bool use_mfma(const cd_model* m, const ConvGeom& g) {
+  if (m->dtype != CD_BF16 || force_simple()) return false;
+  ConvGeom p = g;
+  if (p.Cin == 3) p.Cin = 8;
+  return conv_mfma_supported(p);
+}
+
+}  // namespace
+
+namespace cd {
+
+Plan make_plan(const cd_model* m, int64_t B, bool save) {
+  Plan p;
+  p.batch = B;
+  p.save = save;
+  size_t off = 0;
+  auto alloc = [&](size_t bytes) { size_t o = off; off += align_up(bytes ? bytes : 16, 256); return o; };
+  const int nt = (int)m->tensors.size();
+  p.act.assign(nt, 0);
+  p.grad.assign(nt, 0);
+  for (int t = 1; t < nt; t++)
+    if (!m->tensors[t].f32) p.act[t] = alloc((size_t)B * m->tensors[t].per_sample() * m->esize());
+  p.bn_stats = alloc((size_t)(m->bn_c_total > 0 ? m->bn_c_total : 1) * 4 * sizeof(float));
+  p.bn_coef = alloc((size_t)3 * m->max_c * sizeof(float));
+  p.partials_bytes = kPartialsBytes;
+  p.partials = alloc(p.partials_bytes);
+  if (m->dtype == CD_BF16) {
+    p.xpack = alloc((size_t)B * m->arch.in_h * m->arch.in_w * 8 * 2);
+    size_t wmax = 0;
+    for (const ParamDesc& q : m->params)
+      if (q.kind == CD_P_CONV_W) {
+        size_t e = (size_t)q.shape[0] * q.shape[1] * q.shape[2] * (q.shape[3] == 3 ? 8 : q.shape[3]);
+        if (e > wmax) wmax = e;
+      }
+    p.wpack_bytes = align_up(wmax * 4, 256);  // also holds the fp32 padded stem weight gradient
+    p.wpack = alloc(p.wpack_bytes);
+  }
+  if (save)
+    for (int t = 1; t < nt; t++)
+      if (!m->tensors[t].f32) p.grad[t] = alloc((size_t)B * m->tensors[t].per_sample() * m->esize());
+  p.total = off;
+  return p;
+}
+
+}  // namespace cd
+
+// ------------------------------------------------------------------------------------- C ABI
+extern "C" int codistill_arch_preset(int kind, cd_arch_desc* out) {
+  CD_REQUIRE(out != nullptr, "arch_preset: out is NULL");
+  memset(out, 0, sizeof(*out));
+  out->kind = kind;
+  if (kind == CD_ARCH_TINY_CNN) {
+    out->classes = 10; out->in_h = out->in_w = 32; out->n_stages = 0;
+    out->widths[0] = 16; out->widths[1] = 32;
+  } else if (kind == CD_ARCH_RESNET_BASIC) {
+    out->classes = 10; out->in_h = out->in_w = 32; out->n_stages = 3; out->stem_width = 16;
+    const int w[3] = {16, 32, 64};
+    for (int i = 0; i < 3; i++) { out->widths[i] = w[i]; out->blocks[i] = 3; }
+  } else if (kind == CD_ARCH_RESNET_BOTTLENECK) {
+    out->classes = 1000; out->in_h = out->in_w = 224; out->n_stages = 4; out->stem_width = 64;
+    const int w[4] = {64, 128, 256, 512}, nb[4] = {3, 4, 6, 3};
+    for (int i = 0; i < 4; i++) { out->widths[i] = w[i]; out->blocks[i] = nb[i]; }
+  } else {
+    return set_error(CD_ERR_INVALID_ARG, "arch_preset: unknown kind %d", kind);
+  }
+  return CD_OK;
+}
+
+extern "C" int codistill_model_create(const cd_arch_desc* a, int dtype, cd_model** out) {
+  CD_REQUIRE(a != nullptr && out != nullptr, "model_create: NULL pointer argument");
+  CD_REQUIRE(dtype == CD_F32 || dtype == CD_BF16, "model_create: unknown dtype %d", dtype);
+  CD_REQUIRE(a->kind == CD_ARCH_TINY_CNN || a->kind == CD_ARCH_RESNET_BASIC || a->kind == CD_ARCH_RESNET_BOTTLENECK,
+             "model_create: unknown architecture kind %d", a->kind);
+  CD_REQUIRE(a->classes >= 1 && a->classes <= (1 << 24), "model_create: classes=%d out of range", a->classes);
+  CD_REQUIRE(a->in_h >= 1 && a->in_w >= 1 && a->in_h <= 4096 && a->in_w <= 4096,
+             "model_create: input resolution %dx%d out of range", a->in_h, a->in_w);
+  if (a->kind == CD_ARCH_TINY_CNN) {
+    CD_REQUIRE(a->widths[0] >= 1 && a->widths[1] >= 1 && a->widths[0] <= 4096 && a->widths[1] <= 4096,
+               "model_create: tiny CNN widths out of range");
+  } else {
+    CD_REQUIRE(a->n_stages >= 1 && a->n_stages <= CD_MAX_STAGES, "model_create: n_stages=%d out of range", a->n_stages);
+    CD_REQUIRE(a->stem_width >= 1 && a->stem_width <= 4096, "model_create: stem_width=%d out of range", a->stem_width);
+    for (int i = 0; i < a->n_stages; i++)
+      CD_REQUIRE(a->widths[i] >= 1 && a->widths[i] <= 4096 && a->blocks[i] >= 1 && a->blocks[i] <= 64,
+                 "model_create: stage %d width/blocks out of range", i);
+  }
+  cd_model* m = new cd_model();
+  m->arch = *a;
+  m->dtype = dtype;
+  m->tensors.push_back(TensorDesc());
+  m->tensors[0].h = a->in_h; m->tensors[0].w = a->in_w; m->tensors[0].c = 3;
+  Builder b{m};
+  if (a->kind == CD_ARCH_TINY_CNN) build_tiny(b, *a); else build_resnet(b, *a);
+  for (const TensorDesc& t : m->tensors) {
+    if (t.h < 1 || t.w < 1) {
+      delete m;
+      return set_error(CD_ERR_INVALID_ARG, "model_create: input resolution too small for this architecture");
+    }
+    if (t.c > m->max_c) m->max_c = t.c;
+  }
+  *out = m;
+  return CD_OK;
+}
+
+extern "C" void codistill_model_destroy(cd_model* m) { delete m; }
+
+extern "C" int codistill_param_count(const cd_model* m, int64_t* n_tensors, int64_t* n_elements) {
+  CD_REQUIRE(m != nullptr, "param_count: model is NULL");
+  if (n_tensors) *n_tensors = (int64_t)m->params.size();
+  if (n_elements) *n_elements = m->n_elements;
+  return CD_OK;
+}
+
+extern "C" int codistill_param_info(const cd_model* m, int64_t idx, cd_tensor_info* out) {
+  CD_REQUIRE(m != nullptr && out != nullptr, "param_info: NULL pointer argument");
+  CD_REQUIRE(idx >= 0 && idx < (int64_t)m->params.size(), "param_info: index %lld out of range", (long long)idx);
+  const ParamDesc& p = m->params[idx];
+  memset(out, 0, sizeof(*out));
+  snprintf(out->name, CD_NAME_LEN, "%s", p.name.c_str());
+  out->kind = p.kind; out->ndim = p.ndim;
+  for (int i = 0; i < 4; i++) out->shape[i] = p.shape[i];
+  out->offset = p.offset; out->size = p.size; out->fan_in = p.fan_in;
+  return CD_OK;
+}
+
+extern "C" int codistill_workspace_bytes(const cd_model* m, int64_t batch, int save, size_t* bytes) {
+  CD_REQUIRE(m != nullptr && bytes != nullptr, "workspace_bytes: NULL pointer argument");
+  CD_REQUIRE(batch >= 1 && batch <= (1 << 20), "workspace_bytes: batch=%lld out of range", (long long)batch);
+  *bytes = make_plan(m, batch, save != 0).total;
+  return CD_OK;
+}
+
+extern "C" int codistill_graph_size(const cd_model* m, int64_t* n_ops, int64_t* n_tensors) {
+  CD_REQUIRE(m != nullptr, "graph_size: model is NULL");
+  if (n_ops) *n_ops = (int64_t)m->ops.size();
+  if (n_tensors) *n_tensors = (int64_t)m->tensors.size();
+  return CD_OK;
+}
+
+extern "C" int codistill_op_info(const cd_model* m, int64_t batch, int64_t idx, cd_op_info* out) {
+  CD_REQUIRE(m != nullptr && out != nullptr, "op_info: NULL pointer argument");
+  CD_REQUIRE(idx >= 0 && idx < (int64_t)m->ops.size(), "op_info: index %lld out of range", (long long)idx);
+  CD_REQUIRE(batch >= 1 && batch <= (1 << 20), "op_info: batch=%lld out of range", (long long)batch);
+  const Op& o = m->ops[idx];
+  out->kind = (int32_t)o.kind; out->x = o.x; out->y = o.y; out->res = o.res; out->relu = o.relu ? 1 : 0;
+  out->param_w = o.pw; out->param_b = o.pb; out->k = o.k; out->stride = o.stride; out->pad = o.pad;
+  out->stats_offset = -1;
+  if (o.kind == OP_BN) {
+    Plan p = make_plan(m, batch, true);
+    out->stats_offset = (int64_t)(p.bn_stats + (size_t)4 * m->bn_off[o.bn_slot] * sizeof(float));
+  }
+  return CD_OK;
+}
+
+extern "C" int codistill_tensor_info(const cd_model* m, int64_t batch, int64_t idx, cd_act_info* out) {
+  CD_REQUIRE(m != nullptr && out != nullptr, "tensor_info: NULL pointer argument");
+  CD_REQUIRE(idx >= 0 && idx < (int64_t)m->tensors.size(), "tensor_info: index %lld out of range", (long long)idx);
+  CD_REQUIRE(batch >= 1 && batch <= (1 << 20), "tensor_info: batch=%lld out of range", (long long)batch);
+  const TensorDesc& t = m->tensors[idx];
+  Plan p = make_plan(m, batch, true);
+  out->h = t.h; out->w = t.w; out->c = t.c; out->is_f32 = t.f32 ? 1 : 0;
+  const bool in_ws = idx != 0 && !t.f32;
+  out->act_offset = in_ws ? (int64_t)p.act[idx] : -1;
+  out->grad_offset = in_ws ? (int64_t)p.grad[idx] : -1;
+  return CD_OK;
+}
+
+// ---------------------------------------------------------------------------------- forward
+namespace {
+
+struct Ctx {
+  const cd_model* m;
+  Plan plan;
+  char* ws;
+  const char* params;
+  const void* x;
+  int64_t B;
+  hipStream_t s;
+  const void* P(int idx) const { return idx < 0 ? nullptr : params + (size_t)m->params[idx].offset * m->esize(); }
+  void* act(int t) const { return ws + plan.act[t]; }
+  void* grad(int t) const { return ws + plan.grad[t]; }
+  float* stats(const Op& o) const { return reinterpret_cast<float*>(ws + plan.bn_stats) + 4 * m->bn_off[o.bn_slot]; }
+  float* partials() const { return reinterpret_cast<float*>(ws + plan.partials); }
+  float* coef() const { return reinterpret_cast<float*>(ws + plan.bn_coef); }
+  bf16_t* xpack() const { return reinterpret_cast<bf16_t*>(ws + plan.xpack); }
+  bf16_t* wpack() const { return reinterpret_cast<bf16_t*>(ws + plan.wpack); }
+};
+
+int check_common(const char* fn, const cd_model* m, const void* params, const void* x, int64_t batch, void* ws) {
+  CD_REQUIRE(m && params && x && ws, "%s: NULL pointer argument", fn);
+  CD_REQUIRE(batch >= 1 && batch <= (1 << 20), "%s: batch=%lld out of range", fn, (long long)batch);
+  CD_REQUIRE(aligned16(params) && aligned16(x) && (reinterpret_cast<uintptr_t>(ws) & 255) == 0,
+             "%s: params and x must be 16-byte aligned, the workspace 256-byte aligned", fn);
+  return CD_OK;
+}
+
+double conv_bytes(const cd_model* m, const ConvGeom& g) {
+  return (double)m->esize() * ((double)g.B * g.H * g.W * g.Cin + (double)g.M() * g.Cout + (double)g.Cout * g.K());
+}
+
+}  // namespace
+
+extern "C" int codistill_forward(const cd_model* m, const void* params, const void* x, int64_t batch, int save,
+                                 int bn_mode, float* bn_running, void* workspace, size_t workspace_bytes,
+                                 float* logits_out, void* stream) {
+  int rc = check_common("forward", m, params, x, batch, workspace);
+  if (rc) return rc;
+  CD_REQUIRE(logits_out != nullptr && aligned16(logits_out), "forward: logits_out is NULL or misaligned");
+  CD_REQUIRE(bn_mode == CD_BN_BATCH_STATS || bn_mode == CD_BN_RUNNING, "forward: unknown bn_mode %d", bn_mode);
+  if (bn_mode == CD_BN_RUNNING) return set_error(CD_ERR_UNSUPPORTED, "forward: CD_BN_RUNNING is not implemented");
+  CD_REQUIRE(bn_running == nullptr, "forward: bn_running is reserved and must be NULL");
+  Ctx c;
+  c.m = m;
+  c.plan = make_plan(m, batch, save != 0);
+  if (workspace_bytes < c.plan.total)
+    return set_error(CD_ERR_WORKSPACE_TOO_SMALL, "forward: workspace %zu < %zu bytes", workspace_bytes, c.plan.total);
+  c.ws = static_cast<char*>(workspace);
+  c.params = static_cast<const char*>(params);
+  c.x = x;
+  c.B = batch;
+  c.s = static_cast<hipStream_t>(stream);
+  const int dt = m->dtype;
+  const int logits_t = m->ops.back().y;
+
+  for (const Op& o : m->ops) {
+    const void* in = o.x == 0 ? x : c.act(o.x);
+    void* out = o.y == logits_t ? static_cast<void*>(logits_out) : c.act(o.y);
+    const TensorDesc& tx = m->tensors[o.x];
+    switch (o.kind) {
+      case OP_CONV: {
+        ConvGeom g = conv_geom(m, o, batch);
+        if (use_mfma(m, g) && o.pb < 0 && !o.relu) {
+          const bf16_t* src = static_cast<const bf16_t*>(in);
+          const bf16_t* w = static_cast<const bf16_t*>(c.P(o.pw));
+          if (g.Cin == 3) {  // pad image and filter taps to 8 channels
+            ProfScope pr(CD_K_GLUE, c.s, 0, (double)batch * g.H * g.W * (3 + 8) * 2);
+            pad_c3_to_c8(src, c.xpack(), batch * g.H * g.W, c.s);
+            pad_c3_to_c8(w, c.wpack(), (int64_t)g.Cout * g.kh * g.kw, c.s);
+            src = c.xpack();
+            w = c.wpack();
+          }
+          ProfScope pr(CD_K_CONV_FPROP, c.s, 2.0 * g.M() * g.Cout * g.K(), conv_bytes(m, g));
+          ConvGeom gp = g;
+          if (gp.Cin == 3) gp.Cin = 8;
+          conv_fprop_mfma(src, w, static_cast<bf16_t*>(out), gp, c.s);
+        } else {
+          ProfScope pr(CD_K_CONV_FPROP, c.s, 2.0 * g.M() * g.Cout * g.K(), conv_bytes(m, g));
+          conv_fprop_simple(dt, in, c.P(o.pw), c.P(o.pb), out, g, o.relu, c.s);
+        }
+        break;
+      }
+      case OP_BN: {
+        const int64_t M = batch * tx.h * tx.w;
+        ProfScope pr(CD_K_NORM, c.s, 0, (double)M * tx.c * m->esize() * (3 + (o.res >= 0 ? 1 : 0)));
+        bn_forward(dt, in, c.P(o.pw), c.P(o.pb), o.res >= 0 ? c.act(o.res) : nullptr, o.relu, out, M, tx.c,
+                   c.stats(o), c.partials(), c.s);
+        break;
+      }
+      case OP_MAXPOOL: {
+        ProfScope pr(CD_K_GLUE, c.s, 0, (double)batch * tx.per_sample() * m->esize() * 1.25);
+        maxpool_fwd(dt, in, out, batch, tx.h, tx.w, tx.c, o.k, o.stride, o.pad, c.s);
+        break;
+      }
+      case OP_GAP: {
+        ProfScope pr(CD_K_GLUE, c.s, 0, (double)batch * tx.per_sample() * m->esize());
+        gap_fwd(dt, in, out, batch, tx.h * tx.w, tx.c, c.s);
+        break;
+      }
+      case OP_LINEAR: {
+        const int F = tx.c, C = m->tensors[o.y].c;
+        ProfScope pr(CD_K_LINEAR, c.s, 2.0 * batch * F * C, (double)m->esize() * ((double)batch * F + (double)F * C));
+        linear_fwd(dt, in, c.P(o.pw), c.P(o.pb), static_cast<float*>(out), batch, F, C, c.s);
+        break;
+      }
+    }
+  }
+  return check_launch("forward");
+}
+
+// --------------------------------------------------------------------------------- backward
+extern "C" int codistill_backward(const cd_model* m, const void* params, const void* x, int64_t batch, void* workspace,
+                                  size_t workspace_bytes, const float* dlogits, float* grads_out, void* stream) {
+  int rc = check_common("backward", m, params, x, batch, workspace);
+  if (rc) return rc;
+  CD_REQUIRE(dlogits && grads_out && aligned16(dlogits) && aligned16(grads_out),
+             "backward: dlogits / grads_out is NULL or misaligned");
+  Ctx c;
+  c.m = m;
+  c.plan = make_plan(m, batch, true);
+  if (workspace_bytes < c.plan.total)
+    return set_error(CD_ERR_WORKSPACE_TOO_SMALL, "backward: workspace %zu < %zu bytes", workspace_bytes, c.plan.total);
+  c.ws = static_cast<char*>(workspace);
+  c.params = static_cast<const char*>(params);
+  c.x = x;
+  c.B = batch;
+  c.s = static_cast<hipStream_t>(stream);
+  const int dt = m->dtype;
+  const int logits_t = m->ops.back().y;
+  auto G = [&](int pidx) { return grads_out + m->params[pidx].offset; };
+
+  {  // padding between tensors in the flat gradient
+    std::vector<Gap> gaps;
+    for (const ParamDesc& p : m->params)
+      if (p.size % 8) gaps.push_back(Gap{p.offset + p.size, (int32_t)(8 - p.size % 8)});
+    if (!gaps.empty()) zero_gaps(grads_out, gaps.data(), (int)gaps.size(), c.s);
+  }
+
+  std::vector<char> written(m->tensors.size(), 0);
+  for (int i = (int)m->ops.size() - 1; i >= 0; i--) {
+    const Op& o = m->ops[i];
+    const TensorDesc& tx = m->tensors[o.x];
+    const void* in = o.x == 0 ? x : c.act(o.x);
+    void* dy = o.y == logits_t ? nullptr : c.grad(o.y);
+    void* dx = o.x == 0 ? nullptr : c.grad(o.x);
+    const bool acc = o.x != 0 && written[o.x];
+    switch (o.kind) {
+      case OP_LINEAR: {
+        const int F = tx.c, C = m->tensors[o.y].c;
+        ProfScope pr(CD_K_LINEAR, c.s, 4.0 * batch * F * C, (double)m->esize() * ((double)batch * F + (double)F * C) * 2);
+        linear_bwd(dt, in, c.P(o.pw), dlogits, dx, acc, G(o.pw), G(o.pb), batch, F, C, c.s);
+        break;
+      }
+      case OP_GAP: {
+        ProfScope pr(CD_K_GLUE, c.s, 0, (double)batch * tx.per_sample() * m->esize());
+        gap_bwd(dt, dy, dx, acc, batch, tx.h * tx.w, tx.c, c.s);
+        break;
+      }
+      case OP_MAXPOOL: {
+        ProfScope pr(CD_K_GLUE, c.s, 0, (double)batch * tx.per_sample() * m->esize() * 2.25);
+        maxpool_bwd(dt, in, dy, dx, acc, batch, tx.h, tx.w, tx.c, o.k, o.stride, o.pad, c.s);
+        break;
+      }
+      case OP_BN: {
+        const int64_t M = batch * tx.h * tx.w;
+        void* dres = o.res >= 0 ? c.grad(o.res) : nullptr;
+        const bool acc_res = o.res >= 0 && written[o.res];
+        ProfScope pr(CD_K_NORM, c.s, 0, (double)M * tx.c * m->esize() * (6 + (o.relu ? 2 : 0) + (o.res >= 0 ? 1 : 0)));
+        bn_backward(dt, dy, c.act(o.y), in, c.P(o.pw), c.stats(o), o.relu, dx, acc, dres, acc_res, G(o.pw), G(o.pb),
+                    c.coef(), c.partials(), M, tx.c, c.s);
+        if (o.res >= 0) written[o.res] = 1;
+        break;
+      }
+      case OP_CONV: {
+        ConvGeom g = conv_geom(m, o, batch);
+        if (o.relu) {
+          ProfScope pr(CD_K_GLUE, c.s, 0, (double)g.M() * g.Cout * m->esize() * 3);
+          relu_bwd_inplace(dt, dy, c.act(o.y), g.M() * g.Cout, c.s);
+        }
+        if (o.pb >= 0) {
+          ProfScope pr(CD_K_GLUE, c.s, 0, (double)g.M() * g.Cout * m->esize());
+          colsum(dt, dy, g.M(), g.Cout, G(o.pb), c.partials(), c.s);
+        }
+        const bool mf = use_mfma(m, g) && o.pb < 0 && !o.relu;
+        {
+          ProfScope pr(CD_K_CONV_WGRAD, c.s, 2.0 * g.M() * g.Cout * g.K(), conv_bytes(m, g) + 2.0 * g.Cout * g.K());
+          if (mf) {
+            ConvGeom gp = g;
+            const bf16_t* src = static_cast<const bf16_t*>(in);
+            float* dw = G(o.pw);
+            if (g.Cin == 3) {  // the forward pass left the padded image in xpack
+              gp.Cin = 8;
+              src = c.xpack();
+              dw = reinterpret_cast<float*>(c.wpack());
+            }
+            conv_wgrad_mfma(src, static_cast<const bf16_t*>(dy), dw, gp, c.partials(), c.plan.partials_bytes, c.s);
+            if (g.Cin == 3) unpad_c8_to_c3(dw, G(o.pw), (int64_t)g.Cout * g.kh * g.kw, c.s);
+          } else {
+            conv_wgrad_simple(dt, in, dy, G(o.pw), g, c.s);
+          }
+        }
+        if (o.x != 0) {
+          ProfScope pr(CD_K_CONV_DGRAD, c.s, 2.0 * g.M() * g.Cout * g.K(), conv_bytes(m, g));
+          if (mf) {
+            const bf16_t* w = static_cast<const bf16_t*>(c.P(o.pw));
+            transpose_weight(w, c.wpack(), g.Cout, g.kh * g.kw, g.Cin, c.s);
+            conv_dgrad_mfma(static_cast<const bf16_t*>(dy), c.wpack(), static_cast<bf16_t*>(dx), g, acc, c.s);
+          } else {
+            conv_dgrad_simple(dt, dy, c.P(o.pw), dx, g, acc, c.s);
+          }
+        }
+        break;
+      }
+    }
+    if (o.x != 0) written[o.x] = 1;
+  }
+  return check_launch("backward");
+}

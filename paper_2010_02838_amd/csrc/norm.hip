@@ -1,0 +1,325 @@
+// BatchNorm forward / backward with batch statistics, fused ReLU and residual add, and the
+// per-channel column sums they are built on.  (The paper's networks are the standard ResNets,
+// Section 3; BatchNorm normalises each channel with the biased variance over batch and space.)
+//
+// All of it is HBM-bound.  A tensor is [M rows][C channels] with channels contiguous, so a block
+// reads whole rows (consecutive threads -> consecutive 16-byte channel vectors) and every thread
+// accumulates its own channels down the rows: reductions run along the strided axis while every
+// load stays coalesced.  Partial sums per row chunk go to a scratch array and a second, tiny
+// kernel adds them in a fixed order (deterministic, no atomics).
+#include "kernels.h"
+
+namespace cd {
+
+template <typename T, int VEC> struct Vec;
+template <> struct Vec<float, 1> {
+  __device__ static void ld(const float* p, float (&v)[1]) { v[0] = *p; }
+  __device__ static void st(float* p, const float (&v)[1]) { *p = v[0]; }
+};
+template <> struct Vec<float, 4> {
+  __device__ static void ld(const float* p, float (&v)[4]) {
+    float4 t = *reinterpret_cast<const float4*>(p);
+    v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+  }
+  __device__ static void st(float* p, const float (&v)[4]) {
+    *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+  }
+};
+template <> struct Vec<bf16_t, 1> {
+  __device__ static void ld(const bf16_t* p, float (&v)[1]) { v[0] = bf16_to_f32(*p); }
+  __device__ static void st(bf16_t* p, const float (&v)[1]) { *p = f32_to_bf16(v[0]); }
+};
+template <> struct Vec<bf16_t, 8> {
+  __device__ static void ld(const bf16_t* p, float (&v)[8]) {
+    uint4 t = *reinterpret_cast<const uint4*>(p);
+    const uint32_t u[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      v[2 * i] = __uint_as_float(u[i] << 16);
+      v[2 * i + 1] = __uint_as_float(u[i] & 0xffff0000u);
+    }
+  }
+  __device__ static void st(bf16_t* p, const float (&v)[8]) {
+    uint32_t u[4];
+#pragma unroll
+    for (int i = 0; i < 4; i++) u[i] = (uint32_t)f32_to_bf16(v[2 * i]) | ((uint32_t)f32_to_bf16(v[2 * i + 1]) << 16);
+    *reinterpret_cast<uint4*>(p) = make_uint4(u[0], u[1], u[2], u[3]);
+  }
+};
+
+// MODE 0: sums of x and x^2.  MODE 1: sums of dz and dz*xhat with dz = dy * (relu ? y > 0 : 1).
+// MODE 2: sum of a0.  partials: [chunks][2][C].
+template <typename T, int VEC, int MODE>
+__global__ void __launch_bounds__(256) col_reduce_k(const T* __restrict__ a0, const T* __restrict__ a1,
+                                                    const T* __restrict__ a2, const float* __restrict__ stats,
+                                                    int relu, int64_t M, int C, int64_t rows_per_chunk,
+                                                    float* __restrict__ partials) {
+  __shared__ float sm[2][256 * VEC];
+  const int vc = C / VEC;
+  const int v0 = blockIdx.y * 256;
+  const int vcb = vc - v0 < 256 ? vc - v0 : 256;  // channel vectors handled by this block
+  const int rpi = 256 / vcb;                      // rows per iteration
+  const int ty = threadIdx.x / vcb, tx = threadIdx.x % vcb;
+  const int c0 = (v0 + tx) * VEC;
+  const int64_t r0 = (int64_t)blockIdx.x * rows_per_chunk;
+  const int64_t r1 = r0 + rows_per_chunk < M ? r0 + rows_per_chunk : M;
+  float s0[VEC], s1[VEC], mean[VEC], istd[VEC];
+#pragma unroll
+  for (int k = 0; k < VEC; k++) { s0[k] = 0.f; s1[k] = 0.f; mean[k] = 0.f; istd[k] = 0.f; }
+  if (ty < rpi) {
+    if (MODE == 1) {
+#pragma unroll
+      for (int k = 0; k < VEC; k++) { mean[k] = stats[c0 + k]; istd[k] = stats[C + c0 + k]; }
+    }
+    for (int64_t r = r0 + ty; r < r1; r += rpi) {
+      const int64_t off = r * C + c0;
+      float a[VEC];
+      Vec<T, VEC>::ld(a0 + off, a);
+      if (MODE == 0) {
+#pragma unroll
+        for (int k = 0; k < VEC; k++) { s0[k] += a[k]; s1[k] += a[k] * a[k]; }
+      } else if (MODE == 1) {
+        float x[VEC];
+        Vec<T, VEC>::ld(a2 + off, x);
+        if (relu) {
+          float y[VEC];
+          Vec<T, VEC>::ld(a1 + off, y);
+#pragma unroll
+          for (int k = 0; k < VEC; k++) a[k] = y[k] > 0.f ? a[k] : 0.f;
+        }
+#pragma unroll
+        for (int k = 0; k < VEC; k++) { s0[k] += a[k]; s1[k] += a[k] * (x[k] - mean[k]) * istd[k]; }
+      } else {
+#pragma unroll
+        for (int k = 0; k < VEC; k++) s0[k] += a[k];
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < VEC; k++) { sm[0][threadIdx.x * VEC + k] = s0[k]; sm[1][threadIdx.x * VEC + k] = s1[k]; }
+  }
+  __syncthreads();
+  if ((int)threadIdx.x < vcb) {
+#pragma unroll
+    for (int k = 0; k < VEC; k++) {
+      float t0 = 0.f, t1 = 0.f;
+      for (int j = 0; j < rpi; j++) {
+        t0 += sm[0][(j * vcb + tx) * VEC + k];
+        t1 += sm[1][(j * vcb + tx) * VEC + k];
+      }
+      partials[((int64_t)blockIdx.x * 2 + 0) * C + c0 + k] = t0;
+      partials[((int64_t)blockIdx.x * 2 + 1) * C + c0 + k] = t1;
+    }
+  }
+}
+
+// FIN 0: BatchNorm statistics.  FIN 1: BatchNorm backward sums.  FIN 2: plain column sum.
+template <typename T, int FIN>
+__global__ void __launch_bounds__(256) col_finalize_k(const float* __restrict__ partials, int chunks, int64_t M, int C,
+                                                      const T* __restrict__ gamma, const T* __restrict__ beta,
+                                                      float* __restrict__ stats, float* __restrict__ out0,
+                                                      float* __restrict__ out1, float* __restrict__ coef) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= C) return;
+  double s0 = 0.0, s1 = 0.0;
+  for (int j = 0; j < chunks; j++) {
+    s0 += (double)partials[((int64_t)j * 2 + 0) * C + c];
+    if (FIN != 2) s1 += (double)partials[((int64_t)j * 2 + 1) * C + c];
+  }
+  if (FIN == 0) {
+    const double mean = s0 / (double)M;
+    double var = s1 / (double)M - mean * mean;
+    if (var < 0.0) var = 0.0;
+    const float istd = (float)(1.0 / sqrt(var + (double)kBnEps));
+    const float scale = Cvt<T>::ld(gamma[c]) * istd;
+    stats[c] = (float)mean;
+    stats[C + c] = istd;
+    stats[2 * C + c] = scale;
+    stats[3 * C + c] = Cvt<T>::ld(beta[c]) - (float)mean * scale;
+  } else if (FIN == 1) {
+    // dx = c1*dz + c2*x + c3 with xhat = (x - mean)*invstd
+    const float mean = stats[c], istd = stats[C + c];
+    const float dbeta = (float)s0, dgamma = (float)s1;
+    out0[c] = dgamma;
+    out1[c] = dbeta;
+    const float c1 = Cvt<T>::ld(gamma[c]) * istd;
+    const float c2 = -c1 * istd * dgamma / (float)M;
+    coef[c] = c1;
+    coef[C + c] = c2;
+    coef[2 * C + c] = -c1 * dbeta / (float)M - c2 * mean;
+  } else {
+    out0[c] = (float)s0;
+  }
+}
+
+template <typename T, int VEC>
+__global__ void __launch_bounds__(256) bn_apply_k(const T* __restrict__ x, const T* __restrict__ res, T* __restrict__ y,
+                                                  const float* __restrict__ stats, int relu, int64_t nvec, int C) {
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += stride) {
+    const int c0 = (int)((i * VEC) % C);
+    float a[VEC];
+    Vec<T, VEC>::ld(x + i * VEC, a);
+#pragma unroll
+    for (int k = 0; k < VEC; k++) a[k] = a[k] * stats[2 * C + c0 + k] + stats[3 * C + c0 + k];
+    if (res) {
+      float r[VEC];
+      Vec<T, VEC>::ld(res + i * VEC, r);
+#pragma unroll
+      for (int k = 0; k < VEC; k++) a[k] += r[k];
+    }
+    if (relu) {
+#pragma unroll
+      for (int k = 0; k < VEC; k++) a[k] = fmaxf(a[k], 0.f);
+    }
+    Vec<T, VEC>::st(y + i * VEC, a);
+  }
+}
+
+template <typename T, int VEC>
+__global__ void __launch_bounds__(256) bn_bwd_apply_k(const T* __restrict__ dy, const T* __restrict__ y,
+                                                      const T* __restrict__ x, const float* __restrict__ coef, int relu,
+                                                      T* __restrict__ dx, int acc_dx, T* __restrict__ dres,
+                                                      int acc_dres, int64_t nvec, int C) {
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += stride) {
+    const int c0 = (int)((i * VEC) % C);
+    float dz[VEC], xv[VEC], o[VEC];
+    Vec<T, VEC>::ld(dy + i * VEC, dz);
+    Vec<T, VEC>::ld(x + i * VEC, xv);
+    if (relu) {
+      float yv[VEC];
+      Vec<T, VEC>::ld(y + i * VEC, yv);
+#pragma unroll
+      for (int k = 0; k < VEC; k++) dz[k] = yv[k] > 0.f ? dz[k] : 0.f;
+    }
+#pragma unroll
+    for (int k = 0; k < VEC; k++) o[k] = coef[c0 + k] * dz[k] + coef[C + c0 + k] * xv[k] + coef[2 * C + c0 + k];
+    if (acc_dx) {
+      float p[VEC];
+      Vec<T, VEC>::ld(dx + i * VEC, p);
+#pragma unroll
+      for (int k = 0; k < VEC; k++) o[k] += p[k];
+    }
+    Vec<T, VEC>::st(dx + i * VEC, o);
+    if (dres) {
+      if (acc_dres) {
+        float p[VEC];
+        Vec<T, VEC>::ld(dres + i * VEC, p);
+#pragma unroll
+        for (int k = 0; k < VEC; k++) dz[k] += p[k];
+      }
+      Vec<T, VEC>::st(dres + i * VEC, dz);
+    }
+  }
+}
+
+// How the rows are cut into chunks; the same rule sizes the launch and bounds the partials.
+struct ReducePlan { int chunks; int64_t rows_per_chunk; int cgroups; };
+static ReducePlan reduce_plan(int64_t M, int C, int vec) {
+  ReducePlan p;
+  const int vc = C / vec;
+  p.cgroups = (int)cdiv(vc, 256);
+  const int vcb = vc < 256 ? vc : 256;
+  const int rpi = 256 / vcb;
+  int64_t target = 2048 / p.cgroups;                      // blocks to fill the chip several times
+  const int64_t cap = (int64_t)(kPartialsBytes / ((size_t)2 * C * 4));
+  if (target > cap) target = cap;
+  if (target < 1) target = 1;
+  int64_t rpc = cdiv(M, target);
+  const int64_t min_rows = (int64_t)rpi * 8;              // at least a few iterations per block
+  if (rpc < min_rows) rpc = min_rows;
+  p.rows_per_chunk = rpc;
+  p.chunks = (int)cdiv(M, rpc);
+  return p;
+}
+
+template <typename T> static int pick_vec(int C, const void* p0, const void* p1, const void* p2, const void* p3) {
+  const int v = sizeof(T) == 2 ? 8 : 4;
+  const bool al = aligned16(p0) && aligned16(p1) && aligned16(p2) && aligned16(p3);
+  return (C % v == 0 && al) ? v : 1;
+}
+
+template <typename T, int VEC, int MODE>
+static ReducePlan launch_reduce(const T* a0, const T* a1, const T* a2, const float* stats, bool relu, int64_t M, int C,
+                                float* partials, hipStream_t s) {
+  ReducePlan p = reduce_plan(M, C, VEC);
+  hipLaunchKernelGGL((col_reduce_k<T, VEC, MODE>), dim3(p.chunks, p.cgroups), dim3(256), 0, s, a0, a1, a2, stats,
+                     (int)relu, M, C, p.rows_per_chunk, partials);
+  return p;
+}
+
+template <typename T>
+static void bn_forward_t(const T* x, const T* gamma, const T* beta, const T* res, bool relu, T* y, int64_t M, int C,
+                         float* stats, float* partials, hipStream_t s) {
+  const int vec = pick_vec<T>(C, x, res, y, nullptr);
+  constexpr int V = sizeof(T) == 2 ? 8 : 4;
+  ReducePlan p = vec > 1 ? launch_reduce<T, V, 0>(x, nullptr, nullptr, nullptr, false, M, C, partials, s)
+                         : launch_reduce<T, 1, 0>(x, nullptr, nullptr, nullptr, false, M, C, partials, s);
+  hipLaunchKernelGGL((col_finalize_k<T, 0>), dim3((unsigned)cdiv(C, 256)), dim3(256), 0, s, partials, p.chunks, M, C,
+                     gamma, beta, stats, (float*)nullptr, (float*)nullptr, (float*)nullptr);
+  const int64_t nvec = M * C / vec;
+  int64_t blocks = cdiv(nvec, 256);
+  if (blocks > 8192) blocks = 8192;
+  if (vec > 1)
+    hipLaunchKernelGGL((bn_apply_k<T, V>), dim3((unsigned)blocks), dim3(256), 0, s, x, res, y, stats, (int)relu, nvec, C);
+  else
+    hipLaunchKernelGGL((bn_apply_k<T, 1>), dim3((unsigned)blocks), dim3(256), 0, s, x, res, y, stats, (int)relu, nvec, C);
+}
+
+template <typename T>
+static void bn_backward_t(const T* dy, const T* y, const T* x, const T* gamma, const float* stats, bool relu, T* dx,
+                          bool acc_dx, T* dres, bool acc_dres, float* dgamma, float* dbeta, float* coef,
+                          float* partials, int64_t M, int C, hipStream_t s) {
+  int vec = pick_vec<T>(C, dy, y, x, dx);
+  if (!aligned16(dres)) vec = 1;
+  constexpr int V = sizeof(T) == 2 ? 8 : 4;
+  ReducePlan p = vec > 1 ? launch_reduce<T, V, 1>(dy, y, x, stats, relu, M, C, partials, s)
+                         : launch_reduce<T, 1, 1>(dy, y, x, stats, relu, M, C, partials, s);
+  hipLaunchKernelGGL((col_finalize_k<T, 1>), dim3((unsigned)cdiv(C, 256)), dim3(256), 0, s, partials, p.chunks, M, C,
+                     gamma, (const T*)nullptr, const_cast<float*>(stats), dgamma, dbeta, coef);
+  const int64_t nvec = M * C / vec;
+  int64_t blocks = cdiv(nvec, 256);
+  if (blocks > 8192) blocks = 8192;
+  if (vec > 1)
+    hipLaunchKernelGGL((bn_bwd_apply_k<T, V>), dim3((unsigned)blocks), dim3(256), 0, s, dy, y, x, coef, (int)relu, dx,
+                       (int)acc_dx, dres, (int)acc_dres, nvec, C);
+  else
+    hipLaunchKernelGGL((bn_bwd_apply_k<T, 1>), dim3((unsigned)blocks), dim3(256), 0, s, dy, y, x, coef, (int)relu, dx,
+                       (int)acc_dx, dres, (int)acc_dres, nvec, C);
+}
+
+template <typename T>
+static void colsum_t(const T* a, int64_t M, int C, float* out, float* partials, hipStream_t s) {
+  const int vec = pick_vec<T>(C, a, nullptr, nullptr, nullptr);
+  constexpr int V = sizeof(T) == 2 ? 8 : 4;
+  ReducePlan p = vec > 1 ? launch_reduce<T, V, 2>(a, nullptr, nullptr, nullptr, false, M, C, partials, s)
+                         : launch_reduce<T, 1, 2>(a, nullptr, nullptr, nullptr, false, M, C, partials, s);
+  hipLaunchKernelGGL((col_finalize_k<T, 2>), dim3((unsigned)cdiv(C, 256)), dim3(256), 0, s, partials, p.chunks, M, C,
+                     (const T*)nullptr, (const T*)nullptr, (float*)nullptr, out, (float*)nullptr, (float*)nullptr);
+}
+
+void bn_forward(int dtype, const void* x, const void* gamma, const void* beta, const void* res, bool relu, void* y,
+                int64_t M, int C, float* stats, float* partials, hipStream_t s) {
+  if (dtype == CD_BF16)
+    bn_forward_t<bf16_t>((const bf16_t*)x, (const bf16_t*)gamma, (const bf16_t*)beta, (const bf16_t*)res, relu,
+                         (bf16_t*)y, M, C, stats, partials, s);
+  else
+    bn_forward_t<float>((const float*)x, (const float*)gamma, (const float*)beta, (const float*)res, relu, (float*)y, M,
+                        C, stats, partials, s);
+}
+void bn_backward(int dtype, const void* dy, const void* y, const void* x, const void* gamma, const float* stats,
+                 bool relu, void* dx, bool acc_dx, void* dres, bool acc_dres, float* dgamma, float* dbeta, float* coef,
+                 float* partials, int64_t M, int C, hipStream_t s) {
+  if (dtype == CD_BF16)
+    bn_backward_t<bf16_t>((const bf16_t*)dy, (const bf16_t*)y, (const bf16_t*)x, (const bf16_t*)gamma, stats, relu,
+                          (bf16_t*)dx, acc_dx, (bf16_t*)dres, acc_dres, dgamma, dbeta, coef, partials, M, C, s);
+  else
+    bn_backward_t<float>((const float*)dy, (const float*)y, (const float*)x, (const float*)gamma, stats, relu,
+                         (float*)dx, acc_dx, (float*)dres, acc_dres, dgamma, dbeta, coef, partials, M, C, s);
+}
+void colsum(int dtype, const void* a, int64_t M, int C, float* out, float* partials, hipStream_t s) {
+  if (dtype == CD_BF16) colsum_t<bf16_t>((const bf16_t*)a, M, C, out, partials, s);
+  else colsum_t<float>((const float*)a, M, C, out, partials, s);
+}
+
+}  // namespace cd

@@ -38,6 +38,11 @@ def round_bf16(x):
     return bf16_to_f32(bf16_bits(x)).reshape(np.shape(x))
 
 
+def round_bf16_f64(x):
+    """Round a float64 array to the nearest bfloat16 value, returned as float64."""
+    return round_bf16(np.asarray(x, dtype=np.float32)).astype(np.float64)
+
+
 def he_init(param_table, seed, jitter=0.0):
     """param_table: ordered (name, shape, kind, fan_in); returns the flat float32 vector."""
     rng = _rng(seed)

@@ -1,0 +1,82 @@
+"""Helpers shared by the GPU parity tests: build a case, run it through the C ABI, read tensors back."""
+import numpy as np
+import torch
+
+from oracle.step import codistill_step
+from paper_2010_02838_amd import synth
+
+
+def rel(a, b):
+    nb = np.linalg.norm(b)
+    return float(np.linalg.norm(np.asarray(a, dtype=np.float64) - b) / (nb if nb > 0 else 1.0))
+
+
+def norm_err(a, b):
+    nb = np.linalg.norm(b)
+    return float(abs(np.linalg.norm(np.asarray(a, dtype=np.float64)) - nb) / nb) if nb > 0 else float(np.linalg.norm(a))
+
+
+class Case:
+    """Inputs of one codistillation step for an architecture (library preset kwargs + oracle arch)."""
+
+    def __init__(self, arch_kw, ref_arch, dtype_name, batch, res, classes, jitter=0.1, v_scale=0.0):
+        from paper_2010_02838_amd import binding as B
+        self.B = B
+        self.dtype = B.CD_BF16 if dtype_name == "bf16" else B.CD_F32
+        kw = dict(arch_kw)
+        arch = B.arch_preset(kw.pop("kind"), in_h=res, in_w=res, classes=classes, **kw)
+        self.model, self.peer = B.Model(arch, self.dtype), B.Model(arch, self.dtype)
+        self.ref_arch, self.batch, self.res, self.classes = ref_arch, batch, res, classes
+        table = self.model.param_table()
+        assert table == [(n, tuple(s), k, f) for n, s, k, f in ref_arch.params]
+        self.th, self.thp = synth.he_init(table, 1, jitter), synth.he_init(table, 2, jitter)
+        self.x, self.y = synth.images(batch, res, res, 3, seed=0), synth.labels(batch, classes, seed=3)
+        if self.dtype == B.CD_BF16:   # both sides consume the same bf16-rounded weights and images
+            self.th, self.thp, self.x = (synth.round_bf16(a) for a in (self.th, self.thp, self.x))
+        self.v0 = None
+        if v_scale:
+            self.v0 = (np.random.default_rng(5).standard_normal(self.th.size) * v_scale).astype(np.float32)
+
+    def oracle(self, alpha=1.0, lr=0.1, mu=0.9, wd=0.0, dist="mse", store=None):
+        return codistill_step(self.ref_arch, self.th.astype(np.float64), [self.thp.astype(np.float64)],
+                              self.x.astype(np.float64), self.y, alpha, lr, mu,
+                              v=None if self.v0 is None else self.v0.astype(np.float64), weight_decay=wd, dist=dist,
+                              store=store)
+
+    def gpu(self, alpha=1.0, lr=0.1, mu=0.9, wd=0.0, dist="mse"):
+        from paper_2010_02838_amd.runner import StepRunner, pack_flat, unpack_flat, to_device
+        B, model = self.B, self.model
+        r = StepRunner(model, [self.peer], self.batch)
+        r.load(pack_flat(model, self.th), [pack_flat(self.peer, self.thp)],
+               None if self.v0 is None else pack_flat(model, self.v0))
+        xd = to_device(self.x, model.torch_dtype)
+        yd = torch.from_numpy(self.y).to("cuda:0")
+        r.step(xd, yd, alpha, lr, mu, weight_decay=wd, dist_kind=B.CD_DIST_KL if dist == "kl" else B.CD_DIST_MSE_LOGITS)
+        torch.cuda.synchronize()
+        got = dict(logits=r.logits.cpu().numpy(), peer_logits=r.peer_logits[0].cpu().numpy(),
+                   loss=r.loss.cpu().numpy()[:3].astype(np.float64), dz=r.dz.cpu().numpy(),
+                   grad=unpack_flat(model, r.grads.cpu().numpy()), theta=unpack_flat(model, r.master.cpu().numpy()),
+                   v=unpack_flat(model, r.momentum.cpu().numpy()))
+        if r.lowp is not None:   # the bf16 shadow is the rounded image of the fp32 master weights
+            bits = r.lowp.view(torch.int16).cpu().numpy().view(np.uint16)
+            np.testing.assert_array_equal(bits, synth.bf16_bits(r.master.cpu().numpy()))
+        self.runner = r
+        return got
+
+    def per_tensor(self, flat):
+        off, out = 0, {}
+        for name, shape, _, _ in self.ref_arch.params:
+            n = int(np.prod(shape))
+            out[name] = np.asarray(flat[off:off + n]).reshape(shape)
+            off += n
+        return out
+
+    def read(self, offset, shape, f32=False):
+        """A tensor out of the runner's workspace, as float64."""
+        ws = self.runner.ws
+        n = int(np.prod(shape))
+        if f32 or self.dtype == self.B.CD_F32:
+            a = ws[offset:offset + 4 * n].view(torch.float32).cpu().numpy()
+        else:
+            a = synth.bf16_to_f32(ws[offset:offset + 2 * n].view(torch.int16).cpu().numpy().view(np.uint16))
+        return a.astype(np.float64).reshape(shape)

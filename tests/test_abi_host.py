@@ -1,0 +1,135 @@
+"""Host-only checks of the C-ABI library: it loads, exports every declared symbol, rejects bad
+arguments before any launch, and its parameter tables match the oracle's architecture tables."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from oracle import nets
+from paper_2010_02838_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_exports_every_declared_symbol():
+    text = open(os.path.join(ROOT, "include", "codistill.h")).read()
+    declared = set(re.findall(r"\b(codistill_[a-z_]+)\s*\(", text))
+    assert len(declared) >= 15
+    for name in declared:
+        assert hasattr(B.lib, name), name
+    assert set(B.EXPORTED) == declared
+    assert B.lib.codistill_version().decode().startswith("codistill")
+
+
+def _table(model):
+    return [(p["name"], p["shape"], p["kind"], p["fan_in"]) for p in model.params]
+
+
+@pytest.mark.parametrize("dtype", [B.CD_F32, B.CD_BF16])
+def test_param_tables_match_oracle(dtype):
+    cases = [
+        (B.arch_preset(B.CD_ARCH_TINY_CNN), nets.tiny_cnn()),
+        (B.arch_preset(B.CD_ARCH_RESNET_BASIC), nets.resnet20()),
+        (B.arch_preset(B.CD_ARCH_RESNET_BOTTLENECK), nets.resnet50()),
+        (B.arch_preset(B.CD_ARCH_RESNET_BASIC, widths=[4, 8, 16], blocks=[2, 1, 1], stem_width=4),
+         nets.resnet20(widths=(4, 8, 16), blocks=(2, 1, 1))),
+        (B.arch_preset(B.CD_ARCH_RESNET_BOTTLENECK, widths=[4, 8, 8, 16], blocks=[2, 1, 1, 1], stem_width=8, classes=7),
+         nets.resnet50(classes=7, widths=(4, 8, 8, 16), blocks=(2, 1, 1, 1), stem=8)),
+    ]
+    for arch, ref in cases:
+        m = B.Model(arch, dtype)
+        assert _table(m) == [(n, tuple(s), k, f) for n, s, k, f in ref.params]
+        assert sum(p["size"] for p in m.params) == ref.n_params()
+        for p in m.params:
+            assert p["offset"] % 8 == 0
+        assert m.n_elements >= ref.n_params()
+        assert m.workspace_bytes(2, True) > m.workspace_bytes(2, False) > 0
+
+
+def test_resnet50_size_matches_paper():
+    # Section 3: 32-bit ResNet50 is 8e8 bits
+    m = B.Model(B.arch_preset(B.CD_ARCH_RESNET_BOTTLENECK), B.CD_BF16)
+    assert sum(p["size"] for p in m.params) == 25557032
+
+
+def _rc(fn, *args):
+    return fn(*args)
+
+
+def test_model_create_rejects_bad_arguments():
+    a = B.arch_preset(B.CD_ARCH_TINY_CNN)
+    h = ctypes.c_void_p()
+    assert B.lib.codistill_model_create(None, B.CD_F32, ctypes.byref(h)) == B.CD_ERR_INVALID_ARG
+    assert B.lib.codistill_model_create(ctypes.byref(a), 7, ctypes.byref(h)) == B.CD_ERR_INVALID_ARG
+    a.kind = 99
+    assert B.lib.codistill_model_create(ctypes.byref(a), B.CD_F32, ctypes.byref(h)) == B.CD_ERR_INVALID_ARG
+    assert b"kind" in B.lib.codistill_last_error()
+    bad = B.arch_preset(B.CD_ARCH_RESNET_BOTTLENECK, in_h=0)
+    assert B.lib.codistill_model_create(ctypes.byref(bad), B.CD_F32, ctypes.byref(h)) == B.CD_ERR_INVALID_ARG
+    a2 = B.ArchDesc()
+    assert B.lib.codistill_arch_preset(42, ctypes.byref(a2)) == B.CD_ERR_INVALID_ARG
+
+
+def test_forward_backward_reject_bad_arguments_before_launch():
+    m = B.Model(B.arch_preset(B.CD_ARCH_TINY_CNN), B.CD_F32)
+    fake = ctypes.c_void_p(0x1000)       # never dereferenced: validation fails first
+    f = B.lib.codistill_forward
+    need = m.workspace_bytes(8, True)
+    assert f(m._h, None, fake, 8, 1, 0, None, fake, need, fake, None) == B.CD_ERR_INVALID_ARG
+    assert f(m._h, fake, fake, 0, 1, 0, None, fake, need, fake, None) == B.CD_ERR_INVALID_ARG
+    assert f(m._h, fake, fake, 8, 1, 5, None, fake, need, fake, None) == B.CD_ERR_INVALID_ARG
+    assert f(m._h, fake, fake, 8, 1, B.CD_BN_RUNNING, None, fake, need, fake, None) == B.CD_ERR_UNSUPPORTED
+    assert f(m._h, fake, fake, 8, 1, 0, None, fake, need - 1, fake, None) == B.CD_ERR_WORKSPACE_TOO_SMALL
+    assert f(m._h, ctypes.c_void_p(0x1004), fake, 8, 1, 0, None, fake, need, fake, None) == B.CD_ERR_INVALID_ARG
+    bwd = B.lib.codistill_backward
+    assert bwd(m._h, fake, fake, 8, fake, need, None, fake, None) == B.CD_ERR_INVALID_ARG
+    assert bwd(m._h, fake, fake, 8, fake, need - 1, fake, fake, None) == B.CD_ERR_WORKSPACE_TOO_SMALL
+    assert bwd(m._h, fake, fake, -3, fake, need, fake, fake, None) == B.CD_ERR_INVALID_ARG
+
+
+def test_loss_rejects_bad_arguments_before_launch():
+    fake = ctypes.c_void_p(0x1000)
+    peers = (ctypes.c_void_p * 1)(0x2000)
+    g = B.lib.codistill_loss_grad
+
+    def cfg(**kw):
+        d = dict(alpha=1.0, label_smoothing=0.0, dist_kind=0, mse_reduction=0, ignore_index=-1, n_peers=1)
+        d.update(kw)
+        return ctypes.byref(B.LossCfg(**d))
+
+    need = B.loss_scratch_bytes(16, 32)
+    assert need >= 16 * 8
+    ok_args = lambda c, rows=16, cols=32, sc=need, z=fake, p=peers: (z, p, fake, rows, cols, c, fake, fake, fake, sc, None)
+    assert g(*ok_args(cfg(), z=None)) == B.CD_ERR_INVALID_ARG
+    assert g(*ok_args(cfg(), rows=0)) == B.CD_ERR_INVALID_ARG
+    assert g(*ok_args(cfg(), cols=0)) == B.CD_ERR_INVALID_ARG
+    assert g(*ok_args(cfg(), cols=(1 << 24) + 1)) == B.CD_ERR_INVALID_ARG
+    assert g(*ok_args(cfg(dist_kind=3))) == B.CD_ERR_INVALID_ARG
+    assert g(*ok_args(cfg(mse_reduction=2))) == B.CD_ERR_INVALID_ARG
+    assert g(*ok_args(cfg(n_peers=-1))) == B.CD_ERR_INVALID_ARG
+    assert g(*ok_args(cfg(n_peers=9))) == B.CD_ERR_INVALID_ARG
+    assert g(*ok_args(cfg(label_smoothing=1.0))) == B.CD_ERR_INVALID_ARG
+    assert g(*ok_args(cfg(label_smoothing=-0.1))) == B.CD_ERR_INVALID_ARG
+    assert g(*ok_args(cfg(), p=None)) == B.CD_ERR_INVALID_ARG
+    assert g(*ok_args(cfg(), z=ctypes.c_void_p(0x1008))) == B.CD_ERR_INVALID_ARG
+    assert g(*ok_args(cfg(), sc=need - 1)) == B.CD_ERR_WORKSPACE_TOO_SMALL
+    assert b"scratch" in B.lib.codistill_last_error()
+    b = ctypes.c_size_t()
+    assert B.lib.codistill_loss_scratch_bytes(0, 5, ctypes.byref(b)) == B.CD_ERR_INVALID_ARG
+
+
+def test_sgd_rejects_bad_arguments_before_launch():
+    fake = ctypes.c_void_p(0x1000)
+    s = B.lib.codistill_sgd_step
+    assert s(None, fake, fake, None, 8, 0.1, 0.9, 0.0, 0, None) == B.CD_ERR_INVALID_ARG
+    assert s(fake, fake, fake, None, 0, 0.1, 0.9, 0.0, 0, None) == B.CD_ERR_INVALID_ARG
+    assert s(fake, ctypes.c_void_p(0x1004), fake, None, 8, 0.1, 0.9, 0.0, 0, None) == B.CD_ERR_INVALID_ARG
+    assert s(fake, fake, fake, None, 8, float("nan"), 0.9, 0.0, 0, None) == B.CD_ERR_INVALID_ARG
+
+
+def test_profile_interface_on_host():
+    assert B.lib.codistill_profile_reset() == 0
+    ms = ctypes.c_double(1.0)
+    assert B.lib.codistill_profile_get(99, ctypes.byref(ms), None, None, None) == B.CD_ERR_INVALID_ARG
+    assert B.lib.codistill_profile_get(0, ctypes.byref(ms), None, None, None) == 0 and ms.value == 0.0

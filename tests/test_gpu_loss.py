@@ -1,0 +1,142 @@
+"""GPU parity of the fused loss kernel against the float64 oracle (tolerance 1e-5 relative)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle.loss import codistill_loss_grad as oracle_loss
+from paper_2010_02838_amd import synth
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-5   # stated tolerance for the fp32 loss kernel: relative, L2 for tensors, |a-b|/|b| for scalars
+
+MODES = {"mse": (0, 0, "mse", "mean_all"), "mse_rows": (0, 1, "mse", "mean_rows"), "kl": (1, 0, "kl", "mean_all")}
+
+
+def run_gpu(z, peers, t, alpha, eps, mode, ignore_index=-1, inplace=False):
+    from paper_2010_02838_amd import binding as B
+    dev = "cuda:0"
+    dk, red, _, _ = MODES[mode]
+    zt = torch.from_numpy(z).to(dev)
+    pts = [torch.from_numpy(p).to(dev) for p in peers]
+    tt = torch.from_numpy(np.asarray(t, dtype=np.int32)).to(dev)
+    loss = torch.zeros(4, device=dev)
+    dz = zt if inplace else torch.empty_like(zt)
+    scratch = torch.empty(B.loss_scratch_bytes(*z.shape), dtype=torch.uint8, device=dev)
+    B.codistill_loss_grad(zt, pts, tt, loss, dz, scratch, alpha, eps, dk, red, ignore_index)
+    torch.cuda.synchronize()
+    l = loss.cpu().numpy()
+    return l[:3].astype(np.float64), int(l[3:4].view(np.int32)[0]), dz.cpu().numpy()
+
+
+def rel(a, b):
+    nb = np.linalg.norm(b)
+    return np.linalg.norm(a.astype(np.float64) - b) / (nb if nb > 0 else 1.0)
+
+
+def check(z, peers, t, alpha, eps, mode, **kw):
+    (tot, task, dist), dz_ref = oracle_loss(z, peers, t, alpha, eps, MODES[mode][2], MODES[mode][3])
+    l, status, dz = run_gpu(z, peers, t, alpha, eps, mode, **kw)
+    assert status == 0
+    assert rel(dz, dz_ref) <= TOL
+    for got, want in zip(l, (tot, task, dist)):
+        assert abs(got - want) <= TOL * max(abs(want), 1e-30) or (want == 0 and got == 0), (got, want)
+    return l, dz
+
+
+SHAPES = [(8, 10), (128, 10), (5, 33), (256, 1000), (37, 256), (19, 4100), (21, 8192), (9, 16380), (6, 32768),
+          (3, 40000)]
+
+
+@pytest.mark.parametrize("rows,cols", SHAPES)
+@pytest.mark.parametrize("mode", ["mse", "kl"])
+def test_loss_parity_shapes(rows, cols, mode):
+    z = synth.logits(rows, cols, 3.0, seed=rows)
+    zp = synth.logits(rows, cols, 3.0, seed=rows + 1000)
+    t = synth.labels(rows, cols, seed=7)
+    t[rows // 2] = -1
+    check(z, [zp], t, 0.5, 0.0, mode)
+
+
+@pytest.mark.parametrize("mode", ["mse", "mse_rows", "kl"])
+@pytest.mark.parametrize("eps", [0.0, 0.1])
+def test_loss_parity_modes(mode, eps):
+    z, zp = synth.logits(64, 1000, 3.0, seed=1), synth.logits(64, 1000, 3.0, seed=2)
+    t = synth.labels(64, 1000, seed=3)
+    check(z, [zp], t, 1.0, eps, mode)
+    check(z, [zp], t, 1.0, eps, mode, inplace=True)
+
+
+@pytest.mark.parametrize("cols", [10, 1000, 32768])
+def test_no_peer_and_alpha_zero(cols):
+    z, zp = synth.logits(16, cols, 3.0, seed=1), synth.logits(16, cols, 3.0, seed=2)
+    t = synth.labels(16, cols, seed=3)
+    l0, dz0 = check(z, [], t, 1.0, 0.0, "mse")
+    for mode in ("mse", "kl"):
+        l1, dz1 = check(z, [zp], t, 0.0, 0.0, mode)
+        assert l1[0] == l1[1] == l0[0]
+        np.testing.assert_array_equal(dz0, dz1)
+
+
+@pytest.mark.parametrize("cols", [10, 1000, 32768])
+@pytest.mark.parametrize("mode", ["mse", "kl"])
+def test_identical_peer_is_exactly_zero(cols, mode):
+    z = synth.logits(16, cols, 3.0, seed=1)
+    t = synth.labels(16, cols, seed=3)
+    l, _, dz = run_gpu(z, [z.copy()], t, 0.7, 0.0, mode)
+    l0, _, dz0 = run_gpu(z, [], t, 0.7, 0.0, mode)
+    assert l[2] == 0.0 and l[0] == l[1] == l0[0]
+    np.testing.assert_array_equal(dz, dz0)
+
+
+@pytest.mark.parametrize("mode", ["mse", "kl"])
+@pytest.mark.parametrize("npeers", [2, 3])
+def test_n_way(mode, npeers):
+    z = synth.logits(32, 1000, 3.0, seed=1)
+    peers = [synth.logits(32, 1000, 3.0, seed=10 + j) for j in range(npeers)]
+    t = synth.labels(32, 1000, seed=3)
+    check(z, peers, t, 0.8, 0.1, mode)
+
+
+def test_zero_logits_closed_form_and_edge_rows():
+    z = np.zeros((4, 1000), dtype=np.float32)
+    l, status, dz = run_gpu(z, [], np.array([0, 1, 2, 3]), 1.0, 0.0, "mse")
+    assert abs(l[1] - np.log(1000.0)) <= TOL * np.log(1000.0)
+    # all rows ignored: zero loss, zero gradient
+    l, status, dz = run_gpu(synth.logits(4, 1000, 3.0, 1), [synth.logits(4, 1000, 3.0, 2)], np.full(4, -1), 1.0, 0.0, "kl")
+    assert status == 0 and np.all(l == 0) and np.all(dz == 0)
+    # a target outside [0, cols) is skipped and flagged
+    l, status, dz = run_gpu(synth.logits(4, 1000, 3.0, 1), [], np.array([0, 1000, 2, 3]), 1.0, 0.0, "mse")
+    assert status == 1 and np.all(dz[1] == 0) and np.any(dz[0] != 0)
+    (_, task, _), dref = oracle_loss(synth.logits(4, 1000, 3.0, 1), [], np.array([0, -1, 2, 3]), 1.0)
+    assert abs(l[1] - task) <= TOL * task and rel(dz, dref) <= TOL
+    # single row, single column
+    l, status, dz = run_gpu(np.array([[2.5]], dtype=np.float32), [np.array([[1.5]], dtype=np.float32)], [0], 1.0, 0.0, "mse")
+    assert l[1] == 0.0 and abs(l[2] - 1.0) < 1e-6 and abs(dz[0, 0] - 2.0) < 1e-6
+
+
+@pytest.mark.parametrize("mode", ["mse", "kl"])
+def test_full_size_sampled(mode):
+    """The benchmarked shape, [8192 x 32768] with alpha 0.5: sampled rows one by one, and the
+    scalar losses from the oracle applied to row chunks (the terms are means over rows)."""
+    rows, cols, alpha = 8192, 32768, 0.5
+    z = synth.logits(rows, cols, 3.0, seed=11)
+    zp = synth.logits(rows, cols, 3.0, seed=12)
+    t = synth.labels(rows, cols, seed=13)
+    t[::97] = -1
+    l, status, dz = run_gpu(z, [zp], t, alpha, 0.0, mode)
+    assert status == 0
+    nvalid = int((t != -1).sum())
+    task = dist = 0.0
+    for r0 in range(0, rows, 512):
+        sl = slice(r0, r0 + 512)
+        nv = int((t[sl] != -1).sum())
+        (_, a, b), dref = oracle_loss(z[sl], [zp[sl]], t[sl], alpha, 0.0, MODES[mode][2])
+        task += a * nv / nvalid
+        dist += b * nv / nvalid
+        if r0 % 2048 == 0:
+            assert rel(dz[sl], dref * nv / nvalid) <= TOL
+    assert abs(l[1] - task) <= TOL * task
+    assert abs(l[2] - dist) <= TOL * dist
+    assert abs(l[0] - (task + alpha * dist)) <= TOL * (task + alpha * dist)
+    if mode == "mse":
+        assert abs(l[2] - 18.0) < 0.02      # E[D] = 2 sigma^2 for independent N(0, 9) logits
