@@ -416,13 +416,20 @@ __global__ void __launch_bounds__(256) wgrad_kernel(WgradArgs a) {
     }
 }
 
+// 64 outputs x 4 split lanes per block; every lane adds every 4th split, fixed-order combine in LDS
 __global__ void __launch_bounds__(256) wgrad_reduce_kernel(const float* __restrict__ part, float* __restrict__ out,
                                                            int64_t n, int splits) {
-  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (i >= n) return;
+  __shared__ float sm[4][64];
+  const int ol = threadIdx.x & 63, lane = threadIdx.x >> 6;
+  const int64_t i = (int64_t)blockIdx.x * 64 + ol;
   float s = 0.f;
-  for (int j = 0; j < splits; j++) s += part[(int64_t)j * n + i];
-  out[i] = s;
+  if (i < n) {
+#pragma unroll 8
+    for (int j = lane; j < splits; j += 4) s += part[(int64_t)j * n + i];
+  }
+  sm[lane][ol] = s;
+  __syncthreads();
+  if (lane == 0 && i < n) out[i] = (sm[0][ol] + sm[1][ol]) + (sm[2][ol] + sm[3][ol]);
 }
 
 void conv_wgrad_mfma(const bf16_t* x, const bf16_t* dy, float* dw, const ConvGeom& g, float* partials,
@@ -452,7 +459,7 @@ void conv_wgrad_mfma(const bf16_t* x, const bf16_t* dy, float* dw, const ConvGeo
   else if (bk == 128) hipLaunchKernelGGL((wgrad_kernel<64, 128>), grid, dim3(256), 0, s, a);
   else hipLaunchKernelGGL((wgrad_kernel<64, 64>), grid, dim3(256), 0, s, a);
   if (splits > 1)
-    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)cdiv(nk, 256)), dim3(256), 0, s, partials, dw, nk,
+    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)cdiv(nk, 64)), dim3(256), 0, s, partials, dw, nk,
                        (int)splits);
 }
 

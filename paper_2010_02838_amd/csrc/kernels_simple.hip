@@ -125,78 +125,140 @@ void relu_bwd_inplace(int dtype, void* dy, const void* y, int64_t n, hipStream_t
   CD_DISPATCH_T(dtype, hipLaunchKernelGGL(relu_bwd_k<T>, grid1d(n), dim3(256), 0, s, (T*)dy, (const T*)y, n));
 }
 
-template <typename T>
+// V channels per thread (V = 8 bf16 / 4 fp32 when the channel count allows 16-byte vectors)
+template <typename T, int V> struct PoolVec {
+  __device__ static void ld(const T* p, float (&v)[V]) {
+#pragma unroll
+    for (int i = 0; i < V; i++) v[i] = Cvt<T>::ld(p[i]);
+  }
+  __device__ static void st(T* p, const float (&v)[V]) {
+#pragma unroll
+    for (int i = 0; i < V; i++) p[i] = Cvt<T>::st(v[i]);
+  }
+};
+template <> struct PoolVec<bf16_t, 8> {
+  __device__ static void ld(const bf16_t* p, float (&v)[8]) {
+    const uint4 t = *reinterpret_cast<const uint4*>(p);
+    const uint32_t u[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+    for (int i = 0; i < 4; i++) { v[2 * i] = __uint_as_float(u[i] << 16); v[2 * i + 1] = __uint_as_float(u[i] & 0xffff0000u); }
+  }
+  __device__ static void st(bf16_t* p, const float (&v)[8]) {
+    uint32_t u[4];
+#pragma unroll
+    for (int i = 0; i < 4; i++) u[i] = (uint32_t)f32_to_bf16(v[2 * i]) | ((uint32_t)f32_to_bf16(v[2 * i + 1]) << 16);
+    *reinterpret_cast<uint4*>(p) = make_uint4(u[0], u[1], u[2], u[3]);
+  }
+};
+
+template <typename T, int V>
 __global__ void __launch_bounds__(256) maxpool_fwd_k(const T* __restrict__ x, T* __restrict__ y, int64_t B, int H,
                                                      int W, int C, int Ho, int Wo, int k, int stride, int pad) {
+  const int CV = C / V;
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (idx >= B * Ho * Wo * C) return;
-  const int c = idx % C;
-  int64_t p = idx / C;
+  if (idx >= B * Ho * Wo * CV) return;
+  const int c = (int)(idx % CV) * V;
+  int64_t p = idx / CV;
   const int wo = p % Wo; p /= Wo;
   const int ho = p % Ho;
   const int64_t b = p / Ho;
-  float best = -INFINITY;
+  float best[V];
+#pragma unroll
+  for (int i = 0; i < V; i++) best[i] = -INFINITY;
   for (int r = 0; r < k; r++) {
     const int hi = ho * stride - pad + r;
     if (hi < 0 || hi >= H) continue;
     for (int s = 0; s < k; s++) {
       const int wi = wo * stride - pad + s;
       if (wi < 0 || wi >= W) continue;
-      best = fmaxf(best, Cvt<T>::ld(x[((b * H + hi) * W + wi) * C + c]));
+      float v[V];
+      PoolVec<T, V>::ld(x + ((b * H + hi) * W + wi) * C + c, v);
+#pragma unroll
+      for (int i = 0; i < V; i++) best[i] = fmaxf(best[i], v[i]);
     }
   }
-  y[idx] = Cvt<T>::st(best);
+  PoolVec<T, V>::st(y + ((b * Ho + ho) * Wo + wo) * C + c, best);
 }
 
 // Gradient goes to the first maximum of each window in row-major tap order (recomputed here).
-template <typename T>
+template <typename T, int V>
 __global__ void __launch_bounds__(256) maxpool_bwd_k(const T* __restrict__ x, const T* __restrict__ dy,
                                                      T* __restrict__ dx, int accumulate, int64_t B, int H, int W,
                                                      int C, int Ho, int Wo, int k, int stride, int pad) {
+  const int CV = C / V;
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (idx >= B * H * W * C) return;
-  const int c = idx % C;
-  int64_t p = idx / C;
+  if (idx >= B * H * W * CV) return;
+  const int c = (int)(idx % CV) * V;
+  int64_t p = idx / CV;
   const int wi = p % W; p /= W;
   const int hi = p % H;
   const int64_t b = p / H;
-  float acc = 0.f;
-  for (int ho = 0; ho < Ho; ho++) {
+  float acc[V], mine[V];
+#pragma unroll
+  for (int i = 0; i < V; i++) acc[i] = 0.f;
+  PoolVec<T, V>::ld(x + ((b * H + hi) * W + wi) * C + c, mine);
+  // output windows that contain (hi, wi): ho*stride - pad <= hi <= ho*stride - pad + k - 1
+  int ho0 = hi + pad - k + 1; ho0 = ho0 <= 0 ? 0 : (ho0 + stride - 1) / stride;
+  int wo0 = wi + pad - k + 1; wo0 = wo0 <= 0 ? 0 : (wo0 + stride - 1) / stride;
+  int ho1 = (hi + pad) / stride; if (ho1 > Ho - 1) ho1 = Ho - 1;
+  int wo1 = (wi + pad) / stride; if (wo1 > Wo - 1) wo1 = Wo - 1;
+  for (int ho = ho0; ho <= ho1; ho++) {
     const int h0 = ho * stride - pad;
-    if (hi < h0 || hi >= h0 + k) continue;
-    for (int wo = 0; wo < Wo; wo++) {
+    for (int wo = wo0; wo <= wo1; wo++) {
       const int w0 = wo * stride - pad;
-      if (wi < w0 || wi >= w0 + k) continue;
-      float best = -INFINITY;
-      int bh = -1, bw = -1;
+      // this position wins the window iff no earlier tap is >= it and no later tap is > it
+      bool win[V];
+#pragma unroll
+      for (int i = 0; i < V; i++) win[i] = true;
       for (int r = 0; r < k; r++) {
         const int hh = h0 + r;
         if (hh < 0 || hh >= H) continue;
         for (int s = 0; s < k; s++) {
           const int ww = w0 + s;
-          if (ww < 0 || ww >= W) continue;
-          const float v = Cvt<T>::ld(x[((b * H + hh) * W + ww) * C + c]);
-          if (v > best) { best = v; bh = hh; bw = ww; }
+          if (ww < 0 || ww >= W || (hh == hi && ww == wi)) continue;
+          float v[V];
+          PoolVec<T, V>::ld(x + ((b * H + hh) * W + ww) * C + c, v);
+          const bool earlier = hh < hi || (hh == hi && ww < wi);
+#pragma unroll
+          for (int i = 0; i < V; i++) win[i] = win[i] && (earlier ? v[i] < mine[i] : v[i] <= mine[i]);
         }
       }
-      if (bh == hi && bw == wi) acc += Cvt<T>::ld(dy[((b * Ho + ho) * Wo + wo) * C + c]);
+      float g[V];
+      PoolVec<T, V>::ld(dy + ((b * Ho + ho) * Wo + wo) * C + c, g);
+#pragma unroll
+      for (int i = 0; i < V; i++) acc[i] += win[i] ? g[i] : 0.f;
     }
   }
-  if (accumulate) acc += Cvt<T>::ld(dx[idx]);
-  dx[idx] = Cvt<T>::st(acc);
+  T* dp = dx + ((b * H + hi) * W + wi) * C + c;
+  if (accumulate) {
+    float o[V];
+    PoolVec<T, V>::ld(dp, o);
+#pragma unroll
+    for (int i = 0; i < V; i++) acc[i] += o[i];
+  }
+  PoolVec<T, V>::st(dp, acc);
 }
 
 void maxpool_fwd(int dtype, const void* x, void* y, int64_t B, int H, int W, int C, int k, int stride, int pad,
                  hipStream_t s) {
   const int Ho = (H + 2 * pad - k) / stride + 1, Wo = (W + 2 * pad - k) / stride + 1;
-  CD_DISPATCH_T(dtype, hipLaunchKernelGGL(maxpool_fwd_k<T>, grid1d(B * Ho * Wo * C), dim3(256), 0, s, (const T*)x,
-                                          (T*)y, B, H, W, C, Ho, Wo, k, stride, pad));
+  if (dtype == CD_BF16 && C % 8 == 0 && aligned16(x) && aligned16(y))
+    hipLaunchKernelGGL((maxpool_fwd_k<bf16_t, 8>), grid1d(B * Ho * Wo * (C / 8)), dim3(256), 0, s, (const bf16_t*)x,
+                       (bf16_t*)y, B, H, W, C, Ho, Wo, k, stride, pad);
+  else
+    CD_DISPATCH_T(dtype, hipLaunchKernelGGL((maxpool_fwd_k<T, 1>), grid1d(B * Ho * Wo * C), dim3(256), 0, s,
+                                            (const T*)x, (T*)y, B, H, W, C, Ho, Wo, k, stride, pad));
 }
 void maxpool_bwd(int dtype, const void* x, const void* dy, void* dx, bool accumulate, int64_t B, int H, int W, int C,
                  int k, int stride, int pad, hipStream_t s) {
   const int Ho = (H + 2 * pad - k) / stride + 1, Wo = (W + 2 * pad - k) / stride + 1;
-  CD_DISPATCH_T(dtype, hipLaunchKernelGGL(maxpool_bwd_k<T>, grid1d(B * H * W * C), dim3(256), 0, s, (const T*)x,
-                                          (const T*)dy, (T*)dx, (int)accumulate, B, H, W, C, Ho, Wo, k, stride, pad));
+  if (dtype == CD_BF16 && C % 8 == 0 && aligned16(x) && aligned16(dy) && aligned16(dx))
+    hipLaunchKernelGGL((maxpool_bwd_k<bf16_t, 8>), grid1d(B * H * W * (C / 8)), dim3(256), 0, s, (const bf16_t*)x,
+                       (const bf16_t*)dy, (bf16_t*)dx, (int)accumulate, B, H, W, C, Ho, Wo, k, stride, pad);
+  else
+    CD_DISPATCH_T(dtype, hipLaunchKernelGGL((maxpool_bwd_k<T, 1>), grid1d(B * H * W * C), dim3(256), 0, s,
+                                            (const T*)x, (const T*)dy, (T*)dx, (int)accumulate, B, H, W, C, Ho, Wo, k,
+                                            stride, pad));
 }
 
 template <typename T>

@@ -113,18 +113,31 @@ __global__ void __launch_bounds__(256) col_reduce_k(const T* __restrict__ a0, co
 }
 
 // FIN 0: BatchNorm statistics.  FIN 1: BatchNorm backward sums.  FIN 2: plain column sum.
+// Block = 64 channels x 16 chunk lanes: every lane adds every 16th chunk (loads unrolled so that
+// several are in flight), the 16 lanes of a channel are combined in LDS in a fixed order.
 template <typename T, int FIN>
-__global__ void __launch_bounds__(256) col_finalize_k(const float* __restrict__ partials, int chunks, int64_t M, int C,
-                                                      const T* __restrict__ gamma, const T* __restrict__ beta,
-                                                      float* __restrict__ stats, float* __restrict__ out0,
-                                                      float* __restrict__ out1, float* __restrict__ coef) {
-  const int c = blockIdx.x * 256 + threadIdx.x;
-  if (c >= C) return;
-  double s0 = 0.0, s1 = 0.0;
-  for (int j = 0; j < chunks; j++) {
-    s0 += (double)partials[((int64_t)j * 2 + 0) * C + c];
-    if (FIN != 2) s1 += (double)partials[((int64_t)j * 2 + 1) * C + c];
+__global__ void __launch_bounds__(1024) col_finalize_k(const float* __restrict__ partials, int chunks, int64_t M, int C,
+                                                       const T* __restrict__ gamma, const T* __restrict__ beta,
+                                                       float* __restrict__ stats, float* __restrict__ out0,
+                                                       float* __restrict__ out1, float* __restrict__ coef) {
+  __shared__ double sm[2][16][64];
+  const int cl = threadIdx.x & 63, lane = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + cl;
+  double a0 = 0.0, a1 = 0.0;
+  if (c < C) {
+#pragma unroll 4
+    for (int j = lane; j < chunks; j += 16) {
+      a0 += (double)partials[((int64_t)j * 2 + 0) * C + c];
+      if (FIN != 2) a1 += (double)partials[((int64_t)j * 2 + 1) * C + c];
+    }
   }
+  sm[0][lane][cl] = a0;
+  sm[1][lane][cl] = a1;
+  __syncthreads();
+  if (lane != 0 || c >= C) return;
+  double s0 = 0.0, s1 = 0.0;
+#pragma unroll
+  for (int j = 0; j < 16; j++) { s0 += sm[0][j][cl]; s1 += sm[1][j][cl]; }
   if (FIN == 0) {
     const double mean = s0 / (double)M;
     double var = s1 / (double)M - mean * mean;
@@ -221,7 +234,7 @@ static ReducePlan reduce_plan(int64_t M, int C, int vec) {
   p.cgroups = (int)cdiv(vc, 256);
   const int vcb = vc < 256 ? vc : 256;
   const int rpi = 256 / vcb;
-  int64_t target = 2048 / p.cgroups;                      // blocks to fill the chip several times
+  int64_t target = 1024 / p.cgroups;                      // blocks to fill the chip several times
   const int64_t cap = (int64_t)(kPartialsBytes / ((size_t)2 * C * 4));
   if (target > cap) target = cap;
   if (target < 1) target = 1;
@@ -255,7 +268,7 @@ static void bn_forward_t(const T* x, const T* gamma, const T* beta, const T* res
   constexpr int V = sizeof(T) == 2 ? 8 : 4;
   ReducePlan p = vec > 1 ? launch_reduce<T, V, 0>(x, nullptr, nullptr, nullptr, false, M, C, partials, s)
                          : launch_reduce<T, 1, 0>(x, nullptr, nullptr, nullptr, false, M, C, partials, s);
-  hipLaunchKernelGGL((col_finalize_k<T, 0>), dim3((unsigned)cdiv(C, 256)), dim3(256), 0, s, partials, p.chunks, M, C,
+  hipLaunchKernelGGL((col_finalize_k<T, 0>), dim3((unsigned)cdiv(C, 64)), dim3(1024), 0, s, partials, p.chunks, M, C,
                      gamma, beta, stats, (float*)nullptr, (float*)nullptr, (float*)nullptr);
   const int64_t nvec = M * C / vec;
   int64_t blocks = cdiv(nvec, 256);
@@ -275,7 +288,7 @@ static void bn_backward_t(const T* dy, const T* y, const T* x, const T* gamma, c
   constexpr int V = sizeof(T) == 2 ? 8 : 4;
   ReducePlan p = vec > 1 ? launch_reduce<T, V, 1>(dy, y, x, stats, relu, M, C, partials, s)
                          : launch_reduce<T, 1, 1>(dy, y, x, stats, relu, M, C, partials, s);
-  hipLaunchKernelGGL((col_finalize_k<T, 1>), dim3((unsigned)cdiv(C, 256)), dim3(256), 0, s, partials, p.chunks, M, C,
+  hipLaunchKernelGGL((col_finalize_k<T, 1>), dim3((unsigned)cdiv(C, 64)), dim3(1024), 0, s, partials, p.chunks, M, C,
                      gamma, (const T*)nullptr, const_cast<float*>(stats), dgamma, dbeta, coef);
   const int64_t nvec = M * C / vec;
   int64_t blocks = cdiv(nvec, 256);
@@ -294,7 +307,7 @@ static void colsum_t(const T* a, int64_t M, int C, float* out, float* partials, 
   constexpr int V = sizeof(T) == 2 ? 8 : 4;
   ReducePlan p = vec > 1 ? launch_reduce<T, V, 2>(a, nullptr, nullptr, nullptr, false, M, C, partials, s)
                          : launch_reduce<T, 1, 2>(a, nullptr, nullptr, nullptr, false, M, C, partials, s);
-  hipLaunchKernelGGL((col_finalize_k<T, 2>), dim3((unsigned)cdiv(C, 256)), dim3(256), 0, s, partials, p.chunks, M, C,
+  hipLaunchKernelGGL((col_finalize_k<T, 2>), dim3((unsigned)cdiv(C, 64)), dim3(1024), 0, s, partials, p.chunks, M, C,
                      (const T*)nullptr, (const T*)nullptr, (float*)nullptr, out, (float*)nullptr, (float*)nullptr);
 }
 
