@@ -19,18 +19,18 @@ namespace cd {
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 
-constexpr int BK = 32;        // contraction elements per main-loop step
-constexpr int PITCH = BK + 8; // LDS row pitch in elements (80 bytes)
+constexpr int BK = 32;  // contraction elements per main-loop step (one 64-byte LDS row)
 
 struct IgemmArgs {
   const bf16_t* src;  // gathered tensor [B][Hs][Ws][Cs]
-  const bf16_t* wt;   // [N][K]
+  const bf16_t* wt;   // [N][K], K = kh*kw*Cs, laid out (r, s, c)
   bf16_t* dst;        // [M][N]
   int64_t M;
   int N, K;
   int Hs, Ws, Cs, Hd, Wd, kh, kw, stride, pad;
   int accumulate;
   int ntiles;
+  uint32_t src_bytes, wt_bytes;
 };
 
 // Blocks are handed to the 8 XCDs round-robin; renumber so that consecutive logical tiles (which
@@ -45,102 +45,136 @@ __device__ inline uint32_t pack_bf16x2(float a, float b) {
   return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
 }
 
-// MODE 0: fprop gather (hs = hd*stride - pad + r).  MODE 1: dgrad gather (hs = (hd + pad - r)/stride).
+// 16-byte load through a raw buffer descriptor: an offset at or beyond the buffer size returns
+// zeros, so a masked-out vector costs one select instead of a branch around the load.
+typedef int v4i32_t __attribute__((ext_vector_type(4)));
+__device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+__device__ inline uint4 buf_load16(__amdgpu_buffer_rsrc_t r, uint32_t byte_off) {
+  const v4i32_t v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, 0);
+  return make_uint4((uint32_t)v.x, (uint32_t)v.y, (uint32_t)v.z, (uint32_t)v.w);
+}
+
+// LDS tiles are [row][32 elements] = 64-byte rows without padding; the 16-byte column cv of a row
+// is stored at column cv ^ ((row >> 2) & 3), which makes both the 16-byte stores (4 lanes per row)
+// and the MFMA fragment reads (16 consecutive rows, one column) bank-conflict free.
+__device__ inline int lds_off(int row, int cv) { return row * BK + ((cv ^ ((row >> 2) & 3)) << 3); }
+
+// MODE 0: fprop gather, hs = hd*stride - pad + r.
+// MODE 1: dgrad gather for stride 1, hs = hd + pad - r.
+// MODE 2: dgrad gather for stride 2, hs = (hd + pad - r)/2 where divisible.
+//
+// Schedule of one wave per step kt (software pipelined by hand, the compiler cannot move work across
+// the barrier): write tile kt+1 to LDS (its global loads were issued two steps earlier), issue the
+// global loads of tile kt+3, issue the MFMAs of tile kt from fragments already in registers, barrier,
+// read the fragments of tile kt+1 from LDS.  The MFMAs of a step thus run while the wave waits at the
+// barrier and for its LDS reads, which is what keeps the matrix pipe busy at 1-2 waves per SIMD.
 template <int MODE, int BM, int BN, int WAVES_M, int WAVES_N>
 __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   constexpr int TM = WM / 32, TN = WN / 32;
   constexpr int AV = BM / 64;                  // activation vectors per thread per step
   constexpr int BV = BN >= 64 ? BN / 64 : 1;   // filter vectors per thread per step
-  constexpr int MAIN_BYTES = 2 * (BM + BN) * PITCH * 2;
+  constexpr int MAIN_BYTES = 2 * (BM + BN) * BK * 2;
+  constexpr int EROWS = WM < 64 ? WM : 64;     // rows staged per epilogue pass
   constexpr int EPITCH = WN + 8;
-  constexpr int EPI_BYTES = 4 * WM * EPITCH * 2;
+  constexpr int EPI_BYTES = 4 * EROWS * EPITCH * 2;
   constexpr int SMEM = MAIN_BYTES > EPI_BYTES ? MAIN_BYTES : EPI_BYTES;
+  constexpr int PF = 2;                        // steps of global loads in flight (register ring)
   __shared__ __attribute__((aligned(16))) char smem[SMEM];
-  bf16_t* As = reinterpret_cast<bf16_t*>(smem);                  // [2][BM][PITCH]
-  bf16_t* Bs = As + 2 * BM * PITCH;                              // [2][BN][PITCH]
+  bf16_t* As = reinterpret_cast<bf16_t*>(smem);  // [2][BM][BK]
+  bf16_t* Bs = As + 2 * BM * BK;                 // [2][BN][BK]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm0 = (wave % WAVES_M) * WM, wn0 = (wave / WAVES_M) * WN;
   const unsigned tile = xcd_remap(blockIdx.x, gridDim.x);
   const int64_t m0 = (int64_t)(tile / a.ntiles) * BM;
   const int n0 = (int)(tile % a.ntiles) * BN;
+  const __amdgpu_buffer_rsrc_t rsrc = make_rsrc(a.src, a.src_bytes);
+  const __amdgpu_buffer_rsrc_t rwt = make_rsrc(a.wt, a.wt_bytes);
 
-  // ---- per-thread gather state -----------------------------------------------------------------
-  const int kvec = tid & 3, lrow = tid >> 2;   // this thread's 16-byte column and first row in a tile
-  int64_t pixbase[AV];
-  int h0[AV], w0[AV];
-  bool rowok[AV];
+  // ---- per-thread gather state ---------------------------------------------------------------------
+  const int kvec = tid & 3, lrow = tid >> 2;  // this thread's 16-byte column and first row in a tile
+  int rowoff[AV];                 // element offset of (image, h0, w0, channel 0); may be negative
+  uint32_t hmask[AV], wmask[AV];  // bit r / s set: tap row r / column s reads inside the image
+  int h0[AV], w0[AV];             // MODE 2 only
 #pragma unroll
   for (int j = 0; j < AV; j++) {
     const int64_t m = m0 + lrow + 64 * j;
-    rowok[j] = m < a.M;
-    const int64_t mm = rowok[j] ? m : 0;
+    const bool rowok = m < a.M;
+    const int64_t mm = rowok ? m : 0;
     const int wd = (int)(mm % a.Wd);
     const int64_t q = mm / a.Wd;
     const int hd = (int)(q % a.Hd);
-    pixbase[j] = (q / a.Hd) * a.Hs * a.Ws;
-    if (MODE == 0) { h0[j] = hd * a.stride - a.pad; w0[j] = wd * a.stride - a.pad; }
-    else { h0[j] = hd + a.pad; w0[j] = wd + a.pad; }
+    const int b = (int)(q / a.Hd);
+    const int hh = MODE == 0 ? hd * a.stride - a.pad : hd + a.pad;
+    const int ww = MODE == 0 ? wd * a.stride - a.pad : wd + a.pad;
+    h0[j] = hh;
+    w0[j] = ww;
+    uint32_t hm = 0, wm = 0;
+    for (int r = 0; r < a.kh; r++) {
+      const int hn = MODE == 0 ? hh + r : hh - r;
+      const int hs = MODE == 2 ? hn >> 1 : hn;
+      if (hn >= 0 && hs < a.Hs && (MODE != 2 || (hn & 1) == 0)) hm |= 1u << r;
+    }
+    for (int t = 0; t < a.kw; t++) {
+      const int wn = MODE == 0 ? ww + t : ww - t;
+      const int ws = MODE == 2 ? wn >> 1 : wn;
+      if (wn >= 0 && ws < a.Ws && (MODE != 2 || (wn & 1) == 0)) wm |= 1u << t;
+    }
+    hmask[j] = rowok ? hm : 0u;
+    wmask[j] = wm;
+    rowoff[j] = MODE == 2 ? b * a.Hs * a.Ws : ((b * a.Hs + hh) * a.Ws + ww) * a.Cs;
   }
-  int kc, kr, ks;  // channel offset inside the tap, tap row, tap column of this thread's vector
-  {
-    const int k = kvec * 8;
-    const int tap = k / a.Cs;
-    kc = k - tap * a.Cs;
-    kr = tap / a.kw;
-    ks = tap - kr * a.kw;
-  }
-  const bf16_t* wrow[BV];
-  bool wok[BV];
+  uint32_t woff[BV];  // byte offset of this thread's filter row (+ its 16-byte column), ~0 if masked
 #pragma unroll
   for (int j = 0; j < BV; j++) {
     const int n = n0 + lrow + 64 * j;
-    wok[j] = (lrow + 64 * j) < BN && n < a.N;
-    wrow[j] = a.wt + (int64_t)(wok[j] ? n : 0) * a.K + kvec * 8;
+    woff[j] = ((lrow + 64 * j) < BN && n < a.N) ? (uint32_t)(n * a.K + kvec * 8) * 2u : 0xffffffffu;
   }
-  const int sshift = a.stride == 2 ? 1 : 0;
+  // position of this thread's vector in the contraction: tap (kr, ks) and channel kc
+  int kc = kvec * 8, kr = 0, ks = 0;
+  {
+    const int tap = kc / a.Cs;
+    kc -= tap * a.Cs;
+    kr = tap / a.kw;
+    ks = tap - kr * a.kw;
+  }
+  const int KT = (a.K + BK - 1) / BK;
+  const int tapdir = MODE == 0 ? 1 : -1;
 
-  uint4 ra[AV], rb[BV];
-  auto gload = [&](int kt) {
+  uint4 ra[PF][AV], rb[PF][BV];
+  // Always issues its loads (a step at or beyond the end of the contraction has every vector masked
+  // and costs no memory traffic): with conditional loads the compiler can no longer count how many
+  // are outstanding and falls back to waiting for all of them at every step.
+  auto gload = [&](uint4* ra, uint4* rb, int kt) {
     const bool kok = kr < a.kh;
+    const int koff = tapdir * (kr * a.Ws + ks) * a.Cs + kc;
 #pragma unroll
     for (int j = 0; j < AV; j++) {
-      int hs, ws;
-      bool ok = rowok[j] && kok;
-      if (MODE == 0) {
-        hs = h0[j] + kr;
-        ws = w0[j] + ks;
-      } else {
-        const int hn = h0[j] - kr, wn = w0[j] - ks;
-        ok = ok && hn >= 0 && wn >= 0 && ((hn | wn) & (a.stride - 1)) == 0;
-        hs = hn >> sshift;
-        ws = wn >> sshift;
-      }
-      ok = ok && hs >= 0 && hs < a.Hs && ws >= 0 && ws < a.Ws;
-      ra[j] = make_uint4(0, 0, 0, 0);
-      if (ok) ra[j] = *reinterpret_cast<const uint4*>(a.src + (pixbase[j] + (int64_t)hs * a.Ws + ws) * a.Cs + kc);
+      const bool ok = kok && ((hmask[j] >> kr) & (wmask[j] >> ks) & 1u);
+      int off;
+      if (MODE == 2) off = (rowoff[j] + ((h0[j] - kr) >> 1) * a.Ws + ((w0[j] - ks) >> 1)) * a.Cs + kc;
+      else off = rowoff[j] + koff;
+      ra[j] = buf_load16(rsrc, ok ? (uint32_t)off * 2u : 0xffffffffu);
     }
+    const uint32_t wk = (uint32_t)kt * (BK * 2u);
 #pragma unroll
-    for (int j = 0; j < BV; j++) {
-      rb[j] = make_uint4(0, 0, 0, 0);
-      if (wok[j] && kok) rb[j] = *reinterpret_cast<const uint4*>(wrow[j] + (int64_t)kt * BK);
-    }
-    // advance this thread's (tap, channel) position by BK
+    for (int j = 0; j < BV; j++)
+      rb[j] = buf_load16(rwt, (kok && woff[j] != 0xffffffffu) ? woff[j] + wk : 0xffffffffu);
+    // advance to the next step
     kc += BK;
-    while (kc >= a.Cs) {
-      kc -= a.Cs;
-      if (++ks == a.kw) { ks = 0; ++kr; }
-    }
+    while (kc >= a.Cs) { kc -= a.Cs; if (++ks == a.kw) { ks = 0; ++kr; } }
   };
-  auto lstore = [&](int buf) {
+  auto lstore = [&](const uint4* ra, const uint4* rb, int buf) {
 #pragma unroll
     for (int j = 0; j < AV; j++)
-      *reinterpret_cast<uint4*>(As + ((buf * BM) + lrow + 64 * j) * PITCH + kvec * 8) = ra[j];
+      *reinterpret_cast<uint4*>(As + buf * BM * BK + lds_off(lrow + 64 * j, kvec)) = ra[j];
 #pragma unroll
     for (int j = 0; j < BV; j++)
       if ((lrow + 64 * j) < BN)
-        *reinterpret_cast<uint4*>(Bs + ((buf * BN) + lrow + 64 * j) * PITCH + kvec * 8) = rb[j];
+        *reinterpret_cast<uint4*>(Bs + buf * BN * BK + lds_off(lrow + 64 * j, kvec)) = rb[j];
   };
 
   f32x16_t acc[TN][TM];
@@ -151,81 +185,111 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
 #pragma unroll
       for (int v = 0; v < 16; v++) acc[i][j][v] = 0.f;
 
-  const int KT = (a.K + BK - 1) / BK;
-  gload(0);
-  lstore(0);
-  __syncthreads();
-  const int frow = lane & 31, fk = (lane >> 5) * 8;
-  for (int kt = 0; kt < KT; kt++) {
-    const int cur = kt & 1;
-    if (kt + 1 < KT) gload(kt + 1);
+  const int frow = lane & 31, fcv = lane >> 5;
+  bf16x8_t wf[2][2][TN], xf[2][2][TM];  // [fragment set][k16 half][tile]
+  auto read_frags = [&](bf16x8_t (&wf)[2][TN], bf16x8_t (&xf)[2][TM], int buf) {
 #pragma unroll
-    for (int kk = 0; kk < BK; kk += 16) {
-      bf16x8_t wf[TN], xf[TM];
+    for (int kk = 0; kk < 2; kk++) {
 #pragma unroll
       for (int i = 0; i < TN; i++)
-        wf[i] = *reinterpret_cast<const bf16x8_t*>(Bs + ((cur * BN) + wn0 + i * 32 + frow) * PITCH + kk + fk);
+        wf[kk][i] = *reinterpret_cast<const bf16x8_t*>(Bs + buf * BN * BK + lds_off(wn0 + i * 32 + frow, kk * 2 + fcv));
 #pragma unroll
       for (int j = 0; j < TM; j++)
-        xf[j] = *reinterpret_cast<const bf16x8_t*>(As + ((cur * BM) + wm0 + j * 32 + frow) * PITCH + kk + fk);
+        xf[kk][j] = *reinterpret_cast<const bf16x8_t*>(As + buf * BM * BK + lds_off(wm0 + j * 32 + frow, kk * 2 + fcv));
+    }
+  };
+  static_assert(PF == 2, "the register ring and the fragment sets alternate with the parity of the step");
+  auto mfma_step = [&](const bf16x8_t (&wf)[2][TN], const bf16x8_t (&xf)[2][TM]) {
+#pragma unroll
+    for (int kk = 0; kk < 2; kk++)
 #pragma unroll
       for (int i = 0; i < TN; i++)
 #pragma unroll
         for (int j = 0; j < TM; j++)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], xf[j], acc[i][j], 0, 0, 0);
-    }
-    if (kt + 1 < KT) lstore(cur ^ 1);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk][i], xf[kk][j], acc[i][j], 0, 0, 0);
+  };
+  gload(ra[0], rb[0], 0);
+  gload(ra[1], rb[1], 1);
+  lstore(ra[0], rb[0], 0);
+  gload(ra[0], rb[0], 2);
+  __syncthreads();
+  read_frags(wf[0], xf[0], 0);
+  // two steps per trip, no branches inside: an odd step count is rounded up with an all-zero tile
+  for (int kt = 0; kt < KT; kt += 2) {
+    lstore(ra[1], rb[1], 1);
+    gload(ra[1], rb[1], kt + 3);
+    mfma_step(wf[0], xf[0]);
+    __syncthreads();  // tile kt+1 is in LDS; nobody reads the buffer that the next store overwrites
+    read_frags(wf[1], xf[1], 1);
+    lstore(ra[0], rb[0], 0);
+    gload(ra[0], rb[0], kt + 4);
+    mfma_step(wf[1], xf[1]);
     __syncthreads();
+    read_frags(wf[0], xf[0], 0);
   }
 
   // ---- epilogue: fp32 -> bf16, transpose through LDS, 16-byte stores along the channels -------------
   // accumulator layout: lane holds pixel column (lane % 32); register v holds channel
   // 8*(v/4) + 4*(lane/32) + v%4 of the 32x32 tile
-  bf16_t* stage = reinterpret_cast<bf16_t*>(smem) + wave * WM * EPITCH;
-#pragma unroll
-  for (int i = 0; i < TN; i++)
-#pragma unroll
-    for (int j = 0; j < TM; j++)
-#pragma unroll
-      for (int g = 0; g < 4; g++) {
-        uint2 p;
-        p.x = pack_bf16x2(acc[i][j][4 * g + 0], acc[i][j][4 * g + 1]);
-        p.y = pack_bf16x2(acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
-        *reinterpret_cast<uint2*>(stage + (j * 32 + frow) * EPITCH + i * 32 + 8 * g + 4 * (lane >> 5)) = p;
-      }
-  __syncthreads();
+  bf16_t* stage = reinterpret_cast<bf16_t*>(smem) + wave * EROWS * EPITCH;
   constexpr int LPR = WN / 8;        // lanes per output row
   constexpr int RPP = 64 / LPR;      // rows per pass
+  constexpr int TPG = EROWS / 32;    // 32-row tiles per staging pass
   const int er = lane / LPR, ec = (lane % LPR) * 8;
 #pragma unroll
-  for (int p = 0; p < WM / RPP; p++) {
-    const int row = p * RPP + er;
-    const int64_t m = m0 + wm0 + row;
-    const int n = n0 + wn0 + ec;
-    if (m < a.M && n < a.N) {
-      uint4 v = *reinterpret_cast<const uint4*>(stage + row * EPITCH + ec);
-      bf16_t* dp = a.dst + m * a.N + n;
-      if (a.accumulate) {
-        const uint4 o = *reinterpret_cast<const uint4*>(dp);
-        const uint32_t vv[4] = {v.x, v.y, v.z, v.w}, oo[4] = {o.x, o.y, o.z, o.w};
-        uint32_t r[4];
+  for (int g0 = 0; g0 < TM; g0 += TPG) {
+    __syncthreads();  // tiles (first pass) or the previous pass's staging rows are no longer read
 #pragma unroll
-        for (int q = 0; q < 4; q++)
-          r[q] = pack_bf16x2(__uint_as_float(vv[q] << 16) + __uint_as_float(oo[q] << 16),
-                             __uint_as_float(vv[q] & 0xffff0000u) + __uint_as_float(oo[q] & 0xffff0000u));
-        v = make_uint4(r[0], r[1], r[2], r[3]);
+    for (int i = 0; i < TN; i++)
+#pragma unroll
+      for (int j = 0; j < TPG; j++)
+#pragma unroll
+        for (int g = 0; g < 4; g++) {
+          uint2 p;
+          p.x = pack_bf16x2(acc[i][g0 + j][4 * g + 0], acc[i][g0 + j][4 * g + 1]);
+          p.y = pack_bf16x2(acc[i][g0 + j][4 * g + 2], acc[i][g0 + j][4 * g + 3]);
+          *reinterpret_cast<uint2*>(stage + (j * 32 + frow) * EPITCH + i * 32 + 8 * g + 4 * (lane >> 5)) = p;
+        }
+    __syncthreads();
+#pragma unroll
+    for (int p = 0; p < EROWS / RPP; p++) {
+      const int row = p * RPP + er;
+      const int64_t m = m0 + wm0 + g0 * 32 + row;
+      const int n = n0 + wn0 + ec;
+      if (m < a.M && n < a.N) {
+        uint4 v = *reinterpret_cast<const uint4*>(stage + row * EPITCH + ec);
+        bf16_t* dp = a.dst + m * a.N + n;
+        if (a.accumulate) {
+          const uint4 o = *reinterpret_cast<const uint4*>(dp);
+          const uint32_t vv[4] = {v.x, v.y, v.z, v.w}, oo[4] = {o.x, o.y, o.z, o.w};
+          uint32_t r[4];
+#pragma unroll
+          for (int q = 0; q < 4; q++)
+            r[q] = pack_bf16x2(__uint_as_float(vv[q] << 16) + __uint_as_float(oo[q] << 16),
+                               __uint_as_float(vv[q] & 0xffff0000u) + __uint_as_float(oo[q] & 0xffff0000u));
+          v = make_uint4(r[0], r[1], r[2], r[3]);
+        }
+        *reinterpret_cast<uint4*>(dp) = v;
       }
-      *reinterpret_cast<uint4*>(dp) = v;
     }
   }
 }
+
+// Tile selection override for tuning runs (0 = automatic, 1: 128x128, 2: 256x128).
+int g_tune_tile = 0;
+int g_tune_co = -1;  // unused
 
 template <int MODE>
 static void launch_igemm(IgemmArgs a, hipStream_t s) {
   if (a.N > 64) {
     a.ntiles = (int)cdiv(a.N, 128);
-    const int64_t blocks = cdiv(a.M, 128) * a.ntiles;
-    hipLaunchKernelGGL((igemm_kernel<MODE, 128, 128, 2, 2>), dim3((unsigned)blocks), dim3(256), 0, s, a);
+    if (g_tune_tile == 2) {
+      hipLaunchKernelGGL((igemm_kernel<MODE, 256, 128, 2, 2>), dim3((unsigned)(cdiv(a.M, 256) * a.ntiles)), dim3(256), 0,
+                         s, a);
+    } else {
+      const int64_t blocks = cdiv(a.M, 128) * a.ntiles;
+      hipLaunchKernelGGL((igemm_kernel<MODE, 128, 128, 2, 2>), dim3((unsigned)blocks), dim3(256), 0, s, a);
+    }
   } else if (a.N > 32) {
     a.ntiles = 1;
     hipLaunchKernelGGL((igemm_kernel<MODE, 256, 64, 4, 1>), dim3((unsigned)cdiv(a.M, 256)), dim3(256), 0, s, a);
@@ -236,8 +300,11 @@ static void launch_igemm(IgemmArgs a, hipStream_t s) {
 }
 
 bool conv_mfma_supported(const ConvGeom& g) {
-  return g.Cin % 8 == 0 && g.Cout % 8 == 0 && (g.stride == 1 || g.stride == 2) && g.kh == g.kw &&
-         g.B * g.H * g.W * (int64_t)g.Cin < (1LL << 40);
+  // 32-bit byte offsets into every operand, tap masks of at most 32 bits
+  const int64_t lim = 1LL << 31;
+  return g.Cin % 8 == 0 && g.Cout % 8 == 0 && (g.stride == 1 || g.stride == 2) && g.kh == g.kw && g.kh <= 7 &&
+         g.B * g.H * g.W * (int64_t)g.Cin * 2 < lim && g.M() * (int64_t)g.Cout * 2 < lim &&
+         (int64_t)g.Cout * g.K() * 2 < lim;
 }
 
 void conv_fprop_mfma(const bf16_t* x, const bf16_t* w, bf16_t* y, const ConvGeom& g, hipStream_t s) {
@@ -247,6 +314,8 @@ void conv_fprop_mfma(const bf16_t* x, const bf16_t* w, bf16_t* y, const ConvGeom
   a.Hs = g.H; a.Ws = g.W; a.Cs = g.Cin; a.Hd = g.Ho; a.Wd = g.Wo;
   a.kh = g.kh; a.kw = g.kw; a.stride = g.stride; a.pad = g.pad;
   a.accumulate = 0; a.ntiles = 1;
+  a.src_bytes = (uint32_t)(g.B * g.H * g.W * (int64_t)g.Cin * 2);
+  a.wt_bytes = (uint32_t)((int64_t)g.Cout * g.K() * 2);
   launch_igemm<0>(a, s);
 }
 
@@ -258,7 +327,10 @@ void conv_dgrad_mfma(const bf16_t* dy, const bf16_t* wt, bf16_t* dx, const ConvG
   a.Hs = g.Ho; a.Ws = g.Wo; a.Cs = g.Cout; a.Hd = g.H; a.Wd = g.W;
   a.kh = g.kh; a.kw = g.kw; a.stride = g.stride; a.pad = g.pad;
   a.accumulate = accumulate ? 1 : 0; a.ntiles = 1;
-  launch_igemm<1>(a, s);
+  a.src_bytes = (uint32_t)(g.M() * (int64_t)g.Cout * 2);
+  a.wt_bytes = (uint32_t)((int64_t)g.Cout * g.K() * 2);
+  if (g.stride == 1) launch_igemm<1>(a, s);
+  else launch_igemm<2>(a, s);
 }
 
 // ---- wgrad ------------------------------------------------------------------------------------------
@@ -281,6 +353,7 @@ struct WgradArgs {
   int N, K;
   int H, W, Cin, Ho, Wo, kh, kw, stride, pad;
   int ktiles;
+  uint32_t x_bytes, dy_bytes;
 };
 
 constexpr int WG_MS = 32;  // pixels per main-loop step
@@ -301,6 +374,8 @@ __global__ void __launch_bounds__(256) wgrad_kernel(WgradArgs a) {
   const int n0 = (blockIdx.x / a.ktiles) * BN, k0 = (blockIdx.x % a.ktiles) * BKK;
   const int64_t mbeg = (int64_t)blockIdx.y * a.m_per_split;
   const int64_t mend = mbeg + a.m_per_split < a.M ? mbeg + a.m_per_split : a.M;
+  const __amdgpu_buffer_rsrc_t rx_src = make_rsrc(a.x, a.x_bytes);
+  const __amdgpu_buffer_rsrc_t rdy = make_rsrc(a.dy, a.dy_bytes);
 
   // dy loader: fixed channel vector, DV rows
   const int dnv = tid % NVR, drow = tid / NVR;
@@ -321,21 +396,22 @@ __global__ void __launch_bounds__(256) wgrad_kernel(WgradArgs a) {
     pb[j] = (int)(q / a.Ho);
   }
 
-  uint4 rd[DV], rx[XV];
-  auto gload = [&](int64_t ms) {
+  // Loads are unconditional (masked vectors read nothing) so that the compiler can count the loads in
+  // flight; see igemm_kernel.
+  uint4 rd[2][DV], rx[2][XV];
+  auto gload = [&](uint4* rd, uint4* rx, int64_t st) {
+    const int64_t ms = mbeg + st * WG_MS;
 #pragma unroll
     for (int j = 0; j < DV; j++) {
       const int64_t m = ms + drow + DROWS * j;
-      rd[j] = make_uint4(0, 0, 0, 0);
-      if (dnok && m < mend) rd[j] = *reinterpret_cast<const uint4*>(a.dy + m * a.N + n0 + dnv * 8);
+      rd[j] = buf_load16(rdy, (dnok && m < mend) ? (uint32_t)(m * a.N + n0 + dnv * 8) * 2u : 0xffffffffu);
     }
 #pragma unroll
     for (int j = 0; j < XV; j++) {
       const int64_t m = ms + xrow + XROWS * j;
       const int hi = ph[j] * a.stride - a.pad + kr, wi = pw[j] * a.stride - a.pad + ks;
-      rx[j] = make_uint4(0, 0, 0, 0);
-      if (kok && m < mend && hi >= 0 && hi < a.H && wi >= 0 && wi < a.W)
-        rx[j] = *reinterpret_cast<const uint4*>(a.x + (((int64_t)pb[j] * a.H + hi) * a.W + wi) * a.Cin + kc);
+      const bool ok = kok && m < mend && hi >= 0 && hi < a.H && wi >= 0 && wi < a.W;
+      rx[j] = buf_load16(rx_src, ok ? (uint32_t)(((pb[j] * a.H + hi) * a.W + wi) * a.Cin + kc) * 2u : 0xffffffffu);
       // next step: WG_MS pixels further
       pw[j] += WG_MS;
       while (pw[j] >= a.Wo) {
@@ -344,7 +420,7 @@ __global__ void __launch_bounds__(256) wgrad_kernel(WgradArgs a) {
       }
     }
   };
-  auto lstore = [&](int buf) {
+  auto lstore = [&](const uint4* rd, const uint4* rx, int buf) {
 #pragma unroll
     for (int j = 0; j < DV; j++) *reinterpret_cast<uint4*>(&Dy[buf][drow + DROWS * j][dnv * 8]) = rd[j];
 #pragma unroll
@@ -364,42 +440,58 @@ __global__ void __launch_bounds__(256) wgrad_kernel(WgradArgs a) {
   const int tr_m = 8 * (grp >> 1) + (li >> 2);      // pixel row (second load: +4)
   const int tr_c = 16 * (grp & 1) + 4 * (li & 3);   // first of the 4 channels this lane points at
 
-  const int64_t steps = (mend - mbeg + WG_MS - 1) / WG_MS;
-  if (steps > 0) {
-    gload(mbeg);
-    lstore(0);
-  }
-  __syncthreads();
-  for (int64_t st = 0; st < steps; st++) {
-    const int cur = (int)(st & 1);
-    if (st + 1 < steps) gload(mbeg + (st + 1) * WG_MS);
+  bf16x8_t df[2][2][TN], xf[2][2][TK];  // [fragment set][16-pixel half][tile]
+  auto read_frags = [&](bf16x8_t (&df)[2][TN], bf16x8_t (&xf)[2][TK], int buf) {
 #pragma unroll
-    for (int ms = 0; ms < WG_MS; ms += 16) {
-      bf16x8_t df[TN], xf[TK];
+    for (int h = 0; h < 2; h++) {
 #pragma unroll
       for (int i = 0; i < TN; i++) {
         const bf16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-            (CD_LDS bf16x4_t*)(&Dy[cur][ms + tr_m][wn0 + i * 32 + tr_c]));
+            (CD_LDS bf16x4_t*)(&Dy[buf][h * 16 + tr_m][wn0 + i * 32 + tr_c]));
         const bf16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-            (CD_LDS bf16x4_t*)(&Dy[cur][ms + tr_m + 4][wn0 + i * 32 + tr_c]));
-        df[i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            (CD_LDS bf16x4_t*)(&Dy[buf][h * 16 + tr_m + 4][wn0 + i * 32 + tr_c]));
+        df[h][i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
       }
 #pragma unroll
       for (int j = 0; j < TK; j++) {
         const bf16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-            (CD_LDS bf16x4_t*)(&Xs[cur][ms + tr_m][wk0 + j * 32 + tr_c]));
+            (CD_LDS bf16x4_t*)(&Xs[buf][h * 16 + tr_m][wk0 + j * 32 + tr_c]));
         const bf16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-            (CD_LDS bf16x4_t*)(&Xs[cur][ms + tr_m + 4][wk0 + j * 32 + tr_c]));
-        xf[j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            (CD_LDS bf16x4_t*)(&Xs[buf][h * 16 + tr_m + 4][wk0 + j * 32 + tr_c]));
+        xf[h][j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
       }
+    }
+  };
+  auto mfma_step = [&](const bf16x8_t (&df)[2][TN], const bf16x8_t (&xf)[2][TK]) {
+#pragma unroll
+    for (int h = 0; h < 2; h++)
 #pragma unroll
       for (int i = 0; i < TN; i++)
 #pragma unroll
         for (int j = 0; j < TK; j++)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(df[i], xf[j], acc[i][j], 0, 0, 0);
-    }
-    if (st + 1 < steps) lstore(cur ^ 1);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(df[h][i], xf[h][j], acc[i][j], 0, 0, 0);
+  };
+
+  // same software pipeline as igemm_kernel: store tile st+1, load tile st+3, MFMAs of tile st, barrier,
+  // fragments of tile st+1
+  const int64_t steps = (mend - mbeg + WG_MS - 1) / WG_MS;
+  gload(rd[0], rx[0], 0);
+  gload(rd[1], rx[1], 1);
+  lstore(rd[0], rx[0], 0);
+  gload(rd[0], rx[0], 2);
+  __syncthreads();
+  read_frags(df[0], xf[0], 0);
+  for (int64_t st = 0; st < steps; st += 2) {
+    lstore(rd[1], rx[1], 1);
+    gload(rd[1], rx[1], st + 3);
+    mfma_step(df[0], xf[0]);
     __syncthreads();
+    read_frags(df[1], xf[1], 1);
+    lstore(rd[0], rx[0], 0);
+    gload(rd[0], rx[0], st + 4);
+    mfma_step(df[1], xf[1]);
+    __syncthreads();
+    read_frags(df[0], xf[0], 0);
   }
 
   float* out = a.out + (int64_t)blockIdx.y * a.N * a.K;
@@ -439,6 +531,8 @@ void conv_wgrad_mfma(const bf16_t* x, const bf16_t* dy, float* dw, const ConvGeo
   a.M = g.M(); a.N = g.Cout; a.K = g.K();
   a.H = g.H; a.W = g.W; a.Cin = g.Cin; a.Ho = g.Ho; a.Wo = g.Wo;
   a.kh = g.kh; a.kw = g.kw; a.stride = g.stride; a.pad = g.pad;
+  a.x_bytes = (uint32_t)(g.B * g.H * g.W * (int64_t)g.Cin * 2);
+  a.dy_bytes = (uint32_t)(g.M() * (int64_t)g.Cout * 2);
   const int bn = a.N > 64 ? 128 : 64, bk = a.K > 64 ? 128 : 64;
   const int ntiles = (int)cdiv(a.N, bn);
   a.ktiles = (int)cdiv(a.K, bk);
