@@ -31,6 +31,7 @@ struct IgemmArgs {
   int accumulate;
   int ntiles;
   uint32_t src_bytes, wt_bytes;
+  const bf16_t* bias;  // F32OUT kernels: per-column bias added to the fp32 output (nullable)
 };
 
 // Blocks are handed to the 8 XCDs round-robin; renumber so that consecutive logical tiles (which
@@ -70,7 +71,8 @@ __device__ inline int lds_off(int row, int cv) { return row * BK + ((cv ^ ((row 
 // global loads of tile kt+3, issue the MFMAs of tile kt from fragments already in registers, barrier,
 // read the fragments of tile kt+1 from LDS.  The MFMAs of a step thus run while the wave waits at the
 // barrier and for its LDS reads, which is what keeps the matrix pipe busy at 1-2 waves per SIMD.
-template <int MODE, int BM, int BN, int WAVES_M, int WAVES_N>
+// F32OUT: the output is fp32 [M][N] (+ bias), written straight from the accumulators (dense layers).
+template <int MODE, int BM, int BN, int WAVES_M, int WAVES_N, bool F32OUT = false>
 __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   constexpr int TM = WM / 32, TN = WN / 32;
@@ -228,9 +230,24 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
     read_frags(wf[0], xf[0], 0);
   }
 
-  // ---- epilogue: fp32 -> bf16, transpose through LDS, 16-byte stores along the channels -------------
   // accumulator layout: lane holds pixel column (lane % 32); register v holds channel
   // 8*(v/4) + 4*(lane/32) + v%4 of the 32x32 tile
+  if (F32OUT) {
+    float* dst = reinterpret_cast<float*>(a.dst);
+#pragma unroll
+    for (int i = 0; i < TN; i++)
+#pragma unroll
+      for (int j = 0; j < TM; j++) {
+        const int64_t m = m0 + wm0 + j * 32 + frow;
+#pragma unroll
+        for (int v = 0; v < 16; v++) {
+          const int n = n0 + wn0 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+          if (m < a.M && n < a.N) dst[m * a.N + n] = acc[i][j][v] + (a.bias ? bf16_to_f32(a.bias[n]) : 0.f);
+        }
+      }
+    return;
+  }
+  // ---- epilogue: fp32 -> bf16, transpose through LDS, 16-byte stores along the channels -------------
   bf16_t* stage = reinterpret_cast<bf16_t*>(smem) + wave * EROWS * EPITCH;
   constexpr int LPR = WN / 8;        // lanes per output row
   constexpr int RPP = 64 / LPR;      // rows per pass
@@ -307,8 +324,23 @@ bool conv_mfma_supported(const ConvGeom& g) {
          (int64_t)g.Cout * g.K() * 2 < lim;
 }
 
+void linear_fwd_mfma(const bf16_t* x, const bf16_t* w, const bf16_t* bias, float* y, int64_t B, int F, int C,
+                     hipStream_t s) {
+  IgemmArgs a;
+  a.src = x; a.wt = w; a.dst = reinterpret_cast<bf16_t*>(y); a.bias = bias;
+  a.M = B; a.N = C; a.K = F;
+  a.Hs = 1; a.Ws = 1; a.Cs = F; a.Hd = 1; a.Wd = 1; a.kh = 1; a.kw = 1; a.stride = 1; a.pad = 0;
+  a.accumulate = 0;
+  a.src_bytes = (uint32_t)(B * (int64_t)F * 2);
+  a.wt_bytes = (uint32_t)((int64_t)C * F * 2);
+  a.ntiles = (int)cdiv(C, 128);
+  hipLaunchKernelGGL((igemm_kernel<0, 128, 128, 2, 2, true>), dim3((unsigned)(cdiv(B, 128) * a.ntiles)), dim3(256), 0, s,
+                     a);
+}
+
 void conv_fprop_mfma(const bf16_t* x, const bf16_t* w, bf16_t* y, const ConvGeom& g, hipStream_t s) {
   IgemmArgs a;
+  a.bias = nullptr;
   a.src = x; a.wt = w; a.dst = y;
   a.M = g.M(); a.N = g.Cout; a.K = g.K();
   a.Hs = g.H; a.Ws = g.W; a.Cs = g.Cin; a.Hd = g.Ho; a.Wd = g.Wo;
@@ -322,6 +354,7 @@ void conv_fprop_mfma(const bf16_t* x, const bf16_t* w, bf16_t* y, const ConvGeom
 void conv_dgrad_mfma(const bf16_t* dy, const bf16_t* wt, bf16_t* dx, const ConvGeom& g, bool accumulate,
                      hipStream_t s) {
   IgemmArgs a;
+  a.bias = nullptr;
   a.src = dy; a.wt = wt; a.dst = dx;
   a.M = g.B * g.H * g.W; a.N = g.Cin; a.K = g.kh * g.kw * g.Cout;
   a.Hs = g.Ho; a.Ws = g.Wo; a.Cs = g.Cout; a.Hd = g.H; a.Wd = g.W;
@@ -555,6 +588,14 @@ void conv_wgrad_mfma(const bf16_t* x, const bf16_t* dy, float* dw, const ConvGeo
   if (splits > 1)
     hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)cdiv(nk, 64)), dim3(256), 0, s, partials, dw, nk,
                        (int)splits);
+}
+
+__global__ void __launch_bounds__(256) cast_f32_bf16_k(const float* __restrict__ in, bf16_t* __restrict__ out, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) out[i] = f32_to_bf16(in[i]);
+}
+void cast_f32_bf16(const float* in, bf16_t* out, int64_t n, hipStream_t s) {
+  hipLaunchKernelGGL(cast_f32_bf16_k, dim3((unsigned)cdiv(n, 256)), dim3(256), 0, s, in, out, n);
 }
 
 // ---- layout helpers ---------------------------------------------------------------------------------

@@ -35,10 +35,12 @@ void bn_backward(int dtype, const void* dy, const void* y, const void* x, const 
                  bool relu, void* dx, bool acc_dx, void* dres, bool acc_dres, float* dgamma, float* dbeta,
                  float* coef, float* partials, int64_t M, int C, hipStream_t s);
 
-void maxpool_fwd(int dtype, const void* x, void* y, int64_t B, int H, int W, int C, int k, int stride, int pad,
-                 hipStream_t s);
-void maxpool_bwd(int dtype, const void* x, const void* dy, void* dx, bool accumulate, int64_t B, int H, int W, int C,
-                 int k, int stride, int pad, hipStream_t s);
+// argmax: optional [B][Ho][Wo][C] bytes, the window tap (r*k+s) of the first maximum; written by the
+// forward pass and, when given, used by the backward pass instead of rescanning the windows
+void maxpool_fwd(int dtype, const void* x, void* y, uint8_t* argmax, int64_t B, int H, int W, int C, int k, int stride,
+                 int pad, hipStream_t s);
+void maxpool_bwd(int dtype, const void* x, const void* dy, const uint8_t* argmax, void* dx, bool accumulate, int64_t B,
+                 int H, int W, int C, int k, int stride, int pad, hipStream_t s);
 void gap_fwd(int dtype, const void* x, void* y, int64_t B, int HW, int C, hipStream_t s);
 void gap_bwd(int dtype, const void* dy, void* dx, bool accumulate, int64_t B, int HW, int C, hipStream_t s);
 void linear_fwd(int dtype, const void* x, const void* w, const void* b, float* y, int64_t B, int F, int C,
@@ -64,6 +66,10 @@ void conv_dgrad_mfma(const bf16_t* dy, const bf16_t* wt, bf16_t* dx, const ConvG
 // dw[Cout][K] = dy[M][Cout]^T * im2col(x)[M][K], split over M with fp32 partials reduced in fixed order
 void conv_wgrad_mfma(const bf16_t* x, const bf16_t* dy, float* dw, const ConvGeom& g, float* partials,
                      size_t partials_bytes, hipStream_t s);
+// dense layer on the same kernel: y[B][C] (fp32) = x[B][F] * w[C][F]^T + bias; needs F % 8 == 0
+void linear_fwd_mfma(const bf16_t* x, const bf16_t* w, const bf16_t* bias, float* y, int64_t B, int F, int C,
+                     hipStream_t s);
+void cast_f32_bf16(const float* in, bf16_t* out, int64_t n, hipStream_t s);
 // [n][3] -> [n][8] zero padded (input images and the taps of a 3-channel filter)
 void pad_c3_to_c8(const bf16_t* in, bf16_t* out, int64_t n, hipStream_t s);
 // fp32 [n][8] -> [n][3]

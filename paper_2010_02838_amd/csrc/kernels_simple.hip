@@ -152,8 +152,9 @@ template <> struct PoolVec<bf16_t, 8> {
 };
 
 template <typename T, int V>
-__global__ void __launch_bounds__(256) maxpool_fwd_k(const T* __restrict__ x, T* __restrict__ y, int64_t B, int H,
-                                                     int W, int C, int Ho, int Wo, int k, int stride, int pad) {
+__global__ void __launch_bounds__(256) maxpool_fwd_k(const T* __restrict__ x, T* __restrict__ y,
+                                                     uint8_t* __restrict__ argmax, int64_t B, int H, int W, int C,
+                                                     int Ho, int Wo, int k, int stride, int pad) {
   const int CV = C / V;
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (idx >= B * Ho * Wo * CV) return;
@@ -163,8 +164,9 @@ __global__ void __launch_bounds__(256) maxpool_fwd_k(const T* __restrict__ x, T*
   const int ho = p % Ho;
   const int64_t b = p / Ho;
   float best[V];
+  uint8_t arg[V];
 #pragma unroll
-  for (int i = 0; i < V; i++) best[i] = -INFINITY;
+  for (int i = 0; i < V; i++) { best[i] = -INFINITY; arg[i] = 0; }
   for (int r = 0; r < k; r++) {
     const int hi = ho * stride - pad + r;
     if (hi < 0 || hi >= H) continue;
@@ -174,10 +176,58 @@ __global__ void __launch_bounds__(256) maxpool_fwd_k(const T* __restrict__ x, T*
       float v[V];
       PoolVec<T, V>::ld(x + ((b * H + hi) * W + wi) * C + c, v);
 #pragma unroll
-      for (int i = 0; i < V; i++) best[i] = fmaxf(best[i], v[i]);
+      for (int i = 0; i < V; i++)
+        if (v[i] > best[i]) { best[i] = v[i]; arg[i] = (uint8_t)(r * k + s); }  // strict: the first maximum wins
     }
   }
-  PoolVec<T, V>::st(y + ((b * Ho + ho) * Wo + wo) * C + c, best);
+  const int64_t o = ((b * Ho + ho) * Wo + wo) * C + c;
+  PoolVec<T, V>::st(y + o, best);
+  if (argmax) {
+#pragma unroll
+    for (int i = 0; i < V; i++) argmax[o + i] = arg[i];
+  }
+}
+
+// backward from the stored argmax: 8 channels per thread, at most ceil(k/stride)^2 windows per pixel
+__global__ void __launch_bounds__(256) maxpool_bwd_idx_k(const bf16_t* __restrict__ dy, const uint8_t* __restrict__ argmax,
+                                                         bf16_t* __restrict__ dx, int accumulate, int64_t B, int H,
+                                                         int W, int C, int Ho, int Wo, int k, int stride, int pad) {
+  const int CV = C / 8;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= B * H * W * CV) return;
+  const int c = (int)(idx % CV) * 8;
+  int64_t p = idx / CV;
+  const int wi = p % W; p /= W;
+  const int hi = p % H;
+  const int64_t b = p / H;
+  float acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; i++) acc[i] = 0.f;
+  int ho0 = hi + pad - k + 1; ho0 = ho0 <= 0 ? 0 : (ho0 + stride - 1) / stride;
+  int wo0 = wi + pad - k + 1; wo0 = wo0 <= 0 ? 0 : (wo0 + stride - 1) / stride;
+  int ho1 = (hi + pad) / stride; if (ho1 > Ho - 1) ho1 = Ho - 1;
+  int wo1 = (wi + pad) / stride; if (wo1 > Wo - 1) wo1 = Wo - 1;
+  for (int ho = ho0; ho <= ho1; ho++)
+    for (int wo = wo0; wo <= wo1; wo++) {
+      const uint32_t tap = (uint32_t)((hi - (ho * stride - pad)) * k + (wi - (wo * stride - pad)));
+      const int64_t o = ((b * Ho + ho) * Wo + wo) * C + c;
+      const uint2 a = *reinterpret_cast<const uint2*>(argmax + o);
+      float g[8];
+      PoolVec<bf16_t, 8>::ld(dy + o, g);
+#pragma unroll
+      for (int i = 0; i < 8; i++) {
+        const uint32_t ai = ((i < 4 ? a.x : a.y) >> (8 * (i & 3))) & 0xffu;
+        acc[i] += ai == tap ? g[i] : 0.f;
+      }
+    }
+  bf16_t* dp = dx + ((b * H + hi) * W + wi) * C + c;
+  if (accumulate) {
+    float o[8];
+    PoolVec<bf16_t, 8>::ld(dp, o);
+#pragma unroll
+    for (int i = 0; i < 8; i++) acc[i] += o[i];
+  }
+  PoolVec<bf16_t, 8>::st(dp, acc);
 }
 
 // Gradient goes to the first maximum of each window in row-major tap order (recomputed here).
@@ -239,20 +289,23 @@ __global__ void __launch_bounds__(256) maxpool_bwd_k(const T* __restrict__ x, co
   PoolVec<T, V>::st(dp, acc);
 }
 
-void maxpool_fwd(int dtype, const void* x, void* y, int64_t B, int H, int W, int C, int k, int stride, int pad,
-                 hipStream_t s) {
+void maxpool_fwd(int dtype, const void* x, void* y, uint8_t* argmax, int64_t B, int H, int W, int C, int k, int stride,
+                 int pad, hipStream_t s) {
   const int Ho = (H + 2 * pad - k) / stride + 1, Wo = (W + 2 * pad - k) / stride + 1;
   if (dtype == CD_BF16 && C % 8 == 0 && aligned16(x) && aligned16(y))
     hipLaunchKernelGGL((maxpool_fwd_k<bf16_t, 8>), grid1d(B * Ho * Wo * (C / 8)), dim3(256), 0, s, (const bf16_t*)x,
-                       (bf16_t*)y, B, H, W, C, Ho, Wo, k, stride, pad);
+                       (bf16_t*)y, argmax, B, H, W, C, Ho, Wo, k, stride, pad);
   else
     CD_DISPATCH_T(dtype, hipLaunchKernelGGL((maxpool_fwd_k<T, 1>), grid1d(B * Ho * Wo * C), dim3(256), 0, s,
-                                            (const T*)x, (T*)y, B, H, W, C, Ho, Wo, k, stride, pad));
+                                            (const T*)x, (T*)y, argmax, B, H, W, C, Ho, Wo, k, stride, pad));
 }
-void maxpool_bwd(int dtype, const void* x, const void* dy, void* dx, bool accumulate, int64_t B, int H, int W, int C,
-                 int k, int stride, int pad, hipStream_t s) {
+void maxpool_bwd(int dtype, const void* x, const void* dy, const uint8_t* argmax, void* dx, bool accumulate, int64_t B,
+                 int H, int W, int C, int k, int stride, int pad, hipStream_t s) {
   const int Ho = (H + 2 * pad - k) / stride + 1, Wo = (W + 2 * pad - k) / stride + 1;
-  if (dtype == CD_BF16 && C % 8 == 0 && aligned16(x) && aligned16(dy) && aligned16(dx))
+  if (argmax && dtype == CD_BF16 && C % 8 == 0 && aligned16(dy) && aligned16(dx) && aligned16(argmax))
+    hipLaunchKernelGGL(maxpool_bwd_idx_k, grid1d(B * H * W * (C / 8)), dim3(256), 0, s, (const bf16_t*)dy, argmax,
+                       (bf16_t*)dx, (int)accumulate, B, H, W, C, Ho, Wo, k, stride, pad);
+  else if (dtype == CD_BF16 && C % 8 == 0 && aligned16(x) && aligned16(dy) && aligned16(dx))
     hipLaunchKernelGGL((maxpool_bwd_k<bf16_t, 8>), grid1d(B * H * W * (C / 8)), dim3(256), 0, s, (const bf16_t*)x,
                        (const bf16_t*)dy, (bf16_t*)dx, (int)accumulate, B, H, W, C, Ho, Wo, k, stride, pad);
   else

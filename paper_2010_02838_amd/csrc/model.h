@@ -38,6 +38,7 @@ struct Plan {
   bool save = false;
   std::vector<size_t> act;    // byte offset of every tensor's activation (tensor 0 unused)
   std::vector<size_t> grad;   // byte offset of every tensor's gradient (save only)
+  std::vector<size_t> aux;    // per op: max-pool argmax bytes (save only), 0 = none
   size_t bn_stats = 0;        // per BN slot: mean[C], invstd[C], scale[C], shift[C] fp32
   size_t bn_coef = 0;         // backward coefficients c1,c2,c3 [3][Cmax] fp32
   size_t partials = 0;        // reduction partials / split-K partials
@@ -45,6 +46,7 @@ struct Plan {
   size_t xpack = 0;           // bf16 models: input packed to 8 channels
   size_t wpack = 0;           // bf16 models: re-laid-out weights (stem padding, dgrad transposes)
   size_t wpack_bytes = 0;
+  size_t lin_dz = 0;          // bf16 models: bf16 copy of d loss / d logits for the dense-layer MFMA backward
   size_t total = 0;
 };
 

@@ -210,17 +210,24 @@ Plan make_plan(const cd_model* m, int64_t B, bool save) {
   if (m->dtype == CD_BF16) {
     p.xpack = alloc((size_t)B * m->arch.in_h * m->arch.in_w * 8 * 2);
     size_t wmax = 0;
-    for (const ParamDesc& q : m->params)
+    for (const ParamDesc& q : m->params) {
       if (q.kind == CD_P_CONV_W) {
         size_t e = (size_t)q.shape[0] * q.shape[1] * q.shape[2] * (q.shape[3] == 3 ? 8 : q.shape[3]);
         if (e > wmax) wmax = e;
       }
+      if (q.kind == CD_P_LINEAR_W && (size_t)q.size > wmax) wmax = (size_t)q.size;
+    }
     p.wpack_bytes = align_up(wmax * 4, 256);  // also holds the fp32 padded stem weight gradient
     p.wpack = alloc(p.wpack_bytes);
+    p.lin_dz = alloc((size_t)B * m->arch.classes * 2);
   }
-  if (save)
+  p.aux.assign(m->ops.size(), 0);
+  if (save) {
     for (int t = 1; t < nt; t++)
       if (!m->tensors[t].f32) p.grad[t] = alloc((size_t)B * m->tensors[t].per_sample() * m->esize());
+    for (size_t i = 0; i < m->ops.size(); i++)
+      if (m->ops[i].kind == OP_MAXPOOL) p.aux[i] = alloc((size_t)B * m->tensors[m->ops[i].y].per_sample());
+  }
   p.total = off;
   return p;
 }
@@ -405,7 +412,8 @@ extern "C" int codistill_forward(const cd_model* m, const void* params, const vo
   const int dt = m->dtype;
   const int logits_t = m->ops.back().y;
 
-  for (const Op& o : m->ops) {
+  for (size_t oi = 0; oi < m->ops.size(); oi++) {
+    const Op& o = m->ops[oi];
     const void* in = o.x == 0 ? x : c.act(o.x);
     void* out = o.y == logits_t ? static_cast<void*>(logits_out) : c.act(o.y);
     const TensorDesc& tx = m->tensors[o.x];
@@ -441,7 +449,8 @@ extern "C" int codistill_forward(const cd_model* m, const void* params, const vo
       }
       case OP_MAXPOOL: {
         ProfScope pr(CD_K_GLUE, c.s, 0, (double)batch * tx.per_sample() * m->esize() * 1.25);
-        maxpool_fwd(dt, in, out, batch, tx.h, tx.w, tx.c, o.k, o.stride, o.pad, c.s);
+        maxpool_fwd(dt, in, out, c.plan.aux[oi] ? reinterpret_cast<uint8_t*>(c.ws + c.plan.aux[oi]) : nullptr, batch, tx.h,
+                    tx.w, tx.c, o.k, o.stride, o.pad, c.s);
         break;
       }
       case OP_GAP: {
@@ -452,7 +461,11 @@ extern "C" int codistill_forward(const cd_model* m, const void* params, const vo
       case OP_LINEAR: {
         const int F = tx.c, C = m->tensors[o.y].c;
         ProfScope pr(CD_K_LINEAR, c.s, 2.0 * batch * F * C, (double)m->esize() * ((double)batch * F + (double)F * C));
-        linear_fwd(dt, in, c.P(o.pw), c.P(o.pb), static_cast<float*>(out), batch, F, C, c.s);
+        if (dt == CD_BF16 && !force_simple() && F % 8 == 0 && (int64_t)F * C * 2 < (1LL << 31))
+          linear_fwd_mfma(static_cast<const bf16_t*>(in), static_cast<const bf16_t*>(c.P(o.pw)),
+                          static_cast<const bf16_t*>(c.P(o.pb)), static_cast<float*>(out), batch, F, C, c.s);
+        else
+          linear_fwd(dt, in, c.P(o.pw), c.P(o.pb), static_cast<float*>(out), batch, F, C, c.s);
         break;
       }
     }
@@ -500,7 +513,18 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
       case OP_LINEAR: {
         const int F = tx.c, C = m->tensors[o.y].c;
         ProfScope pr(CD_K_LINEAR, c.s, 4.0 * batch * F * C, (double)m->esize() * ((double)batch * F + (double)F * C) * 2);
-        linear_bwd(dt, in, c.P(o.pw), dlogits, dx, acc, G(o.pw), G(o.pb), batch, F, C, c.s);
+        ConvGeom g;  // the dense layer as a 1x1 convolution over a 1x1 image
+        g.B = batch; g.H = g.W = g.Ho = g.Wo = 1; g.Cin = F; g.Cout = C; g.kh = g.kw = 1; g.stride = 1; g.pad = 0;
+        if (dt == CD_BF16 && !force_simple() && conv_mfma_supported(g)) {
+          bf16_t* dzb = reinterpret_cast<bf16_t*>(c.ws + c.plan.lin_dz);
+          cast_f32_bf16(dlogits, dzb, batch * C, c.s);
+          colsum(CD_F32, dlogits, batch, C, G(o.pb), c.partials(), c.s);
+          conv_wgrad_mfma(static_cast<const bf16_t*>(in), dzb, G(o.pw), g, c.partials(), c.plan.partials_bytes, c.s);
+          transpose_weight(static_cast<const bf16_t*>(c.P(o.pw)), c.wpack(), C, 1, F, c.s);
+          conv_dgrad_mfma(dzb, c.wpack(), static_cast<bf16_t*>(dx), g, acc, c.s);
+        } else {
+          linear_bwd(dt, in, c.P(o.pw), dlogits, dx, acc, G(o.pw), G(o.pb), batch, F, C, c.s);
+        }
         break;
       }
       case OP_GAP: {
@@ -510,7 +534,8 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
       }
       case OP_MAXPOOL: {
         ProfScope pr(CD_K_GLUE, c.s, 0, (double)batch * tx.per_sample() * m->esize() * 2.25);
-        maxpool_bwd(dt, in, dy, dx, acc, batch, tx.h, tx.w, tx.c, o.k, o.stride, o.pad, c.s);
+        maxpool_bwd(dt, in, dy, c.plan.aux[i] ? reinterpret_cast<const uint8_t*>(c.ws + c.plan.aux[i]) : nullptr, dx, acc,
+                    batch, tx.h, tx.w, tx.c, o.k, o.stride, o.pad, c.s);
         break;
       }
       case OP_BN: {

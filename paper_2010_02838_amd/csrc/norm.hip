@@ -164,66 +164,118 @@ __global__ void __launch_bounds__(1024) col_finalize_k(const float* __restrict__
   }
 }
 
-template <typename T, int VEC>
+// Elementwise passes.  FIXC: the number of channel vectors per row divides the grid stride, so a
+// thread keeps the same channels through all of its iterations and holds their coefficients in
+// registers; each thread has UNROLL independent vectors in flight.
+constexpr int kEltUnroll = 4;
+
+template <typename T, int VEC, bool FIXC>
 __global__ void __launch_bounds__(256) bn_apply_k(const T* __restrict__ x, const T* __restrict__ res, T* __restrict__ y,
                                                   const float* __restrict__ stats, int relu, int64_t nvec, int C) {
+  const int vc = C / VEC;
   const int64_t stride = (int64_t)gridDim.x * 256;
-  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += stride) {
-    const int c0 = (int)((i * VEC) % C);
-    float a[VEC];
-    Vec<T, VEC>::ld(x + i * VEC, a);
+  const int64_t i0 = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  float sc[VEC], sh[VEC];
+  if (FIXC) {
+    const int c0 = (int)(i0 % vc) * VEC;
 #pragma unroll
-    for (int k = 0; k < VEC; k++) a[k] = a[k] * stats[2 * C + c0 + k] + stats[3 * C + c0 + k];
-    if (res) {
-      float r[VEC];
-      Vec<T, VEC>::ld(res + i * VEC, r);
+    for (int k = 0; k < VEC; k++) { sc[k] = stats[2 * C + c0 + k]; sh[k] = stats[3 * C + c0 + k]; }
+  }
+  for (int64_t ib = i0; ib < nvec; ib += stride * kEltUnroll) {
+    float a[kEltUnroll][VEC], r[kEltUnroll][VEC];
 #pragma unroll
-      for (int k = 0; k < VEC; k++) a[k] += r[k];
+    for (int u = 0; u < kEltUnroll; u++) {
+      const int64_t i = ib + u * stride;
+      if (i < nvec) {
+        Vec<T, VEC>::ld(x + i * VEC, a[u]);
+        if (res) Vec<T, VEC>::ld(res + i * VEC, r[u]);
+      }
     }
-    if (relu) {
 #pragma unroll
-      for (int k = 0; k < VEC; k++) a[k] = fmaxf(a[k], 0.f);
+    for (int u = 0; u < kEltUnroll; u++) {
+      const int64_t i = ib + u * stride;
+      if (i < nvec) {
+        if (!FIXC) {
+          const int c0 = (int)(i % vc) * VEC;
+#pragma unroll
+          for (int k = 0; k < VEC; k++) { sc[k] = stats[2 * C + c0 + k]; sh[k] = stats[3 * C + c0 + k]; }
+        }
+#pragma unroll
+        for (int k = 0; k < VEC; k++) {
+          float v = a[u][k] * sc[k] + sh[k];
+          if (res) v += r[u][k];
+          a[u][k] = relu ? fmaxf(v, 0.f) : v;
+        }
+        Vec<T, VEC>::st(y + i * VEC, a[u]);
+      }
     }
-    Vec<T, VEC>::st(y + i * VEC, a);
   }
 }
 
-template <typename T, int VEC>
+template <typename T, int VEC, bool FIXC>
 __global__ void __launch_bounds__(256) bn_bwd_apply_k(const T* __restrict__ dy, const T* __restrict__ y,
                                                       const T* __restrict__ x, const float* __restrict__ coef, int relu,
                                                       T* __restrict__ dx, int acc_dx, T* __restrict__ dres,
                                                       int acc_dres, int64_t nvec, int C) {
+  constexpr int U = 2;
+  const int vc = C / VEC;
   const int64_t stride = (int64_t)gridDim.x * 256;
-  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += stride) {
-    const int c0 = (int)((i * VEC) % C);
-    float dz[VEC], xv[VEC], o[VEC];
-    Vec<T, VEC>::ld(dy + i * VEC, dz);
-    Vec<T, VEC>::ld(x + i * VEC, xv);
-    if (relu) {
-      float yv[VEC];
-      Vec<T, VEC>::ld(y + i * VEC, yv);
+  const int64_t i0 = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  float c1[VEC], c2[VEC], c3[VEC];
+  if (FIXC) {
+    const int c0 = (int)(i0 % vc) * VEC;
 #pragma unroll
-      for (int k = 0; k < VEC; k++) dz[k] = yv[k] > 0.f ? dz[k] : 0.f;
-    }
+    for (int k = 0; k < VEC; k++) { c1[k] = coef[c0 + k]; c2[k] = coef[C + c0 + k]; c3[k] = coef[2 * C + c0 + k]; }
+  }
+  for (int64_t ib = i0; ib < nvec; ib += stride * U) {
+    float dz[U][VEC], xv[U][VEC], yv[U][VEC], pdx[U][VEC], pdr[U][VEC];
 #pragma unroll
-    for (int k = 0; k < VEC; k++) o[k] = coef[c0 + k] * dz[k] + coef[C + c0 + k] * xv[k] + coef[2 * C + c0 + k];
-    if (acc_dx) {
-      float p[VEC];
-      Vec<T, VEC>::ld(dx + i * VEC, p);
-#pragma unroll
-      for (int k = 0; k < VEC; k++) o[k] += p[k];
-    }
-    Vec<T, VEC>::st(dx + i * VEC, o);
-    if (dres) {
-      if (acc_dres) {
-        float p[VEC];
-        Vec<T, VEC>::ld(dres + i * VEC, p);
-#pragma unroll
-        for (int k = 0; k < VEC; k++) dz[k] += p[k];
+    for (int u = 0; u < U; u++) {
+      const int64_t i = ib + u * stride;
+      if (i < nvec) {
+        Vec<T, VEC>::ld(dy + i * VEC, dz[u]);
+        Vec<T, VEC>::ld(x + i * VEC, xv[u]);
+        if (relu) Vec<T, VEC>::ld(y + i * VEC, yv[u]);
+        if (acc_dx) Vec<T, VEC>::ld(dx + i * VEC, pdx[u]);
+        if (dres && acc_dres) Vec<T, VEC>::ld(dres + i * VEC, pdr[u]);
       }
-      Vec<T, VEC>::st(dres + i * VEC, dz);
+    }
+#pragma unroll
+    for (int u = 0; u < U; u++) {
+      const int64_t i = ib + u * stride;
+      if (i < nvec) {
+        if (!FIXC) {
+          const int c0 = (int)(i % vc) * VEC;
+#pragma unroll
+          for (int k = 0; k < VEC; k++) { c1[k] = coef[c0 + k]; c2[k] = coef[C + c0 + k]; c3[k] = coef[2 * C + c0 + k]; }
+        }
+        float o[VEC];
+#pragma unroll
+        for (int k = 0; k < VEC; k++) {
+          if (relu) dz[u][k] = yv[u][k] > 0.f ? dz[u][k] : 0.f;
+          o[k] = c1[k] * dz[u][k] + c2[k] * xv[u][k] + c3[k];
+          if (acc_dx) o[k] += pdx[u][k];
+        }
+        Vec<T, VEC>::st(dx + i * VEC, o);
+        if (dres) {
+          if (acc_dres) {
+#pragma unroll
+            for (int k = 0; k < VEC; k++) dz[u][k] += pdr[u][k];
+          }
+          Vec<T, VEC>::st(dres + i * VEC, dz[u]);
+        }
+      }
     }
   }
+}
+
+// grid for the elementwise passes; *fixc tells whether a thread keeps its channels
+static unsigned elt_grid(int64_t nvec, int vc, int unroll, bool* fixc) {
+  int64_t blocks = cdiv(nvec, (int64_t)256 * unroll);
+  if (blocks > 16384) blocks = 16384;
+  if (blocks < 1) blocks = 1;
+  *fixc = (blocks * 256) % vc == 0;
+  return (unsigned)blocks;
 }
 
 // How the rows are cut into chunks; the same rule sizes the launch and bounds the partials.
@@ -271,12 +323,13 @@ static void bn_forward_t(const T* x, const T* gamma, const T* beta, const T* res
   hipLaunchKernelGGL((col_finalize_k<T, 0>), dim3((unsigned)cdiv(C, 64)), dim3(1024), 0, s, partials, p.chunks, M, C,
                      gamma, beta, stats, (float*)nullptr, (float*)nullptr, (float*)nullptr);
   const int64_t nvec = M * C / vec;
-  int64_t blocks = cdiv(nvec, 256);
-  if (blocks > 8192) blocks = 8192;
-  if (vec > 1)
-    hipLaunchKernelGGL((bn_apply_k<T, V>), dim3((unsigned)blocks), dim3(256), 0, s, x, res, y, stats, (int)relu, nvec, C);
-  else
-    hipLaunchKernelGGL((bn_apply_k<T, 1>), dim3((unsigned)blocks), dim3(256), 0, s, x, res, y, stats, (int)relu, nvec, C);
+  bool fixc;
+  const unsigned blocks = elt_grid(nvec, C / vec, kEltUnroll, &fixc);
+#define CD_BN_APPLY(VV, FC) \
+  hipLaunchKernelGGL((bn_apply_k<T, VV, FC>), dim3(blocks), dim3(256), 0, s, x, res, y, stats, (int)relu, nvec, C)
+  if (vec > 1) { if (fixc) CD_BN_APPLY(V, true); else CD_BN_APPLY(V, false); }
+  else { if (fixc) CD_BN_APPLY(1, true); else CD_BN_APPLY(1, false); }
+#undef CD_BN_APPLY
 }
 
 template <typename T>
@@ -291,14 +344,14 @@ static void bn_backward_t(const T* dy, const T* y, const T* x, const T* gamma, c
   hipLaunchKernelGGL((col_finalize_k<T, 1>), dim3((unsigned)cdiv(C, 64)), dim3(1024), 0, s, partials, p.chunks, M, C,
                      gamma, (const T*)nullptr, const_cast<float*>(stats), dgamma, dbeta, coef);
   const int64_t nvec = M * C / vec;
-  int64_t blocks = cdiv(nvec, 256);
-  if (blocks > 8192) blocks = 8192;
-  if (vec > 1)
-    hipLaunchKernelGGL((bn_bwd_apply_k<T, V>), dim3((unsigned)blocks), dim3(256), 0, s, dy, y, x, coef, (int)relu, dx,
-                       (int)acc_dx, dres, (int)acc_dres, nvec, C);
-  else
-    hipLaunchKernelGGL((bn_bwd_apply_k<T, 1>), dim3((unsigned)blocks), dim3(256), 0, s, dy, y, x, coef, (int)relu, dx,
-                       (int)acc_dx, dres, (int)acc_dres, nvec, C);
+  bool fixc;
+  const unsigned blocks = elt_grid(nvec, C / vec, 2, &fixc);
+#define CD_BN_BWD(VV, FC)                                                                                          \
+  hipLaunchKernelGGL((bn_bwd_apply_k<T, VV, FC>), dim3(blocks), dim3(256), 0, s, dy, y, x, coef, (int)relu, dx, \
+                     (int)acc_dx, dres, (int)acc_dres, nvec, C)
+  if (vec > 1) { if (fixc) CD_BN_BWD(V, true); else CD_BN_BWD(V, false); }
+  else { if (fixc) CD_BN_BWD(1, true); else CD_BN_BWD(1, false); }
+#undef CD_BN_BWD
 }
 
 template <typename T>
