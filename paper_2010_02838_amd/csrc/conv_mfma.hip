@@ -27,11 +27,14 @@ struct IgemmArgs {
   bf16_t* dst;        // [M][N]
   int64_t M;
   int N, K;
-  int Hs, Ws, Cs, Hd, Wd, kh, kw, stride, pad;
+  int Hs, Ws, Cs, Hd, Wd, kh, kw, stride, pad, pad_w;
+  // output row m = (b, hd, wd) is written to row (b*Ho + hd*omul + ooff_h)*Wo + wd*omul + ooff_w of dst
+  int omul, ooff_h, ooff_w, Ho, Wo;
   int accumulate;
   int ntiles;
   uint32_t src_bytes, wt_bytes;
   const bf16_t* bias;  // F32OUT kernels: per-column bias added to the fp32 output (nullable)
+  float* stat_partials;  // STATS kernels: [m-tiles][2][N] per-tile column sums and sums of squares
 };
 
 // Blocks are handed to the 8 XCDs round-robin; renumber so that consecutive logical tiles (which
@@ -64,7 +67,8 @@ __device__ inline int lds_off(int row, int cv) { return row * BK + ((cv ^ ((row 
 
 // MODE 0: fprop gather, hs = hd*stride - pad + r.
 // MODE 1: dgrad gather for stride 1, hs = hd + pad - r.
-// MODE 2: dgrad gather for stride 2, hs = (hd + pad - r)/2 where divisible.
+// (The dgrad of a stride-2 convolution is run as four MODE 0 problems, one per parity of the output
+// pixel; see conv_dgrad_mfma.)
 //
 // Schedule of one wave per step kt (software pipelined by hand, the compiler cannot move work across
 // the barrier): write tile kt+1 to LDS (its global loads were issued two steps earlier), issue the
@@ -72,7 +76,10 @@ __device__ inline int lds_off(int row, int cv) { return row * BK + ((cv ^ ((row 
 // read the fragments of tile kt+1 from LDS.  The MFMAs of a step thus run while the wave waits at the
 // barrier and for its LDS reads, which is what keeps the matrix pipe busy at 1-2 waves per SIMD.
 // F32OUT: the output is fp32 [M][N] (+ bias), written straight from the accumulators (dense layers).
-template <int MODE, int BM, int BN, int WAVES_M, int WAVES_N, bool F32OUT = false>
+// STATS: the epilogue also emits, per m-tile, the column sums and sums of squares of the bf16 values
+// it writes: the BatchNorm that follows a convolution gets its batch statistics without re-reading
+// the tensor.
+template <int MODE, int BM, int BN, int WAVES_M, int WAVES_N, bool F32OUT = false, bool STATS = false>
 __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   constexpr int TM = WM / 32, TN = WN / 32;
@@ -100,7 +107,6 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
   const int kvec = tid & 3, lrow = tid >> 2;  // this thread's 16-byte column and first row in a tile
   int rowoff[AV];                 // element offset of (image, h0, w0, channel 0); may be negative
   uint32_t hmask[AV], wmask[AV];  // bit r / s set: tap row r / column s reads inside the image
-  int h0[AV], w0[AV];             // MODE 2 only
 #pragma unroll
   for (int j = 0; j < AV; j++) {
     const int64_t m = m0 + lrow + 64 * j;
@@ -111,23 +117,19 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
     const int hd = (int)(q % a.Hd);
     const int b = (int)(q / a.Hd);
     const int hh = MODE == 0 ? hd * a.stride - a.pad : hd + a.pad;
-    const int ww = MODE == 0 ? wd * a.stride - a.pad : wd + a.pad;
-    h0[j] = hh;
-    w0[j] = ww;
+    const int ww = MODE == 0 ? wd * a.stride - a.pad_w : wd + a.pad_w;
     uint32_t hm = 0, wm = 0;
     for (int r = 0; r < a.kh; r++) {
-      const int hn = MODE == 0 ? hh + r : hh - r;
-      const int hs = MODE == 2 ? hn >> 1 : hn;
-      if (hn >= 0 && hs < a.Hs && (MODE != 2 || (hn & 1) == 0)) hm |= 1u << r;
+      const int hs = MODE == 0 ? hh + r : hh - r;
+      if (hs >= 0 && hs < a.Hs) hm |= 1u << r;
     }
     for (int t = 0; t < a.kw; t++) {
-      const int wn = MODE == 0 ? ww + t : ww - t;
-      const int ws = MODE == 2 ? wn >> 1 : wn;
-      if (wn >= 0 && ws < a.Ws && (MODE != 2 || (wn & 1) == 0)) wm |= 1u << t;
+      const int ws = MODE == 0 ? ww + t : ww - t;
+      if (ws >= 0 && ws < a.Ws) wm |= 1u << t;
     }
     hmask[j] = rowok ? hm : 0u;
     wmask[j] = wm;
-    rowoff[j] = MODE == 2 ? b * a.Hs * a.Ws : ((b * a.Hs + hh) * a.Ws + ww) * a.Cs;
+    rowoff[j] = ((b * a.Hs + hh) * a.Ws + ww) * a.Cs;
   }
   uint32_t woff[BV];  // byte offset of this thread's filter row (+ its 16-byte column), ~0 if masked
 #pragma unroll
@@ -156,9 +158,7 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
 #pragma unroll
     for (int j = 0; j < AV; j++) {
       const bool ok = kok && ((hmask[j] >> kr) & (wmask[j] >> ks) & 1u);
-      int off;
-      if (MODE == 2) off = (rowoff[j] + ((h0[j] - kr) >> 1) * a.Ws + ((w0[j] - ks) >> 1)) * a.Cs + kc;
-      else off = rowoff[j] + koff;
+      const int off = rowoff[j] + koff;
       ra[j] = buf_load16(rsrc, ok ? (uint32_t)off * 2u : 0xffffffffu);
     }
     const uint32_t wk = (uint32_t)kt * (BK * 2u);
@@ -253,6 +253,9 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
   constexpr int RPP = 64 / LPR;      // rows per pass
   constexpr int TPG = EROWS / 32;    // 32-row tiles per staging pass
   const int er = lane / LPR, ec = (lane % LPR) * 8;
+  float ssum[8], ssq[8];
+#pragma unroll
+  for (int k = 0; k < 8; k++) { ssum[k] = 0.f; ssq[k] = 0.f; }
 #pragma unroll
   for (int g0 = 0; g0 < TM; g0 += TPG) {
     __syncthreads();  // tiles (first pass) or the previous pass's staging rows are no longer read
@@ -271,10 +274,25 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
 #pragma unroll
     for (int p = 0; p < EROWS / RPP; p++) {
       const int row = p * RPP + er;
-      const int64_t m = m0 + wm0 + g0 * 32 + row;
+      int64_t m = m0 + wm0 + g0 * 32 + row;
       const int n = n0 + wn0 + ec;
       if (m < a.M && n < a.N) {
         uint4 v = *reinterpret_cast<const uint4*>(stage + row * EPITCH + ec);
+        if (a.omul) {  // strided placement of the rows (parity class of a stride-2 dgrad)
+          const int wd = (int)(m % a.Wd);
+          const int64_t q = m / a.Wd;
+          const int hd = (int)(q % a.Hd);
+          m = ((q / a.Hd) * a.Ho + hd * a.omul + a.ooff_h) * a.Wo + wd * a.omul + a.ooff_w;
+        }
+        if (STATS) {
+          const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+          for (int q = 0; q < 4; q++) {
+            const float f0 = __uint_as_float(u[q] << 16), f1 = __uint_as_float(u[q] & 0xffff0000u);
+            ssum[2 * q] += f0; ssq[2 * q] += f0 * f0;
+            ssum[2 * q + 1] += f1; ssq[2 * q + 1] += f1 * f1;
+          }
+        }
         bf16_t* dp = a.dst + m * a.N + n;
         if (a.accumulate) {
           const uint4 o = *reinterpret_cast<const uint4*>(dp);
@@ -290,30 +308,64 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
       }
     }
   }
+  if (STATS) {
+    // lanes that share a channel group differ in their row index: fold them, then the waves of a column
+#pragma unroll
+    for (int o = LPR; o < 64; o <<= 1)
+#pragma unroll
+      for (int k = 0; k < 8; k++) {
+        ssum[k] += __shfl_xor(ssum[k], o, 64);
+        ssq[k] += __shfl_xor(ssq[k], o, 64);
+      }
+    __syncthreads();  // staging rows are no longer read
+    float* red = reinterpret_cast<float*>(smem);  // [WAVES_M][2][BN]
+    if (lane < LPR) {
+      const int wmi = wave % WAVES_M;
+#pragma unroll
+      for (int k = 0; k < 8; k++) {
+        red[(wmi * 2 + 0) * BN + wn0 + lane * 8 + k] = ssum[k];
+        red[(wmi * 2 + 1) * BN + wn0 + lane * 8 + k] = ssq[k];
+      }
+    }
+    __syncthreads();
+    if (tid < BN && n0 + tid < a.N) {
+      float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+      for (int w = 0; w < WAVES_M; w++) { s0 += red[(w * 2 + 0) * BN + tid]; s1 += red[(w * 2 + 1) * BN + tid]; }
+      const int64_t mt = tile / a.ntiles;
+      a.stat_partials[(mt * 2 + 0) * a.N + n0 + tid] = s0;
+      a.stat_partials[(mt * 2 + 1) * a.N + n0 + tid] = s1;
+    }
+  }
 }
 
 // Tile selection override for tuning runs (0 = automatic, 1: 128x128, 2: 256x128).
 int g_tune_tile = 0;
 int g_tune_co = -1;  // unused
 
-template <int MODE>
-static void launch_igemm(IgemmArgs a, hipStream_t s) {
+// returns the number of m-tiles (= statistics chunks when STATS)
+template <int MODE, bool STATS>
+static int launch_igemm(IgemmArgs a, hipStream_t s) {
   if (a.N > 64) {
     a.ntiles = (int)cdiv(a.N, 128);
     if (g_tune_tile == 2) {
-      hipLaunchKernelGGL((igemm_kernel<MODE, 256, 128, 2, 2>), dim3((unsigned)(cdiv(a.M, 256) * a.ntiles)), dim3(256), 0,
+      const int mt = (int)cdiv(a.M, 256);
+      hipLaunchKernelGGL((igemm_kernel<MODE, 256, 128, 2, 2, false, STATS>), dim3((unsigned)(mt * a.ntiles)), dim3(256), 0,
                          s, a);
-    } else {
-      const int64_t blocks = cdiv(a.M, 128) * a.ntiles;
-      hipLaunchKernelGGL((igemm_kernel<MODE, 128, 128, 2, 2>), dim3((unsigned)blocks), dim3(256), 0, s, a);
+      return mt;
     }
-  } else if (a.N > 32) {
-    a.ntiles = 1;
-    hipLaunchKernelGGL((igemm_kernel<MODE, 256, 64, 4, 1>), dim3((unsigned)cdiv(a.M, 256)), dim3(256), 0, s, a);
-  } else {
-    a.ntiles = 1;
-    hipLaunchKernelGGL((igemm_kernel<MODE, 256, 32, 4, 1>), dim3((unsigned)cdiv(a.M, 256)), dim3(256), 0, s, a);
+    const int mt = (int)cdiv(a.M, 128);
+    hipLaunchKernelGGL((igemm_kernel<MODE, 128, 128, 2, 2, false, STATS>), dim3((unsigned)((int64_t)mt * a.ntiles)),
+                       dim3(256), 0, s, a);
+    return mt;
   }
+  a.ntiles = 1;
+  const int mt = (int)cdiv(a.M, 256);
+  if (a.N > 32)
+    hipLaunchKernelGGL((igemm_kernel<MODE, 256, 64, 4, 1, false, STATS>), dim3((unsigned)mt), dim3(256), 0, s, a);
+  else
+    hipLaunchKernelGGL((igemm_kernel<MODE, 256, 32, 4, 1, false, STATS>), dim3((unsigned)mt), dim3(256), 0, s, a);
+  return mt;
 }
 
 bool conv_mfma_supported(const ConvGeom& g) {
@@ -327,9 +379,10 @@ bool conv_mfma_supported(const ConvGeom& g) {
 void linear_fwd_mfma(const bf16_t* x, const bf16_t* w, const bf16_t* bias, float* y, int64_t B, int F, int C,
                      hipStream_t s) {
   IgemmArgs a;
-  a.src = x; a.wt = w; a.dst = reinterpret_cast<bf16_t*>(y); a.bias = bias;
+  a.src = x; a.wt = w; a.dst = reinterpret_cast<bf16_t*>(y); a.bias = bias; a.stat_partials = nullptr;
   a.M = B; a.N = C; a.K = F;
-  a.Hs = 1; a.Ws = 1; a.Cs = F; a.Hd = 1; a.Wd = 1; a.kh = 1; a.kw = 1; a.stride = 1; a.pad = 0;
+  a.Hs = 1; a.Ws = 1; a.Cs = F; a.Hd = 1; a.Wd = 1; a.kh = 1; a.kw = 1; a.stride = 1; a.pad = 0; a.pad_w = 0;
+  a.omul = 0; a.ooff_h = a.ooff_w = 0; a.Ho = a.Wo = 1;
   a.accumulate = 0;
   a.src_bytes = (uint32_t)(B * (int64_t)F * 2);
   a.wt_bytes = (uint32_t)((int64_t)C * F * 2);
@@ -338,32 +391,101 @@ void linear_fwd_mfma(const bf16_t* x, const bf16_t* w, const bf16_t* bias, float
                      a);
 }
 
-void conv_fprop_mfma(const bf16_t* x, const bf16_t* w, bf16_t* y, const ConvGeom& g, hipStream_t s) {
+int conv_fprop_mfma(const bf16_t* x, const bf16_t* w, bf16_t* y, const ConvGeom& g, float* stat_partials,
+                    hipStream_t s) {
   IgemmArgs a;
   a.bias = nullptr;
+  a.stat_partials = stat_partials;
   a.src = x; a.wt = w; a.dst = y;
   a.M = g.M(); a.N = g.Cout; a.K = g.K();
   a.Hs = g.H; a.Ws = g.W; a.Cs = g.Cin; a.Hd = g.Ho; a.Wd = g.Wo;
-  a.kh = g.kh; a.kw = g.kw; a.stride = g.stride; a.pad = g.pad;
+  a.kh = g.kh; a.kw = g.kw; a.stride = g.stride; a.pad = g.pad; a.pad_w = g.pad;
+  a.omul = 0; a.ooff_h = a.ooff_w = 0; a.Ho = g.Ho; a.Wo = g.Wo;
   a.accumulate = 0; a.ntiles = 1;
   a.src_bytes = (uint32_t)(g.B * g.H * g.W * (int64_t)g.Cin * 2);
   a.wt_bytes = (uint32_t)((int64_t)g.Cout * g.K() * 2);
-  launch_igemm<0>(a, s);
+  return stat_partials ? launch_igemm<0, true>(a, s) : launch_igemm<0, false>(a, s);
 }
 
-void conv_dgrad_mfma(const bf16_t* dy, const bf16_t* wt, bf16_t* dx, const ConvGeom& g, bool accumulate,
+// w[Cout][kh][kw][Cin] -> wt[Cin][th][tw][Cout] with filter row r = r0 - 2*jh, column s = s0 - 2*jw
+__global__ void __launch_bounds__(256) gather_weight_class_k(const bf16_t* __restrict__ w, bf16_t* __restrict__ wt,
+                                                             int cout, int kh, int kw, int cin, int th, int tw, int r0,
+                                                             int s0) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (int64_t)cin * th * tw * cout) return;
+  const int n = i % cout;
+  int64_t q = i / cout;
+  const int jw = q % tw; q /= tw;
+  const int jh = q % th;
+  const int c = q / th;
+  wt[i] = w[(((int64_t)n * kh + (r0 - 2 * jh)) * kw + (s0 - 2 * jw)) * cin + c];
+}
+
+__global__ void __launch_bounds__(256) fill_zero16_k(uint4* p, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = make_uint4(0, 0, 0, 0);
+}
+
+void conv_dgrad_mfma(const bf16_t* dy, const bf16_t* w, bf16_t* wt, bf16_t* dx, const ConvGeom& g, bool accumulate,
                      hipStream_t s) {
   IgemmArgs a;
   a.bias = nullptr;
-  a.src = dy; a.wt = wt; a.dst = dx;
-  a.M = g.B * g.H * g.W; a.N = g.Cin; a.K = g.kh * g.kw * g.Cout;
-  a.Hs = g.Ho; a.Ws = g.Wo; a.Cs = g.Cout; a.Hd = g.H; a.Wd = g.W;
-  a.kh = g.kh; a.kw = g.kw; a.stride = g.stride; a.pad = g.pad;
-  a.accumulate = accumulate ? 1 : 0; a.ntiles = 1;
+  a.stat_partials = nullptr;
+  a.src = dy; a.dst = dx;
+  a.N = g.Cin;
+  a.Hs = g.Ho; a.Ws = g.Wo; a.Cs = g.Cout;
+  a.ntiles = 1;
   a.src_bytes = (uint32_t)(g.M() * (int64_t)g.Cout * 2);
-  a.wt_bytes = (uint32_t)((int64_t)g.Cout * g.K() * 2);
-  if (g.stride == 1) launch_igemm<1>(a, s);
-  else launch_igemm<2>(a, s);
+  a.Ho = g.H; a.Wo = g.W;
+  if (g.stride == 1) {
+    transpose_weight(w, wt, g.Cout, g.kh * g.kw, g.Cin, s);
+    a.wt = wt;
+    a.M = g.B * g.H * g.W; a.K = g.kh * g.kw * g.Cout;
+    a.Hd = g.H; a.Wd = g.W;
+    a.kh = g.kh; a.kw = g.kw; a.stride = 1; a.pad = g.pad; a.pad_w = g.pad;
+    a.omul = 0; a.ooff_h = a.ooff_w = 0;
+    a.accumulate = accumulate ? 1 : 0;
+    a.wt_bytes = (uint32_t)((int64_t)g.Cout * g.K() * 2);
+    launch_igemm<1, false>(a, s);
+    return;
+  }
+  // Stride 2: input pixel (h, w) receives dy[(h + pad - r)/2, (w + pad - s)/2] * w[., r, s, .] for the taps
+  // of matching parity only.  Per parity class (h%2, w%2) that is a stride-1 gather over the half
+  // resolution grid h = 2h' + ph with window rows t in [tmin, tmax], ho = h' + t, r = ph + pad - 2t: a
+  // MODE 0 problem with its own filter layout, writing every second row / column of dx.
+  bool covered_all = true;
+  for (int ph = 0; ph < 2; ph++) {
+    const int tmax = (ph + g.pad) >> 1, lo = ph + g.pad - g.kh + 1;
+    if (tmax < (lo <= 0 ? -((-lo) >> 1) : (lo + 1) >> 1)) covered_all = false;
+  }
+  if (!accumulate && !covered_all) {
+    const int64_t n16 = g.B * g.H * g.W * (int64_t)g.Cin / 8;
+    hipLaunchKernelGGL(fill_zero16_k, dim3((unsigned)cdiv(n16, 256)), dim3(256), 0, s, reinterpret_cast<uint4*>(dx), n16);
+    accumulate = true;
+  }
+  int64_t woff = 0;
+  for (int ph = 0; ph < 2; ph++)
+    for (int pw = 0; pw < 2; pw++) {
+      const int loh = ph + g.pad - g.kh + 1, low = pw + g.pad - g.kw + 1;
+      const int tminh = loh <= 0 ? -((-loh) >> 1) : (loh + 1) >> 1, tmaxh = (ph + g.pad) >> 1;
+      const int tminw = low <= 0 ? -((-low) >> 1) : (low + 1) >> 1, tmaxw = (pw + g.pad) >> 1;
+      const int th = tmaxh - tminh + 1, tw = tmaxw - tminw + 1;
+      const int hd = (g.H - ph + 1) / 2, wd = (g.W - pw + 1) / 2;
+      if (th <= 0 || tw <= 0 || hd <= 0 || wd <= 0) continue;
+      bf16_t* wc = wt + woff;
+      const int64_t wn = (int64_t)g.Cin * th * tw * g.Cout;
+      hipLaunchKernelGGL(gather_weight_class_k, dim3((unsigned)cdiv(wn, 256)), dim3(256), 0, s, w, wc, g.Cout, g.kh,
+                         g.kw, g.Cin, th, tw, ph + g.pad - 2 * tminh, pw + g.pad - 2 * tminw);
+      woff += (wn + 7) / 8 * 8;
+      a.wt = wc;
+      a.M = g.B * hd * wd; a.K = th * tw * g.Cout;
+      a.Hd = hd; a.Wd = wd;
+      a.kh = th; a.kw = tw; a.stride = 1; a.pad = -tminh; a.pad_w = -tminw;
+      a.omul = 2; a.ooff_h = ph; a.ooff_w = pw;
+      a.accumulate = accumulate ? 1 : 0;
+      a.wt_bytes = (uint32_t)(wn * 2);
+      launch_igemm<0, false>(a, s);
+    }
 }
 
 // ---- wgrad ------------------------------------------------------------------------------------------

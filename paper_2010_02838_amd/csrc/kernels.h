@@ -29,6 +29,11 @@ void colsum(int dtype, const void* a, int64_t M, int C, float* out, float* parti
 // stats: [4][C] fp32 = mean, invstd, scale, shift (kept for the backward pass).
 void bn_forward(int dtype, const void* x, const void* gamma, const void* beta, const void* res, bool relu, void* y,
                 int64_t M, int C, float* stats, float* partials, hipStream_t s);
+// Same, with the column sums already in partials ([chunks][2][C], from the producing convolution);
+// scratch: room for 64 * C floats behind them.
+void bn_forward_partials(int dtype, const void* x, const void* gamma, const void* beta, const void* res, bool relu,
+                         void* y, int64_t M, int C, float* stats, const float* partials, int chunks, float* scratch,
+                         hipStream_t s);
 // dz = dy * (relu ? y > 0 : 1); dgamma = sum dz*xhat; dbeta = sum dz;
 // dx = gamma*invstd*(dz - dbeta/M - xhat*dgamma/M); dres = dz.  coef: [3][C] fp32 scratch.
 void bn_backward(int dtype, const void* dy, const void* y, const void* x, const void* gamma, const float* stats,
@@ -57,11 +62,15 @@ namespace cd {
 // ---- bf16 MFMA implicit-GEMM convolution (conv_mfma.hip) -----------------------------------------
 // All need the channel count of the gathered tensor to be a multiple of 8 (16-byte vectors).
 bool conv_mfma_supported(const ConvGeom& g);
-// y[M][Cout] = im2col(x)[M][K] * w[Cout][K]^T
-void conv_fprop_mfma(const bf16_t* x, const bf16_t* w, bf16_t* y, const ConvGeom& g, hipStream_t s);
-// dx[B*H*W][Cin] (+)= gather(dy)[.][kh*kw*Cout] * wt[Cin][kh*kw*Cout]^T, wt = weights re-laid-out by
-// transpose_weight
-void conv_dgrad_mfma(const bf16_t* dy, const bf16_t* wt, bf16_t* dx, const ConvGeom& g, bool accumulate,
+// y[M][Cout] = im2col(x)[M][K] * w[Cout][K]^T.  With stat_partials the kernel also writes per-tile
+// column sums and sums of squares, [chunks][2][Cout] fp32, and returns the number of chunks
+// (needs (M/128 + 1) * 2 * Cout floats); see bn_forward_partials.
+int conv_fprop_mfma(const bf16_t* x, const bf16_t* w, bf16_t* y, const ConvGeom& g, float* stat_partials,
+                    hipStream_t s);
+// dx[B*H*W][Cin] (+)= gather(dy)[.][taps*Cout] * wt[Cin][taps*Cout]^T.  w is the filter as stored; wt is
+// scratch of at least Cout*K + 32 elements that receives its re-laid-out copy (or copies, per parity
+// class, for stride 2).
+void conv_dgrad_mfma(const bf16_t* dy, const bf16_t* w, bf16_t* wt, bf16_t* dx, const ConvGeom& g, bool accumulate,
                      hipStream_t s);
 // dw[Cout][K] = dy[M][Cout]^T * im2col(x)[M][K], split over M with fp32 partials reduced in fixed order
 void conv_wgrad_mfma(const bf16_t* x, const bf16_t* dy, float* dw, const ConvGeom& g, float* partials,

@@ -217,7 +217,7 @@ Plan make_plan(const cd_model* m, int64_t B, bool save) {
       }
       if (q.kind == CD_P_LINEAR_W && (size_t)q.size > wmax) wmax = (size_t)q.size;
     }
-    p.wpack_bytes = align_up(wmax * 4, 256);  // also holds the fp32 padded stem weight gradient
+    p.wpack_bytes = align_up(wmax * 4 + 256, 256);  // also holds the fp32 padded stem weight gradient
     p.wpack = alloc(p.wpack_bytes);
     p.lin_dz = alloc((size_t)B * m->arch.classes * 2);
   }
@@ -412,6 +412,7 @@ extern "C" int codistill_forward(const cd_model* m, const void* params, const vo
   const int dt = m->dtype;
   const int logits_t = m->ops.back().y;
 
+  int stat_chunks = 0, stat_tensor = -1;  // statistics a convolution left in the partials area for its BatchNorm
   for (size_t oi = 0; oi < m->ops.size(); oi++) {
     const Op& o = m->ops[oi];
     const void* in = o.x == 0 ? x : c.act(o.x);
@@ -433,7 +434,11 @@ extern "C" int codistill_forward(const cd_model* m, const void* params, const vo
           ProfScope pr(CD_K_CONV_FPROP, c.s, 2.0 * g.M() * g.Cout * g.K(), conv_bytes(m, g));
           ConvGeom gp = g;
           if (gp.Cin == 3) gp.Cin = 8;
-          conv_fprop_mfma(src, w, static_cast<bf16_t*>(out), gp, c.s);
+          // a BatchNorm that follows directly gets its column sums from the convolution's epilogue
+          const bool fuse = oi + 1 < m->ops.size() && m->ops[oi + 1].kind == OP_BN && m->ops[oi + 1].x == o.y &&
+                            (size_t)(g.M() / 128 + 1 + 64) * 2 * g.Cout * sizeof(float) <= c.plan.partials_bytes;
+          stat_chunks = conv_fprop_mfma(src, w, static_cast<bf16_t*>(out), gp, fuse ? c.partials() : nullptr, c.s);
+          stat_tensor = fuse ? o.y : -1;
         } else {
           ProfScope pr(CD_K_CONV_FPROP, c.s, 2.0 * g.M() * g.Cout * g.K(), conv_bytes(m, g));
           conv_fprop_simple(dt, in, c.P(o.pw), c.P(o.pb), out, g, o.relu, c.s);
@@ -443,8 +448,13 @@ extern "C" int codistill_forward(const cd_model* m, const void* params, const vo
       case OP_BN: {
         const int64_t M = batch * tx.h * tx.w;
         ProfScope pr(CD_K_NORM, c.s, 0, (double)M * tx.c * m->esize() * (3 + (o.res >= 0 ? 1 : 0)));
-        bn_forward(dt, in, c.P(o.pw), c.P(o.pb), o.res >= 0 ? c.act(o.res) : nullptr, o.relu, out, M, tx.c,
-                   c.stats(o), c.partials(), c.s);
+        if (stat_tensor == o.x)
+          bn_forward_partials(dt, in, c.P(o.pw), c.P(o.pb), o.res >= 0 ? c.act(o.res) : nullptr, o.relu, out, M, tx.c,
+                              c.stats(o), c.partials(), stat_chunks, c.partials() + (size_t)stat_chunks * 2 * tx.c, c.s);
+        else
+          bn_forward(dt, in, c.P(o.pw), c.P(o.pb), o.res >= 0 ? c.act(o.res) : nullptr, o.relu, out, M, tx.c,
+                     c.stats(o), c.partials(), c.s);
+        stat_tensor = -1;
         break;
       }
       case OP_MAXPOOL: {
@@ -520,8 +530,7 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
           cast_f32_bf16(dlogits, dzb, batch * C, c.s);
           colsum(CD_F32, dlogits, batch, C, G(o.pb), c.partials(), c.s);
           conv_wgrad_mfma(static_cast<const bf16_t*>(in), dzb, G(o.pw), g, c.partials(), c.plan.partials_bytes, c.s);
-          transpose_weight(static_cast<const bf16_t*>(c.P(o.pw)), c.wpack(), C, 1, F, c.s);
-          conv_dgrad_mfma(dzb, c.wpack(), static_cast<bf16_t*>(dx), g, acc, c.s);
+          conv_dgrad_mfma(dzb, static_cast<const bf16_t*>(c.P(o.pw)), c.wpack(), static_cast<bf16_t*>(dx), g, acc, c.s);
         } else {
           linear_bwd(dt, in, c.P(o.pw), dlogits, dx, acc, G(o.pw), G(o.pb), batch, F, C, c.s);
         }
@@ -579,9 +588,8 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
         if (o.x != 0) {
           ProfScope pr(CD_K_CONV_DGRAD, c.s, 2.0 * g.M() * g.Cout * g.K(), conv_bytes(m, g));
           if (mf) {
-            const bf16_t* w = static_cast<const bf16_t*>(c.P(o.pw));
-            transpose_weight(w, c.wpack(), g.Cout, g.kh * g.kw, g.Cin, c.s);
-            conv_dgrad_mfma(static_cast<const bf16_t*>(dy), c.wpack(), static_cast<bf16_t*>(dx), g, acc, c.s);
+            conv_dgrad_mfma(static_cast<const bf16_t*>(dy), static_cast<const bf16_t*>(c.P(o.pw)), c.wpack(),
+                            static_cast<bf16_t*>(dx), g, acc, c.s);
           } else {
             conv_dgrad_simple(dt, dy, c.P(o.pw), dx, g, acc, c.s);
           }

@@ -169,6 +169,33 @@ __global__ void __launch_bounds__(1024) col_finalize_k(const float* __restrict__
 // registers; each thread has UNROLL independent vectors in flight.
 constexpr int kEltUnroll = 4;
 
+// Fold many chunks of partial sums into 32: block = 64 channels x 16 lanes, grid.y = 32 slices.
+__global__ void __launch_bounds__(1024) col_fold_k(const float* __restrict__ partials, int chunks, int C,
+                                                   float* __restrict__ out) {
+  __shared__ float sm[2][16][64];
+  const int cl = threadIdx.x & 63, lane = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + cl;
+  const int per = (chunks + gridDim.y - 1) / gridDim.y;
+  const int j0 = blockIdx.y * per, j1 = j0 + per < chunks ? j0 + per : chunks;
+  float a0 = 0.f, a1 = 0.f;
+  if (c < C) {
+#pragma unroll 4
+    for (int j = j0 + lane; j < j1; j += 16) {
+      a0 += partials[((int64_t)j * 2 + 0) * C + c];
+      a1 += partials[((int64_t)j * 2 + 1) * C + c];
+    }
+  }
+  sm[0][lane][cl] = a0;
+  sm[1][lane][cl] = a1;
+  __syncthreads();
+  if (lane != 0 || c >= C) return;
+  float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+  for (int j = 0; j < 16; j++) { s0 += sm[0][j][cl]; s1 += sm[1][j][cl]; }
+  out[((int64_t)blockIdx.y * 2 + 0) * C + c] = s0;
+  out[((int64_t)blockIdx.y * 2 + 1) * C + c] = s1;
+}
+
 template <typename T, int VEC, bool FIXC>
 __global__ void __launch_bounds__(256) bn_apply_k(const T* __restrict__ x, const T* __restrict__ res, T* __restrict__ y,
                                                   const float* __restrict__ stats, int relu, int64_t nvec, int C) {
@@ -313,14 +340,24 @@ static ReducePlan launch_reduce(const T* a0, const T* a1, const T* a2, const flo
   return p;
 }
 
+// pre_chunks > 0: the column sums are already in partials (written by the producing convolution)
 template <typename T>
 static void bn_forward_t(const T* x, const T* gamma, const T* beta, const T* res, bool relu, T* y, int64_t M, int C,
-                         float* stats, float* partials, hipStream_t s) {
+                         float* stats, float* partials, int pre_chunks, float* scratch, hipStream_t s) {
   const int vec = pick_vec<T>(C, x, res, y, nullptr);
   constexpr int V = sizeof(T) == 2 ? 8 : 4;
-  ReducePlan p = vec > 1 ? launch_reduce<T, V, 0>(x, nullptr, nullptr, nullptr, false, M, C, partials, s)
-                         : launch_reduce<T, 1, 0>(x, nullptr, nullptr, nullptr, false, M, C, partials, s);
-  hipLaunchKernelGGL((col_finalize_k<T, 0>), dim3((unsigned)cdiv(C, 64)), dim3(1024), 0, s, partials, p.chunks, M, C,
+  int chunks = pre_chunks;
+  const float* src = partials;
+  if (pre_chunks == 0) {
+    ReducePlan p = vec > 1 ? launch_reduce<T, V, 0>(x, nullptr, nullptr, nullptr, false, M, C, partials, s)
+                           : launch_reduce<T, 1, 0>(x, nullptr, nullptr, nullptr, false, M, C, partials, s);
+    chunks = p.chunks;
+  } else if (pre_chunks > 256) {
+    hipLaunchKernelGGL(col_fold_k, dim3((unsigned)cdiv(C, 64), 32), dim3(1024), 0, s, partials, pre_chunks, C, scratch);
+    chunks = 32;
+    src = scratch;
+  }
+  hipLaunchKernelGGL((col_finalize_k<T, 0>), dim3((unsigned)cdiv(C, 64)), dim3(1024), 0, s, src, chunks, M, C,
                      gamma, beta, stats, (float*)nullptr, (float*)nullptr, (float*)nullptr);
   const int64_t nvec = M * C / vec;
   bool fixc;
@@ -368,10 +405,20 @@ void bn_forward(int dtype, const void* x, const void* gamma, const void* beta, c
                 int64_t M, int C, float* stats, float* partials, hipStream_t s) {
   if (dtype == CD_BF16)
     bn_forward_t<bf16_t>((const bf16_t*)x, (const bf16_t*)gamma, (const bf16_t*)beta, (const bf16_t*)res, relu,
-                         (bf16_t*)y, M, C, stats, partials, s);
+                         (bf16_t*)y, M, C, stats, partials, 0, nullptr, s);
   else
     bn_forward_t<float>((const float*)x, (const float*)gamma, (const float*)beta, (const float*)res, relu, (float*)y, M,
-                        C, stats, partials, s);
+                        C, stats, partials, 0, nullptr, s);
+}
+void bn_forward_partials(int dtype, const void* x, const void* gamma, const void* beta, const void* res, bool relu,
+                         void* y, int64_t M, int C, float* stats, const float* partials, int chunks, float* scratch,
+                         hipStream_t s) {
+  if (dtype == CD_BF16)
+    bn_forward_t<bf16_t>((const bf16_t*)x, (const bf16_t*)gamma, (const bf16_t*)beta, (const bf16_t*)res, relu,
+                         (bf16_t*)y, M, C, stats, const_cast<float*>(partials), chunks, scratch, s);
+  else
+    bn_forward_t<float>((const float*)x, (const float*)gamma, (const float*)beta, (const float*)res, relu, (float*)y, M,
+                        C, stats, const_cast<float*>(partials), chunks, scratch, s);
 }
 void bn_backward(int dtype, const void* dy, const void* y, const void* x, const void* gamma, const float* stats,
                  bool relu, void* dx, bool acc_dx, void* dres, bool acc_dres, float* dgamma, float* dbeta, float* coef,
