@@ -355,6 +355,12 @@ static int launch_igemm(IgemmArgs a, hipStream_t s) {
       return mt;
     }
     const int mt = (int)cdiv(a.M, 128);
+    if (g_tune_tile == 3) {
+      a.ntiles = (int)cdiv(a.N, 64);
+      hipLaunchKernelGGL((igemm_kernel<MODE, 128, 64, 2, 2, false, STATS>), dim3((unsigned)((int64_t)mt * a.ntiles)),
+                         dim3(256), 0, s, a);
+      return mt;
+    }
     hipLaunchKernelGGL((igemm_kernel<MODE, 128, 128, 2, 2, false, STATS>), dim3((unsigned)((int64_t)mt * a.ntiles)),
                        dim3(256), 0, s, a);
     return mt;

@@ -129,20 +129,26 @@ __global__ void __launch_bounds__((TPR > 256 ? TPR : 256)) loss_row_kernel(LossA
   group_reduce<TPR, 2, 3u>(mx, smem);
   const float m = mx[0], mp = mx[1];
   // sums: [0] sum exp(z-m)  [1] sum z  [2] MSE: sum (z-z')^2 | KL: sum exp(z'-m')  [3] KL: sum exp(z'-m')(z'-z)
+  // The registers are reused for what the gradient needs: z becomes e = exp(z-m), z' becomes z-z'
+  // (MSE) or e' = exp(z'-m') (KL), so that the gradient costs no second exponential per element.
   float s[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int i = 0; i < V; i++) {
     int64_t c = ((int64_t)i * TPR + lane) * 4;
     if (c < cols) {
-      const float xv[4] = {x[i].x, x[i].y, x[i].z, x[i].w};
-      const float yv[4] = {MODE ? y[i].x : 0.f, MODE ? y[i].y : 0.f, MODE ? y[i].z : 0.f, MODE ? y[i].w : 0.f};
+      float xv[4] = {x[i].x, x[i].y, x[i].z, x[i].w};
+      float yv[4] = {MODE ? y[i].x : 0.f, MODE ? y[i].y : 0.f, MODE ? y[i].z : 0.f, MODE ? y[i].w : 0.f};
 #pragma unroll
       for (int k = 0; k < 4; k++) {
-        s[0] += __expf(xv[k] - m);
+        const float e = __expf(xv[k] - m);
+        s[0] += e;
         s[1] += xv[k];
-        if (MODE == 1) { float d = xv[k] - yv[k]; s[2] += d * d; }
-        if (MODE == 2) { float e = __expf(yv[k] - mp); s[2] += e; s[3] += e * (yv[k] - xv[k]); }
+        if (MODE == 1) { const float d = xv[k] - yv[k]; s[2] += d * d; yv[k] = d; }
+        if (MODE == 2) { const float ep = __expf(yv[k] - mp); s[2] += ep; s[3] += ep * (yv[k] - xv[k]); yv[k] = ep; }
+        xv[k] = e;
       }
+      x[i] = make_float4(xv[0], xv[1], xv[2], xv[3]);
+      if (MODE) y[i] = make_float4(yv[0], yv[1], yv[2], yv[3]);
     }
   }
   group_reduce<TPR, 4, 0u>(s, smem);
@@ -156,12 +162,15 @@ __global__ void __launch_bounds__((TPR > 256 ? TPR : 256)) loss_row_kernel(LossA
     if (MODE == 2) d = s[3] / s[2] - lsep + lse;
     a.row_dist[row] = d;
   }
-  // gradient
+  // gradient: p = e / sum e, p' = e' / sum e'
   const float invn = 1.f / (float)nvalid;
   const float epsc = a.eps / (float)cols;
   float cm = 0.f;
   if (MODE == 1) cm = a.alpha * 2.f * invn / (a.mse_reduction == CD_MEAN_ALL ? (float)cols : 1.f);
   const float onehot = (1.f - a.eps) * invn;
+  const float fp = invn / s[0];                                   // p * invn = e * fp
+  const float fq = MODE == 2 ? invn / s[2] : 0.f;                 // p' * invn = e' * fq (same form as fp: an identical peer cancels exactly)
+  const float base = -epsc * invn;
 #pragma unroll
   for (int i = 0; i < V; i++) {
     int64_t c = ((int64_t)i * TPR + lane) * 4;
@@ -171,10 +180,9 @@ __global__ void __launch_bounds__((TPR > 256 ? TPR : 256)) loss_row_kernel(LossA
       float o[4];
 #pragma unroll
       for (int k = 0; k < 4; k++) {
-        float p = __expf(xv[k] - lse);
-        float gk = (p - epsc) * invn;
-        if (MODE == 1) gk += cm * (xv[k] - yv[k]);
-        if (MODE == 2) gk += a.alpha * invn * (p - __expf(yv[k] - lsep));
+        float gk = xv[k] * fp + base;
+        if (MODE == 1) gk += cm * yv[k];
+        if (MODE == 2) gk += a.alpha * (__fmul_rn(xv[k], fp) - __fmul_rn(yv[k], fq));  // no fma: exact cancellation
         if (c + k == t) gk -= onehot;
         o[k] = gk;
       }

@@ -296,12 +296,16 @@ __global__ void __launch_bounds__(256) bn_bwd_apply_k(const T* __restrict__ dy, 
   }
 }
 
-// grid for the elementwise passes; *fixc tells whether a thread keeps its channels
+// grid for the elementwise passes: one trip of `unroll` vectors per thread; *fixc tells whether a
+// thread keeps its channels (the grid stride is then a multiple of the vectors per row)
 static unsigned elt_grid(int64_t nvec, int vc, int unroll, bool* fixc) {
   int64_t blocks = cdiv(nvec, (int64_t)256 * unroll);
-  if (blocks > 16384) blocks = 16384;
   if (blocks < 1) blocks = 1;
-  *fixc = (blocks * 256) % vc == 0;
+  int g = vc, b = 256;  // blocks*256 % vc == 0  <=>  blocks % (vc / gcd(vc, 256)) == 0
+  while (b) { const int t = g % b; g = b; b = t; }
+  const int mult = vc / g;
+  blocks = cdiv(blocks, mult) * mult;
+  *fixc = (blocks * 256) % vc == 0 && blocks < (1 << 30);
   return (unsigned)blocks;
 }
 
