@@ -92,22 +92,9 @@ __global__ void __launch_bounds__((TPR > 256 ? TPR : 256)) loss_row_kernel(LossA
   const float* __restrict__ zr = a.z + row * cols;
   const float* __restrict__ pr = MODE ? a.zp[0] + row * cols : nullptr;
   float* __restrict__ outr = a.dz + row * cols;
-  int t;
-  const bool valid = row_target(a, row, t);
-  const int nvalid = a.meta[0];
-
-  if (!valid) {  // uniform over the group
-#pragma unroll
-    for (int i = 0; i < V; i++) {
-      int64_t c = ((int64_t)i * TPR + lane) * 4;
-      if (c < cols) *reinterpret_cast<float4*>(outr + c) = make_float4(0.f, 0.f, 0.f, 0.f);
-    }
-    if (lane == 0) { a.row_task[row] = 0.f; a.row_dist[row] = 0.f; }
-    return;
-  }
-
+  // The row's loads are issued before anything that depends on the target (whose own load would
+  // otherwise sit in front of them as a full memory latency).
   float4 x[V], y[V];
-  const float zt = zr[t];
 #pragma unroll
   for (int i = 0; i < V; i++) {
     int64_t c = ((int64_t)i * TPR + lane) * 4;
@@ -119,6 +106,19 @@ __global__ void __launch_bounds__((TPR > 256 ? TPR : 256)) loss_row_kernel(LossA
       if (MODE) y[i] = x[i];
     }
   }
+  int t;
+  const bool valid = row_target(a, row, t);
+  const int nvalid = a.meta[0];
+  if (!valid) {  // uniform over the group
+#pragma unroll
+    for (int i = 0; i < V; i++) {
+      int64_t c = ((int64_t)i * TPR + lane) * 4;
+      if (c < cols) *reinterpret_cast<float4*>(outr + c) = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    if (lane == 0) { a.row_task[row] = 0.f; a.row_dist[row] = 0.f; }
+    return;
+  }
+  const float zt = zr[t];
   // row maxima
   float mx[2] = {-INFINITY, -INFINITY};
 #pragma unroll
