@@ -431,7 +431,8 @@ extern "C" int codistill_forward(const cd_model* m, const void* params, const vo
             src = c.xpack();
             w = c.wpack();
           }
-          ProfScope pr(CD_K_CONV_FPROP, c.s, 2.0 * g.M() * g.Cout * g.K(), conv_bytes(m, g));
+          ProfScope pr(g.Cout > 64 ? CD_K_CONV_FPROP : CD_K_CONV_FPROP_NARROW, c.s, 2.0 * g.M() * g.Cout * g.K(),
+                       conv_bytes(m, g));
           ConvGeom gp = g;
           if (gp.Cin == 3) gp.Cin = 8;
           // a BatchNorm that follows directly gets its column sums from the convolution's epilogue
@@ -440,7 +441,7 @@ extern "C" int codistill_forward(const cd_model* m, const void* params, const vo
           stat_chunks = conv_fprop_mfma(src, w, static_cast<bf16_t*>(out), gp, fuse ? c.partials() : nullptr, c.s);
           stat_tensor = fuse ? o.y : -1;
         } else {
-          ProfScope pr(CD_K_CONV_FPROP, c.s, 2.0 * g.M() * g.Cout * g.K(), conv_bytes(m, g));
+          ProfScope pr(CD_K_CONV_FPROP_NARROW, c.s, 2.0 * g.M() * g.Cout * g.K(), conv_bytes(m, g));
           conv_fprop_simple(dt, in, c.P(o.pw), c.P(o.pb), out, g, o.relu, c.s);
         }
         break;
