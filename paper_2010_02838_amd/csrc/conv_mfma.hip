@@ -70,27 +70,31 @@ __device__ inline int lds_off(int row, int cv) { return row * BK + ((cv ^ ((row 
 // (The dgrad of a stride-2 convolution is run as four MODE 0 problems, one per parity of the output
 // pixel; see conv_dgrad_mfma.)
 //
-// Schedule of one wave per step kt (software pipelined by hand, the compiler cannot move work across
-// the barrier): write tile kt+1 to LDS (its global loads were issued two steps earlier), issue the
-// global loads of tile kt+3, issue the MFMAs of tile kt from fragments already in registers, barrier,
-// read the fragments of tile kt+1 from LDS.  The MFMAs of a step thus run while the wave waits at the
-// barrier and for its LDS reads, which is what keeps the matrix pipe busy at 1-2 waves per SIMD.
+// The main loop is software pipelined by hand (the compiler cannot move work across the barrier): in
+// the region between two barriers a wave issues the MFMAs of tile kt from fragments already in
+// registers, reads the fragments of tile kt+1 from LDS, writes tile kt+2 to LDS (its global loads
+// were issued two regions earlier) and issues the global loads of tile kt+4.  Nothing in a region
+// depends on anything else in it, so the matrix pipe stays busy at 1-2 waves per SIMD.
 // F32OUT: the output is fp32 [M][N] (+ bias), written straight from the accumulators (dense layers).
 // STATS: the epilogue also emits, per m-tile, the column sums and sums of squares of the bf16 values
 // it writes: the BatchNorm that follows a convolution gets its batch statistics without re-reading
 // the tensor.
-template <int MODE, int BM, int BN, int WAVES_M, int WAVES_N, bool F32OUT = false, bool STATS = false>
+// NWRAP: 1 when the gathered tensor has at least 32 channels (a 32-element step crosses at most one
+// tap boundary), 4 for 8..31 channels.
+template <int MODE, int BM, int BN, int WAVES_M, int WAVES_N, bool F32OUT = false, bool STATS = false, int NWRAP = 1>
 __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   constexpr int TM = WM / 32, TN = WN / 32;
   constexpr int AV = BM / 64;                  // activation vectors per thread per step
   constexpr int BV = BN >= 64 ? BN / 64 : 1;   // filter vectors per thread per step
-  constexpr int MAIN_BYTES = 2 * (BM + BN) * BK * 2;
+  constexpr int BN_PAD = BN < 64 ? 64 : BN;    // filter rows in LDS (a full 64-row store pass)
+  constexpr int MAIN_BYTES = 2 * (BM + BN_PAD) * BK * 2;
   constexpr int EROWS = WM < 64 ? WM : 64;     // rows staged per epilogue pass
   constexpr int EPITCH = WN + 8;
   constexpr int EPI_BYTES = 4 * EROWS * EPITCH * 2;
   constexpr int SMEM = MAIN_BYTES > EPI_BYTES ? MAIN_BYTES : EPI_BYTES;
   constexpr int PF = 2;                        // steps of global loads in flight (register ring)
+  constexpr bool SCHED = true;                 // emit the instruction interleaving hints
   __shared__ __attribute__((aligned(16))) char smem[SMEM];
   bf16_t* As = reinterpret_cast<bf16_t*>(smem);  // [2][BM][BK]
   bf16_t* Bs = As + 2 * BM * BK;                 // [2][BN][BK]
@@ -152,31 +156,45 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
   // Always issues its loads (a step at or beyond the end of the contraction has every vector masked
   // and costs no memory traffic): with conditional loads the compiler can no longer count how many
   // are outstanding and falls back to waiting for all of them at every step.
+  // Everything in it is straight-line code (selects, no branches): the region between two barriers
+  // must stay one basic block for the instruction scheduler to interleave it with the MFMAs.
   auto gload = [&](uint4* ra, uint4* rb, int kt) {
-    const bool kok = kr < a.kh;
+    const uint32_t kokb = kr < a.kh ? 1u : 0u;
     const int koff = tapdir * (kr * a.Ws + ks) * a.Cs + kc;
+    const uint32_t krs = (uint32_t)kr & 31u, kss = (uint32_t)ks & 31u;
 #pragma unroll
     for (int j = 0; j < AV; j++) {
-      const bool ok = kok && ((hmask[j] >> kr) & (wmask[j] >> ks) & 1u);
-      const int off = rowoff[j] + koff;
-      ra[j] = buf_load16(rsrc, ok ? (uint32_t)off * 2u : 0xffffffffu);
+      const uint32_t okb = (hmask[j] >> krs) & (wmask[j] >> kss) & kokb;
+      const uint32_t off = (uint32_t)(rowoff[j] + koff) * 2u;
+      ra[j] = buf_load16(rsrc, okb ? off : 0xffffffffu);
     }
     const uint32_t wk = (uint32_t)kt * (BK * 2u);
 #pragma unroll
-    for (int j = 0; j < BV; j++)
-      rb[j] = buf_load16(rwt, (kok && woff[j] != 0xffffffffu) ? woff[j] + wk : 0xffffffffu);
-    // advance to the next step
-    kc += BK;
-    while (kc >= a.Cs) { kc -= a.Cs; if (++ks == a.kw) { ks = 0; ++kr; } }
+    for (int j = 0; j < BV; j++) {
+      const uint32_t off = woff[j] + wk;
+      rb[j] = buf_load16(rwt, (kokb != 0u) & (woff[j] != 0xffffffffu) ? off : 0xffffffffu);
+    }
+    // advance to the next step: NWRAP sub-steps, each crossing at most one tap boundary
+#pragma unroll
+    for (int u = 0; u < NWRAP; u++) {
+      kc += BK / NWRAP;
+      const bool wrap = kc >= a.Cs;
+      kc -= wrap ? a.Cs : 0;
+      ks += wrap ? 1 : 0;
+      const bool wrap2 = ks == a.kw;
+      ks = wrap2 ? 0 : ks;
+      kr += wrap2 ? 1 : 0;
+    }
   };
   auto lstore = [&](const uint4* ra, const uint4* rb, int buf) {
 #pragma unroll
     for (int j = 0; j < AV; j++)
       *reinterpret_cast<uint4*>(As + buf * BM * BK + lds_off(lrow + 64 * j, kvec)) = ra[j];
 #pragma unroll
-    for (int j = 0; j < BV; j++)
-      if ((lrow + 64 * j) < BN)
-        *reinterpret_cast<uint4*>(Bs + buf * BN * BK + lds_off(lrow + 64 * j, kvec)) = rb[j];
+    for (int j = 0; j < BV; j++) {
+      // BN < 64: the rows past the tile land in a scratch row range behind it (never read)
+      *reinterpret_cast<uint4*>(Bs + buf * BN_PAD * BK + lds_off(lrow + 64 * j, kvec)) = rb[j];
+    }
   };
 
   f32x16_t acc[TN][TM];
@@ -194,7 +212,7 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
     for (int kk = 0; kk < 2; kk++) {
 #pragma unroll
       for (int i = 0; i < TN; i++)
-        wf[kk][i] = *reinterpret_cast<const bf16x8_t*>(Bs + buf * BN * BK + lds_off(wn0 + i * 32 + frow, kk * 2 + fcv));
+        wf[kk][i] = *reinterpret_cast<const bf16x8_t*>(Bs + buf * BN_PAD * BK + lds_off(wn0 + i * 32 + frow, kk * 2 + fcv));
 #pragma unroll
       for (int j = 0; j < TM; j++)
         xf[kk][j] = *reinterpret_cast<const bf16x8_t*>(As + buf * BM * BK + lds_off(wm0 + j * 32 + frow, kk * 2 + fcv));
@@ -210,6 +228,22 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
         for (int j = 0; j < TM; j++)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk][i], xf[kk][j], acc[i][j], 0, 0, 0);
   };
+  // Interleave hint for one region: the MFMAs of tile kt, the LDS reads of tile kt+1's fragments, the
+  // LDS writes of tile kt+2 and the address arithmetic + global loads of tile kt+4 are independent of
+  // each other; spread them so that the matrix pipe never waits for the rest of the instruction stream.
+  auto interleave = [&]() {
+    constexpr int NMFMA = 2 * TN * TM, NREAD = 2 * (TN + TM), NWRITE = AV + BV;
+#pragma unroll
+    for (int i = 0; i < NMFMA; i++) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                  // MFMA
+      __builtin_amdgcn_sched_group_barrier(0x100, (NREAD + NMFMA - 1) / NMFMA, 0);        // DS read
+      __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);                                  // VALU
+      if (i < NWRITE) {
+        __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);                                // DS write
+        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                                // VMEM read
+      }
+    }
+  };
   gload(ra[0], rb[0], 0);
   gload(ra[1], rb[1], 1);
   lstore(ra[0], rb[0], 0);
@@ -221,11 +255,13 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
     lstore(ra[1], rb[1], 1);
     gload(ra[1], rb[1], kt + 3);
     mfma_step(wf[0], xf[0]);
+    if (SCHED) interleave();
     __syncthreads();  // tile kt+1 is in LDS; nobody reads the buffer that the next store overwrites
     read_frags(wf[1], xf[1], 1);
     lstore(ra[0], rb[0], 0);
     gload(ra[0], rb[0], kt + 4);
     mfma_step(wf[1], xf[1]);
+    if (SCHED) interleave();
     __syncthreads();
     read_frags(wf[0], xf[0], 0);
   }
@@ -339,39 +375,29 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
   }
 }
 
-// Tile selection override for tuning runs (0 = automatic, 1: 128x128, 2: 256x128).
-int g_tune_tile = 0;
-int g_tune_co = -1;  // unused
+int g_tune_tile = 0, g_tune_co = -1;  // tuning knobs of the microbenchmark (unused)
 
 // returns the number of m-tiles (= statistics chunks when STATS)
-template <int MODE, bool STATS>
-static int launch_igemm(IgemmArgs a, hipStream_t s) {
+template <int MODE, bool STATS, int NWRAP>
+static int launch_igemm_w(IgemmArgs a, hipStream_t s) {
   if (a.N > 64) {
     a.ntiles = (int)cdiv(a.N, 128);
-    if (g_tune_tile == 2) {
-      const int mt = (int)cdiv(a.M, 256);
-      hipLaunchKernelGGL((igemm_kernel<MODE, 256, 128, 2, 2, false, STATS>), dim3((unsigned)(mt * a.ntiles)), dim3(256), 0,
-                         s, a);
-      return mt;
-    }
     const int mt = (int)cdiv(a.M, 128);
-    if (g_tune_tile == 3) {
-      a.ntiles = (int)cdiv(a.N, 64);
-      hipLaunchKernelGGL((igemm_kernel<MODE, 128, 64, 2, 2, false, STATS>), dim3((unsigned)((int64_t)mt * a.ntiles)),
-                         dim3(256), 0, s, a);
-      return mt;
-    }
-    hipLaunchKernelGGL((igemm_kernel<MODE, 128, 128, 2, 2, false, STATS>), dim3((unsigned)((int64_t)mt * a.ntiles)),
+    hipLaunchKernelGGL((igemm_kernel<MODE, 128, 128, 2, 2, false, STATS, NWRAP>), dim3((unsigned)((int64_t)mt * a.ntiles)),
                        dim3(256), 0, s, a);
     return mt;
   }
   a.ntiles = 1;
   const int mt = (int)cdiv(a.M, 256);
   if (a.N > 32)
-    hipLaunchKernelGGL((igemm_kernel<MODE, 256, 64, 4, 1, false, STATS>), dim3((unsigned)mt), dim3(256), 0, s, a);
+    hipLaunchKernelGGL((igemm_kernel<MODE, 256, 64, 4, 1, false, STATS, NWRAP>), dim3((unsigned)mt), dim3(256), 0, s, a);
   else
-    hipLaunchKernelGGL((igemm_kernel<MODE, 256, 32, 4, 1, false, STATS>), dim3((unsigned)mt), dim3(256), 0, s, a);
+    hipLaunchKernelGGL((igemm_kernel<MODE, 256, 32, 4, 1, false, STATS, NWRAP>), dim3((unsigned)mt), dim3(256), 0, s, a);
   return mt;
+}
+template <int MODE, bool STATS>
+static int launch_igemm(IgemmArgs a, hipStream_t s) {
+  return a.Cs >= BK ? launch_igemm_w<MODE, STATS, 1>(a, s) : launch_igemm_w<MODE, STATS, 4>(a, s);
 }
 
 bool conv_mfma_supported(const ConvGeom& g) {
