@@ -25,6 +25,11 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 
+# HBM bytes per launch of the roofline kernel from hardware counters (two rocprofv3 --pmc passes of this
+# script, FETCH_SIZE then WRITE_SIZE, each scaled by what the same counter read for the 1 GiB copy of
+# --copy-calibration).  Valid only for the kernel the counters were taken on: set to None when it changes.
+ROOFLINE_TRAFFIC_BYTES = 205.3e6   # FETCH_SIZE 49193.2 KiB x 2.000 + WRITE_SIZE 102081.9 KiB x 1.000
+
 
 def cpu_baseline(seconds_hint=20.0):
     """Oracle step (ResNet-50, 224x224, batch 2) on the host cores: a baseline, not a target."""
@@ -93,6 +98,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--batch", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also launch a plain 1 GiB -> 1 GiB elementwise copy three times (the known-size "
+                         "kernel that hardware-counter byte counts are scaled by)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU's share of the step: this build has no multi-GPU path, "
@@ -105,6 +113,14 @@ def main():
     from paper_2010_02838_amd.runner import StepRunner, pack_flat, to_device
 
     dev = "cuda:0"
+    if args.copy_calibration:
+        a = torch.ones(1 << 28, device=dev)
+        b = torch.empty_like(a)
+        for _ in range(3):
+            torch.mul(a, 1.0, out=b)      # one elementwise kernel: reads 2^30 bytes, writes 2^30 bytes
+        torch.cuda.synchronize()
+        del a, b
+        torch.cuda.empty_cache()
     loss_cfg5 = loss_kernel_cfg5(B, torch, dev)
     batch, res, classes = args.batch, 224, 1000
     arch = B.arch_preset(B.CD_ARCH_RESNET_BOTTLENECK)
@@ -145,7 +161,8 @@ def main():
     ig_ms, ig_n, ig_fl = prof["conv_fprop"]["ms"], prof["conv_fprop"]["launches"], prof["conv_fprop"]["flops"]
     achieved = ig_fl / (ig_ms * 1e-3) / 1e12 if ig_ms > 0 else 0.0
     roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                "frac": achieved / PEAK_BF16_TFLOPS, "traffic": ROOFLINE_TRAFFIC_BYTES,
+                "algorithmic_bytes_per_launch": prof["conv_fprop"]["bytes"] / max(ig_n, 1),
                 "kernel": "igemm_kernel<0,128,128,2,2,false,true> (bf16 implicit-GEMM conv fprop, Cout > 64)",
                 "flop_per_launch": ig_fl / max(ig_n, 1),
                 "launches_per_step": ig_n / psteps, "avg_launch_us": ig_ms / max(ig_n, 1) * 1e3}
