@@ -37,8 +37,12 @@ __host__ __device__ static inline float bf16_to_f32(bf16_t v) {
   c.u = static_cast<uint32_t>(v) << 16;
   return c.f;
 }
-// round to nearest even; NaN stays NaN
+// round to nearest even; NaN stays NaN.  Device code uses the gfx950 conversion instruction
+// (v_cvt_pk_bf16_f32: the same rounding), host code the integer formula.
 __host__ __device__ static inline bf16_t f32_to_bf16(float f) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  return __builtin_bit_cast(bf16_t, static_cast<__bf16>(f));
+#endif
   union { uint32_t u; float f; } c;
   c.f = f;
   if ((c.u & 0x7fffffffu) > 0x7f800000u) return static_cast<bf16_t>((c.u >> 16) | 0x40);

@@ -45,8 +45,12 @@ __device__ inline unsigned xcd_remap(unsigned bid, unsigned nblocks) {
   return xcd * per + (xcd < rem ? xcd : rem) + idx;
 }
 
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+// two floats -> two bf16 (round to nearest even) in one instruction
 __device__ inline uint32_t pack_bf16x2(float a, float b) {
-  return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
+  const f32x2_t v = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
 // 16-byte load through a raw buffer descriptor: an offset at or beyond the buffer size returns
@@ -102,8 +106,10 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm0 = (wave % WAVES_M) * WM, wn0 = (wave / WAVES_M) * WN;
   const unsigned tile = xcd_remap(blockIdx.x, gridDim.x);
-  const int64_t m0 = (int64_t)(tile / a.ntiles) * BM;
-  const int n0 = (int)(tile % a.ntiles) * BN;
+  // row and element indices fit 32 bits: every operand is smaller than 2 GiB (conv_mfma_supported)
+  const int m0 = (int)(tile / (unsigned)a.ntiles) * BM;
+  const int n0 = (int)(tile % (unsigned)a.ntiles) * BN;
+  const int M = (int)a.M;
   const __amdgpu_buffer_rsrc_t rsrc = make_rsrc(a.src, a.src_bytes);
   const __amdgpu_buffer_rsrc_t rwt = make_rsrc(a.wt, a.wt_bytes);
 
@@ -113,13 +119,13 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
   uint32_t hmask[AV], wmask[AV];  // bit r / s set: tap row r / column s reads inside the image
 #pragma unroll
   for (int j = 0; j < AV; j++) {
-    const int64_t m = m0 + lrow + 64 * j;
-    const bool rowok = m < a.M;
-    const int64_t mm = rowok ? m : 0;
-    const int wd = (int)(mm % a.Wd);
-    const int64_t q = mm / a.Wd;
-    const int hd = (int)(q % a.Hd);
-    const int b = (int)(q / a.Hd);
+    const int m = m0 + lrow + 64 * j;
+    const bool rowok = m < M;
+    const unsigned mm = rowok ? (unsigned)m : 0u;
+    const unsigned q = mm / (unsigned)a.Wd;
+    const int wd = (int)(mm - q * (unsigned)a.Wd);
+    const int b = (int)(q / (unsigned)a.Hd);
+    const int hd = (int)(q - (unsigned)b * (unsigned)a.Hd);
     const int hh = MODE == 0 ? hd * a.stride - a.pad : hd + a.pad;
     const int ww = MODE == 0 ? wd * a.stride - a.pad_w : wd + a.pad_w;
     uint32_t hm = 0, wm = 0;
@@ -274,11 +280,11 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
     for (int i = 0; i < TN; i++)
 #pragma unroll
       for (int j = 0; j < TM; j++) {
-        const int64_t m = m0 + wm0 + j * 32 + frow;
+        const int m = m0 + wm0 + j * 32 + frow;
 #pragma unroll
         for (int v = 0; v < 16; v++) {
           const int n = n0 + wn0 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-          if (m < a.M && n < a.N) dst[m * a.N + n] = acc[i][j][v] + (a.bias ? bf16_to_f32(a.bias[n]) : 0.f);
+          if (m < M && n < a.N) dst[(int64_t)m * a.N + n] = acc[i][j][v] + (a.bias ? bf16_to_f32(a.bias[n]) : 0.f);
         }
       }
     return;
@@ -292,9 +298,12 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
   float ssum[8], ssq[8];
 #pragma unroll
   for (int k = 0; k < 8; k++) { ssum[k] = 0.f; ssq[k] = 0.f; }
+  __syncthreads();  // the main loop's tiles are no longer read: the staging rows alias them
 #pragma unroll
   for (int g0 = 0; g0 < TM; g0 += TPG) {
-    __syncthreads();  // tiles (first pass) or the previous pass's staging rows are no longer read
+    // The staging rows belong to this wave alone, and a wave's LDS accesses execute in program order:
+    // no block barrier between its writes, its reads and the next pass's writes.
+    __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int i = 0; i < TN; i++)
 #pragma unroll
@@ -306,19 +315,20 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
           p.y = pack_bf16x2(acc[i][g0 + j][4 * g + 2], acc[i][g0 + j][4 * g + 3]);
           *reinterpret_cast<uint2*>(stage + (j * 32 + frow) * EPITCH + i * 32 + 8 * g + 4 * (lane >> 5)) = p;
         }
-    __syncthreads();
+    __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int p = 0; p < EROWS / RPP; p++) {
       const int row = p * RPP + er;
-      int64_t m = m0 + wm0 + g0 * 32 + row;
+      int m = m0 + wm0 + g0 * 32 + row;
       const int n = n0 + wn0 + ec;
-      if (m < a.M && n < a.N) {
+      if (m < M && n < a.N) {
         uint4 v = *reinterpret_cast<const uint4*>(stage + row * EPITCH + ec);
         if (a.omul) {  // strided placement of the rows (parity class of a stride-2 dgrad)
-          const int wd = (int)(m % a.Wd);
-          const int64_t q = m / a.Wd;
-          const int hd = (int)(q % a.Hd);
-          m = ((q / a.Hd) * a.Ho + hd * a.omul + a.ooff_h) * a.Wo + wd * a.omul + a.ooff_w;
+          const unsigned q = (unsigned)m / (unsigned)a.Wd;
+          const int wd = m - (int)(q * (unsigned)a.Wd);
+          const int b = (int)(q / (unsigned)a.Hd);
+          const int hd = (int)q - b * a.Hd;
+          m = (b * a.Ho + hd * a.omul + a.ooff_h) * a.Wo + wd * a.omul + a.ooff_w;
         }
         if (STATS) {
           const uint32_t u[4] = {v.x, v.y, v.z, v.w};
@@ -329,7 +339,7 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
             ssum[2 * q + 1] += f1; ssq[2 * q + 1] += f1 * f1;
           }
         }
-        bf16_t* dp = a.dst + m * a.N + n;
+        bf16_t* dp = a.dst + ((unsigned)m * (unsigned)a.N + (unsigned)n);
         if (a.accumulate) {
           const uint4 o = *reinterpret_cast<const uint4*>(dp);
           const uint32_t vv[4] = {v.x, v.y, v.z, v.w}, oo[4] = {o.x, o.y, o.z, o.w};
@@ -368,7 +378,7 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
       float s0 = 0.f, s1 = 0.f;
 #pragma unroll
       for (int w = 0; w < WAVES_M; w++) { s0 += red[(w * 2 + 0) * BN + tid]; s1 += red[(w * 2 + 1) * BN + tid]; }
-      const int64_t mt = tile / a.ntiles;
+      const int64_t mt = tile / (unsigned)a.ntiles;
       a.stat_partials[(mt * 2 + 0) * a.N + n0 + tid] = s0;
       a.stat_partials[(mt * 2 + 1) * a.N + n0 + tid] = s1;
     }
@@ -559,52 +569,67 @@ __global__ void __launch_bounds__(256) wgrad_kernel(WgradArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wn0 = (wave & 1) * WNT, wk0 = (wave >> 1) * WKT;
   const int n0 = (blockIdx.x / a.ktiles) * BN, k0 = (blockIdx.x % a.ktiles) * BKK;
-  const int64_t mbeg = (int64_t)blockIdx.y * a.m_per_split;
-  const int64_t mend = mbeg + a.m_per_split < a.M ? mbeg + a.m_per_split : a.M;
+  // pixel and element indices fit 32 bits: every operand is smaller than 2 GiB (conv_mfma_supported)
+  const int M = (int)a.M;
+  const int mbeg = (int)blockIdx.y * (int)a.m_per_split;
+  const int mend = mbeg + (int)a.m_per_split < M ? mbeg + (int)a.m_per_split : M;
   const __amdgpu_buffer_rsrc_t rx_src = make_rsrc(a.x, a.x_bytes);
   const __amdgpu_buffer_rsrc_t rdy = make_rsrc(a.dy, a.dy_bytes);
 
-  // dy loader: fixed channel vector, DV rows
+  // dy loader: fixed channel vector, DV rows; doff = byte offset of (row, channel vector) at step 0
   const int dnv = tid % NVR, drow = tid / NVR;
   const bool dnok = n0 + dnv * 8 < a.N;
+  int dm[DV];
+  uint32_t doff[DV];
+#pragma unroll
+  for (int j = 0; j < DV; j++) {
+    dm[j] = mbeg + drow + DROWS * j;
+    doff[j] = ((uint32_t)dm[j] * (uint32_t)a.N + (uint32_t)(n0 + dnv * 8)) * 2u;
+  }
+  const uint32_t dstep = (uint32_t)WG_MS * (uint32_t)a.N * 2u;
   // x loader: fixed (tap, channel) vector, XV rows, pixel coordinates advanced incrementally
   const int xkv = tid % KVR, xrow = tid / KVR;
   const int k = k0 + xkv * 8;
   const bool kok = k < a.K;
   const int tap = kok ? k / a.Cin : 0;
   const int kc = k - tap * a.Cin, kr = tap / a.kw, ks = tap - (tap / a.kw) * a.kw;
-  int pb[XV], ph[XV], pw[XV];
+  int xm[XV], pb[XV], ph[XV], pw[XV];
 #pragma unroll
   for (int j = 0; j < XV; j++) {
-    const int64_t m = mbeg + xrow + XROWS * j;
-    pw[j] = (int)(m % a.Wo);
-    const int64_t q = m / a.Wo;
-    ph[j] = (int)(q % a.Ho);
-    pb[j] = (int)(q / a.Ho);
+    const unsigned m = (unsigned)(mbeg + xrow + XROWS * j);
+    const unsigned q = m / (unsigned)a.Wo;
+    xm[j] = (int)m;
+    pw[j] = (int)(m - q * (unsigned)a.Wo);
+    pb[j] = (int)(q / (unsigned)a.Ho);
+    ph[j] = (int)(q - (unsigned)pb[j] * (unsigned)a.Ho);
   }
+  // one step moves every row WG_MS pixels on: whole images, then whole rows, then columns
+  const int adv_b = WG_MS / (a.Ho * a.Wo), adv_r = WG_MS % (a.Ho * a.Wo);
+  const int adv_h = adv_r / a.Wo, adv_w = adv_r % a.Wo;
 
   // Loads are unconditional (masked vectors read nothing) so that the compiler can count the loads in
-  // flight; see igemm_kernel.
+  // flight, and the address update is straight-line code (selects, no loops); see igemm_kernel.
   uint4 rd[2][DV], rx[2][XV];
-  auto gload = [&](uint4* rd, uint4* rx, int64_t st) {
-    const int64_t ms = mbeg + st * WG_MS;
+  auto gload = [&](uint4* rd, uint4* rx) {
 #pragma unroll
     for (int j = 0; j < DV; j++) {
-      const int64_t m = ms + drow + DROWS * j;
-      rd[j] = buf_load16(rdy, (dnok && m < mend) ? (uint32_t)(m * a.N + n0 + dnv * 8) * 2u : 0xffffffffu);
+      rd[j] = buf_load16(rdy, (dnok && dm[j] < mend) ? doff[j] : 0xffffffffu);
+      dm[j] += WG_MS;
+      doff[j] += dstep;
     }
 #pragma unroll
     for (int j = 0; j < XV; j++) {
-      const int64_t m = ms + xrow + XROWS * j;
       const int hi = ph[j] * a.stride - a.pad + kr, wi = pw[j] * a.stride - a.pad + ks;
-      const bool ok = kok && m < mend && hi >= 0 && hi < a.H && wi >= 0 && wi < a.W;
+      const bool ok = kok && xm[j] < mend && (unsigned)hi < (unsigned)a.H && (unsigned)wi < (unsigned)a.W;
       rx[j] = buf_load16(rx_src, ok ? (uint32_t)(((pb[j] * a.H + hi) * a.W + wi) * a.Cin + kc) * 2u : 0xffffffffu);
-      // next step: WG_MS pixels further
-      pw[j] += WG_MS;
-      while (pw[j] >= a.Wo) {
-        pw[j] -= a.Wo;
-        if (++ph[j] == a.Ho) { ph[j] = 0; ++pb[j]; }
-      }
+      xm[j] += WG_MS;
+      pw[j] += adv_w;
+      const int cw = pw[j] >= a.Wo ? 1 : 0;
+      pw[j] -= cw ? a.Wo : 0;
+      ph[j] += adv_h + cw;
+      const int ch = ph[j] >= a.Ho ? 1 : 0;
+      ph[j] -= ch ? a.Ho : 0;
+      pb[j] += adv_b + ch;
     }
   };
   auto lstore = [&](const uint4* rd, const uint4* rx, int buf) {
@@ -661,27 +686,42 @@ __global__ void __launch_bounds__(256) wgrad_kernel(WgradArgs a) {
 
   // same software pipeline as igemm_kernel: store tile st+1, load tile st+3, MFMAs of tile st, barrier,
   // fragments of tile st+1
-  const int64_t steps = (mend - mbeg + WG_MS - 1) / WG_MS;
-  gload(rd[0], rx[0], 0);
-  gload(rd[1], rx[1], 1);
+  auto interleave = [&]() {
+    constexpr int NMFMA = 2 * TN * TK, NREAD = 4 * (TN + TK), NWRITE = DV + XV;
+#pragma unroll
+    for (int i = 0; i < NMFMA; i++) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                  // MFMA
+      __builtin_amdgcn_sched_group_barrier(0x100, (NREAD + NMFMA - 1) / NMFMA, 0);        // DS read
+      __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);                                  // VALU
+      if (i < NWRITE) {
+        __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);                                // DS write
+        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                                // VMEM read
+      }
+    }
+  };
+  const int steps = (mend - mbeg + WG_MS - 1) / WG_MS;
+  gload(rd[0], rx[0]);
+  gload(rd[1], rx[1]);
   lstore(rd[0], rx[0], 0);
-  gload(rd[0], rx[0], 2);
+  gload(rd[0], rx[0]);
   __syncthreads();
   read_frags(df[0], xf[0], 0);
-  for (int64_t st = 0; st < steps; st += 2) {
+  for (int st = 0; st < steps; st += 2) {
     lstore(rd[1], rx[1], 1);
-    gload(rd[1], rx[1], st + 3);
+    gload(rd[1], rx[1]);
     mfma_step(df[0], xf[0]);
+    interleave();
     __syncthreads();
     read_frags(df[1], xf[1], 1);
     lstore(rd[0], rx[0], 0);
-    gload(rd[0], rx[0], st + 4);
+    gload(rd[0], rx[0]);
     mfma_step(df[1], xf[1]);
+    interleave();
     __syncthreads();
     read_frags(df[0], xf[0], 0);
   }
 
-  float* out = a.out + (int64_t)blockIdx.y * a.N * a.K;
+  float* out = a.out + (int64_t)blockIdx.y * a.N * a.K;   // N*K*4 bytes < 2^33: 32-bit element offsets inside
 #pragma unroll
   for (int i = 0; i < TN; i++)
 #pragma unroll
@@ -690,7 +730,7 @@ __global__ void __launch_bounds__(256) wgrad_kernel(WgradArgs a) {
 #pragma unroll
       for (int v = 0; v < 16; v++) {
         const int n = n0 + wn0 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        if (n < a.N && kk < a.K) out[(int64_t)n * a.K + kk] = acc[i][j][v];
+        if (n < a.N && kk < a.K) out[(uint32_t)n * (uint32_t)a.K + (uint32_t)kk] = acc[i][j][v];
       }
     }
 }
