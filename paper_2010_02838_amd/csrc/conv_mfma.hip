@@ -31,11 +31,14 @@ struct IgemmArgs {
   // output row m = (b, hd, wd) is written to row (b*Ho + hd*omul + ooff_h)*Wo + wd*omul + ooff_w of dst
   int omul, ooff_h, ooff_w, Ho, Wo;
   int accumulate;
+  int pointwise;  // kh = kw = 1, stride 1, no padding (set by the launcher)
   int ntiles;
   uint32_t src_bytes, wt_bytes;
   const bf16_t* bias;  // F32OUT kernels: per-column bias added to the fp32 output (nullable)
   float* stat_partials;  // STATS kernels: [m-tiles][2][N] per-tile column sums and sums of squares
 };
+
+int g_tune_tile = 0, g_tune_co = -1;  // tuning knobs of the microbenchmark
 
 // Blocks are handed to the 8 XCDs round-robin; renumber so that consecutive logical tiles (which
 // share activation rows and halos) run on the same XCD and meet in its L2.
@@ -85,7 +88,9 @@ __device__ inline int lds_off(int row, int cv) { return row * BK + ((cv ^ ((row 
 // the tensor.
 // NWRAP: 1 when the gathered tensor has at least 32 channels (a 32-element step crosses at most one
 // tap boundary), 4 for 8..31 channels.
-template <int MODE, int BM, int BN, int WAVES_M, int WAVES_N, bool F32OUT = false, bool STATS = false, int NWRAP = 1>
+// REMAP: output rows are placed with the strided row map of IgemmArgs (parity class of a stride-2 dgrad).
+template <int MODE, int BM, int BN, int WAVES_M, int WAVES_N, bool F32OUT = false, bool STATS = false, int NWRAP = 1,
+          bool REMAP = false>
 __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   constexpr int TM = WM / 32, TN = WN / 32;
@@ -121,6 +126,12 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
   for (int j = 0; j < AV; j++) {
     const int m = m0 + lrow + 64 * j;
     const bool rowok = m < M;
+    if (a.pointwise) {  // 1x1 filter, stride 1, no padding: row m of the gathered tensor, every tap inside
+      hmask[j] = rowok ? 1u : 0u;
+      wmask[j] = 1u;
+      rowoff[j] = m * a.Cs;
+      continue;
+    }
     const unsigned mm = rowok ? (unsigned)m : 0u;
     const unsigned q = mm / (unsigned)a.Wd;
     const int wd = (int)(mm - q * (unsigned)a.Wd);
@@ -323,7 +334,7 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
       const int n = n0 + wn0 + ec;
       if (m < M && n < a.N) {
         uint4 v = *reinterpret_cast<const uint4*>(stage + row * EPITCH + ec);
-        if (a.omul) {  // strided placement of the rows (parity class of a stride-2 dgrad)
+        if (REMAP) {  // strided placement of the rows (parity class of a stride-2 dgrad)
           const unsigned q = (unsigned)m / (unsigned)a.Wd;
           const int wd = m - (int)(q * (unsigned)a.Wd);
           const int b = (int)(q / (unsigned)a.Hd);
@@ -385,29 +396,31 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
   }
 }
 
-int g_tune_tile = 0, g_tune_co = -1;  // tuning knobs of the microbenchmark (unused)
-
 // returns the number of m-tiles (= statistics chunks when STATS)
-template <int MODE, bool STATS, int NWRAP>
+template <int MODE, bool STATS, int NWRAP, bool REMAP>
 static int launch_igemm_w(IgemmArgs a, hipStream_t s) {
-  if (a.N > 64) {
+  a.pointwise = (a.kh == 1 && a.kw == 1 && a.stride == 1 && a.pad == 0 && a.pad_w == 0 && a.Hs == a.Hd &&
+                 a.Ws == a.Wd) ? 1 : 0;
+  if (a.N > 64 && g_tune_tile != 1) {
     a.ntiles = (int)cdiv(a.N, 128);
     const int mt = (int)cdiv(a.M, 128);
-    hipLaunchKernelGGL((igemm_kernel<MODE, 128, 128, 2, 2, false, STATS, NWRAP>), dim3((unsigned)((int64_t)mt * a.ntiles)),
-                       dim3(256), 0, s, a);
+    hipLaunchKernelGGL((igemm_kernel<MODE, 128, 128, 2, 2, false, STATS, NWRAP, REMAP>),
+                       dim3((unsigned)((int64_t)mt * a.ntiles)), dim3(256), 0, s, a);
     return mt;
   }
-  a.ntiles = 1;
+  a.ntiles = (int)cdiv(a.N, 64);
   const int mt = (int)cdiv(a.M, 256);
   if (a.N > 32)
-    hipLaunchKernelGGL((igemm_kernel<MODE, 256, 64, 4, 1, false, STATS, NWRAP>), dim3((unsigned)mt), dim3(256), 0, s, a);
+    hipLaunchKernelGGL((igemm_kernel<MODE, 256, 64, 4, 1, false, STATS, NWRAP, REMAP>),
+                       dim3((unsigned)((int64_t)mt * a.ntiles)), dim3(256), 0, s, a);
   else
-    hipLaunchKernelGGL((igemm_kernel<MODE, 256, 32, 4, 1, false, STATS, NWRAP>), dim3((unsigned)mt), dim3(256), 0, s, a);
+    hipLaunchKernelGGL((igemm_kernel<MODE, 256, 32, 4, 1, false, STATS, NWRAP, REMAP>), dim3((unsigned)mt), dim3(256), 0,
+                       s, a);
   return mt;
 }
-template <int MODE, bool STATS>
+template <int MODE, bool STATS, bool REMAP = false>
 static int launch_igemm(IgemmArgs a, hipStream_t s) {
-  return a.Cs >= BK ? launch_igemm_w<MODE, STATS, 1>(a, s) : launch_igemm_w<MODE, STATS, 4>(a, s);
+  return a.Cs >= BK ? launch_igemm_w<MODE, STATS, 1, REMAP>(a, s) : launch_igemm_w<MODE, STATS, 4, REMAP>(a, s);
 }
 
 bool conv_mfma_supported(const ConvGeom& g) {
@@ -426,6 +439,7 @@ void linear_fwd_mfma(const bf16_t* x, const bf16_t* w, const bf16_t* bias, float
   a.Hs = 1; a.Ws = 1; a.Cs = F; a.Hd = 1; a.Wd = 1; a.kh = 1; a.kw = 1; a.stride = 1; a.pad = 0; a.pad_w = 0;
   a.omul = 0; a.ooff_h = a.ooff_w = 0; a.Ho = a.Wo = 1;
   a.accumulate = 0;
+  a.pointwise = 1;
   a.src_bytes = (uint32_t)(B * (int64_t)F * 2);
   a.wt_bytes = (uint32_t)((int64_t)C * F * 2);
   a.ntiles = (int)cdiv(C, 128);
@@ -526,7 +540,7 @@ void conv_dgrad_mfma(const bf16_t* dy, const bf16_t* w, bf16_t* wt, bf16_t* dx, 
       a.omul = 2; a.ooff_h = ph; a.ooff_w = pw;
       a.accumulate = accumulate ? 1 : 0;
       a.wt_bytes = (uint32_t)(wn * 2);
-      launch_igemm<0, false>(a, s);
+      launch_igemm<0, false, true>(a, s);
     }
 }
 
