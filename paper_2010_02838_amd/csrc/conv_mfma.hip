@@ -16,6 +16,7 @@
 
 namespace cd {
 
+#define CD_LDS __attribute__((address_space(3)))
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 
@@ -67,6 +68,34 @@ __device__ inline uint4 buf_load16(__amdgpu_buffer_rsrc_t r, uint32_t byte_off) 
   return make_uint4((uint32_t)v.x, (uint32_t)v.y, (uint32_t)v.z, (uint32_t)v.w);
 }
 
+// 16 bytes per lane from a buffer straight into LDS: lane l of the wave writes its vector at
+// lds_addr + 16*l (lds_addr is uniform over the wave and travels in M0); an offset outside the
+// buffer writes zeros.  The compiler does not see these loads: the kernel waits for them itself
+// (wait_vmem) before a barrier publishes the tile.
+typedef int rsrc_words_t __attribute__((ext_vector_type(4)));
+// the four descriptor words of a raw buffer (stride 0): base address, size in bytes, data format
+__device__ inline rsrc_words_t make_rsrc_words(const void* p, uint32_t bytes) {
+  const uint64_t b = reinterpret_cast<uint64_t>(p);
+  rsrc_words_t w;
+  w.x = (int)(uint32_t)b;
+  w.y = (int)((uint32_t)(b >> 32) & 0xffffu);
+  w.z = (int)bytes;
+  w.w = 0x00020000;
+  return w;
+}
+__device__ inline void load_lds16(rsrc_words_t w, uint32_t lds_addr, uint32_t byte_off) {
+  asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+               :
+               : "s"(lds_addr), "v"(byte_off), "s"(w)
+               : "memory", "m0");
+}
+// wait until at most N of this wave's vector memory loads are outstanding
+template <int N>
+__device__ inline void wait_vmem() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
+
 // LDS tiles are [row][32 elements] = 64-byte rows without padding; the 16-byte column cv of a row
 // is stored at column cv ^ ((row >> 2) & 3), which makes both the 16-byte stores (4 lanes per row)
 // and the MFMA fragment reads (16 consecutive rows, one column) bank-conflict free.
@@ -97,16 +126,15 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
   constexpr int AV = BM / 64;                  // activation vectors per thread per step
   constexpr int BV = BN >= 64 ? BN / 64 : 1;   // filter vectors per thread per step
   constexpr int BN_PAD = BN < 64 ? 64 : BN;    // filter rows in LDS (a full 64-row store pass)
-  constexpr int MAIN_BYTES = 2 * (BM + BN_PAD) * BK * 2;
+  constexpr int NS = 3;                        // LDS stages: tile kt multiplies, kt+1 and kt+2 are in flight
+  constexpr int STAGE = (BM + BN_PAD) * BK;    // elements per stage: activation rows, then filter rows
+  constexpr int MAIN_BYTES = NS * STAGE * 2;
   constexpr int EROWS = WM < 64 ? WM : 64;     // rows staged per epilogue pass
   constexpr int EPITCH = WN + 8;
   constexpr int EPI_BYTES = 4 * EROWS * EPITCH * 2;
   constexpr int SMEM = MAIN_BYTES > EPI_BYTES ? MAIN_BYTES : EPI_BYTES;
-  constexpr int PF = 2;                        // steps of global loads in flight (register ring)
-  constexpr bool SCHED = true;                 // emit the instruction interleaving hints
   __shared__ __attribute__((aligned(16))) char smem[SMEM];
-  bf16_t* As = reinterpret_cast<bf16_t*>(smem);  // [2][BM][BK]
-  bf16_t* Bs = As + 2 * BM * BK;                 // [2][BN][BK]
+  bf16_t* tiles = reinterpret_cast<bf16_t*>(smem);  // [NS][BM + BN_PAD][BK]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm0 = (wave % WAVES_M) * WM, wn0 = (wave / WAVES_M) * WN;
@@ -115,11 +143,15 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
   const int m0 = (int)(tile / (unsigned)a.ntiles) * BM;
   const int n0 = (int)(tile % (unsigned)a.ntiles) * BN;
   const int M = (int)a.M;
-  const __amdgpu_buffer_rsrc_t rsrc = make_rsrc(a.src, a.src_bytes);
-  const __amdgpu_buffer_rsrc_t rwt = make_rsrc(a.wt, a.wt_bytes);
+  const rsrc_words_t rsrc = make_rsrc_words(a.src, a.src_bytes);
+  const rsrc_words_t rwt = make_rsrc_words(a.wt, a.wt_bytes);
 
   // ---- per-thread gather state ---------------------------------------------------------------------
-  const int kvec = tid & 3, lrow = tid >> 2;  // this thread's 16-byte column and first row in a tile
+  // A wave's load instruction fills 16 consecutive tile rows (64 lanes x 16 bytes, in lane order), so
+  // thread tid owns LDS slot tid & 3 of rows (tid >> 2) + 64 j; the slot holds the 16-byte column
+  // slot ^ ((row >> 2) & 3) of the tile (see lds_off), the same for all of the thread's rows.
+  const int lrow = tid >> 2;
+  const int kvec = (tid & 3) ^ ((tid >> 4) & 3);
   int rowoff[AV];                 // element offset of (image, h0, w0, channel 0); may be negative
   uint32_t hmask[AV], wmask[AV];  // bit r / s set: tap row r / column s reads inside the image
 #pragma unroll
@@ -169,13 +201,13 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
   const int KT = (a.K + BK - 1) / BK;
   const int tapdir = MODE == 0 ? 1 : -1;
 
-  uint4 ra[PF][AV], rb[PF][BV];
-  // Always issues its loads (a step at or beyond the end of the contraction has every vector masked
-  // and costs no memory traffic): with conditional loads the compiler can no longer count how many
-  // are outstanding and falls back to waiting for all of them at every step.
-  // Everything in it is straight-line code (selects, no branches): the region between two barriers
-  // must stay one basic block for the instruction scheduler to interleave it with the MFMAs.
-  auto gload = [&](uint4* ra, uint4* rb, int kt) {
+  // LDS byte address of this wave's first 16 rows of the stage-0 activation tile
+  const uint32_t lds_wave = (uint32_t)(uintptr_t)(CD_LDS char*)smem +
+                            (uint32_t)__builtin_amdgcn_readfirstlane(tid >> 6) * (16u * BK * 2u);
+  // Issues the loads of one step into the stage at byte offset stage_b.  Always issues them (a step at
+  // or beyond the end of the contraction has every vector masked, costs no memory traffic and writes
+  // zeros), so that the number of loads in flight is the same at every step, and is straight-line code.
+  auto gload = [&](uint32_t stage_b, int kt) {
     const uint32_t kokb = kr < a.kh ? 1u : 0u;
     const int koff = tapdir * (kr * a.Ws + ks) * a.Cs + kc;
     const uint32_t krs = (uint32_t)kr & 31u, kss = (uint32_t)ks & 31u;
@@ -183,13 +215,14 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
     for (int j = 0; j < AV; j++) {
       const uint32_t okb = (hmask[j] >> krs) & (wmask[j] >> kss) & kokb;
       const uint32_t off = (uint32_t)(rowoff[j] + koff) * 2u;
-      ra[j] = buf_load16(rsrc, okb ? off : 0xffffffffu);
+      load_lds16(rsrc, lds_wave + stage_b + (uint32_t)j * (64u * BK * 2u), okb ? off : 0xffffffffu);
     }
     const uint32_t wk = (uint32_t)kt * (BK * 2u);
 #pragma unroll
     for (int j = 0; j < BV; j++) {
       const uint32_t off = woff[j] + wk;
-      rb[j] = buf_load16(rwt, (kokb != 0u) & (woff[j] != 0xffffffffu) ? off : 0xffffffffu);
+      load_lds16(rwt, lds_wave + stage_b + (uint32_t)(BM + j * 64) * (BK * 2u),
+                 ((kokb != 0u) & (woff[j] != 0xffffffffu)) ? off : 0xffffffffu);
     }
     // advance to the next step: NWRAP sub-steps, each crossing at most one tap boundary
 #pragma unroll
@@ -203,16 +236,6 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
       kr += wrap2 ? 1 : 0;
     }
   };
-  auto lstore = [&](const uint4* ra, const uint4* rb, int buf) {
-#pragma unroll
-    for (int j = 0; j < AV; j++)
-      *reinterpret_cast<uint4*>(As + buf * BM * BK + lds_off(lrow + 64 * j, kvec)) = ra[j];
-#pragma unroll
-    for (int j = 0; j < BV; j++) {
-      // BN < 64: the rows past the tile land in a scratch row range behind it (never read)
-      *reinterpret_cast<uint4*>(Bs + buf * BN_PAD * BK + lds_off(lrow + 64 * j, kvec)) = rb[j];
-    }
-  };
 
   f32x16_t acc[TN][TM];
 #pragma unroll
@@ -223,20 +246,19 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
       for (int v = 0; v < 16; v++) acc[i][j][v] = 0.f;
 
   const int frow = lane & 31, fcv = lane >> 5;
-  bf16x8_t wf[2][2][TN], xf[2][2][TM];  // [fragment set][k16 half][tile]
-  auto read_frags = [&](bf16x8_t (&wf)[2][TN], bf16x8_t (&xf)[2][TM], int buf) {
+  bf16x8_t wf[2][TN], xf[2][TM];  // [k16 half][tile]
+  auto read_frags = [&](uint32_t stage_e) {
 #pragma unroll
     for (int kk = 0; kk < 2; kk++) {
 #pragma unroll
       for (int i = 0; i < TN; i++)
-        wf[kk][i] = *reinterpret_cast<const bf16x8_t*>(Bs + buf * BN_PAD * BK + lds_off(wn0 + i * 32 + frow, kk * 2 + fcv));
+        wf[kk][i] = *reinterpret_cast<const bf16x8_t*>(tiles + stage_e + BM * BK + lds_off(wn0 + i * 32 + frow, kk * 2 + fcv));
 #pragma unroll
       for (int j = 0; j < TM; j++)
-        xf[kk][j] = *reinterpret_cast<const bf16x8_t*>(As + buf * BM * BK + lds_off(wm0 + j * 32 + frow, kk * 2 + fcv));
+        xf[kk][j] = *reinterpret_cast<const bf16x8_t*>(tiles + stage_e + lds_off(wm0 + j * 32 + frow, kk * 2 + fcv));
     }
   };
-  static_assert(PF == 2, "the register ring and the fragment sets alternate with the parity of the step");
-  auto mfma_step = [&](const bf16x8_t (&wf)[2][TN], const bf16x8_t (&xf)[2][TM]) {
+  auto mfma_step = [&]() {
 #pragma unroll
     for (int kk = 0; kk < 2; kk++)
 #pragma unroll
@@ -245,43 +267,21 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
         for (int j = 0; j < TM; j++)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk][i], xf[kk][j], acc[i][j], 0, 0, 0);
   };
-  // Interleave hint for one region: the MFMAs of tile kt, the LDS reads of tile kt+1's fragments, the
-  // LDS writes of tile kt+2 and the address arithmetic + global loads of tile kt+4 are independent of
-  // each other; spread them so that the matrix pipe never waits for the rest of the instruction stream.
-  auto interleave = [&]() {
-    constexpr int NMFMA = 2 * TN * TM, NREAD = 2 * (TN + TM), NWRITE = AV + BV;
-#pragma unroll
-    for (int i = 0; i < NMFMA; i++) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                  // MFMA
-      __builtin_amdgcn_sched_group_barrier(0x100, (NREAD + NMFMA - 1) / NMFMA, 0);        // DS read
-      __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);                                  // VALU
-      if (i < NWRITE) {
-        __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);                                // DS write
-        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                                // VMEM read
-      }
-    }
-  };
-  gload(ra[0], rb[0], 0);
-  gload(ra[1], rb[1], 1);
-  lstore(ra[0], rb[0], 0);
-  gload(ra[0], rb[0], 2);
-  __syncthreads();
-  read_frags(wf[0], xf[0], 0);
-  // two steps per trip, no branches inside: an odd step count is rounded up with an all-zero tile
-  for (int kt = 0; kt < KT; kt += 2) {
-    lstore(ra[1], rb[1], 1);
-    gload(ra[1], rb[1], kt + 3);
-    mfma_step(wf[0], xf[0]);
-    if (SCHED) interleave();
-    __syncthreads();  // tile kt+1 is in LDS; nobody reads the buffer that the next store overwrites
-    read_frags(wf[1], xf[1], 1);
-    lstore(ra[0], rb[0], 0);
-    gload(ra[0], rb[0], kt + 4);
-    mfma_step(wf[1], xf[1]);
-    if (SCHED) interleave();
+  // Three stages rotate: at step kt the stage `cur` holds tile kt, `nxt` receives tile kt+1 (loads issued
+  // one step ago) and `fre` (read last at step kt-1) receives tile kt+2.  One barrier per step: it
+  // publishes tile kt (every wave has waited for its own loads of it) and retires the reads of tile kt-1.
+  uint32_t cur = 0, nxt = STAGE, fre = 2 * STAGE;  // element offsets
+  gload(cur * 2u, 0);
+  gload(nxt * 2u, 1);
+  for (int kt = 0; kt < KT; kt++) {
+    wait_vmem<AV + BV>();   // all but the newest step's loads have landed
     __syncthreads();
-    read_frags(wf[0], xf[0], 0);
+    gload(fre * 2u, kt + 2);
+    read_frags(cur);
+    mfma_step();
+    const uint32_t t = cur; cur = nxt; nxt = fre; fre = t;
   }
+  wait_vmem<0>();  // the masked loads past the end still write (zeros) into the stages the epilogue reuses
 
   // accumulator layout: lane holds pixel column (lane % 32); register v holds channel
   // 8*(v/4) + 4*(lane/32) + v%4 of the 32x32 tile
@@ -554,7 +554,6 @@ void conv_dgrad_mfma(const bf16_t* dy, const bf16_t* w, bf16_t* wt, bf16_t* dx, 
 // i, which is the MFMA operand layout.  The pixel range is split over blockIdx.y; partial sums are
 // written per split and added by a second kernel in a fixed order.
 typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
-#define CD_LDS __attribute__((address_space(3)))
 
 struct WgradArgs {
   const bf16_t* x;   // [B][H][W][Cin]
