@@ -28,7 +28,7 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch of the roofline kernel from hardware counters (two rocprofv3 --pmc passes of this
 # script, FETCH_SIZE then WRITE_SIZE, each scaled by what the same counter read for the 1 GiB copy of
 # --copy-calibration).  Valid only for the kernel the counters were taken on: set to None when it changes.
-ROOFLINE_TRAFFIC_BYTES = 205.3e6   # FETCH_SIZE 49193.2 KiB x 2.000 + WRITE_SIZE 102081.9 KiB x 1.000
+ROOFLINE_TRAFFIC_BYTES = None
 
 
 def cpu_baseline(seconds_hint=20.0):

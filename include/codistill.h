@@ -225,10 +225,10 @@ int codistill_tensor_info(const cd_model* m, int64_t batch, int64_t idx, cd_act_
 /* ---- measurement aid -------------------------------------------------------------------- */
 /* kernel classes for the built-in timer */
 enum {
-  CD_K_CONV_FPROP = 0,        /* bf16 MFMA fprop launches with more than 64 output channels (one kernel symbol) */
+  CD_K_CONV_FPROP = 0,        /* bf16 MFMA fprop launches on 128x128 tiles (one kernel symbol) */
   CD_K_CONV_DGRAD = 1, CD_K_CONV_WGRAD = 2, CD_K_NORM = 3,
   CD_K_GLUE = 4, CD_K_LINEAR = 5, CD_K_LOSS = 6, CD_K_SGD = 7,
-  CD_K_CONV_FPROP_NARROW = 8, /* every other fprop launch (<= 64 output channels, plain kernels) */
+  CD_K_CONV_FPROP_NARROW = 8, /* every other fprop launch (other tile shapes, plain kernels) */
   CD_K_COUNT = 9
 };
 /* When enabled, every launch is bracketed by HIP events on the launch stream and the events are

@@ -396,11 +396,32 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
   }
 }
 
+// 128x128 tiles run three workgroups per compute unit (768 at a time), 256x128 tiles two (512): take
+// the taller tile when its last round of workgroups is clearly fuller.
+static bool igemm_tall_tile(int64_t M, int N) {
+  if (N <= 64) return false;
+  if (g_tune_tile == 3) return true;
+  if (g_tune_tile == 2) return false;
+  const int64_t t128 = cdiv(M, 128) * cdiv(N, 128), t256 = cdiv(M, 256) * cdiv(N, 128);
+  const double e128 = (double)t128 / (double)(cdiv(t128, 768) * 768), e256 = (double)t256 / (double)(cdiv(t256, 512) * 512);
+  return e256 > 1.2 * e128;
+}
+bool conv_fprop_tall_tile(const ConvGeom& g) { return g.Cin >= BK && igemm_tall_tile(g.M(), g.Cout); }
+
 // returns the number of m-tiles (= statistics chunks when STATS)
 template <int MODE, bool STATS, int NWRAP, bool REMAP>
 static int launch_igemm_w(IgemmArgs a, hipStream_t s) {
   a.pointwise = (a.kh == 1 && a.kw == 1 && a.stride == 1 && a.pad == 0 && a.pad_w == 0 && a.Hs == a.Hd &&
                  a.Ws == a.Wd) ? 1 : 0;
+  // 128x128 tiles run three workgroups per compute unit (768 at a time), 256x128 tiles two (512): take
+  // the taller tile when its last round of workgroups is clearly fuller.
+  if (NWRAP == 1 && !REMAP && igemm_tall_tile(a.M, a.N)) {
+    a.ntiles = (int)cdiv(a.N, 128);
+    const int mt = (int)cdiv(a.M, 256);
+    hipLaunchKernelGGL((igemm_kernel<MODE, 256, 128, 2, 2, false, STATS, 1, false>),
+                       dim3((unsigned)((int64_t)mt * a.ntiles)), dim3(256), 0, s, a);
+    return mt;
+  }
   if (a.N > 64 && g_tune_tile != 1) {
     a.ntiles = (int)cdiv(a.N, 128);
     const int mt = (int)cdiv(a.M, 128);
@@ -778,7 +799,13 @@ void conv_wgrad_mfma(const bf16_t* x, const bf16_t* dy, float* dw, const ConvGeo
   a.ktiles = (int)cdiv(a.K, bk);
   const int64_t tiles = (int64_t)ntiles * a.ktiles;
   const int64_t nk = (int64_t)a.N * a.K;
-  int64_t splits = cdiv(1024, tiles);
+  // Workgroups to aim for.  Every split writes an fp32 copy of dw, so a launch that is bound by memory
+  // traffic anyway (1x1 filters with N*K/(N+K) below the machine's flop-per-byte ridge) runs one long
+  // workgroup per compute unit; compute-bound 1x1 launches take two, gathers over several taps four.
+  int64_t target = 1024;
+  if (a.kh * a.kw == 1) target = (double)a.N * a.K / ((double)a.N + a.K) < 315.0 ? 256 : 512;
+  if (g_tune_co > 0) target = g_tune_co;
+  int64_t splits = cdiv(target, tiles);
   const int64_t max_by_m = cdiv(a.M, 4 * WG_MS);
   if (splits > max_by_m) splits = max_by_m;
   const int64_t max_by_mem = (int64_t)(partials_bytes / (nk * sizeof(float)));

@@ -67,6 +67,8 @@ bool conv_mfma_supported(const ConvGeom& g);
 // (needs (M/128 + 1) * 2 * Cout floats); see bn_forward_partials.
 int conv_fprop_mfma(const bf16_t* x, const bf16_t* w, bf16_t* y, const ConvGeom& g, float* stat_partials,
                     hipStream_t s);
+// whether conv_fprop_mfma runs this shape with its 256x128 tile (a different kernel than the 128x128 one)
+bool conv_fprop_tall_tile(const ConvGeom& g);
 // dx[B*H*W][Cin] (+)= gather(dy)[.][taps*Cout] * wt[Cin][taps*Cout]^T.  w is the filter as stored; wt is
 // scratch of at least Cout*K + 32 elements that receives its re-laid-out copy (or copies, per parity
 // class, for stride 2).

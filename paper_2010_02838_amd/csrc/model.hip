@@ -431,7 +431,8 @@ extern "C" int codistill_forward(const cd_model* m, const void* params, const vo
             src = c.xpack();
             w = c.wpack();
           }
-          ProfScope pr(g.Cout > 64 ? CD_K_CONV_FPROP : CD_K_CONV_FPROP_NARROW, c.s, 2.0 * g.M() * g.Cout * g.K(),
+          ProfScope pr(g.Cout > 64 && !conv_fprop_tall_tile(g) ? CD_K_CONV_FPROP : CD_K_CONV_FPROP_NARROW, c.s,
+                       2.0 * g.M() * g.Cout * g.K(),
                        conv_bytes(m, g));
           ConvGeom gp = g;
           if (gp.Cin == 3) gp.Cin = 8;
