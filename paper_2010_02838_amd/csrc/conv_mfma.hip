@@ -87,7 +87,7 @@ __device__ inline void load_lds16(rsrc_words_t w, uint32_t lds_addr, uint32_t by
   asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                :
                : "s"(lds_addr), "v"(byte_off), "s"(w)
-               : "memory", "m0");
+               : "memory");  // M0 is reserved: the compiler keeps nothing in it, and nothing else here uses it
 }
 // wait until at most N of this wave's vector memory loads are outstanding
 template <int N>

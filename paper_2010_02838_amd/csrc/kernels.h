@@ -27,18 +27,21 @@ void colsum(int dtype, const void* a, int64_t M, int C, float* out, float* parti
 
 // BatchNorm with batch statistics over M rows of C channels, y = relu?(gamma*xhat + beta + res?).
 // stats: [4][C] fp32 = mean, invstd, scale, shift (kept for the backward pass).
+// relu_mask (nullable; bf16 with C % 8 == 0 only): M*C/8 bytes, bit k of byte i = (y[8i + k] > 0).  The
+// forward pass writes it, the backward pass reads it instead of y (an eighth of a byte per element
+// instead of two bytes, in both of its passes).
 void bn_forward(int dtype, const void* x, const void* gamma, const void* beta, const void* res, bool relu, void* y,
-                int64_t M, int C, float* stats, float* partials, hipStream_t s);
+                int64_t M, int C, float* stats, float* partials, uint8_t* relu_mask, hipStream_t s);
 // Same, with the column sums already in partials ([chunks][2][C], from the producing convolution);
 // scratch: room for 64 * C floats behind them.
 void bn_forward_partials(int dtype, const void* x, const void* gamma, const void* beta, const void* res, bool relu,
                          void* y, int64_t M, int C, float* stats, const float* partials, int chunks, float* scratch,
-                         hipStream_t s);
+                         uint8_t* relu_mask, hipStream_t s);
 // dz = dy * (relu ? y > 0 : 1); dgamma = sum dz*xhat; dbeta = sum dz;
 // dx = gamma*invstd*(dz - dbeta/M - xhat*dgamma/M); dres = dz.  coef: [3][C] fp32 scratch.
 void bn_backward(int dtype, const void* dy, const void* y, const void* x, const void* gamma, const float* stats,
                  bool relu, void* dx, bool acc_dx, void* dres, bool acc_dres, float* dgamma, float* dbeta,
-                 float* coef, float* partials, int64_t M, int C, hipStream_t s);
+                 float* coef, float* partials, const uint8_t* relu_mask, int64_t M, int C, hipStream_t s);
 
 // argmax: optional [B][Ho][Wo][C] bytes, the window tap (r*k+s) of the first maximum; written by the
 // forward pass and, when given, used by the backward pass instead of rescanning the windows

@@ -225,8 +225,13 @@ Plan make_plan(const cd_model* m, int64_t B, bool save) {
   if (save) {
     for (int t = 1; t < nt; t++)
       if (!m->tensors[t].f32) p.grad[t] = alloc((size_t)B * m->tensors[t].per_sample() * m->esize());
-    for (size_t i = 0; i < m->ops.size(); i++)
-      if (m->ops[i].kind == OP_MAXPOOL) p.aux[i] = alloc((size_t)B * m->tensors[m->ops[i].y].per_sample());
+    for (size_t i = 0; i < m->ops.size(); i++) {
+      const Op& o = m->ops[i];
+      if (o.kind == OP_MAXPOOL) p.aux[i] = alloc((size_t)B * m->tensors[o.y].per_sample());
+      // sign bits of a fused ReLU's output, one per element (bf16 vector path only)
+      if (o.kind == OP_BN && o.relu && m->dtype == CD_BF16 && m->tensors[o.y].c % 8 == 0)
+        p.aux[i] = alloc((size_t)B * m->tensors[o.y].per_sample() / 8);
+    }
   }
   p.total = off;
   return p;
@@ -450,12 +455,14 @@ extern "C" int codistill_forward(const cd_model* m, const void* params, const vo
       case OP_BN: {
         const int64_t M = batch * tx.h * tx.w;
         ProfScope pr(CD_K_NORM, c.s, 0, (double)M * tx.c * m->esize() * (3 + (o.res >= 0 ? 1 : 0)));
+        uint8_t* mask = c.plan.aux[oi] ? reinterpret_cast<uint8_t*>(c.ws + c.plan.aux[oi]) : nullptr;
         if (stat_tensor == o.x)
           bn_forward_partials(dt, in, c.P(o.pw), c.P(o.pb), o.res >= 0 ? c.act(o.res) : nullptr, o.relu, out, M, tx.c,
-                              c.stats(o), c.partials(), stat_chunks, c.partials() + (size_t)stat_chunks * 2 * tx.c, c.s);
+                              c.stats(o), c.partials(), stat_chunks, c.partials() + (size_t)stat_chunks * 2 * tx.c, mask,
+                              c.s);
         else
           bn_forward(dt, in, c.P(o.pw), c.P(o.pb), o.res >= 0 ? c.act(o.res) : nullptr, o.relu, out, M, tx.c,
-                     c.stats(o), c.partials(), c.s);
+                     c.stats(o), c.partials(), mask, c.s);
         stat_tensor = -1;
         break;
       }
@@ -553,9 +560,12 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
         const int64_t M = batch * tx.h * tx.w;
         void* dres = o.res >= 0 ? c.grad(o.res) : nullptr;
         const bool acc_res = o.res >= 0 && written[o.res];
-        ProfScope pr(CD_K_NORM, c.s, 0, (double)M * tx.c * m->esize() * (6 + (o.relu ? 2 : 0) + (o.res >= 0 ? 1 : 0)));
+        const uint8_t* mask = c.plan.aux[i] ? reinterpret_cast<const uint8_t*>(c.ws + c.plan.aux[i]) : nullptr;
+        // two passes over dy and x (+ y, or its sign bits, under a ReLU), dx written once (+ the residual's copy)
+        const double per_elt = m->esize() * (5 + (o.res >= 0 ? 1 : 0)) + (o.relu ? (mask ? 0.25 : 2.0 * m->esize()) : 0.0);
+        ProfScope pr(CD_K_NORM, c.s, 0, (double)M * tx.c * per_elt);
         bn_backward(dt, dy, c.act(o.y), in, c.P(o.pw), c.stats(o), o.relu, dx, acc, dres, acc_res, G(o.pw), G(o.pb),
-                    c.coef(), c.partials(), M, tx.c, c.s);
+                    c.coef(), c.partials(), mask, M, tx.c, c.s);
         if (o.res >= 0) written[o.res] = 1;
         break;
       }

@@ -12,11 +12,19 @@
 namespace cd {
 
 template <typename T, int VEC> struct Vec;
+// ld / st convert to and from fp32; ldraw + unpack split the load from the conversion, so that a kernel
+// can hold several loads in flight in their packed form (a quarter of the registers for bf16).
 template <> struct Vec<float, 1> {
+  typedef float Raw;
+  __device__ static Raw ldraw(const float* p) { return *p; }
+  __device__ static void unpack(const Raw& r, float (&v)[1]) { v[0] = r; }
   __device__ static void ld(const float* p, float (&v)[1]) { v[0] = *p; }
   __device__ static void st(float* p, const float (&v)[1]) { *p = v[0]; }
 };
 template <> struct Vec<float, 4> {
+  typedef float4 Raw;
+  __device__ static Raw ldraw(const float* p) { return *reinterpret_cast<const float4*>(p); }
+  __device__ static void unpack(const Raw& t, float (&v)[4]) { v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w; }
   __device__ static void ld(const float* p, float (&v)[4]) {
     float4 t = *reinterpret_cast<const float4*>(p);
     v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
@@ -26,12 +34,16 @@ template <> struct Vec<float, 4> {
   }
 };
 template <> struct Vec<bf16_t, 1> {
+  typedef bf16_t Raw;
+  __device__ static Raw ldraw(const bf16_t* p) { return *p; }
+  __device__ static void unpack(const Raw& r, float (&v)[1]) { v[0] = bf16_to_f32(r); }
   __device__ static void ld(const bf16_t* p, float (&v)[1]) { v[0] = bf16_to_f32(*p); }
   __device__ static void st(bf16_t* p, const float (&v)[1]) { *p = f32_to_bf16(v[0]); }
 };
 template <> struct Vec<bf16_t, 8> {
-  __device__ static void ld(const bf16_t* p, float (&v)[8]) {
-    uint4 t = *reinterpret_cast<const uint4*>(p);
+  typedef uint4 Raw;
+  __device__ static Raw ldraw(const bf16_t* p) { return *reinterpret_cast<const uint4*>(p); }
+  __device__ static void unpack(const Raw& t, float (&v)[8]) {
     const uint32_t u[4] = {t.x, t.y, t.z, t.w};
 #pragma unroll
     for (int i = 0; i < 4; i++) {
@@ -39,6 +51,7 @@ template <> struct Vec<bf16_t, 8> {
       v[2 * i + 1] = __uint_as_float(u[i] & 0xffff0000u);
     }
   }
+  __device__ static void ld(const bf16_t* p, float (&v)[8]) { unpack(ldraw(p), v); }
   __device__ static void st(bf16_t* p, const float (&v)[8]) {
     uint32_t u[4];
 #pragma unroll
@@ -49,11 +62,13 @@ template <> struct Vec<bf16_t, 8> {
 
 // MODE 0: sums of x and x^2.  MODE 1: sums of dz and dz*xhat with dz = dy * (relu ? y > 0 : 1).
 // MODE 2: sum of a0.  partials: [chunks][2][C].
+// mask (MODE 1, VEC 8 only, nullable): one byte per 8-channel vector, bit k = (y[k] > 0); read instead of y.
 template <typename T, int VEC, int MODE>
 __global__ void __launch_bounds__(256) col_reduce_k(const T* __restrict__ a0, const T* __restrict__ a1,
                                                     const T* __restrict__ a2, const float* __restrict__ stats,
                                                     int relu, int64_t M, int C, int64_t rows_per_chunk,
-                                                    float* __restrict__ partials) {
+                                                    float* __restrict__ partials,
+                                                    const uint8_t* __restrict__ mask) {
   __shared__ float sm[2][256 * VEC];
   const int vc = C / VEC;
   const int v0 = blockIdx.y * 256;
@@ -61,8 +76,6 @@ __global__ void __launch_bounds__(256) col_reduce_k(const T* __restrict__ a0, co
   const int rpi = 256 / vcb;                      // rows per iteration
   const int ty = threadIdx.x / vcb, tx = threadIdx.x % vcb;
   const int c0 = (v0 + tx) * VEC;
-  const int64_t r0 = (int64_t)blockIdx.x * rows_per_chunk;
-  const int64_t r1 = r0 + rows_per_chunk < M ? r0 + rows_per_chunk : M;
   float s0[VEC], s1[VEC], mean[VEC], istd[VEC];
 #pragma unroll
   for (int k = 0; k < VEC; k++) { s0[k] = 0.f; s1[k] = 0.f; mean[k] = 0.f; istd[k] = 0.f; }
@@ -71,7 +84,44 @@ __global__ void __launch_bounds__(256) col_reduce_k(const T* __restrict__ a0, co
 #pragma unroll
       for (int k = 0; k < VEC; k++) { mean[k] = stats[c0 + k]; istd[k] = stats[C + c0 + k]; }
     }
-    for (int64_t r = r0 + ty; r < r1; r += rpi) {
+    // Row groups are dealt to the blocks round-robin: at any moment the grid reads one contiguous
+    // window of each tensor (as the elementwise passes do), not one distant stream per block.
+    const int64_t rstride = (int64_t)gridDim.x * rpi;
+    int64_t r = (int64_t)blockIdx.x * rpi + ty;
+    if (MODE == 1) {
+      // full trips of UR row groups: every load of the trip is issued before the arithmetic
+      constexpr int UR = 2;
+      const bool use_mask = VEC == 8 && mask != nullptr;
+      for (; r + (UR - 1) * rstride < M; r += UR * rstride) {
+        typename Vec<T, VEC>::Raw ra[UR], rx[UR], ry[UR];
+        uint32_t bits[UR];
+#pragma unroll
+        for (int u = 0; u < UR; u++) {
+          const int64_t off = (r + u * rstride) * C + c0;
+          ra[u] = Vec<T, VEC>::ldraw(a0 + off);
+          rx[u] = Vec<T, VEC>::ldraw(a2 + off);
+          if (relu) {
+            if (use_mask) bits[u] = mask[off >> 3];
+            else ry[u] = Vec<T, VEC>::ldraw(a1 + off);
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < UR; u++) {
+          float a[VEC], x[VEC], y[VEC];
+          Vec<T, VEC>::unpack(ra[u], a);
+          Vec<T, VEC>::unpack(rx[u], x);
+          if (relu && !use_mask) Vec<T, VEC>::unpack(ry[u], y);
+#pragma unroll
+          for (int k = 0; k < VEC; k++) {
+            float d = a[k];
+            if (relu) d = (use_mask ? ((bits[u] >> k) & 1u) != 0u : y[k] > 0.f) ? d : 0.f;
+            s0[k] += d;
+            s1[k] += d * (x[k] - mean[k]) * istd[k];
+          }
+        }
+      }
+    }
+    for (; r < M; r += rstride) {
       const int64_t off = r * C + c0;
       float a[VEC];
       Vec<T, VEC>::ld(a0 + off, a);
@@ -82,10 +132,16 @@ __global__ void __launch_bounds__(256) col_reduce_k(const T* __restrict__ a0, co
         float x[VEC];
         Vec<T, VEC>::ld(a2 + off, x);
         if (relu) {
-          float y[VEC];
-          Vec<T, VEC>::ld(a1 + off, y);
+          if (VEC == 8 && mask) {
+            const uint32_t bits = mask[off >> 3];
 #pragma unroll
-          for (int k = 0; k < VEC; k++) a[k] = y[k] > 0.f ? a[k] : 0.f;
+            for (int k = 0; k < VEC; k++) a[k] = (bits >> k) & 1u ? a[k] : 0.f;
+          } else {
+            float y[VEC];
+            Vec<T, VEC>::ld(a1 + off, y);
+#pragma unroll
+            for (int k = 0; k < VEC; k++) a[k] = y[k] > 0.f ? a[k] : 0.f;
+          }
         }
 #pragma unroll
         for (int k = 0; k < VEC; k++) { s0[k] += a[k]; s1[k] += a[k] * (x[k] - mean[k]) * istd[k]; }
@@ -196,9 +252,11 @@ __global__ void __launch_bounds__(1024) col_fold_k(const float* __restrict__ par
   out[((int64_t)blockIdx.y * 2 + 1) * C + c] = s1;
 }
 
+// mask (VEC 8 only, nullable): receives one byte per vector, bit k = (y[k] > 0), for the backward pass
 template <typename T, int VEC, bool FIXC>
 __global__ void __launch_bounds__(256) bn_apply_k(const T* __restrict__ x, const T* __restrict__ res, T* __restrict__ y,
-                                                  const float* __restrict__ stats, int relu, int64_t nvec, int C) {
+                                                  const float* __restrict__ stats, int relu, int64_t nvec, int C,
+                                                  uint8_t* __restrict__ mask) {
   const int vc = C / VEC;
   const int64_t stride = (int64_t)gridDim.x * 256;
   const int64_t i0 = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -209,13 +267,13 @@ __global__ void __launch_bounds__(256) bn_apply_k(const T* __restrict__ x, const
     for (int k = 0; k < VEC; k++) { sc[k] = stats[2 * C + c0 + k]; sh[k] = stats[3 * C + c0 + k]; }
   }
   for (int64_t ib = i0; ib < nvec; ib += stride * kEltUnroll) {
-    float a[kEltUnroll][VEC], r[kEltUnroll][VEC];
+    typename Vec<T, VEC>::Raw ra[kEltUnroll], rr[kEltUnroll];
 #pragma unroll
     for (int u = 0; u < kEltUnroll; u++) {
       const int64_t i = ib + u * stride;
       if (i < nvec) {
-        Vec<T, VEC>::ld(x + i * VEC, a[u]);
-        if (res) Vec<T, VEC>::ld(res + i * VEC, r[u]);
+        ra[u] = Vec<T, VEC>::ldraw(x + i * VEC);
+        if (res) rr[u] = Vec<T, VEC>::ldraw(res + i * VEC);
       }
     }
 #pragma unroll
@@ -227,13 +285,19 @@ __global__ void __launch_bounds__(256) bn_apply_k(const T* __restrict__ x, const
 #pragma unroll
           for (int k = 0; k < VEC; k++) { sc[k] = stats[2 * C + c0 + k]; sh[k] = stats[3 * C + c0 + k]; }
         }
+        float a[VEC], r[VEC];
+        Vec<T, VEC>::unpack(ra[u], a);
+        if (res) Vec<T, VEC>::unpack(rr[u], r);
+        uint32_t bits = 0;
 #pragma unroll
         for (int k = 0; k < VEC; k++) {
-          float v = a[u][k] * sc[k] + sh[k];
-          if (res) v += r[u][k];
-          a[u][k] = relu ? fmaxf(v, 0.f) : v;
+          float v = a[k] * sc[k] + sh[k];
+          if (res) v += r[k];
+          a[k] = relu ? fmaxf(v, 0.f) : v;
+          bits |= (a[k] > 0.f ? 1u : 0u) << k;
         }
-        Vec<T, VEC>::st(y + i * VEC, a[u]);
+        Vec<T, VEC>::st(y + i * VEC, a);
+        if (VEC == 8 && mask) mask[i] = (uint8_t)bits;
       }
     }
   }
@@ -243,8 +307,10 @@ template <typename T, int VEC, bool FIXC>
 __global__ void __launch_bounds__(256) bn_bwd_apply_k(const T* __restrict__ dy, const T* __restrict__ y,
                                                       const T* __restrict__ x, const float* __restrict__ coef, int relu,
                                                       T* __restrict__ dx, int acc_dx, T* __restrict__ dres,
-                                                      int acc_dres, int64_t nvec, int C) {
+                                                      int acc_dres, int64_t nvec, int C,
+                                                      const uint8_t* __restrict__ mask) {
   constexpr int U = 2;
+  const bool use_mask = VEC == 8 && mask != nullptr;
   const int vc = C / VEC;
   const int64_t stride = (int64_t)gridDim.x * 256;
   const int64_t i0 = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -255,16 +321,20 @@ __global__ void __launch_bounds__(256) bn_bwd_apply_k(const T* __restrict__ dy, 
     for (int k = 0; k < VEC; k++) { c1[k] = coef[c0 + k]; c2[k] = coef[C + c0 + k]; c3[k] = coef[2 * C + c0 + k]; }
   }
   for (int64_t ib = i0; ib < nvec; ib += stride * U) {
-    float dz[U][VEC], xv[U][VEC], yv[U][VEC], pdx[U][VEC], pdr[U][VEC];
+    typename Vec<T, VEC>::Raw rdz[U], rxv[U], ryv[U], rpdx[U], rpdr[U];
+    uint32_t bits[U];
 #pragma unroll
     for (int u = 0; u < U; u++) {
       const int64_t i = ib + u * stride;
       if (i < nvec) {
-        Vec<T, VEC>::ld(dy + i * VEC, dz[u]);
-        Vec<T, VEC>::ld(x + i * VEC, xv[u]);
-        if (relu) Vec<T, VEC>::ld(y + i * VEC, yv[u]);
-        if (acc_dx) Vec<T, VEC>::ld(dx + i * VEC, pdx[u]);
-        if (dres && acc_dres) Vec<T, VEC>::ld(dres + i * VEC, pdr[u]);
+        rdz[u] = Vec<T, VEC>::ldraw(dy + i * VEC);
+        rxv[u] = Vec<T, VEC>::ldraw(x + i * VEC);
+        if (relu) {
+          if (use_mask) bits[u] = mask[i];
+          else ryv[u] = Vec<T, VEC>::ldraw(y + i * VEC);
+        }
+        if (acc_dx) rpdx[u] = Vec<T, VEC>::ldraw(dx + i * VEC);
+        if (dres && acc_dres) rpdr[u] = Vec<T, VEC>::ldraw(dres + i * VEC);
       }
     }
 #pragma unroll
@@ -276,20 +346,25 @@ __global__ void __launch_bounds__(256) bn_bwd_apply_k(const T* __restrict__ dy, 
 #pragma unroll
           for (int k = 0; k < VEC; k++) { c1[k] = coef[c0 + k]; c2[k] = coef[C + c0 + k]; c3[k] = coef[2 * C + c0 + k]; }
         }
-        float o[VEC];
+        float dz[VEC], xv[VEC], yv[VEC], pdx[VEC], pdr[VEC], o[VEC];
+        Vec<T, VEC>::unpack(rdz[u], dz);
+        Vec<T, VEC>::unpack(rxv[u], xv);
+        if (relu && !use_mask) Vec<T, VEC>::unpack(ryv[u], yv);
+        if (acc_dx) Vec<T, VEC>::unpack(rpdx[u], pdx);
+        if (dres && acc_dres) Vec<T, VEC>::unpack(rpdr[u], pdr);
 #pragma unroll
         for (int k = 0; k < VEC; k++) {
-          if (relu) dz[u][k] = yv[u][k] > 0.f ? dz[u][k] : 0.f;
-          o[k] = c1[k] * dz[u][k] + c2[k] * xv[u][k] + c3[k];
-          if (acc_dx) o[k] += pdx[u][k];
+          if (relu) dz[k] = (use_mask ? ((bits[u] >> k) & 1u) != 0u : yv[k] > 0.f) ? dz[k] : 0.f;
+          o[k] = c1[k] * dz[k] + c2[k] * xv[k] + c3[k];
+          if (acc_dx) o[k] += pdx[k];
         }
         Vec<T, VEC>::st(dx + i * VEC, o);
         if (dres) {
           if (acc_dres) {
 #pragma unroll
-            for (int k = 0; k < VEC; k++) dz[u][k] += pdr[u][k];
+            for (int k = 0; k < VEC; k++) dz[k] += pdr[k];
           }
-          Vec<T, VEC>::st(dres + i * VEC, dz[u]);
+          Vec<T, VEC>::st(dres + i * VEC, dz);
         }
       }
     }
@@ -337,17 +412,17 @@ template <typename T> static int pick_vec(int C, const void* p0, const void* p1,
 
 template <typename T, int VEC, int MODE>
 static ReducePlan launch_reduce(const T* a0, const T* a1, const T* a2, const float* stats, bool relu, int64_t M, int C,
-                                float* partials, hipStream_t s) {
+                                float* partials, hipStream_t s, const uint8_t* mask = nullptr) {
   ReducePlan p = reduce_plan(M, C, VEC);
   hipLaunchKernelGGL((col_reduce_k<T, VEC, MODE>), dim3(p.chunks, p.cgroups), dim3(256), 0, s, a0, a1, a2, stats,
-                     (int)relu, M, C, p.rows_per_chunk, partials);
+                     (int)relu, M, C, p.rows_per_chunk, partials, mask);
   return p;
 }
 
 // pre_chunks > 0: the column sums are already in partials (written by the producing convolution)
 template <typename T>
 static void bn_forward_t(const T* x, const T* gamma, const T* beta, const T* res, bool relu, T* y, int64_t M, int C,
-                         float* stats, float* partials, int pre_chunks, float* scratch, hipStream_t s) {
+                         float* stats, float* partials, int pre_chunks, float* scratch, uint8_t* mask, hipStream_t s) {
   const int vec = pick_vec<T>(C, x, res, y, nullptr);
   constexpr int V = sizeof(T) == 2 ? 8 : 4;
   int chunks = pre_chunks;
@@ -367,7 +442,8 @@ static void bn_forward_t(const T* x, const T* gamma, const T* beta, const T* res
   bool fixc;
   const unsigned blocks = elt_grid(nvec, C / vec, kEltUnroll, &fixc);
 #define CD_BN_APPLY(VV, FC) \
-  hipLaunchKernelGGL((bn_apply_k<T, VV, FC>), dim3(blocks), dim3(256), 0, s, x, res, y, stats, (int)relu, nvec, C)
+  hipLaunchKernelGGL((bn_apply_k<T, VV, FC>), dim3(blocks), dim3(256), 0, s, x, res, y, stats, (int)relu, nvec, C, \
+                     relu ? mask : (uint8_t*)nullptr)
   if (vec > 1) { if (fixc) CD_BN_APPLY(V, true); else CD_BN_APPLY(V, false); }
   else { if (fixc) CD_BN_APPLY(1, true); else CD_BN_APPLY(1, false); }
 #undef CD_BN_APPLY
@@ -376,11 +452,11 @@ static void bn_forward_t(const T* x, const T* gamma, const T* beta, const T* res
 template <typename T>
 static void bn_backward_t(const T* dy, const T* y, const T* x, const T* gamma, const float* stats, bool relu, T* dx,
                           bool acc_dx, T* dres, bool acc_dres, float* dgamma, float* dbeta, float* coef,
-                          float* partials, int64_t M, int C, hipStream_t s) {
+                          float* partials, const uint8_t* mask, int64_t M, int C, hipStream_t s) {
   int vec = pick_vec<T>(C, dy, y, x, dx);
   if (!aligned16(dres)) vec = 1;
   constexpr int V = sizeof(T) == 2 ? 8 : 4;
-  ReducePlan p = vec > 1 ? launch_reduce<T, V, 1>(dy, y, x, stats, relu, M, C, partials, s)
+  ReducePlan p = vec > 1 ? launch_reduce<T, V, 1>(dy, y, x, stats, relu, M, C, partials, s, mask)
                          : launch_reduce<T, 1, 1>(dy, y, x, stats, relu, M, C, partials, s);
   hipLaunchKernelGGL((col_finalize_k<T, 1>), dim3((unsigned)cdiv(C, 64)), dim3(1024), 0, s, partials, p.chunks, M, C,
                      gamma, (const T*)nullptr, const_cast<float*>(stats), dgamma, dbeta, coef);
@@ -389,7 +465,7 @@ static void bn_backward_t(const T* dy, const T* y, const T* x, const T* gamma, c
   const unsigned blocks = elt_grid(nvec, C / vec, 2, &fixc);
 #define CD_BN_BWD(VV, FC)                                                                                          \
   hipLaunchKernelGGL((bn_bwd_apply_k<T, VV, FC>), dim3(blocks), dim3(256), 0, s, dy, y, x, coef, (int)relu, dx, \
-                     (int)acc_dx, dres, (int)acc_dres, nvec, C)
+                     (int)acc_dx, dres, (int)acc_dres, nvec, C, mask)
   if (vec > 1) { if (fixc) CD_BN_BWD(V, true); else CD_BN_BWD(V, false); }
   else { if (fixc) CD_BN_BWD(1, true); else CD_BN_BWD(1, false); }
 #undef CD_BN_BWD
@@ -406,33 +482,33 @@ static void colsum_t(const T* a, int64_t M, int C, float* out, float* partials, 
 }
 
 void bn_forward(int dtype, const void* x, const void* gamma, const void* beta, const void* res, bool relu, void* y,
-                int64_t M, int C, float* stats, float* partials, hipStream_t s) {
+                int64_t M, int C, float* stats, float* partials, uint8_t* relu_mask, hipStream_t s) {
   if (dtype == CD_BF16)
     bn_forward_t<bf16_t>((const bf16_t*)x, (const bf16_t*)gamma, (const bf16_t*)beta, (const bf16_t*)res, relu,
-                         (bf16_t*)y, M, C, stats, partials, 0, nullptr, s);
+                         (bf16_t*)y, M, C, stats, partials, 0, nullptr, relu_mask, s);
   else
     bn_forward_t<float>((const float*)x, (const float*)gamma, (const float*)beta, (const float*)res, relu, (float*)y, M,
-                        C, stats, partials, 0, nullptr, s);
+                        C, stats, partials, 0, nullptr, nullptr, s);
 }
 void bn_forward_partials(int dtype, const void* x, const void* gamma, const void* beta, const void* res, bool relu,
                          void* y, int64_t M, int C, float* stats, const float* partials, int chunks, float* scratch,
-                         hipStream_t s) {
+                         uint8_t* relu_mask, hipStream_t s) {
   if (dtype == CD_BF16)
     bn_forward_t<bf16_t>((const bf16_t*)x, (const bf16_t*)gamma, (const bf16_t*)beta, (const bf16_t*)res, relu,
-                         (bf16_t*)y, M, C, stats, const_cast<float*>(partials), chunks, scratch, s);
+                         (bf16_t*)y, M, C, stats, const_cast<float*>(partials), chunks, scratch, relu_mask, s);
   else
     bn_forward_t<float>((const float*)x, (const float*)gamma, (const float*)beta, (const float*)res, relu, (float*)y, M,
-                        C, stats, const_cast<float*>(partials), chunks, scratch, s);
+                        C, stats, const_cast<float*>(partials), chunks, scratch, nullptr, s);
 }
 void bn_backward(int dtype, const void* dy, const void* y, const void* x, const void* gamma, const float* stats,
                  bool relu, void* dx, bool acc_dx, void* dres, bool acc_dres, float* dgamma, float* dbeta, float* coef,
-                 float* partials, int64_t M, int C, hipStream_t s) {
+                 float* partials, const uint8_t* relu_mask, int64_t M, int C, hipStream_t s) {
   if (dtype == CD_BF16)
     bn_backward_t<bf16_t>((const bf16_t*)dy, (const bf16_t*)y, (const bf16_t*)x, (const bf16_t*)gamma, stats, relu,
-                          (bf16_t*)dx, acc_dx, (bf16_t*)dres, acc_dres, dgamma, dbeta, coef, partials, M, C, s);
+                          (bf16_t*)dx, acc_dx, (bf16_t*)dres, acc_dres, dgamma, dbeta, coef, partials, relu_mask, M, C, s);
   else
     bn_backward_t<float>((const float*)dy, (const float*)y, (const float*)x, (const float*)gamma, stats, relu,
-                         (float*)dx, acc_dx, (float*)dres, acc_dres, dgamma, dbeta, coef, partials, M, C, s);
+                         (float*)dx, acc_dx, (float*)dres, acc_dres, dgamma, dbeta, coef, partials, nullptr, M, C, s);
 }
 void colsum(int dtype, const void* a, int64_t M, int C, float* out, float* partials, hipStream_t s) {
   if (dtype == CD_BF16) colsum_t<bf16_t>((const bf16_t*)a, M, C, out, partials, s);
