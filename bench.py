@@ -149,7 +149,9 @@ def main():
     ms_per_step = dt / args.steps * 1e3
     loss = r.loss.cpu().numpy()
 
-    # second pass: per-launch HIP events on the launch stream, per kernel class
+    # second pass: per-launch HIP events on the launch stream, per kernel class; the peer forward runs
+    # after the local one here (on one stream), so that a launch's duration is its own
+    r.overlap_peers = False
     B.profile_reset()
     B.profile_enable(True)
     psteps = max(1, min(args.steps, 5))

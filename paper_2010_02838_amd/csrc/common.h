@@ -29,6 +29,14 @@ struct ProfScope {
   hipStream_t stream;
 };
 
+// ---- second stream for work that forks off the caller's stream ----------------------------
+// One per process, default priority, created on first use together with a pool of timing-free
+// events; nullptr if the runtime refuses.  timer_enabled(): the per-launch timer is on, callers then
+// keep everything on one stream so that a launch's duration is its own.
+hipStream_t side_stream();
+hipEvent_t side_event(int i);
+bool timer_enabled();
+
 // ---- bf16 ---------------------------------------------------------------------------------
 typedef uint16_t bf16_t;  // upper half of an IEEE float32
 

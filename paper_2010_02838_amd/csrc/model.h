@@ -43,6 +43,7 @@ struct Plan {
   size_t bn_coef = 0;         // backward coefficients c1,c2,c3 [3][Cmax] fp32
   size_t partials = 0;        // reduction partials / split-K partials
   size_t partials_bytes = 0;
+  size_t partials_side = 0;   // split-K partials of the weight gradients that run on the side stream (save only)
   size_t xpack = 0;           // bf16 models: input packed to 8 channels
   size_t wpack = 0;           // bf16 models: re-laid-out weights (stem padding, dgrad transposes)
   size_t wpack_bytes = 0;

@@ -171,6 +171,12 @@ bool force_simple() {
   return e && e[0] == '1';
 }
 
+// CODISTILL_SERIAL=1 keeps every launch of a call on the caller's stream (debugging aid)
+bool force_serial() {
+  const char* e = getenv("CODISTILL_SERIAL");
+  return e && e[0] == '1';
+}
+
 ConvGeom conv_geom(const cd_model* m, const Op& o, int64_t B) {
   const TensorDesc& tx = m->tensors[o.x];
   const TensorDesc& ty = m->tensors[o.y];
@@ -223,6 +229,7 @@ Plan make_plan(const cd_model* m, int64_t B, bool save) {
   }
   p.aux.assign(m->ops.size(), 0);
   if (save) {
+    p.partials_side = alloc(p.partials_bytes);
     for (int t = 1; t < nt; t++)
       if (!m->tensors[t].f32) p.grad[t] = alloc((size_t)B * m->tensors[t].per_sample() * m->esize());
     for (size_t i = 0; i < m->ops.size(); i++) {
@@ -376,6 +383,7 @@ struct Ctx {
   void* grad(int t) const { return ws + plan.grad[t]; }
   float* stats(const Op& o) const { return reinterpret_cast<float*>(ws + plan.bn_stats) + 4 * m->bn_off[o.bn_slot]; }
   float* partials() const { return reinterpret_cast<float*>(ws + plan.partials); }
+  float* partials_side() const { return reinterpret_cast<float*>(ws + plan.partials_side); }
   float* coef() const { return reinterpret_cast<float*>(ws + plan.bn_coef); }
   bf16_t* xpack() const { return reinterpret_cast<bf16_t*>(ws + plan.xpack); }
   bf16_t* wpack() const { return reinterpret_cast<bf16_t*>(ws + plan.wpack); }
@@ -520,6 +528,12 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
     if (!gaps.empty()) zero_gaps(grads_out, gaps.data(), (int)gaps.size(), c.s);
   }
 
+  // The weight gradient of a convolution needs dy and the saved input only, and nothing downstream
+  // but the optimizer needs its result: these launches fork onto a second stream (with their own
+  // split-K partials) and run beside the data gradients and BatchNorm passes that follow; the
+  // caller's stream waits for them at the end.  One stream when the per-launch timer is on.
+  hipStream_t side = (timer_enabled() || force_serial()) ? nullptr : side_stream();
+  int forks = 0;
   std::vector<char> written(m->tensors.size(), 0);
   for (int i = (int)m->ops.size() - 1; i >= 0; i--) {
     const Op& o = m->ops[i];
@@ -581,7 +595,17 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
         }
         const bool mf = use_mfma(m, g) && o.pb < 0 && !o.relu;
         {
-          ProfScope pr(CD_K_CONV_WGRAD, c.s, 2.0 * g.M() * g.Cout * g.K(), conv_bytes(m, g) + 2.0 * g.Cout * g.K());
+          hipStream_t ws_ = c.s;
+          float* wpart = c.partials();
+          if (mf && side) {
+            hipEvent_t ev = side_event(forks);
+            if (ev && hipEventRecord(ev, c.s) == hipSuccess && hipStreamWaitEvent(side, ev, 0) == hipSuccess) {
+              ws_ = side;
+              wpart = c.partials_side();
+              forks++;
+            }
+          }
+          ProfScope pr(CD_K_CONV_WGRAD, ws_, 2.0 * g.M() * g.Cout * g.K(), conv_bytes(m, g) + 2.0 * g.Cout * g.K());
           if (mf) {
             ConvGeom gp = g;
             const bf16_t* src = static_cast<const bf16_t*>(in);
@@ -591,8 +615,8 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
               src = c.xpack();
               dw = reinterpret_cast<float*>(c.wpack());
             }
-            conv_wgrad_mfma(src, static_cast<const bf16_t*>(dy), dw, gp, c.partials(), c.plan.partials_bytes, c.s);
-            if (g.Cin == 3) unpad_c8_to_c3(dw, G(o.pw), (int64_t)g.Cout * g.kh * g.kw, c.s);
+            conv_wgrad_mfma(src, static_cast<const bf16_t*>(dy), dw, gp, wpart, c.plan.partials_bytes, ws_);
+            if (g.Cin == 3) unpad_c8_to_c3(dw, G(o.pw), (int64_t)g.Cout * g.kh * g.kw, ws_);
           } else {
             conv_wgrad_simple(dt, in, dy, G(o.pw), g, c.s);
           }
@@ -610,6 +634,12 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
       }
     }
     if (o.x != 0) written[o.x] = 1;
+  }
+  if (forks > 0) {  // join: the caller's stream continues after the last weight gradient
+    hipEvent_t ev = side_event(forks);
+    if (!ev || hipEventRecord(ev, side) != hipSuccess || hipStreamWaitEvent(c.s, ev, 0) != hipSuccess) {
+      (void)hipStreamSynchronize(side);  // no event to wait on: fall back to a host-side join
+    }
   }
   return check_launch("backward");
 }

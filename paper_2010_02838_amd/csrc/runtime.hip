@@ -71,6 +71,42 @@ ProfScope::~ProfScope() {
   (void)hipEventRecord(g_prof_recs[idx].b, stream);
 }
 
+bool timer_enabled() {
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  return g_prof_on;
+}
+
+// ---- side stream --------------------------------------------------------------------------
+static std::mutex g_side_mu;
+static hipStream_t g_side_stream = nullptr;
+static bool g_side_failed = false;
+static std::vector<hipEvent_t> g_side_events;
+
+hipStream_t side_stream() {
+  std::lock_guard<std::mutex> lk(g_side_mu);
+  if (!g_side_stream && !g_side_failed) {
+    if (hipStreamCreateWithFlags(&g_side_stream, hipStreamNonBlocking) != hipSuccess) {
+      g_side_stream = nullptr;
+      g_side_failed = true;
+      (void)hipGetLastError();
+    }
+  }
+  return g_side_stream;
+}
+
+hipEvent_t side_event(int i) {
+  std::lock_guard<std::mutex> lk(g_side_mu);
+  while ((int)g_side_events.size() <= i) {
+    hipEvent_t e = nullptr;
+    if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    g_side_events.push_back(e);
+  }
+  return g_side_events[i];
+}
+
 }  // namespace cd
 
 using namespace cd;

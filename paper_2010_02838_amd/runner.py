@@ -39,8 +39,13 @@ def to_device(arr, torch_dtype, device="cuda:0"):
 class StepRunner:
     """One model's training state plus the stale peer copies it distils against."""
 
-    def __init__(self, model, peer_models, batch, device="cuda:0"):
+    def __init__(self, model, peer_models, batch, device="cuda:0", overlap_peers=True):
         self.model, self.peers, self.batch, self.dev = model, list(peer_models), batch, device
+        # The peer forwards depend on nothing but the minibatch: they run on a second stream (default
+        # priority) beside the local forward, so that one model's memory-bound kernels and partly
+        # filled launches share the chip with the other's.
+        self.overlap_peers = overlap_peers
+        self.side = torch.cuda.Stream(device=device) if overlap_peers else None
         n, C = model.n_elements, model.classes
         f32 = dict(dtype=torch.float32, device=device)
         self.master = torch.zeros(n, **f32)
@@ -75,9 +80,18 @@ class StepRunner:
     def step(self, x, y, alpha, lr, momentum, weight_decay=0.0, label_smoothing=0.0,
              dist_kind=B.CD_DIST_MSE_LOGITS, mse_reduction=B.CD_MEAN_ALL, ignore_index=-1, nesterov=False):
         """x: [B,H,W,3] device tensor in the model dtype; y: int32 device tensor."""
-        B.codistill_forward(self.model, self.params(), x, self.ws, self.logits, True)
-        for pm, pp, pl in zip(self.peers, self.peer_params, self.peer_logits):
-            B.codistill_forward(pm, pp, x, self.ws_peer, pl, False)
+        if self.overlap_peers and self.peers:
+            main = torch.cuda.current_stream()
+            self.side.wait_stream(main)           # x, the peer parameters and the last step's reads are in order
+            with torch.cuda.stream(self.side):
+                for pm, pp, pl in zip(self.peers, self.peer_params, self.peer_logits):
+                    B.codistill_forward(pm, pp, x, self.ws_peer, pl, False)
+            B.codistill_forward(self.model, self.params(), x, self.ws, self.logits, True)
+            main.wait_stream(self.side)           # the loss needs every model's logits
+        else:
+            B.codistill_forward(self.model, self.params(), x, self.ws, self.logits, True)
+            for pm, pp, pl in zip(self.peers, self.peer_params, self.peer_logits):
+                B.codistill_forward(pm, pp, x, self.ws_peer, pl, False)
         B.codistill_loss_grad(self.logits, self.peer_logits, y, self.loss, self.dz, self.scratch, alpha,
                               label_smoothing, dist_kind, mse_reduction, ignore_index)
         B.codistill_backward(self.model, self.params(), x, self.ws, self.dz, self.grads)
