@@ -843,6 +843,67 @@ __global__ void __launch_bounds__(256) pad_c3_to_c8_k(const bf16_t* __restrict__
 void pad_c3_to_c8(const bf16_t* in, bf16_t* out, int64_t n, hipStream_t s) {
   hipLaunchKernelGGL(pad_c3_to_c8_k, dim3((unsigned)cdiv(n, 256)), dim3(256), 0, s, in, out, n);
 }
+// ---- space-to-depth form of a stride-2 convolution on 3-channel images ------------------------------
+// x[b][2I+p][2J+q][c] -> xs[b][I][J][(2p+q)*3 + c] (16 channels, the last four zero): a k x k stride-2
+// filter with padding pad becomes a ks x ks stride-1 filter on xs with padding P = ceil(pad / 2),
+// ks = ceil((k + 2P - pad) / 2), whose tap (R, S), channel (2p+q)*3 + c is the original tap
+// r = 2R + p - (2P - pad), s = 2S + q - (2P - pad) (zero where that falls outside the filter).  The
+// contraction shrinks from k*k*8 (channels padded to a 16-byte vector) to ks*ks*16.
+__global__ void __launch_bounds__(256) s2d_pack_x_k(const bf16_t* __restrict__ x, bf16_t* __restrict__ xs, int64_t n,
+                                                    int Hs, int Ws) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;  // (b, I, J)
+  if (i >= n) return;
+  const int J = (int)(i % Ws);
+  const int64_t q = i / Ws;
+  const int I = (int)(q % Hs);
+  const int64_t b = q / Hs;
+  const int W = 2 * Ws;
+  const bf16_t* r0 = x + ((b * 2 * Hs + 2 * I) * W + 2 * J) * 3;  // six contiguous elements per image row
+  const bf16_t* r1 = r0 + (int64_t)W * 3;
+  uint32_t u[8];
+  u[0] = r0[0] | ((uint32_t)r0[1] << 16); u[1] = r0[2] | ((uint32_t)r0[3] << 16); u[2] = r0[4] | ((uint32_t)r0[5] << 16);
+  u[3] = r1[0] | ((uint32_t)r1[1] << 16); u[4] = r1[2] | ((uint32_t)r1[3] << 16); u[5] = r1[4] | ((uint32_t)r1[5] << 16);
+  u[6] = 0; u[7] = 0;
+  uint4* o = reinterpret_cast<uint4*>(xs + i * 16);
+  o[0] = make_uint4(u[0], u[1], u[2], u[3]);
+  o[1] = make_uint4(u[4], u[5], u[6], u[7]);
+}
+void s2d_pack_x(const bf16_t* x, bf16_t* xs, int64_t B, int H, int W, hipStream_t s) {
+  const int64_t n = B * (H / 2) * (W / 2);
+  hipLaunchKernelGGL(s2d_pack_x_k, dim3((unsigned)cdiv(n, 256)), dim3(256), 0, s, x, xs, n, H / 2, W / 2);
+}
+// w[n][k][k][3] -> ws[n][ks][ks][16]
+__global__ void __launch_bounds__(256) s2d_pack_w_k(const bf16_t* __restrict__ w, bf16_t* __restrict__ ws, int cout,
+                                                    int k, int ks, int shift) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= cout * ks * ks * 16) return;
+  const int ch = i & 15, S = (i >> 4) % ks, R = (i >> 4) / ks % ks, n = (i >> 4) / (ks * ks);
+  bf16_t v = 0;
+  if (ch < 12) {
+    const int pq = ch / 3, c = ch - pq * 3;
+    const int r = 2 * R + (pq >> 1) - shift, t = 2 * S + (pq & 1) - shift;
+    if (r >= 0 && r < k && t >= 0 && t < k) v = w[((n * k + r) * k + t) * 3 + c];
+  }
+  ws[i] = v;
+}
+void s2d_pack_w(const bf16_t* w, bf16_t* ws, int cout, int k, int ks, int shift, hipStream_t s) {
+  hipLaunchKernelGGL(s2d_pack_w_k, dim3((unsigned)cdiv(cout * ks * ks * 16, 256)), dim3(256), 0, s, w, ws, cout, k, ks,
+                     shift);
+}
+// fp32 dws[n][ks][ks][16] -> dw[n][k][k][3]
+__global__ void __launch_bounds__(256) s2d_unpack_dw_k(const float* __restrict__ dws, float* __restrict__ dw, int cout,
+                                                       int k, int ks, int shift) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= cout * k * k * 3) return;
+  const int c = i % 3, t = i / 3 % k, r = i / 3 / k % k, n = i / 3 / (k * k);
+  const int rr = r + shift, tt = t + shift;
+  dw[i] = dws[((n * ks + (rr >> 1)) * ks + (tt >> 1)) * 16 + ((rr & 1) * 2 + (tt & 1)) * 3 + c];
+}
+void s2d_unpack_dw(const float* dws, float* dw, int cout, int k, int ks, int shift, hipStream_t s) {
+  hipLaunchKernelGGL(s2d_unpack_dw_k, dim3((unsigned)cdiv(cout * k * k * 3, 256)), dim3(256), 0, s, dws, dw, cout, k, ks,
+                     shift);
+}
+
 __global__ void __launch_bounds__(256) unpad_c8_to_c3_k(const float* __restrict__ in, float* __restrict__ out,
                                                         int64_t n) {
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;

@@ -86,6 +86,12 @@ void linear_fwd_mfma(const bf16_t* x, const bf16_t* w, const bf16_t* bias, float
 void cast_f32_bf16(const float* in, bf16_t* out, int64_t n, hipStream_t s);
 // [n][3] -> [n][8] zero padded (input images and the taps of a 3-channel filter)
 void pad_c3_to_c8(const bf16_t* in, bf16_t* out, int64_t n, hipStream_t s);
+// Space-to-depth form of a stride-2 convolution on 3-channel images (even H, W): xs is
+// [B][H/2][W/2][16], ws [cout][ks][ks][16] with ks = ceil((k + shift) / 2), shift = 2*ceil(pad/2) - pad;
+// the stride-1 convolution of xs with ws (padding ceil(pad/2)) equals the original one.
+void s2d_pack_x(const bf16_t* x, bf16_t* xs, int64_t B, int H, int W, hipStream_t s);
+void s2d_pack_w(const bf16_t* w, bf16_t* ws, int cout, int k, int ks, int shift, hipStream_t s);
+void s2d_unpack_dw(const float* dws, float* dw, int cout, int k, int ks, int shift, hipStream_t s);
 // fp32 [n][8] -> [n][3]
 void unpad_c8_to_c3(const float* in, float* out, int64_t n, hipStream_t s);
 // w[Cout][taps][Cin] -> wt[Cin][taps][Cout]

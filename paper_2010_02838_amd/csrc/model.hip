@@ -186,12 +186,26 @@ ConvGeom conv_geom(const cd_model* m, const Op& o, int64_t B) {
   return g;
 }
 
-// bf16 convolutions run on the MFMA kernels; a 3-channel input is zero-padded to 8 channels
+// The geometry the MFMA kernels see for a convolution on 3-channel images: stride 2 on even image
+// sizes runs in space-to-depth form (16 channels, stride 1, about half the taps per axis), anything
+// else with the channels zero-padded to 8.
+bool s2d_form(const ConvGeom& g) { return g.Cin == 3 && g.stride == 2 && g.H % 2 == 0 && g.W % 2 == 0 && g.kh == g.kw; }
+ConvGeom packed_geom(const ConvGeom& g) {
+  ConvGeom p = g;
+  if (s2d_form(g)) {
+    const int P = (g.pad + 1) / 2, shift = 2 * P - g.pad;
+    p.H = g.H / 2; p.W = g.W / 2; p.Cin = 16;
+    p.kh = p.kw = (g.kh + shift + 1) / 2;
+    p.stride = 1; p.pad = P;
+  } else if (g.Cin == 3) {
+    p.Cin = 8;
+  }
+  return p;
+}
+// bf16 convolutions run on the MFMA kernels
 bool use_mfma(const cd_model* m, const ConvGeom& g) {
   if (m->dtype != CD_BF16 || force_simple()) return false;
-  ConvGeom p = g;
-  if (p.Cin == 3) p.Cin = 8;
-  return conv_mfma_supported(p);
+  return conv_mfma_supported(packed_geom(g));
 }
 
 }  // namespace
@@ -437,18 +451,22 @@ extern "C" int codistill_forward(const cd_model* m, const void* params, const vo
         if (use_mfma(m, g) && o.pb < 0 && !o.relu) {
           const bf16_t* src = static_cast<const bf16_t*>(in);
           const bf16_t* w = static_cast<const bf16_t*>(c.P(o.pw));
-          if (g.Cin == 3) {  // pad image and filter taps to 8 channels
+          const ConvGeom gp = packed_geom(g);
+          if (g.Cin == 3) {  // re-lay-out image and filter for 16-byte channel vectors
             ProfScope pr(CD_K_GLUE, c.s, 0, (double)batch * g.H * g.W * (3 + 8) * 2);
-            pad_c3_to_c8(src, c.xpack(), batch * g.H * g.W, c.s);
-            pad_c3_to_c8(w, c.wpack(), (int64_t)g.Cout * g.kh * g.kw, c.s);
+            if (s2d_form(g)) {
+              s2d_pack_x(src, c.xpack(), batch, g.H, g.W, c.s);
+              s2d_pack_w(w, c.wpack(), g.Cout, g.kh, gp.kh, 2 * gp.pad - g.pad, c.s);
+            } else {
+              pad_c3_to_c8(src, c.xpack(), batch * g.H * g.W, c.s);
+              pad_c3_to_c8(w, c.wpack(), (int64_t)g.Cout * g.kh * g.kw, c.s);
+            }
             src = c.xpack();
             w = c.wpack();
           }
           ProfScope pr(g.Cout > 64 && !conv_fprop_tall_tile(g) ? CD_K_CONV_FPROP : CD_K_CONV_FPROP_NARROW, c.s,
                        2.0 * g.M() * g.Cout * g.K(),
                        conv_bytes(m, g));
-          ConvGeom gp = g;
-          if (gp.Cin == 3) gp.Cin = 8;
           // a BatchNorm that follows directly gets its column sums from the convolution's epilogue
           const bool fuse = oi + 1 < m->ops.size() && m->ops[oi + 1].kind == OP_BN && m->ops[oi + 1].x == o.y &&
                             (size_t)(g.M() / 128 + 1 + 64) * 2 * g.Cout * sizeof(float) <= c.plan.partials_bytes;
@@ -607,16 +625,16 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
           }
           ProfScope pr(CD_K_CONV_WGRAD, ws_, 2.0 * g.M() * g.Cout * g.K(), conv_bytes(m, g) + 2.0 * g.Cout * g.K());
           if (mf) {
-            ConvGeom gp = g;
+            const ConvGeom gp = packed_geom(g);
             const bf16_t* src = static_cast<const bf16_t*>(in);
             float* dw = G(o.pw);
-            if (g.Cin == 3) {  // the forward pass left the padded image in xpack
-              gp.Cin = 8;
+            if (g.Cin == 3) {  // the forward pass left the re-laid-out image in xpack
               src = c.xpack();
               dw = reinterpret_cast<float*>(c.wpack());
             }
             conv_wgrad_mfma(src, static_cast<const bf16_t*>(dy), dw, gp, wpart, c.plan.partials_bytes, ws_);
-            if (g.Cin == 3) unpad_c8_to_c3(dw, G(o.pw), (int64_t)g.Cout * g.kh * g.kw, ws_);
+            if (s2d_form(g)) s2d_unpack_dw(dw, G(o.pw), g.Cout, g.kh, gp.kh, 2 * gp.pad - g.pad, ws_);
+            else if (g.Cin == 3) unpad_c8_to_c3(dw, G(o.pw), (int64_t)g.Cout * g.kh * g.kw, ws_);
           } else {
             conv_wgrad_simple(dt, in, dy, G(o.pw), g, c.s);
           }
