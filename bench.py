@@ -6,11 +6,13 @@ already resident in HBM: local forward (kept for backward), peer forward
 Workload: two ResNet-50 (bf16 compute, fp32 master weights), batch 256 of
 224x224x3 images ~ N(0,1), 1000 uniform classes, alpha = 1.
 
-Prints ONE JSON line.  `roofline` is for the dominant kernel, the bf16 MFMA
-implicit-GEMM convolution igemm_kernel<0,128,128,2,2,false,true> (every fprop
-launch with more than 64 output channels): algorithmic flops / HIP-event time of
-those launches, measured in a second pass of the same steps with the library's
-per-launch event timer (events on the launch stream) switched on.  `cpu_baseline` is
+Prints ONE JSON line.  `roofline` is for the kernel that takes the most time, the
+bf16 MFMA implicit-GEMM convolution igemm_kernel<0,128,128,2,2,false,true,1,false>
+(every fprop launch on 128x128 tiles): algorithmic flops / HIP-event time of those
+launches, measured in a second pass of the same steps with the library's
+per-launch event timer (events on the launch stream) switched on; that pass keeps
+every launch on one stream, while the timed steps run the peer forward and the
+weight gradients on second streams.  `cpu_baseline` is
 the float64 NumPy oracle of the same step timed on the host on a small batch.
 """
 import argparse
@@ -28,7 +30,7 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch of the roofline kernel from hardware counters (two rocprofv3 --pmc passes of this
 # script, FETCH_SIZE then WRITE_SIZE, each scaled by what the same counter read for the 1 GiB copy of
 # --copy-calibration).  Valid only for the kernel the counters were taken on: set to None when it changes.
-ROOFLINE_TRAFFIC_BYTES = None
+ROOFLINE_TRAFFIC_BYTES = 231.8e6   # FETCH_SIZE 50153.0 KiB x 2.000 + WRITE_SIZE 126033.6 KiB x 1.000
 
 
 def cpu_baseline(seconds_hint=20.0):
@@ -165,7 +167,7 @@ def main():
     roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / PEAK_BF16_TFLOPS, "traffic": ROOFLINE_TRAFFIC_BYTES,
                 "algorithmic_bytes_per_launch": prof["conv_fprop"]["bytes"] / max(ig_n, 1),
-                "kernel": "igemm_kernel<0,128,128,2,2,false,true> (bf16 implicit-GEMM conv fprop, Cout > 64)",
+                "kernel": "igemm_kernel<0,128,128,2,2,false,true,1,false> (bf16 implicit-GEMM conv fprop on 128x128 tiles)",
                 "flop_per_launch": ig_fl / max(ig_n, 1),
                 "launches_per_step": ig_n / psteps, "avg_launch_us": ig_ms / max(ig_n, 1) * 1e3}
     classes_ms = {k: round(v["ms"] / psteps, 4) for k, v in prof.items()}
