@@ -9,7 +9,9 @@ only names the architectures; the layer conventions are the standard ones:
   * convolution is cross-correlation with zero padding;
   * BatchNorm normalises with the biased batch variance over (B, H, W), eps 1e-5;
   * ReLU'(0) = 0; max-pool routes the gradient to the first maximum in
-    row-major window order.
+    row-major window order;
+  * LayerNorm (the Transformer of Section 4, which the paper only names) normalises every row
+    over its last axis with the biased variance, eps 1e-5, then scales and shifts per feature.
 """
 import numpy as np
 
@@ -18,6 +20,9 @@ BN_EPS = 1e-5
 
 def _out_size(n, k, stride, pad):
     return (n + 2 * pad - k) // stride + 1
+
+
+LN_EPS = 1e-5
 
 
 # ---------------------------------------------------------------- convolution
@@ -147,3 +152,25 @@ def linear_backward(x, w, dy, has_bias):
     dw = dy.T.dot(x)
     db = dy.sum(axis=0) if has_bias else None
     return dx, dw, db
+
+
+# ------------------------------------------------------------------ LayerNorm
+def layernorm_forward(x, gamma, beta):
+    """y[..., j] = gamma[j] * (x[..., j] - mean) / sqrt(var + eps) + beta[j], mean and (biased) var over j."""
+    mean = x.mean(axis=-1, keepdims=True)
+    var = ((x - mean) ** 2).mean(axis=-1, keepdims=True)
+    rstd = 1.0 / np.sqrt(var + LN_EPS)
+    xhat = (x - mean) * rstd
+    return gamma * xhat + beta, (xhat, rstd)
+
+
+def layernorm_backward(dy, gamma, cache):
+    """Return (dx, dgamma, dbeta).  With g = dy * gamma:
+    dx = rstd * (g - mean_j(g) - xhat * mean_j(g * xhat))."""
+    xhat, rstd = cache
+    red = tuple(range(dy.ndim - 1))
+    dgamma = (dy * xhat).sum(axis=red)
+    dbeta = dy.sum(axis=red)
+    g = dy * gamma
+    dx = rstd * (g - g.mean(axis=-1, keepdims=True) - xhat * (g * xhat).mean(axis=-1, keepdims=True))
+    return dx, dgamma, dbeta

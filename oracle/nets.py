@@ -16,6 +16,14 @@ gives as 8e8 bits) without defining them; these are the standard definitions:
              shortcut in the first block of every stage, global average pool,
              linear(2048->classes)+bias.
 
+  transformer_head  the last position-wise sublayers of a Transformer decoder (Section 4 trains the
+             Transformer of Vaswani et al.; base size: d_model 512, d_ff 2048, vocabulary 32768): the
+             feed-forward sublayer W2 relu(W1 h + b1) + b2 with its residual connection and
+             post-LayerNorm, then the output projection onto the vocabulary (no bias).  Input: the
+             hidden states h, one row per target token, as a [rows, 1, 1, d_model] tensor (the dense
+             layers are 1x1 convolutions over it).  The attention sublayers and the embeddings
+             are not part of it.
+
 An architecture is (param_table, ops).  param_table is an ordered list of
 (name, shape, kind, fan_in); ops is a list of dicts over integer tensor ids
 (tensor 0 is the input image batch, the last op writes the logits).
@@ -84,9 +92,16 @@ class Arch:
         self.ops.append(dict(op="gap", x=x, y=y, stored=True))
         return y
 
-    def linear(self, x, name, fin, fout):
+    def layernorm(self, x, name, c):
+        g = self._p(name + ".gamma", (c,), "bn_gamma")
+        b = self._p(name + ".beta", (c,), "bn_beta")
+        y = self._t()
+        self.ops.append(dict(op="layernorm", x=x, y=y, gamma=g, beta=b, stored=True))
+        return y
+
+    def linear(self, x, name, fin, fout, bias=True):
         w = self._p(name + ".w", (fout, fin), "linear_w", fin)
-        b = self._p(name + ".b", (fout,), "bias")
+        b = self._p(name + ".b", (fout,), "bias") if bias else None
         y = self._t()
         self.ops.append(dict(op="linear", x=x, y=y, w=w, b=b, stored=False))
         return y
@@ -159,6 +174,16 @@ def resnet50(classes=1000, widths=(64, 128, 256, 512), blocks=(3, 4, 6, 3), stem
     return a
 
 
+def transformer_head(d_model=512, d_ff=2048, vocab=32768):
+    a = Arch("transformer_head")
+    u = a.conv(0, "ffn.w1", d_model, d_ff, 1, 1, 0, bias=True)
+    u = a.relu(u)
+    u = a.conv(u, "ffn.w2", d_ff, d_model, 1, 1, 0, bias=True)
+    t = a.layernorm(a.add(u, 0), "ffn.ln", d_model)
+    a.linear(t, "proj", d_model, vocab, bias=False)
+    return a
+
+
 def forward(arch, params, x, store=None):
     """Training-mode forward.  params: dict name -> float64 array.  Returns (logits, tape).
     store: optional function applied to the tensors a reduced-precision pipeline keeps in memory."""
@@ -181,8 +206,12 @@ def forward(arch, params, x, store=None):
             T[o["y"]], cache[i] = L.maxpool_forward(T[o["x"]], o["k"], o["stride"], o["pad"])
         elif k == "gap":
             T[o["y"]] = L.gap_forward(T[o["x"]])
+        elif k == "layernorm":
+            T[o["y"]], cache[i] = L.layernorm_forward(T[o["x"]], params[o["gamma"]], params[o["beta"]])
         elif k == "linear":
-            T[o["y"]] = L.linear_forward(T[o["x"]], params[o["w"]], params[o["b"]])
+            xin = T[o["x"]]
+            T[o["y"]] = L.linear_forward(xin.reshape(xin.shape[0], -1), params[o["w"]],
+                                         params[o["b"]] if o["b"] else None)
         else:
             raise ValueError(k)
     return T[arch.ops[-1]["y"]], (T, cache)
@@ -223,8 +252,15 @@ def backward(arch, params, tape, dlogits):
             acc(o["x"], L.maxpool_backward(T[o["x"]].shape, cache[i], dy, o["k"], o["stride"], o["pad"]))
         elif k == "gap":
             acc(o["x"], L.gap_backward(T[o["x"]].shape, dy))
-        elif k == "linear":
-            dx, dw, db = L.linear_backward(T[o["x"]], params[o["w"]], dy, True)
-            grads[o["w"]], grads[o["b"]] = dw, db
+        elif k == "layernorm":
+            dx, dg, db = L.layernorm_backward(dy, params[o["gamma"]], cache[i])
+            grads[o["gamma"]], grads[o["beta"]] = dg, db
             acc(o["x"], dx)
+        elif k == "linear":
+            xin = T[o["x"]]
+            dx, dw, db = L.linear_backward(xin.reshape(xin.shape[0], -1), params[o["w"]], dy, o["b"] is not None)
+            grads[o["w"]] = dw
+            if o["b"]:
+                grads[o["b"]] = db
+            acc(o["x"], dx.reshape(xin.shape))
     return grads

@@ -171,8 +171,13 @@ def _torch_forward(arch, params, x):
             T[o["y"]] = F.max_pool2d(T[o["x"]], o["k"], o["stride"], o["pad"])
         elif k == "gap":
             T[o["y"]] = T[o["x"]].mean(dim=(2, 3))
+        elif k == "layernorm":      # over the channel axis (axis 1 in this NCHW view)
+            t = T[o["x"]].permute(0, 2, 3, 1)
+            t = F.layer_norm(t, t.shape[-1:], params[o["gamma"]], params[o["beta"]], 1e-5)
+            T[o["y"]] = t.permute(0, 3, 1, 2)
         elif k == "linear":
-            T[o["y"]] = F.linear(T[o["x"]], params[o["w"]], params[o["b"]])
+            xin = T[o["x"]]
+            T[o["y"]] = F.linear(xin.reshape(xin.shape[0], -1), params[o["w"]], params[o["b"]] if o["b"] else None)
     return T[arch.ops[-1]["y"]]
 
 
@@ -180,6 +185,7 @@ ARCHS = {
     "tiny_cnn": (lambda: nets.tiny_cnn(), (8, 32, 32, 3), 10),
     "resnet20_small": (lambda: nets.resnet20(classes=10, widths=(4, 8, 16), blocks=(2, 1, 1)), (6, 16, 16, 3), 10),
     "resnet50_small": (lambda: nets.resnet50(classes=7, widths=(4, 8, 8, 16), blocks=(2, 1, 1, 1), stem=8), (4, 40, 40, 3), 7),
+    "transformer_head_small": (lambda: nets.transformer_head(d_model=8, d_ff=24, vocab=13), (9, 1, 1, 8), 13),
 }
 
 
@@ -228,11 +234,12 @@ def test_step_matches_library_autograd(name, dist):
     np.testing.assert_allclose(out["theta"], w_ref, atol=1e-11)
 
 
-@pytest.mark.parametrize("name", ["tiny_cnn", "resnet20_small", "resnet50_small"])
+@pytest.mark.parametrize("name", ["tiny_cnn", "resnet20_small", "resnet50_small", "transformer_head_small"])
 def test_step_gradient_by_finite_differences(name):
     mk, xs, classes = ARCHS[name]
     arch = mk()
-    xs = (3, 12, 12, 3) if name != "resnet50_small" else (2, 36, 36, 3)
+    if name != "transformer_head_small":
+        xs = (3, 12, 12, 3) if name != "resnet50_small" else (2, 36, 36, 3)
     th = synth.he_init(arch.params, 1, jitter=0.1).astype(np.float64)
     thp = synth.he_init(arch.params, 2, jitter=0.1).astype(np.float64)
     x = synth.images(*xs, seed=0).astype(np.float64)
