@@ -62,13 +62,19 @@ enum { CD_BN_BATCH_STATS = 0, CD_BN_RUNNING = 1 };
 enum {
   CD_ARCH_TINY_CNN = 0,          /* conv3x3(3->16)+b, ReLU, conv3x3(16->32)+b, ReLU, GAP, linear */
   CD_ARCH_RESNET_BASIC = 1,      /* CIFAR-style: 3x3 stem, basic blocks, projection shortcuts    */
-  CD_ARCH_RESNET_BOTTLENECK = 2  /* 7x7-s2 stem, 3x3-s2 max-pool, bottleneck blocks (x4)         */
+  CD_ARCH_RESNET_BOTTLENECK = 2, /* 7x7-s2 stem, 3x3-s2 max-pool, bottleneck blocks (x4)         */
+  CD_ARCH_TRANSFORMER_HEAD = 3   /* the last position-wise sublayers of a Transformer decoder (Section 4 trains the
+                                    Transformer of Vaswani et al.): h + W2 relu(W1 h + b1) + b2, LayerNorm, projection
+                                    onto the vocabulary without bias.  The input is the hidden state of every
+                                    target token, [rows][1][1][d_model]; the attention sublayers and the embeddings
+                                    are not part of it */
 };
 
 #define CD_MAX_STAGES 4
 #define CD_NAME_LEN 48
 
-/* host struct.  Input images always have 3 channels. */
+/* host struct.  Input images have 3 channels; CD_ARCH_TRANSFORMER_HEAD takes widths[0] = d_model input
+ * channels (in_h = in_w = 1), widths[1] = d_ff, classes = vocabulary size. */
 typedef struct {
   int32_t kind;                   /* CD_ARCH_*                                             */
   int32_t classes;                /* width of the logits                                   */
@@ -98,7 +104,8 @@ typedef struct cd_model cd_model; /* opaque host object */
 
 /* Fill *out with a preset: CD_ARCH_TINY_CNN (32x32, 10 classes), CD_ARCH_RESNET_BASIC
  * (ResNet-20: 32x32, widths 16/32/64, 3 blocks each, 10 classes), CD_ARCH_RESNET_BOTTLENECK
- * (ResNet-50: 224x224, widths 64..512, blocks 3/4/6/3, 1000 classes; Section 3). host. */
+ * (ResNet-50: 224x224, widths 64..512, blocks 3/4/6/3, 1000 classes; Section 3),
+ * CD_ARCH_TRANSFORMER_HEAD (d_model 512, d_ff 2048, vocabulary 32768: the base Transformer). host. */
 int codistill_arch_preset(int kind, cd_arch_desc* out);
 
 /* Build the host-side description (op list, parameter table) of a model.
@@ -118,7 +125,7 @@ int codistill_workspace_bytes(const cd_model* m, int64_t batch, int save_for_bac
  * z = f_params(x): training-mode forward pass (Algorithm 1: f_theta(x); Section 3: the
  * device runs one forward for its own model and one per stale peer, on the same minibatch).
  *   params      flat parameter buffer in the model's dtype (fp32 or bf16), declaration order
- *   x           [batch][in_h][in_w][3] in the model's dtype
+ *   x           [batch][in_h][in_w][3] ([batch][1][1][d_model] for CD_ARCH_TRANSFORMER_HEAD) in the model's dtype
  *   save_for_backward  1: keep in `workspace` what codistill_backward needs (local model);
  *                      0: keep nothing (peer model; its logits are constants)
  *   bn_mode     CD_BN_BATCH_STATS (CD_BN_RUNNING is rejected as unsupported)
@@ -202,15 +209,16 @@ int codistill_sgd_step(float* master_w, float* momentum_v, const float* grad, vo
 /* The fused op list and where each tensor lives inside a save_for_backward workspace, so that
  * tools and tests can read intermediate activations and activation gradients after a forward /
  * backward pair.  Tensor 0 is the input batch; the last op writes the logits (not in the workspace). */
-enum { CD_OP_CONV = 0, CD_OP_BN = 1, CD_OP_MAXPOOL = 2, CD_OP_GAP = 3, CD_OP_LINEAR = 4 };
+enum { CD_OP_CONV = 0, CD_OP_BN = 1, CD_OP_MAXPOOL = 2, CD_OP_GAP = 3, CD_OP_LINEAR = 4, CD_OP_LN = 5 };
 typedef struct {
   int32_t kind;            /* CD_OP_*                                                           */
   int32_t x, y;            /* input / output tensor ids                                         */
-  int32_t res;             /* CD_OP_BN: tensor added before the ReLU, else -1                   */
+  int32_t res;             /* CD_OP_BN: tensor added before the ReLU; CD_OP_LN: tensor added to x; else -1 */
   int32_t relu;            /* CD_OP_CONV (after the bias) and CD_OP_BN: ReLU fused into the op  */
   int32_t param_w, param_b;/* parameter indices: weight + bias, or BN scale + shift; -1 if none */
   int32_t k, stride, pad;  /* window of CD_OP_CONV / CD_OP_MAXPOOL                              */
-  int64_t stats_offset;    /* CD_OP_BN: byte offset of fp32 [4][C] = mean, invstd, scale, shift */
+  int64_t stats_offset;    /* CD_OP_BN: byte offset of fp32 [4][C] = mean, invstd, scale, shift;
+                              CD_OP_LN: of fp32 [batch][2] = mean, rstd per row                 */
 } cd_op_info;
 typedef struct {
   int32_t h, w, c;         /* per-sample shape; the tensor is [batch][h][w][c]                  */

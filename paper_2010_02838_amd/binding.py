@@ -18,7 +18,7 @@ CD_F32, CD_BF16 = 0, 1
 CD_DIST_MSE_LOGITS, CD_DIST_KL = 0, 1
 CD_MEAN_ALL, CD_MEAN_ROWS = 0, 1
 CD_BN_BATCH_STATS, CD_BN_RUNNING = 0, 1
-CD_ARCH_TINY_CNN, CD_ARCH_RESNET_BASIC, CD_ARCH_RESNET_BOTTLENECK = 0, 1, 2
+CD_ARCH_TINY_CNN, CD_ARCH_RESNET_BASIC, CD_ARCH_RESNET_BOTTLENECK, CD_ARCH_TRANSFORMER_HEAD = 0, 1, 2, 3
 CD_MAX_STAGES, CD_NAME_LEN, CD_LOSS_MAX_PEERS = 4, 48, 8
 KERNEL_CLASSES = ["conv_fprop", "conv_dgrad", "conv_wgrad", "norm", "glue", "linear", "loss", "sgd", "conv_fprop_narrow"]
 PARAM_KINDS = ["conv_w", "bias", "bn_gamma", "bn_beta", "linear_w"]
@@ -156,7 +156,7 @@ class Model:
         no, nt = _i64(), _i64()
         _check(lib.codistill_graph_size(self._h, ctypes.byref(no), ctypes.byref(nt)))
         ops, tensors = [], []
-        kinds = ["conv", "bn", "maxpool", "gap", "linear"]
+        kinds = ["conv", "bn", "maxpool", "gap", "linear", "layernorm"]
         for i in range(no.value):
             o = OpInfo()
             _check(lib.codistill_op_info(self._h, batch, i, ctypes.byref(o)))

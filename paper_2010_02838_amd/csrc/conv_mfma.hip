@@ -35,7 +35,8 @@ struct IgemmArgs {
   int pointwise;  // kh = kw = 1, stride 1, no padding (set by the launcher)
   int ntiles;
   uint32_t src_bytes, wt_bytes;
-  const bf16_t* bias;  // F32OUT kernels: per-column bias added to the fp32 output (nullable)
+  const bf16_t* bias;  // per-column bias added to the output (nullable)
+  int relu;            // bf16 output only: clamp at zero after the bias
   float* stat_partials;  // STATS kernels: [m-tiles][2][N] per-tile column sums and sums of squares
 };
 
@@ -111,7 +112,8 @@ __device__ inline int lds_off(int row, int cv) { return row * BK + ((cv ^ ((row 
 // registers, reads the fragments of tile kt+1 from LDS, writes tile kt+2 to LDS (its global loads
 // were issued two regions earlier) and issues the global loads of tile kt+4.  Nothing in a region
 // depends on anything else in it, so the matrix pipe stays busy at 1-2 waves per SIMD.
-// F32OUT: the output is fp32 [M][N] (+ bias), written straight from the accumulators (dense layers).
+// F32OUT: the output is fp32 [M][N] (dense layers that produce logits); like the bf16 output it is
+// transposed through LDS so that a store instruction writes whole 256-byte row segments.
 // STATS: the epilogue also emits, per m-tile, the column sums and sums of squares of the bf16 values
 // it writes: the BatchNorm that follows a convolution gets its batch statistics without re-reading
 // the tensor.
@@ -285,20 +287,68 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
 
   // accumulator layout: lane holds pixel column (lane % 32); register v holds channel
   // 8*(v/4) + 4*(lane/32) + v%4 of the 32x32 tile
-  if (F32OUT) {
-    float* dst = reinterpret_cast<float*>(a.dst);
+  // per-column bias: register v of tile i belongs to channel n0 + wn0 + 32 i + 8 (v / 4) + 4 (lane / 32) + v % 4
+  if (a.bias) {
 #pragma unroll
     for (int i = 0; i < TN; i++)
 #pragma unroll
-      for (int j = 0; j < TM; j++) {
-        const int m = m0 + wm0 + j * 32 + frow;
+      for (int g = 0; g < 4; g++) {
+        const int n = n0 + wn0 + i * 32 + 8 * g + 4 * (lane >> 5);
+        float bv[4];
 #pragma unroll
-        for (int v = 0; v < 16; v++) {
-          const int n = n0 + wn0 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-          if (m < M && n < a.N) dst[(int64_t)m * a.N + n] = acc[i][j][v] + (a.bias ? bf16_to_f32(a.bias[n]) : 0.f);
+        for (int q = 0; q < 4; q++) bv[q] = n + q < a.N ? bf16_to_f32(a.bias[n + q]) : 0.f;
+#pragma unroll
+        for (int j = 0; j < TM; j++)
+#pragma unroll
+          for (int q = 0; q < 4; q++) acc[i][j][4 * g + q] += bv[q];
+      }
+  }
+  if (F32OUT) {
+    // one 32-row tile row of the wave at a time: [32][WN] floats (+4 of padding) per wave
+    constexpr int FP = WN + 4;
+    static_assert(4 * 32 * FP * 4 <= SMEM, "fp32 staging fits the tile memory");
+    float* fst = reinterpret_cast<float*>(smem) + wave * 32 * FP;
+    float* dst = reinterpret_cast<float*>(a.dst);
+    constexpr int FLPR = WN / 4;       // lanes per output row (16-byte vectors)
+    constexpr int FRPP = 64 / FLPR;    // rows per store instruction
+    const int fr = lane / FLPR, fc = (lane % FLPR) * 4;
+    __syncthreads();  // the main loop's tiles are no longer read
+#pragma unroll
+    for (int j = 0; j < TM; j++) {
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int i = 0; i < TN; i++)
+#pragma unroll
+        for (int g = 0; g < 4; g++)
+          *reinterpret_cast<float4*>(fst + frow * FP + i * 32 + 8 * g + 4 * (lane >> 5)) =
+              make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int p = 0; p < 32 / FRPP; p++) {
+        const int row = p * FRPP + fr;
+        const int m = m0 + wm0 + j * 32 + row;
+        const int n = n0 + wn0 + fc;
+        if (m < M && n < a.N) {
+          const float4 v = *reinterpret_cast<const float4*>(fst + row * FP + fc);
+          float* dp = dst + ((int64_t)m * a.N + n);
+          if (n + 3 < a.N && (a.N & 3) == 0) {
+            *reinterpret_cast<float4*>(dp) = v;
+          } else {  // ragged or unaligned row ends
+            const float e[4] = {v.x, v.y, v.z, v.w};
+            for (int q = 0; q < 4 && n + q < a.N; q++) dp[q] = e[q];
+          }
         }
       }
+    }
     return;
+  }
+  if (a.relu) {
+#pragma unroll
+    for (int i = 0; i < TN; i++)
+#pragma unroll
+      for (int j = 0; j < TM; j++)
+#pragma unroll
+        for (int v = 0; v < 16; v++) acc[i][j][v] = fmaxf(acc[i][j][v], 0.f);
   }
   // ---- epilogue: fp32 -> bf16, transpose through LDS, 16-byte stores along the channels -------------
   bf16_t* stage = reinterpret_cast<bf16_t*>(smem) + wave * EROWS * EPITCH;
@@ -455,7 +505,7 @@ bool conv_mfma_supported(const ConvGeom& g) {
 void linear_fwd_mfma(const bf16_t* x, const bf16_t* w, const bf16_t* bias, float* y, int64_t B, int F, int C,
                      hipStream_t s) {
   IgemmArgs a;
-  a.src = x; a.wt = w; a.dst = reinterpret_cast<bf16_t*>(y); a.bias = bias; a.stat_partials = nullptr;
+  a.src = x; a.wt = w; a.dst = reinterpret_cast<bf16_t*>(y); a.bias = bias; a.relu = 0; a.stat_partials = nullptr;
   a.M = B; a.N = C; a.K = F;
   a.Hs = 1; a.Ws = 1; a.Cs = F; a.Hd = 1; a.Wd = 1; a.kh = 1; a.kw = 1; a.stride = 1; a.pad = 0; a.pad_w = 0;
   a.omul = 0; a.ooff_h = a.ooff_w = 0; a.Ho = a.Wo = 1;
@@ -468,10 +518,11 @@ void linear_fwd_mfma(const bf16_t* x, const bf16_t* w, const bf16_t* bias, float
                      a);
 }
 
-int conv_fprop_mfma(const bf16_t* x, const bf16_t* w, bf16_t* y, const ConvGeom& g, float* stat_partials,
-                    hipStream_t s) {
+int conv_fprop_mfma(const bf16_t* x, const bf16_t* w, const bf16_t* bias, bool relu, bf16_t* y, const ConvGeom& g,
+                    float* stat_partials, hipStream_t s) {
   IgemmArgs a;
-  a.bias = nullptr;
+  a.bias = bias;
+  a.relu = relu ? 1 : 0;
   a.stat_partials = stat_partials;
   a.src = x; a.wt = w; a.dst = y;
   a.M = g.M(); a.N = g.Cout; a.K = g.K();
@@ -507,6 +558,7 @@ void conv_dgrad_mfma(const bf16_t* dy, const bf16_t* w, bf16_t* wt, bf16_t* dx, 
                      hipStream_t s) {
   IgemmArgs a;
   a.bias = nullptr;
+  a.relu = 0;
   a.stat_partials = nullptr;
   a.src = dy; a.dst = dx;
   a.N = g.Cin;

@@ -43,6 +43,17 @@ void bn_backward(int dtype, const void* dy, const void* y, const void* x, const 
                  bool relu, void* dx, bool acc_dx, void* dres, bool acc_dres, float* dgamma, float* dbeta,
                  float* coef, float* partials, const uint8_t* relu_mask, int64_t M, int C, hipStream_t s);
 
+// LayerNorm over the last axis of [rows][d] (biased variance, eps 1e-5) of a + r (r nullable):
+// y = gamma * xhat + beta.  stats: [rows][2] fp32 = mean, rstd (kept for the backward pass).
+void ln_forward(int dtype, const void* a, const void* r, const void* gamma, const void* beta, void* y, float* stats,
+                int64_t rows, int d, hipStream_t s);
+// dx = rstd * (g - mean(g) - xhat * mean(g * xhat)) with g = dy * gamma goes to da and dr (each nullable,
+// each added to its old contents if its acc flag is set); dgamma = sum dy * xhat, dbeta = sum dy.
+// partials: room for 1024 * 2 * d floats.
+void ln_backward(int dtype, const void* dy, const void* a, const void* r, const void* gamma, const float* stats, void* da,
+                 bool acc_a, void* dr, bool acc_r, float* dgamma, float* dbeta, float* partials, int64_t rows, int d,
+                 hipStream_t s);
+
 // argmax: optional [B][Ho][Wo][C] bytes, the window tap (r*k+s) of the first maximum; written by the
 // forward pass and, when given, used by the backward pass instead of rescanning the windows
 void maxpool_fwd(int dtype, const void* x, void* y, uint8_t* argmax, int64_t B, int H, int W, int C, int k, int stride,
@@ -68,8 +79,9 @@ bool conv_mfma_supported(const ConvGeom& g);
 // y[M][Cout] = im2col(x)[M][K] * w[Cout][K]^T.  With stat_partials the kernel also writes per-tile
 // column sums and sums of squares, [chunks][2][Cout] fp32, and returns the number of chunks
 // (needs (M/128 + 1) * 2 * Cout floats); see bn_forward_partials.
-int conv_fprop_mfma(const bf16_t* x, const bf16_t* w, bf16_t* y, const ConvGeom& g, float* stat_partials,
-                    hipStream_t s);
+// bias (nullable, [Cout] bf16) is added and, with relu, the result clamped at zero before rounding.
+int conv_fprop_mfma(const bf16_t* x, const bf16_t* w, const bf16_t* bias, bool relu, bf16_t* y, const ConvGeom& g,
+                    float* stat_partials, hipStream_t s);
 // whether conv_fprop_mfma runs this shape with its 256x128 tile (a different kernel than the 128x128 one)
 bool conv_fprop_tall_tile(const ConvGeom& g);
 // dx[B*H*W][Cin] (+)= gather(dy)[.][taps*Cout] * wt[Cin][taps*Cout]^T.  w is the filter as stored; wt is

@@ -383,6 +383,7 @@ __global__ void __launch_bounds__(256) linear_dw_k(const float* __restrict__ dy,
     for (int64_t b = 0; b < B; b++) acc += dy[b * C + c] * Cvt<T>::ld(x[b * F + f]);
     dw[(int64_t)c * F + f] = acc;
   } else {
+    if (!db) return;
     for (int64_t b = 0; b < B; b++) acc += dy[b * C + c];
     db[c] = acc;
   }

@@ -6,7 +6,7 @@
 
 namespace cd {
 
-enum OpKind { OP_CONV, OP_BN, OP_MAXPOOL, OP_GAP, OP_LINEAR };
+enum OpKind { OP_CONV, OP_BN, OP_MAXPOOL, OP_GAP, OP_LINEAR, OP_LN };
 
 struct TensorDesc {
   int h = 1, w = 1, c = 1;  // per-sample shape; a [B, F] tensor has h = w = 1
@@ -17,7 +17,7 @@ struct TensorDesc {
 struct Op {
   OpKind kind;
   int x = -1, y = -1;  // input / output tensor ids
-  int res = -1;        // OP_BN: tensor added before the ReLU (-1: none)
+  int res = -1;        // OP_BN: tensor added before the ReLU; OP_LN: tensor added to x (-1: none)
   bool relu = false;   // OP_CONV (after the bias) and OP_BN
   int pw = -1, pb = -1;  // parameter indices: conv/linear weight + bias, BN gamma + beta
   int k = 1, stride = 1, pad = 0;
@@ -38,7 +38,8 @@ struct Plan {
   bool save = false;
   std::vector<size_t> act;    // byte offset of every tensor's activation (tensor 0 unused)
   std::vector<size_t> grad;   // byte offset of every tensor's gradient (save only)
-  std::vector<size_t> aux;    // per op: max-pool argmax bytes (save only), 0 = none
+  std::vector<size_t> aux;    // per op (save only): max-pool argmax bytes, ReLU sign bits of a BatchNorm,
+                              // per-row mean and rstd of a LayerNorm; 0 = none
   size_t bn_stats = 0;        // per BN slot: mean[C], invstd[C], scale[C], shift[C] fp32
   size_t bn_coef = 0;         // backward coefficients c1,c2,c3 [3][Cmax] fp32
   size_t partials = 0;        // reduction partials / split-K partials

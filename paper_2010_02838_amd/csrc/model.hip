@@ -77,12 +77,20 @@ struct Builder {
     m->ops.push_back(o);
     return o.y;
   }
-  int linear(int x, const std::string& n, int fin, int fout) {
+  int ln(int x, int res, int pg, int pb) {
+    const TensorDesc tx = m->tensors[x];
+    Op o;
+    o.kind = OP_LN; o.x = x; o.res = res; o.pw = pg; o.pb = pb;
+    o.y = add_tensor(tx.h, tx.w, tx.c);
+    m->ops.push_back(o);
+    return o.y;
+  }
+  int linear(int x, const std::string& n, int fin, int fout, bool bias = true) {
     int64_t sh[2] = {fout, fin};
     Op o;
     o.kind = OP_LINEAR; o.x = x;
     o.pw = add_param(n + ".w", CD_P_LINEAR_W, 2, sh, fin);
-    o.pb = vec(n + ".b", CD_P_BIAS, fout);
+    o.pb = bias ? vec(n + ".b", CD_P_BIAS, fout) : -1;
     o.y = add_tensor(1, 1, fout, true);
     m->ops.push_back(o);
     return o.y;
@@ -97,6 +105,19 @@ void build_tiny(Builder& b, const cd_arch_desc& a) {
   t = b.conv(t, w2, b2, c2, 3, 1, 1, true);
   t = b.gap(t);
   b.linear(t, "fc", c2, a.classes);
+}
+
+// h + W2 relu(W1 h + b1) + b2 -> LayerNorm -> projection; the dense layers are 1x1 convolutions over
+// the [rows][1][1][d] tensor
+void build_transformer_head(Builder& b, const cd_arch_desc& a) {
+  const int d = a.widths[0], ff = a.widths[1];
+  int w1 = b.conv_w("ffn.w1", d, ff, 1), b1 = b.vec("ffn.w1.b", CD_P_BIAS, ff);
+  int t = b.conv(0, w1, b1, ff, 1, 1, 0, true);
+  int w2 = b.conv_w("ffn.w2", ff, d, 1), b2 = b.vec("ffn.w2.b", CD_P_BIAS, d);
+  t = b.conv(t, w2, b2, d, 1, 1, 0, false);
+  int g = b.vec("ffn.ln.gamma", CD_P_BN_GAMMA, d), be = b.vec("ffn.ln.beta", CD_P_BN_BETA, d);
+  t = b.ln(t, 0, g, be);
+  b.linear(t, "proj", d, a.classes, false);
 }
 
 struct BnP { int g, b; };
@@ -252,6 +273,7 @@ Plan make_plan(const cd_model* m, int64_t B, bool save) {
       // sign bits of a fused ReLU's output, one per element (bf16 vector path only)
       if (o.kind == OP_BN && o.relu && m->dtype == CD_BF16 && m->tensors[o.y].c % 8 == 0)
         p.aux[i] = alloc((size_t)B * m->tensors[o.y].per_sample() / 8);
+      if (o.kind == OP_LN) p.aux[i] = alloc((size_t)B * m->tensors[o.y].h * m->tensors[o.y].w * 2 * sizeof(float));
     }
   }
   p.total = off;
@@ -276,6 +298,9 @@ extern "C" int codistill_arch_preset(int kind, cd_arch_desc* out) {
     out->classes = 1000; out->in_h = out->in_w = 224; out->n_stages = 4; out->stem_width = 64;
     const int w[4] = {64, 128, 256, 512}, nb[4] = {3, 4, 6, 3};
     for (int i = 0; i < 4; i++) { out->widths[i] = w[i]; out->blocks[i] = nb[i]; }
+  } else if (kind == CD_ARCH_TRANSFORMER_HEAD) {
+    out->classes = 32768; out->in_h = out->in_w = 1; out->n_stages = 0;
+    out->widths[0] = 512; out->widths[1] = 2048;
   } else {
     return set_error(CD_ERR_INVALID_ARG, "arch_preset: unknown kind %d", kind);
   }
@@ -285,7 +310,8 @@ extern "C" int codistill_arch_preset(int kind, cd_arch_desc* out) {
 extern "C" int codistill_model_create(const cd_arch_desc* a, int dtype, cd_model** out) {
   CD_REQUIRE(a != nullptr && out != nullptr, "model_create: NULL pointer argument");
   CD_REQUIRE(dtype == CD_F32 || dtype == CD_BF16, "model_create: unknown dtype %d", dtype);
-  CD_REQUIRE(a->kind == CD_ARCH_TINY_CNN || a->kind == CD_ARCH_RESNET_BASIC || a->kind == CD_ARCH_RESNET_BOTTLENECK,
+  CD_REQUIRE(a->kind == CD_ARCH_TINY_CNN || a->kind == CD_ARCH_RESNET_BASIC || a->kind == CD_ARCH_RESNET_BOTTLENECK ||
+                 a->kind == CD_ARCH_TRANSFORMER_HEAD,
              "model_create: unknown architecture kind %d", a->kind);
   CD_REQUIRE(a->classes >= 1 && a->classes <= (1 << 24), "model_create: classes=%d out of range", a->classes);
   CD_REQUIRE(a->in_h >= 1 && a->in_w >= 1 && a->in_h <= 4096 && a->in_w <= 4096,
@@ -293,6 +319,10 @@ extern "C" int codistill_model_create(const cd_arch_desc* a, int dtype, cd_model
   if (a->kind == CD_ARCH_TINY_CNN) {
     CD_REQUIRE(a->widths[0] >= 1 && a->widths[1] >= 1 && a->widths[0] <= 4096 && a->widths[1] <= 4096,
                "model_create: tiny CNN widths out of range");
+  } else if (a->kind == CD_ARCH_TRANSFORMER_HEAD) {
+    CD_REQUIRE(a->widths[0] >= 1 && a->widths[1] >= 1 && a->widths[0] <= 16384 && a->widths[1] <= 65536,
+               "model_create: d_model / d_ff out of range");
+    CD_REQUIRE(a->in_h == 1 && a->in_w == 1, "model_create: the Transformer head takes [rows][1][1][d_model] inputs");
   } else {
     CD_REQUIRE(a->n_stages >= 1 && a->n_stages <= CD_MAX_STAGES, "model_create: n_stages=%d out of range", a->n_stages);
     CD_REQUIRE(a->stem_width >= 1 && a->stem_width <= 4096, "model_create: stem_width=%d out of range", a->stem_width);
@@ -304,9 +334,12 @@ extern "C" int codistill_model_create(const cd_arch_desc* a, int dtype, cd_model
   m->arch = *a;
   m->dtype = dtype;
   m->tensors.push_back(TensorDesc());
-  m->tensors[0].h = a->in_h; m->tensors[0].w = a->in_w; m->tensors[0].c = 3;
+  m->tensors[0].h = a->in_h; m->tensors[0].w = a->in_w;
+  m->tensors[0].c = a->kind == CD_ARCH_TRANSFORMER_HEAD ? a->widths[0] : 3;
   Builder b{m};
-  if (a->kind == CD_ARCH_TINY_CNN) build_tiny(b, *a); else build_resnet(b, *a);
+  if (a->kind == CD_ARCH_TINY_CNN) build_tiny(b, *a);
+  else if (a->kind == CD_ARCH_TRANSFORMER_HEAD) build_transformer_head(b, *a);
+  else build_resnet(b, *a);
   for (const TensorDesc& t : m->tensors) {
     if (t.h < 1 || t.w < 1) {
       delete m;
@@ -365,6 +398,7 @@ extern "C" int codistill_op_info(const cd_model* m, int64_t batch, int64_t idx, 
     Plan p = make_plan(m, batch, true);
     out->stats_offset = (int64_t)(p.bn_stats + (size_t)4 * m->bn_off[o.bn_slot] * sizeof(float));
   }
+  if (o.kind == OP_LN) out->stats_offset = (int64_t)make_plan(m, batch, true).aux[idx];
   return CD_OK;
 }
 
@@ -448,7 +482,7 @@ extern "C" int codistill_forward(const cd_model* m, const void* params, const vo
     switch (o.kind) {
       case OP_CONV: {
         ConvGeom g = conv_geom(m, o, batch);
-        if (use_mfma(m, g) && o.pb < 0 && !o.relu) {
+        if (use_mfma(m, g)) {
           const bf16_t* src = static_cast<const bf16_t*>(in);
           const bf16_t* w = static_cast<const bf16_t*>(c.P(o.pw));
           const ConvGeom gp = packed_geom(g);
@@ -470,7 +504,8 @@ extern "C" int codistill_forward(const cd_model* m, const void* params, const vo
           // a BatchNorm that follows directly gets its column sums from the convolution's epilogue
           const bool fuse = oi + 1 < m->ops.size() && m->ops[oi + 1].kind == OP_BN && m->ops[oi + 1].x == o.y &&
                             (size_t)(g.M() / 128 + 1 + 64) * 2 * g.Cout * sizeof(float) <= c.plan.partials_bytes;
-          stat_chunks = conv_fprop_mfma(src, w, static_cast<bf16_t*>(out), gp, fuse ? c.partials() : nullptr, c.s);
+          stat_chunks = conv_fprop_mfma(src, w, static_cast<const bf16_t*>(c.P(o.pb)), o.relu, static_cast<bf16_t*>(out), gp,
+                                        fuse ? c.partials() : nullptr, c.s);
           stat_tensor = fuse ? o.y : -1;
         } else {
           ProfScope pr(CD_K_CONV_FPROP_NARROW, c.s, 2.0 * g.M() * g.Cout * g.K(), conv_bytes(m, g));
@@ -490,6 +525,14 @@ extern "C" int codistill_forward(const cd_model* m, const void* params, const vo
           bn_forward(dt, in, c.P(o.pw), c.P(o.pb), o.res >= 0 ? c.act(o.res) : nullptr, o.relu, out, M, tx.c,
                      c.stats(o), c.partials(), mask, c.s);
         stat_tensor = -1;
+        break;
+      }
+      case OP_LN: {
+        const int64_t rows = batch * tx.h * tx.w;
+        const void* res = o.res < 0 ? nullptr : (o.res == 0 ? x : c.act(o.res));
+        ProfScope pr(CD_K_NORM, c.s, 0, (double)rows * tx.c * m->esize() * (2 + (res ? 1 : 0)));
+        ln_forward(dt, in, res, c.P(o.pw), c.P(o.pb), out,
+                   c.plan.aux[oi] ? reinterpret_cast<float*>(c.ws + c.plan.aux[oi]) : nullptr, rows, tx.c, c.s);
         break;
       }
       case OP_MAXPOOL: {
@@ -569,11 +612,11 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
         if (dt == CD_BF16 && !force_simple() && conv_mfma_supported(g)) {
           bf16_t* dzb = reinterpret_cast<bf16_t*>(c.ws + c.plan.lin_dz);
           cast_f32_bf16(dlogits, dzb, batch * C, c.s);
-          colsum(CD_F32, dlogits, batch, C, G(o.pb), c.partials(), c.s);
+          if (o.pb >= 0) colsum(CD_F32, dlogits, batch, C, G(o.pb), c.partials(), c.s);
           conv_wgrad_mfma(static_cast<const bf16_t*>(in), dzb, G(o.pw), g, c.partials(), c.plan.partials_bytes, c.s);
           conv_dgrad_mfma(dzb, static_cast<const bf16_t*>(c.P(o.pw)), c.wpack(), static_cast<bf16_t*>(dx), g, acc, c.s);
         } else {
-          linear_bwd(dt, in, c.P(o.pw), dlogits, dx, acc, G(o.pw), G(o.pb), batch, F, C, c.s);
+          linear_bwd(dt, in, c.P(o.pw), dlogits, dx, acc, G(o.pw), o.pb >= 0 ? G(o.pb) : nullptr, batch, F, C, c.s);
         }
         break;
       }
@@ -601,6 +644,17 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
         if (o.res >= 0) written[o.res] = 1;
         break;
       }
+      case OP_LN: {
+        const int64_t rows = batch * tx.h * tx.w;
+        const void* res = o.res < 0 ? nullptr : (o.res == 0 ? x : c.act(o.res));
+        void* dres = o.res > 0 ? c.grad(o.res) : nullptr;   // the input batch takes no gradient
+        const bool acc_res = o.res > 0 && written[o.res];
+        ProfScope pr(CD_K_NORM, c.s, 0, (double)rows * tx.c * m->esize() * (3 + (res ? 1 : 0) + (dres ? 1 : 0)));
+        ln_backward(dt, dy, in, res, c.P(o.pw), reinterpret_cast<const float*>(c.ws + c.plan.aux[i]), dx, acc, dres,
+                    acc_res, G(o.pw), G(o.pb), c.partials(), rows, tx.c, c.s);
+        if (o.res > 0) written[o.res] = 1;
+        break;
+      }
       case OP_CONV: {
         ConvGeom g = conv_geom(m, o, batch);
         if (o.relu) {
@@ -611,7 +665,7 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
           ProfScope pr(CD_K_GLUE, c.s, 0, (double)g.M() * g.Cout * m->esize());
           colsum(dt, dy, g.M(), g.Cout, G(o.pb), c.partials(), c.s);
         }
-        const bool mf = use_mfma(m, g) && o.pb < 0 && !o.relu;
+        const bool mf = use_mfma(m, g);
         {
           hipStream_t ws_ = c.s;
           float* wpart = c.partials();

@@ -19,7 +19,7 @@ def norm_err(a, b):
 class Case:
     """Inputs of one codistillation step for an architecture (library preset kwargs + oracle arch)."""
 
-    def __init__(self, arch_kw, ref_arch, dtype_name, batch, res, classes, jitter=0.1, v_scale=0.0):
+    def __init__(self, arch_kw, ref_arch, dtype_name, batch, res, classes, jitter=0.1, v_scale=0.0, in_c=3):
         from paper_2010_02838_amd import binding as B
         self.B = B
         self.dtype = B.CD_BF16 if dtype_name == "bf16" else B.CD_F32
@@ -30,20 +30,20 @@ class Case:
         table = self.model.param_table()
         assert table == [(n, tuple(s), k, f) for n, s, k, f in ref_arch.params]
         self.th, self.thp = synth.he_init(table, 1, jitter), synth.he_init(table, 2, jitter)
-        self.x, self.y = synth.images(batch, res, res, 3, seed=0), synth.labels(batch, classes, seed=3)
+        self.x, self.y = synth.images(batch, res, res, in_c, seed=0), synth.labels(batch, classes, seed=3)
         if self.dtype == B.CD_BF16:   # both sides consume the same bf16-rounded weights and images
             self.th, self.thp, self.x = (synth.round_bf16(a) for a in (self.th, self.thp, self.x))
         self.v0 = None
         if v_scale:
             self.v0 = (np.random.default_rng(5).standard_normal(self.th.size) * v_scale).astype(np.float32)
 
-    def oracle(self, alpha=1.0, lr=0.1, mu=0.9, wd=0.0, dist="mse", store=None):
+    def oracle(self, alpha=1.0, lr=0.1, mu=0.9, wd=0.0, dist="mse", store=None, label_smoothing=0.0):
         return codistill_step(self.ref_arch, self.th.astype(np.float64), [self.thp.astype(np.float64)],
                               self.x.astype(np.float64), self.y, alpha, lr, mu,
                               v=None if self.v0 is None else self.v0.astype(np.float64), weight_decay=wd, dist=dist,
-                              store=store)
+                              store=store, label_smoothing=label_smoothing)
 
-    def gpu(self, alpha=1.0, lr=0.1, mu=0.9, wd=0.0, dist="mse"):
+    def gpu(self, alpha=1.0, lr=0.1, mu=0.9, wd=0.0, dist="mse", label_smoothing=0.0):
         from paper_2010_02838_amd.runner import StepRunner, pack_flat, unpack_flat, to_device
         B, model = self.B, self.model
         r = StepRunner(model, [self.peer], self.batch)
@@ -51,7 +51,8 @@ class Case:
                None if self.v0 is None else pack_flat(model, self.v0))
         xd = to_device(self.x, model.torch_dtype)
         yd = torch.from_numpy(self.y).to("cuda:0")
-        r.step(xd, yd, alpha, lr, mu, weight_decay=wd, dist_kind=B.CD_DIST_KL if dist == "kl" else B.CD_DIST_MSE_LOGITS)
+        r.step(xd, yd, alpha, lr, mu, weight_decay=wd, label_smoothing=label_smoothing,
+               dist_kind=B.CD_DIST_KL if dist == "kl" else B.CD_DIST_MSE_LOGITS)
         torch.cuda.synchronize()
         got = dict(logits=r.logits.cpu().numpy(), peer_logits=r.peer_logits[0].cpu().numpy(),
                    loss=r.loss.cpu().numpy()[:3].astype(np.float64), dz=r.dz.cpu().numpy(),

@@ -163,15 +163,34 @@ def check_layers(c, got):
         elif o["kind"] == "gap":
             note("act", rel(y.reshape(c.batch, -1), L.gap_forward(x)), tag, tol_t)
             contribute(o["x"], L.gap_backward(x.shape, dy.reshape(c.batch, -1)))
+        elif o["kind"] == "layernorm":
+            s = x + act(o["res"]) if o["res"] >= 0 else x
+            yr, cache = L.layernorm_forward(s, w, b)
+            stats = c.read(o["stats_offset"], (c.batch * x.shape[1] * x.shape[2], 2), f32=True)
+            mean = s.mean(axis=-1).reshape(-1)
+            note("stats", float(np.abs(stats[:, 0] - mean).max() / np.sqrt((s ** 2).mean())), tag + ".mean", 1e-5)
+            note("stats", rel(stats[:, 1], cache[1].reshape(-1)), tag + ".rstd", 1e-4)
+            note("act", rel(y, yr), tag, tol_t)
+            dx, dg, db = L.layernorm_backward(dy, w, cache)
+            note("pgrad", rel(G[names[o["param_w"]]], dg), tag + ".gamma", TOL_F32_TENSOR)
+            note("pgrad", rel(G[names[o["param_b"]]], db), tag + ".beta", TOL_F32_TENSOR)
+            contribute(o["x"], dx)
+            if o["res"] >= 0:
+                contribute(o["res"], dx)
         elif o["kind"] == "linear":
             x2 = x.reshape(c.batch, -1)
             note("act", rel(y, L.linear_forward(x2, w, b)), tag, 2e-5 if f32 else 1e-4)
-            dx, dw, db = L.linear_backward(x2, w, dy, True)
+            dx, dw, db = L.linear_backward(x2, w, dy, b is not None)
             # the bf16 model's dense-layer backward runs on the MFMA kernels from a bf16 copy of d loss / d logits
             note("pgrad", rel(G[names[o["param_w"]]], dw), tag + ".w", TOL_F32_TENSOR if f32 else TOL_BF16_TENSOR)
-            note("pgrad", rel(G[names[o["param_b"]]], db), tag + ".b", TOL_F32_TENSOR)
+            if b is not None:
+                note("pgrad", rel(G[names[o["param_b"]]], db), tag + ".b", TOL_F32_TENSOR)
             contribute(o["x"], dx.reshape(x.shape))
+    # the backward pass of a convolution with a fused ReLU masks the stored gradient of its output in place
+    masked = {o["y"] for o in ops if o["kind"] == "conv" and o["relu"]}
     for t, g in expected.items():
+        if t in masked:
+            g = L.relu_backward(act(t), g)
         note("agrad", rel(grad(t), g), "grad of tensor %d" % t, tol_t)
     print("layer parity, worst relative errors:", worst)
     return worst
