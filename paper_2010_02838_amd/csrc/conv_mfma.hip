@@ -33,6 +33,7 @@ struct IgemmArgs {
   int omul, ooff_h, ooff_w, Ho, Wo;
   int accumulate;
   int pointwise;  // kh = kw = 1, stride 1, no padding (set by the launcher)
+  int group_m;    // > 1: tile order in groups of this many row tiles (set by the launcher)
   int ntiles;
   uint32_t src_bytes, wt_bytes;
   const bf16_t* bias;  // per-column bias added to the output (nullable)
@@ -142,8 +143,20 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
   const int wm0 = (wave % WAVES_M) * WM, wn0 = (wave / WAVES_M) * WN;
   const unsigned tile = xcd_remap(blockIdx.x, gridDim.x);
   // row and element indices fit 32 bits: every operand is smaller than 2 GiB (conv_mfma_supported)
-  const int m0 = (int)(tile / (unsigned)a.ntiles) * BM;
-  const int n0 = (int)(tile % (unsigned)a.ntiles) * BN;
+  unsigned tm = tile / (unsigned)a.ntiles, tn = tile % (unsigned)a.ntiles;
+  if (a.group_m > 1) {
+    // Wide outputs (a filter matrix that does not fit an L2): tiles run down groups of group_m row
+    // tiles before moving to the next column tile, so that the workgroups resident at one time share
+    // a few filter tiles and a few activation tiles instead of sweeping the whole filter matrix.
+    const unsigned per = (unsigned)a.group_m * (unsigned)a.ntiles;
+    const unsigned grp = tile / per, loc = tile - grp * per;
+    const unsigned mt = (unsigned)((a.M + BM - 1) / BM);
+    const unsigned gm = mt - grp * a.group_m < (unsigned)a.group_m ? mt - grp * a.group_m : (unsigned)a.group_m;
+    tm = grp * a.group_m + loc % gm;
+    tn = loc / gm;
+  }
+  const int m0 = (int)tm * BM;
+  const int n0 = (int)tn * BN;
   const int M = (int)a.M;
   const rsrc_words_t rsrc = make_rsrc_words(a.src, a.src_bytes);
   const rsrc_words_t rwt = make_rsrc_words(a.wt, a.wt_bytes);
@@ -439,7 +452,7 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
       float s0 = 0.f, s1 = 0.f;
 #pragma unroll
       for (int w = 0; w < WAVES_M; w++) { s0 += red[(w * 2 + 0) * BN + tid]; s1 += red[(w * 2 + 1) * BN + tid]; }
-      const int64_t mt = tile / (unsigned)a.ntiles;
+      const int64_t mt = tm;
       a.stat_partials[(mt * 2 + 0) * a.N + n0 + tid] = s0;
       a.stat_partials[(mt * 2 + 1) * a.N + n0 + tid] = s1;
     }
@@ -463,6 +476,7 @@ template <int MODE, bool STATS, int NWRAP, bool REMAP>
 static int launch_igemm_w(IgemmArgs a, hipStream_t s) {
   a.pointwise = (a.kh == 1 && a.kw == 1 && a.stride == 1 && a.pad == 0 && a.pad_w == 0 && a.Hs == a.Hd &&
                  a.Ws == a.Wd) ? 1 : 0;
+  a.group_m = ((int64_t)a.N * a.K * 2 > (4 << 20) && a.N >= 2048) ? 8 : 1;   // filter matrix beyond an L2's 4 MiB
   // 128x128 tiles run three workgroups per compute unit (768 at a time), 256x128 tiles two (512): take
   // the taller tile when its last round of workgroups is clearly fuller.
   if (NWRAP == 1 && !REMAP && igemm_tall_tile(a.M, a.N)) {
@@ -511,6 +525,7 @@ void linear_fwd_mfma(const bf16_t* x, const bf16_t* w, const bf16_t* bias, float
   a.omul = 0; a.ooff_h = a.ooff_w = 0; a.Ho = a.Wo = 1;
   a.accumulate = 0;
   a.pointwise = 1;
+  a.group_m = ((int64_t)C * F * 2 > (4 << 20) && C >= 2048) ? 8 : 1;
   a.src_bytes = (uint32_t)(B * (int64_t)F * 2);
   a.wt_bytes = (uint32_t)((int64_t)C * F * 2);
   a.ntiles = (int)cdiv(C, 128);
@@ -876,12 +891,19 @@ void conv_wgrad_mfma(const bf16_t* x, const bf16_t* dy, float* dw, const ConvGeo
                        (int)splits);
 }
 
+// eight elements per thread (two 16-byte loads, one 16-byte store); the ragged tail element by element
 __global__ void __launch_bounds__(256) cast_f32_bf16_k(const float* __restrict__ in, bf16_t* __restrict__ out, int64_t n) {
-  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (i < n) out[i] = f32_to_bf16(in[i]);
+  const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 8;
+  if (i + 8 <= n) {
+    const float4 a = *reinterpret_cast<const float4*>(in + i), b = *reinterpret_cast<const float4*>(in + i + 4);
+    *reinterpret_cast<uint4*>(out + i) =
+        make_uint4(pack_bf16x2(a.x, a.y), pack_bf16x2(a.z, a.w), pack_bf16x2(b.x, b.y), pack_bf16x2(b.z, b.w));
+  } else {
+    for (int64_t j = i; j < n; j++) out[j] = f32_to_bf16(in[j]);
+  }
 }
-void cast_f32_bf16(const float* in, bf16_t* out, int64_t n, hipStream_t s) {
-  hipLaunchKernelGGL(cast_f32_bf16_k, dim3((unsigned)cdiv(n, 256)), dim3(256), 0, s, in, out, n);
+void cast_f32_bf16(const float* in, bf16_t* out, int64_t n, hipStream_t s) {   // in, out 16-byte aligned
+  hipLaunchKernelGGL(cast_f32_bf16_k, dim3((unsigned)cdiv(cdiv(n, 8), 256)), dim3(256), 0, s, in, out, n);
 }
 
 // ---- layout helpers ---------------------------------------------------------------------------------

@@ -292,9 +292,10 @@ __global__ void __launch_bounds__(1024) ln_finalize_k(const float* __restrict__ 
   dgamma[c] = s1;
 }
 
-// waves to launch: enough to fill the chip, few enough that the partials stay small
-static int ln_blocks(int64_t rows) {
-  int64_t waves = rows < 1024 ? rows : 1024;
+// waves to launch.  Backward: enough to fill the chip, few enough that the per-wave partials stay
+// small.  Forward: a wave per row up to 64 Ki waves (a row's load, reductions and store are serial).
+static int ln_blocks(int64_t rows, int64_t max_waves = 1024) {
+  int64_t waves = rows < max_waves ? rows : max_waves;
   return (int)cdiv(waves, 4);
 }
 
@@ -304,7 +305,7 @@ static void ln_forward_t(const T* a, const T* r, const T* gamma, const T* beta, 
   constexpr int V = LnVec<T>::N;
   const bool vec = d % V == 0 && aligned16(a) && aligned16(r) && aligned16(gamma) && aligned16(beta) && aligned16(y) &&
                    d <= 64 * 8 * V;
-  const dim3 grid(ln_blocks(rows)), block(256);
+  const dim3 grid(ln_blocks(rows, 65536)), block(256);
   if (!vec) {
     hipLaunchKernelGGL((ln_fwd_generic_k<T>), grid, block, 0, s, a, r, gamma, beta, y, stats, rows, d);
     return;
