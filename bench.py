@@ -93,6 +93,69 @@ def loss_kernel_cfg5(B, torch, dev, iters=20):
     return out
 
 
+def transformer_head(args, B, synth, StepRunner, pack_flat, to_device, torch, dev):
+    """One codistillation step of the Transformer output block (two models: d_model 512, d_ff 2048,
+    vocabulary 32768, bf16) on 8192 target tokens: hidden states ~ N(0,1), targets uniform, label
+    smoothing 0.1, alpha 1.  roofline: the fp32-output vocabulary projection (one launch per forward)."""
+    rows, d, vocab = 8192, 512, 32768
+    arch = B.arch_preset(B.CD_ARCH_TRANSFORMER_HEAD)
+    model, peer = B.Model(arch, B.CD_BF16), B.Model(arch, B.CD_BF16)
+    table = model.param_table()
+    r = StepRunner(model, [peer], rows, dev)
+    r.load(pack_flat(model, synth.he_init(table, 1)), [pack_flat(peer, synth.he_init(table, 2))])
+    x = to_device(synth.images(rows, 1, 1, d, seed=100), torch.bfloat16, dev)
+    y = torch.from_numpy(synth.labels(rows, vocab, seed=3)).to(dev)
+
+    def step():
+        r.step(x, y, 1.0, 0.1, 0.9, label_smoothing=0.1)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / args.steps * 1e3
+    loss = r.loss.cpu().numpy()
+    r.overlap_peers = False           # the timer pass keeps every launch on one stream
+    B.profile_reset()
+    B.profile_enable(True)
+    psteps = max(1, min(args.steps, 5))
+    for _ in range(psteps):
+        step()
+    torch.cuda.synchronize()
+    prof = B.profile_collect()
+    B.profile_enable(False)
+    lin = prof["linear"]
+    achieved = lin["flops"] / (lin["ms"] * 1e-3) / 1e12 if lin["ms"] > 0 else 0.0
+    hbm = {}
+    for k in ("norm", "loss", "sgd"):
+        if prof[k]["ms"] > 0:
+            hbm[k] = {"GB/s": prof[k]["bytes"] / (prof[k]["ms"] * 1e-3) / 1e9}
+            hbm[k]["frac"] = hbm[k]["GB/s"] / PEAK_HBM_GBS
+    return {
+        "metric": "codistill-step target tokens/sec on 1 MI355X (Transformer-base output block, 8192 tokens, vocab 32768)",
+        "value": rows / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "transformer_head_codistill_step", "rows": rows, "d_model": d, "d_ff": 2048, "vocab": vocab,
+                   "models": "2 x output block (local fwd+bwd+SGD, peer fwd)", "alpha": 1.0, "label_smoothing": 0.1,
+                   "distillation": "mse_logits"},
+        "loss": [float(v) for v in loss[:3]],
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "kernel": "igemm_kernel<0,128,128,2,2,true,false,1,false> (vocabulary projection, fp32 logits)",
+                     "flop_per_launch": lin["flops"] / max(lin["launches"], 1),
+                     "algorithmic_bytes_per_launch": lin["bytes"] / max(lin["launches"], 1),
+                     "launches_per_step": lin["launches"] / psteps,
+                     "avg_launch_us": lin["ms"] / max(lin["launches"], 1) * 1e3},
+        "kernel_class_ms_per_step": {k: round(v["ms"] / psteps, 4) for k, v in prof.items()},
+        "hbm_kernels": hbm,
+        "cpu_baseline": None,
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -100,6 +163,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--batch", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--workload", default="resnet50", choices=["resnet50", "transformer_head"],
+                    help="resnet50 (default): the headline metric.  transformer_head: the output block of the base "
+                         "Transformer (feed-forward sublayer, residual, LayerNorm, vocabulary projection) on 8192 target "
+                         "tokens, a separate JSON line with its own metric")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch a plain 1 GiB -> 1 GiB elementwise copy three times (the known-size "
                          "kernel that hardware-counter byte counts are scaled by)")
@@ -115,6 +182,9 @@ def main():
     from paper_2010_02838_amd.runner import StepRunner, pack_flat, to_device
 
     dev = "cuda:0"
+    if args.workload == "transformer_head":
+        print(json.dumps(transformer_head(args, B, synth, StepRunner, pack_flat, to_device, torch, dev)))
+        return
     if args.copy_calibration:
         a = torch.ones(1 << 28, device=dev)
         b = torch.empty_like(a)

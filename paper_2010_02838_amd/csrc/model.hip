@@ -548,7 +548,8 @@ extern "C" int codistill_forward(const cd_model* m, const void* params, const vo
       }
       case OP_LINEAR: {
         const int F = tx.c, C = m->tensors[o.y].c;
-        ProfScope pr(CD_K_LINEAR, c.s, 2.0 * batch * F * C, (double)m->esize() * ((double)batch * F + (double)F * C));
+        ProfScope pr(CD_K_LINEAR, c.s, 2.0 * batch * F * C,
+                     (double)m->esize() * ((double)batch * F + (double)F * C) + 4.0 * batch * C);
         if (dt == CD_BF16 && !force_simple() && F % 8 == 0 && (int64_t)F * C * 2 < (1LL << 31))
           linear_fwd_mfma(static_cast<const bf16_t*>(in), static_cast<const bf16_t*>(c.P(o.pw)),
                           static_cast<const bf16_t*>(c.P(o.pb)), static_cast<float*>(out), batch, F, C, c.s);
@@ -606,16 +607,25 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
     switch (o.kind) {
       case OP_LINEAR: {
         const int F = tx.c, C = m->tensors[o.y].c;
-        ProfScope pr(CD_K_LINEAR, c.s, 4.0 * batch * F * C, (double)m->esize() * ((double)batch * F + (double)F * C) * 2);
         ConvGeom g;  // the dense layer as a 1x1 convolution over a 1x1 image
         g.B = batch; g.H = g.W = g.Ho = g.Wo = 1; g.Cin = F; g.Cout = C; g.kh = g.kw = 1; g.stride = 1; g.pad = 0;
         if (dt == CD_BF16 && !force_simple() && conv_mfma_supported(g)) {
           bf16_t* dzb = reinterpret_cast<bf16_t*>(c.ws + c.plan.lin_dz);
-          cast_f32_bf16(dlogits, dzb, batch * C, c.s);
-          if (o.pb >= 0) colsum(CD_F32, dlogits, batch, C, G(o.pb), c.partials(), c.s);
-          conv_wgrad_mfma(static_cast<const bf16_t*>(in), dzb, G(o.pw), g, c.partials(), c.plan.partials_bytes, c.s);
-          conv_dgrad_mfma(dzb, static_cast<const bf16_t*>(c.P(o.pw)), c.wpack(), static_cast<bf16_t*>(dx), g, acc, c.s);
+          {
+            ProfScope pr(CD_K_GLUE, c.s, 0, (double)batch * C * (6.0 + (o.pb >= 0 ? 4.0 : 0.0)));
+            cast_f32_bf16(dlogits, dzb, batch * C, c.s);
+            if (o.pb >= 0) colsum(CD_F32, dlogits, batch, C, G(o.pb), c.partials(), c.s);
+          }
+          {
+            ProfScope pr(CD_K_CONV_WGRAD, c.s, 2.0 * batch * F * C, conv_bytes(m, g) + 2.0 * C * F);
+            conv_wgrad_mfma(static_cast<const bf16_t*>(in), dzb, G(o.pw), g, c.partials(), c.plan.partials_bytes, c.s);
+          }
+          {
+            ProfScope pr(CD_K_CONV_DGRAD, c.s, 2.0 * batch * F * C, conv_bytes(m, g));
+            conv_dgrad_mfma(dzb, static_cast<const bf16_t*>(c.P(o.pw)), c.wpack(), static_cast<bf16_t*>(dx), g, acc, c.s);
+          }
         } else {
+          ProfScope pr(CD_K_LINEAR, c.s, 4.0 * batch * F * C, (double)m->esize() * ((double)batch * F + (double)F * C) * 2);
           linear_bwd(dt, in, c.P(o.pw), dlogits, dx, acc, G(o.pw), o.pb >= 0 ? G(o.pb) : nullptr, batch, F, C, c.s);
         }
         break;
