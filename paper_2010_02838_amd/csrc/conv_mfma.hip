@@ -7,11 +7,11 @@
 //   wgrad  dw[n][k] = sum_m dy[m][n] * im2col(x)[m][k]
 //
 // fprop and dgrad share one kernel: both operands are contiguous along the contraction index, so
-// a lane's 8-element MFMA operand is one 16-byte load.  Block = 4 waves; global -> registers ->
-// LDS (double buffered, 80-byte row pitch: conflict-free 16-byte reads) -> MFMA; the fp32 tile is
-// rounded to bf16, transposed through LDS and written as full 16-byte vectors along the channels.
-// The MFMA "A" operand is the filter tile and "B" the activation tile, so that a lane's 16
-// accumulators run along the output channels of one pixel.
+// a lane's 8-element MFMA operand is one 16-byte load.  Block = 4 waves; buffer loads write global
+// memory straight into LDS (three stages of unpadded, XOR-swizzled 64-byte rows: conflict-free
+// 16-byte reads) -> MFMA; the fp32 tile is rounded to bf16, transposed through LDS and written as
+// full 16-byte vectors along the channels.  The MFMA "A" operand is the filter tile and "B" the
+// activation tile, so that a lane's 16 accumulators run along the output channels of one pixel.
 #include "kernels.h"
 
 namespace cd {
@@ -108,11 +108,10 @@ __device__ inline int lds_off(int row, int cv) { return row * BK + ((cv ^ ((row 
 // (The dgrad of a stride-2 convolution is run as four MODE 0 problems, one per parity of the output
 // pixel; see conv_dgrad_mfma.)
 //
-// The main loop is software pipelined by hand (the compiler cannot move work across the barrier): in
-// the region between two barriers a wave issues the MFMAs of tile kt from fragments already in
-// registers, reads the fragments of tile kt+1 from LDS, writes tile kt+2 to LDS (its global loads
-// were issued two regions earlier) and issues the global loads of tile kt+4.  Nothing in a region
-// depends on anything else in it, so the matrix pipe stays busy at 1-2 waves per SIMD.
+// Main loop: one barrier per 32-wide step.  At step kt the waves wait for their own loads of tile kt
+// (issued two steps earlier), meet at the barrier, issue the loads of tile kt+2 into the stage that
+// tile kt-1 occupied, read the fragments of tile kt and multiply.  The loads are inline assembly: the
+// compiler does not track them, so it cannot serialise them against the LDS reads.
 // F32OUT: the output is fp32 [M][N] (dense layers that produce logits); like the bf16 output it is
 // transposed through LDS so that a store instruction writes whole 256-byte row segments.
 // STATS: the epilogue also emits, per m-tile, the column sums and sums of squares of the bf16 values
