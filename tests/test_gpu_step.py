@@ -233,6 +233,14 @@ def compare_bf16(c, ref, floor, got):
     assert rel(got["theta"], ref["theta"]) <= max(2e-2, 2 * rel(floor["theta"], ref["theta"]))
 
 
+def test_tall_tile_convolutions_bf16_layers():
+    """One bottleneck block at 196 x 64 x 64: after the stem and the pool M = 196*16*16 = 50176 rows, and the
+    two 64 -> 256 convolutions have 784 tiles of 128x128, the case that is run on 256x128 tiles instead."""
+    c = Case(dict(kind=2, widths=[64], blocks=[1], stem_width=64),
+             nets.resnet50(classes=10, widths=(64,), blocks=(1,), stem=64), "bf16", 196, 64, 10)
+    check_layers(c, c.gpu())
+
+
 @pytest.mark.parametrize("name", list(SMALL))
 def test_small_resnet_bf16_layers(name):
     kw, mk, batch, res, classes = SMALL[name]
