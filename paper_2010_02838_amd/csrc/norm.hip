@@ -259,7 +259,9 @@ __global__ void __launch_bounds__(256) bn_apply_k(const T* __restrict__ x, const
                                                   uint8_t* __restrict__ mask) {
   const int vc = C / VEC;
   const int64_t stride = (int64_t)gridDim.x * 256;
-  const int64_t i0 = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  // last rows first: the producing convolution wrote them most recently, so they are the part of x
+  // that the caches still hold
+  const int64_t i0 = (int64_t)(gridDim.x - 1 - blockIdx.x) * 256 + threadIdx.x;
   float sc[VEC], sh[VEC];
   if (FIXC) {
     const int c0 = (int)(i0 % vc) * VEC;
