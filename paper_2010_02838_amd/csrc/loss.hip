@@ -106,6 +106,39 @@ __global__ void __launch_bounds__((TPR > 256 ? TPR : 256)) loss_row_kernel(LossA
       if (MODE) y[i] = x[i];
     }
   }
+  // Several peers (MSE only): the gradient needs z - mean_j z'_j and the loss sum_j (z - z'_j)^2, so each
+  // further peer is folded in as it arrives: its squared distance into a scalar, its logits into the
+  // running sum that takes the place of z'.  (One peer: sq_extra stays 0 and y is that peer.)
+  float sq_extra = 0.f;
+  const bool many = MODE == 1 && a.n_peers > 1;
+  if (many) {
+#pragma unroll
+    for (int i = 0; i < V; i++) {   // the first peer, already in y
+      int64_t c = ((int64_t)i * TPR + lane) * 4;
+      if (c < cols) {
+        const float d0 = x[i].x - y[i].x, d1 = x[i].y - y[i].y, d2 = x[i].z - y[i].z, d3 = x[i].w - y[i].w;
+        sq_extra += d0 * d0 + d1 * d1 + d2 * d2 + d3 * d3;
+      }
+    }
+    for (int j = 1; j < a.n_peers; j++) {
+      const float* __restrict__ pj = a.zp[j] + row * cols;
+#pragma unroll
+      for (int i = 0; i < V; i++) {
+        int64_t c = ((int64_t)i * TPR + lane) * 4;
+        if (c < cols) {
+          const float4 t = *reinterpret_cast<const float4*>(pj + c);
+          const float d0 = x[i].x - t.x, d1 = x[i].y - t.y, d2 = x[i].z - t.z, d3 = x[i].w - t.w;
+          sq_extra += d0 * d0 + d1 * d1 + d2 * d2 + d3 * d3;
+          y[i].x += t.x; y[i].y += t.y; y[i].z += t.z; y[i].w += t.w;
+        }
+      }
+    }
+    const float inv_n = 1.f / (float)a.n_peers;
+#pragma unroll
+    for (int i = 0; i < V; i++) {   // y becomes the mean over the peers
+      y[i].x *= inv_n; y[i].y *= inv_n; y[i].z *= inv_n; y[i].w *= inv_n;
+    }
+  }
   int t;
   const bool valid = row_target(a, row, t);
   const int nvalid = a.meta[0];
@@ -143,7 +176,7 @@ __global__ void __launch_bounds__((TPR > 256 ? TPR : 256)) loss_row_kernel(LossA
         const float e = __expf(xv[k] - m);
         s[0] += e;
         s[1] += xv[k];
-        if (MODE == 1) { const float d = xv[k] - yv[k]; s[2] += d * d; yv[k] = d; }
+        if (MODE == 1) { const float d = xv[k] - yv[k]; s[2] += many ? 0.f : d * d; yv[k] = d; }
         if (MODE == 2) { const float ep = __expf(yv[k] - mp); s[2] += ep; s[3] += ep * (yv[k] - xv[k]); yv[k] = ep; }
         xv[k] = e;
       }
@@ -151,6 +184,7 @@ __global__ void __launch_bounds__((TPR > 256 ? TPR : 256)) loss_row_kernel(LossA
       if (MODE) y[i] = make_float4(yv[0], yv[1], yv[2], yv[3]);
     }
   }
+  s[2] += sq_extra;
   group_reduce<TPR, 4, 0u>(s, smem);
   const float lse = m + logf(s[0]);
   float lsep = 0.f;
@@ -367,7 +401,8 @@ extern "C" int codistill_loss_grad(const float* z_local, const float* const* z_p
   ProfScope prof(CD_K_LOSS, s, (double)rows * cols * 12.0, bytes);
   hipLaunchKernelGGL(loss_prep_kernel, dim3(1), dim3(1024), 0, s, a);
   const int mode = cfg->n_peers == 0 ? 0 : (cfg->dist_kind == CD_DIST_MSE_LOGITS ? 1 : 2);
-  const bool fast = cols % 4 == 0 && cols <= 32768 && cfg->n_peers <= 1;
+  // register-resident kernel: one peer, or several with the MSE term (folded into a running mean)
+  const bool fast = cols % 4 == 0 && cols <= 32768 && (cfg->n_peers <= 1 || mode == 1);
   if (!fast) {
     hipLaunchKernelGGL(loss_row_generic_kernel, dim3((unsigned)rows), dim3(256), 0, s, a);
   } else if (cols <= 256) launch_rows<64, 1>(a, mode, s);

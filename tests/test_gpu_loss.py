@@ -88,6 +88,17 @@ def test_identical_peer_is_exactly_zero(cols, mode):
     np.testing.assert_array_equal(dz, dz0)
 
 
+@pytest.mark.parametrize("cols", [4096, 32768])
+def test_n_way_wide_rows(cols):
+    """Three peers at the widths of the register-resident kernel's larger groups (MSE folds the peers into a
+    running mean; the same shapes with KL take the multi-pass kernel)."""
+    z = synth.logits(24, cols, 3.0, seed=1)
+    peers = [synth.logits(24, cols, 3.0, seed=20 + j) for j in range(3)]
+    t = synth.labels(24, cols, seed=3)
+    for mode in MODES:
+        check(z, peers, t, 0.5, 0.1, mode)
+
+
 @pytest.mark.parametrize("mode", ["mse", "kl"])
 @pytest.mark.parametrize("npeers", [2, 3])
 def test_n_way(mode, npeers):
