@@ -20,4 +20,4 @@ the CPU tests (closed forms, invariants, brute force, finite differences and a
 library autograd cross-check); the accuracy / loss / BLEU figures printed in
 the paper need its datasets and full training runs and are "parity unpinned".
 """
-from . import loss, layers, nets, sgd, step  # noqa: F401
+from . import loss, layers, nets, sgd, step, driver  # noqa: F401
