@@ -33,11 +33,10 @@ struct IgemmArgs {
   int omul, ooff_h, ooff_w, Ho, Wo;
   int accumulate;
   int pointwise;  // kh = kw = 1, stride 1, no padding (set by the launcher)
-  int group_m;    // > 1: tile order in groups of this many row tiles (set by the launcher)
+  int group_m;    // GROUP kernels: tile order in groups of this many row tiles
   int ntiles;
   uint32_t src_bytes, wt_bytes;
-  const bf16_t* bias;  // per-column bias added to the output (nullable)
-  int relu;            // bf16 output only: clamp at zero after the bias
+  const bf16_t* bias;  // per-column bias added to the output (kernels with EPI >= 1)
   float* stat_partials;  // STATS kernels: [m-tiles][2][N] per-tile column sums and sums of squares
 };
 
@@ -120,8 +119,10 @@ __device__ inline int lds_off(int row, int cv) { return row * BK + ((cv ^ ((row 
 // NWRAP: 1 when the gathered tensor has at least 32 channels (a 32-element step crosses at most one
 // tap boundary), 4 for 8..31 channels.
 // REMAP: output rows are placed with the strided row map of IgemmArgs (parity class of a stride-2 dgrad).
+// EPI: 0 plain output, 1 per-column bias added, 2 bias and ReLU.  GROUP: grouped tile order (wide outputs).
+// Both are compile-time: the plain kernels pay nothing for them.
 template <int MODE, int BM, int BN, int WAVES_M, int WAVES_N, bool F32OUT = false, bool STATS = false, int NWRAP = 1,
-          bool REMAP = false>
+          bool REMAP = false, int EPI = 0, bool GROUP = false>
 __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   constexpr int TM = WM / 32, TN = WN / 32;
@@ -143,7 +144,7 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
   const unsigned tile = xcd_remap(blockIdx.x, gridDim.x);
   // row and element indices fit 32 bits: every operand is smaller than 2 GiB (conv_mfma_supported)
   unsigned tm = tile / (unsigned)a.ntiles, tn = tile % (unsigned)a.ntiles;
-  if (a.group_m > 1) {
+  if (GROUP) {
     // Wide outputs (a filter matrix that does not fit an L2): tiles run down groups of group_m row
     // tiles before moving to the next column tile, so that the workgroups resident at one time share
     // a few filter tiles and a few activation tiles instead of sweeping the whole filter matrix.
@@ -300,7 +301,7 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
   // accumulator layout: lane holds pixel column (lane % 32); register v holds channel
   // 8*(v/4) + 4*(lane/32) + v%4 of the 32x32 tile
   // per-column bias: register v of tile i belongs to channel n0 + wn0 + 32 i + 8 (v / 4) + 4 (lane / 32) + v % 4
-  if (a.bias) {
+  if (EPI >= 1) {
 #pragma unroll
     for (int i = 0; i < TN; i++)
 #pragma unroll
@@ -354,7 +355,7 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
     }
     return;
   }
-  if (a.relu) {
+  if (EPI == 2) {
 #pragma unroll
     for (int i = 0; i < TN; i++)
 #pragma unroll
@@ -471,14 +472,14 @@ static bool igemm_tall_tile(int64_t M, int N) {
 bool conv_fprop_tall_tile(const ConvGeom& g) { return g.Cin >= BK && igemm_tall_tile(g.M(), g.Cout); }
 
 // returns the number of m-tiles (= statistics chunks when STATS)
-template <int MODE, bool STATS, int NWRAP, bool REMAP>
+template <int MODE, bool STATS, int NWRAP, bool REMAP, int EPI>
 static int launch_igemm_w(IgemmArgs a, hipStream_t s) {
   a.pointwise = (a.kh == 1 && a.kw == 1 && a.stride == 1 && a.pad == 0 && a.pad_w == 0 && a.Hs == a.Hd &&
                  a.Ws == a.Wd) ? 1 : 0;
-  a.group_m = ((int64_t)a.N * a.K * 2 > (4 << 20) && a.N >= 2048) ? 8 : 1;   // filter matrix beyond an L2's 4 MiB
+  a.group_m = 1;
   // 128x128 tiles run three workgroups per compute unit (768 at a time), 256x128 tiles two (512): take
   // the taller tile when its last round of workgroups is clearly fuller.
-  if (NWRAP == 1 && !REMAP && igemm_tall_tile(a.M, a.N)) {
+  if (NWRAP == 1 && !REMAP && EPI == 0 && igemm_tall_tile(a.M, a.N)) {
     a.ntiles = (int)cdiv(a.N, 128);
     const int mt = (int)cdiv(a.M, 256);
     hipLaunchKernelGGL((igemm_kernel<MODE, 256, 128, 2, 2, false, STATS, 1, false>),
@@ -488,23 +489,23 @@ static int launch_igemm_w(IgemmArgs a, hipStream_t s) {
   if (a.N > 64 && g_tune_tile != 1) {
     a.ntiles = (int)cdiv(a.N, 128);
     const int mt = (int)cdiv(a.M, 128);
-    hipLaunchKernelGGL((igemm_kernel<MODE, 128, 128, 2, 2, false, STATS, NWRAP, REMAP>),
+    hipLaunchKernelGGL((igemm_kernel<MODE, 128, 128, 2, 2, false, STATS, NWRAP, REMAP, EPI>),
                        dim3((unsigned)((int64_t)mt * a.ntiles)), dim3(256), 0, s, a);
     return mt;
   }
   a.ntiles = (int)cdiv(a.N, 64);
   const int mt = (int)cdiv(a.M, 256);
   if (a.N > 32)
-    hipLaunchKernelGGL((igemm_kernel<MODE, 256, 64, 4, 1, false, STATS, NWRAP, REMAP>),
+    hipLaunchKernelGGL((igemm_kernel<MODE, 256, 64, 4, 1, false, STATS, NWRAP, REMAP, EPI>),
                        dim3((unsigned)((int64_t)mt * a.ntiles)), dim3(256), 0, s, a);
   else
-    hipLaunchKernelGGL((igemm_kernel<MODE, 256, 32, 4, 1, false, STATS, NWRAP, REMAP>), dim3((unsigned)mt), dim3(256), 0,
-                       s, a);
+    hipLaunchKernelGGL((igemm_kernel<MODE, 256, 32, 4, 1, false, STATS, NWRAP, REMAP, EPI>), dim3((unsigned)mt), dim3(256),
+                       0, s, a);
   return mt;
 }
-template <int MODE, bool STATS, bool REMAP = false>
+template <int MODE, bool STATS, bool REMAP = false, int EPI = 0>
 static int launch_igemm(IgemmArgs a, hipStream_t s) {
-  return a.Cs >= BK ? launch_igemm_w<MODE, STATS, 1, REMAP>(a, s) : launch_igemm_w<MODE, STATS, 4, REMAP>(a, s);
+  return a.Cs >= BK ? launch_igemm_w<MODE, STATS, 1, REMAP, EPI>(a, s) : launch_igemm_w<MODE, STATS, 4, REMAP, EPI>(a, s);
 }
 
 bool conv_mfma_supported(const ConvGeom& g) {
@@ -518,25 +519,32 @@ bool conv_mfma_supported(const ConvGeom& g) {
 void linear_fwd_mfma(const bf16_t* x, const bf16_t* w, const bf16_t* bias, float* y, int64_t B, int F, int C,
                      hipStream_t s) {
   IgemmArgs a;
-  a.src = x; a.wt = w; a.dst = reinterpret_cast<bf16_t*>(y); a.bias = bias; a.relu = 0; a.stat_partials = nullptr;
+  a.src = x; a.wt = w; a.dst = reinterpret_cast<bf16_t*>(y); a.bias = bias; a.stat_partials = nullptr;
   a.M = B; a.N = C; a.K = F;
   a.Hs = 1; a.Ws = 1; a.Cs = F; a.Hd = 1; a.Wd = 1; a.kh = 1; a.kw = 1; a.stride = 1; a.pad = 0; a.pad_w = 0;
   a.omul = 0; a.ooff_h = a.ooff_w = 0; a.Ho = a.Wo = 1;
   a.accumulate = 0;
   a.pointwise = 1;
-  a.group_m = ((int64_t)C * F * 2 > (4 << 20) && C >= 2048) ? 8 : 1;
+  a.group_m = 8;
   a.src_bytes = (uint32_t)(B * (int64_t)F * 2);
   a.wt_bytes = (uint32_t)((int64_t)C * F * 2);
   a.ntiles = (int)cdiv(C, 128);
-  hipLaunchKernelGGL((igemm_kernel<0, 128, 128, 2, 2, true>), dim3((unsigned)(cdiv(B, 128) * a.ntiles)), dim3(256), 0, s,
-                     a);
+  const dim3 grid((unsigned)(cdiv(B, 128) * a.ntiles));
+  // a filter matrix beyond an L2's 4 MiB under a wide output: grouped tile order
+  const bool group = (int64_t)C * F * 2 > (4 << 20) && C >= 2048;
+  if (group) {
+    if (bias) hipLaunchKernelGGL((igemm_kernel<0, 128, 128, 2, 2, true, false, 1, false, 1, true>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((igemm_kernel<0, 128, 128, 2, 2, true, false, 1, false, 0, true>), grid, dim3(256), 0, s, a);
+  } else {
+    if (bias) hipLaunchKernelGGL((igemm_kernel<0, 128, 128, 2, 2, true, false, 1, false, 1, false>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((igemm_kernel<0, 128, 128, 2, 2, true, false, 1, false, 0, false>), grid, dim3(256), 0, s, a);
+  }
 }
 
 int conv_fprop_mfma(const bf16_t* x, const bf16_t* w, const bf16_t* bias, bool relu, bf16_t* y, const ConvGeom& g,
                     float* stat_partials, hipStream_t s) {
   IgemmArgs a;
   a.bias = bias;
-  a.relu = relu ? 1 : 0;
   a.stat_partials = stat_partials;
   a.src = x; a.wt = w; a.dst = y;
   a.M = g.M(); a.N = g.Cout; a.K = g.K();
@@ -546,6 +554,11 @@ int conv_fprop_mfma(const bf16_t* x, const bf16_t* w, const bf16_t* bias, bool r
   a.accumulate = 0; a.ntiles = 1;
   a.src_bytes = (uint32_t)(g.B * g.H * g.W * (int64_t)g.Cin * 2);
   a.wt_bytes = (uint32_t)((int64_t)g.Cout * g.K() * 2);
+  if (bias) {  // bias (+ ReLU) in the epilogue; no statistics variant (a BatchNorm follows bias-free convolutions)
+    if (stat_partials) return -1;
+    return relu ? launch_igemm<0, false, false, 2>(a, s) : launch_igemm<0, false, false, 1>(a, s);
+  }
+  if (relu) return -1;  // ReLU without bias does not occur in the supported graphs
   return stat_partials ? launch_igemm<0, true>(a, s) : launch_igemm<0, false>(a, s);
 }
 
@@ -572,7 +585,6 @@ void conv_dgrad_mfma(const bf16_t* dy, const bf16_t* w, bf16_t* wt, bf16_t* dx, 
                      hipStream_t s) {
   IgemmArgs a;
   a.bias = nullptr;
-  a.relu = 0;
   a.stat_partials = nullptr;
   a.src = dy; a.dst = dx;
   a.N = g.Cin;

@@ -482,7 +482,7 @@ extern "C" int codistill_forward(const cd_model* m, const void* params, const vo
     switch (o.kind) {
       case OP_CONV: {
         ConvGeom g = conv_geom(m, o, batch);
-        if (use_mfma(m, g)) {
+        if (use_mfma(m, g) && !(o.relu && o.pb < 0)) {   // (a fused ReLU comes with a bias in every graph built here)
           const bf16_t* src = static_cast<const bf16_t*>(in);
           const bf16_t* w = static_cast<const bf16_t*>(c.P(o.pw));
           const ConvGeom gp = packed_geom(g);
@@ -502,7 +502,7 @@ extern "C" int codistill_forward(const cd_model* m, const void* params, const vo
                        2.0 * g.M() * g.Cout * g.K(),
                        conv_bytes(m, g));
           // a BatchNorm that follows directly gets its column sums from the convolution's epilogue
-          const bool fuse = oi + 1 < m->ops.size() && m->ops[oi + 1].kind == OP_BN && m->ops[oi + 1].x == o.y &&
+          const bool fuse = o.pb < 0 && oi + 1 < m->ops.size() && m->ops[oi + 1].kind == OP_BN && m->ops[oi + 1].x == o.y &&
                             (size_t)(g.M() / 128 + 1 + 64) * 2 * g.Cout * sizeof(float) <= c.plan.partials_bytes;
           stat_chunks = conv_fprop_mfma(src, w, static_cast<const bf16_t*>(c.P(o.pb)), o.relu, static_cast<bf16_t*>(out), gp,
                                         fuse ? c.partials() : nullptr, c.s);
