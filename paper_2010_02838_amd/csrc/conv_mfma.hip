@@ -37,7 +37,7 @@ struct IgemmArgs {
   int ntiles;
   uint32_t src_bytes, wt_bytes;
   const bf16_t* bias;  // per-column bias added to the output (kernels with EPI >= 1)
-  float* stat_partials;  // STATS kernels: [m-tiles][2][N] per-tile column sums and sums of squares
+  float* stat_partials;  // STATS kernels: [m-tiles][stat_pitch(N)] per-tile column sums and sums of squares
 };
 
 int g_tune_tile = 0, g_tune_co = -1;  // tuning knobs of the microbenchmark
@@ -453,8 +453,8 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
 #pragma unroll
       for (int w = 0; w < WAVES_M; w++) { s0 += red[(w * 2 + 0) * BN + tid]; s1 += red[(w * 2 + 1) * BN + tid]; }
       const int64_t mt = tm;
-      a.stat_partials[(mt * 2 + 0) * a.N + n0 + tid] = s0;
-      a.stat_partials[(mt * 2 + 1) * a.N + n0 + tid] = s1;
+      a.stat_partials[mt * stat_pitch(a.N) + n0 + tid] = s0;
+      a.stat_partials[mt * stat_pitch(a.N) + a.N + n0 + tid] = s1;
     }
   }
 }

@@ -15,6 +15,10 @@ struct ConvGeom {
 
 constexpr float kBnEps = 1e-5f;
 constexpr size_t kPartialsBytes = 128u << 20;  // reduction / split-K partials inside the workspace
+// Per-chunk column sums are stored [chunks][stat_pitch(C)] floats: sums at [0, C), second sums at
+// [C, 2C).  The 64 floats of padding keep the chunk pitch off the powers of two that C takes, which
+// would send every chunk's writes to the same memory channel.
+__host__ __device__ inline int64_t stat_pitch(int C) { return 2 * (int64_t)C + 64; }
 
 // ---- plain kernels: any shape, fp32 or bf16 storage, fp32 arithmetic ------------------------------
 void conv_fprop_simple(int dtype, const void* x, const void* w, const void* bias, void* y, const ConvGeom& g,
@@ -32,8 +36,8 @@ void colsum(int dtype, const void* a, int64_t M, int C, float* out, float* parti
 // instead of two bytes, in both of its passes).
 void bn_forward(int dtype, const void* x, const void* gamma, const void* beta, const void* res, bool relu, void* y,
                 int64_t M, int C, float* stats, float* partials, uint8_t* relu_mask, hipStream_t s);
-// Same, with the column sums already in partials ([chunks][2][C], from the producing convolution);
-// scratch: room for 64 * C floats behind them.
+// Same, with the column sums already in partials ([chunks][stat_pitch(C)], from the producing
+// convolution); scratch: room for 32 * stat_pitch(C) floats behind them.
 void bn_forward_partials(int dtype, const void* x, const void* gamma, const void* beta, const void* res, bool relu,
                          void* y, int64_t M, int C, float* stats, const float* partials, int chunks, float* scratch,
                          uint8_t* relu_mask, hipStream_t s);
@@ -77,8 +81,8 @@ namespace cd {
 // All need the channel count of the gathered tensor to be a multiple of 8 (16-byte vectors).
 bool conv_mfma_supported(const ConvGeom& g);
 // y[M][Cout] = im2col(x)[M][K] * w[Cout][K]^T.  With stat_partials the kernel also writes per-tile
-// column sums and sums of squares, [chunks][2][Cout] fp32, and returns the number of chunks
-// (needs (M/128 + 1) * 2 * Cout floats); see bn_forward_partials.
+// column sums and sums of squares, [chunks][stat_pitch(Cout)] fp32, and returns the number of chunks
+// (needs (M/128 + 1) * stat_pitch(Cout) floats); see bn_forward_partials.
 // bias (nullable, [Cout] bf16) is added and, with relu, the result clamped at zero before rounding.
 int conv_fprop_mfma(const bf16_t* x, const bf16_t* w, const bf16_t* bias, bool relu, bf16_t* y, const ConvGeom& g,
                     float* stat_partials, hipStream_t s);

@@ -503,7 +503,7 @@ extern "C" int codistill_forward(const cd_model* m, const void* params, const vo
                        conv_bytes(m, g));
           // a BatchNorm that follows directly gets its column sums from the convolution's epilogue
           const bool fuse = o.pb < 0 && oi + 1 < m->ops.size() && m->ops[oi + 1].kind == OP_BN && m->ops[oi + 1].x == o.y &&
-                            (size_t)(g.M() / 128 + 1 + 64) * 2 * g.Cout * sizeof(float) <= c.plan.partials_bytes;
+                            (size_t)(g.M() / 128 + 1 + 32) * stat_pitch(g.Cout) * sizeof(float) <= c.plan.partials_bytes;
           stat_chunks = conv_fprop_mfma(src, w, static_cast<const bf16_t*>(c.P(o.pb)), o.relu, static_cast<bf16_t*>(out), gp,
                                         fuse ? c.partials() : nullptr, c.s);
           stat_tensor = fuse ? o.y : -1;
@@ -519,7 +519,7 @@ extern "C" int codistill_forward(const cd_model* m, const void* params, const vo
         uint8_t* mask = c.plan.aux[oi] ? reinterpret_cast<uint8_t*>(c.ws + c.plan.aux[oi]) : nullptr;
         if (stat_tensor == o.x)
           bn_forward_partials(dt, in, c.P(o.pw), c.P(o.pb), o.res >= 0 ? c.act(o.res) : nullptr, o.relu, out, M, tx.c,
-                              c.stats(o), c.partials(), stat_chunks, c.partials() + (size_t)stat_chunks * 2 * tx.c, mask,
+                              c.stats(o), c.partials(), stat_chunks, c.partials() + (size_t)stat_chunks * stat_pitch(tx.c), mask,
                               c.s);
         else
           bn_forward(dt, in, c.P(o.pw), c.P(o.pb), o.res >= 0 ? c.act(o.res) : nullptr, o.relu, out, M, tx.c,

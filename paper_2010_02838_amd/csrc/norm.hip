@@ -61,7 +61,7 @@ template <> struct Vec<bf16_t, 8> {
 };
 
 // MODE 0: sums of x and x^2.  MODE 1: sums of dz and dz*xhat with dz = dy * (relu ? y > 0 : 1).
-// MODE 2: sum of a0.  partials: [chunks][2][C].
+// MODE 2: sum of a0.  partials: [chunks][stat_pitch(C)].
 // mask (MODE 1, VEC 8 only, nullable): one byte per 8-channel vector, bit k = (y[k] > 0); read instead of y.
 template <typename T, int VEC, int MODE>
 __global__ void __launch_bounds__(256) col_reduce_k(const T* __restrict__ a0, const T* __restrict__ a1,
@@ -162,8 +162,8 @@ __global__ void __launch_bounds__(256) col_reduce_k(const T* __restrict__ a0, co
         t0 += sm[0][(j * vcb + tx) * VEC + k];
         t1 += sm[1][(j * vcb + tx) * VEC + k];
       }
-      partials[((int64_t)blockIdx.x * 2 + 0) * C + c0 + k] = t0;
-      partials[((int64_t)blockIdx.x * 2 + 1) * C + c0 + k] = t1;
+      partials[(int64_t)blockIdx.x * stat_pitch(C) + c0 + k] = t0;
+      partials[(int64_t)blockIdx.x * stat_pitch(C) + C + c0 + k] = t1;
     }
   }
 }
@@ -183,8 +183,8 @@ __global__ void __launch_bounds__(1024) col_finalize_k(const float* __restrict__
   if (c < C) {
 #pragma unroll 4
     for (int j = lane; j < chunks; j += 16) {
-      a0 += (double)partials[((int64_t)j * 2 + 0) * C + c];
-      if (FIN != 2) a1 += (double)partials[((int64_t)j * 2 + 1) * C + c];
+      a0 += (double)partials[(int64_t)j * stat_pitch(C) + c];
+      if (FIN != 2) a1 += (double)partials[(int64_t)j * stat_pitch(C) + C + c];
     }
   }
   sm[0][lane][cl] = a0;
@@ -237,8 +237,8 @@ __global__ void __launch_bounds__(1024) col_fold_k(const float* __restrict__ par
   if (c < C) {
 #pragma unroll 4
     for (int j = j0 + lane; j < j1; j += 16) {
-      a0 += partials[((int64_t)j * 2 + 0) * C + c];
-      a1 += partials[((int64_t)j * 2 + 1) * C + c];
+      a0 += partials[(int64_t)j * stat_pitch(C) + c];
+      a1 += partials[(int64_t)j * stat_pitch(C) + C + c];
     }
   }
   sm[0][lane][cl] = a0;
@@ -248,8 +248,8 @@ __global__ void __launch_bounds__(1024) col_fold_k(const float* __restrict__ par
   float s0 = 0.f, s1 = 0.f;
 #pragma unroll
   for (int j = 0; j < 16; j++) { s0 += sm[0][j][cl]; s1 += sm[1][j][cl]; }
-  out[((int64_t)blockIdx.y * 2 + 0) * C + c] = s0;
-  out[((int64_t)blockIdx.y * 2 + 1) * C + c] = s1;
+  out[(int64_t)blockIdx.y * stat_pitch(C) + c] = s0;
+  out[(int64_t)blockIdx.y * stat_pitch(C) + C + c] = s1;
 }
 
 // mask (VEC 8 only, nullable): receives one byte per vector, bit k = (y[k] > 0), for the backward pass
@@ -395,7 +395,7 @@ static ReducePlan reduce_plan(int64_t M, int C, int vec) {
   const int vcb = vc < 256 ? vc : 256;
   const int rpi = 256 / vcb;
   int64_t target = 1024 / p.cgroups;                      // blocks to fill the chip several times
-  const int64_t cap = (int64_t)(kPartialsBytes / ((size_t)2 * C * 4));
+  const int64_t cap = (int64_t)(kPartialsBytes / ((size_t)stat_pitch(C) * 4));
   if (target > cap) target = cap;
   if (target < 1) target = 1;
   int64_t rpc = cdiv(M, target);
