@@ -49,8 +49,11 @@ enum { CD_F32 = 0, CD_BF16 = 1 };
 
 /* distillation term D.  CD_DIST_MSE_LOGITS: mean squared error between the raw,
  * uncentred logits (paper, appendix "Implementation Details").  CD_DIST_KL:
- * KL(softmax(z') || softmax(z)), the choice of the prior work cited in Section 2. */
-enum { CD_DIST_MSE_LOGITS = 0, CD_DIST_KL = 1 };
+ * KL(softmax(z') || softmax(z)), the choice of the prior work cited in Section 2.
+ * CD_DIST_MSE_CENTERED: the squared error after each model's logit row has had its
+ * own mean over the classes subtracted (the centring the same appendix reports trying);
+ * normalised like CD_DIST_MSE_LOGITS. */
+enum { CD_DIST_MSE_LOGITS = 0, CD_DIST_KL = 1, CD_DIST_MSE_CENTERED = 2 };
 /* normaliser of the squared error: all rows*cols elements, or rows only */
 enum { CD_MEAN_ALL = 0, CD_MEAN_ROWS = 1 };
 
@@ -145,7 +148,7 @@ typedef struct {
   float alpha;            /* penalty coefficient alpha^k of Algorithm 1                        */
   float label_smoothing;  /* in [0,1): target distribution (1-eps) onehot + eps/cols           */
   int32_t dist_kind;      /* CD_DIST_*                                                         */
-  int32_t mse_reduction;  /* CD_MEAN_*; only read for CD_DIST_MSE_LOGITS                       */
+  int32_t mse_reduction;  /* CD_MEAN_*; read for the two squared-error terms                  */
   int32_t ignore_index;   /* rows whose target equals this add nothing and get a zero gradient */
   int32_t n_peers;        /* n-1 of Algorithm 1; 0 = no distillation term this iteration       */
 } cd_loss_cfg;

@@ -8,9 +8,11 @@ averaged over the n-1 peers.  L is cross-entropy (Section 2 names cross-entropy
 or MSE; every experiment is classification or translation).  D is, by default,
 the mean squared error between the raw, uncentred logits of the two models
 (appendix, "Implementation Details"); the KL divergence that prior work used
-(Section 2) is the second mode.  Gradients flow only into the local logits
-(Section 3: the backward pass is taken with respect to the local parameters
-only), so the peer logits are constants.
+(Section 2) is the second mode, and the centred variant of the squared error
+that the same appendix reports trying (with similar results) the third.
+Gradients flow only into the local logits (Section 3: the backward pass is
+taken with respect to the local parameters only), so the peer logits are
+constants.
 
 Readings where the paper is silent:
   * cross-entropy is averaged over the N valid rows (target != ignore_index);
@@ -19,7 +21,10 @@ Readings where the paper is silent:
     over all C classes, q = (1-eps) onehot + eps/C;
   * "mean squared error" is the mean over all N*C elements ("mean_all"); the
     per-row sum averaged over rows ("mean_rows") is offered as well;
-  * KL is KL(p' || p) with the peer as target, temperature 1, mean over rows.
+  * KL is KL(p' || p) with the peer as target, temperature 1, mean over rows;
+  * "centring" the logits subtracts from each model's logit row its own mean
+    over the classes before the squared error is taken ("mse_centered"); the
+    normalisers are those of the uncentred term.
 """
 import numpy as np
 
@@ -67,8 +72,13 @@ def codistill_loss_grad(z, z_peers, targets, alpha, label_smoothing=0.0,
         w = 1.0 / len(peers)
         for zp in peers:
             zp = np.asarray(zp, dtype=np.float64)
-            if dist == "mse":
-                diff = (z - zp) * vmask
+            if dist in ("mse", "mse_centered"):
+                if dist == "mse_centered":
+                    zc = z - z.mean(axis=1, keepdims=True)
+                    zpc = zp - zp.mean(axis=1, keepdims=True)
+                    diff = (zc - zpc) * vmask
+                else:
+                    diff = (z - zp) * vmask
                 if mse_reduction == "mean_all":
                     denom = n_valid * cols
                 elif mse_reduction == "mean_rows":
@@ -76,6 +86,8 @@ def codistill_loss_grad(z, z_peers, targets, alpha, label_smoothing=0.0,
                 else:
                     raise ValueError(mse_reduction)
                 distill += w * float((diff ** 2).sum() / denom)
+                # d/dz of the centred term: the centring projector I - 11^T/C is applied to a
+                # difference whose rows already sum to zero, which leaves it unchanged
                 dz += alpha * w * 2.0 * diff / denom
             elif dist == "kl":
                 logpp = log_softmax(zp)

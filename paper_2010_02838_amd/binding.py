@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libcodistill.so")
 
 CD_OK, CD_ERR_INVALID_ARG, CD_ERR_UNSUPPORTED, CD_ERR_WORKSPACE_TOO_SMALL, CD_ERR_HIP = 0, -1, -2, -3, -4
 CD_F32, CD_BF16 = 0, 1
-CD_DIST_MSE_LOGITS, CD_DIST_KL = 0, 1
+CD_DIST_MSE_LOGITS, CD_DIST_KL, CD_DIST_MSE_CENTERED = 0, 1, 2
 CD_MEAN_ALL, CD_MEAN_ROWS = 0, 1
 CD_BN_BATCH_STATS, CD_BN_RUNNING = 0, 1
 CD_ARCH_TINY_CNN, CD_ARCH_RESNET_BASIC, CD_ARCH_RESNET_BOTTLENECK, CD_ARCH_TRANSFORMER_HEAD = 0, 1, 2, 3

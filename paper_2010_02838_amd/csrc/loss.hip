@@ -3,7 +3,8 @@
 //
 // Paper, Algorithm 1: the objective is L(y, z) + alpha * mean over peers of D(z, z').  D is the
 // mean squared error between raw logits (appendix "Implementation Details") or the KL divergence
-// of the prior work named in Section 2.  Peer logits are constants (Section 3).
+// of the prior work named in Section 2, or the squared error between logits centred per row (the
+// variant the same appendix reports trying).  Peer logits are constants (Section 3).
 //
 // HBM-bound: each logit of z and z' is read once and each gradient element written once
 // (12 bytes per logit pair).  A row lives in registers between the reduction and the gradient:
@@ -78,7 +79,8 @@ __device__ inline bool row_target(const LossArgs& a, int64_t row, int& t) {
   return t != a.ignore_index && t >= 0 && t < a.cols;
 }
 
-// MODE: 0 = no peer, 1 = MSE between logits, 2 = KL(p'||p).  At most one peer.
+// MODE: 0 = no peer, 1 = MSE between logits, 2 = KL(p'||p), 3 = MSE between logits centred per row
+// (one peer only).
 template <int TPR, int V, int MODE>
 __global__ void __launch_bounds__((TPR > 256 ? TPR : 256)) loss_row_kernel(LossArgs a) {
   constexpr int BLOCK = TPR > 256 ? TPR : 256;
@@ -161,7 +163,8 @@ __global__ void __launch_bounds__((TPR > 256 ? TPR : 256)) loss_row_kernel(LossA
   }
   group_reduce<TPR, 2, 3u>(mx, smem);
   const float m = mx[0], mp = mx[1];
-  // sums: [0] sum exp(z-m)  [1] sum z  [2] MSE: sum (z-z')^2 | KL: sum exp(z'-m')  [3] KL: sum exp(z'-m')(z'-z)
+  // sums: [0] sum exp(z-m)  [1] sum z  [2] MSE: sum (z-z')^2 | KL: sum exp(z'-m')
+  //       [3] KL: sum exp(z'-m')(z'-z) | centred MSE: sum (z-z')
   // The registers are reused for what the gradient needs: z becomes e = exp(z-m), z' becomes z-z'
   // (MSE) or e' = exp(z'-m') (KL), so that the gradient costs no second exponential per element.
   float s[4] = {0.f, 0.f, 0.f, 0.f};
@@ -178,6 +181,7 @@ __global__ void __launch_bounds__((TPR > 256 ? TPR : 256)) loss_row_kernel(LossA
         s[1] += xv[k];
         if (MODE == 1) { const float d = xv[k] - yv[k]; s[2] += many ? 0.f : d * d; yv[k] = d; }
         if (MODE == 2) { const float ep = __expf(yv[k] - mp); s[2] += ep; s[3] += ep * (yv[k] - xv[k]); yv[k] = ep; }
+        if (MODE == 3) { const float d = xv[k] - yv[k]; s[3] += d; yv[k] = d; }
         xv[k] = e;
       }
       x[i] = make_float4(xv[0], xv[1], xv[2], xv[3]);
@@ -186,13 +190,30 @@ __global__ void __launch_bounds__((TPR > 256 ? TPR : 256)) loss_row_kernel(LossA
   }
   s[2] += sq_extra;
   group_reduce<TPR, 4, 0u>(s, smem);
+  if (MODE == 3) {
+    // Centring both rows subtracts the mean of z - z' from their difference.  The squared error is
+    // summed from the centred differences (not as sum d^2 - C mean^2, which cancels when the two
+    // models differ mostly by a constant).
+    const float md = s[3] / (float)cols;
+    float q[1] = {0.f};
+#pragma unroll
+    for (int i = 0; i < V; i++) {
+      int64_t c = ((int64_t)i * TPR + lane) * 4;
+      if (c < cols) {
+        y[i].x -= md; y[i].y -= md; y[i].z -= md; y[i].w -= md;
+        q[0] += y[i].x * y[i].x + y[i].y * y[i].y + y[i].z * y[i].z + y[i].w * y[i].w;
+      }
+    }
+    group_reduce<TPR, 1, 0u>(q, smem);
+    s[2] = q[0];
+  }
   const float lse = m + logf(s[0]);
   float lsep = 0.f;
   if (MODE == 2) lsep = mp + logf(s[2]);
   if (lane == 0) {
     a.row_task[row] = lse - (1.f - a.eps) * zt - (a.eps / (float)cols) * s[1];
     float d = 0.f;
-    if (MODE == 1) d = s[2];
+    if (MODE == 1 || MODE == 3) d = s[2];
     if (MODE == 2) d = s[3] / s[2] - lsep + lse;
     a.row_dist[row] = d;
   }
@@ -200,7 +221,7 @@ __global__ void __launch_bounds__((TPR > 256 ? TPR : 256)) loss_row_kernel(LossA
   const float invn = 1.f / (float)nvalid;
   const float epsc = a.eps / (float)cols;
   float cm = 0.f;
-  if (MODE == 1) cm = a.alpha * 2.f * invn / (a.mse_reduction == CD_MEAN_ALL ? (float)cols : 1.f);
+  if (MODE == 1 || MODE == 3) cm = a.alpha * 2.f * invn / (a.mse_reduction == CD_MEAN_ALL ? (float)cols : 1.f);
   const float onehot = (1.f - a.eps) * invn;
   const float fp = invn / s[0];                                   // p * invn = e * fp
   const float fq = MODE == 2 ? invn / s[2] : 0.f;                 // p' * invn = e' * fq (same form as fp: an identical peer cancels exactly)
@@ -215,7 +236,7 @@ __global__ void __launch_bounds__((TPR > 256 ? TPR : 256)) loss_row_kernel(LossA
 #pragma unroll
       for (int k = 0; k < 4; k++) {
         float gk = xv[k] * fp + base;
-        if (MODE == 1) gk += cm * yv[k];
+        if (MODE == 1 || MODE == 3) gk += cm * yv[k];
         if (MODE == 2) gk += a.alpha * (__fmul_rn(xv[k], fp) - __fmul_rn(yv[k], fq));  // no fma: exact cancellation
         if (c + k == t) gk -= onehot;
         o[k] = gk;
@@ -229,7 +250,8 @@ __global__ void __launch_bounds__((TPR > 256 ? TPR : 256)) loss_row_kernel(LossA
 // passes hit in cache).  Scalar accesses, so rows need no alignment.
 __global__ void __launch_bounds__(256) loss_row_generic_kernel(LossArgs a) {
   __shared__ float smem[5 * 4];
-  __shared__ float s_lsep[CD_LOSS_MAX_PEERS];
+  __shared__ float s_lsep[CD_LOSS_MAX_PEERS];  // KL: log-sum-exp of peer j; squared errors: mean of z - z'_j (0 uncentred)
+  const bool squared = a.dist == CD_DIST_MSE_LOGITS || a.dist == CD_DIST_MSE_CENTERED;
   const int64_t row = blockIdx.x;
   const int64_t cols = a.cols;
   const float* zr = a.z + row * cols;
@@ -254,11 +276,19 @@ __global__ void __launch_bounds__(256) loss_row_generic_kernel(LossArgs a) {
   float dsum = 0.f;
   for (int j = 0; j < a.n_peers; j++) {
     const float* pr = a.zp[j] + row * cols;
-    if (a.dist == CD_DIST_MSE_LOGITS) {
+    if (squared) {
+      float md = 0.f;
+      if (a.dist == CD_DIST_MSE_CENTERED) {
+        float u[1] = {0.f};
+        for (int64_t c = threadIdx.x; c < cols; c += 256) u[0] += zr[c] - pr[c];
+        group_reduce<256, 1, 0u>(u, smem);
+        md = u[0] / (float)cols;
+      }
       float q[1] = {0.f};
-      for (int64_t c = threadIdx.x; c < cols; c += 256) { float d = zr[c] - pr[c]; q[0] += d * d; }
+      for (int64_t c = threadIdx.x; c < cols; c += 256) { float d = zr[c] - pr[c] - md; q[0] += d * d; }
       group_reduce<256, 1, 0u>(q, smem);
       dsum += q[0];
+      if (threadIdx.x == 0) s_lsep[j] = md;
     } else {
       float q[1] = {-INFINITY};
       for (int64_t c = threadIdx.x; c < cols; c += 256) q[0] = fmaxf(q[0], pr[c]);
@@ -292,7 +322,7 @@ __global__ void __launch_bounds__(256) loss_row_generic_kernel(LossArgs a) {
     float gk = (p - epsc) * invn;
     for (int j = 0; j < a.n_peers; j++) {
       const float y = a.zp[j][row * cols + c];
-      if (a.dist == CD_DIST_MSE_LOGITS) gk += cm * (x - y);
+      if (squared) gk += cm * (x - y - s_lsep[j]);
       else gk += ck * (p - __expf(y - s_lsep[j]));
     }
     if (c == t) gk -= (1.f - a.eps) * invn;
@@ -319,7 +349,8 @@ __global__ void __launch_bounds__(256) loss_finalize_kernel(LossArgs a, float* l
       task = s_t[0] / n;
       if (a.n_peers > 0) {
         double denom = (double)n * a.n_peers;
-        if (a.dist == CD_DIST_MSE_LOGITS && a.mse_reduction == CD_MEAN_ALL) denom *= (double)a.cols;
+        if ((a.dist == CD_DIST_MSE_LOGITS || a.dist == CD_DIST_MSE_CENTERED) && a.mse_reduction == CD_MEAN_ALL)
+          denom *= (double)a.cols;
         dist = s_d[0] / denom;
       }
     }
@@ -337,6 +368,7 @@ static void launch_rows(const LossArgs& a, int mode, hipStream_t s) {
   dim3 grid((unsigned)cdiv(a.rows, RPB));
   if (mode == 0) hipLaunchKernelGGL((loss_row_kernel<TPR, V, 0>), grid, dim3(BLOCK), 0, s, a);
   else if (mode == 1) hipLaunchKernelGGL((loss_row_kernel<TPR, V, 1>), grid, dim3(BLOCK), 0, s, a);
+  else if (mode == 3) hipLaunchKernelGGL((loss_row_kernel<TPR, V, 3>), grid, dim3(BLOCK), 0, s, a);
   else hipLaunchKernelGGL((loss_row_kernel<TPR, V, 2>), grid, dim3(BLOCK), 0, s, a);
 }
 
@@ -362,8 +394,9 @@ extern "C" int codistill_loss_grad(const float* z_local, const float* const* z_p
   CD_REQUIRE(cols >= 1 && cols <= (1LL << 24), "loss_grad: cols=%lld out of range [1, 2^24]", (long long)cols);
   CD_REQUIRE(cfg->n_peers >= 0 && cfg->n_peers <= CD_LOSS_MAX_PEERS, "loss_grad: n_peers=%d out of range [0, %d]",
              cfg->n_peers, CD_LOSS_MAX_PEERS);
-  CD_REQUIRE(cfg->dist_kind == CD_DIST_MSE_LOGITS || cfg->dist_kind == CD_DIST_KL, "loss_grad: unknown dist_kind %d",
-             cfg->dist_kind);
+  CD_REQUIRE(cfg->dist_kind == CD_DIST_MSE_LOGITS || cfg->dist_kind == CD_DIST_KL ||
+                 cfg->dist_kind == CD_DIST_MSE_CENTERED,
+             "loss_grad: unknown dist_kind %d", cfg->dist_kind);
   CD_REQUIRE(cfg->mse_reduction == CD_MEAN_ALL || cfg->mse_reduction == CD_MEAN_ROWS,
              "loss_grad: unknown mse_reduction %d", cfg->mse_reduction);
   CD_REQUIRE(cfg->label_smoothing >= 0.f && cfg->label_smoothing < 1.f, "loss_grad: label_smoothing %g outside [0,1)",
@@ -400,7 +433,10 @@ extern "C" int codistill_loss_grad(const float* z_local, const float* const* z_p
   const double bytes = (double)rows * cols * 4.0 * (2 + cfg->n_peers);
   ProfScope prof(CD_K_LOSS, s, (double)rows * cols * 12.0, bytes);
   hipLaunchKernelGGL(loss_prep_kernel, dim3(1), dim3(1024), 0, s, a);
-  const int mode = cfg->n_peers == 0 ? 0 : (cfg->dist_kind == CD_DIST_MSE_LOGITS ? 1 : 2);
+  const int mode = cfg->n_peers == 0 ? 0
+                   : cfg->dist_kind == CD_DIST_MSE_LOGITS ? 1
+                   : cfg->dist_kind == CD_DIST_KL         ? 2
+                                                          : 3;
   // register-resident kernel: one peer, or several with the MSE term (folded into a running mean)
   const bool fast = cols % 4 == 0 && cols <= 32768 && (cfg->n_peers <= 1 || mode == 1);
   if (!fast) {

@@ -52,7 +52,7 @@ class Case:
         xd = to_device(self.x, model.torch_dtype)
         yd = torch.from_numpy(self.y).to("cuda:0")
         r.step(xd, yd, alpha, lr, mu, weight_decay=wd, label_smoothing=label_smoothing,
-               dist_kind=B.CD_DIST_KL if dist == "kl" else B.CD_DIST_MSE_LOGITS)
+               dist_kind={"kl": B.CD_DIST_KL, "mse": B.CD_DIST_MSE_LOGITS, "mse_centered": B.CD_DIST_MSE_CENTERED}[dist])
         torch.cuda.synchronize()
         got = dict(logits=r.logits.cpu().numpy(), peer_logits=r.peer_logits[0].cpu().numpy(),
                    loss=r.loss.cpu().numpy()[:3].astype(np.float64), dz=r.dz.cpu().numpy(),

@@ -9,7 +9,8 @@ from paper_2010_02838_amd import synth
 pytestmark = pytest.mark.gpu
 TOL = 1e-5   # stated tolerance for the fp32 loss kernel: relative, L2 for tensors, |a-b|/|b| for scalars
 
-MODES = {"mse": (0, 0, "mse", "mean_all"), "mse_rows": (0, 1, "mse", "mean_rows"), "kl": (1, 0, "kl", "mean_all")}
+MODES = {"mse": (0, 0, "mse", "mean_all"), "mse_rows": (0, 1, "mse", "mean_rows"), "kl": (1, 0, "kl", "mean_all"),
+         "mse_centered": (2, 0, "mse_centered", "mean_all"), "mse_centered_rows": (2, 1, "mse_centered", "mean_rows")}
 
 
 def run_gpu(z, peers, t, alpha, eps, mode, ignore_index=-1, inplace=False):
@@ -48,7 +49,7 @@ SHAPES = [(8, 10), (128, 10), (5, 33), (256, 1000), (37, 256), (19, 4100), (21, 
 
 
 @pytest.mark.parametrize("rows,cols", SHAPES)
-@pytest.mark.parametrize("mode", ["mse", "kl"])
+@pytest.mark.parametrize("mode", ["mse", "kl", "mse_centered"])
 def test_loss_parity_shapes(rows, cols, mode):
     z = synth.logits(rows, cols, 3.0, seed=rows)
     zp = synth.logits(rows, cols, 3.0, seed=rows + 1000)
@@ -57,7 +58,7 @@ def test_loss_parity_shapes(rows, cols, mode):
     check(z, [zp], t, 0.5, 0.0, mode)
 
 
-@pytest.mark.parametrize("mode", ["mse", "mse_rows", "kl"])
+@pytest.mark.parametrize("mode", ["mse", "mse_rows", "kl", "mse_centered", "mse_centered_rows"])
 @pytest.mark.parametrize("eps", [0.0, 0.1])
 def test_loss_parity_modes(mode, eps):
     z, zp = synth.logits(64, 1000, 3.0, seed=1), synth.logits(64, 1000, 3.0, seed=2)
@@ -99,13 +100,32 @@ def test_n_way_wide_rows(cols):
         check(z, peers, t, 0.5, 0.1, mode)
 
 
-@pytest.mark.parametrize("mode", ["mse", "kl"])
+@pytest.mark.parametrize("mode", ["mse", "kl", "mse_centered"])
 @pytest.mark.parametrize("npeers", [2, 3])
 def test_n_way(mode, npeers):
     z = synth.logits(32, 1000, 3.0, seed=1)
     peers = [synth.logits(32, 1000, 3.0, seed=10 + j) for j in range(npeers)]
     t = synth.labels(32, 1000, seed=3)
     check(z, peers, t, 0.8, 0.1, mode)
+
+
+@pytest.mark.parametrize("cols", [10, 1000, 4100, 32768])
+def test_centered_mse_ignores_row_offsets(cols):
+    """A peer that differs from the local model mostly by a per-row constant (up to 4 against a spread of 0.05):
+    the centred distance keeps its relative accuracy, because the squared error is summed after the centring
+    (sum d^2 - C mean^2 would lose four digits here)."""
+    z = synth.logits(12, cols, 3.0, seed=1)
+    noise = synth.logits(12, cols, 0.05, seed=2)
+    off = (np.arange(12, dtype=np.float32)[:, None] - 5.5) * 0.75
+    t = synth.labels(12, cols, seed=3)
+    zp = (z + noise + off).astype(np.float32)
+    l, _ = check(z, [zp], t, 0.9, 0.0, "mse_centered")
+    assert l[2] < 4e-3          # about (0.05)^2 per element, against an uncentred distance of several units
+    # a constant offset (up to the rounding of z + 4): distance ~ 0 and the gradient of the plain loss
+    zq = z + np.float32(4.0)
+    l1, _, dz1 = run_gpu(z, [zq], t, 0.9, 0.0, "mse_centered")
+    l0, _, dz0 = run_gpu(z, [], t, 0.9, 0.0, "mse_centered")
+    assert l1[2] <= 1e-10 and rel(dz1, dz0.astype(np.float64)) <= 1e-6
 
 
 def test_zero_logits_closed_form_and_edge_rows():

@@ -56,7 +56,7 @@ def test_tiny_cnn_fp32_step():
     np.testing.assert_array_equal(got["v"], got["grad"])       # first step from v = 0
 
 
-@pytest.mark.parametrize("dist", ["mse", "kl"])
+@pytest.mark.parametrize("dist", ["mse", "kl", "mse_centered"])
 def test_tiny_cnn_fp32_step_variants(dist):
     c = Case(dict(kind=0), nets.tiny_cnn(), "f32", 5, 12, 10, v_scale=0.01)
     ref, got = c.oracle(alpha=0.5, wd=1e-3, dist=dist), c.gpu(alpha=0.5, wd=1e-3, dist=dist)

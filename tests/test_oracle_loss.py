@@ -141,7 +141,49 @@ def test_kl_library_special_cases():
     np.testing.assert_allclose(dz2, dz, atol=1e-15)
 
 
-@pytest.mark.parametrize("dist", ["mse", "kl"])
+def test_centered_mse_invariances_and_reduction_to_plain_mse():
+    z, zp = rnd(9, 13, 30), rnd(9, 13, 31)
+    t = np.random.default_rng(32).integers(0, 13, 9)
+    alpha = 0.7
+    (_, _, d), dz = codistill_loss_grad(z, [zp], t, alpha, dist="mse_centered")
+    (_, _, _), dz0 = codistill_loss_grad(z, None, t, alpha)
+    # a per-row constant added to either model's logits changes nothing
+    shift = np.random.default_rng(33).standard_normal((9, 1)) * 4
+    (_, _, d2), dz2 = codistill_loss_grad(z, [zp + shift], t, alpha, dist="mse_centered")
+    assert d2 == pytest.approx(d, rel=1e-12)
+    np.testing.assert_allclose(dz2, dz, atol=1e-15)
+    # so a peer that differs by a constant per row is at distance zero, with the plain CE gradient
+    (_, _, d3), dz3 = codistill_loss_grad(z, [z + shift], t, alpha, dist="mse_centered")
+    assert abs(d3) < 1e-28
+    np.testing.assert_allclose(dz3, dz0, atol=1e-15)
+    # the distillation part of the gradient sums to zero over the classes of each row
+    np.testing.assert_allclose((dz - dz0).sum(axis=1), 0, atol=1e-15)
+    # rows that already have zero mean: identical to the uncentred term
+    zc, zpc = z - z.mean(axis=1, keepdims=True), zp - zp.mean(axis=1, keepdims=True)
+    a, dza = codistill_loss_grad(zc, [zpc], t, alpha, dist="mse_centered")
+    b, dzb = codistill_loss_grad(zc, [zpc], t, alpha, dist="mse")
+    np.testing.assert_allclose(a, b, rtol=1e-13)
+    np.testing.assert_allclose(dza, dzb, atol=1e-15)
+    # variance decomposition: uncentred = centred + squared difference of the row means
+    (_, _, du), _ = codistill_loss_grad(z, [zp], t, alpha, dist="mse")
+    gap = ((z.mean(axis=1) - zp.mean(axis=1)) ** 2).mean()
+    assert du == pytest.approx(d + gap, rel=1e-12)
+    # torch: mse_loss of the centred tensors, differentiated through the centring
+    zt = torch.tensor(z, requires_grad=True)
+    zpt = torch.tensor(zp)
+    l = torch.nn.functional.cross_entropy(zt, torch.tensor(t)) + alpha * torch.nn.functional.mse_loss(
+        zt - zt.mean(1, keepdim=True), zpt - zpt.mean(1, keepdim=True))
+    l.backward()
+    (tot, _, _), _ = codistill_loss_grad(z, [zp], t, alpha, dist="mse_centered")
+    assert tot == pytest.approx(l.item(), rel=1e-13)
+    np.testing.assert_allclose(dz, zt.grad.numpy(), atol=1e-15)
+    # mean over rows instead of over all elements: C times larger
+    (_, _, dr), dzr = codistill_loss_grad(z, [zp], t, alpha, dist="mse_centered", mse_reduction="mean_rows")
+    assert dr == pytest.approx(13 * d, rel=1e-12)
+    np.testing.assert_allclose(dzr - dz0, 13 * (dz - dz0), rtol=1e-11, atol=1e-16)
+
+
+@pytest.mark.parametrize("dist", ["mse", "kl", "mse_centered"])
 def test_n_way_average(dist):
     # Algorithm 1 averages D over the n-1 peers: two identical peers == one peer
     z, zp, zq = rnd(4, 9, 12), rnd(4, 9, 13), rnd(4, 9, 14)
@@ -157,7 +199,7 @@ def test_n_way_average(dist):
     assert c[2] == pytest.approx(0.5 * (a[2] + b[2]), rel=1e-13)
 
 
-@pytest.mark.parametrize("dist", ["mse", "kl"])
+@pytest.mark.parametrize("dist", ["mse", "kl", "mse_centered"])
 def test_ignored_rows(dist):
     z, zp = rnd(6, 8, 15), rnd(6, 8, 16)
     t = np.array([1, -1, 3, -1, 0, 7])
@@ -171,7 +213,8 @@ def test_ignored_rows(dist):
     assert out == (0.0, 0.0, 0.0) and np.all(dz0 == 0)
 
 
-@pytest.mark.parametrize("dist,red", [("mse", "mean_all"), ("mse", "mean_rows"), ("kl", "mean_all")])
+@pytest.mark.parametrize("dist,red", [("mse", "mean_all"), ("mse", "mean_rows"), ("kl", "mean_all"),
+                                      ("mse_centered", "mean_all"), ("mse_centered", "mean_rows")])
 def test_gradient_by_finite_differences(dist, red):
     z, zp = rnd(3, 5, 17, 1.0), rnd(3, 5, 18, 1.0)
     t = np.array([4, -1, 2])

@@ -190,7 +190,7 @@ ARCHS = {
 
 
 @pytest.mark.parametrize("name", list(ARCHS))
-@pytest.mark.parametrize("dist", ["mse", "kl"])
+@pytest.mark.parametrize("dist", ["mse", "kl", "mse_centered"])
 def test_step_matches_library_autograd(name, dist):
     mk, xs, classes = ARCHS[name]
     arch = mk()
@@ -211,6 +211,8 @@ def test_step_matches_library_autograd(name, dist):
     ce = F.cross_entropy(z, torch.tensor(y).long())
     if dist == "mse":
         d = F.mse_loss(z, zp)
+    elif dist == "mse_centered":
+        d = F.mse_loss(z - z.mean(1, keepdim=True), zp - zp.mean(1, keepdim=True))
     else:
         d = F.kl_div(torch.log_softmax(z, 1), torch.softmax(zp, 1), reduction="batchmean")
     loss = ce + alpha * d
