@@ -459,17 +459,29 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
   }
 }
 
-// 128x128 tiles run three workgroups per compute unit (768 at a time), 256x128 tiles two (512): take
-// the taller tile when its last round of workgroups is clearly fuller.
-static bool igemm_tall_tile(int64_t M, int N) {
-  if (N <= 64) return false;
-  if (g_tune_tile == 3) return true;
-  if (g_tune_tile == 2) return false;
+// Output tile of the wide-output kernels (N > 64): 128x128 (three workgroups per compute unit, 768 at a
+// time), 256x128 or 128x256 (two per compute unit, 512 at a time).  Measured on the layer shapes of
+// ResNet-50 at batch 256:
+//  - a short contraction leaves a tile little more than its prologue and epilogue, and the larger
+//    tiles halve those per output element: 128x256, which also reads the activations once per 256
+//    columns and stores 512-byte row segments, wins up to K = 1024; with very short contractions
+//    onto many columns (K <= 128, N >= 512) 256x128 wins instead;
+//  - otherwise the taller tile pays only when its last round of workgroups is clearly fuller.
+enum { TILE_SQUARE = 0, TILE_TALL = 1, TILE_WIDE = 2 };
+static int igemm_tile(int64_t M, int N, int K) {
+  if (N <= 64) return TILE_SQUARE;
+  if (g_tune_tile == 2) return TILE_SQUARE;
+  if (g_tune_tile == 3) return TILE_TALL;
+  if (g_tune_tile == 4) return N % 256 == 0 ? TILE_WIDE : TILE_SQUARE;
+  if (K <= 128 && N >= 512) return TILE_TALL;
+  if (N % 256 == 0 && K <= 1024) return TILE_WIDE;
   const int64_t t128 = cdiv(M, 128) * cdiv(N, 128), t256 = cdiv(M, 256) * cdiv(N, 128);
   const double e128 = (double)t128 / (double)(cdiv(t128, 768) * 768), e256 = (double)t256 / (double)(cdiv(t256, 512) * 512);
-  return e256 > 1.2 * e128;
+  return e256 > 1.2 * e128 ? TILE_TALL : TILE_SQUARE;
 }
-bool conv_fprop_tall_tile(const ConvGeom& g) { return g.Cin >= BK && igemm_tall_tile(g.M(), g.Cout); }
+bool conv_fprop_square_tile(const ConvGeom& g) {
+  return g.Cout > 64 && (g.Cin < BK || igemm_tile(g.M(), g.Cout, (int)g.K()) == TILE_SQUARE);
+}
 
 // returns the number of m-tiles (= statistics chunks when STATS)
 template <int MODE, bool STATS, int NWRAP, bool REMAP, int EPI>
@@ -477,12 +489,18 @@ static int launch_igemm_w(IgemmArgs a, hipStream_t s) {
   a.pointwise = (a.kh == 1 && a.kw == 1 && a.stride == 1 && a.pad == 0 && a.pad_w == 0 && a.Hs == a.Hd &&
                  a.Ws == a.Wd) ? 1 : 0;
   a.group_m = 1;
-  // 128x128 tiles run three workgroups per compute unit (768 at a time), 256x128 tiles two (512): take
-  // the taller tile when its last round of workgroups is clearly fuller.
-  if (NWRAP == 1 && !REMAP && EPI == 0 && igemm_tall_tile(a.M, a.N)) {
+  const int tile = (NWRAP == 1 && !REMAP && EPI == 0) ? igemm_tile(a.M, a.N, a.K) : TILE_SQUARE;
+  if (tile == TILE_TALL) {
     a.ntiles = (int)cdiv(a.N, 128);
     const int mt = (int)cdiv(a.M, 256);
     hipLaunchKernelGGL((igemm_kernel<MODE, 256, 128, 2, 2, false, STATS, 1, false>),
+                       dim3((unsigned)((int64_t)mt * a.ntiles)), dim3(256), 0, s, a);
+    return mt;
+  }
+  if (tile == TILE_WIDE) {
+    a.ntiles = a.N / 256;
+    const int mt = (int)cdiv(a.M, 128);
+    hipLaunchKernelGGL((igemm_kernel<MODE, 128, 256, 2, 2, false, STATS, 1, false>),
                        dim3((unsigned)((int64_t)mt * a.ntiles)), dim3(256), 0, s, a);
     return mt;
   }

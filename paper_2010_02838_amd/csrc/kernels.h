@@ -86,8 +86,8 @@ bool conv_mfma_supported(const ConvGeom& g);
 // bias (nullable, [Cout] bf16) is added and, with relu, the result clamped at zero before rounding.
 int conv_fprop_mfma(const bf16_t* x, const bf16_t* w, const bf16_t* bias, bool relu, bf16_t* y, const ConvGeom& g,
                     float* stat_partials, hipStream_t s);
-// whether conv_fprop_mfma runs this shape with its 256x128 tile (a different kernel than the 128x128 one)
-bool conv_fprop_tall_tile(const ConvGeom& g);
+// whether conv_fprop_mfma runs this shape on 128x128 tiles (the taller and wider tiles are other kernels)
+bool conv_fprop_square_tile(const ConvGeom& g);
 // dx[B*H*W][Cin] (+)= gather(dy)[.][taps*Cout] * wt[Cin][taps*Cout]^T.  w is the filter as stored; wt is
 // scratch of at least Cout*K + 32 elements that receives its re-laid-out copy (or copies, per parity
 // class, for stride 2).

@@ -498,7 +498,7 @@ extern "C" int codistill_forward(const cd_model* m, const void* params, const vo
             src = c.xpack();
             w = c.wpack();
           }
-          ProfScope pr(g.Cout > 64 && !conv_fprop_tall_tile(g) ? CD_K_CONV_FPROP : CD_K_CONV_FPROP_NARROW, c.s,
+          ProfScope pr(conv_fprop_square_tile(g) ? CD_K_CONV_FPROP : CD_K_CONV_FPROP_NARROW, c.s,
                        2.0 * g.M() * g.Cout * g.K(),
                        conv_bytes(m, g));
           // a BatchNorm that follows directly gets its column sums from the convolution's epilogue

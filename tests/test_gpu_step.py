@@ -234,10 +234,18 @@ def compare_bf16(c, ref, floor, got):
 
 
 def test_tall_tile_convolutions_bf16_layers():
-    """One bottleneck block at 196 x 64 x 64: after the stem and the pool M = 196*16*16 = 50176 rows, and the
-    two 64 -> 256 convolutions have 784 tiles of 128x128, the case that is run on 256x128 tiles instead."""
+    """One bottleneck block at 196 x 64 x 64: after the stem and the pool M = 196*16*16 = 50176 rows.  The two
+    64 -> 256 convolutions (short contraction, 256 columns) run on 128x256 tiles, forward and backward."""
     c = Case(dict(kind=2, widths=[64], blocks=[1], stem_width=64),
              nets.resnet50(classes=10, widths=(64,), blocks=(1,), stem=64), "bf16", 196, 64, 10)
+    check_layers(c, c.gpu())
+
+
+def test_short_contraction_onto_many_columns_bf16_layers():
+    """One bottleneck block of width 128: its 128 -> 512 and 64 -> 512 convolutions (K <= 128, N = 512) take
+    the 256x128 tile; M = 40*16*16 = 10240 rows is 40 of those tiles."""
+    c = Case(dict(kind=2, widths=[128], blocks=[1], stem_width=64),
+             nets.resnet50(classes=10, widths=(128,), blocks=(1,), stem=64), "bf16", 40, 64, 10)
     check_layers(c, c.gpu())
 
 
