@@ -33,6 +33,29 @@ PEAK_HBM_GBS = 8000.0
 ROOFLINE_TRAFFIC_BYTES = 231.8e6   # FETCH_SIZE 50153.0 KiB x 2.000 + WRITE_SIZE 126033.6 KiB x 1.000
 
 
+def roofline_of(flops, nbytes, ms, launches, kernel, traffic):
+    """Roofline entry of one kernel class from its algorithmic flops and HBM bytes (every operand once) and
+    the HIP-event time of its launches.  The bound is the roof its arithmetic intensity puts it under: HBM
+    below the machine's ridge (peak flops / peak bytes), MFMA above; `achieved` is in that roof's unit and the
+    fraction of the MFMA peak is given either way."""
+    tflops = flops / (ms * 1e-3) / 1e12 if ms > 0 else 0.0
+    gbs = nbytes / (ms * 1e-3) / 1e9 if ms > 0 else 0.0
+    intensity = flops / nbytes if nbytes > 0 else 0.0
+    ridge = PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
+    hbm_bound = intensity < ridge
+    return {"bound": "hbm" if hbm_bound else "mfma",
+            "achieved": gbs if hbm_bound else tflops,
+            "peak": PEAK_HBM_GBS if hbm_bound else PEAK_BF16_TFLOPS,
+            "unit": "GB/s" if hbm_bound else "TFLOP/s",
+            "frac": gbs / PEAK_HBM_GBS if hbm_bound else tflops / PEAK_BF16_TFLOPS,
+            "traffic": traffic,
+            "algorithmic_bytes_per_launch": nbytes / max(launches, 1),
+            "flop_per_launch": flops / max(launches, 1),
+            "intensity_flop_per_byte": intensity, "ridge_flop_per_byte": ridge,
+            "mfma_tflops": tflops, "mfma_frac": tflops / PEAK_BF16_TFLOPS,
+            "kernel": kernel, "avg_launch_us": ms / max(launches, 1) * 1e3}
+
+
 def cpu_baseline(seconds_hint=20.0):
     """Oracle step (ResNet-50, 224x224, batch 2) on the host cores: a baseline, not a target."""
     import numpy as np
@@ -128,7 +151,6 @@ def transformer_head(args, B, synth, StepRunner, pack_flat, to_device, torch, de
     prof = B.profile_collect()
     B.profile_enable(False)
     lin = prof["linear"]
-    achieved = lin["flops"] / (lin["ms"] * 1e-3) / 1e12 if lin["ms"] > 0 else 0.0
     hbm = {}
     for k in ("norm", "loss", "sgd"):
         if prof[k]["ms"] > 0:
@@ -143,13 +165,9 @@ def transformer_head(args, B, synth, StepRunner, pack_flat, to_device, torch, de
                    "models": "2 x output block (local fwd+bwd+SGD, peer fwd)", "alpha": 1.0, "label_smoothing": 0.1,
                    "distillation": "mse_logits"},
         "loss": [float(v) for v in loss[:3]],
-        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
-                     "kernel": "igemm_kernel<0,128,128,2,2,true,false,1,false> (vocabulary projection, fp32 logits)",
-                     "flop_per_launch": lin["flops"] / max(lin["launches"], 1),
-                     "algorithmic_bytes_per_launch": lin["bytes"] / max(lin["launches"], 1),
-                     "launches_per_step": lin["launches"] / psteps,
-                     "avg_launch_us": lin["ms"] / max(lin["launches"], 1) * 1e3},
+        "roofline": dict(roofline_of(lin["flops"], lin["bytes"], lin["ms"], lin["launches"],
+                                     "igemm_kernel<0,128,128,2,2,true,false,1,false> (vocabulary projection, fp32 logits)",
+                                     None), launches_per_step=lin["launches"] / psteps),
         "kernel_class_ms_per_step": {k: round(v["ms"] / psteps, 4) for k, v in prof.items()},
         "hbm_kernels": hbm,
         "cpu_baseline": None,
@@ -233,13 +251,10 @@ def main():
     prof = B.profile_collect()
     B.profile_enable(False)
     ig_ms, ig_n, ig_fl = prof["conv_fprop"]["ms"], prof["conv_fprop"]["launches"], prof["conv_fprop"]["flops"]
-    achieved = ig_fl / (ig_ms * 1e-3) / 1e12 if ig_ms > 0 else 0.0
-    roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": achieved / PEAK_BF16_TFLOPS, "traffic": ROOFLINE_TRAFFIC_BYTES,
-                "algorithmic_bytes_per_launch": prof["conv_fprop"]["bytes"] / max(ig_n, 1),
-                "kernel": "igemm_kernel<0,128,128,2,2,false,true,1,false> (bf16 implicit-GEMM conv fprop on 128x128 tiles)",
-                "flop_per_launch": ig_fl / max(ig_n, 1),
-                "launches_per_step": ig_n / psteps, "avg_launch_us": ig_ms / max(ig_n, 1) * 1e3}
+    roofline = roofline_of(ig_fl, prof["conv_fprop"]["bytes"], ig_ms, ig_n,
+                           "igemm_kernel<0,128,128,2,2,false,true,1,false> (bf16 implicit-GEMM conv fprop on 128x128 tiles)",
+                           ROOFLINE_TRAFFIC_BYTES)
+    roofline["launches_per_step"] = ig_n / psteps
     classes_ms = {k: round(v["ms"] / psteps, 4) for k, v in prof.items()}
     hbm = {}
     for k in ("norm", "loss", "sgd"):

@@ -679,7 +679,7 @@ struct WgradArgs {
   int64_t M, m_per_split;
   int N, K;
   int H, W, Cin, Ho, Wo, kh, kw, stride, pad;
-  int ktiles;
+  int ktiles, tiles;  // tiles along K; tiles of dw in all
   uint32_t x_bytes, dy_bytes;
 };
 
@@ -698,10 +698,15 @@ __global__ void __launch_bounds__(256) wgrad_kernel(WgradArgs a) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wn0 = (wave & 1) * WNT, wk0 = (wave >> 1) * WKT;
-  const int n0 = (blockIdx.x / a.ktiles) * BN, k0 = (blockIdx.x % a.ktiles) * BKK;
+  // One-dimensional grid of tiles x splits, renumbered per XCD: the tiles of one pixel range (they
+  // read the same rows of dy, and the same rows of x up to the filter's reach) run side by side on
+  // one XCD and share those rows in its L2 instead of each fetching them from memory.
+  const unsigned wg = xcd_remap(blockIdx.x, gridDim.x);
+  const unsigned split = wg / (unsigned)a.tiles, tile = wg - split * (unsigned)a.tiles;
+  const int n0 = (int)(tile / (unsigned)a.ktiles) * BN, k0 = (int)(tile % (unsigned)a.ktiles) * BKK;
   // pixel and element indices fit 32 bits: every operand is smaller than 2 GiB (conv_mfma_supported)
   const int M = (int)a.M;
-  const int mbeg = (int)blockIdx.y * (int)a.m_per_split;
+  const int mbeg = (int)split * (int)a.m_per_split;
   const int mend = mbeg + (int)a.m_per_split < M ? mbeg + (int)a.m_per_split : M;
   const __amdgpu_buffer_rsrc_t rx_src = make_rsrc(a.x, a.x_bytes);
   const __amdgpu_buffer_rsrc_t rdy = make_rsrc(a.dy, a.dy_bytes);
@@ -851,7 +856,7 @@ __global__ void __launch_bounds__(256) wgrad_kernel(WgradArgs a) {
     read_frags(df[0], xf[0], 0);
   }
 
-  float* out = a.out + (int64_t)blockIdx.y * a.N * a.K;   // N*K*4 bytes < 2^33: 32-bit element offsets inside
+  float* out = a.out + (int64_t)split * a.N * a.K;   // N*K*4 bytes < 2^33: 32-bit element offsets inside
 #pragma unroll
   for (int i = 0; i < TN; i++)
 #pragma unroll
@@ -895,11 +900,12 @@ void conv_wgrad_mfma(const bf16_t* x, const bf16_t* dy, float* dw, const ConvGeo
   a.ktiles = (int)cdiv(a.K, bk);
   const int64_t tiles = (int64_t)ntiles * a.ktiles;
   const int64_t nk = (int64_t)a.N * a.K;
-  // Workgroups to aim for.  Every split writes an fp32 copy of dw, so a launch that is bound by memory
-  // traffic anyway (1x1 filters with N*K/(N+K) below the machine's flop-per-byte ridge) runs one long
-  // workgroup per compute unit; compute-bound 1x1 launches take two, gathers over several taps four.
+  // Workgroups to aim for (measured on the layer shapes of ResNet-50 at batch 256).  Every split writes
+  // an fp32 copy of dw, so 1x1 filters with small N*K/(N+K) (few flops per byte of dy and x: the launch
+  // is bound by memory traffic whatever the split) run one long workgroup per compute unit; the other
+  // 1x1 launches take two, gathers over several taps four.
   int64_t target = 1024;
-  if (a.kh * a.kw == 1) target = (double)a.N * a.K / ((double)a.N + a.K) < 315.0 ? 256 : 512;
+  if (a.kh * a.kw == 1) target = (double)a.N * a.K / ((double)a.N + a.K) < 150.0 ? 256 : 512;
   if (g_tune_co > 0) target = g_tune_co;
   int64_t splits = cdiv(target, tiles);
   const int64_t max_by_m = cdiv(a.M, 4 * WG_MS);
@@ -910,7 +916,8 @@ void conv_wgrad_mfma(const bf16_t* x, const bf16_t* dy, float* dw, const ConvGeo
   a.m_per_split = cdiv(cdiv(a.M, splits), WG_MS) * WG_MS;
   splits = cdiv(a.M, a.m_per_split);
   a.out = splits == 1 ? dw : partials;
-  dim3 grid((unsigned)tiles, (unsigned)splits);
+  a.tiles = (int)tiles;
+  dim3 grid((unsigned)(tiles * splits));
   if (bn == 128 && bk == 128) hipLaunchKernelGGL((wgrad_kernel<128, 128>), grid, dim3(256), 0, s, a);
   else if (bn == 128) hipLaunchKernelGGL((wgrad_kernel<128, 64>), grid, dim3(256), 0, s, a);
   else if (bk == 128) hipLaunchKernelGGL((wgrad_kernel<64, 128>), grid, dim3(256), 0, s, a);
