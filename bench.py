@@ -6,14 +6,17 @@ already resident in HBM: local forward (kept for backward), peer forward
 Workload: two ResNet-50 (bf16 compute, fp32 master weights), batch 256 of
 224x224x3 images ~ N(0,1), 1000 uniform classes, alpha = 1.
 
-Prints ONE JSON line.  `roofline` is for the kernel that takes the most time, the
-bf16 MFMA implicit-GEMM convolution igemm_kernel<0,128,128,2,2,false,true,1,false>
-(every fprop launch on 128x128 tiles): algorithmic flops / HIP-event time of those
-launches, measured in a second pass of the same steps with the library's
-per-launch event timer (events on the launch stream) switched on; that pass keeps
-every launch on one stream, while the timed steps run the peer forward and the
-weight gradients on second streams.  `cpu_baseline` is
-the float64 NumPy oracle of the same step timed on the host on a small batch.
+Prints ONE JSON line.  `roofline` is for the kernel that takes the most time of the step,
+bn_apply_k<bf16,8,true> (the elementwise pass of every BatchNorm forward, both models):
+HBM-bound, algorithmic bytes (input, residual, output and ReLU bit mask, each once) over
+the HIP-event time of its launches.  `roofline_conv` is the same for the convolution kernel
+that takes the most time, igemm_kernel<0,128,256,2,2,false,true,1,false,0,false> (bf16 MFMA
+implicit GEMM, forward, 128x256 tiles): its arithmetic intensity decides which roof bounds
+it, and its fraction of the MFMA peak is given either way.  Both are measured in a second
+pass of the same steps with the library's per-launch event timer (events on the launch
+stream) switched on; that pass keeps every launch on one stream, while the timed steps run
+the peer forward and the weight gradients on second streams.  `cpu_baseline` is the float64
+NumPy oracle of the same step timed on the host on a small batch.
 """
 import argparse
 import json
@@ -27,10 +30,11 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 
-# HBM bytes per launch of the roofline kernel from hardware counters (two rocprofv3 --pmc passes of this
-# script, FETCH_SIZE then WRITE_SIZE, each scaled by what the same counter read for the 1 GiB copy of
-# --copy-calibration).  Valid only for the kernel the counters were taken on: set to None when it changes.
-ROOFLINE_TRAFFIC_BYTES = 231.8e6   # FETCH_SIZE 50153.0 KiB x 2.000 + WRITE_SIZE 126033.6 KiB x 1.000
+# HBM bytes per launch of the two roofline kernels from hardware counters (two rocprofv3 --pmc passes of
+# this script, FETCH_SIZE then WRITE_SIZE, each scaled by what the same counter read for the 1 GiB copy of
+# --copy-calibration).  Valid only for the kernels the counters were taken on: set to None when one changes.
+ROOFLINE_TRAFFIC_BYTES = None        # bn_apply_k<bf16,8,true>
+ROOFLINE_CONV_TRAFFIC_BYTES = None   # igemm_kernel<0,128,256,2,2,false,true,1,false,0,false>
 
 
 def roofline_of(flops, nbytes, ms, launches, kernel, traffic):
@@ -250,14 +254,19 @@ def main():
     torch.cuda.synchronize()
     prof = B.profile_collect()
     B.profile_enable(False)
-    ig_ms, ig_n, ig_fl = prof["conv_fprop"]["ms"], prof["conv_fprop"]["launches"], prof["conv_fprop"]["flops"]
-    roofline = roofline_of(ig_fl, prof["conv_fprop"]["bytes"], ig_ms, ig_n,
-                           "igemm_kernel<0,128,128,2,2,false,true,1,false> (bf16 implicit-GEMM conv fprop on 128x128 tiles)",
+    bn = prof["bn_apply"]
+    roofline = roofline_of(bn["flops"], bn["bytes"], bn["ms"], bn["launches"],
+                           "bn_apply_k<bf16,8,true> (BatchNorm forward: normalise, add the residual, ReLU, bit mask)",
                            ROOFLINE_TRAFFIC_BYTES)
-    roofline["launches_per_step"] = ig_n / psteps
+    roofline["launches_per_step"] = bn["launches"] / psteps
+    cw = prof["conv_fprop_wide"]
+    roofline_conv = roofline_of(cw["flops"], cw["bytes"], cw["ms"], cw["launches"],
+                                "igemm_kernel<0,128,256,2,2,false,true,1,false,0,false> (bf16 implicit-GEMM conv fprop on "
+                                "128x256 tiles, BatchNorm column sums in the epilogue)", ROOFLINE_CONV_TRAFFIC_BYTES)
+    roofline_conv["launches_per_step"] = cw["launches"] / psteps
     classes_ms = {k: round(v["ms"] / psteps, 4) for k, v in prof.items()}
     hbm = {}
-    for k in ("norm", "loss", "sgd"):
+    for k in ("bn_apply", "norm", "loss", "sgd"):
         if prof[k]["ms"] > 0:
             hbm[k] = {"GB/s": prof[k]["bytes"] / (prof[k]["ms"] * 1e-3) / 1e9}
             hbm[k]["frac"] = hbm[k]["GB/s"] / PEAK_HBM_GBS
@@ -272,6 +281,7 @@ def main():
                    "distillation": "mse_logits", "lr": lr, "momentum": mu},
         "loss": [float(v) for v in loss[:3]],
         "roofline": roofline,
+        "roofline_conv": roofline_conv,
         "kernel_class_ms_per_step": classes_ms,
         "hbm_kernels": hbm,
         "loss_kernel_8192x32768": loss_cfg5,

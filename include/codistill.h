@@ -237,10 +237,13 @@ int codistill_tensor_info(const cd_model* m, int64_t batch, int64_t idx, cd_act_
 /* kernel classes for the built-in timer */
 enum {
   CD_K_CONV_FPROP = 0,        /* bf16 MFMA fprop launches on 128x128 tiles (one kernel symbol) */
-  CD_K_CONV_DGRAD = 1, CD_K_CONV_WGRAD = 2, CD_K_NORM = 3,
+  CD_K_CONV_DGRAD = 1, CD_K_CONV_WGRAD = 2,
+  CD_K_NORM = 3,              /* normalisation launches other than CD_K_BN_APPLY */
   CD_K_GLUE = 4, CD_K_LINEAR = 5, CD_K_LOSS = 6, CD_K_SGD = 7,
   CD_K_CONV_FPROP_NARROW = 8, /* every other fprop launch (other tile shapes, plain kernels) */
-  CD_K_COUNT = 9
+  CD_K_BN_APPLY = 9,          /* BatchNorm forward: the elementwise normalise (+ residual, ReLU) kernel alone */
+  CD_K_CONV_FPROP_WIDE = 10,  /* bf16 MFMA fprop launches on 128x256 tiles (one kernel symbol) */
+  CD_K_COUNT = 11
 };
 /* When enabled, every launch is bracketed by HIP events on the launch stream and the events are
  * kept in a host-side pool (created at enable time; no device memory).  host. */

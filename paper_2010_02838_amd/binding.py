@@ -20,7 +20,8 @@ CD_MEAN_ALL, CD_MEAN_ROWS = 0, 1
 CD_BN_BATCH_STATS, CD_BN_RUNNING = 0, 1
 CD_ARCH_TINY_CNN, CD_ARCH_RESNET_BASIC, CD_ARCH_RESNET_BOTTLENECK, CD_ARCH_TRANSFORMER_HEAD = 0, 1, 2, 3
 CD_MAX_STAGES, CD_NAME_LEN, CD_LOSS_MAX_PEERS = 4, 48, 8
-KERNEL_CLASSES = ["conv_fprop", "conv_dgrad", "conv_wgrad", "norm", "glue", "linear", "loss", "sgd", "conv_fprop_narrow"]
+KERNEL_CLASSES = ["conv_fprop", "conv_dgrad", "conv_wgrad", "norm", "glue", "linear", "loss", "sgd", "conv_fprop_narrow",
+                  "bn_apply", "conv_fprop_wide"]
 PARAM_KINDS = ["conv_w", "bias", "bn_gamma", "bn_beta", "linear_w"]
 
 
@@ -143,7 +144,7 @@ class Model:
         self.torch_dtype = torch.bfloat16 if dtype == CD_BF16 else torch.float32
 
     def __del__(self):
-        if getattr(self, "_h", None):
+        if getattr(self, "_h", None) and lib is not None:   # module globals are gone at interpreter exit
             lib.codistill_model_destroy(self._h)
             self._h = None
 

@@ -479,8 +479,11 @@ static int igemm_tile(int64_t M, int N, int K) {
   const double e128 = (double)t128 / (double)(cdiv(t128, 768) * 768), e256 = (double)t256 / (double)(cdiv(t256, 512) * 512);
   return e256 > 1.2 * e128 ? TILE_TALL : TILE_SQUARE;
 }
-bool conv_fprop_square_tile(const ConvGeom& g) {
-  return g.Cout > 64 && (g.Cin < BK || igemm_tile(g.M(), g.Cout, (int)g.K()) == TILE_SQUARE);
+int conv_fprop_tile_class(const ConvGeom& g, bool bias) {
+  if (g.Cout <= 64) return 2;
+  if (g.Cin < BK || bias) return 0;
+  const int t = igemm_tile(g.M(), g.Cout, (int)g.K());
+  return t == TILE_SQUARE ? 0 : (t == TILE_WIDE ? 1 : 2);
 }
 
 // returns the number of m-tiles (= statistics chunks when STATS)

@@ -34,13 +34,14 @@ void colsum(int dtype, const void* a, int64_t M, int C, float* out, float* parti
 // relu_mask (nullable; bf16 with C % 8 == 0 only): M*C/8 bytes, bit k of byte i = (y[8i + k] > 0).  The
 // forward pass writes it, the backward pass reads it instead of y (an eighth of a byte per element
 // instead of two bytes, in both of its passes).
-void bn_forward(int dtype, const void* x, const void* gamma, const void* beta, const void* res, bool relu, void* y,
-                int64_t M, int C, float* stats, float* partials, uint8_t* relu_mask, hipStream_t s);
-// Same, with the column sums already in partials ([chunks][stat_pitch(C)], from the producing
-// convolution); scratch: room for 32 * stat_pitch(C) floats behind them.
-void bn_forward_partials(int dtype, const void* x, const void* gamma, const void* beta, const void* res, bool relu,
-                         void* y, int64_t M, int C, float* stats, const float* partials, int chunks, float* scratch,
-                         uint8_t* relu_mask, hipStream_t s);
+// Two steps.  bn_stats: the batch statistics of x into stats; with pre_chunks > 0 the column sums are
+// already in partials ([pre_chunks][stat_pitch(C)], from the producing convolution; scratch: room for
+// 32 * stat_pitch(C) floats behind them), with pre_chunks == 0 x is reduced first (partials is scratch).
+// bn_apply: the elementwise pass with those statistics.
+void bn_stats(int dtype, const void* x, const void* gamma, const void* beta, int64_t M, int C, float* stats,
+              float* partials, int pre_chunks, float* scratch, hipStream_t s);
+void bn_apply(int dtype, const void* x, const void* res, bool relu, void* y, int64_t M, int C, const float* stats,
+              uint8_t* relu_mask, hipStream_t s);
 // dz = dy * (relu ? y > 0 : 1); dgamma = sum dz*xhat; dbeta = sum dz;
 // dx = gamma*invstd*(dz - dbeta/M - xhat*dgamma/M); dres = dz.  coef: [3][C] fp32 scratch.
 void bn_backward(int dtype, const void* dy, const void* y, const void* x, const void* gamma, const float* stats,
@@ -82,12 +83,12 @@ namespace cd {
 bool conv_mfma_supported(const ConvGeom& g);
 // y[M][Cout] = im2col(x)[M][K] * w[Cout][K]^T.  With stat_partials the kernel also writes per-tile
 // column sums and sums of squares, [chunks][stat_pitch(Cout)] fp32, and returns the number of chunks
-// (needs (M/128 + 1) * stat_pitch(Cout) floats); see bn_forward_partials.
+// (needs (M/128 + 1) * stat_pitch(Cout) floats); see bn_stats.
 // bias (nullable, [Cout] bf16) is added and, with relu, the result clamped at zero before rounding.
 int conv_fprop_mfma(const bf16_t* x, const bf16_t* w, const bf16_t* bias, bool relu, bf16_t* y, const ConvGeom& g,
                     float* stat_partials, hipStream_t s);
-// whether conv_fprop_mfma runs this shape on 128x128 tiles (the taller and wider tiles are other kernels)
-bool conv_fprop_square_tile(const ConvGeom& g);
+// which kernel conv_fprop_mfma runs this shape with: 0 the 128x128 tiles, 1 the 128x256 tiles, 2 any other
+int conv_fprop_tile_class(const ConvGeom& g, bool bias);
 // dx[B*H*W][Cin] (+)= gather(dy)[.][taps*Cout] * wt[Cin][taps*Cout]^T.  w is the filter as stored; wt is
 // scratch of at least Cout*K + 32 elements that receives its re-laid-out copy (or copies, per parity
 // class, for stride 2).

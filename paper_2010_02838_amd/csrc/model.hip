@@ -498,7 +498,8 @@ extern "C" int codistill_forward(const cd_model* m, const void* params, const vo
             src = c.xpack();
             w = c.wpack();
           }
-          ProfScope pr(conv_fprop_square_tile(g) ? CD_K_CONV_FPROP : CD_K_CONV_FPROP_NARROW, c.s,
+          const int tc = conv_fprop_tile_class(g, o.pb >= 0);
+          ProfScope pr(tc == 0 ? CD_K_CONV_FPROP : (tc == 1 ? CD_K_CONV_FPROP_WIDE : CD_K_CONV_FPROP_NARROW), c.s,
                        2.0 * g.M() * g.Cout * g.K(),
                        conv_bytes(m, g));
           // a BatchNorm that follows directly gets its column sums from the convolution's epilogue
@@ -515,15 +516,19 @@ extern "C" int codistill_forward(const cd_model* m, const void* params, const vo
       }
       case OP_BN: {
         const int64_t M = batch * tx.h * tx.w;
-        ProfScope pr(CD_K_NORM, c.s, 0, (double)M * tx.c * m->esize() * (3 + (o.res >= 0 ? 1 : 0)));
         uint8_t* mask = c.plan.aux[oi] ? reinterpret_cast<uint8_t*>(c.ws + c.plan.aux[oi]) : nullptr;
-        if (stat_tensor == o.x)
-          bn_forward_partials(dt, in, c.P(o.pw), c.P(o.pb), o.res >= 0 ? c.act(o.res) : nullptr, o.relu, out, M, tx.c,
-                              c.stats(o), c.partials(), stat_chunks, c.partials() + (size_t)stat_chunks * stat_pitch(tx.c), mask,
-                              c.s);
-        else
-          bn_forward(dt, in, c.P(o.pw), c.P(o.pb), o.res >= 0 ? c.act(o.res) : nullptr, o.relu, out, M, tx.c,
-                     c.stats(o), c.partials(), mask, c.s);
+        const bool fused = stat_tensor == o.x;   // the column sums came with the convolution
+        const void* res = o.res >= 0 ? c.act(o.res) : nullptr;
+        {
+          ProfScope pr(CD_K_NORM, c.s, 0, fused ? 0.0 : (double)M * tx.c * m->esize());
+          bn_stats(dt, in, c.P(o.pw), c.P(o.pb), M, tx.c, c.stats(o), c.partials(), fused ? stat_chunks : 0,
+                   fused ? c.partials() + (size_t)stat_chunks * stat_pitch(tx.c) : nullptr, c.s);
+        }
+        {
+          ProfScope pr(CD_K_BN_APPLY, c.s, 0,
+                       (double)M * tx.c * (m->esize() * (2 + (res ? 1 : 0)) + (o.relu && mask ? 0.125 : 0.0)));
+          bn_apply(dt, in, res, o.relu, out, M, tx.c, c.stats(o), mask, c.s);
+        }
         stat_tensor = -1;
         break;
       }

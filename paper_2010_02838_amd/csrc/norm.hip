@@ -315,7 +315,9 @@ __global__ void __launch_bounds__(256) bn_bwd_apply_k(const T* __restrict__ dy, 
   const bool use_mask = VEC == 8 && mask != nullptr;
   const int vc = C / VEC;
   const int64_t stride = (int64_t)gridDim.x * 256;
-  const int64_t i0 = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  // last rows first: the reduction that ran just before read them last, so they are the part of dy
+  // and x that the memory-side cache still holds
+  const int64_t i0 = (int64_t)(gridDim.x - 1 - blockIdx.x) * 256 + threadIdx.x;
   float c1[VEC], c2[VEC], c3[VEC];
   if (FIXC) {
     const int c0 = (int)(i0 % vc) * VEC;
@@ -421,11 +423,12 @@ static ReducePlan launch_reduce(const T* a0, const T* a1, const T* a2, const flo
   return p;
 }
 
-// pre_chunks > 0: the column sums are already in partials (written by the producing convolution)
+// Batch statistics -> stats.  pre_chunks > 0: the column sums are already in partials (written by the
+// producing convolution); otherwise x is reduced first.
 template <typename T>
-static void bn_forward_t(const T* x, const T* gamma, const T* beta, const T* res, bool relu, T* y, int64_t M, int C,
-                         float* stats, float* partials, int pre_chunks, float* scratch, uint8_t* mask, hipStream_t s) {
-  const int vec = pick_vec<T>(C, x, res, y, nullptr);
+static void bn_stats_t(const T* x, const T* gamma, const T* beta, int64_t M, int C, float* stats, float* partials,
+                       int pre_chunks, float* scratch, hipStream_t s) {
+  const int vec = pick_vec<T>(C, x, nullptr, nullptr, nullptr);
   constexpr int V = sizeof(T) == 2 ? 8 : 4;
   int chunks = pre_chunks;
   const float* src = partials;
@@ -440,6 +443,14 @@ static void bn_forward_t(const T* x, const T* gamma, const T* beta, const T* res
   }
   hipLaunchKernelGGL((col_finalize_k<T, 0>), dim3((unsigned)cdiv(C, 64)), dim3(1024), 0, s, src, chunks, M, C,
                      gamma, beta, stats, (float*)nullptr, (float*)nullptr, (float*)nullptr);
+}
+
+// y = relu?(scale * x + shift (+ res)) with the scale and shift that bn_stats_t left in stats
+template <typename T>
+static void bn_apply_t(const T* x, const T* res, bool relu, T* y, int64_t M, int C, const float* stats, uint8_t* mask,
+                       hipStream_t s) {
+  const int vec = pick_vec<T>(C, x, res, y, nullptr);
+  constexpr int V = sizeof(T) == 2 ? 8 : 4;
   const int64_t nvec = M * C / vec;
   bool fixc;
   const unsigned blocks = elt_grid(nvec, C / vec, kEltUnroll, &fixc);
@@ -483,24 +494,20 @@ static void colsum_t(const T* a, int64_t M, int C, float* out, float* partials, 
                      (const T*)nullptr, (const T*)nullptr, (float*)nullptr, out, (float*)nullptr, (float*)nullptr);
 }
 
-void bn_forward(int dtype, const void* x, const void* gamma, const void* beta, const void* res, bool relu, void* y,
-                int64_t M, int C, float* stats, float* partials, uint8_t* relu_mask, hipStream_t s) {
+void bn_stats(int dtype, const void* x, const void* gamma, const void* beta, int64_t M, int C, float* stats,
+              float* partials, int pre_chunks, float* scratch, hipStream_t s) {
   if (dtype == CD_BF16)
-    bn_forward_t<bf16_t>((const bf16_t*)x, (const bf16_t*)gamma, (const bf16_t*)beta, (const bf16_t*)res, relu,
-                         (bf16_t*)y, M, C, stats, partials, 0, nullptr, relu_mask, s);
+    bn_stats_t<bf16_t>((const bf16_t*)x, (const bf16_t*)gamma, (const bf16_t*)beta, M, C, stats, partials, pre_chunks,
+                       scratch, s);
   else
-    bn_forward_t<float>((const float*)x, (const float*)gamma, (const float*)beta, (const float*)res, relu, (float*)y, M,
-                        C, stats, partials, 0, nullptr, nullptr, s);
+    bn_stats_t<float>((const float*)x, (const float*)gamma, (const float*)beta, M, C, stats, partials, pre_chunks, scratch, s);
 }
-void bn_forward_partials(int dtype, const void* x, const void* gamma, const void* beta, const void* res, bool relu,
-                         void* y, int64_t M, int C, float* stats, const float* partials, int chunks, float* scratch,
-                         uint8_t* relu_mask, hipStream_t s) {
+void bn_apply(int dtype, const void* x, const void* res, bool relu, void* y, int64_t M, int C, const float* stats,
+              uint8_t* relu_mask, hipStream_t s) {
   if (dtype == CD_BF16)
-    bn_forward_t<bf16_t>((const bf16_t*)x, (const bf16_t*)gamma, (const bf16_t*)beta, (const bf16_t*)res, relu,
-                         (bf16_t*)y, M, C, stats, const_cast<float*>(partials), chunks, scratch, relu_mask, s);
+    bn_apply_t<bf16_t>((const bf16_t*)x, (const bf16_t*)res, relu, (bf16_t*)y, M, C, stats, relu_mask, s);
   else
-    bn_forward_t<float>((const float*)x, (const float*)gamma, (const float*)beta, (const float*)res, relu, (float*)y, M,
-                        C, stats, const_cast<float*>(partials), chunks, scratch, nullptr, s);
+    bn_apply_t<float>((const float*)x, (const float*)res, relu, (float*)y, M, C, stats, relu_mask, s);
 }
 void bn_backward(int dtype, const void* dy, const void* y, const void* x, const void* gamma, const float* stats,
                  bool relu, void* dx, bool acc_dx, void* dres, bool acc_dres, float* dgamma, float* dbeta, float* coef,
