@@ -222,6 +222,14 @@ typedef struct {
   int32_t k, stride, pad;  /* window of CD_OP_CONV / CD_OP_MAXPOOL                              */
   int64_t stats_offset;    /* CD_OP_BN: byte offset of fp32 [4][C] = mean, invstd, scale, shift;
                               CD_OP_LN: of fp32 [batch][2] = mean, rstd per row                 */
+  int32_t res_grad;        /* CD_OP_BN with a residual input: how the backward pass hands on the gradient of
+                              that input (this op's dy, gated by its ReLU).  0: added to the residual tensor's
+                              gradient buffer.  1: not written; the op that produced the residual tensor (a
+                              ReLU-free BatchNorm read by nothing else) reads this op's dy through the ReLU bit
+                              mask, and the residual tensor's gradient buffer stays unused.  2: not written by
+                              this op; the data gradient of the one convolution that reads the same tensor adds
+                              it, so the buffer holds the complete gradient after that launch.            */
+  int32_t reserved;
 } cd_op_info;
 typedef struct {
   int32_t h, w, c;         /* per-sample shape; the tensor is [batch][h][w][c]                  */

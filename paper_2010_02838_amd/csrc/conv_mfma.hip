@@ -31,7 +31,13 @@ struct IgemmArgs {
   int Hs, Ws, Cs, Hd, Wd, kh, kw, stride, pad, pad_w;
   // output row m = (b, hd, wd) is written to row (b*Ho + hd*omul + ooff_h)*Wo + wd*omul + ooff_w of dst
   int omul, ooff_h, ooff_w, Ho, Wo;
-  int accumulate;
+  int accumulate;     // the result is added to what dst holds, or to `addend` when that is set
+  // accumulate only (nullable): a second tensor [M][N] added instead of the old contents of dst, and
+  // (nullable) its gate, one bit per element (bit k of byte i gates element 8i + k): a cleared bit
+  // drops the addend's element.  Lets a data gradient pick up the gated gradient of a residual branch
+  // without that branch's gradient ever being written out.
+  const bf16_t* addend = nullptr;
+  const uint8_t* addend_gate = nullptr;
   int pointwise;  // kh = kw = 1, stride 1, no padding (set by the launcher)
   int group_m;    // GROUP kernels: tile order in groups of this many row tiles
   int ntiles;
@@ -413,10 +419,18 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
             ssum[2 * q + 1] += f1; ssq[2 * q + 1] += f1 * f1;
           }
         }
-        bf16_t* dp = a.dst + ((unsigned)m * (unsigned)a.N + (unsigned)n);
+        const unsigned idx = (unsigned)m * (unsigned)a.N + (unsigned)n;
+        bf16_t* dp = a.dst + idx;
         if (a.accumulate) {
-          const uint4 o = *reinterpret_cast<const uint4*>(dp);
-          const uint32_t vv[4] = {v.x, v.y, v.z, v.w}, oo[4] = {o.x, o.y, o.z, o.w};
+          const uint4 o = *reinterpret_cast<const uint4*>(a.addend ? a.addend + idx : dp);
+          const uint32_t vv[4] = {v.x, v.y, v.z, v.w};
+          uint32_t oo[4] = {o.x, o.y, o.z, o.w};
+          if (a.addend_gate) {
+            const uint32_t bits = a.addend_gate[idx >> 3];
+#pragma unroll
+            for (int q = 0; q < 4; q++)
+              oo[q] &= ((bits >> (2 * q)) & 1u ? 0x0000ffffu : 0u) | ((bits >> (2 * q + 1)) & 1u ? 0xffff0000u : 0u);
+          }
           uint32_t r[4];
 #pragma unroll
           for (int q = 0; q < 4; q++)
@@ -603,7 +617,7 @@ __global__ void __launch_bounds__(256) fill_zero16_k(uint4* p, int64_t n) {
 }
 
 void conv_dgrad_mfma(const bf16_t* dy, const bf16_t* w, bf16_t* wt, bf16_t* dx, const ConvGeom& g, bool accumulate,
-                     hipStream_t s) {
+                     hipStream_t s, const bf16_t* addend, const uint8_t* addend_gate) {
   IgemmArgs a;
   a.bias = nullptr;
   a.stat_partials = nullptr;
@@ -620,7 +634,9 @@ void conv_dgrad_mfma(const bf16_t* dy, const bf16_t* w, bf16_t* wt, bf16_t* dx, 
     a.Hd = g.H; a.Wd = g.W;
     a.kh = g.kh; a.kw = g.kw; a.stride = 1; a.pad = g.pad; a.pad_w = g.pad;
     a.omul = 0; a.ooff_h = a.ooff_w = 0;
-    a.accumulate = accumulate ? 1 : 0;
+    a.accumulate = (accumulate || addend) ? 1 : 0;
+    a.addend = addend;          // stride 1 only (see the declaration); never together with accumulate
+    a.addend_gate = addend_gate;
     a.wt_bytes = (uint32_t)((int64_t)g.Cout * g.K() * 2);
     launch_igemm<1, false>(a, s);
     return;

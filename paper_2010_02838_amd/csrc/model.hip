@@ -192,6 +192,13 @@ bool force_simple() {
   return e && e[0] == '1';
 }
 
+// CODISTILL_WRITE_RESIDUAL_GRADS=1 makes every BatchNorm write the gradient of its residual input
+// (debugging aid; see residual_grad_route)
+bool force_residual_grads() {
+  const char* e = getenv("CODISTILL_WRITE_RESIDUAL_GRADS");
+  return e && e[0] == '1';
+}
+
 // CODISTILL_SERIAL=1 keeps every launch of a call on the caller's stream (debugging aid)
 bool force_serial() {
   const char* e = getenv("CODISTILL_SERIAL");
@@ -227,6 +234,39 @@ ConvGeom packed_geom(const ConvGeom& g) {
 bool use_mfma(const cd_model* m, const ConvGeom& g) {
   if (m->dtype != CD_BF16 || force_simple()) return false;
   return conv_mfma_supported(packed_geom(g));
+}
+
+// How the backward pass of BatchNorm op i hands the gradient of its residual input on (that gradient
+// is the op's own dy, gated by its ReLU).  Where the branch's next reader can take "dy and the ReLU
+// bit mask" in place of a tensor, the gradient is never written out:
+//  1: the residual is the output of a ReLU-free BatchNorm used nowhere else (a projection shortcut):
+//     that layer's backward pass reads dy through the mask;
+//  2: the residual is read by exactly one other op, a stride-1 convolution on the MFMA kernels that
+//     comes earlier in the graph (the block input of an identity block): that convolution's data
+//     gradient adds the gated dy in its epilogue;
+//  0: it is added to the residual tensor's gradient buffer.
+int residual_grad_route(const cd_model* m, int i, int64_t batch) {
+  const Op& o = m->ops[i];
+  const int r = o.res;
+  if (o.kind != OP_BN || r <= 0 || m->dtype != CD_BF16 || force_simple() || force_residual_grads() ||
+      m->tensors[r].c % 8 != 0)
+    return 0;
+  int others = 0, conv = -1, producer = -1;
+  for (int j = 0; j < (int)m->ops.size(); j++) {
+    const Op& q = m->ops[j];
+    if (q.y == r) producer = j;
+    if (j == i) continue;
+    if (q.x == r || q.res == r) { others++; if (q.kind == OP_CONV && q.x == r && j < i) conv = j; }
+  }
+  if (others == 0 && producer >= 0) {
+    const Op& q = m->ops[producer];
+    if (q.kind == OP_BN && !q.relu && q.res < 0) return 1;
+  }
+  if (others == 1 && conv >= 0) {
+    const Op& q = m->ops[conv];
+    if (q.stride == 1 && use_mfma(m, conv_geom(m, q, batch))) return 2;
+  }
+  return 0;
 }
 
 }  // namespace
@@ -399,6 +439,8 @@ extern "C" int codistill_op_info(const cd_model* m, int64_t batch, int64_t idx, 
     out->stats_offset = (int64_t)(p.bn_stats + (size_t)4 * m->bn_off[o.bn_slot] * sizeof(float));
   }
   if (o.kind == OP_LN) out->stats_offset = (int64_t)make_plan(m, batch, true).aux[idx];
+  out->res_grad = residual_grad_route(m, (int)idx, batch);
+  out->reserved = 0;
   return CD_OK;
 }
 
@@ -602,6 +644,10 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
   hipStream_t side = (timer_enabled() || force_serial()) ? nullptr : side_stream();
   int forks = 0;
   std::vector<char> written(m->tensors.size(), 0);
+  // gradients of residual inputs that are handed on as "dy and a bit mask" instead of being written
+  // (see residual_grad_route)
+  struct Deferred { const void* src = nullptr; const uint8_t* gate = nullptr; };
+  std::vector<Deferred> deferred(m->tensors.size());
   for (int i = (int)m->ops.size() - 1; i >= 0; i--) {
     const Op& o = m->ops[i];
     const TensorDesc& tx = m->tensors[o.x];
@@ -651,12 +697,25 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
         void* dres = o.res >= 0 ? c.grad(o.res) : nullptr;
         const bool acc_res = o.res >= 0 && written[o.res];
         const uint8_t* mask = c.plan.aux[i] ? reinterpret_cast<const uint8_t*>(c.ws + c.plan.aux[i]) : nullptr;
-        // two passes over dy and x (+ y, or its sign bits, under a ReLU), dx written once (+ the residual's copy)
-        const double per_elt = m->esize() * (5 + (o.res >= 0 ? 1 : 0)) + (o.relu ? (mask ? 0.25 : 2.0 * m->esize()) : 0.0);
+        // two passes over dy and x (+ y, or its sign bits, under a ReLU), dx written once (+ the residual's copy).
+        // This layer's own dy may be a deferred one (kind 1): read it through the gate it came with.
+        const void* dy_in = dy;
+        bool gated = o.relu;
+        if (deferred[o.y].src) {
+          dy_in = deferred[o.y].src;
+          if (deferred[o.y].gate) { gated = true; mask = deferred[o.y].gate; }
+        }
+        const bool defer = o.res >= 0 && !acc_res && residual_grad_route(m, i, batch) != 0;
+        if (defer) {
+          deferred[o.res].src = dy_in;
+          deferred[o.res].gate = gated ? mask : nullptr;
+          dres = nullptr;
+        }
+        const double per_elt = m->esize() * (5 + (dres ? 1 : 0)) + (gated ? (mask ? 0.25 : 2.0 * m->esize()) : 0.0);
         ProfScope pr(CD_K_NORM, c.s, 0, (double)M * tx.c * per_elt);
-        bn_backward(dt, dy, c.act(o.y), in, c.P(o.pw), c.stats(o), o.relu, dx, acc, dres, acc_res, G(o.pw), G(o.pb),
+        bn_backward(dt, dy_in, c.act(o.y), in, c.P(o.pw), c.stats(o), gated, dx, acc, dres, acc_res, G(o.pw), G(o.pb),
                     c.coef(), c.partials(), mask, M, tx.c, c.s);
-        if (o.res >= 0) written[o.res] = 1;
+        if (o.res >= 0 && !defer) written[o.res] = 1;
         break;
       }
       case OP_LN: {
@@ -711,8 +770,10 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
         if (o.x != 0) {
           ProfScope pr(CD_K_CONV_DGRAD, c.s, 2.0 * g.M() * g.Cout * g.K(), conv_bytes(m, g));
           if (mf) {
+            const Deferred df = deferred[o.x];   // kind 2: set only where this launch can take it
+            deferred[o.x] = Deferred();
             conv_dgrad_mfma(static_cast<const bf16_t*>(dy), static_cast<const bf16_t*>(c.P(o.pw)), c.wpack(),
-                            static_cast<bf16_t*>(dx), g, acc, c.s);
+                            static_cast<bf16_t*>(dx), g, acc, c.s, static_cast<const bf16_t*>(df.src), df.gate);
           } else {
             conv_dgrad_simple(dt, dy, c.P(o.pw), dx, g, acc, c.s);
           }

@@ -116,6 +116,17 @@ def check_layers(c, got):
         assert e <= tol, (kind, what, e)
 
     expected = {}   # tensor id -> float64 sum of the oracle's gradient contributions
+    # Residual gradients that the backward pass hands on without writing them (res_grad 1): the op that
+    # produced the residual tensor reads the BatchNorm's dy through its ReLU mask; the tensor's own
+    # gradient buffer stays unused.
+    handed_on = {o["res"]: j for j, o in enumerate(ops) if o["kind"] == "bn" and o["res"] >= 0 and o["res_grad"] == 1}
+
+    def grad_in(t):
+        if t in handed_on:
+            q = ops[handed_on[t]]
+            g = grad(q["y"])
+            return L.relu_backward(act(q["y"]), g) if q["relu"] else g
+        return grad(t)
 
     def contribute(t, g):
         if t != 0:
@@ -124,7 +135,7 @@ def check_layers(c, got):
     for i, o in enumerate(ops):
         x = act(o["x"])
         y = got["logits"].astype(np.float64) if o["y"] == logits_t else act(o["y"])
-        dy = got["dz"].astype(np.float64) if o["y"] == logits_t else grad(o["y"])
+        dy = got["dz"].astype(np.float64) if o["y"] == logits_t else grad_in(o["y"])
         w = P[names[o["param_w"]]] if o["param_w"] >= 0 else None
         b = P[names[o["param_b"]]] if o["param_b"] >= 0 else None
         tag = "op%d:%s" % (i, o["kind"])
@@ -189,6 +200,8 @@ def check_layers(c, got):
     # the backward pass of a convolution with a fused ReLU masks the stored gradient of its output in place
     masked = {o["y"] for o in ops if o["kind"] == "conv" and o["relu"]}
     for t, g in expected.items():
+        if t in handed_on:
+            continue
         if t in masked:
             g = L.relu_backward(act(t), g)
         note("agrad", rel(grad(t), g), "grad of tensor %d" % t, tol_t)
@@ -247,6 +260,23 @@ def test_short_contraction_onto_many_columns_bf16_layers():
     c = Case(dict(kind=2, widths=[128], blocks=[1], stem_width=64),
              nets.resnet50(classes=10, widths=(128,), blocks=(1,), stem=64), "bf16", 40, 64, 10)
     check_layers(c, c.gpu())
+
+
+def test_residual_gradient_routes_agree(monkeypatch):
+    """The gradient of a residual input reaches its reader either through the tensor's gradient buffer or as
+    "dy and the ReLU bit mask" (a projection shortcut's BatchNorm, the first convolution of an identity block):
+    the arithmetic is the same, so the parameter gradients of a step are identical bit for bit."""
+    mk = lambda: Case(dict(kind=2, widths=[16, 32], blocks=[2, 2], stem_width=16),
+                      nets.resnet50(classes=10, widths=(16, 32), blocks=(2, 2), stem=16), "bf16", 24, 64, 10)
+    c = mk()
+    routes = [o["res_grad"] for o in c.model.graph(c.batch)[0] if o["kind"] == "bn" and o["res"] >= 0]
+    assert sorted(set(routes)) == [1, 2]
+    a = c.gpu()
+    monkeypatch.setenv("CODISTILL_WRITE_RESIDUAL_GRADS", "1")
+    assert all(o["res_grad"] == 0 for o in c.model.graph(c.batch)[0])
+    b = mk().gpu()
+    np.testing.assert_array_equal(a["grad"], b["grad"])
+    np.testing.assert_array_equal(a["theta"], b["theta"])
 
 
 @pytest.mark.parametrize("name", list(SMALL))
