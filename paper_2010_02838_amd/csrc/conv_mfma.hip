@@ -64,6 +64,20 @@ __device__ inline uint32_t pack_bf16x2(float a, float b) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
+typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+
+// Element (c, c) of a 32x32 accumulator tile held in the MFMA output layout (the lane owns column
+// lane % 32; register v holds row 8 (v / 4) + 4 (lane / 32) + v % 4), for c = lane % 32: register
+// 4 (c / 8) + c % 4, picked by a select tree.  Only the half-wave with lane / 32 == (c / 4) % 2 holds it.
+__device__ inline float tile_diagonal(f32x16_t d, int c) {
+  const bool b0 = (c & 1) != 0, b1 = (c & 2) != 0, b3 = (c & 8) != 0, b4 = (c & 16) != 0;
+  const float u0 = b0 ? d[1] : d[0], u1 = b0 ? d[3] : d[2], u2 = b0 ? d[5] : d[4], u3 = b0 ? d[7] : d[6];
+  const float u4 = b0 ? d[9] : d[8], u5 = b0 ? d[11] : d[10], u6 = b0 ? d[13] : d[12], u7 = b0 ? d[15] : d[14];
+  const float w0 = b1 ? u1 : u0, w1 = b1 ? u3 : u2, w2 = b1 ? u5 : u4, w3 = b1 ? u7 : u6;
+  const float x0 = b3 ? w1 : w0, x1 = b3 ? w3 : w2;
+  return b4 ? x1 : x0;
+}
+
 // 16-byte load through a raw buffer descriptor: an offset at or beyond the buffer size returns
 // zeros, so a masked-out vector costs one select instead of a branch around the load.
 typedef int v4i32_t __attribute__((ext_vector_type(4)));
@@ -120,8 +134,8 @@ __device__ inline int lds_off(int row, int cv) { return row * BK + ((cv ^ ((row 
 // F32OUT: the output is fp32 [M][N] (dense layers that produce logits); like the bf16 output it is
 // transposed through LDS so that a store instruction writes whole 256-byte row segments.
 // STATS: the epilogue also emits, per m-tile, the column sums and sums of squares of the bf16 values
-// it writes: the BatchNorm that follows a convolution gets its batch statistics without re-reading
-// the tensor.
+// it writes (taken from the staged rows with transposing LDS reads and two MFMAs per fragment): the
+// BatchNorm that follows a convolution gets its batch statistics without re-reading the tensor.
 // NWRAP: 1 when the gathered tensor has at least 32 channels (a 32-element step crosses at most one
 // tap boundary), 4 for 8..31 channels.
 // REMAP: output rows are placed with the strided row map of IgemmArgs (parity class of a stride-2 dgrad).
@@ -375,9 +389,9 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
   constexpr int RPP = 64 / LPR;      // rows per pass
   constexpr int TPG = EROWS / 32;    // 32-row tiles per staging pass
   const int er = lane / LPR, ec = (lane % LPR) * 8;
-  float ssum[8], ssq[8];
-#pragma unroll
-  for (int k = 0; k < 8; k++) { ssum[k] = 0.f; ssq[k] = 0.f; }
+  // STATS: per-wave column sums [WAVES_M][2][BN], behind the staging rows
+  static_assert(!STATS || EPI_BYTES + WAVES_M * 2 * BN * 4 <= SMEM, "no room for the column sums behind the staging rows");
+  float* red = reinterpret_cast<float*>(smem + EPI_BYTES);
   __syncthreads();  // the main loop's tiles are no longer read: the staging rows alias them
 #pragma unroll
   for (int g0 = 0; g0 < TM; g0 += TPG) {
@@ -396,6 +410,41 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
           *reinterpret_cast<uint2*>(stage + (j * 32 + frow) * EPITCH + i * 32 + 8 * g + 4 * (lane >> 5)) = p;
         }
     __builtin_amdgcn_wave_barrier();
+    if (STATS) {
+      // Column sums and sums of squares of the staged (rounded) rows on the matrix cores, which idle in
+      // the epilogue: the transposing LDS read hands a lane 8 pixels of its column (16 pixels x 32
+      // columns per fragment, the operand layout of wgrad_kernel); ones^T Y gives the sums in every row
+      // of one accumulator tile, Y^T Y the sums of squares on the diagonal of another.  Rows past M and
+      // columns past N were computed from zero-filled operands and add nothing.
+      const int grp = lane >> 4, li = lane & 15;
+      const int tr_m = 8 * (grp >> 1) + (li >> 2), tr_c = 16 * (grp & 1) + 4 * (li & 3);
+      const __bf16 one = (__bf16)1.0f;
+      const bf16x8_t ones = {one, one, one, one, one, one, one, one};
+      const int wmi = wave % WAVES_M, c = lane & 31;
+#pragma unroll 1
+      for (int i = 0; i < TN; i++) {   // one 32-column block at a time: two accumulator tiles live
+        f32x16_t ds, dq;
+#pragma unroll
+        for (int v = 0; v < 16; v++) { ds[v] = 0.f; dq[v] = 0.f; }
+#pragma unroll
+        for (int pc = 0; pc < EROWS / 16; pc++) {
+          const bf16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+              (CD_LDS bf16x4_t*)(stage + (pc * 16 + tr_m) * EPITCH + i * 32 + tr_c));
+          const bf16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+              (CD_LDS bf16x4_t*)(stage + (pc * 16 + tr_m + 4) * EPITCH + i * 32 + tr_c));
+          const bf16x8_t f = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          ds = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, f, ds, 0, 0, 0);
+          dq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, f, dq, 0, 0, 0);
+        }
+        // every lane holds the sum of its column, one half-wave per column the sum of squares; a later
+        // pass over further rows of the tile adds to what this lane wrote
+        float* r0 = red + (wmi * 2 + 0) * BN + wn0 + i * 32 + c;
+        float* r1 = red + (wmi * 2 + 1) * BN + wn0 + i * 32 + c;
+        const float sq = tile_diagonal(dq, c);
+        if (lane < 32) *r0 = g0 == 0 ? ds[0] : *r0 + ds[0];
+        if (((c >> 2) & 1) == (lane >> 5)) *r1 = g0 == 0 ? sq : *r1 + sq;
+      }
+    }
 #pragma unroll
     for (int p = 0; p < EROWS / RPP; p++) {
       const int row = p * RPP + er;
@@ -409,15 +458,6 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
           const int b = (int)(q / (unsigned)a.Hd);
           const int hd = (int)q - b * a.Hd;
           m = (b * a.Ho + hd * a.omul + a.ooff_h) * a.Wo + wd * a.omul + a.ooff_w;
-        }
-        if (STATS) {
-          const uint32_t u[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-          for (int q = 0; q < 4; q++) {
-            const float f0 = __uint_as_float(u[q] << 16), f1 = __uint_as_float(u[q] & 0xffff0000u);
-            ssum[2 * q] += f0; ssq[2 * q] += f0 * f0;
-            ssum[2 * q + 1] += f1; ssq[2 * q + 1] += f1 * f1;
-          }
         }
         const unsigned idx = (unsigned)m * (unsigned)a.N + (unsigned)n;
         bf16_t* dp = a.dst + idx;
@@ -443,24 +483,7 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
     }
   }
   if (STATS) {
-    // lanes that share a channel group differ in their row index: fold them, then the waves of a column
-#pragma unroll
-    for (int o = LPR; o < 64; o <<= 1)
-#pragma unroll
-      for (int k = 0; k < 8; k++) {
-        ssum[k] += __shfl_xor(ssum[k], o, 64);
-        ssq[k] += __shfl_xor(ssq[k], o, 64);
-      }
-    __syncthreads();  // staging rows are no longer read
-    float* red = reinterpret_cast<float*>(smem);  // [WAVES_M][2][BN]
-    if (lane < LPR) {
-      const int wmi = wave % WAVES_M;
-#pragma unroll
-      for (int k = 0; k < 8; k++) {
-        red[(wmi * 2 + 0) * BN + wn0 + lane * 8 + k] = ssum[k];
-        red[(wmi * 2 + 1) * BN + wn0 + lane * 8 + k] = ssq[k];
-      }
-    }
+    // fold the waves of a column
     __syncthreads();
     if (tid < BN && n0 + tid < a.N) {
       float s0 = 0.f, s1 = 0.f;
@@ -689,8 +712,6 @@ void conv_dgrad_mfma(const bf16_t* dy, const bf16_t* w, bf16_t* wt, bf16_t* dx, 
 // chunk 4e+q at pixel e, channels 4q..4q+3 therefore hands lane i four consecutive pixels of channel
 // i, which is the MFMA operand layout.  The pixel range is split over blockIdx.y; partial sums are
 // written per split and added by a second kernel in a fixed order.
-typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
-
 struct WgradArgs {
   const bf16_t* x;   // [B][H][W][Cin]
   const bf16_t* dy;  // [M][N]
