@@ -229,7 +229,9 @@ typedef struct {
                               mask, and the residual tensor's gradient buffer stays unused.  2: not written by
                               this op; the data gradient of the one convolution that reads the same tensor adds
                               it, so the buffer holds the complete gradient after that launch.            */
-  int32_t reserved;
+  int32_t fused_pool;      /* CD_OP_BN: 1 if the max-pool op that follows is computed by this op's kernel; this op's
+                              output tensor is then never written (its workspace slot stays unused), its ReLU bit
+                              mask and the pool's argmax are.                                             */
 } cd_op_info;
 typedef struct {
   int32_t h, w, c;         /* per-sample shape; the tensor is [batch][h][w][c]                  */

@@ -42,7 +42,7 @@ class OpInfo(ctypes.Structure):
     _fields_ = [("kind", ctypes.c_int32), ("x", ctypes.c_int32), ("y", ctypes.c_int32), ("res", ctypes.c_int32),
                 ("relu", ctypes.c_int32), ("param_w", ctypes.c_int32), ("param_b", ctypes.c_int32),
                 ("k", ctypes.c_int32), ("stride", ctypes.c_int32), ("pad", ctypes.c_int32),
-                ("stats_offset", ctypes.c_int64), ("res_grad", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+                ("stats_offset", ctypes.c_int64), ("res_grad", ctypes.c_int32), ("fused_pool", ctypes.c_int32)]
 
 
 class ActInfo(ctypes.Structure):

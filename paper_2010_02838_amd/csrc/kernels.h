@@ -42,6 +42,11 @@ void bn_stats(int dtype, const void* x, const void* gamma, const void* beta, int
               float* partials, int pre_chunks, float* scratch, hipStream_t s);
 void bn_apply(int dtype, const void* x, const void* res, bool relu, void* y, int64_t M, int C, const float* stats,
               uint8_t* relu_mask, hipStream_t s);
+// bn_apply with ReLU followed by a 3x3 stride-2 pad-1 max-pool, in one pass: y [B][H/2][W/2][C] is the pooled
+// tensor, the normalised one is not written.  bf16, C % 8 == 0, even H and W, 16-byte aligned pointers.
+// argmax (nullable): as maxpool_fwd writes it; relu_mask (nullable): as bn_apply writes it.
+void bn_relu_pool(const bf16_t* x, const float* stats, bf16_t* y, uint8_t* argmax, uint8_t* relu_mask, int64_t B, int H,
+                  int W, int C, hipStream_t s);
 // dz = dy * (relu ? y > 0 : 1); dgamma = sum dz*xhat; dbeta = sum dz;
 // dx = gamma*invstd*(dz - dbeta/M - xhat*dgamma/M); dres = dz.  coef: [3][C] fp32 scratch.
 void bn_backward(int dtype, const void* dy, const void* y, const void* x, const void* gamma, const float* stats,

@@ -192,6 +192,12 @@ bool force_simple() {
   return e && e[0] == '1';
 }
 
+// CODISTILL_NO_POOL_FUSION=1 keeps a BatchNorm and the max-pool behind it in separate kernels (debugging aid)
+bool force_separate_pool() {
+  const char* e = getenv("CODISTILL_NO_POOL_FUSION");
+  return e && e[0] == '1';
+}
+
 // CODISTILL_WRITE_RESIDUAL_GRADS=1 makes every BatchNorm write the gradient of its residual input
 // (debugging aid; see residual_grad_route)
 bool force_residual_grads() {
@@ -245,6 +251,21 @@ bool use_mfma(const cd_model* m, const ConvGeom& g) {
 //     comes earlier in the graph (the block input of an identity block): that convolution's data
 //     gradient adds the gated dy in its epilogue;
 //  0: it is added to the residual tensor's gradient buffer.
+// Whether BatchNorm op i (with ReLU) and the 3x3 stride-2 max-pool that follows it run as one kernel
+// (bn_relu_pool): the pool is the only reader of the normalised tensor, which is then never written.
+bool pool_fused(const cd_model* m, int i) {
+  if (i < 0 || i + 1 >= (int)m->ops.size() || m->dtype != CD_BF16 || force_simple() || force_separate_pool()) return false;
+  const Op& o = m->ops[i];
+  const Op& q = m->ops[i + 1];
+  if (o.kind != OP_BN || !o.relu || o.res >= 0 || q.kind != OP_MAXPOOL || q.x != o.y) return false;
+  if (q.k != 3 || q.stride != 2 || q.pad != 1) return false;
+  const TensorDesc& t = m->tensors[o.y];
+  if (t.h % 2 || t.w % 2 || t.c % 8) return false;
+  for (int j = 0; j < (int)m->ops.size(); j++)
+    if (j != i + 1 && (m->ops[j].x == o.y || m->ops[j].res == o.y)) return false;
+  return true;
+}
+
 int residual_grad_route(const cd_model* m, int i, int64_t batch) {
   const Op& o = m->ops[i];
   const int r = o.res;
@@ -440,7 +461,7 @@ extern "C" int codistill_op_info(const cd_model* m, int64_t batch, int64_t idx, 
   }
   if (o.kind == OP_LN) out->stats_offset = (int64_t)make_plan(m, batch, true).aux[idx];
   out->res_grad = residual_grad_route(m, (int)idx, batch);
-  out->reserved = 0;
+  out->fused_pool = pool_fused(m, (int)idx) ? 1 : 0;
   return CD_OK;
 }
 
@@ -566,7 +587,13 @@ extern "C" int codistill_forward(const cd_model* m, const void* params, const vo
           bn_stats(dt, in, c.P(o.pw), c.P(o.pb), M, tx.c, c.stats(o), c.partials(), fused ? stat_chunks : 0,
                    fused ? c.partials() + (size_t)stat_chunks * stat_pitch(tx.c) : nullptr, c.s);
         }
-        {
+        if (pool_fused(m, (int)oi)) {   // the next op, a max-pool, is computed here; `out` stays unwritten
+          const Op& q = m->ops[oi + 1];
+          ProfScope pr(CD_K_NORM, c.s, 0, (double)M * tx.c * (m->esize() * 1.25 + (mask ? 0.125 : 0.0) + (c.plan.aux[oi + 1] ? 0.25 : 0.0)));
+          bn_relu_pool(static_cast<const bf16_t*>(in), c.stats(o), static_cast<bf16_t*>(c.act(q.y)),
+                       c.plan.aux[oi + 1] ? reinterpret_cast<uint8_t*>(c.ws + c.plan.aux[oi + 1]) : nullptr, mask, batch, tx.h,
+                       tx.w, tx.c, c.s);
+        } else {
           ProfScope pr(CD_K_BN_APPLY, c.s, 0,
                        (double)M * tx.c * (m->esize() * (2 + (res ? 1 : 0)) + (o.relu && mask ? 0.125 : 0.0)));
           bn_apply(dt, in, res, o.relu, out, M, tx.c, c.stats(o), mask, c.s);
@@ -583,6 +610,7 @@ extern "C" int codistill_forward(const cd_model* m, const void* params, const vo
         break;
       }
       case OP_MAXPOOL: {
+        if (pool_fused(m, (int)oi - 1)) break;   // computed by the BatchNorm in front of it
         ProfScope pr(CD_K_GLUE, c.s, 0, (double)batch * tx.per_sample() * m->esize() * 1.25);
         maxpool_fwd(dt, in, out, c.plan.aux[oi] ? reinterpret_cast<uint8_t*>(c.ws + c.plan.aux[oi]) : nullptr, batch, tx.h,
                     tx.w, tx.c, o.k, o.stride, o.pad, c.s);

@@ -305,6 +305,70 @@ __global__ void __launch_bounds__(256) bn_apply_k(const T* __restrict__ x, const
   }
 }
 
+// BatchNorm apply + ReLU + 3x3 stride-2 pad-1 max-pool in one pass (bf16, C % 8 == 0, even H and W): the
+// normalised tensor is never written.  One thread per pooled 8-channel vector; the window's values are
+// normalised on the fly (each input is read by 2.25 windows on average, from cache).  argmax
+// (nullable) receives the window tap r*3+s of the first maximum, as maxpool_fwd_k writes it.  mask
+// (nullable) receives the ReLU sign bits of the whole normalised tensor, as bn_apply_k writes them:
+// every input pixel belongs to exactly one window as one of its taps (1..2, 1..2), and that window's
+// thread writes its byte.
+__global__ void __launch_bounds__(256) bn_relu_pool_k(const bf16_t* __restrict__ x, const float* __restrict__ stats,
+                                                      bf16_t* __restrict__ y, uint8_t* __restrict__ argmax,
+                                                      uint8_t* __restrict__ mask, int64_t B, int H, int W, int C) {
+  const int Ho = H / 2, Wo = W / 2, vc = C / 8;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= B * Ho * Wo * vc) return;
+  const int cv = (int)(idx % vc);
+  int64_t p = idx / vc;
+  const int wo = (int)(p % Wo); p /= Wo;
+  const int ho = (int)(p % Ho);
+  const int64_t b = p / Ho;
+  float sc[8], sh[8], best[8];
+  uint32_t arg[8];
+#pragma unroll
+  for (int k = 0; k < 8; k++) {
+    sc[k] = stats[2 * C + cv * 8 + k];
+    sh[k] = stats[3 * C + cv * 8 + k];
+    best[k] = -1.f;   // below every ReLU output: the first tap inside the image always wins
+    arg[k] = 0;
+  }
+  // all loads of the window first (taps outside the image re-read the centre, and are skipped below)
+  Vec<bf16_t, 8>::Raw raw[9];
+#pragma unroll
+  for (int r = 0; r < 3; r++)
+#pragma unroll
+    for (int t = 0; t < 3; t++) {
+      const int hi = 2 * ho - 1 + r, wi = 2 * wo - 1 + t;
+      const bool in = hi >= 0 && wi >= 0;   // hi <= H - 1 and wi <= W - 1 always (even H, W)
+      raw[r * 3 + t] = Vec<bf16_t, 8>::ldraw(x + ((b * H + (in ? hi : 2 * ho)) * W + (in ? wi : 2 * wo)) * C + cv * 8);
+    }
+#pragma unroll
+  for (int r = 0; r < 3; r++)
+#pragma unroll
+    for (int t = 0; t < 3; t++) {
+      const int hi = 2 * ho - 1 + r, wi = 2 * wo - 1 + t;
+      if (hi < 0 || wi < 0) continue;
+      float a[8];
+      Vec<bf16_t, 8>::unpack(raw[r * 3 + t], a);
+      uint32_t bits = 0;
+#pragma unroll
+      for (int k = 0; k < 8; k++) {
+        a[k] = fmaxf(a[k] * sc[k] + sh[k], 0.f);
+        bits |= (a[k] > 0.f ? 1u : 0u) << k;
+        if (a[k] > best[k]) { best[k] = a[k]; arg[k] = (uint32_t)(r * 3 + t); }  // strict: the first maximum wins
+      }
+      if (mask && r >= 1 && t >= 1) mask[((b * H + hi) * W + wi) * vc + cv] = (uint8_t)bits;
+    }
+  const int64_t o = ((b * Ho + ho) * Wo + wo) * C + cv * 8;
+  Vec<bf16_t, 8>::st(y + o, best);
+  if (argmax) {
+    uint2 pk;
+    pk.x = arg[0] | (arg[1] << 8) | (arg[2] << 16) | (arg[3] << 24);
+    pk.y = arg[4] | (arg[5] << 8) | (arg[6] << 16) | (arg[7] << 24);
+    *reinterpret_cast<uint2*>(argmax + o) = pk;
+  }
+}
+
 template <typename T, int VEC, bool FIXC>
 __global__ void __launch_bounds__(256) bn_bwd_apply_k(const T* __restrict__ dy, const T* __restrict__ y,
                                                       const T* __restrict__ x, const float* __restrict__ coef, int relu,
@@ -501,6 +565,12 @@ void bn_stats(int dtype, const void* x, const void* gamma, const void* beta, int
                        scratch, s);
   else
     bn_stats_t<float>((const float*)x, (const float*)gamma, (const float*)beta, M, C, stats, partials, pre_chunks, scratch, s);
+}
+void bn_relu_pool(const bf16_t* x, const float* stats, bf16_t* y, uint8_t* argmax, uint8_t* relu_mask, int64_t B, int H,
+                  int W, int C, hipStream_t s) {
+  const int64_t n = B * (H / 2) * (W / 2) * (C / 8);
+  hipLaunchKernelGGL(bn_relu_pool_k, dim3((unsigned)cdiv(n, 256)), dim3(256), 0, s, x, stats, y, argmax, relu_mask, B, H,
+                     W, C);
 }
 void bn_apply(int dtype, const void* x, const void* res, bool relu, void* y, int64_t M, int C, const float* stats,
               uint8_t* relu_mask, hipStream_t s) {
