@@ -47,6 +47,12 @@ void bn_apply(int dtype, const void* x, const void* res, bool relu, void* y, int
 // argmax (nullable): as maxpool_fwd writes it; relu_mask (nullable): as bn_apply writes it.
 void bn_relu_pool(const bf16_t* x, const float* stats, bf16_t* y, uint8_t* argmax, uint8_t* relu_mask, int64_t B, int H,
                   int W, int C, hipStream_t s);
+// Its backward pass: dpool [B][H/2][W/2][C] is the gradient of the pooled tensor, argmax and relu_mask what the
+// forward pass wrote; the gradient of the normalised tensor is gathered on the fly in both passes (never
+// written).  dx [B][H][W][C] is overwritten; dgamma, dbeta, coef, partials as in bn_backward.
+void bn_relu_pool_backward(const bf16_t* dpool, const uint8_t* argmax, const bf16_t* x, const bf16_t* gamma,
+                           const float* stats, bf16_t* dx, float* dgamma, float* dbeta, float* coef, float* partials,
+                           const uint8_t* relu_mask, int64_t B, int H, int W, int C, hipStream_t s);
 // dz = dy * (relu ? y > 0 : 1); dgamma = sum dz*xhat; dbeta = sum dz;
 // dx = gamma*invstd*(dz - dbeta/M - xhat*dgamma/M); dres = dz.  coef: [3][C] fp32 scratch.
 void bn_backward(int dtype, const void* dy, const void* y, const void* x, const void* gamma, const float* stats,

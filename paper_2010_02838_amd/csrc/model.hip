@@ -676,6 +676,13 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
   // (see residual_grad_route)
   struct Deferred { const void* src = nullptr; const uint8_t* gate = nullptr; };
   std::vector<Deferred> deferred(m->tensors.size());
+  // BatchNorm op b whose kernel also computed the max-pool behind it: its backward pass gathers its dy from
+  // the pooled gradient and the argmax, and the max-pool's own backward launch is dropped
+  auto pool_fused_bwd = [&](int b) {
+    const TensorDesc& t = m->tensors[m->ops[b].y];   // 32-bit element offsets in the gather kernels
+    return pool_fused(m, b) && m->ops[b].x != 0 && !written[m->ops[b].x] && c.plan.aux[b] != 0 && c.plan.aux[b + 1] != 0 &&
+           batch * t.per_sample() < (1LL << 31);
+  };
   for (int i = (int)m->ops.size() - 1; i >= 0; i--) {
     const Op& o = m->ops[i];
     const TensorDesc& tx = m->tensors[o.x];
@@ -715,6 +722,7 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
         break;
       }
       case OP_MAXPOOL: {
+        if (pool_fused_bwd(i - 1)) continue;   // gathered by the BatchNorm's backward pass instead (nothing written)
         ProfScope pr(CD_K_GLUE, c.s, 0, (double)batch * tx.per_sample() * m->esize() * 2.25);
         maxpool_bwd(dt, in, dy, c.plan.aux[i] ? reinterpret_cast<const uint8_t*>(c.ws + c.plan.aux[i]) : nullptr, dx, acc,
                     batch, tx.h, tx.w, tx.c, o.k, o.stride, o.pad, c.s);
@@ -725,6 +733,16 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
         void* dres = o.res >= 0 ? c.grad(o.res) : nullptr;
         const bool acc_res = o.res >= 0 && written[o.res];
         const uint8_t* mask = c.plan.aux[i] ? reinterpret_cast<const uint8_t*>(c.ws + c.plan.aux[i]) : nullptr;
+        if (pool_fused_bwd(i)) {
+          // the max-pool behind this op did not write this op's dy: both passes gather it from the pooled gradient
+          const Op& q = m->ops[i + 1];
+          ProfScope pr(CD_K_NORM, c.s, 0, (double)M * tx.c * (m->esize() * 3.5 + 0.25 + 0.5));
+          bn_relu_pool_backward(static_cast<const bf16_t*>(c.grad(q.y)), reinterpret_cast<const uint8_t*>(c.ws + c.plan.aux[i + 1]),
+                                static_cast<const bf16_t*>(in), static_cast<const bf16_t*>(c.P(o.pw)), c.stats(o),
+                                static_cast<bf16_t*>(dx), G(o.pw), G(o.pb), c.coef(), c.partials(), mask, batch, tx.h, tx.w,
+                                tx.c, c.s);
+          break;
+        }
         // two passes over dy and x (+ y, or its sign bits, under a ReLU), dx written once (+ the residual's copy).
         // This layer's own dy may be a deferred one (kind 1): read it through the gate it came with.
         const void* dy_in = dy;

@@ -369,6 +369,119 @@ __global__ void __launch_bounds__(256) bn_relu_pool_k(const bf16_t* __restrict__
   }
 }
 
+// ---- backward of bn_relu_pool_k: the gradient of the (unwritten) normalised tensor is gathered from the
+// pooled gradient and the argmax wherever it is needed, instead of being written by a max-pool backward
+// kernel and read twice.  Pixel (h, w) lies in the windows (h/2, w/2) as tap (1 + h%2, 1 + w%2) and, for
+// odd h or w, in the next window down or right as tap row / column 0.
+__device__ inline void pool_grad8(const bf16_t* __restrict__ dp, const uint8_t* __restrict__ arg, int b, int h, int w,
+                                  int H, int W, int C, int c0, float (&dz)[8]) {
+  const int Ho = H >> 1, Wo = W >> 1;
+#pragma unroll
+  for (int k = 0; k < 8; k++) dz[k] = 0.f;
+#pragma unroll
+  for (int dh = 0; dh < 2; dh++) {
+    const int ho = (h >> 1) + dh, r = dh ? 0 : 1 + (h & 1);
+    if (dh && (!(h & 1) || ho >= Ho)) continue;
+#pragma unroll
+    for (int dw = 0; dw < 2; dw++) {
+      const int wo = (w >> 1) + dw, t = dw ? 0 : 1 + (w & 1);
+      if (dw && (!(w & 1) || wo >= Wo)) continue;
+      const uint32_t o = (uint32_t)((b * Ho + ho) * Wo + wo) * (uint32_t)C + (uint32_t)c0;   // < 2^31 (checked on the host)
+      const uint2 a8 = *reinterpret_cast<const uint2*>(arg + o);
+      float g[8];
+      Vec<bf16_t, 8>::ld(dp + o, g);
+      const uint32_t tap = (uint32_t)(r * 3 + t);
+#pragma unroll
+      for (int k = 0; k < 8; k++) {
+        const uint32_t ak = ((k < 4 ? a8.x : a8.y) >> (8 * (k & 3))) & 0xffu;
+        dz[k] += ak == tap ? g[k] : 0.f;
+      }
+    }
+  }
+}
+
+// sums of dz and dz * xhat over the rows; same partials as col_reduce_k MODE 1 (finalised by col_finalize_k<., 1>)
+__global__ void __launch_bounds__(256) bn_pool_bwd_reduce_k(const bf16_t* __restrict__ dp, const uint8_t* __restrict__ arg,
+                                                            const bf16_t* __restrict__ x, const float* __restrict__ stats,
+                                                            const uint8_t* __restrict__ mask, int64_t B, int H, int W,
+                                                            int C, float* __restrict__ partials) {
+  __shared__ float sm[2][256 * 8];
+  const int vc = C / 8;
+  const int v0 = blockIdx.y * 256;
+  const int vcb = vc - v0 < 256 ? vc - v0 : 256;
+  const int rpi = 256 / vcb;
+  const int ty = threadIdx.x / vcb, tx = threadIdx.x % vcb;
+  const int c0 = (v0 + tx) * 8;
+  const int64_t M = B * H * W;
+  float s0[8], s1[8], mean[8], istd[8];
+#pragma unroll
+  for (int k = 0; k < 8; k++) { s0[k] = 0.f; s1[k] = 0.f; mean[k] = 0.f; istd[k] = 0.f; }
+  if (ty < rpi) {
+#pragma unroll
+    for (int k = 0; k < 8; k++) { mean[k] = stats[c0 + k]; istd[k] = stats[C + c0 + k]; }
+    const uint32_t rstride = gridDim.x * (uint32_t)rpi;
+    for (uint32_t r = blockIdx.x * (uint32_t)rpi + (uint32_t)ty; r < (uint32_t)M; r += rstride) {
+      const uint32_t q = r / (uint32_t)W;
+      const int w = (int)(r - q * (uint32_t)W);
+      const int b = (int)(q / (uint32_t)H);
+      const int h = (int)(q - (uint32_t)b * (uint32_t)H);
+      const uint32_t off = r * (uint32_t)C + (uint32_t)c0;
+      const typename Vec<bf16_t, 8>::Raw rx = Vec<bf16_t, 8>::ldraw(x + off);
+      const uint32_t bits = mask[off >> 3];
+      float dz[8], xv[8];
+      pool_grad8(dp, arg, b, h, w, H, W, C, c0, dz);
+      Vec<bf16_t, 8>::unpack(rx, xv);
+#pragma unroll
+      for (int k = 0; k < 8; k++) {
+        const float d = (bits >> k) & 1u ? dz[k] : 0.f;
+        s0[k] += d;
+        s1[k] += d * (xv[k] - mean[k]) * istd[k];
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < 8; k++) { sm[0][threadIdx.x * 8 + k] = s0[k]; sm[1][threadIdx.x * 8 + k] = s1[k]; }
+  }
+  __syncthreads();
+  if ((int)threadIdx.x < vcb) {
+#pragma unroll
+    for (int k = 0; k < 8; k++) {
+      float t0 = 0.f, t1 = 0.f;
+      for (int j = 0; j < rpi; j++) {
+        t0 += sm[0][(j * vcb + tx) * 8 + k];
+        t1 += sm[1][(j * vcb + tx) * 8 + k];
+      }
+      partials[(int64_t)blockIdx.x * stat_pitch(C) + c0 + k] = t0;
+      partials[(int64_t)blockIdx.x * stat_pitch(C) + C + c0 + k] = t1;
+    }
+  }
+}
+
+// dx = c1 * dz + c2 * x + c3 with the coefficients col_finalize_k<., 1> left in coef
+__global__ void __launch_bounds__(256) bn_pool_bwd_apply_k(const bf16_t* __restrict__ dp, const uint8_t* __restrict__ arg,
+                                                           const bf16_t* __restrict__ x, const float* __restrict__ coef,
+                                                           const uint8_t* __restrict__ mask, bf16_t* __restrict__ dx,
+                                                           int64_t B, int H, int W, int C) {
+  const int vc = C / 8;
+  const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+  if (i >= (uint32_t)(B * H * W * vc)) return;
+  const uint32_t r = i / (uint32_t)vc, q = r / (uint32_t)W;
+  const int c0 = (int)(i - r * (uint32_t)vc) * 8;
+  const int w = (int)(r - q * (uint32_t)W);
+  const int b = (int)(q / (uint32_t)H);
+  const int h = (int)(q - (uint32_t)b * (uint32_t)H);
+  const typename Vec<bf16_t, 8>::Raw rx = Vec<bf16_t, 8>::ldraw(x + (size_t)i * 8);
+  const uint32_t bits = mask[i];
+  float dz[8], xv[8], o[8];
+  pool_grad8(dp, arg, b, h, w, H, W, C, c0, dz);
+  Vec<bf16_t, 8>::unpack(rx, xv);
+#pragma unroll
+  for (int k = 0; k < 8; k++) {
+    const float d = (bits >> k) & 1u ? dz[k] : 0.f;
+    o[k] = coef[c0 + k] * d + coef[C + c0 + k] * xv[k] + coef[2 * C + c0 + k];
+  }
+  Vec<bf16_t, 8>::st(dx + (size_t)i * 8, o);
+}
+
 template <typename T, int VEC, bool FIXC>
 __global__ void __launch_bounds__(256) bn_bwd_apply_k(const T* __restrict__ dy, const T* __restrict__ y,
                                                       const T* __restrict__ x, const float* __restrict__ coef, int relu,
@@ -571,6 +684,22 @@ void bn_relu_pool(const bf16_t* x, const float* stats, bf16_t* y, uint8_t* argma
   const int64_t n = B * (H / 2) * (W / 2) * (C / 8);
   hipLaunchKernelGGL(bn_relu_pool_k, dim3((unsigned)cdiv(n, 256)), dim3(256), 0, s, x, stats, y, argmax, relu_mask, B, H,
                      W, C);
+}
+void bn_relu_pool_backward(const bf16_t* dpool, const uint8_t* argmax, const bf16_t* x, const bf16_t* gamma,
+                           const float* stats, bf16_t* dx, float* dgamma, float* dbeta, float* coef, float* partials,
+                           const uint8_t* relu_mask, int64_t B, int H, int W, int C, hipStream_t s) {
+  const int64_t M = B * H * W;
+  ReducePlan p = reduce_plan(M, C, 8);
+  // the gathers leave a thread one row in flight at a time: four times the usual number of blocks keeps
+  // the memory system busy instead
+  const int64_t cap = (int64_t)(kPartialsBytes / ((size_t)stat_pitch(C) * 4));
+  p.chunks = (int)(p.chunks * 4 < cap ? p.chunks * 4 : cap);
+  hipLaunchKernelGGL(bn_pool_bwd_reduce_k, dim3(p.chunks, p.cgroups), dim3(256), 0, s, dpool, argmax, x, stats, relu_mask, B,
+                     H, W, C, partials);
+  hipLaunchKernelGGL((col_finalize_k<bf16_t, 1>), dim3((unsigned)cdiv(C, 64)), dim3(1024), 0, s, partials, p.chunks, M, C,
+                     gamma, (const bf16_t*)nullptr, const_cast<float*>(stats), dgamma, dbeta, coef);
+  hipLaunchKernelGGL(bn_pool_bwd_apply_k, dim3((unsigned)cdiv(M * (C / 8), 256)), dim3(256), 0, s, dpool, argmax, x, coef,
+                     relu_mask, dx, B, H, W, C);
 }
 void bn_apply(int dtype, const void* x, const void* res, bool relu, void* y, int64_t M, int C, const float* stats,
               uint8_t* relu_mask, hipStream_t s) {
