@@ -174,3 +174,70 @@ def layernorm_backward(dy, gamma, cache):
     g = dy * gamma
     dx = rstd * (g - g.mean(axis=-1, keepdims=True) - xhat * (g * xhat).mean(axis=-1, keepdims=True))
     return dx, dgamma, dbeta
+
+
+# ------------------------------------------------------------- Transformer pieces
+def sinusoid_positions(T, d):
+    """Fixed position signal of the Transformer: PE[t, 2i] = sin(t / 10000^(2i/d)), PE[t, 2i+1] = cos(same)."""
+    t = np.arange(T, dtype=np.float64)[:, None]
+    i = np.arange(0, d, 2, dtype=np.float64)[None, :]
+    ang = t / np.power(10000.0, i / d)
+    pe = np.zeros((T, d))
+    pe[:, 0::2] = np.sin(ang)
+    pe[:, 1::2] = np.cos(ang)
+    return pe
+
+
+def embed_forward(tokens, table):
+    """tokens [S, T] integer ids -> [S*T, d]: table row times sqrt(d), plus the position signal."""
+    S, T = tokens.shape
+    d = table.shape[1]
+    x = table[tokens.astype(np.int64)] * np.sqrt(d) + sinusoid_positions(T, d)[None, :, :]
+    return x.reshape(S * T, d)
+
+
+def embed_backward(tokens, table_shape, dy):
+    """Gradient of the table: every occurrence of a token adds sqrt(d) times its row of dy."""
+    d = table_shape[1]
+    dw = np.zeros(table_shape)
+    np.add.at(dw, tokens.astype(np.int64).reshape(-1), dy.reshape(-1, d) * np.sqrt(d))
+    return dw
+
+
+def attention_forward(q, k, v, S, heads, causal):
+    """Scaled dot-product attention with several heads.  q [S*Tq, d], k, v [S*Tk, d] (sentence-major rows);
+    head h owns columns h*dh .. (h+1)*dh.  P = softmax(Q K^T / sqrt(dh)) over the keys of the same sentence
+    (causal: keys at positions <= the query's only), output P V, heads side by side.  Returns (out, P)."""
+    d = q.shape[1]
+    dh = d // heads
+    Tq, Tk = q.shape[0] // S, k.shape[0] // S
+    Q = q.reshape(S, Tq, heads, dh).transpose(0, 2, 1, 3)
+    K = k.reshape(S, Tk, heads, dh).transpose(0, 2, 1, 3)
+    V = v.reshape(S, Tk, heads, dh).transpose(0, 2, 1, 3)
+    s = np.einsum("shid,shjd->shij", Q, K) / np.sqrt(dh)
+    if causal:
+        s = np.where(np.arange(Tk)[None, :] <= np.arange(Tq)[:, None], s, -np.inf)
+    s = s - s.max(axis=-1, keepdims=True)
+    e = np.exp(s)
+    P = e / e.sum(axis=-1, keepdims=True)
+    out = np.einsum("shij,shjd->shid", P, V).transpose(0, 2, 1, 3).reshape(S * Tq, d)
+    return out, P
+
+
+def attention_backward(q, k, v, P, dout, S, heads):
+    """Returns (dq, dk, dv).  dV = P^T dO, dP = dO V^T, dS = P (dP - rowsum(dP P)), dQ = dS K / sqrt(dh),
+    dK = dS^T Q / sqrt(dh) (masked entries have P = 0 and drop out by themselves)."""
+    d = q.shape[1]
+    dh = d // heads
+    Tq, Tk = q.shape[0] // S, k.shape[0] // S
+    Q = q.reshape(S, Tq, heads, dh).transpose(0, 2, 1, 3)
+    K = k.reshape(S, Tk, heads, dh).transpose(0, 2, 1, 3)
+    V = v.reshape(S, Tk, heads, dh).transpose(0, 2, 1, 3)
+    dO = dout.reshape(S, Tq, heads, dh).transpose(0, 2, 1, 3)
+    dV = np.einsum("shij,shid->shjd", P, dO)
+    dP = np.einsum("shid,shjd->shij", dO, V)
+    dS = P * (dP - (dP * P).sum(axis=-1, keepdims=True))
+    dQ = np.einsum("shij,shjd->shid", dS, K) / np.sqrt(dh)
+    dK = np.einsum("shij,shid->shjd", dS, Q) / np.sqrt(dh)
+    back = lambda a, T: a.transpose(0, 2, 1, 3).reshape(S * T, d)
+    return back(dQ, Tq), back(dK, Tk), back(dV, Tk)

@@ -24,6 +24,18 @@ gives as 8e8 bits) without defining them; these are the standard definitions:
              layers are 1x1 convolutions over it).  The attention sublayers and the embeddings
              are not part of it.
 
+  transformer  the encoder-decoder Transformer that Section 4 trains (Vaswani et al.; base size: 6 + 6
+             layers, d_model 512, 8 heads, d_ff 2048, vocabulary 32768, shared by source, target and
+             output projection).  Input: integer token ids [S, Ts + Tt], per sentence the Ts source
+             tokens, then the Tt (shifted) target tokens; every sentence has the same lengths (no
+             padding).  Embedding rows times sqrt(d_model) plus the sinusoidal position signal; an
+             encoder layer is self-attention and feed-forward sublayers, each with a residual connection
+             followed by LayerNorm (post-LN); a decoder layer is causal self-attention, attention over
+             the encoder output, and feed-forward; the logits are the decoder output times the
+             transposed embedding table (tied, no bias).  The three (two) input projections of an
+             attention sublayer are one dense layer d -> 3d (d -> d for the queries and d -> 2d for
+             keys and values of the encoder output), with biases; no dropout.
+
 An architecture is (param_table, ops).  param_table is an ordered list of
 (name, shape, kind, fan_in); ops is a list of dicts over integer tensor ids
 (tensor 0 is the input image batch, the last op writes the logits).
@@ -106,6 +118,26 @@ class Arch:
         self.ops.append(dict(op="linear", x=x, y=y, w=w, b=b, stored=False))
         return y
 
+    def embed(self, name, vocab, d, col0, T, table=None):
+        """Rows of the embedding table for the tokens in columns col0 .. col0+T of the input."""
+        w = table if table is not None else self._p(name + ".w", (vocab, d), "embed_w", d)
+        y = self._t()
+        self.ops.append(dict(op="embed", x=0, y=y, w=w, col0=col0, T=T, stored=True))
+        return y, w
+
+    def attention(self, q, q_col, kv, k_col, v_col, d, heads, S, causal):
+        """q, k, v are column ranges of width d of tensors q and kv (which may be the same tensor)."""
+        y = self._t()
+        self.ops.append(dict(op="attn", x=q, kv=kv, y=y, q_col=q_col, k_col=k_col, v_col=v_col, d=d, heads=heads,
+                             S=S, causal=causal, stored=True))
+        return y
+
+    def tied_linear(self, x, w):
+        """Logits against an existing [vocab, d] table (no bias)."""
+        y = self._t()
+        self.ops.append(dict(op="linear", x=x, y=y, w=w, b=None, stored=False))
+        return y
+
     def n_params(self):
         return int(sum(int(np.prod(s)) for _, s, _, _ in self.params))
 
@@ -184,6 +216,41 @@ def transformer_head(d_model=512, d_ff=2048, vocab=32768):
     return a
 
 
+def transformer(S, Ts, Tt, d=512, heads=8, d_ff=2048, vocab=32768, enc_layers=6, dec_layers=6):
+    a = Arch("transformer")
+
+    def dense(x, name, fin, fout):
+        return a.conv(x, name, fin, fout, 1, 1, 0, bias=True)
+
+    def add_norm(x, sub, name):
+        return a.layernorm(a.add(sub, x), name, d)
+
+    def ffn(x, p):
+        u = a.relu(dense(x, p + ".ffn.w1", d, d_ff))
+        return add_norm(x, dense(u, p + ".ffn.w2", d_ff, d), p + ".ffn.ln")
+
+    def self_attention(x, p, causal):
+        qkv = dense(x, p + ".qkv", d, 3 * d)
+        o = a.attention(qkv, 0, qkv, d, 2 * d, d, heads, S, causal)
+        return add_norm(x, dense(o, p + ".out", d, d), p + ".ln")
+
+    x, table = a.embed("embed", vocab, d, 0, Ts)
+    for i in range(enc_layers):
+        x = ffn(self_attention(x, "enc%d.self" % i, False), "enc%d" % i)
+    memory = x
+    y, _ = a.embed("embed", vocab, d, Ts, Tt, table=table)
+    for i in range(dec_layers):
+        p = "dec%d" % i
+        y = self_attention(y, p + ".self", True)
+        q = dense(y, p + ".cross.q", d, d)
+        kv = dense(memory, p + ".cross.kv", d, 2 * d)
+        o = a.attention(q, 0, kv, 0, d, d, heads, S, False)
+        y = add_norm(y, dense(o, p + ".cross.out", d, d), p + ".cross.ln")
+        y = ffn(y, p)
+    a.tied_linear(y, table)
+    return a
+
+
 def forward(arch, params, x, store=None):
     """Training-mode forward.  params: dict name -> float64 array.  Returns (logits, tape).
     store: optional function applied to the tensors a reduced-precision pipeline keeps in memory."""
@@ -208,6 +275,16 @@ def forward(arch, params, x, store=None):
             T[o["y"]] = L.gap_forward(T[o["x"]])
         elif k == "layernorm":
             T[o["y"]], cache[i] = L.layernorm_forward(T[o["x"]], params[o["gamma"]], params[o["beta"]])
+        elif k == "embed":
+            tok = T[0][:, o["col0"]:o["col0"] + o["T"]]
+            T[o["y"]] = L.embed_forward(tok, params[o["w"]]).reshape(-1, 1, 1, params[o["w"]].shape[1])
+        elif k == "attn":
+            d = o["d"]
+            q2 = T[o["x"]].reshape(T[o["x"]].shape[0], -1)
+            kv2 = T[o["kv"]].reshape(T[o["kv"]].shape[0], -1)
+            q, kk, v = q2[:, o["q_col"]:o["q_col"] + d], kv2[:, o["k_col"]:o["k_col"] + d], kv2[:, o["v_col"]:o["v_col"] + d]
+            out, P = L.attention_forward(q, kk, v, o["S"], o["heads"], o["causal"])
+            T[o["y"]], cache[i] = out.reshape(-1, 1, 1, d), P
         elif k == "linear":
             xin = T[o["x"]]
             T[o["y"]] = L.linear_forward(xin.reshape(xin.shape[0], -1), params[o["w"]],
@@ -227,6 +304,9 @@ def backward(arch, params, tape, dlogits):
         if t == 0 or g is None:
             return
         G[t] = g if t not in G else G[t] + g
+
+    def accp(name, g):       # a parameter used by several ops (the tied embedding table) sums their gradients
+        grads[name] = g if name not in grads else grads[name] + g
 
     for i in reversed(range(len(arch.ops))):
         o = arch.ops[i]
@@ -256,10 +336,29 @@ def backward(arch, params, tape, dlogits):
             dx, dg, db = L.layernorm_backward(dy, params[o["gamma"]], cache[i])
             grads[o["gamma"]], grads[o["beta"]] = dg, db
             acc(o["x"], dx)
+        elif k == "embed":
+            tok = T[0][:, o["col0"]:o["col0"] + o["T"]]
+            accp(o["w"], L.embed_backward(tok, params[o["w"]].shape, dy))
+        elif k == "attn":
+            d = o["d"]
+            xq, xkv = T[o["x"]], T[o["kv"]]
+            q2, kv2 = xq.reshape(xq.shape[0], -1), xkv.reshape(xkv.shape[0], -1)
+            q, kk, v = q2[:, o["q_col"]:o["q_col"] + d], kv2[:, o["k_col"]:o["k_col"] + d], kv2[:, o["v_col"]:o["v_col"] + d]
+            dq, dk, dv = L.attention_backward(q, kk, v, cache[i], dy.reshape(-1, d), o["S"], o["heads"])
+            gq, gkv = np.zeros_like(q2), np.zeros_like(kv2)
+            gq[:, o["q_col"]:o["q_col"] + d] += dq
+            if o["kv"] == o["x"]:
+                gq[:, o["k_col"]:o["k_col"] + d] += dk
+                gq[:, o["v_col"]:o["v_col"] + d] += dv
+            else:
+                gkv[:, o["k_col"]:o["k_col"] + d] += dk
+                gkv[:, o["v_col"]:o["v_col"] + d] += dv
+                acc(o["kv"], gkv.reshape(xkv.shape))
+            acc(o["x"], gq.reshape(xq.shape))
         elif k == "linear":
             xin = T[o["x"]]
             dx, dw, db = L.linear_backward(xin.reshape(xin.shape[0], -1), params[o["w"]], dy, o["b"] is not None)
-            grads[o["w"]] = dw
+            accp(o["w"], dw)
             if o["b"]:
                 grads[o["b"]] = db
             acc(o["x"], dx.reshape(xin.shape))
