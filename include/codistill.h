@@ -66,6 +66,12 @@ enum {
   CD_ARCH_TINY_CNN = 0,          /* conv3x3(3->16)+b, ReLU, conv3x3(16->32)+b, ReLU, GAP, linear */
   CD_ARCH_RESNET_BASIC = 1,      /* CIFAR-style: 3x3 stem, basic blocks, projection shortcuts    */
   CD_ARCH_RESNET_BOTTLENECK = 2, /* 7x7-s2 stem, 3x3-s2 max-pool, bottleneck blocks (x4)         */
+  CD_ARCH_TRANSFORMER = 4,       /* the encoder-decoder Transformer of Section 4 (Vaswani et al.): embedding of the shared
+                                    vocabulary times sqrt(d_model) plus the sinusoidal position signal; encoder layers
+                                    (self-attention, feed-forward), decoder layers (causal self-attention, attention over
+                                    the encoder output, feed-forward), every sublayer followed by its residual connection
+                                    and LayerNorm; logits against the tied embedding table.  No dropout; every sentence
+                                    has in_h source and in_w target tokens (no padding).  CD_BF16 only */
   CD_ARCH_TRANSFORMER_HEAD = 3   /* the last position-wise sublayers of a Transformer decoder (Section 4 trains the
                                     Transformer of Vaswani et al.): h + W2 relu(W1 h + b1) + b2, LayerNorm, projection
                                     onto the vocabulary without bias.  The input is the hidden state of every
@@ -77,7 +83,10 @@ enum {
 #define CD_NAME_LEN 48
 
 /* host struct.  Input images have 3 channels; CD_ARCH_TRANSFORMER_HEAD takes widths[0] = d_model input
- * channels (in_h = in_w = 1), widths[1] = d_ff, classes = vocabulary size. */
+ * channels (in_h = in_w = 1), widths[1] = d_ff, classes = vocabulary size.  CD_ARCH_TRANSFORMER: in_h = source
+ * tokens and in_w = target tokens per sentence, widths[0] = d_model, widths[1] = d_ff, widths[2] = heads,
+ * blocks[0] = encoder layers, blocks[1] = decoder layers, classes = vocabulary size; its input x is
+ * int32 [batch][in_h + in_w] token ids (batch = sentences) and it produces batch * in_w rows of logits. */
 typedef struct {
   int32_t kind;                   /* CD_ARCH_*                                             */
   int32_t classes;                /* width of the logits                                   */
@@ -90,7 +99,8 @@ typedef struct {
 } cd_arch_desc;
 
 /* kind of a parameter tensor */
-enum { CD_P_CONV_W = 0, CD_P_BIAS = 1, CD_P_BN_GAMMA = 2, CD_P_BN_BETA = 3, CD_P_LINEAR_W = 4 };
+enum { CD_P_CONV_W = 0, CD_P_BIAS = 1, CD_P_BN_GAMMA = 2, CD_P_BN_BETA = 3, CD_P_LINEAR_W = 4,
+       CD_P_EMBED_W = 5 /* [vocabulary][d_model] table, also the weight of the tied output projection */ };
 
 /* host struct describing one parameter tensor inside the flat buffers */
 typedef struct {
@@ -108,7 +118,9 @@ typedef struct cd_model cd_model; /* opaque host object */
 /* Fill *out with a preset: CD_ARCH_TINY_CNN (32x32, 10 classes), CD_ARCH_RESNET_BASIC
  * (ResNet-20: 32x32, widths 16/32/64, 3 blocks each, 10 classes), CD_ARCH_RESNET_BOTTLENECK
  * (ResNet-50: 224x224, widths 64..512, blocks 3/4/6/3, 1000 classes; Section 3),
- * CD_ARCH_TRANSFORMER_HEAD (d_model 512, d_ff 2048, vocabulary 32768: the base Transformer). host. */
+ * CD_ARCH_TRANSFORMER_HEAD (d_model 512, d_ff 2048, vocabulary 32768: the base Transformer),
+ * CD_ARCH_TRANSFORMER (the base model: 6 + 6 layers, d_model 512, 8 heads, d_ff 2048, vocabulary 32768,
+ * 128 source and 128 target tokens per sentence). host. */
 int codistill_arch_preset(int kind, cd_arch_desc* out);
 
 /* Build the host-side description (op list, parameter table) of a model.
@@ -212,14 +224,18 @@ int codistill_sgd_step(float* master_w, float* momentum_v, const float* grad, vo
 /* The fused op list and where each tensor lives inside a save_for_backward workspace, so that
  * tools and tests can read intermediate activations and activation gradients after a forward /
  * backward pair.  Tensor 0 is the input batch; the last op writes the logits (not in the workspace). */
-enum { CD_OP_CONV = 0, CD_OP_BN = 1, CD_OP_MAXPOOL = 2, CD_OP_GAP = 3, CD_OP_LINEAR = 4, CD_OP_LN = 5 };
+enum { CD_OP_CONV = 0, CD_OP_BN = 1, CD_OP_MAXPOOL = 2, CD_OP_GAP = 3, CD_OP_LINEAR = 4, CD_OP_LN = 5,
+       CD_OP_EMBED = 6, CD_OP_ATTN = 7 };
 typedef struct {
   int32_t kind;            /* CD_OP_*                                                           */
   int32_t x, y;            /* input / output tensor ids                                         */
-  int32_t res;             /* CD_OP_BN: tensor added before the ReLU; CD_OP_LN: tensor added to x; else -1 */
+  int32_t res;             /* CD_OP_BN: tensor added before the ReLU; CD_OP_LN: tensor added to x; CD_OP_ATTN: the
+                              tensor that holds keys and values (may be x); else -1                      */
   int32_t relu;            /* CD_OP_CONV (after the bias) and CD_OP_BN: ReLU fused into the op  */
   int32_t param_w, param_b;/* parameter indices: weight + bias, or BN scale + shift; -1 if none */
-  int32_t k, stride, pad;  /* window of CD_OP_CONV / CD_OP_MAXPOOL                              */
+  int32_t k, stride, pad;  /* window of CD_OP_CONV / CD_OP_MAXPOOL; CD_OP_ATTN: k = heads, stride = 1 if causal;
+                              CD_OP_EMBED: k = first token column of the input, stride = tokens per sentence;
+                              CD_OP_ATTN also: pad = first column of the queries in x                   */
   int64_t stats_offset;    /* CD_OP_BN: byte offset of fp32 [4][C] = mean, invstd, scale, shift;
                               CD_OP_LN: of fp32 [batch][2] = mean, rstd per row                 */
   int32_t res_grad;        /* CD_OP_BN with a residual input: how the backward pass hands on the gradient of
@@ -229,6 +245,8 @@ typedef struct {
                               mask, and the residual tensor's gradient buffer stays unused.  2: not written by
                               this op; the data gradient of the one convolution that reads the same tensor adds
                               it, so the buffer holds the complete gradient after that launch.            */
+  int32_t k_col, v_col;    /* CD_OP_ATTN: first column of the keys and of the values in tensor res (each range is
+                              as wide as the op's output)                                                */
   int32_t fused_pool;      /* CD_OP_BN: 1 if the max-pool op that follows is computed by this op's kernel; this op's
                               output tensor is then never written (its workspace slot stays unused), its ReLU bit
                               mask and the pool's argmax are.                                             */
@@ -253,7 +271,8 @@ enum {
   CD_K_CONV_FPROP_NARROW = 8, /* every other fprop launch (other tile shapes, plain kernels) */
   CD_K_BN_APPLY = 9,          /* BatchNorm forward: the elementwise normalise (+ residual, ReLU) kernel alone */
   CD_K_CONV_FPROP_WIDE = 10,  /* bf16 MFMA fprop launches on 128x256 tiles (one kernel symbol) */
-  CD_K_COUNT = 11
+  CD_K_ATTN = 11,             /* attention forward and backward launches */
+  CD_K_COUNT = 12
 };
 /* When enabled, every launch is bracketed by HIP events on the launch stream and the events are
  * kept in a host-side pool (created at enable time; no device memory).  host. */

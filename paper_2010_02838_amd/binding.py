@@ -19,10 +19,11 @@ CD_DIST_MSE_LOGITS, CD_DIST_KL, CD_DIST_MSE_CENTERED = 0, 1, 2
 CD_MEAN_ALL, CD_MEAN_ROWS = 0, 1
 CD_BN_BATCH_STATS, CD_BN_RUNNING = 0, 1
 CD_ARCH_TINY_CNN, CD_ARCH_RESNET_BASIC, CD_ARCH_RESNET_BOTTLENECK, CD_ARCH_TRANSFORMER_HEAD = 0, 1, 2, 3
+CD_ARCH_TRANSFORMER = 4
 CD_MAX_STAGES, CD_NAME_LEN, CD_LOSS_MAX_PEERS = 4, 48, 8
 KERNEL_CLASSES = ["conv_fprop", "conv_dgrad", "conv_wgrad", "norm", "glue", "linear", "loss", "sgd", "conv_fprop_narrow",
-                  "bn_apply", "conv_fprop_wide"]
-PARAM_KINDS = ["conv_w", "bias", "bn_gamma", "bn_beta", "linear_w"]
+                  "bn_apply", "conv_fprop_wide", "attention"]
+PARAM_KINDS = ["conv_w", "bias", "bn_gamma", "bn_beta", "linear_w", "embed_w"]
 
 
 class ArchDesc(ctypes.Structure):
@@ -42,7 +43,8 @@ class OpInfo(ctypes.Structure):
     _fields_ = [("kind", ctypes.c_int32), ("x", ctypes.c_int32), ("y", ctypes.c_int32), ("res", ctypes.c_int32),
                 ("relu", ctypes.c_int32), ("param_w", ctypes.c_int32), ("param_b", ctypes.c_int32),
                 ("k", ctypes.c_int32), ("stride", ctypes.c_int32), ("pad", ctypes.c_int32),
-                ("stats_offset", ctypes.c_int64), ("res_grad", ctypes.c_int32), ("fused_pool", ctypes.c_int32)]
+                ("stats_offset", ctypes.c_int64), ("res_grad", ctypes.c_int32), ("k_col", ctypes.c_int32), ("v_col", ctypes.c_int32),
+                ("fused_pool", ctypes.c_int32)]
 
 
 class ActInfo(ctypes.Structure):
@@ -141,6 +143,8 @@ class Model:
             self.params.append(dict(name=ti.name.decode(), kind=PARAM_KINDS[ti.kind], shape=tuple(ti.shape[:ti.ndim]),
                                     offset=ti.offset, size=ti.size, fan_in=ti.fan_in))
         self.classes = arch.classes
+        # rows of logits per element of the batch: target tokens per sentence for the Transformer, else 1
+        self.rows_per_sample = arch.in_w if arch.kind == CD_ARCH_TRANSFORMER else 1
         self.torch_dtype = torch.bfloat16 if dtype == CD_BF16 else torch.float32
 
     def __del__(self):
@@ -157,7 +161,7 @@ class Model:
         no, nt = _i64(), _i64()
         _check(lib.codistill_graph_size(self._h, ctypes.byref(no), ctypes.byref(nt)))
         ops, tensors = [], []
-        kinds = ["conv", "bn", "maxpool", "gap", "linear", "layernorm"]
+        kinds = ["conv", "bn", "maxpool", "gap", "linear", "layernorm", "embed", "attn"]
         for i in range(no.value):
             o = OpInfo()
             _check(lib.codistill_op_info(self._h, batch, i, ctypes.byref(o)))

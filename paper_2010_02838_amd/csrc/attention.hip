@@ -1,0 +1,333 @@
+// Multi-head scaled dot-product attention (forward, backward) and the token embedding of the
+// encoder-decoder Transformer that the paper trains (Section 4; Vaswani et al.).
+//
+// out[i] = sum_j softmax_j(q_i . k_j / sqrt(dh)) v_j per sentence and head, keys j <= i only under the
+// causal mask.  q, k, v are column ranges of bf16 row-major tensors (the fused projections write
+// [rows][3d] or [rows][2d]); head h owns columns h*dh .. (h+1)*dh of each range.
+//
+// Plain fp32 arithmetic, no matrix cores: a pair of threads owns one query (forward, dq) or one key
+// (dk, dv), each thread one half of the head dimension; the dot products are completed with one
+// exchange inside the pair.  The other operand streams through LDS in chunks of 64 rows, every thread
+// reading the same address (a broadcast).  The forward pass keeps only the log-sum-exp of every row
+// (softmax is recomputed in the backward pass), so nothing of size Tq x Tk is ever stored.
+#include "common.h"
+#include "kernels.h"
+#include <math.h>
+
+namespace cd {
+
+namespace {
+
+constexpr int ATT_ROWS = 128;  // rows (queries or keys) per workgroup: two threads each
+constexpr int ATT_KC = 64;     // rows of the streamed operand per LDS chunk
+
+__device__ inline float pair_sum(float v) { return v + __shfl_xor(v, 1, 64); }
+
+// bf16 row (row pitch ld elements) -> n floats at dst, 8 at a time
+__device__ inline void load_bf16_8(const bf16_t* p, float* dst) {
+  const uint4 u = *reinterpret_cast<const uint4*>(p);
+  const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+  for (int q = 0; q < 4; q++) {
+    dst[2 * q] = __uint_as_float(w[q] << 16);
+    dst[2 * q + 1] = __uint_as_float(w[q] & 0xffff0000u);
+  }
+}
+
+// A chunk of up to ATT_KC rows x DH columns of a bf16 tensor into LDS as fp32 (rows past n are zero).
+template <int DH>
+__device__ inline void stage_chunk(const bf16_t* __restrict__ base, int64_t ld, int n, float* __restrict__ dst) {
+  constexpr int VPR = DH / 8;  // 16-byte vectors per row
+  for (int v = threadIdx.x; v < ATT_KC * VPR; v += 256) {
+    const int r = v / VPR, c = (v % VPR) * 8;
+    float t[8];
+    if (r < n) load_bf16_8(base + (int64_t)r * ld + c, t);
+    else {
+#pragma unroll
+      for (int e = 0; e < 8; e++) t[e] = 0.f;
+    }
+#pragma unroll
+    for (int e = 0; e < 8; e++) dst[r * DH + c + e] = t[e];
+  }
+}
+
+struct AttArgs {
+  const bf16_t* q; const bf16_t* k; const bf16_t* v;   // already offset to their first column
+  int64_t ldq, ldkv;                                  // row pitches in elements
+  bf16_t* out; int64_t ldo;                           // forward output [S*Tq][d]
+  float* lse;                                         // [S][heads][Tq] log-sum-exp of the scaled scores
+  float* dsum;                                        // [S][heads][Tq] backward: dO . O per row
+  const bf16_t* dout;                                 // backward: gradient of out, pitch ldo
+  bf16_t* dq; bf16_t* dk; bf16_t* dv;                 // backward outputs, pitches ldq / ldkv
+  int S, heads, Tq, Tk, causal;
+  float scale;                                        // 1 / sqrt(dh)
+};
+
+// blockIdx.x = (sentence * heads + head) * tiles + tile of ATT_ROWS queries
+template <int DH>
+__global__ void __launch_bounds__(256) attn_fwd_k(AttArgs a) {
+  constexpr int HALF = DH / 2;
+  __shared__ float Ks[ATT_KC * DH], Vs[ATT_KC * DH];
+  const int tiles = (a.Tq + ATT_ROWS - 1) / ATT_ROWS;
+  const int tile = blockIdx.x % tiles, sh = blockIdx.x / tiles;
+  const int h = sh % a.heads, s = sh / a.heads;
+  const int i = tile * ATT_ROWS + (threadIdx.x >> 1), hf = threadIdx.x & 1;
+  const bool live = i < a.Tq;
+  float q[HALF], o[HALF];
+#pragma unroll
+  for (int c = 0; c < HALF; c++) { q[c] = 0.f; o[c] = 0.f; }
+  if (live) {
+    const bf16_t* qp = a.q + ((int64_t)s * a.Tq + i) * a.ldq + h * DH + hf * HALF;
+#pragma unroll
+    for (int c = 0; c < HALF; c++) q[c] = bf16_to_f32(qp[c]) * a.scale;
+  }
+  float m = -INFINITY, l = 0.f;
+  const int last = a.causal ? min(a.Tk, tile * ATT_ROWS + ATT_ROWS) : a.Tk;   // keys any query of the tile sees
+  for (int j0 = 0; j0 < last; j0 += ATT_KC) {
+    const int n = min(ATT_KC, a.Tk - j0);
+    __syncthreads();
+    stage_chunk<DH>(a.k + ((int64_t)s * a.Tk + j0) * a.ldkv + h * DH, a.ldkv, n, Ks);
+    stage_chunk<DH>(a.v + ((int64_t)s * a.Tk + j0) * a.ldkv + h * DH, a.ldkv, n, Vs);
+    __syncthreads();
+    for (int j = 0; j < n; j++) {
+      float part = 0.f;
+#pragma unroll
+      for (int c = 0; c < HALF; c++) part += q[c] * Ks[j * DH + hf * HALF + c];
+      const float sc = pair_sum(part);
+      if (!live || (a.causal && j0 + j > i)) continue;
+      if (sc > m) {   // a new maximum: rescale what has been accumulated (rare after the first keys)
+        const float r = __expf(m - sc);
+        l *= r;
+#pragma unroll
+        for (int c = 0; c < HALF; c++) o[c] *= r;
+        m = sc;
+      }
+      const float p = __expf(sc - m);
+      l += p;
+#pragma unroll
+      for (int c = 0; c < HALF; c++) o[c] += p * Vs[j * DH + hf * HALF + c];
+    }
+  }
+  if (!live) return;
+  const float inv = 1.f / l;
+  bf16_t* op = a.out + ((int64_t)s * a.Tq + i) * a.ldo + h * DH + hf * HALF;
+#pragma unroll
+  for (int c = 0; c < HALF; c++) op[c] = f32_to_bf16(o[c] * inv);
+  if (hf == 0 && a.lse) a.lse[((int64_t)s * a.heads + h) * a.Tq + i] = m + __logf(l);
+}
+
+// dq: one pair of threads per query.  p_ij = exp(s_ij - lse_i); D_i = dO_i . O_i = sum_j p_ij dP_ij;
+// dS_ij = p_ij (dP_ij - D_i); dq_i = scale * sum_j dS_ij k_j.  D_i is accumulated on the way (first
+// pass over the keys) so that the stored output is not needed, then dq in a second pass.
+template <int DH>
+__global__ void __launch_bounds__(256) attn_bwd_dq_k(AttArgs a) {
+  constexpr int HALF = DH / 2;
+  __shared__ float Ks[ATT_KC * DH], Vs[ATT_KC * DH];
+  const int tiles = (a.Tq + ATT_ROWS - 1) / ATT_ROWS;
+  const int tile = blockIdx.x % tiles, sh = blockIdx.x / tiles;
+  const int h = sh % a.heads, s = sh / a.heads;
+  const int i = tile * ATT_ROWS + (threadIdx.x >> 1), hf = threadIdx.x & 1;
+  const bool live = i < a.Tq;
+  float q[HALF], go[HALF], dq[HALF];
+#pragma unroll
+  for (int c = 0; c < HALF; c++) { q[c] = 0.f; go[c] = 0.f; dq[c] = 0.f; }
+  float lse = 0.f;
+  if (live) {
+    const bf16_t* qp = a.q + ((int64_t)s * a.Tq + i) * a.ldq + h * DH + hf * HALF;
+    const bf16_t* gp = a.dout + ((int64_t)s * a.Tq + i) * a.ldo + h * DH + hf * HALF;
+#pragma unroll
+    for (int c = 0; c < HALF; c++) { q[c] = bf16_to_f32(qp[c]) * a.scale; go[c] = bf16_to_f32(gp[c]); }
+    lse = a.lse[((int64_t)s * a.heads + h) * a.Tq + i];
+  }
+  const int last = a.causal ? min(a.Tk, tile * ATT_ROWS + ATT_ROWS) : a.Tk;
+  float D = 0.f;
+  for (int pass = 0; pass < 2; pass++) {
+    for (int j0 = 0; j0 < last; j0 += ATT_KC) {
+      const int n = min(ATT_KC, a.Tk - j0);
+      __syncthreads();
+      stage_chunk<DH>(a.k + ((int64_t)s * a.Tk + j0) * a.ldkv + h * DH, a.ldkv, n, Ks);
+      stage_chunk<DH>(a.v + ((int64_t)s * a.Tk + j0) * a.ldkv + h * DH, a.ldkv, n, Vs);
+      __syncthreads();
+      for (int j = 0; j < n; j++) {
+        float ps = 0.f, pd = 0.f;
+#pragma unroll
+        for (int c = 0; c < HALF; c++) {
+          ps += q[c] * Ks[j * DH + hf * HALF + c];
+          pd += go[c] * Vs[j * DH + hf * HALF + c];
+        }
+        const float sc = pair_sum(ps), dp = pair_sum(pd);
+        if (!live || (a.causal && j0 + j > i)) continue;
+        const float p = __expf(sc - lse);
+        if (pass == 0) {
+          D += p * dp;
+        } else {
+          const float ds = p * (dp - D);
+#pragma unroll
+          for (int c = 0; c < HALF; c++) dq[c] += ds * Ks[j * DH + hf * HALF + c];
+        }
+      }
+    }
+  }
+  if (!live) return;
+  bf16_t* dp_ = a.dq + ((int64_t)s * a.Tq + i) * a.ldq + h * DH + hf * HALF;
+#pragma unroll
+  for (int c = 0; c < HALF; c++) dp_[c] = f32_to_bf16(dq[c] * a.scale);
+  if (hf == 0) a.dsum[((int64_t)s * a.heads + h) * a.Tq + i] = D;
+}
+
+// dk, dv: one pair of threads per key; the queries (scaled), their output gradients, log-sum-exps and
+// D_i stream through LDS.  dv_j = sum_i p_ij dO_i; dk_j = scale * sum_i dS_ij q_i.
+template <int DH>
+__global__ void __launch_bounds__(256) attn_bwd_dkv_k(AttArgs a) {
+  constexpr int HALF = DH / 2;
+  __shared__ float Qs[ATT_KC * DH], Gs[ATT_KC * DH], Ls[ATT_KC], Ds[ATT_KC];
+  const int tiles = (a.Tk + ATT_ROWS - 1) / ATT_ROWS;
+  const int tile = blockIdx.x % tiles, sh = blockIdx.x / tiles;
+  const int h = sh % a.heads, s = sh / a.heads;
+  const int j = tile * ATT_ROWS + (threadIdx.x >> 1), hf = threadIdx.x & 1;
+  const bool live = j < a.Tk;
+  float k[HALF], v[HALF], dk[HALF], dv[HALF];
+#pragma unroll
+  for (int c = 0; c < HALF; c++) { k[c] = 0.f; v[c] = 0.f; dk[c] = 0.f; dv[c] = 0.f; }
+  if (live) {
+    const bf16_t* kp = a.k + ((int64_t)s * a.Tk + j) * a.ldkv + h * DH + hf * HALF;
+    const bf16_t* vp = a.v + ((int64_t)s * a.Tk + j) * a.ldkv + h * DH + hf * HALF;
+#pragma unroll
+    for (int c = 0; c < HALF; c++) { k[c] = bf16_to_f32(kp[c]); v[c] = bf16_to_f32(vp[c]); }
+  }
+  const int first = a.causal ? tile * ATT_ROWS / ATT_KC * ATT_KC : 0;   // queries before the tile's first key see none of it
+  for (int i0 = first; i0 < a.Tq; i0 += ATT_KC) {
+    const int n = min(ATT_KC, a.Tq - i0);
+    __syncthreads();
+    stage_chunk<DH>(a.q + ((int64_t)s * a.Tq + i0) * a.ldq + h * DH, a.ldq, n, Qs);
+    stage_chunk<DH>(a.dout + ((int64_t)s * a.Tq + i0) * a.ldo + h * DH, a.ldo, n, Gs);
+    if ((int)threadIdx.x < ATT_KC) {
+      const bool in = (int)threadIdx.x < n;
+      Ls[threadIdx.x] = in ? a.lse[((int64_t)s * a.heads + h) * a.Tq + i0 + threadIdx.x] : 0.f;
+      Ds[threadIdx.x] = in ? a.dsum[((int64_t)s * a.heads + h) * a.Tq + i0 + threadIdx.x] : 0.f;
+    }
+    __syncthreads();
+    for (int i = 0; i < n; i++) {
+      float ps = 0.f, pd = 0.f;
+#pragma unroll
+      for (int c = 0; c < HALF; c++) {
+        ps += k[c] * Qs[i * DH + hf * HALF + c];
+        pd += v[c] * Gs[i * DH + hf * HALF + c];
+      }
+      const float sc = pair_sum(ps) * a.scale, dp = pair_sum(pd);
+      if (!live || (a.causal && j > i0 + i)) continue;
+      const float p = __expf(sc - Ls[i]);
+      const float ds = p * (dp - Ds[i]);
+#pragma unroll
+      for (int c = 0; c < HALF; c++) {
+        dv[c] += p * Gs[i * DH + hf * HALF + c];
+        dk[c] += ds * Qs[i * DH + hf * HALF + c];
+      }
+    }
+  }
+  if (!live) return;
+  bf16_t* dkp = a.dk + ((int64_t)s * a.Tk + j) * a.ldkv + h * DH + hf * HALF;
+  bf16_t* dvp = a.dv + ((int64_t)s * a.Tk + j) * a.ldkv + h * DH + hf * HALF;
+#pragma unroll
+  for (int c = 0; c < HALF; c++) { dkp[c] = f32_to_bf16(dk[c] * a.scale); dvp[c] = f32_to_bf16(dv[c]); }
+}
+
+// ---- embedding ------------------------------------------------------------------------------------
+// y[s*T + t][:] = table[tok[s][col0 + t]][:] * sqrt(d) + PE[t][:], PE[t][2i] = sin(t / 10000^(2i/d)),
+// PE[t][2i+1] = cos(same).  One thread per pair of columns.
+template <typename T>
+__global__ void __launch_bounds__(256) embed_fwd_k(const int32_t* __restrict__ tok, int64_t tok_pitch, int col0, int T_,
+                                                   const T* __restrict__ table, int vocab, int d, T* __restrict__ y,
+                                                   int64_t rows) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int half = d / 2;
+  if (idx >= rows * half) return;
+  const int i = (int)(idx % half);
+  const int64_t row = idx / half;
+  const int t = (int)(row % T_);
+  const int64_t s = row / T_;
+  int id = tok[s * tok_pitch + col0 + t];
+  id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);   // ids are validated by the caller; clamp keeps the access in bounds
+  const float ang = (float)t * __expf(-(float)(2 * i) / (float)d * 9.210340371976184f);   // ln 10000
+  const float scale = sqrtf((float)d);
+  const T* tr = table + (int64_t)id * d + 2 * i;
+  y[row * d + 2 * i] = Cvt<T>::st(Cvt<T>::ld(tr[0]) * scale + sinf(ang));
+  y[row * d + 2 * i + 1] = Cvt<T>::st(Cvt<T>::ld(tr[1]) * scale + cosf(ang));
+}
+
+// dtable[tok] += sqrt(d) * dy[row] for every occurrence (fp32 atomics: the order of the additions,
+// and with it the last bits of the result, varies from run to run)
+template <typename T>
+__global__ void __launch_bounds__(256) embed_bwd_k(const int32_t* __restrict__ tok, int64_t tok_pitch, int col0, int T_,
+                                                   const T* __restrict__ dy, int vocab, int d, float* __restrict__ dtable,
+                                                   int64_t rows) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= rows * d) return;
+  const int c = (int)(idx % d);
+  const int64_t row = idx / d;
+  const int t = (int)(row % T_);
+  const int64_t s = row / T_;
+  int id = tok[s * tok_pitch + col0 + t];
+  id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);
+  atomicAdd(dtable + (int64_t)id * d + c, Cvt<T>::ld(dy[idx]) * sqrtf((float)d));
+}
+
+}  // namespace
+
+bool attention_supported(int dh) { return dh == 8 || dh == 16 || dh == 32 || dh == 64; }
+
+#define CD_ATT_DISPATCH(KERNEL, grid)                                                                      \
+  switch (dh) {                                                                                           \
+    case 8: hipLaunchKernelGGL((KERNEL<8>), dim3(grid), dim3(256), 0, s, a); break;                       \
+    case 16: hipLaunchKernelGGL((KERNEL<16>), dim3(grid), dim3(256), 0, s, a); break;                     \
+    case 32: hipLaunchKernelGGL((KERNEL<32>), dim3(grid), dim3(256), 0, s, a); break;                     \
+    default: hipLaunchKernelGGL((KERNEL<64>), dim3(grid), dim3(256), 0, s, a); break;                     \
+  }
+
+void attention_forward(const bf16_t* q, int64_t ldq, const bf16_t* k, const bf16_t* v, int64_t ldkv, bf16_t* out, int64_t ldo,
+                       float* lse, int S, int heads, int Tq, int Tk, int dh, bool causal, hipStream_t s) {
+  AttArgs a = {};
+  a.q = q; a.k = k; a.v = v; a.ldq = ldq; a.ldkv = ldkv; a.out = out; a.ldo = ldo; a.lse = lse;
+  a.S = S; a.heads = heads; a.Tq = Tq; a.Tk = Tk; a.causal = causal ? 1 : 0;
+  a.scale = 1.f / sqrtf((float)dh);
+  const unsigned grid = (unsigned)((int64_t)S * heads * cdiv(Tq, ATT_ROWS));
+  CD_ATT_DISPATCH(attn_fwd_k, grid);
+}
+
+void attention_backward(const bf16_t* q, int64_t ldq, const bf16_t* k, const bf16_t* v, int64_t ldkv, const bf16_t* dout,
+                        int64_t ldo, const float* lse, float* dsum, bf16_t* dq, bf16_t* dk, bf16_t* dv, int S, int heads,
+                        int Tq, int Tk, int dh, bool causal, hipStream_t s) {
+  AttArgs a = {};
+  a.q = q; a.k = k; a.v = v; a.ldq = ldq; a.ldkv = ldkv; a.dout = dout; a.ldo = ldo;
+  a.lse = const_cast<float*>(lse); a.dsum = dsum; a.dq = dq; a.dk = dk; a.dv = dv;
+  a.S = S; a.heads = heads; a.Tq = Tq; a.Tk = Tk; a.causal = causal ? 1 : 0;
+  a.scale = 1.f / sqrtf((float)dh);
+  const unsigned gq = (unsigned)((int64_t)S * heads * cdiv(Tq, ATT_ROWS));
+  const unsigned gk = (unsigned)((int64_t)S * heads * cdiv(Tk, ATT_ROWS));
+  CD_ATT_DISPATCH(attn_bwd_dq_k, gq);
+  CD_ATT_DISPATCH(attn_bwd_dkv_k, gk);
+}
+
+void embed_forward(int dtype, const int32_t* tok, int64_t tok_pitch, int col0, int len, const void* table, int vocab, int d,
+                   void* y, int64_t rows, hipStream_t s) {
+  const unsigned grid = (unsigned)cdiv(rows * (d / 2), 256);
+  if (dtype == CD_BF16)
+    hipLaunchKernelGGL(embed_fwd_k<bf16_t>, dim3(grid), dim3(256), 0, s, tok, tok_pitch, col0, len, (const bf16_t*)table,
+                       vocab, d, (bf16_t*)y, rows);
+  else
+    hipLaunchKernelGGL(embed_fwd_k<float>, dim3(grid), dim3(256), 0, s, tok, tok_pitch, col0, len, (const float*)table,
+                       vocab, d, (float*)y, rows);
+}
+
+void embed_backward(int dtype, const int32_t* tok, int64_t tok_pitch, int col0, int len, const void* dy, int vocab, int d,
+                    float* dtable, int64_t rows, hipStream_t s) {
+  const unsigned grid = (unsigned)cdiv(rows * d, 256);
+  if (dtype == CD_BF16)
+    hipLaunchKernelGGL(embed_bwd_k<bf16_t>, dim3(grid), dim3(256), 0, s, tok, tok_pitch, col0, len, (const bf16_t*)dy, vocab,
+                       d, dtable, rows);
+  else
+    hipLaunchKernelGGL(embed_bwd_k<float>, dim3(grid), dim3(256), 0, s, tok, tok_pitch, col0, len, (const float*)dy, vocab, d,
+                       dtable, rows);
+}
+
+}  // namespace cd

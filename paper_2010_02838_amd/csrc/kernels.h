@@ -125,4 +125,24 @@ void s2d_unpack_dw(const float* dws, float* dw, int cout, int k, int ks, int shi
 void unpad_c8_to_c3(const float* in, float* out, int64_t n, hipStream_t s);
 // w[Cout][taps][Cin] -> wt[Cin][taps][Cout]
 void transpose_weight(const bf16_t* w, bf16_t* wt, int cout, int taps, int cin, hipStream_t s);
+
+// ---- attention.hip: multi-head scaled dot-product attention and the token embedding (bf16 tensors) ----
+// q [S*Tq][.] and k, v [S*Tk][.] are bf16 row-major with row pitches ldq / ldkv (elements), already
+// pointing at their first column; head h owns columns h*dh .. (h+1)*dh.  out [S*Tq][.] with pitch ldo.
+// lse (nullable in a forward pass that keeps nothing): [S][heads][Tq] fp32 log-sum-exp of the scaled
+// scores.  dh in {8, 16, 32, 64} (attention_supported).
+bool attention_supported(int dh);
+void attention_forward(const bf16_t* q, int64_t ldq, const bf16_t* k, const bf16_t* v, int64_t ldkv, bf16_t* out, int64_t ldo,
+                       float* lse, int S, int heads, int Tq, int Tk, int dh, bool causal, hipStream_t s);
+// dq, dk, dv are written (not accumulated), with the pitches of q and k / v; dsum: [S][heads][Tq] fp32 scratch.
+void attention_backward(const bf16_t* q, int64_t ldq, const bf16_t* k, const bf16_t* v, int64_t ldkv, const bf16_t* dout,
+                        int64_t ldo, const float* lse, float* dsum, bf16_t* dq, bf16_t* dk, bf16_t* dv, int S, int heads,
+                        int Tq, int Tk, int dh, bool causal, hipStream_t s);
+// y[s*len + t][:] = table[tok[s*tok_pitch + col0 + t]][:] * sqrt(d) + the sinusoidal position signal of t (d even)
+void embed_forward(int dtype, const int32_t* tok, int64_t tok_pitch, int col0, int len, const void* table, int vocab, int d,
+                   void* y, int64_t rows, hipStream_t s);
+// dtable[tok] += sqrt(d) * dy[row] (fp32 atomics onto a gradient that already holds the other uses of the table)
+void embed_backward(int dtype, const int32_t* tok, int64_t tok_pitch, int col0, int len, const void* dy, int vocab, int d,
+                    float* dtable, int64_t rows, hipStream_t s);
+
 }  // namespace cd

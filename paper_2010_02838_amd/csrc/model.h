@@ -6,7 +6,7 @@
 
 namespace cd {
 
-enum OpKind { OP_CONV, OP_BN, OP_MAXPOOL, OP_GAP, OP_LINEAR, OP_LN };
+enum OpKind { OP_CONV, OP_BN, OP_MAXPOOL, OP_GAP, OP_LINEAR, OP_LN, OP_EMBED, OP_ATTN };
 
 struct TensorDesc {
   int h = 1, w = 1, c = 1;  // per-sample shape; a [B, F] tensor has h = w = 1
@@ -17,11 +17,18 @@ struct TensorDesc {
 struct Op {
   OpKind kind;
   int x = -1, y = -1;  // input / output tensor ids
-  int res = -1;        // OP_BN: tensor added before the ReLU; OP_LN: tensor added to x (-1: none)
+  int res = -1;        // OP_BN: tensor added before the ReLU; OP_LN: tensor added to x (-1: none);
+                       // OP_ATTN: the tensor that holds keys and values (may be x itself)
   bool relu = false;   // OP_CONV (after the bias) and OP_BN
   int pw = -1, pb = -1;  // parameter indices: conv/linear weight + bias, BN gamma + beta
   int k = 1, stride = 1, pad = 0;
   int bn_slot = -1;    // OP_BN: index into the per-BN statistics area
+  // OP_EMBED: a0 = first token column of the input, a1 = tokens per sentence.
+  // OP_ATTN: a0, a1, a2 = first column of the queries in x, of the keys and of the values in res;
+  //          heads, causal; the width of each column range is the width of y.
+  int a0 = 0, a1 = 0, a2 = 0, heads = 0;
+  bool causal = false;
+  bool tied = false;   // OP_LINEAR: the weight is another op's parameter (the embedding table)
 };
 
 struct ParamDesc {
@@ -39,7 +46,8 @@ struct Plan {
   std::vector<size_t> act;    // byte offset of every tensor's activation (tensor 0 unused)
   std::vector<size_t> grad;   // byte offset of every tensor's gradient (save only)
   std::vector<size_t> aux;    // per op (save only): max-pool argmax bytes, ReLU sign bits of a BatchNorm,
-                              // per-row mean and rstd of a LayerNorm; 0 = none
+                              // per-row mean and rstd of a LayerNorm, per (sentence, head, query) log-sum-exp
+                              // and dO.O of an attention; 0 = none
   size_t bn_stats = 0;        // per BN slot: mean[C], invstd[C], scale[C], shift[C] fp32
   size_t bn_coef = 0;         // backward coefficients c1,c2,c3 [3][Cmax] fp32
   size_t partials = 0;        // reduction partials / split-K partials

@@ -87,11 +87,36 @@ struct Builder {
   }
   int linear(int x, const std::string& n, int fin, int fout, bool bias = true) {
     int64_t sh[2] = {fout, fin};
+    const TensorDesc tx = m->tensors[x];
     Op o;
     o.kind = OP_LINEAR; o.x = x;
     o.pw = add_param(n + ".w", CD_P_LINEAR_W, 2, sh, fin);
     o.pb = bias ? vec(n + ".b", CD_P_BIAS, fout) : -1;
-    o.y = add_tensor(1, 1, fout, true);
+    o.y = add_tensor(tx.h, tx.w, fout, true);   // one row of logits per row of x
+    m->ops.push_back(o);
+    return o.y;
+  }
+  // logits against an existing [fout][fin] table (the embedding), no bias
+  int tied_linear(int x, int pw, int fout) {
+    const TensorDesc tx = m->tensors[x];
+    Op o;
+    o.kind = OP_LINEAR; o.x = x; o.pw = pw; o.pb = -1; o.tied = true;
+    o.y = add_tensor(tx.h, tx.w, fout, true);
+    m->ops.push_back(o);
+    return o.y;
+  }
+  int embed(int pw, int col0, int len, int d) {
+    Op o;
+    o.kind = OP_EMBED; o.x = 0; o.pw = pw; o.a0 = col0; o.a1 = len;
+    o.y = add_tensor(len, 1, d);
+    m->ops.push_back(o);
+    return o.y;
+  }
+  int attention(int q, int q_col, int kv, int k_col, int v_col, int d, int heads, bool causal) {
+    const TensorDesc tq = m->tensors[q];
+    Op o;
+    o.kind = OP_ATTN; o.x = q; o.res = kv; o.a0 = q_col; o.a1 = k_col; o.a2 = v_col; o.heads = heads; o.causal = causal;
+    o.y = add_tensor(tq.h, tq.w, d);
     m->ops.push_back(o);
     return o.y;
   }
@@ -118,6 +143,57 @@ void build_transformer_head(Builder& b, const cd_arch_desc& a) {
   int g = b.vec("ffn.ln.gamma", CD_P_BN_GAMMA, d), be = b.vec("ffn.ln.beta", CD_P_BN_BETA, d);
   t = b.ln(t, 0, g, be);
   b.linear(t, "proj", d, a.classes, false);
+}
+
+// Encoder-decoder Transformer (paper, Section 4; Vaswani et al.): token embedding times sqrt(d) plus
+// the sinusoidal position signal; encoder layers of self-attention and feed-forward sublayers, decoder
+// layers of causal self-attention, attention over the encoder output and feed-forward, every sublayer
+// followed by its residual connection and LayerNorm; logits against the (tied) embedding table.  The
+// input projections of an attention sublayer are one dense layer (d -> 3d, or d -> d for the queries and
+// d -> 2d for keys and values of the encoder output); dense layers are 1x1 convolutions over
+// [sentences][tokens][1][d] tensors.  No dropout, no padding (all sentences have the same lengths).
+void build_transformer(Builder& b, const cd_arch_desc& a) {
+  const int d = a.widths[0], ff = a.widths[1], heads = a.widths[2];
+  const int Ts = a.in_h, Tt = a.in_w;
+  auto dense = [&](int x, const std::string& n, int fin, int fout, bool relu) {
+    int w = b.conv_w(n, fin, fout, 1), bi = b.vec(n + ".b", CD_P_BIAS, fout);
+    return b.conv(x, w, bi, fout, 1, 1, 0, relu);
+  };
+  auto add_norm = [&](int x, int sub, const std::string& n) {
+    int g = b.vec(n + ".gamma", CD_P_BN_GAMMA, d), be = b.vec(n + ".beta", CD_P_BN_BETA, d);
+    return b.ln(sub, x, g, be);
+  };
+  auto ffn = [&](int x, const std::string& p) {
+    int u = dense(x, p + ".ffn.w1", d, ff, true);
+    u = dense(u, p + ".ffn.w2", ff, d, false);
+    return add_norm(x, u, p + ".ffn.ln");
+  };
+  auto self_attention = [&](int x, const std::string& p, bool causal) {
+    int qkv = dense(x, p + ".qkv", d, 3 * d, false);
+    int o = b.attention(qkv, 0, qkv, d, 2 * d, d, heads, causal);
+    return add_norm(x, dense(o, p + ".out", d, d, false), p + ".ln");
+  };
+  int64_t sh[2] = {a.classes, d};
+  const int table = b.add_param("embed.w", CD_P_EMBED_W, 2, sh, d);
+  char name[32];
+  int x = b.embed(table, 0, Ts, d);
+  for (int i = 0; i < a.blocks[0]; i++) {
+    snprintf(name, sizeof(name), "enc%d", i);
+    x = ffn(self_attention(x, std::string(name) + ".self", false), name);
+  }
+  const int memory = x;
+  int y = b.embed(table, Ts, Tt, d);
+  for (int i = 0; i < a.blocks[1]; i++) {
+    snprintf(name, sizeof(name), "dec%d", i);
+    const std::string p(name);
+    y = self_attention(y, p + ".self", true);
+    int q = dense(y, p + ".cross.q", d, d, false);
+    int kv = dense(memory, p + ".cross.kv", d, 2 * d, false);
+    int o = b.attention(q, 0, kv, 0, d, d, heads, false);
+    y = add_norm(y, dense(o, p + ".cross.out", d, d, false), p + ".cross.ln");
+    y = ffn(y, p);
+  }
+  b.tied_linear(y, table, a.classes);
 }
 
 struct BnP { int g, b; };
@@ -317,11 +393,11 @@ Plan make_plan(const cd_model* m, int64_t B, bool save) {
         size_t e = (size_t)q.shape[0] * q.shape[1] * q.shape[2] * (q.shape[3] == 3 ? 8 : q.shape[3]);
         if (e > wmax) wmax = e;
       }
-      if (q.kind == CD_P_LINEAR_W && (size_t)q.size > wmax) wmax = (size_t)q.size;
+      if ((q.kind == CD_P_LINEAR_W || q.kind == CD_P_EMBED_W) && (size_t)q.size > wmax) wmax = (size_t)q.size;
     }
     p.wpack_bytes = align_up(wmax * 4 + 256, 256);  // also holds the fp32 padded stem weight gradient
     p.wpack = alloc(p.wpack_bytes);
-    p.lin_dz = alloc((size_t)B * m->arch.classes * 2);
+    p.lin_dz = alloc((size_t)B * m->tensors[m->ops.back().y].per_sample() * 2);
   }
   p.aux.assign(m->ops.size(), 0);
   if (save) {
@@ -335,6 +411,7 @@ Plan make_plan(const cd_model* m, int64_t B, bool save) {
       if (o.kind == OP_BN && o.relu && m->dtype == CD_BF16 && m->tensors[o.y].c % 8 == 0)
         p.aux[i] = alloc((size_t)B * m->tensors[o.y].per_sample() / 8);
       if (o.kind == OP_LN) p.aux[i] = alloc((size_t)B * m->tensors[o.y].h * m->tensors[o.y].w * 2 * sizeof(float));
+      if (o.kind == OP_ATTN) p.aux[i] = alloc((size_t)B * o.heads * m->tensors[o.y].h * 2 * sizeof(float));
     }
   }
   p.total = off;
@@ -362,6 +439,10 @@ extern "C" int codistill_arch_preset(int kind, cd_arch_desc* out) {
   } else if (kind == CD_ARCH_TRANSFORMER_HEAD) {
     out->classes = 32768; out->in_h = out->in_w = 1; out->n_stages = 0;
     out->widths[0] = 512; out->widths[1] = 2048;
+  } else if (kind == CD_ARCH_TRANSFORMER) {
+    out->classes = 32768; out->in_h = out->in_w = 128; out->n_stages = 0;
+    out->widths[0] = 512; out->widths[1] = 2048; out->widths[2] = 8;
+    out->blocks[0] = out->blocks[1] = 6;
   } else {
     return set_error(CD_ERR_INVALID_ARG, "arch_preset: unknown kind %d", kind);
   }
@@ -372,7 +453,7 @@ extern "C" int codistill_model_create(const cd_arch_desc* a, int dtype, cd_model
   CD_REQUIRE(a != nullptr && out != nullptr, "model_create: NULL pointer argument");
   CD_REQUIRE(dtype == CD_F32 || dtype == CD_BF16, "model_create: unknown dtype %d", dtype);
   CD_REQUIRE(a->kind == CD_ARCH_TINY_CNN || a->kind == CD_ARCH_RESNET_BASIC || a->kind == CD_ARCH_RESNET_BOTTLENECK ||
-                 a->kind == CD_ARCH_TRANSFORMER_HEAD,
+                 a->kind == CD_ARCH_TRANSFORMER_HEAD || a->kind == CD_ARCH_TRANSFORMER,
              "model_create: unknown architecture kind %d", a->kind);
   CD_REQUIRE(a->classes >= 1 && a->classes <= (1 << 24), "model_create: classes=%d out of range", a->classes);
   CD_REQUIRE(a->in_h >= 1 && a->in_w >= 1 && a->in_h <= 4096 && a->in_w <= 4096,
@@ -380,6 +461,15 @@ extern "C" int codistill_model_create(const cd_arch_desc* a, int dtype, cd_model
   if (a->kind == CD_ARCH_TINY_CNN) {
     CD_REQUIRE(a->widths[0] >= 1 && a->widths[1] >= 1 && a->widths[0] <= 4096 && a->widths[1] <= 4096,
                "model_create: tiny CNN widths out of range");
+  } else if (a->kind == CD_ARCH_TRANSFORMER) {
+    const int d = a->widths[0], heads = a->widths[2];
+    CD_REQUIRE(d >= 8 && d <= 16384 && a->widths[1] >= 8 && a->widths[1] <= 65536 && d % 8 == 0 && a->widths[1] % 8 == 0,
+               "model_create: d_model / d_ff out of range or not a multiple of 8");
+    CD_REQUIRE(heads >= 1 && d % heads == 0 && attention_supported(d / heads),
+               "model_create: d_model / heads must be 8, 16, 32 or 64");
+    CD_REQUIRE(a->blocks[0] >= 1 && a->blocks[0] <= 64 && a->blocks[1] >= 1 && a->blocks[1] <= 64,
+               "model_create: encoder / decoder layer counts out of range");
+    if (dtype != CD_BF16) return set_error(CD_ERR_UNSUPPORTED, "model_create: the Transformer is implemented for CD_BF16 only");
   } else if (a->kind == CD_ARCH_TRANSFORMER_HEAD) {
     CD_REQUIRE(a->widths[0] >= 1 && a->widths[1] >= 1 && a->widths[0] <= 16384 && a->widths[1] <= 65536,
                "model_create: d_model / d_ff out of range");
@@ -397,9 +487,13 @@ extern "C" int codistill_model_create(const cd_arch_desc* a, int dtype, cd_model
   m->tensors.push_back(TensorDesc());
   m->tensors[0].h = a->in_h; m->tensors[0].w = a->in_w;
   m->tensors[0].c = a->kind == CD_ARCH_TRANSFORMER_HEAD ? a->widths[0] : 3;
+  if (a->kind == CD_ARCH_TRANSFORMER) {   // tensor 0: int32 token ids, per sentence in_h source tokens then in_w target tokens
+    m->tensors[0].h = 1; m->tensors[0].w = a->in_h + a->in_w; m->tensors[0].c = 1;
+  }
   Builder b{m};
   if (a->kind == CD_ARCH_TINY_CNN) build_tiny(b, *a);
   else if (a->kind == CD_ARCH_TRANSFORMER_HEAD) build_transformer_head(b, *a);
+  else if (a->kind == CD_ARCH_TRANSFORMER) build_transformer(b, *a);
   else build_resnet(b, *a);
   for (const TensorDesc& t : m->tensors) {
     if (t.h < 1 || t.w < 1) {
@@ -460,6 +554,9 @@ extern "C" int codistill_op_info(const cd_model* m, int64_t batch, int64_t idx, 
     out->stats_offset = (int64_t)(p.bn_stats + (size_t)4 * m->bn_off[o.bn_slot] * sizeof(float));
   }
   if (o.kind == OP_LN) out->stats_offset = (int64_t)make_plan(m, batch, true).aux[idx];
+  out->k_col = out->v_col = 0;
+  if (o.kind == OP_EMBED) { out->k = o.a0; out->stride = o.a1; }
+  if (o.kind == OP_ATTN) { out->k = o.heads; out->stride = o.causal ? 1 : 0; out->pad = o.a0; out->k_col = o.a1; out->v_col = o.a2; }
   out->res_grad = residual_grad_route(m, (int)idx, batch);
   out->fused_pool = pool_fused(m, (int)idx) ? 1 : 0;
   return CD_OK;
@@ -623,13 +720,33 @@ extern "C" int codistill_forward(const cd_model* m, const void* params, const vo
       }
       case OP_LINEAR: {
         const int F = tx.c, C = m->tensors[o.y].c;
-        ProfScope pr(CD_K_LINEAR, c.s, 2.0 * batch * F * C,
-                     (double)m->esize() * ((double)batch * F + (double)F * C) + 4.0 * batch * C);
+        const int64_t rows = batch * tx.h * tx.w;
+        ProfScope pr(CD_K_LINEAR, c.s, 2.0 * rows * F * C,
+                     (double)m->esize() * ((double)rows * F + (double)F * C) + 4.0 * rows * C);
         if (dt == CD_BF16 && !force_simple() && F % 8 == 0 && (int64_t)F * C * 2 < (1LL << 31))
           linear_fwd_mfma(static_cast<const bf16_t*>(in), static_cast<const bf16_t*>(c.P(o.pw)),
-                          static_cast<const bf16_t*>(c.P(o.pb)), static_cast<float*>(out), batch, F, C, c.s);
+                          static_cast<const bf16_t*>(c.P(o.pb)), static_cast<float*>(out), rows, F, C, c.s);
         else
-          linear_fwd(dt, in, c.P(o.pw), c.P(o.pb), static_cast<float*>(out), batch, F, C, c.s);
+          linear_fwd(dt, in, c.P(o.pw), c.P(o.pb), static_cast<float*>(out), rows, F, C, c.s);
+        break;
+      }
+      case OP_EMBED: {
+        const TensorDesc& ty = m->tensors[o.y];
+        ProfScope pr(CD_K_GLUE, c.s, 0, (double)batch * ty.per_sample() * m->esize() * 2);
+        embed_forward(dt, static_cast<const int32_t*>(x), m->tensors[0].w, o.a0, o.a1, c.P(o.pw), m->arch.classes, ty.c, out,
+                      batch * ty.h, c.s);
+        break;
+      }
+      case OP_ATTN: {
+        const TensorDesc& tkv = m->tensors[o.res];
+        const TensorDesc& ty = m->tensors[o.y];
+        const int d = ty.c, dh = d / o.heads, Tq = tx.h, Tk = tkv.h;
+        const bf16_t* kvp = static_cast<const bf16_t*>(c.act(o.res));
+        ProfScope pr(CD_K_ATTN, c.s, 4.0 * batch * o.heads * Tq * (double)Tk * dh * (o.causal ? 0.5 : 1.0),
+                     2.0 * batch * ((double)Tq * 2 + (double)Tk * 2) * d);
+        attention_forward(static_cast<const bf16_t*>(in) + o.a0, tx.c, kvp + o.a1, kvp + o.a2, tkv.c,
+                          static_cast<bf16_t*>(out), d, c.plan.aux[oi] ? reinterpret_cast<float*>(c.ws + c.plan.aux[oi]) : nullptr,
+                          (int)batch, o.heads, Tq, Tk, dh, o.causal, c.s);
         break;
       }
     }
@@ -693,27 +810,56 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
     switch (o.kind) {
       case OP_LINEAR: {
         const int F = tx.c, C = m->tensors[o.y].c;
-        ConvGeom g;  // the dense layer as a 1x1 convolution over a 1x1 image
-        g.B = batch; g.H = g.W = g.Ho = g.Wo = 1; g.Cin = F; g.Cout = C; g.kh = g.kw = 1; g.stride = 1; g.pad = 0;
+        const int64_t rows = batch * tx.h * tx.w;
+        ConvGeom g;  // the dense layer as a 1x1 convolution over one pixel per row
+        g.B = rows; g.H = g.W = g.Ho = g.Wo = 1; g.Cin = F; g.Cout = C; g.kh = g.kw = 1; g.stride = 1; g.pad = 0;
         if (dt == CD_BF16 && !force_simple() && conv_mfma_supported(g)) {
           bf16_t* dzb = reinterpret_cast<bf16_t*>(c.ws + c.plan.lin_dz);
           {
-            ProfScope pr(CD_K_GLUE, c.s, 0, (double)batch * C * (6.0 + (o.pb >= 0 ? 4.0 : 0.0)));
-            cast_f32_bf16(dlogits, dzb, batch * C, c.s);
-            if (o.pb >= 0) colsum(CD_F32, dlogits, batch, C, G(o.pb), c.partials(), c.s);
+            ProfScope pr(CD_K_GLUE, c.s, 0, (double)rows * C * (6.0 + (o.pb >= 0 ? 4.0 : 0.0)));
+            cast_f32_bf16(dlogits, dzb, rows * C, c.s);
+            if (o.pb >= 0) colsum(CD_F32, dlogits, rows, C, G(o.pb), c.partials(), c.s);
           }
           {
-            ProfScope pr(CD_K_CONV_WGRAD, c.s, 2.0 * batch * F * C, conv_bytes(m, g) + 2.0 * C * F);
+            // (on the caller's stream: a tied table's gradient is added to by the embedding ops at the end)
+            ProfScope pr(CD_K_CONV_WGRAD, c.s, 2.0 * rows * F * C, conv_bytes(m, g) + 2.0 * C * F);
             conv_wgrad_mfma(static_cast<const bf16_t*>(in), dzb, G(o.pw), g, c.partials(), c.plan.partials_bytes, c.s);
           }
           {
-            ProfScope pr(CD_K_CONV_DGRAD, c.s, 2.0 * batch * F * C, conv_bytes(m, g));
+            ProfScope pr(CD_K_CONV_DGRAD, c.s, 2.0 * rows * F * C, conv_bytes(m, g));
             conv_dgrad_mfma(dzb, static_cast<const bf16_t*>(c.P(o.pw)), c.wpack(), static_cast<bf16_t*>(dx), g, acc, c.s);
           }
         } else {
-          ProfScope pr(CD_K_LINEAR, c.s, 4.0 * batch * F * C, (double)m->esize() * ((double)batch * F + (double)F * C) * 2);
-          linear_bwd(dt, in, c.P(o.pw), dlogits, dx, acc, G(o.pw), o.pb >= 0 ? G(o.pb) : nullptr, batch, F, C, c.s);
+          ProfScope pr(CD_K_LINEAR, c.s, 4.0 * rows * F * C, (double)m->esize() * ((double)rows * F + (double)F * C) * 2);
+          linear_bwd(dt, in, c.P(o.pw), dlogits, dx, acc, G(o.pw), o.pb >= 0 ? G(o.pb) : nullptr, rows, F, C, c.s);
         }
+        break;
+      }
+      case OP_EMBED: {
+        // every occurrence of a token adds its row of dy to the table's gradient, which already holds the
+        // gradient of the tied output projection (the first op of this pass)
+        const TensorDesc& ty = m->tensors[o.y];
+        ProfScope pr(CD_K_GLUE, c.s, 0, (double)batch * ty.per_sample() * (m->esize() + 8.0));
+        embed_backward(dt, static_cast<const int32_t*>(x), m->tensors[0].w, o.a0, o.a1, dy, m->arch.classes, ty.c, G(o.pw),
+                       batch * ty.h, c.s);
+        break;
+      }
+      case OP_ATTN: {
+        const TensorDesc& tkv = m->tensors[o.res];
+        const TensorDesc& ty = m->tensors[o.y];
+        const int d = ty.c, dh = d / o.heads, Tq = tx.h, Tk = tkv.h;
+        if (written[o.x] || written[o.res])
+          return set_error(CD_ERR_UNSUPPORTED, "backward: the inputs of an attention op must have no other reader");
+        const bf16_t* kvp = static_cast<const bf16_t*>(c.act(o.res));
+        bf16_t* dkv = static_cast<bf16_t*>(c.grad(o.res));
+        float* lse = reinterpret_cast<float*>(c.ws + c.plan.aux[i]);
+        ProfScope pr(CD_K_ATTN, c.s, 14.0 * batch * o.heads * Tq * (double)Tk * dh * (o.causal ? 0.5 : 1.0),
+                     2.0 * batch * ((double)Tq * 3 + (double)Tk * 4) * d);
+        attention_backward(static_cast<const bf16_t*>(in) + o.a0, tx.c, kvp + o.a1, kvp + o.a2, tkv.c,
+                           static_cast<const bf16_t*>(dy), d, lse, lse + (size_t)batch * o.heads * Tq,
+                           static_cast<bf16_t*>(dx) + o.a0, dkv + o.a1, dkv + o.a2, (int)batch, o.heads, Tq, Tk, dh, o.causal,
+                           c.s);
+        written[o.res] = 1;
         break;
       }
       case OP_GAP: {

@@ -56,11 +56,12 @@ class StepRunner:
         self.peer_params = [torch.zeros(pm.n_elements, dtype=pm.torch_dtype, device=device) for pm in self.peers]
         wsp = max([pm.workspace_bytes(batch, False) for pm in self.peers] + [256])
         self.ws_peer = torch.empty(wsp, dtype=torch.uint8, device=device)
-        self.logits = torch.empty(batch, C, **f32)
-        self.peer_logits = [torch.empty(batch, C, **f32) for _ in self.peers]
-        self.dz = torch.empty(batch, C, **f32)
+        rows = batch * model.rows_per_sample
+        self.logits = torch.empty(rows, C, **f32)
+        self.peer_logits = [torch.empty(rows, C, **f32) for _ in self.peers]
+        self.dz = torch.empty(rows, C, **f32)
         self.loss = torch.zeros(4, **f32)
-        self.scratch = torch.empty(B.loss_scratch_bytes(batch, C), dtype=torch.uint8, device=device)
+        self.scratch = torch.empty(B.loss_scratch_bytes(rows, C), dtype=torch.uint8, device=device)
 
     def params(self):
         return self.lowp if self.lowp is not None else self.master
@@ -79,7 +80,8 @@ class StepRunner:
 
     def step(self, x, y, alpha, lr, momentum, weight_decay=0.0, label_smoothing=0.0,
              dist_kind=B.CD_DIST_MSE_LOGITS, mse_reduction=B.CD_MEAN_ALL, ignore_index=-1, nesterov=False):
-        """x: [B,H,W,3] device tensor in the model dtype; y: int32 device tensor."""
+        """x: [B,H,W,3] device tensor in the model dtype (the Transformer: int32 [B, source + target tokens]);
+        y: int32 device tensor, one target per row of logits."""
         if self.overlap_peers and self.peers:
             main = torch.cuda.current_stream()
             self.side.wait_stream(main)           # x, the peer parameters and the last step's reads are in order

@@ -51,6 +51,8 @@ def he_init(param_table, seed, jitter=0.0):
         n = int(np.prod(shape))
         if kind in ("conv_w", "linear_w"):
             a = rng.standard_normal(n) * np.sqrt(2.0 / fan_in)
+        elif kind == "embed_w":     # rows of variance 1/d: times sqrt(d) they match the position signal's scale
+            a = rng.standard_normal(n) / np.sqrt(fan_in)
         elif kind == "bn_gamma":
             a = 1.0 + jitter * rng.standard_normal(n)
         else:
@@ -61,6 +63,11 @@ def he_init(param_table, seed, jitter=0.0):
 
 def images(batch, h, w, c, seed):
     return _rng(seed).standard_normal((batch, h, w, c)).astype(np.float32)
+
+
+def tokens(sentences, length, vocab, seed):
+    """Uniform token ids, int32 [sentences, length] (stand-in for byte-pair encoded text)."""
+    return _rng(seed).integers(0, vocab, size=(sentences, length)).astype(np.int32)
 
 
 def labels(n, classes, seed):

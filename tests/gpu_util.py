@@ -19,20 +19,30 @@ def norm_err(a, b):
 class Case:
     """Inputs of one codistillation step for an architecture (library preset kwargs + oracle arch)."""
 
-    def __init__(self, arch_kw, ref_arch, dtype_name, batch, res, classes, jitter=0.1, v_scale=0.0, in_c=3):
+    def __init__(self, arch_kw, ref_arch, dtype_name, batch, res, classes, jitter=0.1, v_scale=0.0, in_c=3, tokens=None):
+        """tokens = (source length, target length): the input is int32 token ids and there is one row of logits
+        (and one label) per target token; res is then unused."""
         from paper_2010_02838_amd import binding as B
         self.B = B
         self.dtype = B.CD_BF16 if dtype_name == "bf16" else B.CD_F32
         kw = dict(arch_kw)
-        arch = B.arch_preset(kw.pop("kind"), in_h=res, in_w=res, classes=classes, **kw)
+        if tokens:
+            arch = B.arch_preset(kw.pop("kind"), in_h=tokens[0], in_w=tokens[1], classes=classes, **kw)
+        else:
+            arch = B.arch_preset(kw.pop("kind"), in_h=res, in_w=res, classes=classes, **kw)
         self.model, self.peer = B.Model(arch, self.dtype), B.Model(arch, self.dtype)
         self.ref_arch, self.batch, self.res, self.classes = ref_arch, batch, res, classes
         table = self.model.param_table()
         assert table == [(n, tuple(s), k, f) for n, s, k, f in ref_arch.params]
         self.th, self.thp = synth.he_init(table, 1, jitter), synth.he_init(table, 2, jitter)
-        self.x, self.y = synth.images(batch, res, res, in_c, seed=0), synth.labels(batch, classes, seed=3)
-        if self.dtype == B.CD_BF16:   # both sides consume the same bf16-rounded weights and images
-            self.th, self.thp, self.x = (synth.round_bf16(a) for a in (self.th, self.thp, self.x))
+        if tokens:
+            self.x = synth.tokens(batch, tokens[0] + tokens[1], classes, seed=0)
+            self.y = synth.labels(batch * tokens[1], classes, seed=3)
+            self.th, self.thp = synth.round_bf16(self.th), synth.round_bf16(self.thp)
+        else:
+            self.x, self.y = synth.images(batch, res, res, in_c, seed=0), synth.labels(batch, classes, seed=3)
+            if self.dtype == B.CD_BF16:   # both sides consume the same bf16-rounded weights and images
+                self.th, self.thp, self.x = (synth.round_bf16(a) for a in (self.th, self.thp, self.x))
         self.v0 = None
         if v_scale:
             self.v0 = (np.random.default_rng(5).standard_normal(self.th.size) * v_scale).astype(np.float32)
@@ -49,7 +59,7 @@ class Case:
         r = StepRunner(model, [self.peer], self.batch)
         r.load(pack_flat(model, self.th), [pack_flat(self.peer, self.thp)],
                None if self.v0 is None else pack_flat(model, self.v0))
-        xd = to_device(self.x, model.torch_dtype)
+        xd = torch.from_numpy(self.x).to("cuda:0") if self.x.dtype == np.int32 else to_device(self.x, model.torch_dtype)
         yd = torch.from_numpy(self.y).to("cuda:0")
         r.step(xd, yd, alpha, lr, mu, weight_decay=wd, label_smoothing=label_smoothing,
                dist_kind={"kl": B.CD_DIST_KL, "mse": B.CD_DIST_MSE_LOGITS, "mse_centered": B.CD_DIST_MSE_CENTERED}[dist])

@@ -138,6 +138,20 @@ def check_layers(c, got):
         if t != 0:
             expected[t] = g if t not in expected else expected[t] + g
 
+    # a parameter used by several ops (the tied embedding table) gets the sum of their gradients
+    uses = {}
+    for o in ops:
+        if o["param_w"] >= 0:
+            uses[o["param_w"]] = uses.get(o["param_w"], 0) + 1
+    shared = {}
+
+    def pgrad(o, g, tag, tol):
+        name = names[o["param_w"]]
+        if uses[o["param_w"]] > 1:
+            shared[name] = g if name not in shared else shared[name] + g
+        else:
+            note("pgrad", rel(G[name], g), tag + ".w", tol)
+
     for i, o in enumerate(ops):
         x = act(o["x"])
         fused_pool = o["kind"] == "bn" and o["fused_pool"]
@@ -153,10 +167,32 @@ def check_layers(c, got):
                 dy = L.relu_backward(y, dy)
             note("act", rel(y, yr), tag, tol_t)
             dx, dw, db = L.conv2d_backward(x, w, dy, o["stride"], o["pad"], b is not None, o["x"] != 0)
-            note("pgrad", rel(G[names[o["param_w"]]], dw), tag + ".w", TOL_F32_TENSOR)
+            pgrad(o, dw, tag, TOL_F32_TENSOR)
             if b is not None:
                 note("pgrad", rel(G[names[o["param_b"]]], db), tag + ".b", TOL_F32_TENSOR)
             contribute(o["x"], dx)
+        elif o["kind"] == "embed":
+            tok = c.x[:, o["k"]:o["k"] + o["stride"]]
+            yr = L.embed_forward(tok, w).reshape(y.shape)
+            note("act", rel(y, yr), tag, tol_t)
+            pgrad(o, L.embed_backward(tok, w.shape, dy), tag, TOL_F32_TENSOR)
+        elif o["kind"] == "attn":
+            d = y.shape[-1]
+            kv = act(o["res"])
+            x2, kv2 = x.reshape(-1, x.shape[-1]), kv.reshape(-1, kv.shape[-1])
+            qc, kc, vc = o["pad"], o["k_col"], o["v_col"]
+            q, kk, v = x2[:, qc:qc + d], kv2[:, kc:kc + d], kv2[:, vc:vc + d]
+            yr, Pm = L.attention_forward(q, kk, v, c.batch, o["k"], bool(o["stride"]))
+            note("act", rel(y.reshape(-1, d), yr), tag, tol_t)
+            dq, dk, dv = L.attention_backward(q, kk, v, Pm, dy.reshape(-1, d), c.batch, o["k"])
+            gx, gkv = np.zeros_like(x2), np.zeros_like(kv2)
+            gx[:, qc:qc + d] = dq
+            tgt = gx if o["res"] == o["x"] else gkv
+            tgt[:, kc:kc + d] += dk
+            tgt[:, vc:vc + d] += dv
+            contribute(o["x"], gx.reshape(x.shape))
+            if o["res"] != o["x"]:
+                contribute(o["res"], gkv.reshape(kv.shape))
         elif o["kind"] == "bn":
             yr, cache = L.batchnorm_forward(x, w, b)
             stats = c.read(o["stats_offset"], (4, x.shape[-1]), f32=True)
@@ -204,14 +240,16 @@ def check_layers(c, got):
             if o["res"] >= 0:
                 contribute(o["res"], dx)
         elif o["kind"] == "linear":
-            x2 = x.reshape(c.batch, -1)
+            x2 = x.reshape(-1, x.shape[-1]) if x.shape[1] * x.shape[2] > 1 else x.reshape(c.batch, -1)
             note("act", rel(y, L.linear_forward(x2, w, b)), tag, 2e-5 if f32 else 1e-4)
             dx, dw, db = L.linear_backward(x2, w, dy, b is not None)
             # the bf16 model's dense-layer backward runs on the MFMA kernels from a bf16 copy of d loss / d logits
-            note("pgrad", rel(G[names[o["param_w"]]], dw), tag + ".w", TOL_F32_TENSOR if f32 else TOL_BF16_TENSOR)
+            pgrad(o, dw, tag, TOL_F32_TENSOR if f32 else TOL_BF16_TENSOR)
             if b is not None:
                 note("pgrad", rel(G[names[o["param_b"]]], db), tag + ".b", TOL_F32_TENSOR)
             contribute(o["x"], dx.reshape(x.shape))
+    for name, g in shared.items():
+        note("pgrad", rel(G[name], g), name, TOL_BF16_TENSOR)
     # the backward pass of a convolution with a fused ReLU masks the stored gradient of its output in place
     masked = {o["y"] for o in ops if o["kind"] == "conv" and o["relu"]}
     for t, g in expected.items():

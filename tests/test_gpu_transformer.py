@@ -1,0 +1,48 @@
+"""GPU parity of the encoder-decoder Transformer (bf16) through the C ABI: every op teacher-forced against
+the float64 oracle, and the whole codistillation step end to end."""
+import numpy as np
+import pytest
+
+from oracle import nets
+from paper_2010_02838_amd import synth
+from gpu_util import Case, rel
+from test_gpu_step import check_layers, compare_bf16
+
+pytestmark = pytest.mark.gpu
+
+CASES = {
+    # S, Ts, Tt, d, heads, d_ff, vocab, encoder layers, decoder layers
+    "small": (3, 10, 7, 32, 4, 64, 64, 2, 2),                 # head dimension 8
+    "ragged_vocab": (2, 5, 9, 32, 2, 40, 50, 1, 2),           # head dimension 16, vocabulary not a multiple of 8
+    "long": (2, 150, 131, 128, 2, 128, 96, 1, 1),             # head dimension 64; several query tiles and key chunks
+}
+
+
+def make(name):
+    S, Ts, Tt, d, heads, ff, vocab, ne, nd = CASES[name]
+    ref = nets.transformer(S, Ts, Tt, d=d, heads=heads, d_ff=ff, vocab=vocab, enc_layers=ne, dec_layers=nd)
+    return Case(dict(kind=4, widths=[d, ff, heads], blocks=[ne, nd]), ref, "bf16", S, 0, vocab, jitter=0.1,
+                tokens=(Ts, Tt))
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_transformer_bf16_layers(name):
+    c = make(name)
+    check_layers(c, c.gpu(alpha=0.5, label_smoothing=0.1))
+
+
+@pytest.mark.parametrize("name", ["small", "ragged_vocab"])
+def test_transformer_bf16_step(name):
+    c = make(name)
+    kw = dict(alpha=0.5, label_smoothing=0.1)
+    compare_bf16(c, c.oracle(**kw), c.oracle(store=synth.round_bf16_f64, **kw), c.gpu(**kw))
+
+
+def test_transformer_kl_step_and_base_shape_metadata():
+    c = make("small")
+    kw = dict(alpha=1.0, label_smoothing=0.1, dist="kl")
+    compare_bf16(c, c.oracle(**kw), c.oracle(store=synth.round_bf16_f64, **kw), c.gpu(**kw))
+    B = c.B
+    base = B.Model(B.arch_preset(B.CD_ARCH_TRANSFORMER), B.CD_BF16)
+    assert sum(p["size"] for p in base.params) == 60915712
+    assert base.rows_per_sample == 128
