@@ -178,6 +178,62 @@ def transformer_head(args, B, synth, StepRunner, pack_flat, to_device, torch, de
     }
 
 
+def transformer(args, B, synth, StepRunner, pack_flat, torch, dev):
+    """One codistillation step of the base encoder-decoder Transformer (two models: 6 + 6 layers, d_model 512,
+    8 heads, d_ff 2048, shared vocabulary 32768, bf16) on 64 sentence pairs of 128 + 128 tokens = 8192 target
+    tokens: token ids uniform, label smoothing 0.1, alpha 1, KL distillation term.  roofline: the kernel class
+    that takes the most time of the step."""
+    S, Ts, Tt, vocab = 64, 128, 128, 32768
+    arch = B.arch_preset(B.CD_ARCH_TRANSFORMER)
+    model, peer = B.Model(arch, B.CD_BF16), B.Model(arch, B.CD_BF16)
+    table = model.param_table()
+    r = StepRunner(model, [peer], S, dev)
+    r.load(pack_flat(model, synth.he_init(table, 1)), [pack_flat(peer, synth.he_init(table, 2))])
+    x = torch.from_numpy(synth.tokens(S, Ts + Tt, vocab, seed=100)).to(dev)
+    y = torch.from_numpy(synth.labels(S * Tt, vocab, seed=3)).to(dev)
+
+    def step():
+        r.step(x, y, 1.0, 0.1, 0.9, label_smoothing=0.1, dist_kind=B.CD_DIST_KL)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / args.steps * 1e3
+    loss = r.loss.cpu().numpy()
+    r.overlap_peers = False           # the timer pass keeps every launch on one stream
+    B.profile_reset()
+    B.profile_enable(True)
+    psteps = max(1, min(args.steps, 5))
+    for _ in range(psteps):
+        step()
+    torch.cuda.synchronize()
+    prof = B.profile_collect()
+    B.profile_enable(False)
+    classes_ms = {k: round(v["ms"] / psteps, 4) for k, v in prof.items()}
+    top = max(("conv_fprop", "conv_dgrad", "conv_wgrad", "attention", "linear", "loss", "norm"), key=lambda k: prof[k]["ms"])
+    p = prof[top]
+    roof = roofline_of(p["flops"], p["bytes"], p["ms"], p["launches"], "kernel class '%s' of the library's timer" % top, None)
+    roof["launches_per_step"] = p["launches"] / psteps
+    return {
+        "metric": "codistill-step target tokens/sec on 1 MI355X (Transformer-base, 64 x (128 + 128) tokens, vocab 32768)",
+        "value": S * Tt / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "transformer_base_codistill_step", "sentences": S, "source_tokens": Ts, "target_tokens": Tt,
+                   "d_model": 512, "heads": 8, "d_ff": 2048, "layers": "6+6", "vocab": vocab,
+                   "models": "2 x Transformer-base (local fwd+bwd+SGD, peer fwd)", "alpha": 1.0, "label_smoothing": 0.1,
+                   "distillation": "kl"},
+        "loss": [float(v) for v in loss[:3]],
+        "roofline": roof,
+        "kernel_class_ms_per_step": classes_ms,
+        "cpu_baseline": None,
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -185,7 +241,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--batch", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", default="resnet50", choices=["resnet50", "transformer_head"],
+    ap.add_argument("--workload", default="resnet50", choices=["resnet50", "transformer_head", "transformer"],
                     help="resnet50 (default): the headline metric.  transformer_head: the output block of the base "
                          "Transformer (feed-forward sublayer, residual, LayerNorm, vocabulary projection) on 8192 target "
                          "tokens, a separate JSON line with its own metric")
@@ -206,6 +262,9 @@ def main():
     dev = "cuda:0"
     if args.workload == "transformer_head":
         print(json.dumps(transformer_head(args, B, synth, StepRunner, pack_flat, to_device, torch, dev)))
+        return
+    if args.workload == "transformer":
+        print(json.dumps(transformer(args, B, synth, StepRunner, pack_flat, torch, dev)))
         return
     if args.copy_calibration:
         a = torch.ones(1 << 28, device=dev)
