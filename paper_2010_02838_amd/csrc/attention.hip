@@ -140,8 +140,19 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_k(AttArgs a) {
     lse = a.lse[((int64_t)s * a.heads + h) * a.Tq + i];
   }
   const int last = a.causal ? min(a.Tk, tile * ATT_ROWS + ATT_ROWS) : a.Tk;
-  float D = 0.f;
+  // Where the weights are nearly uniform dq is a small difference of large terms (10^4 times smaller at the base
+  // model's initialisation), so relative errors of 1e-7 in the recomputed probabilities matter.  Two measures:
+  // the weights are recomputed as w_j = exp(s_j - (lse - log n)), n the number of visible keys, whose exponent is
+  // near zero exactly in the uniform case (small exponents round finely), and they are normalised by their own
+  // sum Z, which makes sum_j w_j (dp_j - D) vanish whatever Z is: D = sum w dp / Z, dq = sum w (dp - D) k / Z.
+  // Third, dp is taken relative to the first key's (dp_j - dp_0; dp - D does not change): when the values are
+  // nearly alike D then is as small as the differences, and its rounding error, which every term shares and
+  // which multiplies the keys' common part, shrinks with it.
+  const int visible = a.causal ? min(i + 1, a.Tk) : a.Tk;
+  const float ref = lse - __logf((float)max(visible, 1));
+  float D = 0.f, Z = 0.f, dp0 = 0.f;
   for (int pass = 0; pass < 2; pass++) {
+    if (pass == 1 && Z > 0.f) D /= Z;
     for (int j0 = 0; j0 < last; j0 += ATT_KC) {
       const int n = min(ATT_KC, a.Tk - j0);
       __syncthreads();
@@ -155,11 +166,15 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_k(AttArgs a) {
           ps += q[c] * Ks[j * DH + hf * HALF + c];
           pd += go[c] * Vs[j * DH + hf * HALF + c];
         }
-        const float sc = pair_sum(ps), dp = pair_sum(pd);
+        const float sc = pair_sum(ps);
+        float dp = pair_sum(pd);
         if (!live || (a.causal && j0 + j > i)) continue;
-        const float p = __expf(sc - lse);
+        if (pass == 0 && j0 + j == 0) dp0 = dp;
+        dp -= dp0;
+        const float p = __expf(sc - ref);
         if (pass == 0) {
           D += p * dp;
+          Z += p;
         } else {
           const float ds = p * (dp - D);
 #pragma unroll
@@ -170,9 +185,10 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_k(AttArgs a) {
   }
   if (!live) return;
   bf16_t* dp_ = a.dq + ((int64_t)s * a.Tq + i) * a.ldq + h * DH + hf * HALF;
+  const float fin = Z > 0.f ? a.scale / Z : 0.f;
 #pragma unroll
-  for (int c = 0; c < HALF; c++) dp_[c] = f32_to_bf16(dq[c] * a.scale);
-  if (hf == 0) a.dsum[((int64_t)s * a.heads + h) * a.Tq + i] = D;
+  for (int c = 0; c < HALF; c++) dp_[c] = f32_to_bf16(dq[c] * fin);
+  if (hf == 0) a.dsum[((int64_t)s * a.heads + h) * a.Tq + i] = D + dp0;
 }
 
 // dk, dv: one pair of threads per key; the queries (scaled), their output gradients, log-sum-exps and

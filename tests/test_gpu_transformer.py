@@ -46,3 +46,15 @@ def test_transformer_kl_step_and_base_shape_metadata():
     base = B.Model(B.arch_preset(B.CD_ARCH_TRANSFORMER), B.CD_BF16)
     assert sum(p["size"] for p in base.params) == 60915712
     assert base.rows_per_sample == 128
+
+
+@pytest.mark.timeout(900)
+def test_transformer_base_size_layers():
+    """The benchmarked shape (base model, 64 sentences of 128 source + 128 target tokens, vocabulary 32768, the
+    two-stream launch configuration): every op of the 12 layers teacher-forced against the oracle, all elements."""
+    S, Ts, Tt = 64, 128, 128
+    ref = nets.transformer(S, Ts, Tt)
+    c = Case(dict(kind=4), ref, "bf16", S, 0, 32768, jitter=0.1, tokens=(Ts, Tt))
+    got = c.gpu(alpha=1.0, label_smoothing=0.1)
+    assert np.isfinite(got["loss"]).all() and got["loss"][2] > 0
+    check_layers(c, got)
