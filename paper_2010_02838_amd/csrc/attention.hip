@@ -13,6 +13,7 @@
 #include "common.h"
 #include "kernels.h"
 #include <math.h>
+#include <stdlib.h>
 
 namespace cd {
 
@@ -248,6 +249,178 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_k(AttArgs a) {
   for (int c = 0; c < HALF; c++) { dkp[c] = f32_to_bf16(dk[c] * a.scale); dvp[c] = f32_to_bf16(dv[c]); }
 }
 
+// ---- matrix-core kernels (head dimension 64) -------------------------------------------------------
+// v_mfma_f32_32x32x16_bf16 computes D[32x32] += A[32x16] B[16x32]: lane l holds row l % 32 of A and
+// column l % 32 of B, eight contraction elements 8 (l / 32) .. + 7 each, and column l % 32 of D, whose
+// register v is row 8 (v / 4) + 4 (l / 32) + v % 4.
+//
+// All three kernels put the 32 rows a wave owns (queries in the forward pass and for dq, keys for dk and dv)
+// on the lanes, as the B operand, so that everything per row (running maximum, sums, rescaling) is per lane
+// and a score tile leaves the matrix core as [streamed rows on registers][own row on the lane].  Rounded
+// to bf16, eight registers of such a tile are a B operand again, with the streamed rows as contraction index
+// in the order 8 (e / 4) + 4 (l / 32) + e % 4 (e = 0..7) inside each group of 16: the A operand of that second
+// product is read from a transposed copy of the streamed tensor in LDS, as two 8-byte pieces 8 elements
+// apart, which is exactly that order.
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+constexpr int MF_KC = 64;     // streamed rows per LDS chunk
+constexpr int MF_PITCH = 72;  // LDS row pitch in elements: 144 bytes, so that 16-byte reads of 8 rows cover all banks
+
+__device__ inline uint32_t pack_bf16_pair(float lo, float hi) {
+  const f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+
+__device__ inline bf16x8_t frag_from(uint4 u) { return __builtin_bit_cast(bf16x8_t, u); }
+
+// eight consecutive registers 8 * t2 .. of a tile, rounded to bf16: one B operand
+__device__ inline bf16x8_t tile_to_operand(const f32x16_t& d, int t2) {
+  uint4 u;
+  u.x = pack_bf16_pair(d[8 * t2 + 0], d[8 * t2 + 1]);
+  u.y = pack_bf16_pair(d[8 * t2 + 2], d[8 * t2 + 3]);
+  u.z = pack_bf16_pair(d[8 * t2 + 4], d[8 * t2 + 5]);
+  u.w = pack_bf16_pair(d[8 * t2 + 6], d[8 * t2 + 7]);
+  return frag_from(u);
+}
+
+// A operand from a transposed LDS copy: row `row`, contraction group u of 16, for the lane half hh
+__device__ inline bf16x8_t transposed_operand(const bf16_t* t, int row, int u, int hh) {
+  const bf16_t* p = t + row * MF_PITCH + 16 * u + 4 * hh;
+  const uint2 lo = *reinterpret_cast<const uint2*>(p), hi = *reinterpret_cast<const uint2*>(p + 8);
+  return frag_from(make_uint4(lo.x, lo.y, hi.x, hi.y));
+}
+
+// n rows x DH columns of a bf16 tensor into LDS, row-major with pitch MF_PITCH; rows n .. MF_KC-1 are zero
+template <int DH>
+__device__ inline void stage_rows(const bf16_t* __restrict__ base, int64_t ld, int n, bf16_t* __restrict__ dst) {
+  constexpr int VPR = DH / 8;
+  for (int v = threadIdx.x; v < MF_KC * VPR; v += 256) {
+    const int r = v / VPR, c = (v % VPR) * 8;
+    const uint4 u = r < n ? *reinterpret_cast<const uint4*>(base + (int64_t)r * ld + c) : make_uint4(0, 0, 0, 0);
+    *reinterpret_cast<uint4*>(dst + r * MF_PITCH + c) = u;
+  }
+}
+
+// The same rows transposed: dst[column][row].  Consecutive lanes take consecutive rows, so the 2-byte LDS
+// writes of a wave fall into consecutive addresses.  With CENTRE, ref[column] (fp32) is subtracted first.
+template <int DH, bool CENTRE>
+__device__ inline void stage_transposed(const bf16_t* __restrict__ base, int64_t ld, int n, bf16_t* __restrict__ dst,
+                                        const float* __restrict__ ref) {
+  constexpr int VPR = DH / 8;
+  for (int v = threadIdx.x; v < MF_KC * VPR; v += 256) {
+    const int r = v % MF_KC, g = v / MF_KC;
+    float t[8];
+    if (r < n) {
+      load_bf16_8(base + (int64_t)r * ld + 8 * g, t);
+      if (CENTRE) {
+#pragma unroll
+        for (int e = 0; e < 8; e++) t[e] -= ref[8 * g + e];
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; e++) t[e] = 0.f;
+    }
+#pragma unroll
+    for (int e = 0; e < 8; e++) dst[(8 * g + e) * MF_PITCH + r] = f32_to_bf16(t[e]);
+  }
+}
+
+// One wave: 32 queries on the lanes.  Per chunk of 64 keys: S^T = K Q^T (two 32-key tiles), online softmax per
+// lane (the two half-waves of a query exchange their maxima; their partial sums are added at the end),
+// O^T += V^T P^T with P rounded to bf16.
+template <int DH>
+__global__ void __launch_bounds__(256) attn_fwd_mfma_k(AttArgs a) {
+  constexpr int KS = DH / 16, DT = DH / 32;
+  __shared__ __attribute__((aligned(16))) bf16_t Ks[MF_KC * MF_PITCH];
+  __shared__ __attribute__((aligned(16))) bf16_t Vt[DH * MF_PITCH];
+  const int tiles = (a.Tq + ATT_ROWS - 1) / ATT_ROWS;
+  const int tile = blockIdx.x % tiles, sh = blockIdx.x / tiles;
+  const int h = sh % a.heads, s = sh / a.heads;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int c = lane & 31, hh = lane >> 5;
+  const int qi = tile * ATT_ROWS + wave * 32 + c;
+  const bool live = qi < a.Tq;
+  bf16x8_t qf[KS];
+#pragma unroll
+  for (int t = 0; t < KS; t++) {
+    uint4 u = make_uint4(0, 0, 0, 0);
+    if (live) u = *reinterpret_cast<const uint4*>(a.q + ((int64_t)s * a.Tq + qi) * a.ldq + h * DH + 16 * t + 8 * hh);
+    qf[t] = frag_from(u);
+  }
+  f32x16_t o[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; dt++)
+#pragma unroll
+    for (int v = 0; v < 16; v++) o[dt][v] = 0.f;
+  float m = -INFINITY, lsum = 0.f;
+  const int last = a.causal ? min(a.Tk, tile * ATT_ROWS + ATT_ROWS) : a.Tk;
+  for (int j0 = 0; j0 < last; j0 += MF_KC) {
+    const int n = min(MF_KC, a.Tk - j0);
+    __syncthreads();
+    stage_rows<DH>(a.k + ((int64_t)s * a.Tk + j0) * a.ldkv + h * DH, a.ldkv, n, Ks);
+    stage_transposed<DH, false>(a.v + ((int64_t)s * a.Tk + j0) * a.ldkv + h * DH, a.ldkv, n, Vt, nullptr);
+    __syncthreads();
+    f32x16_t sc[2];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int kt = 0; kt < 2; kt++) {
+#pragma unroll
+      for (int v = 0; v < 16; v++) sc[kt][v] = 0.f;
+#pragma unroll
+      for (int t = 0; t < KS; t++) {
+        const bf16x8_t kf = frag_from(*reinterpret_cast<const uint4*>(Ks + (32 * kt + c) * MF_PITCH + 16 * t + 8 * hh));
+        sc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[t], sc[kt], 0, 0, 0);
+      }
+#pragma unroll
+      for (int v = 0; v < 16; v++) {
+        const int kj = j0 + 32 * kt + 8 * (v >> 2) + 4 * hh + (v & 3);
+        float x = sc[kt][v] * a.scale;
+        if (kj >= a.Tk || (a.causal && kj > qi)) x = -INFINITY;
+        sc[kt][v] = x;
+        mx = fmaxf(mx, x);
+      }
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float mn = fmaxf(m, mx);          // finite from the first chunk on: key 0 is visible to every query
+    const float alpha = __expf(m - mn);     // 0 on the first chunk
+    m = mn;
+    float ps = 0.f;
+#pragma unroll
+    for (int kt = 0; kt < 2; kt++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) {
+        const float p = __expf(sc[kt][v] - mn);
+        sc[kt][v] = p;
+        ps += p;
+      }
+    lsum = lsum * alpha + ps;
+#pragma unroll
+    for (int dt = 0; dt < DT; dt++) o[dt] *= alpha;
+#pragma unroll
+    for (int u = 0; u < 4; u++) {
+      const bf16x8_t pb = tile_to_operand(sc[u >> 1], u & 1);
+#pragma unroll
+      for (int dt = 0; dt < DT; dt++)
+        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(transposed_operand(Vt, 32 * dt + c, u, hh), pb, o[dt], 0, 0, 0);
+    }
+  }
+  const float lt = lsum + __shfl_xor(lsum, 32, 64);
+  if (!live) return;
+  const float inv = 1.f / lt;
+  bf16_t* op = a.out + ((int64_t)s * a.Tq + qi) * a.ldo + h * DH + 4 * hh;
+#pragma unroll
+  for (int dt = 0; dt < DT; dt++)
+#pragma unroll
+    for (int g = 0; g < 4; g++)
+      *reinterpret_cast<uint2*>(op + 32 * dt + 8 * g) =
+          make_uint2(pack_bf16_pair(o[dt][4 * g] * inv, o[dt][4 * g + 1] * inv),
+                     pack_bf16_pair(o[dt][4 * g + 2] * inv, o[dt][4 * g + 3] * inv));
+  if (hh == 0 && a.lse) a.lse[((int64_t)s * a.heads + h) * a.Tq + qi] = m + __logf(lt);
+}
+
 // ---- embedding ------------------------------------------------------------------------------------
 // y[s*T + t][:] = table[tok[s][col0 + t]][:] * sqrt(d) + PE[t][:], PE[t][2i] = sin(t / 10000^(2i/d)),
 // PE[t][2i+1] = cos(same).  One thread per pair of columns.
@@ -290,6 +463,13 @@ __global__ void __launch_bounds__(256) embed_bwd_k(const int32_t* __restrict__ t
 
 }  // namespace
 
+// The matrix-core kernels read 16-byte vectors: head dimension 64 and row pitches that keep every row aligned.
+// CODISTILL_PLAIN_ATTENTION=1 keeps the plain kernels (for comparing the two).
+static bool use_mfma(int dh, int64_t ldq, int64_t ldkv, int64_t ldo) {
+  static const bool plain = [] { const char* e = getenv("CODISTILL_PLAIN_ATTENTION"); return e && e[0] == '1'; }();
+  return !plain && dh == 64 && ldq % 8 == 0 && ldkv % 8 == 0 && ldo % 8 == 0;
+}
+
 bool attention_supported(int dh) { return dh == 8 || dh == 16 || dh == 32 || dh == 64; }
 
 #define CD_ATT_DISPATCH(KERNEL, grid)                                                                      \
@@ -307,6 +487,10 @@ void attention_forward(const bf16_t* q, int64_t ldq, const bf16_t* k, const bf16
   a.S = S; a.heads = heads; a.Tq = Tq; a.Tk = Tk; a.causal = causal ? 1 : 0;
   a.scale = 1.f / sqrtf((float)dh);
   const unsigned grid = (unsigned)((int64_t)S * heads * cdiv(Tq, ATT_ROWS));
+  if (use_mfma(dh, ldq, ldkv, ldo)) {
+    hipLaunchKernelGGL((attn_fwd_mfma_k<64>), dim3(grid), dim3(256), 0, s, a);
+    return;
+  }
   CD_ATT_DISPATCH(attn_fwd_k, grid);
 }
 
