@@ -421,6 +421,209 @@ __global__ void __launch_bounds__(256) attn_fwd_mfma_k(AttArgs a) {
   if (hh == 0 && a.lse) a.lse[((int64_t)s * a.heads + h) * a.Tq + qi] = m + __logf(lt);
 }
 
+// dq on the matrix cores: 32 queries of a wave on the lanes, two passes over the keys as in the plain kernel
+// (the first for Z = sum w and D, the second for dq^T += (K - k_0)^T dS^T).  dS is rounded to bf16 for that last
+// product, which breaks sum_j dS_ij = 0 at the 1e-3 level; the keys are therefore taken relative to the first
+// key of the sentence (exactly what a vanishing sum allows), so that the rounding errors multiply the keys'
+// differences and not their common part.
+template <int DH>
+__global__ void __launch_bounds__(256) attn_bwd_dq_mfma_k(AttArgs a) {
+  constexpr int KS = DH / 16, DT = DH / 32;
+  __shared__ __attribute__((aligned(16))) bf16_t Ks[MF_KC * MF_PITCH];
+  __shared__ __attribute__((aligned(16))) bf16_t Vs[MF_KC * MF_PITCH];
+  __shared__ __attribute__((aligned(16))) bf16_t Kc[DH * MF_PITCH];
+  __shared__ float K0[DH];
+  const int tiles = (a.Tq + ATT_ROWS - 1) / ATT_ROWS;
+  const int tile = blockIdx.x % tiles, sh = blockIdx.x / tiles;
+  const int h = sh % a.heads, s = sh / a.heads;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int c = lane & 31, hh = lane >> 5;
+  const int qi = tile * ATT_ROWS + wave * 32 + c;
+  const bool live = qi < a.Tq;
+  bf16x8_t qf[KS], gf[KS];
+#pragma unroll
+  for (int t = 0; t < KS; t++) {
+    uint4 u = make_uint4(0, 0, 0, 0), g = make_uint4(0, 0, 0, 0);
+    if (live) {
+      u = *reinterpret_cast<const uint4*>(a.q + ((int64_t)s * a.Tq + qi) * a.ldq + h * DH + 16 * t + 8 * hh);
+      g = *reinterpret_cast<const uint4*>(a.dout + ((int64_t)s * a.Tq + qi) * a.ldo + h * DH + 16 * t + 8 * hh);
+    }
+    qf[t] = frag_from(u);
+    gf[t] = frag_from(g);
+  }
+  const float lse = live ? a.lse[((int64_t)s * a.heads + h) * a.Tq + qi] : 0.f;
+  const int visible = a.causal ? min(qi + 1, a.Tk) : a.Tk;
+  const float ref = lse - __logf((float)max(visible, 1));
+  if ((int)threadIdx.x < DH) K0[threadIdx.x] = bf16_to_f32(a.k[(int64_t)s * a.Tk * a.ldkv + h * DH + threadIdx.x]);
+  f32x16_t dq[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; dt++)
+#pragma unroll
+    for (int v = 0; v < 16; v++) dq[dt][v] = 0.f;
+  const int last = a.causal ? min(a.Tk, tile * ATT_ROWS + ATT_ROWS) : a.Tk;
+  float D = 0.f, Z = 0.f, dp0 = 0.f;
+  for (int pass = 0; pass < 2; pass++) {
+    if (pass == 1) {
+      Z += __shfl_xor(Z, 32, 64);
+      D += __shfl_xor(D, 32, 64);
+      D = Z > 0.f ? D / Z : 0.f;
+    }
+    for (int j0 = 0; j0 < last; j0 += MF_KC) {
+      const int n = min(MF_KC, a.Tk - j0);
+      const bf16_t* kb = a.k + ((int64_t)s * a.Tk + j0) * a.ldkv + h * DH;
+      __syncthreads();
+      stage_rows<DH>(kb, a.ldkv, n, Ks);
+      stage_rows<DH>(a.v + ((int64_t)s * a.Tk + j0) * a.ldkv + h * DH, a.ldkv, n, Vs);
+      if (pass == 1) stage_transposed<DH, true>(kb, a.ldkv, n, Kc, K0);
+      __syncthreads();
+      f32x16_t sc[2], dp[2];
+#pragma unroll
+      for (int kt = 0; kt < 2; kt++) {
+#pragma unroll
+        for (int v = 0; v < 16; v++) { sc[kt][v] = 0.f; dp[kt][v] = 0.f; }
+#pragma unroll
+        for (int t = 0; t < KS; t++) {
+          const int off = (32 * kt + c) * MF_PITCH + 16 * t + 8 * hh;
+          sc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_from(*reinterpret_cast<const uint4*>(Ks + off)), qf[t], sc[kt], 0, 0, 0);
+          dp[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_from(*reinterpret_cast<const uint4*>(Vs + off)), gf[t], dp[kt], 0, 0, 0);
+        }
+      }
+      if (pass == 0 && j0 == 0) dp0 = __shfl(dp[0][0], c, 64);   // register 0 of the lower half-wave is key 0
+#pragma unroll
+      for (int kt = 0; kt < 2; kt++)
+#pragma unroll
+        for (int v = 0; v < 16; v++) {
+          const int kj = j0 + 32 * kt + 8 * (v >> 2) + 4 * hh + (v & 3);
+          float w = __expf(sc[kt][v] * a.scale - ref);
+          if (kj >= a.Tk || (a.causal && kj > qi)) w = 0.f;
+          const float d = dp[kt][v] - dp0;
+          if (pass == 0) {
+            Z += w;
+            D += w * d;
+          } else {
+            dp[kt][v] = w * (d - D);
+          }
+        }
+      if (pass == 1) {
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+          const bf16x8_t dsb = tile_to_operand(dp[u >> 1], u & 1);
+#pragma unroll
+          for (int dt = 0; dt < DT; dt++)
+            dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(transposed_operand(Kc, 32 * dt + c, u, hh), dsb, dq[dt], 0, 0, 0);
+        }
+      }
+    }
+  }
+  if (!live) return;
+  const float fin = Z > 0.f ? a.scale / Z : 0.f;
+  bf16_t* op = a.dq + ((int64_t)s * a.Tq + qi) * a.ldq + h * DH + 4 * hh;
+#pragma unroll
+  for (int dt = 0; dt < DT; dt++)
+#pragma unroll
+    for (int g = 0; g < 4; g++)
+      *reinterpret_cast<uint2*>(op + 32 * dt + 8 * g) =
+          make_uint2(pack_bf16_pair(dq[dt][4 * g] * fin, dq[dt][4 * g + 1] * fin),
+                     pack_bf16_pair(dq[dt][4 * g + 2] * fin, dq[dt][4 * g + 3] * fin));
+  if (hh == 0) a.dsum[((int64_t)s * a.heads + h) * a.Tq + qi] = D + dp0;
+}
+
+// dk, dv on the matrix cores: 32 keys of a wave on the lanes; per chunk of 64 queries S = Q K^T and
+// dP = dO V^T (queries on the registers), then dV^T += dO^T P and dK^T += Q^T dS with P, dS rounded to bf16
+// and Q, dO read from transposed LDS copies.
+template <int DH>
+__global__ void __launch_bounds__(256) attn_bwd_dkv_mfma_k(AttArgs a) {
+  constexpr int KS = DH / 16, DT = DH / 32;
+  __shared__ __attribute__((aligned(16))) bf16_t Qs[MF_KC * MF_PITCH];
+  __shared__ __attribute__((aligned(16))) bf16_t Gs[MF_KC * MF_PITCH];
+  __shared__ __attribute__((aligned(16))) bf16_t Qt[DH * MF_PITCH];
+  __shared__ __attribute__((aligned(16))) bf16_t Gt[DH * MF_PITCH];
+  __shared__ float Ls[MF_KC], Ds[MF_KC];
+  const int tiles = (a.Tk + ATT_ROWS - 1) / ATT_ROWS;
+  const int tile = blockIdx.x % tiles, sh = blockIdx.x / tiles;
+  const int h = sh % a.heads, s = sh / a.heads;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int c = lane & 31, hh = lane >> 5;
+  const int kj = tile * ATT_ROWS + wave * 32 + c;
+  const bool live = kj < a.Tk;
+  bf16x8_t kf[KS], vf[KS];
+#pragma unroll
+  for (int t = 0; t < KS; t++) {
+    uint4 u = make_uint4(0, 0, 0, 0), w = make_uint4(0, 0, 0, 0);
+    if (live) {
+      u = *reinterpret_cast<const uint4*>(a.k + ((int64_t)s * a.Tk + kj) * a.ldkv + h * DH + 16 * t + 8 * hh);
+      w = *reinterpret_cast<const uint4*>(a.v + ((int64_t)s * a.Tk + kj) * a.ldkv + h * DH + 16 * t + 8 * hh);
+    }
+    kf[t] = frag_from(u);
+    vf[t] = frag_from(w);
+  }
+  f32x16_t dk[DT], dv[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; dt++)
+#pragma unroll
+    for (int v = 0; v < 16; v++) { dk[dt][v] = 0.f; dv[dt][v] = 0.f; }
+  const int first = a.causal ? tile * ATT_ROWS / MF_KC * MF_KC : 0;   // earlier queries see none of the tile's keys
+  for (int i0 = first; i0 < a.Tq; i0 += MF_KC) {
+    const int n = min(MF_KC, a.Tq - i0);
+    const bf16_t* qb = a.q + ((int64_t)s * a.Tq + i0) * a.ldq + h * DH;
+    const bf16_t* gb = a.dout + ((int64_t)s * a.Tq + i0) * a.ldo + h * DH;
+    __syncthreads();
+    stage_rows<DH>(qb, a.ldq, n, Qs);
+    stage_rows<DH>(gb, a.ldo, n, Gs);
+    stage_transposed<DH, false>(qb, a.ldq, n, Qt, nullptr);
+    stage_transposed<DH, false>(gb, a.ldo, n, Gt, nullptr);
+    if ((int)threadIdx.x < MF_KC) {
+      const bool in = (int)threadIdx.x < n;
+      Ls[threadIdx.x] = in ? a.lse[((int64_t)s * a.heads + h) * a.Tq + i0 + threadIdx.x] : 0.f;
+      Ds[threadIdx.x] = in ? a.dsum[((int64_t)s * a.heads + h) * a.Tq + i0 + threadIdx.x] : 0.f;
+    }
+    __syncthreads();
+    f32x16_t sc[2], dp[2];
+#pragma unroll
+    for (int qt = 0; qt < 2; qt++) {
+#pragma unroll
+      for (int v = 0; v < 16; v++) { sc[qt][v] = 0.f; dp[qt][v] = 0.f; }
+#pragma unroll
+      for (int t = 0; t < KS; t++) {
+        const int off = (32 * qt + c) * MF_PITCH + 16 * t + 8 * hh;
+        sc[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_from(*reinterpret_cast<const uint4*>(Qs + off)), kf[t], sc[qt], 0, 0, 0);
+        dp[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_from(*reinterpret_cast<const uint4*>(Gs + off)), vf[t], dp[qt], 0, 0, 0);
+      }
+#pragma unroll
+      for (int v = 0; v < 16; v++) {
+        const int r = 32 * qt + 8 * (v >> 2) + 4 * hh + (v & 3);
+        const int qi = i0 + r;
+        float p = __expf(sc[qt][v] * a.scale - Ls[r]);
+        if (qi >= a.Tq || (a.causal && kj > qi)) p = 0.f;
+        dp[qt][v] = p * (dp[qt][v] - Ds[r]);
+        sc[qt][v] = p;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; u++) {
+      const bf16x8_t pb = tile_to_operand(sc[u >> 1], u & 1), dsb = tile_to_operand(dp[u >> 1], u & 1);
+#pragma unroll
+      for (int dt = 0; dt < DT; dt++) {
+        dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(transposed_operand(Gt, 32 * dt + c, u, hh), pb, dv[dt], 0, 0, 0);
+        dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(transposed_operand(Qt, 32 * dt + c, u, hh), dsb, dk[dt], 0, 0, 0);
+      }
+    }
+  }
+  if (!live) return;
+  bf16_t* dkp = a.dk + ((int64_t)s * a.Tk + kj) * a.ldkv + h * DH + 4 * hh;
+  bf16_t* dvp = a.dv + ((int64_t)s * a.Tk + kj) * a.ldkv + h * DH + 4 * hh;
+#pragma unroll
+  for (int dt = 0; dt < DT; dt++)
+#pragma unroll
+    for (int g = 0; g < 4; g++) {
+      *reinterpret_cast<uint2*>(dkp + 32 * dt + 8 * g) =
+          make_uint2(pack_bf16_pair(dk[dt][4 * g] * a.scale, dk[dt][4 * g + 1] * a.scale),
+                     pack_bf16_pair(dk[dt][4 * g + 2] * a.scale, dk[dt][4 * g + 3] * a.scale));
+      *reinterpret_cast<uint2*>(dvp + 32 * dt + 8 * g) =
+          make_uint2(pack_bf16_pair(dv[dt][4 * g], dv[dt][4 * g + 1]), pack_bf16_pair(dv[dt][4 * g + 2], dv[dt][4 * g + 3]));
+    }
+}
+
 // ---- embedding ------------------------------------------------------------------------------------
 // y[s*T + t][:] = table[tok[s][col0 + t]][:] * sqrt(d) + PE[t][:], PE[t][2i] = sin(t / 10000^(2i/d)),
 // PE[t][2i+1] = cos(same).  One thread per pair of columns.
@@ -504,6 +707,11 @@ void attention_backward(const bf16_t* q, int64_t ldq, const bf16_t* k, const bf1
   a.scale = 1.f / sqrtf((float)dh);
   const unsigned gq = (unsigned)((int64_t)S * heads * cdiv(Tq, ATT_ROWS));
   const unsigned gk = (unsigned)((int64_t)S * heads * cdiv(Tk, ATT_ROWS));
+  if (use_mfma(dh, ldq, ldkv, ldo)) {
+    hipLaunchKernelGGL((attn_bwd_dq_mfma_k<64>), dim3(gq), dim3(256), 0, s, a);
+    hipLaunchKernelGGL((attn_bwd_dkv_mfma_k<64>), dim3(gk), dim3(256), 0, s, a);
+    return;
+  }
   CD_ATT_DISPATCH(attn_bwd_dq_k, gq);
   CD_ATT_DISPATCH(attn_bwd_dkv_k, gk);
 }
