@@ -5,7 +5,8 @@
 // causal mask.  q, k, v are column ranges of bf16 row-major tensors (the fused projections write
 // [rows][3d] or [rows][2d]); head h owns columns h*dh .. (h+1)*dh of each range.
 //
-// Plain fp32 arithmetic, no matrix cores: a pair of threads owns one query (forward, dq) or one key
+// Two sets of kernels.  Head dimension 64 runs on the matrix cores (second half of this file).  The others use
+// plain fp32 arithmetic: a pair of threads owns one query (forward, dq) or one key
 // (dk, dv), each thread one half of the head dimension; the dot products are completed with one
 // exchange inside the pair.  The other operand streams through LDS in chunks of 64 rows, every thread
 // reading the same address (a broadcast).  The forward pass keeps only the log-sum-exp of every row

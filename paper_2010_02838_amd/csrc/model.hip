@@ -927,10 +927,6 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
           ProfScope pr(CD_K_GLUE, c.s, 0, (double)g.M() * g.Cout * m->esize() * 3);
           relu_bwd_inplace(dt, dy, c.act(o.y), g.M() * g.Cout, c.s);
         }
-        if (o.pb >= 0) {
-          ProfScope pr(CD_K_GLUE, c.s, 0, (double)g.M() * g.Cout * m->esize());
-          colsum(dt, dy, g.M(), g.Cout, G(o.pb), c.partials(), c.s);
-        }
         const bool mf = use_mfma(m, g);
         {
           hipStream_t ws_ = c.s;
@@ -942,6 +938,10 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
               wpart = c.partials_side();
               forks++;
             }
+          }
+          if (o.pb >= 0) {  // the bias gradient reads dy only, like the weight gradient: same stream, same partials area
+            ProfScope pr(CD_K_GLUE, ws_, 0, (double)g.M() * g.Cout * m->esize());
+            colsum(dt, dy, g.M(), g.Cout, G(o.pb), wpart, ws_);
           }
           ProfScope pr(CD_K_CONV_WGRAD, ws_, 2.0 * g.M() * g.Cout * g.K(), conv_bytes(m, g) + 2.0 * g.Cout * g.K());
           if (mf) {

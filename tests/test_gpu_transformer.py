@@ -14,7 +14,9 @@ CASES = {
     # S, Ts, Tt, d, heads, d_ff, vocab, encoder layers, decoder layers
     "small": (3, 10, 7, 32, 4, 64, 64, 2, 2),                 # head dimension 8
     "ragged_vocab": (2, 5, 9, 32, 2, 40, 50, 1, 2),           # head dimension 16, vocabulary not a multiple of 8
-    "long": (2, 150, 131, 128, 2, 128, 96, 1, 1),             # head dimension 64; several query tiles and key chunks
+    "long": (2, 150, 131, 128, 2, 128, 96, 1, 1),             # head dimension 64 (the matrix-core kernels); several
+                                                              # query tiles and key chunks, ragged last ones
+    "mid": (2, 70, 33, 64, 2, 96, 80, 1, 1),                  # head dimension 32 (the plain kernels' largest here)
 }
 
 
