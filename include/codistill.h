@@ -8,7 +8,7 @@
  *     z' = f_theta'(x)     codistill_forward(stale peer copy, save_for_backward = 0)
  *     l  = L(y,z) + alpha * mean_j D(z, z'_j),  dz = dl/dz      codistill_loss_grad
  *     g  = dl/dtheta       codistill_backward (local model only)
- *     theta <- momentum-SGD(theta, g)                           codistill_sgd_step
+ *     theta <- momentum-SGD(theta, g)                           codistill_sgd_step (or codistill_adam_step)
  *
  * Conventions
  *   - Every function returns CD_OK (0) or a negative CD_ERR_* code and never
@@ -219,6 +219,21 @@ int codistill_backward(const cd_model* m, const void* params, const void* x, int
 int codistill_sgd_step(float* master_w, float* momentum_v, const float* grad, void* lowp_w_out,
                        int64_t n, float lr, float momentum, float weight_decay, int nesterov,
                        void* stream);
+
+/*
+ * Adam update, in place: the optimiser of the translation recipe that Section 4 follows (Ott et al.: beta1 0.9,
+ * beta2 0.98, eps 1e-8); Kingma & Ba's algorithm with the coupled L2 term of codistill_sgd_step:
+ *     g = grad + weight_decay * w;  m = beta1 m + (1 - beta1) g;  v = beta2 v + (1 - beta2) g^2;
+ *     w = w - lr * (m / (1 - beta1^t)) / (sqrt(v / (1 - beta2^t)) + eps)
+ *   master_w, exp_avg (m), exp_avg_sq (v)  [n] device fp32, updated in place (m and v start at zero)
+ *   grad  [n] device fp32, read only;  lowp_w_out  [n] device bf16 copy of the updated weights, or NULL
+ *   t     number of this update, counted from 1 (host value; the bias corrections are computed on the host)
+ * Errors (CD_ERR_INVALID_ARG, nothing launched): NULL or misaligned pointers, n < 1, t < 1, beta outside [0, 1),
+ * eps <= 0, NaN lr or weight_decay.
+ */
+int codistill_adam_step(float* master_w, float* exp_avg, float* exp_avg_sq, const float* grad, void* lowp_w_out,
+                        int64_t n, float lr, float beta1, float beta2, float eps, float weight_decay, int64_t t,
+                        void* stream);
 
 /* ---- introspection ----------------------------------------------------------------------- */
 /* The fused op list and where each tensor lives inside a save_for_backward workspace, so that

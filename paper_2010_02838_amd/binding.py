@@ -77,6 +77,7 @@ _SIGS = {
     "codistill_loss_grad": [_vp, ctypes.POINTER(_vp), _vp, _i64, _i64, ctypes.POINTER(LossCfg), _vp, _vp, _vp, _sz, _vp],
     "codistill_backward": [_vp, _vp, _vp, _i64, _vp, _sz, _vp, _vp, _vp],
     "codistill_sgd_step": [_vp, _vp, _vp, _vp, _i64, _f32, _f32, _f32, _i32, _vp],
+    "codistill_adam_step": [_vp, _vp, _vp, _vp, _vp, _i64, _f32, _f32, _f32, _f32, _f32, _i64, _vp],
     "codistill_profile_enable": [_i32],
     "codistill_profile_collect": [],
     "codistill_profile_get": [_i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_i64),
@@ -215,6 +216,12 @@ def codistill_backward(model, params, x, workspace, dlogits, grads_out):
 def codistill_sgd_step(master_w, momentum_v, grad, lowp_w_out, lr, momentum, weight_decay=0.0, nesterov=False):
     _check(lib.codistill_sgd_step(_ptr(master_w), _ptr(momentum_v), _ptr(grad), _ptr(lowp_w_out), master_w.numel(),
                                   lr, momentum, weight_decay, int(nesterov), _stream()))
+
+
+def codistill_adam_step(master_w, exp_avg, exp_avg_sq, grad, lowp_w_out, lr, t, beta1=0.9, beta2=0.98, eps=1e-8,
+                        weight_decay=0.0):
+    _check(lib.codistill_adam_step(_ptr(master_w), _ptr(exp_avg), _ptr(exp_avg_sq), _ptr(grad), _ptr(lowp_w_out),
+                                   master_w.numel(), lr, beta1, beta2, eps, weight_decay, int(t), _stream()))
 
 
 def profile_enable(on):

@@ -50,6 +50,8 @@ class StepRunner:
         f32 = dict(dtype=torch.float32, device=device)
         self.master = torch.zeros(n, **f32)
         self.momentum = torch.zeros(n, **f32)
+        self.second_moment = None   # Adam's second buffer, allocated on the first step_adam
+        self.updates = 0            # Adam's update counter
         self.grads = torch.empty(n, **f32)
         self.lowp = torch.zeros(n, dtype=torch.bfloat16, device=device) if model.dtype == B.CD_BF16 else None
         self.ws = torch.empty(model.workspace_bytes(batch, True), dtype=torch.uint8, device=device)
@@ -79,9 +81,10 @@ class StepRunner:
             self.momentum.copy_(torch.from_numpy(np.ascontiguousarray(v, dtype=np.float32)))
 
     def step(self, x, y, alpha, lr, momentum, weight_decay=0.0, label_smoothing=0.0,
-             dist_kind=B.CD_DIST_MSE_LOGITS, mse_reduction=B.CD_MEAN_ALL, ignore_index=-1, nesterov=False):
+             dist_kind=B.CD_DIST_MSE_LOGITS, mse_reduction=B.CD_MEAN_ALL, ignore_index=-1, nesterov=False, adam=None):
         """x: [B,H,W,3] device tensor in the model dtype (the Transformer: int32 [B, source + target tokens]);
-        y: int32 device tensor, one target per row of logits."""
+        y: int32 device tensor, one target per row of logits.  adam = (beta1, beta2, eps) replaces the momentum-SGD
+        update by Adam (momentum and nesterov are then unused)."""
         if self.overlap_peers and self.peers:
             main = torch.cuda.current_stream()
             self.side.wait_stream(main)           # x, the peer parameters and the last step's reads are in order
@@ -97,4 +100,11 @@ class StepRunner:
         B.codistill_loss_grad(self.logits, self.peer_logits, y, self.loss, self.dz, self.scratch, alpha,
                               label_smoothing, dist_kind, mse_reduction, ignore_index)
         B.codistill_backward(self.model, self.params(), x, self.ws, self.dz, self.grads)
-        B.codistill_sgd_step(self.master, self.momentum, self.grads, self.lowp, lr, momentum, weight_decay, nesterov)
+        if adam is None:
+            B.codistill_sgd_step(self.master, self.momentum, self.grads, self.lowp, lr, momentum, weight_decay, nesterov)
+        else:   # the momentum buffer holds Adam's first moment
+            if self.second_moment is None:
+                self.second_moment = torch.zeros_like(self.momentum)
+            self.updates += 1
+            B.codistill_adam_step(self.master, self.momentum, self.second_moment, self.grads, self.lowp, lr, self.updates,
+                                  adam[0], adam[1], adam[2], weight_decay)

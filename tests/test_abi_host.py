@@ -128,6 +128,25 @@ def test_sgd_rejects_bad_arguments_before_launch():
     assert s(fake, fake, fake, None, 8, float("nan"), 0.9, 0.0, 0, None) == B.CD_ERR_INVALID_ARG
 
 
+def test_adam_rejects_bad_arguments_before_launch():
+    fake = ctypes.c_void_p(0x1000)
+    a = B.lib.codistill_adam_step
+    ok = dict(lr=1e-3, b1=0.9, b2=0.98, eps=1e-8, wd=0.0, t=1)
+
+    def call(w=fake, m=fake, v=fake, g=fake, n=8, **kw):
+        k = dict(ok, **kw)
+        return a(w, m, v, g, None, n, k["lr"], k["b1"], k["b2"], k["eps"], k["wd"], k["t"], None)
+
+    assert call(w=None) == B.CD_ERR_INVALID_ARG
+    assert call(n=0) == B.CD_ERR_INVALID_ARG
+    assert call(t=0) == B.CD_ERR_INVALID_ARG
+    assert call(b1=1.0) == B.CD_ERR_INVALID_ARG
+    assert call(eps=0.0) == B.CD_ERR_INVALID_ARG
+    assert call(lr=float("nan")) == B.CD_ERR_INVALID_ARG
+    assert call(v=ctypes.c_void_p(0x1004)) == B.CD_ERR_INVALID_ARG
+    assert b"adam_step" in B.lib.codistill_last_error()
+
+
 def test_profile_interface_on_host():
     assert B.lib.codistill_profile_reset() == 0
     ms = ctypes.c_double(1.0)
