@@ -189,25 +189,36 @@ def sinusoid_positions(T, d):
 
 
 def embed_forward(tokens, table):
-    """tokens [S, T] integer ids -> [S*T, d]: table row times sqrt(d), plus the position signal."""
+    """tokens [S, T] integer ids -> [S*T, d]: table row times sqrt(d), plus the position signal.  A negative id
+    is padding: it embeds as a zero row (the position signal is still added; nothing reads that row)."""
     S, T = tokens.shape
     d = table.shape[1]
-    x = table[tokens.astype(np.int64)] * np.sqrt(d) + sinusoid_positions(T, d)[None, :, :]
+    ids = tokens.astype(np.int64)
+    rows = np.where((ids >= 0)[:, :, None], table[np.maximum(ids, 0)], 0.0)
+    x = rows * np.sqrt(d) + sinusoid_positions(T, d)[None, :, :]
     return x.reshape(S * T, d)
 
 
 def embed_backward(tokens, table_shape, dy):
-    """Gradient of the table: every occurrence of a token adds sqrt(d) times its row of dy."""
+    """Gradient of the table: every occurrence of a token adds sqrt(d) times its row of dy (padding adds nothing)."""
     d = table_shape[1]
     dw = np.zeros(table_shape)
-    np.add.at(dw, tokens.astype(np.int64).reshape(-1), dy.reshape(-1, d) * np.sqrt(d))
+    ids = tokens.astype(np.int64).reshape(-1)
+    keep = ids >= 0
+    np.add.at(dw, ids[keep], dy.reshape(-1, d)[keep] * np.sqrt(d))
     return dw
 
 
-def attention_forward(q, k, v, S, heads, causal):
+def sentence_lengths(tokens):
+    """Tokens of each sentence that are not padding (negative ids; padding follows the tokens), at least 1."""
+    return np.maximum((np.asarray(tokens) >= 0).sum(axis=1), 1)
+
+
+def attention_forward(q, k, v, S, heads, causal, klen=None):
     """Scaled dot-product attention with several heads.  q [S*Tq, d], k, v [S*Tk, d] (sentence-major rows);
     head h owns columns h*dh .. (h+1)*dh.  P = softmax(Q K^T / sqrt(dh)) over the keys of the same sentence
-    (causal: keys at positions <= the query's only), output P V, heads side by side.  Returns (out, P)."""
+    (causal: keys at positions <= the query's only; klen [S]: only the first klen[s] keys of sentence s, the rest
+    is padding), output P V, heads side by side.  Returns (out, P)."""
     d = q.shape[1]
     dh = d // heads
     Tq, Tk = q.shape[0] // S, k.shape[0] // S
@@ -217,6 +228,8 @@ def attention_forward(q, k, v, S, heads, causal):
     s = np.einsum("shid,shjd->shij", Q, K) / np.sqrt(dh)
     if causal:
         s = np.where(np.arange(Tk)[None, :] <= np.arange(Tq)[:, None], s, -np.inf)
+    if klen is not None:
+        s = np.where(np.arange(Tk)[None, None, None, :] < np.asarray(klen).reshape(S, 1, 1, 1), s, -np.inf)
     s = s - s.max(axis=-1, keepdims=True)
     e = np.exp(s)
     P = e / e.sum(axis=-1, keepdims=True)

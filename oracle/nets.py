@@ -125,11 +125,13 @@ class Arch:
         self.ops.append(dict(op="embed", x=0, y=y, w=w, col0=col0, T=T, stored=True))
         return y, w
 
-    def attention(self, q, q_col, kv, k_col, v_col, d, heads, S, causal):
-        """q, k, v are column ranges of width d of tensors q and kv (which may be the same tensor)."""
+    def attention(self, q, q_col, kv, k_col, v_col, d, heads, S, causal, key_tokens):
+        """q, k, v are column ranges of width d of tensors q and kv (which may be the same tensor).  key_tokens =
+        (first column, count): the columns of the token input whose sentences the keys come from; their lengths
+        (padding excluded) limit the keys each sentence attends to."""
         y = self._t()
         self.ops.append(dict(op="attn", x=q, kv=kv, y=y, q_col=q_col, k_col=k_col, v_col=v_col, d=d, heads=heads,
-                             S=S, causal=causal, stored=True))
+                             S=S, causal=causal, key_tokens=key_tokens, stored=True))
         return y
 
     def tied_linear(self, x, w):
@@ -231,7 +233,7 @@ def transformer(S, Ts, Tt, d=512, heads=8, d_ff=2048, vocab=32768, enc_layers=6,
 
     def self_attention(x, p, causal):
         qkv = dense(x, p + ".qkv", d, 3 * d)
-        o = a.attention(qkv, 0, qkv, d, 2 * d, d, heads, S, causal)
+        o = a.attention(qkv, 0, qkv, d, 2 * d, d, heads, S, causal, (Ts, Tt) if causal else (0, Ts))
         return add_norm(x, dense(o, p + ".out", d, d), p + ".ln")
 
     x, table = a.embed("embed", vocab, d, 0, Ts)
@@ -244,7 +246,7 @@ def transformer(S, Ts, Tt, d=512, heads=8, d_ff=2048, vocab=32768, enc_layers=6,
         y = self_attention(y, p + ".self", True)
         q = dense(y, p + ".cross.q", d, d)
         kv = dense(memory, p + ".cross.kv", d, 2 * d)
-        o = a.attention(q, 0, kv, 0, d, d, heads, S, False)
+        o = a.attention(q, 0, kv, 0, d, d, heads, S, False, (0, Ts))
         y = add_norm(y, dense(o, p + ".cross.out", d, d), p + ".cross.ln")
         y = ffn(y, p)
     a.tied_linear(y, table)
@@ -283,7 +285,8 @@ def forward(arch, params, x, store=None):
             q2 = T[o["x"]].reshape(T[o["x"]].shape[0], -1)
             kv2 = T[o["kv"]].reshape(T[o["kv"]].shape[0], -1)
             q, kk, v = q2[:, o["q_col"]:o["q_col"] + d], kv2[:, o["k_col"]:o["k_col"] + d], kv2[:, o["v_col"]:o["v_col"] + d]
-            out, P = L.attention_forward(q, kk, v, o["S"], o["heads"], o["causal"])
+            c0, n = o["key_tokens"]
+            out, P = L.attention_forward(q, kk, v, o["S"], o["heads"], o["causal"], L.sentence_lengths(T[0][:, c0:c0 + n]))
             T[o["y"]], cache[i] = out.reshape(-1, 1, 1, d), P
         elif k == "linear":
             xin = T[o["x"]]

@@ -196,3 +196,66 @@ def test_codistillation_step_by_finite_differences():
     # an identical peer adds nothing
     same = codistill_step(arch, theta, [theta], tok, y, **kw)
     assert abs(same["loss"][2]) < 1e-14
+
+
+def test_attention_key_lengths_match_truncation_and_torch_mask():
+    S, T, H, dh = 3, 6, 2, 4
+    d = H * dh
+    q, k, v = rnd((S * T, d), 20), rnd((S * T, d), 21), rnd((S * T, d), 22)
+    klen = np.array([6, 2, 4])
+    out, P = L.attention_forward(q, k, v, S, H, False, klen)
+    for s in range(S):
+        n = klen[s]
+        assert np.all(P[s, :, :, n:] == 0)
+        # the same sentence alone, cut to its length (all T queries kept)
+        o1, _ = L.attention_forward(q[s * T:(s + 1) * T], k[s * T:s * T + n], v[s * T:s * T + n], 1, H, False)
+        np.testing.assert_allclose(out[s * T:(s + 1) * T], o1, atol=1e-14)
+    mask = torch.tensor(np.arange(T)[None, :] < klen[:, None])[:, None, None, :]
+    tq, tk, tv = (torch.tensor(a.reshape(S, T, H, dh).transpose(0, 2, 1, 3).copy(), requires_grad=True) for a in (q, k, v))
+    to = F.scaled_dot_product_attention(tq, tk, tv, attn_mask=mask)
+    np.testing.assert_allclose(out.reshape(S, T, H, dh).transpose(0, 2, 1, 3), to.detach().numpy(), atol=1e-12)
+    dout = rnd((S * T, d), 23)
+    to.backward(torch.tensor(dout.reshape(S, T, H, dh).transpose(0, 2, 1, 3).copy()))
+    dq, dk, dv = L.attention_backward(q, k, v, P, dout, S, H)
+    for got, t in ((dq, tq), (dk, tk), (dv, tv)):
+        np.testing.assert_allclose(got.reshape(S, T, H, dh).transpose(0, 2, 1, 3), t.grad.numpy(), atol=1e-12)
+    assert np.all(dk.reshape(S, T, d)[1, 2:] == 0) and np.all(dv.reshape(S, T, d)[1, 2:] == 0)   # padded keys: no gradient
+
+
+def test_padded_batch_equals_its_sentences_run_alone():
+    """Sentences of different lengths padded into one batch (negative ids): the logits of every real target position,
+    and the parameter gradients when the padded positions carry no loss gradient, are those of the sentences run one
+    at a time at their own lengths."""
+    S, Ts, Tt, d, heads, vocab = 3, 6, 5, 16, 4, 11
+    kw = dict(d=d, heads=heads, d_ff=24, vocab=vocab, enc_layers=2, dec_layers=2)
+    arch = nets.transformer(S, Ts, Tt, **kw)
+    rng = np.random.default_rng(3)
+    theta = np.concatenate([rng.standard_normal(int(np.prod(s))) * 0.3 for _, s, _, _ in arch.params])
+    P = unflatten(arch, theta)
+    slen, tlen = [6, 3, 1], [2, 5, 4]
+    tok = rng.integers(0, vocab, (S, Ts + Tt))
+    for s in range(S):
+        tok[s, slen[s]:Ts] = -1
+        tok[s, Ts + tlen[s]:] = -1
+    z, tape = nets.forward(arch, P, tok)
+    z3 = z.reshape(S, Tt, vocab)
+    dz = rnd(z.shape, 6).reshape(S, Tt, vocab)
+    for s in range(S):
+        dz[s, tlen[s]:] = 0.0
+    grads = nets.backward(arch, P, tape, dz.reshape(z.shape))
+    total = {n: np.zeros_like(v) for n, v in P.items()}
+    for s in range(S):
+        one = nets.transformer(1, slen[s], tlen[s], **kw)
+        t1 = np.concatenate([tok[s, :slen[s]], tok[s, Ts:Ts + tlen[s]]])[None, :]
+        z1, tape1 = nets.forward(one, P, t1)
+        np.testing.assert_allclose(z3[s, :tlen[s]], z1, atol=1e-11)
+        g1 = nets.backward(one, P, tape1, dz[s, :tlen[s]])
+        for n in total:
+            total[n] += g1[n]
+    for n in total:
+        np.testing.assert_allclose(grads[n], total[n], atol=1e-10, err_msg=n)
+    # padding changes nothing for the others: another sentence's padding length is invisible to sentence 0
+    tok2 = tok.copy()
+    tok2[1, 2] = -1
+    z2, _ = nets.forward(arch, P, tok2)
+    np.testing.assert_array_equal(z3[0], z2.reshape(S, Tt, vocab)[0])
