@@ -86,7 +86,10 @@ enum {
  * channels (in_h = in_w = 1), widths[1] = d_ff, classes = vocabulary size.  CD_ARCH_TRANSFORMER: in_h = source
  * tokens and in_w = target tokens per sentence, widths[0] = d_model, widths[1] = d_ff, widths[2] = heads,
  * blocks[0] = encoder layers, blocks[1] = decoder layers, classes = vocabulary size; its input x is
- * int32 [batch][in_h + in_w] token ids (batch = sentences) and it produces batch * in_w rows of logits. */
+ * int32 [batch][in_h + in_w] token ids (batch = sentences) and it produces batch * in_w rows of logits.  Shorter
+ * sentences are padded at the end of their source / target part with negative ids: padding embeds as a zero row,
+ * is masked as a key in every attention and takes no gradient; give its rows of the targets ignore_index.  Every
+ * part needs at least one real token. */
 typedef struct {
   int32_t kind;                   /* CD_ARCH_*                                             */
   int32_t classes;                /* width of the logits                                   */
@@ -265,6 +268,8 @@ typedef struct {
   int32_t fused_pool;      /* CD_OP_BN: 1 if the max-pool op that follows is computed by this op's kernel; this op's
                               output tensor is then never written (its workspace slot stays unused), its ReLU bit
                               mask and the pool's argmax are.                                             */
+  int32_t key_tok0;        /* CD_OP_ATTN: first column of the token input whose sentences the keys come from; the
+                              keys at and after a sentence's first negative id (padding) are masked        */
 } cd_op_info;
 typedef struct {
   int32_t h, w, c;         /* per-sample shape; the tensor is [batch][h][w][c]                  */

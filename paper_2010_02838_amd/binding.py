@@ -44,7 +44,7 @@ class OpInfo(ctypes.Structure):
                 ("relu", ctypes.c_int32), ("param_w", ctypes.c_int32), ("param_b", ctypes.c_int32),
                 ("k", ctypes.c_int32), ("stride", ctypes.c_int32), ("pad", ctypes.c_int32),
                 ("stats_offset", ctypes.c_int64), ("res_grad", ctypes.c_int32), ("k_col", ctypes.c_int32), ("v_col", ctypes.c_int32),
-                ("fused_pool", ctypes.c_int32)]
+                ("fused_pool", ctypes.c_int32), ("key_tok0", ctypes.c_int32)]
 
 
 class ActInfo(ctypes.Structure):

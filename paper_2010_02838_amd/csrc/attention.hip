@@ -63,7 +63,22 @@ struct AttArgs {
   bf16_t* dq; bf16_t* dk; bf16_t* dv;                 // backward outputs, pitches ldq / ldkv
   int S, heads, Tq, Tk, causal;
   float scale;                                        // 1 / sqrt(dh)
+  // Padding (nullable): token ids [S][tok_pitch]; the keys of sentence s come from columns ktok0 .. ktok0 + Tk,
+  // and only those before the first negative id are real.
+  const int32_t* ktok; int64_t tok_pitch; int ktok0;
 };
+
+// Number of real keys of sentence s (at least 1), the same value in every thread of the workgroup.
+// Contains barriers: every thread of the workgroup calls it.
+__device__ inline int key_count(const AttArgs& a, int s) {
+  if (!a.ktok) return a.Tk;
+  int n = 0;
+  for (int j0 = 0; j0 < a.Tk; j0 += 256) {
+    const int j = j0 + (int)threadIdx.x;
+    n += __syncthreads_count(j < a.Tk && a.ktok[(int64_t)s * a.tok_pitch + a.ktok0 + j] >= 0);
+  }
+  return max(n, 1);
+}
 
 // blockIdx.x = (sentence * heads + head) * tiles + tile of ATT_ROWS queries
 template <int DH>
@@ -84,9 +99,10 @@ __global__ void __launch_bounds__(256) attn_fwd_k(AttArgs a) {
     for (int c = 0; c < HALF; c++) q[c] = bf16_to_f32(qp[c]) * a.scale;
   }
   float m = -INFINITY, l = 0.f;
-  const int last = a.causal ? min(a.Tk, tile * ATT_ROWS + ATT_ROWS) : a.Tk;   // keys any query of the tile sees
+  const int nk = key_count(a, s);
+  const int last = a.causal ? min(nk, tile * ATT_ROWS + ATT_ROWS) : nk;   // keys any query of the tile sees
   for (int j0 = 0; j0 < last; j0 += ATT_KC) {
-    const int n = min(ATT_KC, a.Tk - j0);
+    const int n = min(ATT_KC, nk - j0);
     __syncthreads();
     stage_chunk<DH>(a.k + ((int64_t)s * a.Tk + j0) * a.ldkv + h * DH, a.ldkv, n, Ks);
     stage_chunk<DH>(a.v + ((int64_t)s * a.Tk + j0) * a.ldkv + h * DH, a.ldkv, n, Vs);
@@ -141,7 +157,8 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_k(AttArgs a) {
     for (int c = 0; c < HALF; c++) { q[c] = bf16_to_f32(qp[c]) * a.scale; go[c] = bf16_to_f32(gp[c]); }
     lse = a.lse[((int64_t)s * a.heads + h) * a.Tq + i];
   }
-  const int last = a.causal ? min(a.Tk, tile * ATT_ROWS + ATT_ROWS) : a.Tk;
+  const int nk = key_count(a, s);
+  const int last = a.causal ? min(nk, tile * ATT_ROWS + ATT_ROWS) : nk;
   // Where the weights are nearly uniform dq is a small difference of large terms (10^4 times smaller at the base
   // model's initialisation), so relative errors of 1e-7 in the recomputed probabilities matter.  Two measures:
   // the weights are recomputed as w_j = exp(s_j - (lse - log n)), n the number of visible keys, whose exponent is
@@ -150,13 +167,13 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_k(AttArgs a) {
   // Third, dp is taken relative to the first key's (dp_j - dp_0; dp - D does not change): when the values are
   // nearly alike D then is as small as the differences, and its rounding error, which every term shares and
   // which multiplies the keys' common part, shrinks with it.
-  const int visible = a.causal ? min(i + 1, a.Tk) : a.Tk;
+  const int visible = a.causal ? min(i + 1, nk) : nk;
   const float ref = lse - __logf((float)max(visible, 1));
   float D = 0.f, Z = 0.f, dp0 = 0.f;
   for (int pass = 0; pass < 2; pass++) {
     if (pass == 1 && Z > 0.f) D /= Z;
     for (int j0 = 0; j0 < last; j0 += ATT_KC) {
-      const int n = min(ATT_KC, a.Tk - j0);
+      const int n = min(ATT_KC, nk - j0);
       __syncthreads();
       stage_chunk<DH>(a.k + ((int64_t)s * a.Tk + j0) * a.ldkv + h * DH, a.ldkv, n, Ks);
       stage_chunk<DH>(a.v + ((int64_t)s * a.Tk + j0) * a.ldkv + h * DH, a.ldkv, n, Vs);
@@ -213,6 +230,7 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_k(AttArgs a) {
 #pragma unroll
     for (int c = 0; c < HALF; c++) { k[c] = bf16_to_f32(kp[c]); v[c] = bf16_to_f32(vp[c]); }
   }
+  const bool real = j < key_count(a, s);   // a padded key gets no weight from any query: its dk, dv stay zero
   const int first = a.causal ? tile * ATT_ROWS / ATT_KC * ATT_KC : 0;   // queries before the tile's first key see none of it
   for (int i0 = first; i0 < a.Tq; i0 += ATT_KC) {
     const int n = min(ATT_KC, a.Tq - i0);
@@ -233,7 +251,7 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_k(AttArgs a) {
         pd += v[c] * Gs[i * DH + hf * HALF + c];
       }
       const float sc = pair_sum(ps) * a.scale, dp = pair_sum(pd);
-      if (!live || (a.causal && j > i0 + i)) continue;
+      if (!real || (a.causal && j > i0 + i)) continue;
       const float p = __expf(sc - Ls[i]);
       const float ds = p * (dp - Ds[i]);
 #pragma unroll
@@ -357,9 +375,10 @@ __global__ void __launch_bounds__(256) attn_fwd_mfma_k(AttArgs a) {
 #pragma unroll
     for (int v = 0; v < 16; v++) o[dt][v] = 0.f;
   float m = -INFINITY, lsum = 0.f;
-  const int last = a.causal ? min(a.Tk, tile * ATT_ROWS + ATT_ROWS) : a.Tk;
+  const int nk = key_count(a, s);
+  const int last = a.causal ? min(nk, tile * ATT_ROWS + ATT_ROWS) : nk;
   for (int j0 = 0; j0 < last; j0 += MF_KC) {
-    const int n = min(MF_KC, a.Tk - j0);
+    const int n = min(MF_KC, nk - j0);
     __syncthreads();
     stage_rows<DH>(a.k + ((int64_t)s * a.Tk + j0) * a.ldkv + h * DH, a.ldkv, n, Ks);
     stage_transposed<DH, false>(a.v + ((int64_t)s * a.Tk + j0) * a.ldkv + h * DH, a.ldkv, n, Vt, nullptr);
@@ -379,7 +398,7 @@ __global__ void __launch_bounds__(256) attn_fwd_mfma_k(AttArgs a) {
       for (int v = 0; v < 16; v++) {
         const int kj = j0 + 32 * kt + 8 * (v >> 2) + 4 * hh + (v & 3);
         float x = sc[kt][v] * a.scale;
-        if (kj >= a.Tk || (a.causal && kj > qi)) x = -INFINITY;
+        if (kj >= nk || (a.causal && kj > qi)) x = -INFINITY;
         sc[kt][v] = x;
         mx = fmaxf(mx, x);
       }
@@ -453,7 +472,8 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_mfma_k(AttArgs a) {
     gf[t] = frag_from(g);
   }
   const float lse = live ? a.lse[((int64_t)s * a.heads + h) * a.Tq + qi] : 0.f;
-  const int visible = a.causal ? min(qi + 1, a.Tk) : a.Tk;
+  const int nk = key_count(a, s);
+  const int visible = a.causal ? min(qi + 1, nk) : nk;
   const float ref = lse - __logf((float)max(visible, 1));
   if ((int)threadIdx.x < DH) K0[threadIdx.x] = bf16_to_f32(a.k[(int64_t)s * a.Tk * a.ldkv + h * DH + threadIdx.x]);
   f32x16_t dq[DT];
@@ -461,7 +481,7 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_mfma_k(AttArgs a) {
   for (int dt = 0; dt < DT; dt++)
 #pragma unroll
     for (int v = 0; v < 16; v++) dq[dt][v] = 0.f;
-  const int last = a.causal ? min(a.Tk, tile * ATT_ROWS + ATT_ROWS) : a.Tk;
+  const int last = a.causal ? min(nk, tile * ATT_ROWS + ATT_ROWS) : nk;
   float D = 0.f, Z = 0.f, dp0 = 0.f;
   for (int pass = 0; pass < 2; pass++) {
     if (pass == 1) {
@@ -470,7 +490,7 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_mfma_k(AttArgs a) {
       D = Z > 0.f ? D / Z : 0.f;
     }
     for (int j0 = 0; j0 < last; j0 += MF_KC) {
-      const int n = min(MF_KC, a.Tk - j0);
+      const int n = min(MF_KC, nk - j0);
       const bf16_t* kb = a.k + ((int64_t)s * a.Tk + j0) * a.ldkv + h * DH;
       __syncthreads();
       stage_rows<DH>(kb, a.ldkv, n, Ks);
@@ -496,7 +516,7 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_mfma_k(AttArgs a) {
         for (int v = 0; v < 16; v++) {
           const int kj = j0 + 32 * kt + 8 * (v >> 2) + 4 * hh + (v & 3);
           float w = __expf(sc[kt][v] * a.scale - ref);
-          if (kj >= a.Tk || (a.causal && kj > qi)) w = 0.f;
+          if (kj >= nk || (a.causal && kj > qi)) w = 0.f;
           const float d = dp[kt][v] - dp0;
           if (pass == 0) {
             Z += w;
@@ -563,6 +583,7 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_mfma_k(AttArgs a) {
   for (int dt = 0; dt < DT; dt++)
 #pragma unroll
     for (int v = 0; v < 16; v++) { dk[dt][v] = 0.f; dv[dt][v] = 0.f; }
+  const bool real = kj < key_count(a, s);   // a padded key gets no weight from any query: its dk, dv stay zero
   const int first = a.causal ? tile * ATT_ROWS / MF_KC * MF_KC : 0;   // earlier queries see none of the tile's keys
   for (int i0 = first; i0 < a.Tq; i0 += MF_KC) {
     const int n = min(MF_KC, a.Tq - i0);
@@ -595,7 +616,7 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_mfma_k(AttArgs a) {
         const int r = 32 * qt + 8 * (v >> 2) + 4 * hh + (v & 3);
         const int qi = i0 + r;
         float p = __expf(sc[qt][v] * a.scale - Ls[r]);
-        if (qi >= a.Tq || (a.causal && kj > qi)) p = 0.f;
+        if (qi >= a.Tq || !real || (a.causal && kj > qi)) p = 0.f;
         dp[qt][v] = p * (dp[qt][v] - Ds[r]);
         sc[qt][v] = p;
       }
@@ -640,9 +661,10 @@ __global__ void __launch_bounds__(256) embed_fwd_k(const int32_t* __restrict__ t
   const int t = (int)(row % T_);
   const int64_t s = row / T_;
   int id = tok[s * tok_pitch + col0 + t];
+  const float keep = id < 0 ? 0.f : 1.f;      // a negative id is padding: a zero row (plus the position signal)
   id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);   // ids are validated by the caller; clamp keeps the access in bounds
   const float ang = (float)t * __expf(-(float)(2 * i) / (float)d * 9.210340371976184f);   // ln 10000
-  const float scale = sqrtf((float)d);
+  const float scale = keep * sqrtf((float)d);
   const T* tr = table + (int64_t)id * d + 2 * i;
   y[row * d + 2 * i] = Cvt<T>::st(Cvt<T>::ld(tr[0]) * scale + sinf(ang));
   y[row * d + 2 * i + 1] = Cvt<T>::st(Cvt<T>::ld(tr[1]) * scale + cosf(ang));
@@ -661,7 +683,8 @@ __global__ void __launch_bounds__(256) embed_bwd_k(const int32_t* __restrict__ t
   const int t = (int)(row % T_);
   const int64_t s = row / T_;
   int id = tok[s * tok_pitch + col0 + t];
-  id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);
+  if (id < 0) return;   // padding
+  id = id >= vocab ? vocab - 1 : id;
   atomicAdd(dtable + (int64_t)id * d + c, Cvt<T>::ld(dy[idx]) * sqrtf((float)d));
 }
 
@@ -685,8 +708,10 @@ bool attention_supported(int dh) { return dh == 8 || dh == 16 || dh == 32 || dh 
   }
 
 void attention_forward(const bf16_t* q, int64_t ldq, const bf16_t* k, const bf16_t* v, int64_t ldkv, bf16_t* out, int64_t ldo,
-                       float* lse, int S, int heads, int Tq, int Tk, int dh, bool causal, hipStream_t s) {
+                       float* lse, int S, int heads, int Tq, int Tk, int dh, bool causal, const int32_t* key_tokens,
+                       int64_t tok_pitch, int key_col0, hipStream_t s) {
   AttArgs a = {};
+  a.ktok = key_tokens; a.tok_pitch = tok_pitch; a.ktok0 = key_col0;
   a.q = q; a.k = k; a.v = v; a.ldq = ldq; a.ldkv = ldkv; a.out = out; a.ldo = ldo; a.lse = lse;
   a.S = S; a.heads = heads; a.Tq = Tq; a.Tk = Tk; a.causal = causal ? 1 : 0;
   a.scale = 1.f / sqrtf((float)dh);
@@ -700,8 +725,10 @@ void attention_forward(const bf16_t* q, int64_t ldq, const bf16_t* k, const bf16
 
 void attention_backward(const bf16_t* q, int64_t ldq, const bf16_t* k, const bf16_t* v, int64_t ldkv, const bf16_t* dout,
                         int64_t ldo, const float* lse, float* dsum, bf16_t* dq, bf16_t* dk, bf16_t* dv, int S, int heads,
-                        int Tq, int Tk, int dh, bool causal, hipStream_t s) {
+                        int Tq, int Tk, int dh, bool causal, const int32_t* key_tokens, int64_t tok_pitch, int key_col0,
+                        hipStream_t s) {
   AttArgs a = {};
+  a.ktok = key_tokens; a.tok_pitch = tok_pitch; a.ktok0 = key_col0;
   a.q = q; a.k = k; a.v = v; a.ldq = ldq; a.ldkv = ldkv; a.dout = dout; a.ldo = ldo;
   a.lse = const_cast<float*>(lse); a.dsum = dsum; a.dq = dq; a.dk = dk; a.dv = dv;
   a.S = S; a.heads = heads; a.Tq = Tq; a.Tk = Tk; a.causal = causal ? 1 : 0;

@@ -130,15 +130,20 @@ void transpose_weight(const bf16_t* w, bf16_t* wt, int cout, int taps, int cin, 
 // q [S*Tq][.] and k, v [S*Tk][.] are bf16 row-major with row pitches ldq / ldkv (elements), already
 // pointing at their first column; head h owns columns h*dh .. (h+1)*dh.  out [S*Tq][.] with pitch ldo.
 // lse (nullable in a forward pass that keeps nothing): [S][heads][Tq] fp32 log-sum-exp of the scaled
-// scores.  dh in {8, 16, 32, 64} (attention_supported).
+// scores.  dh in {8, 16, 32, 64} (attention_supported).  key_tokens (nullable): int32 token ids [S][tok_pitch]; the keys
+// of sentence s belong to columns key_col0 .. key_col0 + Tk, and only those before the first negative id (padding)
+// take part; padded keys get zero dk, dv.
 bool attention_supported(int dh);
 void attention_forward(const bf16_t* q, int64_t ldq, const bf16_t* k, const bf16_t* v, int64_t ldkv, bf16_t* out, int64_t ldo,
-                       float* lse, int S, int heads, int Tq, int Tk, int dh, bool causal, hipStream_t s);
+                       float* lse, int S, int heads, int Tq, int Tk, int dh, bool causal, const int32_t* key_tokens,
+                       int64_t tok_pitch, int key_col0, hipStream_t s);
 // dq, dk, dv are written (not accumulated), with the pitches of q and k / v; dsum: [S][heads][Tq] fp32 scratch.
 void attention_backward(const bf16_t* q, int64_t ldq, const bf16_t* k, const bf16_t* v, int64_t ldkv, const bf16_t* dout,
                         int64_t ldo, const float* lse, float* dsum, bf16_t* dq, bf16_t* dk, bf16_t* dv, int S, int heads,
-                        int Tq, int Tk, int dh, bool causal, hipStream_t s);
-// y[s*len + t][:] = table[tok[s*tok_pitch + col0 + t]][:] * sqrt(d) + the sinusoidal position signal of t (d even)
+                        int Tq, int Tk, int dh, bool causal, const int32_t* key_tokens, int64_t tok_pitch, int key_col0,
+                        hipStream_t s);
+// y[s*len + t][:] = table[tok[s*tok_pitch + col0 + t]][:] * sqrt(d) + the sinusoidal position signal of t (d even);
+// a negative id (padding) gives the position signal alone and takes no gradient
 void embed_forward(int dtype, const int32_t* tok, int64_t tok_pitch, int col0, int len, const void* table, int vocab, int d,
                    void* y, int64_t rows, hipStream_t s);
 // dtable[tok] += sqrt(d) * dy[row] (fp32 atomics onto a gradient that already holds the other uses of the table)

@@ -27,6 +27,7 @@ struct Op {
   // OP_ATTN: a0, a1, a2 = first column of the queries in x, of the keys and of the values in res;
   //          heads, causal; the width of each column range is the width of y.
   int a0 = 0, a1 = 0, a2 = 0, heads = 0;
+  int key_tok0 = 0;    // OP_ATTN: first token column of the sentences the keys come from (their padding is masked)
   bool causal = false;
   bool tied = false;   // OP_LINEAR: the weight is another op's parameter (the embedding table)
 };

@@ -112,10 +112,11 @@ struct Builder {
     m->ops.push_back(o);
     return o.y;
   }
-  int attention(int q, int q_col, int kv, int k_col, int v_col, int d, int heads, bool causal) {
+  int attention(int q, int q_col, int kv, int k_col, int v_col, int d, int heads, bool causal, int key_tok0) {
     const TensorDesc tq = m->tensors[q];
     Op o;
     o.kind = OP_ATTN; o.x = q; o.res = kv; o.a0 = q_col; o.a1 = k_col; o.a2 = v_col; o.heads = heads; o.causal = causal;
+    o.key_tok0 = key_tok0;
     o.y = add_tensor(tq.h, tq.w, d);
     m->ops.push_back(o);
     return o.y;
@@ -170,7 +171,7 @@ void build_transformer(Builder& b, const cd_arch_desc& a) {
   };
   auto self_attention = [&](int x, const std::string& p, bool causal) {
     int qkv = dense(x, p + ".qkv", d, 3 * d, false);
-    int o = b.attention(qkv, 0, qkv, d, 2 * d, d, heads, causal);
+    int o = b.attention(qkv, 0, qkv, d, 2 * d, d, heads, causal, causal ? Ts : 0);   // decoder keys: target sentences
     return add_norm(x, dense(o, p + ".out", d, d, false), p + ".ln");
   };
   int64_t sh[2] = {a.classes, d};
@@ -189,7 +190,7 @@ void build_transformer(Builder& b, const cd_arch_desc& a) {
     y = self_attention(y, p + ".self", true);
     int q = dense(y, p + ".cross.q", d, d, false);
     int kv = dense(memory, p + ".cross.kv", d, 2 * d, false);
-    int o = b.attention(q, 0, kv, 0, d, d, heads, false);
+    int o = b.attention(q, 0, kv, 0, d, d, heads, false, 0);
     y = add_norm(y, dense(o, p + ".cross.out", d, d, false), p + ".cross.ln");
     y = ffn(y, p);
   }
@@ -556,7 +557,10 @@ extern "C" int codistill_op_info(const cd_model* m, int64_t batch, int64_t idx, 
   if (o.kind == OP_LN) out->stats_offset = (int64_t)make_plan(m, batch, true).aux[idx];
   out->k_col = out->v_col = 0;
   if (o.kind == OP_EMBED) { out->k = o.a0; out->stride = o.a1; }
-  if (o.kind == OP_ATTN) { out->k = o.heads; out->stride = o.causal ? 1 : 0; out->pad = o.a0; out->k_col = o.a1; out->v_col = o.a2; }
+  if (o.kind == OP_ATTN) {
+    out->k = o.heads; out->stride = o.causal ? 1 : 0; out->pad = o.a0; out->k_col = o.a1; out->v_col = o.a2;
+    out->key_tok0 = o.key_tok0;
+  }
   out->res_grad = residual_grad_route(m, (int)idx, batch);
   out->fused_pool = pool_fused(m, (int)idx) ? 1 : 0;
   return CD_OK;
@@ -746,7 +750,8 @@ extern "C" int codistill_forward(const cd_model* m, const void* params, const vo
                      2.0 * batch * ((double)Tq * 2 + (double)Tk * 2) * d);
         attention_forward(static_cast<const bf16_t*>(in) + o.a0, tx.c, kvp + o.a1, kvp + o.a2, tkv.c,
                           static_cast<bf16_t*>(out), d, c.plan.aux[oi] ? reinterpret_cast<float*>(c.ws + c.plan.aux[oi]) : nullptr,
-                          (int)batch, o.heads, Tq, Tk, dh, o.causal, c.s);
+                          (int)batch, o.heads, Tq, Tk, dh, o.causal, static_cast<const int32_t*>(x), m->tensors[0].w, o.key_tok0,
+                          c.s);
         break;
       }
     }
@@ -858,7 +863,7 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
         attention_backward(static_cast<const bf16_t*>(in) + o.a0, tx.c, kvp + o.a1, kvp + o.a2, tkv.c,
                            static_cast<const bf16_t*>(dy), d, lse, lse + (size_t)batch * o.heads * Tq,
                            static_cast<bf16_t*>(dx) + o.a0, dkv + o.a1, dkv + o.a2, (int)batch, o.heads, Tq, Tk, dh, o.causal,
-                           c.s);
+                           static_cast<const int32_t*>(x), m->tensors[0].w, o.key_tok0, c.s);
         written[o.res] = 1;
         break;
       }

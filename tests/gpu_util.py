@@ -19,9 +19,11 @@ def norm_err(a, b):
 class Case:
     """Inputs of one codistillation step for an architecture (library preset kwargs + oracle arch)."""
 
-    def __init__(self, arch_kw, ref_arch, dtype_name, batch, res, classes, jitter=0.1, v_scale=0.0, in_c=3, tokens=None):
+    def __init__(self, arch_kw, ref_arch, dtype_name, batch, res, classes, jitter=0.1, v_scale=0.0, in_c=3, tokens=None,
+                 ragged=False):
         """tokens = (source length, target length): the input is int32 token ids and there is one row of logits
-        (and one label) per target token; res is then unused."""
+        (and one label) per target token; res is then unused.  ragged: the sentences get random lengths (one of them
+        a single token, one the full length); the rest of each part is padding (-1) and its labels are -1 (ignored)."""
         from paper_2010_02838_amd import binding as B
         self.B = B
         self.dtype = B.CD_BF16 if dtype_name == "bf16" else B.CD_F32
@@ -39,6 +41,17 @@ class Case:
             self.x = synth.tokens(batch, tokens[0] + tokens[1], classes, seed=0)
             self.y = synth.labels(batch * tokens[1], classes, seed=3)
             self.th, self.thp = synth.round_bf16(self.th), synth.round_bf16(self.thp)
+            if ragged:
+                rng = np.random.default_rng(11)
+                self.y = self.y.copy().reshape(batch, tokens[1])
+                for part, (c0, n) in enumerate(((0, tokens[0]), (tokens[0], tokens[1]))):
+                    lens = rng.integers(1, n + 1, batch)
+                    lens[0], lens[-1] = (1, n) if part == 0 else (n, 1)
+                    for s_, l in enumerate(lens):
+                        self.x[s_, c0 + l:c0 + n] = -1
+                        if part == 1:
+                            self.y[s_, l:] = -1
+                self.y = self.y.reshape(-1)
         else:
             self.x, self.y = synth.images(batch, res, res, in_c, seed=0), synth.labels(batch, classes, seed=3)
             if self.dtype == B.CD_BF16:   # both sides consume the same bf16-rounded weights and images

@@ -182,7 +182,8 @@ def check_layers(c, got):
             x2, kv2 = x.reshape(-1, x.shape[-1]), kv.reshape(-1, kv.shape[-1])
             qc, kc, vc = o["pad"], o["k_col"], o["v_col"]
             q, kk, v = x2[:, qc:qc + d], kv2[:, kc:kc + d], kv2[:, vc:vc + d]
-            yr, Pm = L.attention_forward(q, kk, v, c.batch, o["k"], bool(o["stride"]))
+            klen = L.sentence_lengths(c.x[:, o["key_tok0"]:o["key_tok0"] + kv.shape[1]])
+            yr, Pm = L.attention_forward(q, kk, v, c.batch, o["k"], bool(o["stride"]), klen)
             note("act", rel(y.reshape(-1, d), yr), tag, tol_t)
             dq, dk, dv = L.attention_backward(q, kk, v, Pm, dy.reshape(-1, d), c.batch, o["k"])
             gx, gkv = np.zeros_like(x2), np.zeros_like(kv2)

@@ -20,17 +20,34 @@ CASES = {
 }
 
 
-def make(name):
+def make(name, ragged=False):
     S, Ts, Tt, d, heads, ff, vocab, ne, nd = CASES[name]
     ref = nets.transformer(S, Ts, Tt, d=d, heads=heads, d_ff=ff, vocab=vocab, enc_layers=ne, dec_layers=nd)
     return Case(dict(kind=4, widths=[d, ff, heads], blocks=[ne, nd]), ref, "bf16", S, 0, vocab, jitter=0.1,
-                tokens=(Ts, Tt))
+                tokens=(Ts, Tt), ragged=ragged)
 
 
 @pytest.mark.parametrize("name", list(CASES))
 def test_transformer_bf16_layers(name):
     c = make(name)
     check_layers(c, c.gpu(alpha=0.5, label_smoothing=0.1))
+
+
+@pytest.mark.parametrize("name", ["small", "long", "mid"])
+def test_transformer_padded_sentences_bf16_layers(name):
+    """Sentences of different lengths in one batch (padding = negative ids, ignored labels): both sets of attention
+    kernels mask the padded keys, the embedding skips them, forward and backward."""
+    c = make(name, ragged=True)
+    got = c.gpu(alpha=0.5, label_smoothing=0.1)
+    check_layers(c, got)
+    # padded positions carry no loss gradient
+    assert np.all(got["dz"][c.y < 0] == 0)
+
+
+def test_transformer_padded_sentences_bf16_step():
+    c = make("small", ragged=True)
+    kw = dict(alpha=0.5, label_smoothing=0.1)
+    compare_bf16(c, c.oracle(**kw), c.oracle(store=synth.round_bf16_f64, **kw), c.gpu(**kw))
 
 
 @pytest.mark.parametrize("name", ["small", "ragged_vocab"])
