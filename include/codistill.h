@@ -66,6 +66,10 @@ enum {
   CD_ARCH_TINY_CNN = 0,          /* conv3x3(3->16)+b, ReLU, conv3x3(16->32)+b, ReLU, GAP, linear */
   CD_ARCH_RESNET_BASIC = 1,      /* CIFAR-style: 3x3 stem, basic blocks, projection shortcuts    */
   CD_ARCH_RESNET_BOTTLENECK = 2, /* 7x7-s2 stem, 3x3-s2 max-pool, bottleneck blocks (x4)         */
+  CD_ARCH_RESNET_BASIC_IMAGENET = 5, /* basic blocks behind the 7x7 stride-2 stem and 3x3 stride-2 max-pool of
+                                        CD_ARCH_RESNET_BOTTLENECK (ResNet-18/34: the smaller model of the pairs of
+                                        different architectures in Section 5); projection shortcut where the
+                                        stride or the width changes */
   CD_ARCH_TRANSFORMER = 4,       /* the encoder-decoder Transformer of Section 4 (Vaswani et al.): embedding of the shared
                                     vocabulary times sqrt(d_model) plus the sinusoidal position signal; encoder layers
                                     (self-attention, feed-forward), decoder layers (causal self-attention, attention over
@@ -122,6 +126,7 @@ typedef struct cd_model cd_model; /* opaque host object */
  * (ResNet-20: 32x32, widths 16/32/64, 3 blocks each, 10 classes), CD_ARCH_RESNET_BOTTLENECK
  * (ResNet-50: 224x224, widths 64..512, blocks 3/4/6/3, 1000 classes; Section 3),
  * CD_ARCH_TRANSFORMER_HEAD (d_model 512, d_ff 2048, vocabulary 32768: the base Transformer),
+ * CD_ARCH_RESNET_BASIC_IMAGENET (ResNet-18: blocks 2,2,2,2, widths 64..512, 224x224, 1000 classes),
  * CD_ARCH_TRANSFORMER (the base model: 6 + 6 layers, d_model 512, 8 heads, d_ff 2048, vocabulary 32768,
  * 128 source and 128 target tokens per sentence). host. */
 int codistill_arch_preset(int kind, cd_arch_desc* out);

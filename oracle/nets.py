@@ -180,6 +180,34 @@ def resnet20(classes=10, widths=(16, 32, 64), blocks=(3, 3, 3)):
     return a
 
 
+def resnet18(classes=1000, widths=(64, 128, 256, 512), blocks=(2, 2, 2, 2), stem=64):
+    """The basic-block network with the ImageNet front end (7x7 stride-2 stem, 3x3 stride-2 max-pool): the smaller
+    model of the paper's pairs of different architectures (Section 5)."""
+    a = Arch("resnet18")
+    t = a.conv(0, "stem.conv", 3, stem, 7, 2, 3, bias=False)
+    t = a.relu(a.bn(t, "stem.bn", stem))
+    t = a.maxpool(t, 3, 2, 1)
+    cin = stem
+    for si, (wd, nb) in enumerate(zip(widths, blocks)):
+        for bi in range(nb):
+            stride = 2 if (si > 0 and bi == 0) else 1
+            p = "s%d.b%d" % (si + 1, bi)
+            u = a.conv(t, p + ".conv1", cin, wd, 3, stride, 1, bias=False)
+            u = a.relu(a.bn(u, p + ".bn1", wd))
+            u = a.conv(u, p + ".conv2", wd, wd, 3, 1, 1, bias=False)
+            u = a.bn(u, p + ".bn2", wd)
+            if stride != 1 or cin != wd:
+                sc = a.conv(t, p + ".down.conv", cin, wd, 1, stride, 0, bias=False)
+                sc = a.bn(sc, p + ".down.bn", wd, stored=True)
+            else:
+                sc = t
+            t = a.relu(a.add(u, sc))
+            cin = wd
+    t = a.gap(t)
+    a.linear(t, "fc", cin, classes)
+    return a
+
+
 def resnet50(classes=1000, widths=(64, 128, 256, 512), blocks=(3, 4, 6, 3), stem=64):
     a = Arch("resnet50")
     t = a.conv(0, "stem.conv", 3, stem, 7, 2, 3, bias=False)

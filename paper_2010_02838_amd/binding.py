@@ -20,6 +20,7 @@ CD_MEAN_ALL, CD_MEAN_ROWS = 0, 1
 CD_BN_BATCH_STATS, CD_BN_RUNNING = 0, 1
 CD_ARCH_TINY_CNN, CD_ARCH_RESNET_BASIC, CD_ARCH_RESNET_BOTTLENECK, CD_ARCH_TRANSFORMER_HEAD = 0, 1, 2, 3
 CD_ARCH_TRANSFORMER = 4
+CD_ARCH_RESNET_BASIC_IMAGENET = 5
 CD_MAX_STAGES, CD_NAME_LEN, CD_LOSS_MAX_PEERS = 4, 48, 8
 KERNEL_CLASSES = ["conv_fprop", "conv_dgrad", "conv_wgrad", "norm", "glue", "linear", "loss", "sgd", "conv_fprop_narrow",
                   "bn_apply", "conv_fprop_wide", "attention"]

@@ -207,14 +207,15 @@ BnP bn_params(Builder& b, const std::string& n, int c) {
 
 void build_resnet(Builder& b, const cd_arch_desc& a) {
   const bool bott = a.kind == CD_ARCH_RESNET_BOTTLENECK;
+  const bool big_stem = bott || a.kind == CD_ARCH_RESNET_BASIC_IMAGENET;   // 7x7 stride 2 + max-pool
   char name[64];
   int t, cin = a.stem_width;
   {
-    int w = b.conv_w("stem.conv", 3, a.stem_width, bott ? 7 : 3);
+    int w = b.conv_w("stem.conv", 3, a.stem_width, big_stem ? 7 : 3);
     BnP p = bn_params(b, "stem.bn", a.stem_width);
-    t = bott ? b.conv(0, w, -1, a.stem_width, 7, 2, 3, false) : b.conv(0, w, -1, a.stem_width, 3, 1, 1, false);
+    t = big_stem ? b.conv(0, w, -1, a.stem_width, 7, 2, 3, false) : b.conv(0, w, -1, a.stem_width, 3, 1, 1, false);
     t = b.bn(t, p.g, p.b, -1, true);
-    if (bott) t = b.maxpool(t, 3, 2, 1);
+    if (big_stem) t = b.maxpool(t, 3, 2, 1);
   }
   for (int si = 0; si < a.n_stages; si++) {
     const int wd = a.widths[si];
@@ -437,6 +438,10 @@ extern "C" int codistill_arch_preset(int kind, cd_arch_desc* out) {
     out->classes = 1000; out->in_h = out->in_w = 224; out->n_stages = 4; out->stem_width = 64;
     const int w[4] = {64, 128, 256, 512}, nb[4] = {3, 4, 6, 3};
     for (int i = 0; i < 4; i++) { out->widths[i] = w[i]; out->blocks[i] = nb[i]; }
+  } else if (kind == CD_ARCH_RESNET_BASIC_IMAGENET) {
+    out->classes = 1000; out->in_h = out->in_w = 224; out->n_stages = 4; out->stem_width = 64;
+    const int w[4] = {64, 128, 256, 512};
+    for (int i = 0; i < 4; i++) { out->widths[i] = w[i]; out->blocks[i] = 2; }
   } else if (kind == CD_ARCH_TRANSFORMER_HEAD) {
     out->classes = 32768; out->in_h = out->in_w = 1; out->n_stages = 0;
     out->widths[0] = 512; out->widths[1] = 2048;
@@ -454,7 +459,8 @@ extern "C" int codistill_model_create(const cd_arch_desc* a, int dtype, cd_model
   CD_REQUIRE(a != nullptr && out != nullptr, "model_create: NULL pointer argument");
   CD_REQUIRE(dtype == CD_F32 || dtype == CD_BF16, "model_create: unknown dtype %d", dtype);
   CD_REQUIRE(a->kind == CD_ARCH_TINY_CNN || a->kind == CD_ARCH_RESNET_BASIC || a->kind == CD_ARCH_RESNET_BOTTLENECK ||
-                 a->kind == CD_ARCH_TRANSFORMER_HEAD || a->kind == CD_ARCH_TRANSFORMER,
+                 a->kind == CD_ARCH_RESNET_BASIC_IMAGENET || a->kind == CD_ARCH_TRANSFORMER_HEAD ||
+                 a->kind == CD_ARCH_TRANSFORMER,
              "model_create: unknown architecture kind %d", a->kind);
   CD_REQUIRE(a->classes >= 1 && a->classes <= (1 << 24), "model_create: classes=%d out of range", a->classes);
   CD_REQUIRE(a->in_h >= 1 && a->in_w >= 1 && a->in_h <= 4096 && a->in_w <= 4096,

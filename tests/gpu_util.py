@@ -20,10 +20,12 @@ class Case:
     """Inputs of one codistillation step for an architecture (library preset kwargs + oracle arch)."""
 
     def __init__(self, arch_kw, ref_arch, dtype_name, batch, res, classes, jitter=0.1, v_scale=0.0, in_c=3, tokens=None,
-                 ragged=False):
+                 ragged=False, peer=None):
         """tokens = (source length, target length): the input is int32 token ids and there is one row of logits
         (and one label) per target token; res is then unused.  ragged: the sentences get random lengths (one of them
-        a single token, one the full length); the rest of each part is padding (-1) and its labels are -1 (ignored)."""
+        a single token, one the full length); the rest of each part is padding (-1) and its labels are -1 (ignored).
+        peer = (library preset kwargs, oracle arch): the stale peer is a model of another architecture (same input and
+        number of classes)."""
         from paper_2010_02838_amd import binding as B
         self.B = B
         self.dtype = B.CD_BF16 if dtype_name == "bf16" else B.CD_F32
@@ -34,9 +36,17 @@ class Case:
             arch = B.arch_preset(kw.pop("kind"), in_h=res, in_w=res, classes=classes, **kw)
         self.model, self.peer = B.Model(arch, self.dtype), B.Model(arch, self.dtype)
         self.ref_arch, self.batch, self.res, self.classes = ref_arch, batch, res, classes
+        self.peer_ref = None
         table = self.model.param_table()
         assert table == [(n, tuple(s), k, f) for n, s, k, f in ref_arch.params]
-        self.th, self.thp = synth.he_init(table, 1, jitter), synth.he_init(table, 2, jitter)
+        ptable = table
+        if peer:
+            pkw = dict(peer[0])
+            self.peer = B.Model(B.arch_preset(pkw.pop("kind"), in_h=res, in_w=res, classes=classes, **pkw), self.dtype)
+            self.peer_ref = peer[1]
+            ptable = self.peer.param_table()
+            assert ptable == [(n, tuple(s), k, f) for n, s, k, f in self.peer_ref.params]
+        self.th, self.thp = synth.he_init(table, 1, jitter), synth.he_init(ptable, 2, jitter)
         if tokens:
             self.x = synth.tokens(batch, tokens[0] + tokens[1], classes, seed=0)
             self.y = synth.labels(batch * tokens[1], classes, seed=3)
@@ -64,7 +74,8 @@ class Case:
         return codistill_step(self.ref_arch, self.th.astype(np.float64), [self.thp.astype(np.float64)],
                               self.x.astype(np.float64), self.y, alpha, lr, mu,
                               v=None if self.v0 is None else self.v0.astype(np.float64), weight_decay=wd, dist=dist,
-                              store=store, label_smoothing=label_smoothing)
+                              store=store, label_smoothing=label_smoothing,
+                              peer_archs=None if self.peer_ref is None else [self.peer_ref])
 
     def gpu(self, alpha=1.0, lr=0.1, mu=0.9, wd=0.0, dist="mse", label_smoothing=0.0):
         from paper_2010_02838_amd.runner import StepRunner, pack_flat, unpack_flat, to_device

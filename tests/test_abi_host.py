@@ -32,6 +32,7 @@ def test_param_tables_match_oracle(dtype):
         (B.arch_preset(B.CD_ARCH_TINY_CNN), nets.tiny_cnn()),
         (B.arch_preset(B.CD_ARCH_RESNET_BASIC), nets.resnet20()),
         (B.arch_preset(B.CD_ARCH_RESNET_BOTTLENECK), nets.resnet50()),
+        (B.arch_preset(B.CD_ARCH_RESNET_BASIC_IMAGENET), nets.resnet18()),
         (B.arch_preset(B.CD_ARCH_RESNET_BASIC, widths=[4, 8, 16], blocks=[2, 1, 1], stem_width=4),
          nets.resnet20(widths=(4, 8, 16), blocks=(2, 1, 1))),
         (B.arch_preset(B.CD_ARCH_RESNET_BOTTLENECK, widths=[4, 8, 8, 16], blocks=[2, 1, 1, 1], stem_width=8, classes=7),
@@ -51,6 +52,9 @@ def test_resnet50_size_matches_paper():
     # Section 3: 32-bit ResNet50 is 8e8 bits
     m = B.Model(B.arch_preset(B.CD_ARCH_RESNET_BOTTLENECK), B.CD_BF16)
     assert sum(p["size"] for p in m.params) == 25557032
+    # the 18-layer network of the mixed-architecture pairs (Section 5)
+    m18 = B.Model(B.arch_preset(B.CD_ARCH_RESNET_BASIC_IMAGENET), B.CD_BF16)
+    assert sum(p["size"] for p in m18.params) == 11689512
 
 
 def _rc(fn, *args):

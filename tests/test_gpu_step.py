@@ -75,6 +75,10 @@ SMALL = {
                         5, 72, 10),
     "basic_mfma": (dict(kind=1, widths=[16, 24, 40], blocks=[1, 2, 1], stem_width=16),
                    lambda: nets.resnet20(widths=(16, 24, 40), blocks=(1, 2, 1)), 7, 20, 10),
+    # basic blocks behind the 7x7 stem and the max-pool (the ResNet-18 family)
+    "basic_imagenet_mfma": (dict(kind=5, widths=[16, 24, 32, 40], blocks=[1, 2, 1, 1], stem_width=16),
+                            lambda: nets.resnet18(classes=10, widths=(16, 24, 32, 40), blocks=(1, 2, 1, 1), stem=16),
+                            5, 72, 10),
 }
 
 
@@ -381,6 +385,16 @@ def test_small_resnet_fp32_layers(name):
 def test_small_resnet_bf16_step(name):
     kw, mk, batch, res, classes = SMALL[name]
     c = Case(kw, mk(), "bf16", batch, res, classes)
+    compare_bf16(c, c.oracle(), c.oracle(store=synth.round_bf16_f64), c.gpu())
+
+
+def test_peer_of_another_architecture_bf16_step():
+    """Section 5 pairs models of different architectures: the local bottleneck network distils against a stale
+    basic-block network; only the shape of the logits is shared."""
+    kw, mk, batch, res, classes = SMALL["bottleneck_mfma"]
+    pkw, pmk, _, _, _ = SMALL["basic_imagenet_mfma"]
+    c = Case(kw, mk(), "bf16", batch, res, classes, peer=(pkw, pmk()))
+    assert c.peer.n_elements != c.model.n_elements
     compare_bf16(c, c.oracle(), c.oracle(store=synth.round_bf16_f64), c.gpu())
 
 

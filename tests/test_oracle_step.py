@@ -152,6 +152,10 @@ def test_parameter_counts():
     assert r20.n_params() == 272474
     assert sum(1 for o in r20.ops if o["op"] == "conv") == 21
     assert sum(1 for o in r50.ops if o["op"] == "conv") == 53
+    # the 18-layer basic-block network at ImageNet size: 17 3x3/7x7 convolutions + 3 projection shortcuts + the classifier
+    r18 = nets.resnet18()
+    assert r18.n_params() == 11689512
+    assert sum(1 for o in r18.ops if o["op"] == "conv") == 20
 
 
 def _torch_forward(arch, params, x):
@@ -186,6 +190,7 @@ ARCHS = {
     "resnet20_small": (lambda: nets.resnet20(classes=10, widths=(4, 8, 16), blocks=(2, 1, 1)), (6, 16, 16, 3), 10),
     "resnet50_small": (lambda: nets.resnet50(classes=7, widths=(4, 8, 8, 16), blocks=(2, 1, 1, 1), stem=8), (4, 40, 40, 3), 7),
     "transformer_head_small": (lambda: nets.transformer_head(d_model=8, d_ff=24, vocab=13), (9, 1, 1, 8), 13),
+    "resnet18_small": (lambda: nets.resnet18(classes=7, widths=(8, 8, 16, 16), blocks=(1, 2, 1, 1), stem=8), (3, 40, 40, 3), 7),
 }
 
 
