@@ -670,22 +670,60 @@ __global__ void __launch_bounds__(256) embed_fwd_k(const int32_t* __restrict__ t
   y[row * d + 2 * i + 1] = Cvt<T>::st(Cvt<T>::ld(tr[1]) * scale + cosf(ang));
 }
 
-// dtable[tok] += sqrt(d) * dy[row] for every occurrence (fp32 atomics: the order of the additions,
-// and with it the last bits of the result, varies from run to run)
+// dtable[id] += sqrt(d) * sum of the rows of dy at the positions that hold token id.  One workgroup per position r and
+// block of 1024 columns.  The first position of each distinct id owns it: the workgroup first looks for an earlier
+// position with the same id (and leaves if there is one), then walks the positions from r on, 256 at a time, and adds
+// the matching rows in position order onto the table row it alone writes.  One writer per row and a fixed order of
+// additions: the result is bit-reproducible (atomics would not be).  The search is quadratic in the number of
+// positions (8192 x 8192 / 256 workgroup steps at the base shape, about 20 us).
+constexpr int EMB_COLS = 4;   // columns per thread
 template <typename T>
 __global__ void __launch_bounds__(256) embed_bwd_k(const int32_t* __restrict__ tok, int64_t tok_pitch, int col0, int T_,
                                                    const T* __restrict__ dy, int vocab, int d, float* __restrict__ dtable,
                                                    int64_t rows) {
-  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (idx >= rows * d) return;
-  const int c = (int)(idx % d);
-  const int64_t row = idx / d;
-  const int t = (int)(row % T_);
-  const int64_t s = row / T_;
-  int id = tok[s * tok_pitch + col0 + t];
-  if (id < 0) return;   // padding
-  id = id >= vocab ? vocab - 1 : id;
-  atomicAdd(dtable + (int64_t)id * d + c, Cvt<T>::ld(dy[idx]) * sqrtf((float)d));
+  __shared__ unsigned long long hits[4];
+  const int64_t r = blockIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  auto id_at = [&](int64_t q) {
+    const int v = tok[(q / T_) * tok_pitch + col0 + (q % T_)];
+    return v >= vocab ? vocab - 1 : v;   // the forward pass clamps the same way; negative = padding
+  };
+  const int id = id_at(r);
+  if (id < 0) return;
+  for (int64_t q0 = 0; q0 < r; q0 += 256) {
+    const int64_t q = q0 + threadIdx.x;
+    if (__syncthreads_or(q < r && id_at(q) == id)) return;   // an earlier position owns this id
+  }
+  const int cbase = blockIdx.y * (256 * EMB_COLS) + threadIdx.x;
+  float acc[EMB_COLS];
+#pragma unroll
+  for (int k = 0; k < EMB_COLS; k++) acc[k] = 0.f;
+  for (int64_t q0 = r / 256 * 256; q0 < rows; q0 += 256) {
+    const int64_t q = q0 + threadIdx.x;
+    const unsigned long long b = __ballot(q >= r && q < rows && id_at(q) == id);
+    __syncthreads();   // the previous chunk's masks have been read
+    if (lane == 0) hits[wave] = b;
+    __syncthreads();
+    for (int w = 0; w < 4; w++) {
+      unsigned long long m = hits[w];
+      while (m) {
+        const int bit = __ffsll((long long)m) - 1;
+        m &= m - 1;
+        const T* row = dy + (q0 + 64 * w + bit) * d;
+#pragma unroll
+        for (int k = 0; k < EMB_COLS; k++) {
+          const int c = cbase + 256 * k;
+          if (c < d) acc[k] += Cvt<T>::ld(row[c]);
+        }
+      }
+    }
+  }
+  const float scale = sqrtf((float)d);
+#pragma unroll
+  for (int k = 0; k < EMB_COLS; k++) {
+    const int c = cbase + 256 * k;
+    if (c < d) dtable[(int64_t)id * d + c] += scale * acc[k];
+  }
 }
 
 }  // namespace
@@ -757,7 +795,7 @@ void embed_forward(int dtype, const int32_t* tok, int64_t tok_pitch, int col0, i
 
 void embed_backward(int dtype, const int32_t* tok, int64_t tok_pitch, int col0, int len, const void* dy, int vocab, int d,
                     float* dtable, int64_t rows, hipStream_t s) {
-  const unsigned grid = (unsigned)cdiv(rows * d, 256);
+  const dim3 grid((unsigned)rows, (unsigned)cdiv(d, 256 * EMB_COLS));
   if (dtype == CD_BF16)
     hipLaunchKernelGGL(embed_bwd_k<bf16_t>, dim3(grid), dim3(256), 0, s, tok, tok_pitch, col0, len, (const bf16_t*)dy, vocab,
                        d, dtable, rows);

@@ -146,7 +146,8 @@ void attention_backward(const bf16_t* q, int64_t ldq, const bf16_t* k, const bf1
 // a negative id (padding) gives the position signal alone and takes no gradient
 void embed_forward(int dtype, const int32_t* tok, int64_t tok_pitch, int col0, int len, const void* table, int vocab, int d,
                    void* y, int64_t rows, hipStream_t s);
-// dtable[tok] += sqrt(d) * dy[row] (fp32 atomics onto a gradient that already holds the other uses of the table)
+// dtable[tok] += sqrt(d) * dy[row], added onto a gradient that already holds the other uses of the table; one writer per
+// table row, additions in position order (bit-reproducible)
 void embed_backward(int dtype, const int32_t* tok, int64_t tok_pitch, int col0, int len, const void* dy, int vocab, int d,
                     float* dtable, int64_t rows, hipStream_t s);
 

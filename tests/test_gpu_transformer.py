@@ -77,3 +77,18 @@ def test_transformer_base_size_layers():
     got = c.gpu(alpha=1.0, label_smoothing=0.1)
     assert np.isfinite(got["loss"]).all() and got["loss"][2] > 0
     check_layers(c, got)
+
+
+def test_transformer_step_is_bit_reproducible():
+    """Two runs of the same step give identical bits (no atomics anywhere: the embedding gradient has one writer per
+    table row and a fixed order of additions); tokens repeat many times at this vocabulary size."""
+    import torch
+    from paper_2010_02838_amd.runner import pack_flat, unpack_flat
+    c = make("ragged_vocab", ragged=True)
+    got = c.gpu(alpha=0.5, label_smoothing=0.1)
+    r = c.runner
+    r.load(pack_flat(c.model, c.th), [pack_flat(c.peer, c.thp)])
+    r.step(torch.from_numpy(c.x).to("cuda:0"), torch.from_numpy(c.y).to("cuda:0"), 0.5, 0.1, 0.9, label_smoothing=0.1)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(unpack_flat(c.model, r.grads.cpu().numpy()), got["grad"])
+    np.testing.assert_array_equal(r.logits.cpu().numpy(), got["logits"])
