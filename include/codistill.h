@@ -171,6 +171,8 @@ typedef struct {
   int32_t mse_reduction;  /* CD_MEAN_*; read for the two squared-error terms                  */
   int32_t ignore_index;   /* rows whose target equals this add nothing and get a zero gradient */
   int32_t n_peers;        /* n-1 of Algorithm 1; 0 = no distillation term this iteration       */
+  float temperature;      /* CD_DIST_KL only: tau^2 KL(softmax(z'/tau) || softmax(z/tau)), the usual form of
+                             distillation; the paper uses none: 1 (or 0, read as 1) is its term     */
 } cd_loss_cfg;
 
 #define CD_LOSS_MAX_PEERS 8

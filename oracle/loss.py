@@ -21,7 +21,11 @@ Readings where the paper is silent:
     over all C classes, q = (1-eps) onehot + eps/C;
   * "mean squared error" is the mean over all N*C elements ("mean_all"); the
     per-row sum averaged over rows ("mean_rows") is offered as well;
-  * KL is KL(p' || p) with the peer as target, temperature 1, mean over rows;
+  * KL is KL(p' || p) with the peer as target, mean over rows.  The paper uses no
+    temperature; the optional one here is the usual form of distillation (Hinton
+    et al.): both logit rows are divided by tau before the softmax and the term is
+    multiplied by tau^2 (so that its gradient keeps its scale); tau = 1 is the
+    paper's term;
   * "centring" the logits subtracts from each model's logit row its own mean
     over the classes before the squared error is taken ("mse_centered"); the
     normalisers are those of the uncentred term.
@@ -38,7 +42,7 @@ def log_softmax(z):
 
 
 def codistill_loss_grad(z, z_peers, targets, alpha, label_smoothing=0.0,
-                        dist="mse", mse_reduction="mean_all", ignore_index=-1):
+                        dist="mse", mse_reduction="mean_all", ignore_index=-1, temperature=1.0):
     """Return ((total, task, distill), dz).
 
     z        [rows, cols] local logits
@@ -90,10 +94,13 @@ def codistill_loss_grad(z, z_peers, targets, alpha, label_smoothing=0.0,
                 # difference whose rows already sum to zero, which leaves it unchanged
                 dz += alpha * w * 2.0 * diff / denom
             elif dist == "kl":
-                logpp = log_softmax(zp)
+                tau = float(temperature)
+                logpt = log_softmax(z / tau)
+                logpp = log_softmax(zp / tau)
                 pp = np.exp(logpp)
-                distill += w * float((pp * (logpp - logp) * vmask).sum() / n_valid)
-                dz += alpha * w * (p - pp) * vmask / n_valid
+                distill += w * tau * tau * float((pp * (logpp - logpt) * vmask).sum() / n_valid)
+                # d/dz of tau^2 KL(softmax(z'/tau) || softmax(z/tau)) = tau (p_tau - p'_tau)
+                dz += alpha * w * tau * (np.exp(logpt) - pp) * vmask / n_valid
             else:
                 raise ValueError(dist)
     total = task + alpha * distill

@@ -55,7 +55,8 @@ class ActInfo(ctypes.Structure):
 
 class LossCfg(ctypes.Structure):
     _fields_ = [("alpha", ctypes.c_float), ("label_smoothing", ctypes.c_float), ("dist_kind", ctypes.c_int32),
-                ("mse_reduction", ctypes.c_int32), ("ignore_index", ctypes.c_int32), ("n_peers", ctypes.c_int32)]
+                ("mse_reduction", ctypes.c_int32), ("ignore_index", ctypes.c_int32), ("n_peers", ctypes.c_int32),
+                ("temperature", ctypes.c_float)]
 
 
 if not os.path.exists(LIB_PATH):
@@ -197,11 +198,11 @@ def loss_scratch_bytes(rows, cols):
 
 
 def codistill_loss_grad(z_local, z_peers, targets, loss_out, dz_out, scratch, alpha, label_smoothing=0.0,
-                        dist_kind=CD_DIST_MSE_LOGITS, mse_reduction=CD_MEAN_ALL, ignore_index=-1):
+                        dist_kind=CD_DIST_MSE_LOGITS, mse_reduction=CD_MEAN_ALL, ignore_index=-1, temperature=1.0):
     """loss_out: float32[4] device tensor (total, task, distill, status bits)."""
     rows, cols = z_local.shape
     peers = list(z_peers) if z_peers is not None else []
-    cfg = LossCfg(alpha, label_smoothing, dist_kind, mse_reduction, ignore_index, len(peers))
+    cfg = LossCfg(alpha, label_smoothing, dist_kind, mse_reduction, ignore_index, len(peers), temperature)
     arr = (_vp * max(len(peers), 1))(*[p.data_ptr() for p in peers])
     _check(lib.codistill_loss_grad(_ptr(z_local), arr if peers else None, _ptr(targets), rows, cols,
                                    ctypes.byref(cfg), _ptr(loss_out), _ptr(dz_out), _ptr(scratch),

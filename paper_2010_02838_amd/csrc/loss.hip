@@ -21,6 +21,7 @@ struct LossArgs {
   float* dz;
   int64_t rows, cols;
   float alpha, eps;
+  float tau, inv_tau;   // temperature of the KL term (1 = the paper's); only the generic kernel reads it
   int32_t dist, mse_reduction, ignore_index, n_peers;
   int32_t* meta;    // [0] number of valid rows, [1] status bits
   float* row_task;  // [rows]
@@ -273,6 +274,15 @@ __global__ void __launch_bounds__(256) loss_row_generic_kernel(LossArgs a) {
   for (int64_t c = threadIdx.x; c < cols; c += 256) { float x = zr[c]; v2[0] += __expf(x - m); v2[1] += x; }
   group_reduce<256, 2, 0u>(v2, smem);
   const float lse = m + logf(v2[0]);
+  // KL with a temperature: tau^2 KL(softmax(z'/tau) || softmax(z/tau)); lse_t = log-sum-exp of z / tau
+  const float it = a.inv_tau;
+  float lse_t = lse;
+  if (!squared && a.n_peers > 0 && it != 1.f) {
+    float u[1] = {0.f};
+    for (int64_t c = threadIdx.x; c < cols; c += 256) u[0] += __expf((zr[c] - m) * it);
+    group_reduce<256, 1, 0u>(u, smem);
+    lse_t = m * it + logf(u[0]);
+  }
   float dsum = 0.f;
   for (int j = 0; j < a.n_peers; j++) {
     const float* pr = a.zp[j] + row * cols;
@@ -296,13 +306,13 @@ __global__ void __launch_bounds__(256) loss_row_generic_kernel(LossArgs a) {
       const float mp = q[0];
       float w[2] = {0.f, 0.f};
       for (int64_t c = threadIdx.x; c < cols; c += 256) {
-        float y = pr[c], e = __expf(y - mp);
+        float y = pr[c], e = __expf((y - mp) * it);
         w[0] += e;
-        w[1] += e * (y - zr[c]);
+        w[1] += e * ((y - zr[c]) * it);
       }
       group_reduce<256, 2, 0u>(w, smem);
-      const float lsep = mp + logf(w[0]);
-      dsum += w[1] / w[0] - lsep + lse;
+      const float lsep = mp * it + logf(w[0]);
+      dsum += (w[1] / w[0] - lsep + lse_t) * (a.tau * a.tau);
       if (threadIdx.x == 0) s_lsep[j] = lsep;
     }
   }
@@ -315,15 +325,16 @@ __global__ void __launch_bounds__(256) loss_row_generic_kernel(LossArgs a) {
   const float epsc = a.eps / (float)cols;
   const float wj = a.n_peers > 0 ? 1.f / (float)a.n_peers : 0.f;
   const float cm = a.alpha * wj * 2.f * invn / (a.mse_reduction == CD_MEAN_ALL ? (float)cols : 1.f);
-  const float ck = a.alpha * wj * invn;
+  const float ck = a.alpha * wj * invn * a.tau;   // d/dz of tau^2 KL = tau (p_tau - p'_tau)
   for (int64_t c = threadIdx.x; c < cols; c += 256) {
     const float x = zr[c];
     const float p = __expf(x - lse);
+    const float pt = it != 1.f ? __expf(x * it - lse_t) : p;
     float gk = (p - epsc) * invn;
     for (int j = 0; j < a.n_peers; j++) {
       const float y = a.zp[j][row * cols + c];
       if (squared) gk += cm * (x - y - s_lsep[j]);
-      else gk += ck * (p - __expf(y - s_lsep[j]));
+      else gk += ck * (pt - __expf(y * it - s_lsep[j]));
     }
     if (c == t) gk -= (1.f - a.eps) * invn;
     outr[c] = gk;
@@ -402,6 +413,8 @@ extern "C" int codistill_loss_grad(const float* z_local, const float* const* z_p
   CD_REQUIRE(cfg->label_smoothing >= 0.f && cfg->label_smoothing < 1.f, "loss_grad: label_smoothing %g outside [0,1)",
              (double)cfg->label_smoothing);
   CD_REQUIRE(cfg->alpha == cfg->alpha, "loss_grad: alpha is NaN");
+  CD_REQUIRE(cfg->temperature >= 0.f && cfg->temperature <= 1e6f, "loss_grad: temperature %g outside [0, 1e6] (0 means 1)",
+             (double)cfg->temperature);
   CD_REQUIRE(cfg->n_peers == 0 || z_peers != nullptr, "loss_grad: z_peers is NULL with n_peers=%d", cfg->n_peers);
   CD_REQUIRE(aligned16(z_local) && aligned16(dz_out) && aligned16(scratch) && aligned16(loss_out),
              "loss_grad: pointers must be 16-byte aligned");
@@ -420,6 +433,8 @@ extern "C" int codistill_loss_grad(const float* z_local, const float* const* z_p
   a.cols = cols;
   a.alpha = cfg->alpha;
   a.eps = cfg->label_smoothing;
+  a.tau = cfg->temperature > 0.f ? cfg->temperature : 1.f;
+  a.inv_tau = 1.f / a.tau;
   a.dist = cfg->dist_kind;
   a.mse_reduction = cfg->mse_reduction;
   a.ignore_index = cfg->ignore_index;
@@ -438,7 +453,8 @@ extern "C" int codistill_loss_grad(const float* z_local, const float* const* z_p
                    : cfg->dist_kind == CD_DIST_KL         ? 2
                                                           : 3;
   // register-resident kernel: one peer, or several with the MSE term (folded into a running mean)
-  const bool fast = cols % 4 == 0 && cols <= 32768 && (cfg->n_peers <= 1 || mode == 1);
+  // (a temperature other than 1 needs a second softmax of the local row: the generic kernel has it)
+  const bool fast = cols % 4 == 0 && cols <= 32768 && (cfg->n_peers <= 1 || mode == 1) && (mode != 2 || a.tau == 1.f);
   if (!fast) {
     hipLaunchKernelGGL(loss_row_generic_kernel, dim3((unsigned)rows), dim3(256), 0, s, a);
   } else if (cols <= 256) launch_rows<64, 1>(a, mode, s);

@@ -13,7 +13,7 @@ MODES = {"mse": (0, 0, "mse", "mean_all"), "mse_rows": (0, 1, "mse", "mean_rows"
          "mse_centered": (2, 0, "mse_centered", "mean_all"), "mse_centered_rows": (2, 1, "mse_centered", "mean_rows")}
 
 
-def run_gpu(z, peers, t, alpha, eps, mode, ignore_index=-1, inplace=False):
+def run_gpu(z, peers, t, alpha, eps, mode, ignore_index=-1, inplace=False, temperature=1.0):
     from paper_2010_02838_amd import binding as B
     dev = "cuda:0"
     dk, red, _, _ = MODES[mode]
@@ -23,7 +23,7 @@ def run_gpu(z, peers, t, alpha, eps, mode, ignore_index=-1, inplace=False):
     loss = torch.zeros(4, device=dev)
     dz = zt if inplace else torch.empty_like(zt)
     scratch = torch.empty(B.loss_scratch_bytes(*z.shape), dtype=torch.uint8, device=dev)
-    B.codistill_loss_grad(zt, pts, tt, loss, dz, scratch, alpha, eps, dk, red, ignore_index)
+    B.codistill_loss_grad(zt, pts, tt, loss, dz, scratch, alpha, eps, dk, red, ignore_index, temperature)
     torch.cuda.synchronize()
     l = loss.cpu().numpy()
     return l[:3].astype(np.float64), int(l[3:4].view(np.int32)[0]), dz.cpu().numpy()
@@ -35,7 +35,8 @@ def rel(a, b):
 
 
 def check(z, peers, t, alpha, eps, mode, **kw):
-    (tot, task, dist), dz_ref = oracle_loss(z, peers, t, alpha, eps, MODES[mode][2], MODES[mode][3])
+    (tot, task, dist), dz_ref = oracle_loss(z, peers, t, alpha, eps, MODES[mode][2], MODES[mode][3],
+                                            temperature=kw.get("temperature", 1.0))
     l, status, dz = run_gpu(z, peers, t, alpha, eps, mode, **kw)
     assert status == 0
     assert rel(dz, dz_ref) <= TOL
@@ -171,3 +172,20 @@ def test_full_size_sampled(mode):
     assert abs(l[0] - (task + alpha * dist)) <= TOL * (task + alpha * dist)
     if mode == "mse":
         assert abs(l[2] - 18.0) < 0.02      # E[D] = 2 sigma^2 for independent N(0, 9) logits
+
+
+@pytest.mark.parametrize("rows,cols", [(8, 10), (64, 1000), (19, 4100), (6, 32768)])
+@pytest.mark.parametrize("tau", [0.5, 2.0, 4.0])
+def test_kl_temperature(rows, cols, tau):
+    z = synth.logits(rows, cols, 3.0, seed=1)
+    t = synth.labels(rows, cols, seed=3)
+    t[0] = -1
+    for npeers in (1, 2):
+        peers = [synth.logits(rows, cols, 3.0, seed=20 + j) for j in range(npeers)]
+        check(z, peers, t, 0.6, 0.1, "kl", temperature=tau)
+    # temperature 1 (and 0, read as 1) is the register-resident kernel's result
+    peers = [synth.logits(rows, cols, 3.0, seed=20)]
+    a = run_gpu(z, peers, t, 0.6, 0.1, "kl")
+    b = run_gpu(z, peers, t, 0.6, 0.1, "kl", temperature=0.0)
+    np.testing.assert_array_equal(a[2], b[2])
+    np.testing.assert_array_equal(a[0], b[0])

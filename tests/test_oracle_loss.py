@@ -141,6 +141,29 @@ def test_kl_library_special_cases():
     np.testing.assert_allclose(dz2, dz, atol=1e-15)
 
 
+def test_kl_temperature_against_torch_and_its_high_temperature_limit():
+    z, zp = rnd(6, 17, 12), rnd(6, 17, 13)
+    t = np.arange(6)
+    for tau in (0.5, 1.0, 3.0):
+        (tot, task, d), dz = codistill_loss_grad(z, [zp], t, 0.7, dist="kl", temperature=tau)
+        zt = torch.tensor(z, requires_grad=True)
+        kl = tau * tau * torch.nn.functional.kl_div(torch.log_softmax(zt / tau, 1), torch.softmax(torch.tensor(zp) / tau, 1),
+                                                    reduction="batchmean")
+        ce = torch.nn.functional.cross_entropy(zt, torch.tensor(t))
+        (ce + 0.7 * kl).backward()
+        assert d == pytest.approx(kl.item(), rel=1e-12)
+        assert task == pytest.approx(ce.item(), rel=1e-12)       # the supervised term keeps temperature 1
+        np.testing.assert_allclose(dz, zt.grad.numpy(), atol=1e-15)
+    # tau = 1 is the default
+    assert codistill_loss_grad(z, [zp], t, 0.7, dist="kl")[0] == codistill_loss_grad(z, [zp], t, 0.7, dist="kl", temperature=1.0)[0]
+    # tau -> infinity: tau^2 KL tends to half the squared distance of the centred logit rows, per class
+    delta = zp - z
+    delta = delta - delta.mean(axis=1, keepdims=True)
+    limit = (delta ** 2).sum() / (2 * 17) / 6
+    (_, _, dbig), _ = codistill_loss_grad(z, [zp], t, 1.0, dist="kl", temperature=1e4)
+    assert dbig == pytest.approx(limit, rel=2e-3)
+
+
 def test_centered_mse_invariances_and_reduction_to_plain_mse():
     z, zp = rnd(9, 13, 30), rnd(9, 13, 31)
     t = np.random.default_rng(32).integers(0, 13, 9)
