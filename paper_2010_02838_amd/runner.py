@@ -81,7 +81,8 @@ class StepRunner:
             self.momentum.copy_(torch.from_numpy(np.ascontiguousarray(v, dtype=np.float32)))
 
     def step(self, x, y, alpha, lr, momentum, weight_decay=0.0, label_smoothing=0.0,
-             dist_kind=B.CD_DIST_MSE_LOGITS, mse_reduction=B.CD_MEAN_ALL, ignore_index=-1, nesterov=False, adam=None):
+             dist_kind=B.CD_DIST_MSE_LOGITS, mse_reduction=B.CD_MEAN_ALL, ignore_index=-1, nesterov=False, adam=None,
+             temperature=1.0):
         """x: [B,H,W,3] device tensor in the model dtype (the Transformer: int32 [B, source + target tokens]);
         y: int32 device tensor, one target per row of logits.  adam = (beta1, beta2, eps) replaces the momentum-SGD
         update by Adam (momentum and nesterov are then unused)."""
@@ -98,7 +99,7 @@ class StepRunner:
             for pm, pp, pl in zip(self.peers, self.peer_params, self.peer_logits):
                 B.codistill_forward(pm, pp, x, self.ws_peer, pl, False)
         B.codistill_loss_grad(self.logits, self.peer_logits, y, self.loss, self.dz, self.scratch, alpha,
-                              label_smoothing, dist_kind, mse_reduction, ignore_index)
+                              label_smoothing, dist_kind, mse_reduction, ignore_index, temperature)
         B.codistill_backward(self.model, self.params(), x, self.ws, self.dz, self.grads)
         if adam is None:
             B.codistill_sgd_step(self.master, self.momentum, self.grads, self.lowp, lr, momentum, weight_decay, nesterov)
