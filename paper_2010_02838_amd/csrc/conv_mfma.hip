@@ -38,6 +38,9 @@ struct IgemmArgs {
   // without that branch's gradient ever being written out.
   const bf16_t* addend = nullptr;
   const uint8_t* addend_gate = nullptr;
+  // (nullable) a tensor [M][N] of which the output is the gradient behind a ReLU: output elements whose element
+  // of relu_out is not positive are written as zero (the ReLU's backward pass, without a pass of its own)
+  const bf16_t* relu_out = nullptr;
   int pointwise;  // kh = kw = 1, stride 1, no padding (set by the launcher)
   int group_m;    // GROUP kernels: tile order in groups of this many row tiles
   int ntiles;
@@ -478,6 +481,15 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
                                __uint_as_float(vv[q] & 0xffff0000u) + __uint_as_float(oo[q] & 0xffff0000u));
           v = make_uint4(r[0], r[1], r[2], r[3]);
         }
+        if (a.relu_out) {
+          const uint4 y = *reinterpret_cast<const uint4*>(a.relu_out + idx);
+          const uint32_t yy[4] = {y.x, y.y, y.z, y.w};
+          uint32_t vv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+          for (int q = 0; q < 4; q++)   // a bf16 is positive iff its bits, read as int16, are
+            vv[q] &= ((int16_t)(yy[q] & 0xffffu) > 0 ? 0x0000ffffu : 0u) | ((int16_t)(yy[q] >> 16) > 0 ? 0xffff0000u : 0u);
+          v = make_uint4(vv[0], vv[1], vv[2], vv[3]);
+        }
         *reinterpret_cast<uint4*>(dp) = v;
       }
     }
@@ -640,7 +652,7 @@ __global__ void __launch_bounds__(256) fill_zero16_k(uint4* p, int64_t n) {
 }
 
 void conv_dgrad_mfma(const bf16_t* dy, const bf16_t* w, bf16_t* wt, bf16_t* dx, const ConvGeom& g, bool accumulate,
-                     hipStream_t s, const bf16_t* addend, const uint8_t* addend_gate) {
+                     hipStream_t s, const bf16_t* addend, const uint8_t* addend_gate, const bf16_t* relu_out) {
   IgemmArgs a;
   a.bias = nullptr;
   a.stat_partials = nullptr;
@@ -660,6 +672,7 @@ void conv_dgrad_mfma(const bf16_t* dy, const bf16_t* w, bf16_t* wt, bf16_t* dx, 
     a.accumulate = (accumulate || addend) ? 1 : 0;
     a.addend = addend;          // stride 1 only (see the declaration); never together with accumulate
     a.addend_gate = addend_gate;
+    a.relu_out = relu_out;      // stride 1 only, like the addend
     a.wt_bytes = (uint32_t)((int64_t)g.Cout * g.K() * 2);
     launch_igemm<1, false>(a, s);
     return;

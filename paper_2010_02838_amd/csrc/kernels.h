@@ -104,8 +104,11 @@ int conv_fprop_tile_class(const ConvGeom& g, bool bias);
 // scratch of at least Cout*K + 32 elements that receives its re-laid-out copy (or copies, per parity
 // class, for stride 2).  addend (nullable; stride 1 and accumulate == false only): dx = product + addend,
 // with addend_gate (nullable, one bit per element of addend) dropping the elements whose bit is clear.
+// relu_out (nullable; stride 1 only): dx is the gradient behind a ReLU whose result is relu_out [B*H*W][Cin]; its
+// elements where relu_out is not positive are written as zero.
 void conv_dgrad_mfma(const bf16_t* dy, const bf16_t* w, bf16_t* wt, bf16_t* dx, const ConvGeom& g, bool accumulate,
-                     hipStream_t s, const bf16_t* addend = nullptr, const uint8_t* addend_gate = nullptr);
+                     hipStream_t s, const bf16_t* addend = nullptr, const uint8_t* addend_gate = nullptr,
+                     const bf16_t* relu_out = nullptr);
 // dw[Cout][K] = dy[M][Cout]^T * im2col(x)[M][K], split over M with fp32 partials reduced in fixed order
 void conv_wgrad_mfma(const bf16_t* x, const bf16_t* dy, float* dw, const ConvGeom& g, float* partials,
                      size_t partials_bytes, hipStream_t s);

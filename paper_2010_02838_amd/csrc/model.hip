@@ -283,6 +283,13 @@ bool force_residual_grads() {
   return e && e[0] == '1';
 }
 
+// CODISTILL_SEPARATE_RELU_MASK=1 keeps the backward pass of a convolution's fused ReLU in a kernel of its own
+// instead of the epilogue of the data-gradient kernel that writes the masked tensor (debugging aid)
+bool fuse_off() {
+  const char* e = getenv("CODISTILL_SEPARATE_RELU_MASK");
+  return e && e[0] == '1';
+}
+
 // CODISTILL_SERIAL=1 keeps every launch of a call on the caller's stream (debugging aid)
 bool force_serial() {
   const char* e = getenv("CODISTILL_SERIAL");
@@ -811,6 +818,16 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
     return pool_fused(m, b) && m->ops[b].x != 0 && !written[m->ops[b].x] && c.plan.aux[b] != 0 && c.plan.aux[b + 1] != 0 &&
            batch * t.per_sample() < (1LL << 31);
   };
+  // Tensors that are the ReLU'd output of a convolution and have one reader, itself a stride-1 convolution on the
+  // matrix-core path: that reader's data-gradient kernel applies the ReLU mask as it writes the tensor's gradient,
+  // and the producing convolution's own masking pass is dropped.
+  std::vector<int> producer(m->tensors.size(), -1), readers(m->tensors.size(), 0);
+  for (size_t j = 0; j < m->ops.size(); j++) {
+    producer[m->ops[j].y] = (int)j;
+    readers[m->ops[j].x]++;
+    if (m->ops[j].res >= 0 && m->ops[j].res != m->ops[j].x) readers[m->ops[j].res]++;
+  }
+  std::vector<char> relu_done(m->tensors.size(), 0);
   for (int i = (int)m->ops.size() - 1; i >= 0; i--) {
     const Op& o = m->ops[i];
     const TensorDesc& tx = m->tensors[o.x];
@@ -934,7 +951,7 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
       }
       case OP_CONV: {
         ConvGeom g = conv_geom(m, o, batch);
-        if (o.relu) {
+        if (o.relu && !relu_done[o.y]) {
           ProfScope pr(CD_K_GLUE, c.s, 0, (double)g.M() * g.Cout * m->esize() * 3);
           relu_bwd_inplace(dt, dy, c.act(o.y), g.M() * g.Cout, c.s);
         }
@@ -975,8 +992,13 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
           if (mf) {
             const Deferred df = deferred[o.x];   // kind 2: set only where this launch can take it
             deferred[o.x] = Deferred();
+            const int pi = producer[o.x];
+            const bool gate = g.stride == 1 && !acc && readers[o.x] == 1 && pi >= 0 && m->ops[pi].kind == OP_CONV &&
+                              m->ops[pi].relu && use_mfma(m, conv_geom(m, m->ops[pi], batch)) && !fuse_off();
             conv_dgrad_mfma(static_cast<const bf16_t*>(dy), static_cast<const bf16_t*>(c.P(o.pw)), c.wpack(),
-                            static_cast<bf16_t*>(dx), g, acc, c.s, static_cast<const bf16_t*>(df.src), df.gate);
+                            static_cast<bf16_t*>(dx), g, acc, c.s, static_cast<const bf16_t*>(df.src), df.gate,
+                            gate ? static_cast<const bf16_t*>(c.act(o.x)) : nullptr);
+            if (gate) relu_done[o.x] = 1;
           } else {
             conv_dgrad_simple(dt, dy, c.P(o.pw), dx, g, acc, c.s);
           }
