@@ -26,8 +26,23 @@ LN_EPS = 1e-5
 
 
 # ---------------------------------------------------------------- convolution
+def _groups(cin, w):
+    """Grouped convolution (the ResNeXt block): the filter holds cin / groups input channels per output channel;
+    output channels [g*Cout/G, (g+1)*Cout/G) read input channels [g*Cin/G, (g+1)*Cin/G) only."""
+    if cin % w.shape[3] or w.shape[0] % (cin // w.shape[3]):
+        raise ValueError("filter %s does not divide %d input channels into groups" % (w.shape, cin))
+    return cin // w.shape[3]
+
+
 def conv2d_forward(x, w, bias, stride, pad):
-    """y[b,ho,wo,o] = bias[o] + sum_{r,s,c} x[b, ho*stride-pad+r, wo*stride-pad+s, c] * w[o,r,s,c]."""
+    """y[b,ho,wo,o] = bias[o] + sum_{r,s,c} x[b, ho*stride-pad+r, wo*stride-pad+s, c] * w[o,r,s,c]
+    (within the group of o when the filter has fewer input channels than x: see _groups)."""
+    G = _groups(x.shape[3], w)
+    if G > 1:
+        cg, og = w.shape[3], w.shape[0] // G
+        y = np.concatenate([conv2d_forward(x[..., g * cg:(g + 1) * cg], w[g * og:(g + 1) * og], None, stride, pad)
+                            for g in range(G)], axis=3)
+        return y if bias is None else y + bias
     B, H, W, Cin = x.shape
     Cout, kh, kw, _ = w.shape
     Ho, Wo = _out_size(H, kh, stride, pad), _out_size(W, kw, stride, pad)
@@ -45,6 +60,14 @@ def conv2d_forward(x, w, bias, stride, pad):
 
 def conv2d_backward(x, w, dy, stride, pad, has_bias, need_dx=True):
     """Return (dx, dw, dbias) of conv2d_forward for upstream gradient dy."""
+    G = _groups(x.shape[3], w)
+    if G > 1:
+        cg, og = w.shape[3], w.shape[0] // G
+        parts = [conv2d_backward(x[..., g * cg:(g + 1) * cg], w[g * og:(g + 1) * og], dy[..., g * og:(g + 1) * og],
+                                 stride, pad, False, need_dx) for g in range(G)]
+        dx = np.concatenate([p[0] for p in parts], axis=3) if need_dx else None
+        dw = np.concatenate([p[1] for p in parts], axis=0)
+        return dx, dw, (dy.reshape(-1, dy.shape[3]).sum(axis=0) if has_bias else None)
     B, H, W, Cin = x.shape
     Cout, kh, kw, _ = w.shape
     _, Ho, Wo, _ = dy.shape

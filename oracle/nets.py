@@ -70,8 +70,8 @@ class Arch:
         self.params.append((name, tuple(shape), kind, fan_in))
         return name
 
-    def conv(self, x, name, cin, cout, k, stride, pad, bias):
-        w = self._p(name + ".w", (cout, k, k, cin), "conv_w", cin * k * k)
+    def conv(self, x, name, cin, cout, k, stride, pad, bias, groups=1):
+        w = self._p(name + ".w", (cout, k, k, cin // groups), "conv_w", cin // groups * k * k)
         b = self._p(name + ".b", (cout,), "bias") if bias else None
         y = self._t()
         self.ops.append(dict(op="conv", x=x, y=y, w=w, b=b, stride=stride, pad=pad, stored=True))
@@ -203,6 +203,39 @@ def resnet18(classes=1000, widths=(64, 128, 256, 512), blocks=(2, 2, 2, 2), stem
                 sc = t
             t = a.relu(a.add(u, sc))
             cin = wd
+    t = a.gap(t)
+    a.linear(t, "fc", cin, classes)
+    return a
+
+
+def resnext(classes=1000, widths=(256, 512, 1024, 2048), outs=(256, 512, 1024, 2048), groups=32, blocks=(3, 4, 23, 3),
+            stem=64):
+    """The bottleneck network with a grouped 3x3 convolution (aggregated transformations; the defaults are the
+    101-layer 32x8d model, widths (128, ..., 1024) and blocks (3, 4, 6, 3) the 50-layer 32x4d one): the largest
+    model of the paper's pairs of different architectures (Section 5).  widths: channels of the grouped
+    convolution per stage; outs: channels of the block's output."""
+    a = Arch("resnext")
+    t = a.conv(0, "stem.conv", 3, stem, 7, 2, 3, bias=False)
+    t = a.relu(a.bn(t, "stem.bn", stem))
+    t = a.maxpool(t, 3, 2, 1)
+    cin = stem
+    for si, (wd, out, nb) in enumerate(zip(widths, outs, blocks)):
+        for bi in range(nb):
+            stride = 2 if (si > 0 and bi == 0) else 1
+            p = "s%d.b%d" % (si + 1, bi)
+            u = a.conv(t, p + ".conv1", cin, wd, 1, 1, 0, bias=False)
+            u = a.relu(a.bn(u, p + ".bn1", wd))
+            u = a.conv(u, p + ".conv2", wd, wd, 3, stride, 1, bias=False, groups=groups)
+            u = a.relu(a.bn(u, p + ".bn2", wd))
+            u = a.conv(u, p + ".conv3", wd, out, 1, 1, 0, bias=False)
+            u = a.bn(u, p + ".bn3", out)
+            if bi == 0:
+                sc = a.conv(t, p + ".down.conv", cin, out, 1, stride, 0, bias=False)
+                sc = a.bn(sc, p + ".down.bn", out, stored=True)
+            else:
+                sc = t
+            t = a.relu(a.add(u, sc))
+            cin = out
     t = a.gap(t)
     a.linear(t, "fc", cin, classes)
     return a

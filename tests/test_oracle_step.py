@@ -153,6 +153,9 @@ def test_parameter_counts():
     assert sum(1 for o in r20.ops if o["op"] == "conv") == 21
     assert sum(1 for o in r50.ops if o["op"] == "conv") == 53
     # the 18-layer basic-block network at ImageNet size: 17 3x3/7x7 convolutions + 3 projection shortcuts + the classifier
+    # aggregated-transformation networks: 50 layers 32x4d and 101 layers 32x8d
+    assert nets.resnext(widths=(128, 256, 512, 1024), blocks=(3, 4, 6, 3)).n_params() == 25028904
+    assert nets.resnext().n_params() == 88791336
     r18 = nets.resnet18()
     assert r18.n_params() == 11689512
     assert sum(1 for o in r18.ops if o["op"] == "conv") == 20
@@ -164,7 +167,8 @@ def _torch_forward(arch, params, x):
         k = o["op"]
         if k == "conv":
             b = params[o["b"]] if o["b"] else None
-            T[o["y"]] = F.conv2d(T[o["x"]], params[o["w"]].permute(0, 3, 1, 2), b, o["stride"], o["pad"])
+            wt = params[o["w"]].permute(0, 3, 1, 2)
+            T[o["y"]] = F.conv2d(T[o["x"]], wt, b, o["stride"], o["pad"], groups=T[o["x"]].shape[1] // wt.shape[1])
         elif k == "bn":
             T[o["y"]] = F.batch_norm(T[o["x"]], None, None, params[o["gamma"]], params[o["beta"]], True, 0.1, 1e-5)
         elif k == "relu":
@@ -190,6 +194,8 @@ ARCHS = {
     "resnet20_small": (lambda: nets.resnet20(classes=10, widths=(4, 8, 16), blocks=(2, 1, 1)), (6, 16, 16, 3), 10),
     "resnet50_small": (lambda: nets.resnet50(classes=7, widths=(4, 8, 8, 16), blocks=(2, 1, 1, 1), stem=8), (4, 40, 40, 3), 7),
     "transformer_head_small": (lambda: nets.transformer_head(d_model=8, d_ff=24, vocab=13), (9, 1, 1, 8), 13),
+    "resnext_small": (lambda: nets.resnext(classes=7, widths=(8, 16, 16, 24), outs=(12, 16, 24, 32), groups=4,
+                                           blocks=(2, 1, 1, 1), stem=8), (3, 40, 40, 3), 7),
     "resnet18_small": (lambda: nets.resnet18(classes=7, widths=(8, 8, 16, 16), blocks=(1, 2, 1, 1), stem=8), (3, 40, 40, 3), 7),
 }
 
@@ -307,3 +313,27 @@ def test_peer_gets_no_gradient_and_plain_step():
     # first step from v = 0: theta_1 = theta_0 - lr * g
     np.testing.assert_allclose(b["theta"], th - 0.1 * b["grad"], atol=1e-15)
     assert flatten(arch, unflatten(arch, th)).tolist() == th.tolist()
+
+
+def test_grouped_convolution_is_the_block_diagonal_dense_one():
+    """A grouped convolution equals the dense one whose filter is zero outside the groups' diagonal blocks, forward
+    and backward (the dense routine is pinned above); its filter gradient is the diagonal blocks of the dense one."""
+    from oracle import layers as L
+    rng = np.random.default_rng(8)
+    B, H, Cin, Cout, G, k = 2, 7, 12, 8, 4, 3
+    cg, og = Cin // G, Cout // G
+    x, w = rng.standard_normal((B, H, H, Cin)), rng.standard_normal((Cout, k, k, cg))
+    wd = np.zeros((Cout, k, k, Cin))
+    for g in range(G):
+        wd[g * og:(g + 1) * og, :, :, g * cg:(g + 1) * cg] = w[g * og:(g + 1) * og]
+    for stride in (1, 2):
+        y = L.conv2d_forward(x, w, None, stride, 1)
+        np.testing.assert_allclose(y, L.conv2d_forward(x, wd, None, stride, 1), atol=1e-13)
+        dy = rng.standard_normal(y.shape)
+        dx, dw, _ = L.conv2d_backward(x, w, dy, stride, 1, False)
+        dxd, dwd, _ = L.conv2d_backward(x, wd, dy, stride, 1, False)
+        np.testing.assert_allclose(dx, dxd, atol=1e-13)
+        for g in range(G):
+            np.testing.assert_allclose(dw[g * og:(g + 1) * og], dwd[g * og:(g + 1) * og, :, :, g * cg:(g + 1) * cg], atol=1e-13)
+    with pytest.raises(ValueError):
+        L.conv2d_forward(x, rng.standard_normal((Cout, k, k, 5)), None, 1, 1)
