@@ -70,6 +70,10 @@ enum {
                                         CD_ARCH_RESNET_BOTTLENECK (ResNet-18/34: the smaller model of the pairs of
                                         different architectures in Section 5); projection shortcut where the
                                         stride or the width changes */
+  CD_ARCH_RESNEXT = 6,           /* CD_ARCH_RESNET_BOTTLENECK with a grouped 3x3 convolution (aggregated
+                                    transformations; the largest model of the pairs of different architectures in
+                                    Section 5).  CD_BF16 only; the grouped convolution's channel count must be a
+                                    multiple of 8 and, above 128, of 128, with whole groups per 128 channels */
   CD_ARCH_TRANSFORMER = 4,       /* the encoder-decoder Transformer of Section 4 (Vaswani et al.): embedding of the shared
                                     vocabulary times sqrt(d_model) plus the sinusoidal position signal; encoder layers
                                     (self-attention, feed-forward), decoder layers (causal self-attention, attention over
@@ -103,6 +107,9 @@ typedef struct {
                                   /* tiny CNN: widths[0], widths[1] = the two conv widths  */
   int32_t blocks[CD_MAX_STAGES];  /* blocks per stage                                      */
   int32_t stem_width;             /* output channels of the stem convolution               */
+  int32_t groups;                 /* CD_ARCH_RESNEXT: groups of the 3x3 convolution        */
+  int32_t out_widths[CD_MAX_STAGES]; /* CD_ARCH_RESNEXT: output channels of a stage's blocks
+                                        (widths[] are those of its grouped convolution)    */
 } cd_arch_desc;
 
 /* kind of a parameter tensor */
@@ -126,6 +133,7 @@ typedef struct cd_model cd_model; /* opaque host object */
  * (ResNet-20: 32x32, widths 16/32/64, 3 blocks each, 10 classes), CD_ARCH_RESNET_BOTTLENECK
  * (ResNet-50: 224x224, widths 64..512, blocks 3/4/6/3, 1000 classes; Section 3),
  * CD_ARCH_TRANSFORMER_HEAD (d_model 512, d_ff 2048, vocabulary 32768: the base Transformer),
+ * CD_ARCH_RESNEXT (the 101-layer 32x8d model: blocks 3,4,23,3, grouped widths 256..2048 in 32 groups),
  * CD_ARCH_RESNET_BASIC_IMAGENET (ResNet-18: blocks 2,2,2,2, widths 64..512, 224x224, 1000 classes),
  * CD_ARCH_TRANSFORMER (the base model: 6 + 6 layers, d_model 512, 8 heads, d_ff 2048, vocabulary 32768,
  * 128 source and 128 target tokens per sentence). host. */

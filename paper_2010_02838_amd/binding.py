@@ -21,6 +21,7 @@ CD_BN_BATCH_STATS, CD_BN_RUNNING = 0, 1
 CD_ARCH_TINY_CNN, CD_ARCH_RESNET_BASIC, CD_ARCH_RESNET_BOTTLENECK, CD_ARCH_TRANSFORMER_HEAD = 0, 1, 2, 3
 CD_ARCH_TRANSFORMER = 4
 CD_ARCH_RESNET_BASIC_IMAGENET = 5
+CD_ARCH_RESNEXT = 6
 CD_MAX_STAGES, CD_NAME_LEN, CD_LOSS_MAX_PEERS = 4, 48, 8
 KERNEL_CLASSES = ["conv_fprop", "conv_dgrad", "conv_wgrad", "norm", "glue", "linear", "loss", "sgd", "conv_fprop_narrow",
                   "bn_apply", "conv_fprop_wide", "attention"]
@@ -31,7 +32,8 @@ class ArchDesc(ctypes.Structure):
     _fields_ = [("kind", ctypes.c_int32), ("classes", ctypes.c_int32), ("in_h", ctypes.c_int32),
                 ("in_w", ctypes.c_int32), ("n_stages", ctypes.c_int32),
                 ("widths", ctypes.c_int32 * CD_MAX_STAGES), ("blocks", ctypes.c_int32 * CD_MAX_STAGES),
-                ("stem_width", ctypes.c_int32)]
+                ("stem_width", ctypes.c_int32), ("groups", ctypes.c_int32),
+                ("out_widths", ctypes.c_int32 * CD_MAX_STAGES)]
 
 
 class TensorInfo(ctypes.Structure):
@@ -119,7 +121,7 @@ def arch_preset(kind, **overrides):
     a = ArchDesc()
     _check(lib.codistill_arch_preset(kind, ctypes.byref(a)))
     for k, v in overrides.items():
-        if k in ("widths", "blocks"):
+        if k in ("widths", "blocks", "out_widths"):
             for i, x in enumerate(v):
                 getattr(a, k)[i] = x
             if k == "widths" and a.kind != CD_ARCH_TINY_CNN:

@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcodistill.so")
-SOURCES = ["runtime.hip", "loss.hip", "sgd.hip", "kernels_simple.hip", "norm.hip", "layernorm.hip", "attention.hip", "conv_mfma.hip", "model.hip"]
+SOURCES = ["runtime.hip", "loss.hip", "sgd.hip", "kernels_simple.hip", "norm.hip", "layernorm.hip", "attention.hip", "conv_grouped.hip", "conv_mfma.hip", "model.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option",

@@ -129,6 +129,18 @@ void unpad_c8_to_c3(const float* in, float* out, int64_t n, hipStream_t s);
 // w[Cout][taps][Cin] -> wt[Cin][taps][Cout]
 void transpose_weight(const bf16_t* w, bf16_t* wt, int cout, int taps, int cin, hipStream_t s);
 
+// ---- conv_grouped.hip: a grouped convolution (Cin = Cout = C) as dense convolutions on channel slices ----
+// slices of grouped_slice_width(C) channels (C itself up to 128, else 128), each a whole number of groups
+int grouped_slice_width(int C);
+bool grouped_conv_supported(int C, int groups);
+// x [M][C] -> xs [C / SW][M][SW] and back (accumulate: added to what x holds)
+void slices_gather(const bf16_t* x, bf16_t* xs, int64_t M, int C, hipStream_t s);
+void slices_scatter(const bf16_t* xs, bf16_t* x, int64_t M, int C, bool accumulate, hipStream_t s);
+// w [C][taps][C / groups] -> wd [C / SW][SW][taps][SW], zero outside the groups' diagonal blocks
+void expand_group_weights(const bf16_t* w, bf16_t* wd, int C, int taps, int groups, hipStream_t s);
+// dwd [C / SW][SW][taps][SW] fp32 -> dw [C][taps][C / groups]: the diagonal blocks
+void extract_group_dw(const float* dwd, float* dw, int C, int taps, int groups, hipStream_t s);
+
 // ---- attention.hip: multi-head scaled dot-product attention and the token embedding (bf16 tensors) ----
 // q [S*Tq][.] and k, v [S*Tk][.] are bf16 row-major with row pitches ldq / ldkv (elements), already
 // pointing at their first column; head h owns columns h*dh .. (h+1)*dh.  out [S*Tq][.] with pitch ldo.

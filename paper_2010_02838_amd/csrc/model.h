@@ -30,6 +30,7 @@ struct Op {
   int key_tok0 = 0;    // OP_ATTN: first token column of the sentences the keys come from (their padding is masked)
   bool causal = false;
   bool tied = false;   // OP_LINEAR: the weight is another op's parameter (the embedding table)
+  int groups = 1;      // OP_CONV: groups of a grouped convolution (input and output channels are then equal)
 };
 
 struct ParamDesc {
@@ -58,6 +59,12 @@ struct Plan {
   size_t wpack = 0;           // bf16 models: re-laid-out weights (stem padding, dgrad transposes)
   size_t wpack_bytes = 0;
   size_t lin_dz = 0;          // bf16 models: bf16 copy of d loss / d logits for the dense-layer MFMA backward
+  // grouped convolutions (see conv_grouped.hip)
+  std::vector<size_t> gx;     // per op (save only): the op's input in slice-major form, kept for the weight gradient
+  size_t gtmp = 0;            // two slice-major tensors of scratch (output / gradients), each gtmp_bytes
+  size_t gtmp_bytes = 0;
+  size_t gw = 0;              // the dense per-slice filters of the op at hand
+  size_t gdw = 0;             // save only: the dense per-slice filter gradients of the op at hand (fp32)
   size_t total = 0;
 };
 

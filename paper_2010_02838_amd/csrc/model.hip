@@ -42,10 +42,11 @@ struct Builder {
     return add_param(n, kind, 1, sh, 0);
   }
   // ops
-  int conv(int x, int pw, int pb, int cout, int k, int stride, int pad, bool relu) {
+  int conv(int x, int pw, int pb, int cout, int k, int stride, int pad, bool relu, int groups = 1) {
     const TensorDesc& tx = m->tensors[x];
     Op o;
     o.kind = OP_CONV; o.x = x; o.pw = pw; o.pb = pb; o.k = k; o.stride = stride; o.pad = pad; o.relu = relu;
+    o.groups = groups;
     o.y = add_tensor((tx.h + 2 * pad - k) / stride + 1, (tx.w + 2 * pad - k) / stride + 1, cout);
     m->ops.push_back(o);
     return o.y;
@@ -206,8 +207,10 @@ BnP bn_params(Builder& b, const std::string& n, int c) {
 }
 
 void build_resnet(Builder& b, const cd_arch_desc& a) {
-  const bool bott = a.kind == CD_ARCH_RESNET_BOTTLENECK;
+  const bool next = a.kind == CD_ARCH_RESNEXT;   // bottleneck blocks with a grouped 3x3 and their own output widths
+  const bool bott = a.kind == CD_ARCH_RESNET_BOTTLENECK || next;
   const bool big_stem = bott || a.kind == CD_ARCH_RESNET_BASIC_IMAGENET;   // 7x7 stride 2 + max-pool
+  const int groups = next ? a.groups : 1;
   char name[64];
   int t, cin = a.stem_width;
   {
@@ -219,7 +222,7 @@ void build_resnet(Builder& b, const cd_arch_desc& a) {
   }
   for (int si = 0; si < a.n_stages; si++) {
     const int wd = a.widths[si];
-    const int cout = bott ? 4 * wd : wd;
+    const int cout = next ? a.out_widths[si] : (bott ? 4 * wd : wd);
     for (int bi = 0; bi < a.blocks[si]; bi++) {
       const int stride = (si > 0 && bi == 0) ? 2 : 1;
       snprintf(name, sizeof(name), "s%d.b%d", si + 1, bi);
@@ -230,7 +233,7 @@ void build_resnet(Builder& b, const cd_arch_desc& a) {
       BnP p1, p2, p3 = {-1, -1}, pdn = {-1, -1};
       if (bott) {
         w1 = b.conv_w(p + ".conv1", cin, wd, 1); p1 = bn_params(b, p + ".bn1", wd);
-        w2 = b.conv_w(p + ".conv2", wd, wd, 3);  p2 = bn_params(b, p + ".bn2", wd);
+        w2 = b.conv_w(p + ".conv2", wd / groups, wd, 3);  p2 = bn_params(b, p + ".bn2", wd);
         w3 = b.conv_w(p + ".conv3", wd, cout, 1); p3 = bn_params(b, p + ".bn3", cout);
       } else {
         w1 = b.conv_w(p + ".conv1", cin, wd, 3); p1 = bn_params(b, p + ".bn1", wd);
@@ -247,7 +250,7 @@ void build_resnet(Builder& b, const cd_arch_desc& a) {
       if (bott) {
         u = b.conv(t, w1, -1, wd, 1, 1, 0, false);
         u = b.bn(u, p1.g, p1.b, -1, true);
-        u = b.conv(u, w2, -1, wd, 3, stride, 1, false);
+        u = b.conv(u, w2, -1, wd, 3, stride, 1, false, groups);
         u = b.bn(u, p2.g, p2.b, -1, true);
         u = b.conv(u, w3, -1, cout, 1, 1, 0, false);
         t = b.bn(u, p3.g, p3.b, sc, true);
@@ -404,11 +407,36 @@ Plan make_plan(const cd_model* m, int64_t B, bool save) {
       }
       if ((q.kind == CD_P_LINEAR_W || q.kind == CD_P_EMBED_W) && (size_t)q.size > wmax) wmax = (size_t)q.size;
     }
+    for (const Op& o : m->ops)   // the dense per-slice filter of a grouped convolution, re-laid-out for its data gradient
+      if (o.kind == OP_CONV && o.groups > 1) {
+        const size_t sw = (size_t)grouped_slice_width(m->tensors[o.x].c);
+        if (sw * o.k * o.k * sw > wmax) wmax = sw * o.k * o.k * sw;
+      }
     p.wpack_bytes = align_up(wmax * 4 + 256, 256);  // also holds the fp32 padded stem weight gradient
     p.wpack = alloc(p.wpack_bytes);
     p.lin_dz = alloc((size_t)B * m->tensors[m->ops.back().y].per_sample() * 2);
   }
   p.aux.assign(m->ops.size(), 0);
+  p.gx.assign(m->ops.size(), 0);
+  {
+    size_t tmax = 0, wdmax = 0;
+    for (size_t i = 0; i < m->ops.size(); i++) {
+      const Op& o = m->ops[i];
+      if (o.kind != OP_CONV || o.groups <= 1) continue;
+      const size_t in_b = (size_t)B * m->tensors[o.x].per_sample() * 2, out_b = (size_t)B * m->tensors[o.y].per_sample() * 2;
+      if (in_b > tmax) tmax = in_b;
+      if (out_b > tmax) tmax = out_b;
+      const size_t wd = (size_t)m->tensors[o.x].c * o.k * o.k * grouped_slice_width(m->tensors[o.x].c);
+      if (wd > wdmax) wdmax = wd;
+      if (save) p.gx[i] = alloc(in_b);
+    }
+    if (tmax) {
+      p.gtmp_bytes = align_up(tmax, 256);
+      p.gtmp = alloc(2 * p.gtmp_bytes);
+      p.gw = alloc(wdmax * 2);
+      if (save) p.gdw = alloc(wdmax * 4);
+    }
+  }
   if (save) {
     p.partials_side = alloc(p.partials_bytes);
     for (int t = 1; t < nt; t++)
@@ -445,6 +473,10 @@ extern "C" int codistill_arch_preset(int kind, cd_arch_desc* out) {
     out->classes = 1000; out->in_h = out->in_w = 224; out->n_stages = 4; out->stem_width = 64;
     const int w[4] = {64, 128, 256, 512}, nb[4] = {3, 4, 6, 3};
     for (int i = 0; i < 4; i++) { out->widths[i] = w[i]; out->blocks[i] = nb[i]; }
+  } else if (kind == CD_ARCH_RESNEXT) {
+    out->classes = 1000; out->in_h = out->in_w = 224; out->n_stages = 4; out->stem_width = 64; out->groups = 32;
+    const int w[4] = {256, 512, 1024, 2048}, nb[4] = {3, 4, 23, 3};
+    for (int i = 0; i < 4; i++) { out->widths[i] = w[i]; out->out_widths[i] = w[i]; out->blocks[i] = nb[i]; }
   } else if (kind == CD_ARCH_RESNET_BASIC_IMAGENET) {
     out->classes = 1000; out->in_h = out->in_w = 224; out->n_stages = 4; out->stem_width = 64;
     const int w[4] = {64, 128, 256, 512};
@@ -466,8 +498,8 @@ extern "C" int codistill_model_create(const cd_arch_desc* a, int dtype, cd_model
   CD_REQUIRE(a != nullptr && out != nullptr, "model_create: NULL pointer argument");
   CD_REQUIRE(dtype == CD_F32 || dtype == CD_BF16, "model_create: unknown dtype %d", dtype);
   CD_REQUIRE(a->kind == CD_ARCH_TINY_CNN || a->kind == CD_ARCH_RESNET_BASIC || a->kind == CD_ARCH_RESNET_BOTTLENECK ||
-                 a->kind == CD_ARCH_RESNET_BASIC_IMAGENET || a->kind == CD_ARCH_TRANSFORMER_HEAD ||
-                 a->kind == CD_ARCH_TRANSFORMER,
+                 a->kind == CD_ARCH_RESNET_BASIC_IMAGENET || a->kind == CD_ARCH_RESNEXT ||
+                 a->kind == CD_ARCH_TRANSFORMER_HEAD || a->kind == CD_ARCH_TRANSFORMER,
              "model_create: unknown architecture kind %d", a->kind);
   CD_REQUIRE(a->classes >= 1 && a->classes <= (1 << 24), "model_create: classes=%d out of range", a->classes);
   CD_REQUIRE(a->in_h >= 1 && a->in_w >= 1 && a->in_h <= 4096 && a->in_w <= 4096,
@@ -494,6 +526,16 @@ extern "C" int codistill_model_create(const cd_arch_desc* a, int dtype, cd_model
     for (int i = 0; i < a->n_stages; i++)
       CD_REQUIRE(a->widths[i] >= 1 && a->widths[i] <= 4096 && a->blocks[i] >= 1 && a->blocks[i] <= 64,
                  "model_create: stage %d width/blocks out of range", i);
+    if (a->kind == CD_ARCH_RESNEXT) {
+      if (dtype != CD_BF16) return set_error(CD_ERR_UNSUPPORTED, "model_create: grouped convolutions are implemented for CD_BF16 only");
+      for (int i = 0; i < a->n_stages; i++) {
+        CD_REQUIRE(a->out_widths[i] >= 1 && a->out_widths[i] <= 16384, "model_create: stage %d output width out of range", i);
+        if (!grouped_conv_supported(a->widths[i], a->groups))
+          return set_error(CD_ERR_UNSUPPORTED,
+                           "model_create: stage %d: %d channels in %d groups (need a multiple of 8 channels, of 128 above "
+                           "128, and whole groups per 128 channels)", i, a->widths[i], a->groups);
+      }
+    }
   }
   cd_model* m = new cd_model();
   m->arch = *a;
@@ -659,6 +701,36 @@ extern "C" int codistill_forward(const cd_model* m, const void* params, const vo
     switch (o.kind) {
       case OP_CONV: {
         ConvGeom g = conv_geom(m, o, batch);
+        if (o.groups > 1) {
+          // grouped: slice-major copy of the input, dense per-slice filters, one dense convolution per slice of
+          // channels, copy back (conv_grouped.hip); the BatchNorm behind it takes its statistics from the tensor
+          if (dt != CD_BF16 || force_simple() || o.pb >= 0 || o.relu || g.Cin != g.Cout)
+            return set_error(CD_ERR_UNSUPPORTED, "forward: this grouped convolution has no kernel (bf16, no bias, Cin = Cout)");
+          const int C = g.Cin, sw = grouped_slice_width(C), ns = C / sw;
+          const int64_t Min = batch * g.H * g.W, Mout = g.M();
+          bf16_t* tmp0 = reinterpret_cast<bf16_t*>(c.ws + c.plan.gtmp);
+          bf16_t* tmp1 = reinterpret_cast<bf16_t*>(c.ws + c.plan.gtmp + c.plan.gtmp_bytes);
+          bf16_t* xs = c.plan.gx[oi] ? reinterpret_cast<bf16_t*>(c.ws + c.plan.gx[oi]) : tmp0;
+          bf16_t* wd = reinterpret_cast<bf16_t*>(c.ws + c.plan.gw);
+          {
+            ProfScope pr(CD_K_GLUE, c.s, 0, 2.0 * (double)(Min + Mout) * C * 2);
+            slices_gather(static_cast<const bf16_t*>(in), xs, Min, C, c.s);
+            expand_group_weights(static_cast<const bf16_t*>(c.P(o.pw)), wd, C, g.kh * g.kw, o.groups, c.s);
+          }
+          ConvGeom gs = g;
+          gs.Cin = gs.Cout = sw;
+          {
+            ProfScope pr(CD_K_CONV_FPROP, c.s, 2.0 * Mout * C * (double)sw * g.kh * g.kw, 2.0 * (double)(Min + Mout) * C);
+            for (int sl = 0; sl < ns; sl++)
+              conv_fprop_mfma(xs + (int64_t)sl * Min * sw, wd + (int64_t)sl * sw * g.kh * g.kw * sw, nullptr, false,
+                              tmp1 + (int64_t)sl * Mout * sw, gs, nullptr, c.s);
+          }
+          {
+            ProfScope pr(CD_K_GLUE, c.s, 0, 2.0 * (double)Mout * C * 2);
+            slices_scatter(tmp1, static_cast<bf16_t*>(out), Mout, C, false, c.s);
+          }
+          break;
+        }
         if (use_mfma(m, g) && !(o.relu && o.pb < 0)) {   // (a fused ReLU comes with a bias in every graph built here)
           const bf16_t* src = static_cast<const bf16_t*>(in);
           const bf16_t* w = static_cast<const bf16_t*>(c.P(o.pw));
@@ -951,6 +1023,43 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
       }
       case OP_CONV: {
         ConvGeom g = conv_geom(m, o, batch);
+        if (o.groups > 1) {
+          if (dt != CD_BF16 || force_simple() || !c.plan.gx[i] || o.x == 0)
+            return set_error(CD_ERR_UNSUPPORTED, "backward: this grouped convolution has no kernel");
+          const int C = g.Cin, sw = grouped_slice_width(C), ns = C / sw, taps = g.kh * g.kw;
+          const int64_t Min = batch * g.H * g.W, Mout = g.M();
+          bf16_t* dys = reinterpret_cast<bf16_t*>(c.ws + c.plan.gtmp);
+          bf16_t* dxs = reinterpret_cast<bf16_t*>(c.ws + c.plan.gtmp + c.plan.gtmp_bytes);
+          const bf16_t* xs = reinterpret_cast<const bf16_t*>(c.ws + c.plan.gx[i]);
+          bf16_t* wd = reinterpret_cast<bf16_t*>(c.ws + c.plan.gw);
+          float* dwd = reinterpret_cast<float*>(c.ws + c.plan.gdw);
+          {
+            ProfScope pr(CD_K_GLUE, c.s, 0, 2.0 * (double)Mout * C * 2);
+            slices_gather(static_cast<const bf16_t*>(dy), dys, Mout, C, c.s);
+            expand_group_weights(static_cast<const bf16_t*>(c.P(o.pw)), wd, C, taps, o.groups, c.s);
+          }
+          ConvGeom gs = g;
+          gs.Cin = gs.Cout = sw;
+          const int64_t wsl = (int64_t)sw * taps * sw;   // elements of one slice's dense filter
+          {
+            ProfScope pr(CD_K_CONV_WGRAD, c.s, 2.0 * Mout * C * (double)sw * taps, 2.0 * (double)(Min + Mout) * C);
+            for (int sl = 0; sl < ns; sl++)
+              conv_wgrad_mfma(xs + (int64_t)sl * Min * sw, dys + (int64_t)sl * Mout * sw, dwd + sl * wsl, gs, c.partials(),
+                              c.plan.partials_bytes, c.s);
+            extract_group_dw(dwd, G(o.pw), C, taps, o.groups, c.s);
+          }
+          {
+            ProfScope pr(CD_K_CONV_DGRAD, c.s, 2.0 * Mout * C * (double)sw * taps, 2.0 * (double)(Min + Mout) * C);
+            for (int sl = 0; sl < ns; sl++)
+              conv_dgrad_mfma(dys + (int64_t)sl * Mout * sw, wd + sl * wsl, c.wpack(), dxs + (int64_t)sl * Min * sw, gs, false,
+                              c.s);
+          }
+          {
+            ProfScope pr(CD_K_GLUE, c.s, 0, 2.0 * (double)Min * C * (acc ? 3 : 2));
+            slices_scatter(dxs, static_cast<bf16_t*>(dx), Min, C, acc, c.s);
+          }
+          break;
+        }
         if (o.relu && !relu_done[o.y]) {
           ProfScope pr(CD_K_GLUE, c.s, 0, (double)g.M() * g.Cout * m->esize() * 3);
           relu_bwd_inplace(dt, dy, c.act(o.y), g.M() * g.Cout, c.s);

@@ -26,6 +26,16 @@ def _table(model):
     return [(p["name"], p["shape"], p["kind"], p["fan_in"]) for p in model.params]
 
 
+def test_grouped_convolution_limits_are_reported():
+    # grouped convolutions: bf16 only; whole groups per slice of 128 channels
+    a = B.arch_preset(B.CD_ARCH_RESNEXT)
+    h = ctypes.c_void_p()
+    assert B.lib.codistill_model_create(ctypes.byref(a), B.CD_F32, ctypes.byref(h)) == B.CD_ERR_UNSUPPORTED
+    bad = B.arch_preset(B.CD_ARCH_RESNEXT, widths=[192, 512, 1024, 2048])      # 192 is no multiple of 128
+    assert B.lib.codistill_model_create(ctypes.byref(bad), B.CD_BF16, ctypes.byref(h)) == B.CD_ERR_UNSUPPORTED
+    assert b"groups" in B.lib.codistill_last_error()
+
+
 @pytest.mark.parametrize("dtype", [B.CD_F32, B.CD_BF16])
 def test_param_tables_match_oracle(dtype):
     cases = [
@@ -33,12 +43,17 @@ def test_param_tables_match_oracle(dtype):
         (B.arch_preset(B.CD_ARCH_RESNET_BASIC), nets.resnet20()),
         (B.arch_preset(B.CD_ARCH_RESNET_BOTTLENECK), nets.resnet50()),
         (B.arch_preset(B.CD_ARCH_RESNET_BASIC_IMAGENET), nets.resnet18()),
+        (B.arch_preset(B.CD_ARCH_RESNEXT), nets.resnext()),
+        (B.arch_preset(B.CD_ARCH_RESNEXT, widths=[128, 256, 512, 1024], blocks=[3, 4, 6, 3]),
+         nets.resnext(widths=(128, 256, 512, 1024), blocks=(3, 4, 6, 3))),
         (B.arch_preset(B.CD_ARCH_RESNET_BASIC, widths=[4, 8, 16], blocks=[2, 1, 1], stem_width=4),
          nets.resnet20(widths=(4, 8, 16), blocks=(2, 1, 1))),
         (B.arch_preset(B.CD_ARCH_RESNET_BOTTLENECK, widths=[4, 8, 8, 16], blocks=[2, 1, 1, 1], stem_width=8, classes=7),
          nets.resnet50(classes=7, widths=(4, 8, 8, 16), blocks=(2, 1, 1, 1), stem=8)),
     ]
     for arch, ref in cases:
+        if arch.kind == B.CD_ARCH_RESNEXT and dtype != B.CD_BF16:
+            continue
         m = B.Model(arch, dtype)
         assert _table(m) == [(n, tuple(s), k, f) for n, s, k, f in ref.params]
         assert sum(p["size"] for p in m.params) == ref.n_params()

@@ -75,6 +75,14 @@ SMALL = {
                         5, 72, 10),
     "basic_mfma": (dict(kind=1, widths=[16, 24, 40], blocks=[1, 2, 1], stem_width=16),
                    lambda: nets.resnet20(widths=(16, 24, 40), blocks=(1, 2, 1)), 7, 20, 10),
+    # grouped 3x3 convolutions (the ResNeXt family): 4, 8 and 12 channels per group in one slice of channels ...
+    "resnext": (dict(kind=6, widths=[16, 32, 32, 48], out_widths=[24, 32, 48, 64], groups=4, blocks=[2, 1, 1, 1], stem_width=16),
+                lambda: nets.resnext(classes=10, widths=(16, 32, 32, 48), outs=(24, 32, 48, 64), groups=4, blocks=(2, 1, 1, 1),
+                                     stem=16), 5, 72, 10),
+    # ... and 256 channels in two slices of 128 (four groups of 32 each), stride 1 and stride 2
+    "resnext_slices": (dict(kind=6, widths=[256, 256], out_widths=[64, 64], groups=8, blocks=[1, 1], stem_width=32),
+                       lambda: nets.resnext(classes=10, widths=(256, 256), outs=(64, 64), groups=8, blocks=(1, 1), stem=32),
+                       3, 40, 10),
     # basic blocks behind the 7x7 stem and the max-pool (the ResNet-18 family)
     "basic_imagenet_mfma": (dict(kind=5, widths=[16, 24, 32, 40], blocks=[1, 2, 1, 1], stem_width=16),
                             lambda: nets.resnet18(classes=10, widths=(16, 24, 32, 40), blocks=(1, 2, 1, 1), stem=16),
