@@ -246,9 +246,11 @@ def main():
                     help="resnet50 (default): the headline metric.  transformer_head: the output block of the base "
                          "Transformer (feed-forward sublayer, residual, LayerNorm, vocabulary projection) on 8192 target "
                          "tokens, a separate JSON line with its own metric")
-    ap.add_argument("--peer", default="resnet50", choices=["resnet50", "resnet18"],
+    ap.add_argument("--peer", default="resnet50", choices=["resnet50", "resnet18", "resnext101"],
                     help="architecture of the stale peer of the ResNet-50 workload (Section 5 pairs different "
                          "architectures); the default line is the two-ResNet-50 step")
+    ap.add_argument("--local", default="resnet50", choices=["resnet50", "resnext101"],
+                    help="architecture of the local model of that workload (default: ResNet-50, the benchmarked step)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch a plain 1 GiB -> 1 GiB elementwise copy three times (the known-size "
                          "kernel that hardware-counter byte counts are scaled by)")
@@ -280,9 +282,10 @@ def main():
         torch.cuda.empty_cache()
     loss_cfg5 = loss_kernel_cfg5(B, torch, dev)
     batch, res, classes = args.batch, 224, 1000
-    arch = B.arch_preset(B.CD_ARCH_RESNET_BOTTLENECK)
-    peer_arch = arch if args.peer == "resnet50" else B.arch_preset(B.CD_ARCH_RESNET_BASIC_IMAGENET)
-    model, peer = B.Model(arch, B.CD_BF16), B.Model(peer_arch, B.CD_BF16)
+    kinds = {"resnet50": B.CD_ARCH_RESNET_BOTTLENECK, "resnet18": B.CD_ARCH_RESNET_BASIC_IMAGENET,
+             "resnext101": B.CD_ARCH_RESNEXT}
+    default_pair = args.peer == "resnet50" and args.local == "resnet50"
+    model, peer = B.Model(B.arch_preset(kinds[args.local]), B.CD_BF16), B.Model(B.arch_preset(kinds[args.peer]), B.CD_BF16)
     table = model.param_table()
     r = StepRunner(model, [peer], batch, dev)
     r.load(pack_flat(model, synth.he_init(table, 1)), [pack_flat(peer, synth.he_init(peer.param_table(), 2))])
@@ -321,12 +324,12 @@ def main():
     bn = prof["bn_apply"]
     roofline = roofline_of(bn["flops"], bn["bytes"], bn["ms"], bn["launches"],
                            "bn_apply_k<bf16,8,true> (BatchNorm forward: normalise, add the residual, ReLU, bit mask)",
-                           ROOFLINE_TRAFFIC_BYTES if args.peer == "resnet50" else None)
+                           ROOFLINE_TRAFFIC_BYTES if default_pair else None)
     roofline["launches_per_step"] = bn["launches"] / psteps
     cw = prof["conv_fprop_wide"]
     roofline_conv = roofline_of(cw["flops"], cw["bytes"], cw["ms"], cw["launches"],
                                 "igemm_kernel<0,128,256,2,2,false,true,1,false,0,false> (bf16 implicit-GEMM conv fprop on "
-                                "128x256 tiles, BatchNorm column sums in the epilogue)", ROOFLINE_CONV_TRAFFIC_BYTES if args.peer == "resnet50" else None)
+                                "128x256 tiles, BatchNorm column sums in the epilogue)", ROOFLINE_CONV_TRAFFIC_BYTES if default_pair else None)
     roofline_conv["launches_per_step"] = cw["launches"] / psteps
     classes_ms = {k: round(v["ms"] / psteps, 4) for k, v in prof.items()}
     hbm = {}
@@ -336,13 +339,13 @@ def main():
             hbm[k]["frac"] = hbm[k]["GB/s"] / PEAK_HBM_GBS
 
     out = {
-        "metric": "codistill-step samples/sec on 1 MI355X (ResNet-50, 224^2, bs256)",
+        "metric": "codistill-step samples/sec on 1 MI355X (%s, 224^2, bs%d)" % ("ResNet-50" if args.local == "resnet50" else args.local, batch),
         "value": batch / (ms_per_step * 1e-3), "unit": "samples/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "resnet50_codistill_step", "batch": batch, "resolution": res, "classes": classes,
-                   "models": "2 x ResNet-50 (local fwd+bwd+SGD, peer fwd)" if args.peer == "resnet50" else
-                             "ResNet-50 (local fwd+bwd+SGD) + ResNet-18 (peer fwd)", "alpha": alpha,
+                   "models": "2 x ResNet-50 (local fwd+bwd+SGD, peer fwd)" if default_pair else
+                             "%s (local fwd+bwd+SGD) + %s (peer fwd)" % (args.local, args.peer), "alpha": alpha,
                    "distillation": "mse_logits", "lr": lr, "momentum": mu},
         "loss": [float(v) for v in loss[:3]],
         "roofline": roofline,

@@ -196,3 +196,66 @@ def test_run_to_run_determinism(full):
     np.testing.assert_array_equal(unpack_flat(c.model, r.grads.cpu().numpy()), got["grad"])
     np.testing.assert_array_equal(r.logits.cpu().numpy(), got["logits"])
     np.testing.assert_array_equal(r.loss.cpu().numpy()[:3].astype(np.float64), got["loss"])
+
+
+def test_resnext101_grouped_convolutions_sampled():
+    """The 101-layer 32x8d aggregated-transformation network at 224x224, batch 32: all 33 grouped convolutions run
+    with 2 to 16 slices of 128 channels (8 to 64 channels per group); sampled outputs, data gradients and filter
+    gradients as plain float64 sums over the group's channels, from the tensors the kernels consumed."""
+    c = Case(dict(kind=6), nets.resnext(), "bf16", 32, 224, 1000, jitter=0.0)
+    got = c.gpu(alpha=1.0, lr=0.1, mu=0.9)
+    ops, tensors = c.model.graph(c.batch)
+    rng = np.random.default_rng(5)
+    G = c.per_tensor(got["grad"])
+    names = [n for n, _, _, _ in c.ref_arch.params]
+    P = c.per_tensor(c.th.astype(np.float64))
+    grouped = [(i, o) for i, o in conv_ops(ops) if P[names[o["param_w"]]].shape[3] != tensors[o["x"]]["c"] and o["x"] > 0]
+    assert len(grouped) == 33
+    for i, o in grouped:
+        name = names[o["param_w"]]
+        w = P[name]                                    # [C][3][3][cg]
+        C, k, _, cg = w.shape
+        st, p = o["stride"], o["pad"]
+        x4, y4 = dev_tensor(c, tensors, o["x"]), dev_tensor(c, tensors, o["y"])
+        dy4, dx4 = dev_tensor(c, tensors, o["y"], grad=True), dev_tensor(c, tensors, o["x"], grad=True)
+        B, H, W, _ = x4.shape
+        Ho, Wo = y4.shape[1:3]
+        for _ in range(6):                             # outputs
+            b, ho, wo, n = (int(rng.integers(0, d)) for d in (B, Ho, Wo, C))
+            if rng.random() < 0.3:
+                b, ho, wo = B - 1, int(rng.choice([0, Ho - 1])), int(rng.choice([0, Wo - 1]))
+            c0 = n // cg * cg
+            h0, w0 = ho * st - p, wo * st - p
+            hs, ws, he, we = max(h0, 0), max(w0, 0), min(h0 + k, H), min(w0 + k, W)
+            terms = host(x4[b, hs:he, ws:we, c0:c0 + cg]) * w[n, hs - h0:he - h0, ws - w0:we - w0, :]
+            ref, rss = terms.sum(), np.sqrt((terms ** 2).sum())
+            out = float(y4[b, ho, wo, n].float())
+            assert abs(out - ref) <= BF16_STEP * abs(ref) + 1e-4 * rss + 1e-30, (i, name, "y", out, ref)
+        for _ in range(4):                             # data gradients (the input has this one reader)
+            b, h, wi, ci = (int(rng.integers(0, d)) for d in (B, H, W, C))
+            c0 = ci // cg * cg
+            ref, sq = 0.0, 0.0
+            for r in range(k):
+                for s in range(k):
+                    hn, wn = h + p - r, wi + p - s
+                    if hn % st or wn % st or not (0 <= hn // st < Ho and 0 <= wn // st < Wo):
+                        continue
+                    terms = host(dy4[b, hn // st, wn // st, c0:c0 + cg]) * w[c0:c0 + cg, r, s, ci - c0]
+                    ref += terms.sum()
+                    sq += (terms ** 2).sum()
+            out = float(dx4[b, h, wi, ci].float())
+            assert abs(out - ref) <= BF16_STEP * abs(ref) + 1e-4 * np.sqrt(sq) + 1e-30, (i, name, "dx", out, ref)
+        for _ in range(2):                             # filter gradients: sums over every pixel of the batch
+            n, r, s, j = int(rng.integers(0, C)), int(rng.integers(0, k)), int(rng.integers(0, k)), int(rng.integers(0, cg))
+            ci = n // cg * cg + j
+            ho, wo = np.arange(Ho), np.arange(Wo)
+            hv = ho[(ho * st - p + r >= 0) & (ho * st - p + r < H)]
+            wv = wo[(wo * st - p + s >= 0) & (wo * st - p + s < W)]
+            a = host(dy4[:, hv[0]:hv[-1] + 1, wv[0]:wv[-1] + 1, n])
+            bsl = x4[:, hv[0] * st - p + r:hv[-1] * st - p + r + 1:st, wv[0] * st - p + s:wv[-1] * st - p + s + 1:st, ci]
+            terms = a * host(bsl)
+            ref, rss = terms.sum(), np.sqrt((terms ** 2).sum())
+            out = float(G[name][n, r, s, j])
+            assert abs(out - ref) <= 1e-3 * abs(ref) + 1e-3 * rss, (i, name, "dw", (n, r, s, j), out, ref)
+    del c.runner
+    torch.cuda.empty_cache()
