@@ -185,6 +185,10 @@ def transformer(args, B, synth, StepRunner, pack_flat, torch, dev):
     that takes the most time of the step."""
     S, Ts, Tt, vocab = 64, 128, 128, 32768
     arch = B.arch_preset(B.CD_ARCH_TRANSFORMER)
+    big = args.transformer_size == "big"
+    if big:   # the model Section 4 trains: d_model 1024, 16 heads, d_ff 4096; about the 3.8 k tokens per GPU of its recipe
+        S = 30
+        arch = B.arch_preset(B.CD_ARCH_TRANSFORMER, widths=[1024, 4096, 16])
     model, peer = B.Model(arch, B.CD_BF16), B.Model(arch, B.CD_BF16)
     table = model.param_table()
     r = StepRunner(model, [peer], S, dev)
@@ -220,13 +224,16 @@ def transformer(args, B, synth, StepRunner, pack_flat, torch, dev):
     roof = roofline_of(p["flops"], p["bytes"], p["ms"], p["launches"], "kernel class '%s' of the library's timer" % top, None)
     roof["launches_per_step"] = p["launches"] / psteps
     return {
-        "metric": "codistill-step target tokens/sec on 1 MI355X (Transformer-base, 64 x (128 + 128) tokens, vocab 32768)",
+        "metric": "codistill-step target tokens/sec on 1 MI355X (Transformer-%s, %d x (128 + 128) tokens, vocab 32768)"
+                  % ("big" if big else "base", S),
         "value": S * Tt / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": "transformer_base_codistill_step", "sentences": S, "source_tokens": Ts, "target_tokens": Tt,
-                   "d_model": 512, "heads": 8, "d_ff": 2048, "layers": "6+6", "vocab": vocab,
-                   "models": "2 x Transformer-base (local fwd+bwd+Adam, peer fwd)", "alpha": 1.0, "label_smoothing": 0.1,
+        "config": {"workload": "transformer_%s_codistill_step" % ("big" if big else "base"), "sentences": S,
+                   "source_tokens": Ts, "target_tokens": Tt, "d_model": arch.widths[0], "heads": arch.widths[2],
+                   "d_ff": arch.widths[1], "layers": "6+6", "vocab": vocab,
+                   "models": "2 x Transformer-%s (local fwd+bwd+Adam, peer fwd)" % ("big" if big else "base"), "alpha": 1.0,
+                   "label_smoothing": 0.1,
                    "distillation": "kl", "optimizer": "adam(0.9, 0.98, 1e-8), lr 5e-4"},
         "loss": [float(v) for v in loss[:3]],
         "roofline": roof,
@@ -246,6 +253,8 @@ def main():
                     help="resnet50 (default): the headline metric.  transformer_head: the output block of the base "
                          "Transformer (feed-forward sublayer, residual, LayerNorm, vocabulary projection) on 8192 target "
                          "tokens, a separate JSON line with its own metric")
+    ap.add_argument("--transformer-size", default="base", choices=["base", "big"],
+                    help="--workload transformer: base (64 sentences) or big (d_model 1024, 16 heads, d_ff 4096; 30 sentences)")
     ap.add_argument("--peer", default="resnet50", choices=["resnet50", "resnet18", "resnext101"],
                     help="architecture of the stale peer of the ResNet-50 workload (Section 5 pairs different "
                          "architectures); the default line is the two-ResNet-50 step")
