@@ -258,6 +258,8 @@ def main():
     ap.add_argument("--peer", default="resnet50", choices=["resnet50", "resnet18", "resnext101"],
                     help="architecture of the stale peer of the ResNet-50 workload (Section 5 pairs different "
                          "architectures); the default line is the two-ResNet-50 step")
+    ap.add_argument("--n-way", type=int, default=2,
+                    help="models that codistill (Section 5: 2, 3, 4, 8): the step runs n-1 peer forwards; default 2")
     ap.add_argument("--local", default="resnet50", choices=["resnet50", "resnext101"],
                     help="architecture of the local model of that workload (default: ResNet-50, the benchmarked step)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -293,11 +295,15 @@ def main():
     batch, res, classes = args.batch, 224, 1000
     kinds = {"resnet50": B.CD_ARCH_RESNET_BOTTLENECK, "resnet18": B.CD_ARCH_RESNET_BASIC_IMAGENET,
              "resnext101": B.CD_ARCH_RESNEXT}
-    default_pair = args.peer == "resnet50" and args.local == "resnet50"
+    if not 2 <= args.n_way <= 9:
+        raise SystemExit("--n-way: 2 to 9 models (the loss takes up to 8 peers)")
+    default_pair = args.peer == "resnet50" and args.local == "resnet50" and args.n_way == 2
     model, peer = B.Model(B.arch_preset(kinds[args.local]), B.CD_BF16), B.Model(B.arch_preset(kinds[args.peer]), B.CD_BF16)
     table = model.param_table()
-    r = StepRunner(model, [peer], batch, dev)
-    r.load(pack_flat(model, synth.he_init(table, 1)), [pack_flat(peer, synth.he_init(peer.param_table(), 2))])
+    npeers = args.n_way - 1
+    r = StepRunner(model, [peer] * npeers, batch, dev)
+    r.load(pack_flat(model, synth.he_init(table, 1)),
+           [pack_flat(peer, synth.he_init(peer.param_table(), 2 + j)) for j in range(npeers)])
     x = torch.empty(batch, res, res, 3, dtype=torch.bfloat16, device=dev)
     for b0 in range(0, batch, 32):       # images ~ N(0,1), generated on the host in slices
         n = min(32, batch - b0)
@@ -354,7 +360,7 @@ def main():
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "resnet50_codistill_step", "batch": batch, "resolution": res, "classes": classes,
                    "models": "2 x ResNet-50 (local fwd+bwd+SGD, peer fwd)" if default_pair else
-                             "%s (local fwd+bwd+SGD) + %s (peer fwd)" % (args.local, args.peer), "alpha": alpha,
+                             "%s (local fwd+bwd+SGD) + %d x %s (peer fwd)" % (args.local, npeers, args.peer), "alpha": alpha,
                    "distillation": "mse_logits", "lr": lr, "momentum": mu},
         "loss": [float(v) for v in loss[:3]],
         "roofline": roofline,
