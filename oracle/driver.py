@@ -16,7 +16,8 @@ def codistill_train(arch, thetas, batches, steps, exchange_every, alpha, lr, mom
                     weight_decay=0.0, label_smoothing=0.0, dist="mse"):
     """thetas: list of n flat parameter vectors (one per model).
     batches(k, i) -> (x, y): the minibatch of model i at update k.
-    alpha, lr, weight_decay: numbers or functions of the update index k.
+    alpha, lr, weight_decay, label_smoothing: numbers or functions of the update index k (Section 4 grows alpha and
+    decays the L2 term or, for translation, the label smoothing over training).
     Returns dict(theta=[...], v=[...], loss=[steps][n][3], refreshed=[update indices of exchanges])."""
     n = len(thetas)
     sched = lambda s, k: s(k) if callable(s) else s
@@ -33,7 +34,7 @@ def codistill_train(arch, thetas, batches, steps, exchange_every, alpha, lr, mom
             x, y = batches(k, i)
             peers = [stale[j] for j in range(n) if j != i]
             out = codistill_step(arch, theta[i], peers, x, y, sched(alpha, k), sched(lr, k), momentum, v=v[i],
-                                 weight_decay=sched(weight_decay, k), label_smoothing=label_smoothing, dist=dist)
+                                 weight_decay=sched(weight_decay, k), label_smoothing=sched(label_smoothing, k), dist=dist)
             row.append(out["loss"])
             new_theta.append(out["theta"])
             new_v.append(out["v"])

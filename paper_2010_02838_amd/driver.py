@@ -47,7 +47,7 @@ class CodistillTrainer:
         for i, r in enumerate(self.runners):
             x, y = batches(k, i)
             r.step(x, y, sched(alpha), sched(lr), momentum, weight_decay=sched(weight_decay),
-                   label_smoothing=label_smoothing, dist_kind=dist_kind)
+                   label_smoothing=sched(label_smoothing), dist_kind=dist_kind)
             out.append(r.loss.clone())
         self.k += 1
         return out

@@ -23,16 +23,17 @@ def test_tiny_cnn_fp32_trajectory(n, T):
     th = [synth.he_init(arch.params, 1 + i, jitter=0.05) for i in range(n)]
     host = lambda k, i: (synth.images(batch, res, res, 3, seed=100 + 7 * k + i), synth.labels(batch, 10, seed=300 + 7 * k + i))
     alpha, lr, wd = (lambda k: 0.5 * 1.1 ** k), (lambda k: 0.1 / (1 + 0.5 * k)), (lambda k: 1e-3 * 0.5 ** k)
+    smooth = lambda k: 0.2 * 0.5 ** k
     ref = codistill_train(arch, [t.astype(np.float64) for t in th],
                           lambda k, i: (host(k, i)[0].astype(np.float64), host(k, i)[1]), steps, T, alpha, lr, 0.9,
-                          weight_decay=wd)
+                          weight_decay=wd, label_smoothing=smooth)
     kw = dict(in_h=res, in_w=res)
     models = [B.Model(B.arch_preset(B.CD_ARCH_TINY_CNN, **kw), B.CD_F32) for _ in range(n)]
     tr = CodistillTrainer(models, batch)
     tr.load([pack_flat(models[i], th[i]) for i in range(n)])
     dev = lambda k, i: (torch.from_numpy(host(k, i)[0]).to("cuda:0"), torch.from_numpy(host(k, i)[1]).to("cuda:0"))
     for k in range(steps):
-        losses = tr.step(dev, T, alpha, lr, 0.9, weight_decay=wd)
+        losses = tr.step(dev, T, alpha, lr, 0.9, weight_decay=wd, label_smoothing=smooth)
         for i in range(n):
             got = losses[i].cpu().numpy()[:3]
             np.testing.assert_allclose(got, ref["loss"][k][i], rtol=2e-4, atol=1e-6)

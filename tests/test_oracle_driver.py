@@ -36,7 +36,9 @@ def test_alpha_zero_is_independent_sgd():
 def test_stale_copies_and_simultaneous_updates():
     th = _thetas(3)
     T, steps = 2, 5
-    r = codistill_train(ARCH, th, _batches, steps, T, lambda k: 0.5 * 1.1 ** k, lambda k: 0.1 / (1 + k), 0.9)
+    smooth = lambda k: 0.2 * 0.5 ** k          # label smoothing decayed over training (Section 4, translation)
+    r = codistill_train(ARCH, th, _batches, steps, T, lambda k: 0.5 * 1.1 ** k, lambda k: 0.1 / (1 + k), 0.9,
+                        label_smoothing=smooth)
     assert r["refreshed"] == [0, 2, 4]
     # replay by hand: the copies are the parameters at the last multiple of T, taken before that update
     theta, v = [t.copy() for t in th], [None] * 3
@@ -47,7 +49,7 @@ def test_stale_copies_and_simultaneous_updates():
         for i in range(3):
             x, y = _batches(k, i)
             out = codistill_step(ARCH, theta[i], [stale[j] for j in range(3) if j != i], x, y, 0.5 * 1.1 ** k,
-                                 0.1 / (1 + k), 0.9, v=v[i])
+                                 0.1 / (1 + k), 0.9, v=v[i], label_smoothing=smooth(k))
             np.testing.assert_allclose(r["loss"][k][i], out["loss"], rtol=1e-14)
             new.append((out["theta"], out["v"]))
         theta, v = [a for a, _ in new], [b for _, b in new]
