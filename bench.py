@@ -33,8 +33,8 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch of the two roofline kernels from hardware counters (two rocprofv3 --pmc passes of
 # this script, FETCH_SIZE then WRITE_SIZE, each scaled by what the same counter read for the 1 GiB copy of
 # --copy-calibration).  Valid only for the kernels the counters were taken on: set to None when one changes.
-ROOFLINE_TRAFFIC_BYTES = 260.2e6        # bn_apply_k<bf16,8,true>: FETCH_SIZE 76162.0 KiB x 2.000 + WRITE_SIZE 101798.0 KiB x 1.000
-ROOFLINE_CONV_TRAFFIC_BYTES = 221.0e6   # igemm_kernel<0,128,256,...>: FETCH_SIZE 40994.2 KiB x 2.000 + WRITE_SIZE 133859.5 KiB x 1.000
+ROOFLINE_TRAFFIC_BYTES = 260.2e6        # bn_apply_k<bf16,8,true>: FETCH_SIZE 76161.8 KiB x 2.000 + WRITE_SIZE 101798.1 KiB x 1.000
+ROOFLINE_CONV_TRAFFIC_BYTES = 221.5e6   # igemm_kernel<0,128,256,...>: FETCH_SIZE 41240.6 KiB x 2.000 + WRITE_SIZE 133859.5 KiB x 1.000
 
 
 def roofline_of(flops, nbytes, ms, launches, kernel, traffic):
