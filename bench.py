@@ -37,7 +37,7 @@ ROOFLINE_TRAFFIC_BYTES = 260.2e6        # bn_apply_k<bf16,8,true>: FETCH_SIZE 76
 ROOFLINE_CONV_TRAFFIC_BYTES = 221.5e6   # igemm_kernel<0,128,256,...>: FETCH_SIZE 41240.6 KiB x 2.000 + WRITE_SIZE 133859.5 KiB x 1.000
 
 
-def roofline_of(flops, nbytes, ms, launches, kernel, traffic):
+def roofline_of(flops, nbytes, ms, launches, kernel, traffic, event_overhead_us=None):
     """Roofline entry of one kernel class from its algorithmic flops and HBM bytes (every operand once) and
     the HIP-event time of its launches.  The bound is the roof its arithmetic intensity puts it under: HBM
     below the machine's ridge (peak flops / peak bytes), MFMA above; `achieved` is in that roof's unit and the
@@ -57,7 +57,10 @@ def roofline_of(flops, nbytes, ms, launches, kernel, traffic):
             "flop_per_launch": flops / max(launches, 1),
             "intensity_flop_per_byte": intensity, "ridge_flop_per_byte": ridge,
             "mfma_tflops": tflops, "mfma_frac": tflops / PEAK_BF16_TFLOPS,
-            "kernel": kernel, "avg_launch_us": ms / max(launches, 1) * 1e3}
+            "kernel": kernel, "avg_launch_us": ms / max(launches, 1) * 1e3,
+            # what the event pair itself adds to every launch (measured around an empty kernel): `achieved` keeps it
+            # in, so a profiler's kernel durations are shorter by about this much
+            "event_pair_overhead_us": event_overhead_us}
 
 
 def cpu_baseline(seconds_hint=20.0):
@@ -337,14 +340,16 @@ def main():
     prof = B.profile_collect()
     B.profile_enable(False)
     bn = prof["bn_apply"]
+    ev_us = B.profile_event_overhead()
     roofline = roofline_of(bn["flops"], bn["bytes"], bn["ms"], bn["launches"],
                            "bn_apply_k<bf16,8,true> (BatchNorm forward: normalise, add the residual, ReLU, bit mask)",
-                           ROOFLINE_TRAFFIC_BYTES if default_pair else None)
+                           ROOFLINE_TRAFFIC_BYTES if default_pair else None, ev_us)
     roofline["launches_per_step"] = bn["launches"] / psteps
     cw = prof["conv_fprop_wide"]
     roofline_conv = roofline_of(cw["flops"], cw["bytes"], cw["ms"], cw["launches"],
                                 "igemm_kernel<0,128,256,2,2,false,true,1,false,0,false> (bf16 implicit-GEMM conv fprop on "
-                                "128x256 tiles, BatchNorm column sums in the epilogue)", ROOFLINE_CONV_TRAFFIC_BYTES if default_pair else None)
+                                "128x256 tiles, BatchNorm column sums in the epilogue)", ROOFLINE_CONV_TRAFFIC_BYTES if default_pair else None,
+                                ev_us)
     roofline_conv["launches_per_step"] = cw["launches"] / psteps
     classes_ms = {k: round(v["ms"] / psteps, 4) for k, v in prof.items()}
     hbm = {}

@@ -318,6 +318,10 @@ int codistill_profile_collect(void);
 /* totals since the last reset: milliseconds, launches, algorithmic flops and bytes. host outputs. */
 int codistill_profile_get(int kernel_class, double* ms, int64_t* launches, double* flops, double* bytes);
 int codistill_profile_reset(void);
+/* What the timer's pair of events adds to a launch: mean time between two events recorded around an empty kernel
+ * on `stream` (200 launches, the last 100 averaged; synchronises the stream).  A class's time per launch exceeds
+ * the kernel durations a profiler reports by about this much.  host output, microseconds. */
+int codistill_profile_event_overhead(double* microseconds, void* stream);
 
 const char* codistill_last_error(void);
 const char* codistill_version(void);

@@ -87,6 +87,7 @@ _SIGS = {
     "codistill_profile_get": [_i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_i64),
                               ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)],
     "codistill_profile_reset": [],
+    "codistill_profile_event_overhead": [ctypes.POINTER(ctypes.c_double), _vp],
 }
 for _n, _a in _SIGS.items():
     getattr(lib, _n).argtypes = _a
@@ -234,6 +235,13 @@ def profile_enable(on):
 
 def profile_reset():
     _check(lib.codistill_profile_reset())
+
+
+def profile_event_overhead():
+    """Microseconds that the timer's event pair adds to a launch (measured on the current stream)."""
+    us = ctypes.c_double()
+    _check(lib.codistill_profile_event_overhead(ctypes.byref(us), _stream()))
+    return us.value
 
 
 def profile_collect():
