@@ -93,3 +93,26 @@ def test_transformer_step_is_bit_reproducible():
     torch.cuda.synchronize()
     np.testing.assert_array_equal(unpack_flat(c.model, r.grads.cpu().numpy()), got["grad"])
     np.testing.assert_array_equal(r.logits.cpu().numpy(), got["logits"])
+
+
+def test_transformer_adam_updates_through_the_runner():
+    """Two steps with the Adam update: the weights follow the oracle's Adam applied to the gradients the backward
+    pass produced (update counter, moment buffers and the bf16 shadow copy are wired correctly)."""
+    import torch
+    from oracle.adam import adam_step
+    from paper_2010_02838_amd.runner import StepRunner, pack_flat
+    c = make("small")
+    r = StepRunner(c.model, [c.peer], c.batch)
+    r.load(pack_flat(c.model, c.th), [pack_flat(c.peer, c.thp)])
+    x, y = torch.from_numpy(c.x).to("cuda:0"), torch.from_numpy(c.y).to("cuda:0")
+    w = r.master.cpu().numpy().astype(np.float64)
+    m, v = np.zeros_like(w), np.zeros_like(w)
+    for t in (1, 2):
+        r.step(x, y, 0.5, 1e-2, 0.0, label_smoothing=0.1, adam=(0.9, 0.98, 1e-8))
+        torch.cuda.synchronize()
+        w, m, v = adam_step(w, m, v, r.grads.cpu().numpy(), 1e-2, t, 0.9, 0.98, 1e-8)
+        got = r.master.cpu().numpy()
+        assert np.abs(got - w).max() <= 1e-5 * 1e-2 * t + 2e-7 * np.abs(w).max()
+        bits = r.lowp.view(torch.int16).cpu().numpy().view(np.uint16)
+        np.testing.assert_array_equal(bits, synth.bf16_bits(got))
+    assert r.updates == 2
