@@ -13,12 +13,17 @@ from .step import codistill_step
 
 
 def codistill_train(arch, thetas, batches, steps, exchange_every, alpha, lr, momentum,
-                    weight_decay=0.0, label_smoothing=0.0, dist="mse"):
+                    weight_decay=0.0, label_smoothing=0.0, dist="mse", exchange="checkpoints"):
     """thetas: list of n flat parameter vectors (one per model).
     batches(k, i) -> (x, y): the minibatch of model i at update k.
     alpha, lr, weight_decay, label_smoothing: numbers or functions of the update index k (Section 4 grows alpha and
     decays the L2 term or, for translation, the label smoothing over training).
+    exchange: "checkpoints" (above), or "predictions", the other implementation of Section 3: all models process
+    the same minibatch batches(k, 0) (coordinated sampling); on every T-th update each model distils against the
+    predictions its peers make with their current parameters, on the other updates the distillation term is left out.
     Returns dict(theta=[...], v=[...], loss=[steps][n][3], refreshed=[update indices of exchanges])."""
+    if exchange not in ("checkpoints", "predictions"):
+        raise ValueError(exchange)
     n = len(thetas)
     sched = lambda s, k: s(k) if callable(s) else s
     theta = [np.asarray(t, dtype=np.float64).copy() for t in thetas]
@@ -31,8 +36,12 @@ def codistill_train(arch, thetas, batches, steps, exchange_every, alpha, lr, mom
             refreshed.append(k)
         row, new_theta, new_v = [], [], []
         for i in range(n):                       # all models step from the same (old) state
-            x, y = batches(k, i)
-            peers = [stale[j] for j in range(n) if j != i]
+            if exchange == "predictions":
+                x, y = batches(k, 0)
+                peers = [theta[j] for j in range(n) if j != i] if k % exchange_every == 0 else []
+            else:
+                x, y = batches(k, i)
+                peers = [stale[j] for j in range(n) if j != i]
             out = codistill_step(arch, theta[i], peers, x, y, sched(alpha, k), sched(lr, k), momentum, v=v[i],
                                  weight_decay=sched(weight_decay, k), label_smoothing=sched(label_smoothing, k), dist=dist)
             row.append(out["loss"])

@@ -37,17 +37,32 @@ class CodistillTrainer:
                 dst.copy_(s)
 
     def step(self, batches, exchange_every, alpha, lr, momentum, weight_decay=0.0, label_smoothing=0.0,
-             dist_kind=B.CD_DIST_MSE_LOGITS):
-        """One update of every model.  batches(k, i) -> (x, y) device tensors.  Returns the [n][3] losses as device tensors."""
+             dist_kind=B.CD_DIST_MSE_LOGITS, exchange="checkpoints"):
+        """One update of every model.  batches(k, i) -> (x, y) device tensors.  Returns the [n][3] losses as device tensors.
+        exchange = "predictions": the other implementation of Section 3.  All models process the minibatch
+        batches(k, 0); on every exchange_every-th update each distils against the logits the others just computed
+        (their one forward pass each), on the other updates the distillation term is left out."""
         k = self.k
         sched = lambda s: s(k) if callable(s) else s
-        if k % exchange_every == 0:
-            self.exchange()
+        kw = dict(weight_decay=sched(weight_decay), label_smoothing=sched(label_smoothing), dist_kind=dist_kind)
         out = []
-        for i, r in enumerate(self.runners):
-            x, y = batches(k, i)
-            r.step(x, y, sched(alpha), sched(lr), momentum, weight_decay=sched(weight_decay),
-                   label_smoothing=sched(label_smoothing), dist_kind=dist_kind)
-            out.append(r.loss.clone())
+        if exchange == "predictions":
+            x, y = batches(k, 0)
+            for r in self.runners:
+                r.forward_local(x)
+            send = k % exchange_every == 0
+            for i, r in enumerate(self.runners):
+                peers = [q.logits for j, q in enumerate(self.runners) if j != i] if send else []
+                r.finish(x, y, peers, sched(alpha), sched(lr), momentum, **kw)
+                out.append(r.loss.clone())
+        elif exchange == "checkpoints":
+            if k % exchange_every == 0:
+                self.exchange()
+            for i, r in enumerate(self.runners):
+                x, y = batches(k, i)
+                r.step(x, y, sched(alpha), sched(lr), momentum, **kw)
+                out.append(r.loss.clone())
+        else:
+            raise ValueError(exchange)
         self.k += 1
         return out

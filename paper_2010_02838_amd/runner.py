@@ -80,6 +80,27 @@ class StepRunner:
         else:
             self.momentum.copy_(torch.from_numpy(np.ascontiguousarray(v, dtype=np.float32)))
 
+    def forward_local(self, x):
+        """The local model's forward pass alone (logits in self.logits, activations kept for the backward pass)."""
+        B.codistill_forward(self.model, self.params(), x, self.ws, self.logits, True)
+
+    def finish(self, x, y, peer_logits, alpha, lr, momentum, weight_decay=0.0, label_smoothing=0.0,
+               dist_kind=B.CD_DIST_MSE_LOGITS, mse_reduction=B.CD_MEAN_ALL, ignore_index=-1, nesterov=False, adam=None,
+               temperature=1.0):
+        """Loss against the given peer logits (a list of [rows, classes] fp32 device tensors, possibly empty: the
+        predictions other models sent, or none on an iteration without exchange), backward pass, update."""
+        B.codistill_loss_grad(self.logits, peer_logits, y, self.loss, self.dz, self.scratch, alpha,
+                              label_smoothing, dist_kind, mse_reduction, ignore_index, temperature)
+        B.codistill_backward(self.model, self.params(), x, self.ws, self.dz, self.grads)
+        if adam is None:
+            B.codistill_sgd_step(self.master, self.momentum, self.grads, self.lowp, lr, momentum, weight_decay, nesterov)
+        else:   # the momentum buffer holds Adam's first moment
+            if self.second_moment is None:
+                self.second_moment = torch.zeros_like(self.momentum)
+            self.updates += 1
+            B.codistill_adam_step(self.master, self.momentum, self.second_moment, self.grads, self.lowp, lr, self.updates,
+                                  adam[0], adam[1], adam[2], weight_decay)
+
     def step(self, x, y, alpha, lr, momentum, weight_decay=0.0, label_smoothing=0.0,
              dist_kind=B.CD_DIST_MSE_LOGITS, mse_reduction=B.CD_MEAN_ALL, ignore_index=-1, nesterov=False, adam=None,
              temperature=1.0):
@@ -92,20 +113,11 @@ class StepRunner:
             with torch.cuda.stream(self.side):
                 for pm, pp, pl in zip(self.peers, self.peer_params, self.peer_logits):
                     B.codistill_forward(pm, pp, x, self.ws_peer, pl, False)
-            B.codistill_forward(self.model, self.params(), x, self.ws, self.logits, True)
+            self.forward_local(x)
             main.wait_stream(self.side)           # the loss needs every model's logits
         else:
-            B.codistill_forward(self.model, self.params(), x, self.ws, self.logits, True)
+            self.forward_local(x)
             for pm, pp, pl in zip(self.peers, self.peer_params, self.peer_logits):
                 B.codistill_forward(pm, pp, x, self.ws_peer, pl, False)
-        B.codistill_loss_grad(self.logits, self.peer_logits, y, self.loss, self.dz, self.scratch, alpha,
-                              label_smoothing, dist_kind, mse_reduction, ignore_index, temperature)
-        B.codistill_backward(self.model, self.params(), x, self.ws, self.dz, self.grads)
-        if adam is None:
-            B.codistill_sgd_step(self.master, self.momentum, self.grads, self.lowp, lr, momentum, weight_decay, nesterov)
-        else:   # the momentum buffer holds Adam's first moment
-            if self.second_moment is None:
-                self.second_moment = torch.zeros_like(self.momentum)
-            self.updates += 1
-            B.codistill_adam_step(self.master, self.momentum, self.second_moment, self.grads, self.lowp, lr, self.updates,
-                                  adam[0], adam[1], adam[2], weight_decay)
+        self.finish(x, y, self.peer_logits, alpha, lr, momentum, weight_decay, label_smoothing, dist_kind, mse_reduction,
+                    ignore_index, nesterov, adam, temperature)

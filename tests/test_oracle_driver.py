@@ -82,3 +82,29 @@ def test_models_move_towards_each_other():
     for r in (solo, co, stale):                       # the task loss goes down on the fixed batch
         assert (r["loss"][-1, :, 1] < r["loss"][0, :, 1]).all()
     assert co["loss"][-1, :, 2].max() < 0.1 * co["loss"][0, :, 2].min()   # and so does the distillation term
+
+
+def test_prediction_exchange():
+    """The other implementation of Section 3.  With an exchange at every update and the same minibatch for all
+    models it is the checkpoint form with T = 1 (fresh copies predict on that minibatch); between exchanges a
+    model takes plain supervised steps whatever alpha is."""
+    th = _thetas(3)
+    same = lambda k, i: _batches(k, 0)
+    a = codistill_train(ARCH, th, same, 4, 1, 0.8, 0.1, 0.9, exchange="predictions")
+    b = codistill_train(ARCH, th, same, 4, 1, 0.8, 0.1, 0.9, exchange="checkpoints")
+    for i in range(3):
+        np.testing.assert_array_equal(a["theta"][i], b["theta"][i])
+    np.testing.assert_array_equal(a["loss"], b["loss"])
+    # T = 3: updates 1 and 2 have no distillation term
+    c = codistill_train(ARCH, th, _batches, 3, 3, 0.8, 0.1, 0.9, exchange="predictions")
+    assert c["refreshed"] == [0]
+    assert np.all(c["loss"][0, :, 2] > 0) and np.all(c["loss"][1:, :, 2] == 0)
+    t, v = th[1].copy(), None
+    x, y = _batches(0, 0)                                   # model 1 sees model 0's minibatch (coordinated sampling)
+    out = codistill_step(ARCH, t, [th[0], th[2]], x, y, 0.8, 0.1, 0.9)
+    t, v = out["theta"], out["v"]
+    for k in (1, 2):
+        x, y = _batches(k, 0)
+        out = codistill_step(ARCH, t, [], x, y, 123.0, 0.1, 0.9, v=v)
+        t, v = out["theta"], out["v"]
+    np.testing.assert_allclose(c["theta"][1], t, atol=1e-15)
