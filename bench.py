@@ -261,6 +261,9 @@ def main():
     ap.add_argument("--peer", default="resnet50", choices=["resnet50", "resnet18", "resnext101"],
                     help="architecture of the stale peer of the ResNet-50 workload (Section 5 pairs different "
                          "architectures); the default line is the two-ResNet-50 step")
+    ap.add_argument("--exchange", default="checkpoints", choices=["checkpoints", "predictions"],
+                    help="checkpoints (default): the step computes the stale peers' forward passes itself; predictions: "
+                         "the peers' logits arrive from outside (Section 3's second implementation), no peer forward")
     ap.add_argument("--n-way", type=int, default=2,
                     help="models that codistill (Section 5: 2, 3, 4, 8): the step runs n-1 peer forwards; default 2")
     ap.add_argument("--local", default="resnet50", choices=["resnet50", "resnext101"],
@@ -300,7 +303,7 @@ def main():
              "resnext101": B.CD_ARCH_RESNEXT}
     if not 2 <= args.n_way <= 9:
         raise SystemExit("--n-way: 2 to 9 models (the loss takes up to 8 peers)")
-    default_pair = args.peer == "resnet50" and args.local == "resnet50" and args.n_way == 2
+    default_pair = args.peer == "resnet50" and args.local == "resnet50" and args.n_way == 2 and args.exchange == "checkpoints"
     model, peer = B.Model(B.arch_preset(kinds[args.local]), B.CD_BF16), B.Model(B.arch_preset(kinds[args.peer]), B.CD_BF16)
     table = model.param_table()
     npeers = args.n_way - 1
@@ -314,8 +317,14 @@ def main():
     y = torch.from_numpy(synth.labels(batch, classes, seed=3)).to(dev)
     alpha, lr, mu = 1.0, 0.1, 0.9
 
+    received = [torch.randn(batch, classes, device=dev) * 3.0 for _ in range(npeers)]   # predictions mode: what peers sent
+
     def step():
-        r.step(x, y, alpha, lr, mu)
+        if args.exchange == "predictions":
+            r.forward_local(x)
+            r.finish(x, y, received, alpha, lr, mu)
+        else:
+            r.step(x, y, alpha, lr, mu)
 
     for _ in range(args.warmup):
         step()
@@ -365,7 +374,9 @@ def main():
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "resnet50_codistill_step", "batch": batch, "resolution": res, "classes": classes,
                    "models": "2 x ResNet-50 (local fwd+bwd+SGD, peer fwd)" if default_pair else
-                             "%s (local fwd+bwd+SGD) + %d x %s (peer fwd)" % (args.local, npeers, args.peer), "alpha": alpha,
+                             ("%s (local fwd+bwd+SGD) + %d x %s (peer fwd)" % (args.local, npeers, args.peer)
+                              if args.exchange == "checkpoints" else
+                              "%s (local fwd+bwd+SGD), logits of %d peer(s) received" % (args.local, npeers)), "alpha": alpha,
                    "distillation": "mse_logits", "lr": lr, "momentum": mu},
         "loss": [float(v) for v in loss[:3]],
         "roofline": roofline,
