@@ -27,6 +27,9 @@ def codistill_train(arch, thetas, batches, steps, exchange_every, alpha, lr, mom
     n = len(thetas)
     sched = lambda s, k: s(k) if callable(s) else s
     theta = [np.asarray(t, dtype=np.float64).copy() for t in thetas]
+    first = [t.copy() for t in theta]
+    distance = []                                # per update and model: the L2 distance of the parameters from their
+                                                 # initial values (the diagnostic of the appendix on regularisation)
     v = [np.zeros_like(t) for t in theta]
     stale = [t.copy() for t in theta]
     losses, refreshed = [], []
@@ -49,4 +52,6 @@ def codistill_train(arch, thetas, batches, steps, exchange_every, alpha, lr, mom
             new_v.append(out["v"])
         theta, v = new_theta, new_v
         losses.append(row)
-    return dict(theta=theta, v=v, loss=np.asarray(losses, dtype=np.float64), refreshed=refreshed)
+        distance.append([float(np.linalg.norm(theta[i] - first[i])) for i in range(n)])
+    return dict(theta=theta, v=v, loss=np.asarray(losses, dtype=np.float64), refreshed=refreshed,
+                distance_from_init=np.asarray(distance))

@@ -1,4 +1,4 @@
-"""Several codistillation steps of n models on one GPU, in the checkpoint-exchange form.
+"""Several codistillation steps of n models on one GPU, in the checkpoint-exchange or the prediction-exchange form.
 
 Host logic only (paper, Algorithm 1 and Section 3): every model owns a StepRunner; the copies of its
 peers' parameters that it distils against are refreshed every `exchange_every` updates by device
@@ -26,6 +26,12 @@ class CodistillTrainer:
         """thetas[i]: float32 host array in model i's flat layout.  The stale copies start equal to them."""
         for i, r in enumerate(self.runners):
             r.load(thetas[i], [thetas[j] for j in range(self.n) if j != i])
+        self.first = [r.master.clone() for r in self.runners]
+
+    def distance_from_init(self):
+        """L2 distance of every model's fp32 weights from the ones loaded (the diagnostic the paper's appendix plots:
+        codistillation keeps the parameters closer to their initial values).  Synchronises."""
+        return [float(torch.linalg.vector_norm((r.master - f).double())) for r, f in zip(self.runners, self.first)]
 
     def exchange(self):
         """Refresh every model's stale copies from the peers' current weights (device to device)."""

@@ -38,6 +38,7 @@ def test_tiny_cnn_fp32_trajectory(n, T):
             got = losses[i].cpu().numpy()[:3]
             np.testing.assert_allclose(got, ref["loss"][k][i], rtol=2e-4, atol=1e-6)
     torch.cuda.synchronize()
+    np.testing.assert_allclose(tr.distance_from_init(), ref["distance_from_init"][-1], rtol=1e-4)
     for i in range(n):
         got = unpack_flat(models[i], tr.runners[i].master.cpu().numpy())
         assert rel(got, ref["theta"][i]) <= 1e-4

@@ -55,6 +55,8 @@ def test_stale_copies_and_simultaneous_updates():
         theta, v = [a for a, _ in new], [b for _, b in new]
     for i in range(3):
         np.testing.assert_allclose(r["theta"][i], theta[i], atol=1e-15)
+        assert r["distance_from_init"][-1][i] == np.linalg.norm(theta[i] - th[i])
+    assert r["distance_from_init"].shape == (steps, 3) and np.all(r["distance_from_init"] > 0)
     # with T = 1 model 1 distils against model 0's parameters from before model 0's update of the same iteration
     r1 = codistill_train(ARCH, th[:2], _batches, 1, 1, 1.0, 0.1, 0.0)
     x, y = _batches(0, 1)
