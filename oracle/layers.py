@@ -101,6 +101,23 @@ def batchnorm_forward(x, gamma, beta):
     return y, (xhat, invstd, mean, var)
 
 
+BN_MOMENTUM = 0.1
+
+
+def batchnorm_running_update(running_mean, running_var, cache, rows, momentum=BN_MOMENTUM):
+    """The averages an evaluation-mode BatchNorm uses, after one training-mode forward pass (cache from
+    batchnorm_forward over `rows` rows): (1 - momentum) * old + momentum * batch value, with the unbiased batch
+    variance (the convention of the common implementations; the paper is silent).  Returns (mean, var)."""
+    _, _, mean, var = cache
+    unbiased = var * rows / max(rows - 1, 1)
+    return (1.0 - momentum) * running_mean + momentum * mean, (1.0 - momentum) * running_var + momentum * unbiased
+
+
+def batchnorm_eval(x, gamma, beta, running_mean, running_var):
+    """Evaluation-mode BatchNorm: normalise with the running averages instead of the batch's statistics."""
+    return gamma * (x - running_mean) / np.sqrt(running_var + BN_EPS) + beta
+
+
 def batchnorm_backward(dy, gamma, cache):
     """Return (dx, dgamma, dbeta)."""
     xhat, invstd, _, _ = cache

@@ -314,11 +314,15 @@ def transformer(S, Ts, Tt, d=512, heads=8, d_ff=2048, vocab=32768, enc_layers=6,
     return a
 
 
-def forward(arch, params, x, store=None):
+def forward(arch, params, x, store=None, running=None, bn_eval=False):
     """Training-mode forward.  params: dict name -> float64 array.  Returns (logits, tape).
-    store: optional function applied to the tensors a reduced-precision pipeline keeps in memory."""
+    store: optional function applied to the tensors a reduced-precision pipeline keeps in memory.
+    running: list with one [mean, var] pair per BatchNorm op, in graph order.  With bn_eval the BatchNorms
+    normalise with these averages (evaluation mode; the tape then cannot be used for a backward pass);
+    otherwise they use the batch's statistics and, if running is given, update it in place."""
     T = {0: np.asarray(x, dtype=np.float64)}
     cache = {}
+    bn_index = 0
     for i, o in enumerate(arch.ops):
         if i > 0 and store is not None and arch.ops[i - 1]["stored"]:
             T[arch.ops[i - 1]["y"]] = store(T[arch.ops[i - 1]["y"]])
@@ -327,7 +331,14 @@ def forward(arch, params, x, store=None):
             b = params[o["b"]] if o["b"] else None
             T[o["y"]] = L.conv2d_forward(T[o["x"]], params[o["w"]], b, o["stride"], o["pad"])
         elif k == "bn":
-            T[o["y"]], cache[i] = L.batchnorm_forward(T[o["x"]], params[o["gamma"]], params[o["beta"]])
+            if bn_eval:
+                T[o["y"]] = L.batchnorm_eval(T[o["x"]], params[o["gamma"]], params[o["beta"]], *running[bn_index])
+            else:
+                T[o["y"]], cache[i] = L.batchnorm_forward(T[o["x"]], params[o["gamma"]], params[o["beta"]])
+                if running is not None:
+                    rows = T[o["x"]].size // T[o["x"]].shape[-1]
+                    running[bn_index][:] = L.batchnorm_running_update(running[bn_index][0], running[bn_index][1], cache[i], rows)
+            bn_index += 1
         elif k == "relu":
             T[o["y"]] = L.relu_forward(T[o["x"]])
         elif k == "add":

@@ -337,3 +337,47 @@ def test_grouped_convolution_is_the_block_diagonal_dense_one():
             np.testing.assert_allclose(dw[g * og:(g + 1) * og], dwd[g * og:(g + 1) * og, :, :, g * cg:(g + 1) * cg], atol=1e-13)
     with pytest.raises(ValueError):
         L.conv2d_forward(x, rng.standard_normal((Cout, k, k, 5)), None, 1, 1)
+
+
+def test_batchnorm_running_averages_and_evaluation_mode_against_torch():
+    """torch.nn.BatchNorm2d keeps the same averages over two training-mode passes and gives the same
+    evaluation-mode output; through a small ResNet the evaluation-mode logits agree as well."""
+    from oracle import layers as L
+    rng = np.random.default_rng(12)
+    C = 5
+    bn = torch.nn.BatchNorm2d(C, eps=1e-5, momentum=0.1).double()
+    gamma, beta = rng.standard_normal(C), rng.standard_normal(C)
+    with torch.no_grad():
+        bn.weight.copy_(torch.tensor(gamma))
+        bn.bias.copy_(torch.tensor(beta))
+    rm, rv = np.zeros(C), np.ones(C)
+    for step in range(2):
+        x = rng.standard_normal((3, 4, 6, C)) * (1 + step) + step
+        y, cache = L.batchnorm_forward(x, gamma, beta)
+        rm, rv = L.batchnorm_running_update(rm, rv, cache, 3 * 4 * 6)
+        yt = bn(torch.tensor(x).permute(0, 3, 1, 2))
+        np.testing.assert_allclose(y, yt.detach().permute(0, 2, 3, 1).numpy(), atol=1e-12)
+        np.testing.assert_allclose(rm, bn.running_mean.numpy(), atol=1e-14)
+        np.testing.assert_allclose(rv, bn.running_var.numpy(), atol=1e-14)
+    bn.eval()
+    xe = rng.standard_normal((2, 3, 3, C))
+    np.testing.assert_allclose(L.batchnorm_eval(xe, gamma, beta, rm, rv),
+                               bn(torch.tensor(xe).permute(0, 3, 1, 2)).detach().permute(0, 2, 3, 1).numpy(), atol=1e-12)
+    # whole network: a training pass updates every BatchNorm's averages, an evaluation pass uses them
+    arch = nets.resnet20(classes=10, widths=(4, 8, 16), blocks=(1, 1, 1))
+    th = synth.he_init(arch.params, 1, jitter=0.1).astype(np.float64)
+    P = unflatten(arch, th)
+    n_bn = sum(1 for o in arch.ops if o["op"] == "bn")
+    widths = [P[o["gamma"]].shape[0] for o in arch.ops if o["op"] == "bn"]
+    running = [[np.zeros(c), np.ones(c)] for c in widths]
+    x = synth.images(6, 12, 12, 3, seed=0).astype(np.float64)
+    z_train, _ = nets.forward(arch, P, x, running=running)
+    assert len(running) == n_bn and all(np.any(r[0] != 0) for r in running)
+    z_plain, _ = nets.forward(arch, P, x)
+    np.testing.assert_array_equal(z_train, z_plain)                  # keeping averages changes nothing in a training pass
+    z_eval, _ = nets.forward(arch, P, x, running=running, bn_eval=True)
+    assert np.abs(z_eval - z_train).max() > 1e-3                     # one update from (0, 1): far from the batch statistics
+    frozen = [[r[0].copy(), r[1].copy()] for r in running]
+    nets.forward(arch, P, x[:3], running=frozen, bn_eval=True)
+    for a, b in zip(frozen, running):
+        np.testing.assert_array_equal(a[0], b[0])                    # an evaluation pass leaves the averages alone
