@@ -159,14 +159,21 @@ int codistill_workspace_bytes(const cd_model* m, int64_t batch, int save_for_bac
  *   x           [batch][in_h][in_w][3] ([batch][1][1][d_model] for CD_ARCH_TRANSFORMER_HEAD) in the model's dtype
  *   save_for_backward  1: keep in `workspace` what codistill_backward needs (local model);
  *                      0: keep nothing (peer model; its logits are constants)
- *   bn_mode     CD_BN_BATCH_STATS (CD_BN_RUNNING is rejected as unsupported)
- *   bn_running  reserved, must be NULL
+ *   bn_mode     CD_BN_BATCH_STATS: every BatchNorm uses the statistics of this batch (training; also what the stale
+ *               peer's forward pass uses).  CD_BN_RUNNING: evaluation mode, the running averages in bn_running are
+ *               used instead (save_for_backward must be 0)
+ *   bn_running  NULL, or device fp32 [codistill_bn_running_elements(m)]: per BatchNorm op, in graph order, its
+ *               running mean [C] then running variance [C] (the caller initialises them to 0 and 1).  With
+ *               CD_BN_BATCH_STATS and a non-NULL pointer the pass also updates them: 0.9 old + 0.1 batch value,
+ *               the batch variance in its unbiased form (the paper is silent; the common convention)
  *   workspace   at least codistill_workspace_bytes(m, batch, save_for_backward) bytes; with
  *               save_for_backward the same buffer must be handed, untouched, to codistill_backward
  *   logits_out  [batch][classes] fp32
  * Errors: NULL pointer, batch <= 0, unknown mode -> CD_ERR_INVALID_ARG; small workspace ->
  * CD_ERR_WORKSPACE_TOO_SMALL; launch failure -> CD_ERR_HIP.
  */
+/* elements of the bn_running buffer of codistill_forward: twice the channels of all BatchNorm ops. host output. */
+int codistill_bn_running_elements(const cd_model* m, int64_t* n);
 int codistill_forward(const cd_model* m, const void* params, const void* x, int64_t batch,
                       int save_for_backward, int bn_mode, float* bn_running,
                       void* workspace, size_t workspace_bytes, float* logits_out, void* stream);

@@ -73,6 +73,7 @@ _SIGS = {
     "codistill_param_count": [_vp, ctypes.POINTER(_i64), ctypes.POINTER(_i64)],
     "codistill_param_info": [_vp, _i64, ctypes.POINTER(TensorInfo)],
     "codistill_workspace_bytes": [_vp, _i64, _i32, ctypes.POINTER(_sz)],
+    "codistill_bn_running_elements": [_vp, ctypes.POINTER(_i64)],
     "codistill_graph_size": [_vp, ctypes.POINTER(_i64), ctypes.POINTER(_i64)],
     "codistill_op_info": [_vp, _i64, _i64, ctypes.POINTER(OpInfo)],
     "codistill_tensor_info": [_vp, _i64, _i64, ctypes.POINTER(ActInfo)],
@@ -180,16 +181,22 @@ class Model:
             tensors.append({f: getattr(t, f) for f, _ in ActInfo._fields_})
         return ops, tensors
 
+    def bn_running_elements(self):
+        n = _i64()
+        _check(lib.codistill_bn_running_elements(self._h, ctypes.byref(n)))
+        return n.value
+
     def workspace_bytes(self, batch, save_for_backward):
         b = _sz()
         _check(lib.codistill_workspace_bytes(self._h, batch, int(save_for_backward), ctypes.byref(b)))
         return b.value
 
 
-def codistill_forward(model, params, x, workspace, logits_out, save_for_backward, bn_mode=CD_BN_BATCH_STATS):
+def codistill_forward(model, params, x, workspace, logits_out, save_for_backward, bn_mode=CD_BN_BATCH_STATS,
+                      bn_running=None):
     """z = f_params(x).  params: flat tensor in the model dtype; x: [B,H,W,3]; logits_out: [B,classes] fp32."""
     batch = x.shape[0]
-    _check(lib.codistill_forward(model._h, _ptr(params), _ptr(x), batch, int(save_for_backward), bn_mode, None,
+    _check(lib.codistill_forward(model._h, _ptr(params), _ptr(x), batch, int(save_for_backward), bn_mode, _ptr(bn_running),
                                  _ptr(workspace), workspace.numel() * workspace.element_size(), _ptr(logits_out),
                                  _stream()))
 

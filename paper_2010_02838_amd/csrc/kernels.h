@@ -40,6 +40,11 @@ void colsum(int dtype, const void* a, int64_t M, int C, float* out, float* parti
 // bn_apply: the elementwise pass with those statistics.
 void bn_stats(int dtype, const void* x, const void* gamma, const void* beta, int64_t M, int C, float* stats,
               float* partials, int pre_chunks, float* scratch, hipStream_t s);
+// Running averages [mean[C] | var[C]] (fp32) for the evaluation mode: updated from the statistics of a training-mode
+// pass over M rows (momentum 0.1, unbiased variance), or turned into stats in place of the batch's.
+void bn_running_update(const float* stats, float* running, int64_t M, int C, float momentum, hipStream_t s);
+void bn_stats_from_running(int dtype, const float* running, const void* gamma, const void* beta, float* stats, int C,
+                           hipStream_t s);
 void bn_apply(int dtype, const void* x, const void* res, bool relu, void* y, int64_t M, int C, const float* stats,
               uint8_t* relu_mask, hipStream_t s);
 // bn_apply with ReLU followed by a 3x3 stride-2 pad-1 max-pool, in one pass: y [B][H/2][W/2][C] is the pooled

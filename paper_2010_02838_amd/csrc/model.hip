@@ -564,6 +564,12 @@ extern "C" int codistill_model_create(const cd_arch_desc* a, int dtype, cd_model
 
 extern "C" void codistill_model_destroy(cd_model* m) { delete m; }
 
+extern "C" int codistill_bn_running_elements(const cd_model* m, int64_t* n) {
+  CD_REQUIRE(m != nullptr && n != nullptr, "bn_running_elements: NULL pointer argument");
+  *n = 2 * m->bn_c_total;
+  return CD_OK;
+}
+
 extern "C" int codistill_param_count(const cd_model* m, int64_t* n_tensors, int64_t* n_elements) {
   CD_REQUIRE(m != nullptr, "param_count: model is NULL");
   if (n_tensors) *n_tensors = (int64_t)m->params.size();
@@ -677,8 +683,10 @@ extern "C" int codistill_forward(const cd_model* m, const void* params, const vo
   if (rc) return rc;
   CD_REQUIRE(logits_out != nullptr && aligned16(logits_out), "forward: logits_out is NULL or misaligned");
   CD_REQUIRE(bn_mode == CD_BN_BATCH_STATS || bn_mode == CD_BN_RUNNING, "forward: unknown bn_mode %d", bn_mode);
-  if (bn_mode == CD_BN_RUNNING) return set_error(CD_ERR_UNSUPPORTED, "forward: CD_BN_RUNNING is not implemented");
-  CD_REQUIRE(bn_running == nullptr, "forward: bn_running is reserved and must be NULL");
+  CD_REQUIRE(bn_mode == CD_BN_BATCH_STATS || bn_running != nullptr, "forward: CD_BN_RUNNING needs the running averages");
+  if (bn_mode == CD_BN_RUNNING && save)
+    return set_error(CD_ERR_UNSUPPORTED, "forward: no backward pass through an evaluation-mode BatchNorm (save_for_backward = 0)");
+  CD_REQUIRE((reinterpret_cast<uintptr_t>(bn_running) & 3) == 0, "forward: bn_running is not 4-byte aligned");
   Ctx c;
   c.m = m;
   c.plan = make_plan(m, batch, save != 0);
@@ -752,7 +760,8 @@ extern "C" int codistill_forward(const cd_model* m, const void* params, const vo
                        2.0 * g.M() * g.Cout * g.K(),
                        conv_bytes(m, g));
           // a BatchNorm that follows directly gets its column sums from the convolution's epilogue
-          const bool fuse = o.pb < 0 && oi + 1 < m->ops.size() && m->ops[oi + 1].kind == OP_BN && m->ops[oi + 1].x == o.y &&
+          const bool fuse = bn_mode == CD_BN_BATCH_STATS && o.pb < 0 && oi + 1 < m->ops.size() &&
+                            m->ops[oi + 1].kind == OP_BN && m->ops[oi + 1].x == o.y &&
                             (size_t)(g.M() / 128 + 1 + 32) * stat_pitch(g.Cout) * sizeof(float) <= c.plan.partials_bytes;
           stat_chunks = conv_fprop_mfma(src, w, static_cast<const bf16_t*>(c.P(o.pb)), o.relu, static_cast<bf16_t*>(out), gp,
                                         fuse ? c.partials() : nullptr, c.s);
@@ -768,10 +777,15 @@ extern "C" int codistill_forward(const cd_model* m, const void* params, const vo
         uint8_t* mask = c.plan.aux[oi] ? reinterpret_cast<uint8_t*>(c.ws + c.plan.aux[oi]) : nullptr;
         const bool fused = stat_tensor == o.x;   // the column sums came with the convolution
         const void* res = o.res >= 0 ? c.act(o.res) : nullptr;
-        {
+        float* running = bn_running ? bn_running + 2 * m->bn_off[o.bn_slot] : nullptr;   // this op's [mean | var]
+        if (bn_mode == CD_BN_RUNNING) {
+          ProfScope pr(CD_K_NORM, c.s, 0, 0.0);
+          bn_stats_from_running(dt, running, c.P(o.pw), c.P(o.pb), c.stats(o), tx.c, c.s);
+        } else {
           ProfScope pr(CD_K_NORM, c.s, 0, fused ? 0.0 : (double)M * tx.c * m->esize());
           bn_stats(dt, in, c.P(o.pw), c.P(o.pb), M, tx.c, c.stats(o), c.partials(), fused ? stat_chunks : 0,
                    fused ? c.partials() + (size_t)stat_chunks * stat_pitch(tx.c) : nullptr, c.s);
+          if (running) bn_running_update(c.stats(o), running, M, tx.c, 0.1f, c.s);
         }
         if (pool_fused(m, (int)oi)) {   // the next op, a max-pool, is computed here; `out` stays unwritten
           const Op& q = m->ops[oi + 1];

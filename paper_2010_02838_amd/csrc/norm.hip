@@ -671,6 +671,48 @@ static void colsum_t(const T* a, int64_t M, int C, float* out, float* partials, 
                      (const T*)nullptr, (const T*)nullptr, (float*)nullptr, out, (float*)nullptr, (float*)nullptr);
 }
 
+// ---- running averages (evaluation mode) ----------------------------------------------------------
+// running = [mean[C] | var[C]].  After a training-mode pass: (1 - mom) * old + mom * batch value, the batch
+// variance in its unbiased form (rows / (rows - 1) times the biased one that stats holds as 1 / invstd^2 - eps).
+__global__ void __launch_bounds__(256) bn_running_update_k(const float* __restrict__ stats, float* __restrict__ running,
+                                                           int C, float mom, float unbias) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= C) return;
+  const float mean = stats[c], istd = stats[C + c];
+  const float var = fmaxf(1.f / (istd * istd) - kBnEps, 0.f) * unbias;
+  running[c] = (1.f - mom) * running[c] + mom * mean;
+  running[C + c] = (1.f - mom) * running[C + c] + mom * var;
+}
+
+// stats (mean, invstd, scale, shift) from the running averages instead of the batch
+template <typename T>
+__global__ void __launch_bounds__(256) bn_stats_from_running_k(const float* __restrict__ running, const T* __restrict__ gamma,
+                                                               const T* __restrict__ beta, float* __restrict__ stats, int C) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= C) return;
+  const float mean = running[c], istd = 1.f / sqrtf(running[C + c] + kBnEps);
+  const float scale = Cvt<T>::ld(gamma[c]) * istd;
+  stats[c] = mean;
+  stats[C + c] = istd;
+  stats[2 * C + c] = scale;
+  stats[3 * C + c] = Cvt<T>::ld(beta[c]) - mean * scale;
+}
+
+void bn_running_update(const float* stats, float* running, int64_t M, int C, float momentum, hipStream_t s) {
+  hipLaunchKernelGGL(bn_running_update_k, dim3((unsigned)cdiv(C, 256)), dim3(256), 0, s, stats, running, C, momentum,
+                     M > 1 ? (float)((double)M / (double)(M - 1)) : 1.f);
+}
+
+void bn_stats_from_running(int dtype, const float* running, const void* gamma, const void* beta, float* stats, int C,
+                           hipStream_t s) {
+  if (dtype == CD_BF16)
+    hipLaunchKernelGGL(bn_stats_from_running_k<bf16_t>, dim3((unsigned)cdiv(C, 256)), dim3(256), 0, s, running,
+                       (const bf16_t*)gamma, (const bf16_t*)beta, stats, C);
+  else
+    hipLaunchKernelGGL(bn_stats_from_running_k<float>, dim3((unsigned)cdiv(C, 256)), dim3(256), 0, s, running,
+                       (const float*)gamma, (const float*)beta, stats, C);
+}
+
 void bn_stats(int dtype, const void* x, const void* gamma, const void* beta, int64_t M, int C, float* stats,
               float* partials, int pre_chunks, float* scratch, hipStream_t s) {
   if (dtype == CD_BF16)

@@ -98,7 +98,10 @@ def test_forward_backward_reject_bad_arguments_before_launch():
     assert f(m._h, None, fake, 8, 1, 0, None, fake, need, fake, None) == B.CD_ERR_INVALID_ARG
     assert f(m._h, fake, fake, 0, 1, 0, None, fake, need, fake, None) == B.CD_ERR_INVALID_ARG
     assert f(m._h, fake, fake, 8, 1, 5, None, fake, need, fake, None) == B.CD_ERR_INVALID_ARG
-    assert f(m._h, fake, fake, 8, 1, B.CD_BN_RUNNING, None, fake, need, fake, None) == B.CD_ERR_UNSUPPORTED
+    # evaluation-mode BatchNorm: needs the running averages, and has no backward pass
+    assert f(m._h, fake, fake, 8, 0, B.CD_BN_RUNNING, None, fake, need, fake, None) == B.CD_ERR_INVALID_ARG
+    assert f(m._h, fake, fake, 8, 1, B.CD_BN_RUNNING, fake, fake, need, fake, None) == B.CD_ERR_UNSUPPORTED
+    assert B.Model(B.arch_preset(B.CD_ARCH_RESNET_BOTTLENECK), B.CD_BF16).bn_running_elements() == 2 * 26560
     assert f(m._h, fake, fake, 8, 1, 0, None, fake, need - 1, fake, None) == B.CD_ERR_WORKSPACE_TOO_SMALL
     assert f(m._h, ctypes.c_void_p(0x1004), fake, 8, 1, 0, None, fake, need, fake, None) == B.CD_ERR_INVALID_ARG
     bwd = B.lib.codistill_backward

@@ -429,3 +429,52 @@ def test_resnet50_bf16_step_reduced_batch():
     ref = c.oracle()
     got = c.gpu()
     compare_bf16(c, ref, c.oracle(store=synth.round_bf16_f64), got)
+
+
+@pytest.mark.parametrize("name,dtype_name", [("basic", "f32"), ("bottleneck_mfma", "bf16")])
+def test_batchnorm_running_averages_and_evaluation_mode(name, dtype_name):
+    """A training-mode forward pass with a buffer of running averages updates them as the oracle does; an
+    evaluation-mode pass normalises with them (statistics kernels skipped, the fused BatchNorm + max-pool included)."""
+    import torch
+    from paper_2010_02838_amd.runner import pack_flat, to_device
+    kw, mk, batch, res, classes = SMALL[name]
+    c = Case(kw, mk(), dtype_name, batch, res, classes)
+    B, model = c.B, c.model
+    dev = "cuda:0"
+    params = to_device(pack_flat(model, c.th), model.torch_dtype)
+    x = to_device(c.x, model.torch_dtype)
+    ws = torch.empty(model.workspace_bytes(batch, False), dtype=torch.uint8, device=dev)
+    logits = torch.empty(batch, classes, device=dev)
+    # the buffer holds [mean | var] per BatchNorm op in the order of the library's op list (a projection shortcut's
+    # BatchNorm comes before the block's own there, after them in the oracle's list): match them by parameter name
+    names = [n for n, _, _, _ in c.ref_arch.params]
+    ops, _ = model.graph(batch)
+    lib_order = [names[o["param_w"]] for o in ops if o["kind"] == "bn"]
+    ref_order = [o["gamma"] for o in c.ref_arch.ops if o["op"] == "bn"]
+    assert sorted(lib_order) == sorted(ref_order)
+    P32 = c.per_tensor(c.th)
+    widths = [P32[n].shape[0] for n in lib_order]
+    assert model.bn_running_elements() == 2 * sum(widths)
+    run = torch.cat([torch.cat([torch.zeros(w), torch.ones(w)]) for w in widths]).to(dev)
+    B.codistill_forward(model, params, x, ws, logits, False, B.CD_BN_BATCH_STATS, run)
+    torch.cuda.synchronize()
+    z_train = logits.cpu().numpy().copy()
+    P = c.per_tensor(c.th.astype(np.float64))
+    ref_run = [[np.zeros(P32[n].shape[0]), np.ones(P32[n].shape[0])] for n in ref_order]
+    z_ref, _ = nets.forward(c.ref_arch, P, c.x.astype(np.float64), running=ref_run)
+    by_name = dict(zip(ref_order, ref_run))
+    got, off = run.cpu().numpy(), 0
+    tol = 1e-4 if dtype_name == "f32" else 3e-2        # bf16: the activations the statistics are taken from are rounded
+    for n, w in zip(lib_order, widths):
+        rm, rv = by_name[n]
+        assert rel(got[off:off + w], rm) <= tol and rel(got[off + w:off + 2 * w], rv) <= tol, n
+        off += 2 * w
+    # evaluation mode with the oracle's averages
+    run_ref = torch.from_numpy(np.concatenate([np.concatenate(by_name[n]) for n in lib_order]).astype(np.float32)).to(dev)
+    before = run_ref.clone()
+    B.codistill_forward(model, params, x, ws, logits, False, B.CD_BN_RUNNING, run_ref)
+    torch.cuda.synchronize()
+    z_eval_ref, _ = nets.forward(c.ref_arch, P, c.x.astype(np.float64), running=ref_run, bn_eval=True)
+    assert rel(logits.cpu().numpy(), z_eval_ref) <= (1e-4 if dtype_name == "f32" else 3e-2)
+    assert rel(z_train, z_eval_ref) > 5 * tol          # the two modes differ by far more than the tolerance
+    assert torch.equal(run_ref, before)                # an evaluation pass leaves the averages alone
