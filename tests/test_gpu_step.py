@@ -396,11 +396,12 @@ def test_small_resnet_bf16_step(name):
     compare_bf16(c, c.oracle(), c.oracle(store=synth.round_bf16_f64), c.gpu())
 
 
-def test_peer_of_another_architecture_bf16_step():
+@pytest.mark.parametrize("peer", ["basic_imagenet_mfma", "resnext"])
+def test_peer_of_another_architecture_bf16_step(peer):
     """Section 5 pairs models of different architectures: the local bottleneck network distils against a stale
-    basic-block network; only the shape of the logits is shared."""
+    basic-block network, or one with grouped convolutions; only the shape of the logits is shared."""
     kw, mk, batch, res, classes = SMALL["bottleneck_mfma"]
-    pkw, pmk, _, _, _ = SMALL["basic_imagenet_mfma"]
+    pkw, pmk, _, _, _ = SMALL[peer]
     c = Case(kw, mk(), "bf16", batch, res, classes, peer=(pkw, pmk()))
     assert c.peer.n_elements != c.model.n_elements
     compare_bf16(c, c.oracle(), c.oracle(store=synth.round_bf16_f64), c.gpu())
