@@ -5,7 +5,7 @@
 // causal mask.  q, k, v are column ranges of bf16 row-major tensors (the fused projections write
 // [rows][3d] or [rows][2d]); head h owns columns h*dh .. (h+1)*dh of each range.
 //
-// Two sets of kernels.  Head dimension 64 runs on the matrix cores (second half of this file).  The others use
+// Two sets of kernels.  Head dimensions 64 and 32 run on the matrix cores (second half of this file).  The others use
 // plain fp32 arithmetic: a pair of threads owns one query (forward, dq) or one key
 // (dk, dv), each thread one half of the head dimension; the dot products are completed with one
 // exchange inside the pair.  The other operand streams through LDS in chunks of 64 rows, every thread
@@ -268,7 +268,7 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_k(AttArgs a) {
   for (int c = 0; c < HALF; c++) { dkp[c] = f32_to_bf16(dk[c] * a.scale); dvp[c] = f32_to_bf16(dv[c]); }
 }
 
-// ---- matrix-core kernels (head dimension 64) -------------------------------------------------------
+// ---- matrix-core kernels (head dimensions 64 and 32) -------------------------------------------------------
 // v_mfma_f32_32x32x16_bf16 computes D[32x32] += A[32x16] B[16x32]: lane l holds row l % 32 of A and
 // column l % 32 of B, eight contraction elements 8 (l / 32) .. + 7 each, and column l % 32 of D, whose
 // register v is row 8 (v / 4) + 4 (l / 32) + v % 4.
@@ -728,11 +728,11 @@ __global__ void __launch_bounds__(256) embed_bwd_k(const int32_t* __restrict__ t
 
 }  // namespace
 
-// The matrix-core kernels read 16-byte vectors: head dimension 64 and row pitches that keep every row aligned.
+// The matrix-core kernels read 16-byte vectors: head dimension 64 or 32 and row pitches that keep every row aligned.
 // CODISTILL_PLAIN_ATTENTION=1 keeps the plain kernels (for comparing the two).
 static bool use_mfma(int dh, int64_t ldq, int64_t ldkv, int64_t ldo) {
   static const bool plain = [] { const char* e = getenv("CODISTILL_PLAIN_ATTENTION"); return e && e[0] == '1'; }();
-  return !plain && dh == 64 && ldq % 8 == 0 && ldkv % 8 == 0 && ldo % 8 == 0;
+  return !plain && (dh == 64 || dh == 32) && ldq % 8 == 0 && ldkv % 8 == 0 && ldo % 8 == 0;
 }
 
 bool attention_supported(int dh) { return dh == 8 || dh == 16 || dh == 32 || dh == 64; }
@@ -755,7 +755,8 @@ void attention_forward(const bf16_t* q, int64_t ldq, const bf16_t* k, const bf16
   a.scale = 1.f / sqrtf((float)dh);
   const unsigned grid = (unsigned)((int64_t)S * heads * cdiv(Tq, ATT_ROWS));
   if (use_mfma(dh, ldq, ldkv, ldo)) {
-    hipLaunchKernelGGL((attn_fwd_mfma_k<64>), dim3(grid), dim3(256), 0, s, a);
+    if (dh == 64) hipLaunchKernelGGL((attn_fwd_mfma_k<64>), dim3(grid), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((attn_fwd_mfma_k<32>), dim3(grid), dim3(256), 0, s, a);
     return;
   }
   CD_ATT_DISPATCH(attn_fwd_k, grid);
@@ -774,8 +775,13 @@ void attention_backward(const bf16_t* q, int64_t ldq, const bf16_t* k, const bf1
   const unsigned gq = (unsigned)((int64_t)S * heads * cdiv(Tq, ATT_ROWS));
   const unsigned gk = (unsigned)((int64_t)S * heads * cdiv(Tk, ATT_ROWS));
   if (use_mfma(dh, ldq, ldkv, ldo)) {
-    hipLaunchKernelGGL((attn_bwd_dq_mfma_k<64>), dim3(gq), dim3(256), 0, s, a);
-    hipLaunchKernelGGL((attn_bwd_dkv_mfma_k<64>), dim3(gk), dim3(256), 0, s, a);
+    if (dh == 64) {
+      hipLaunchKernelGGL((attn_bwd_dq_mfma_k<64>), dim3(gq), dim3(256), 0, s, a);
+      hipLaunchKernelGGL((attn_bwd_dkv_mfma_k<64>), dim3(gk), dim3(256), 0, s, a);
+    } else {
+      hipLaunchKernelGGL((attn_bwd_dq_mfma_k<32>), dim3(gq), dim3(256), 0, s, a);
+      hipLaunchKernelGGL((attn_bwd_dkv_mfma_k<32>), dim3(gk), dim3(256), 0, s, a);
+    }
     return;
   }
   CD_ATT_DISPATCH(attn_bwd_dq_k, gq);

@@ -16,7 +16,7 @@ CASES = {
     "ragged_vocab": (2, 5, 9, 32, 2, 40, 50, 1, 2),           # head dimension 16, vocabulary not a multiple of 8
     "long": (2, 150, 131, 128, 2, 128, 96, 1, 1),             # head dimension 64 (the matrix-core kernels); several
                                                               # query tiles and key chunks, ragged last ones
-    "mid": (2, 70, 33, 64, 2, 96, 80, 1, 1),                  # head dimension 32 (the plain kernels' largest here)
+    "mid": (2, 70, 33, 64, 2, 96, 80, 1, 1),                  # head dimension 32 (matrix-core kernels as well)
     "wide": (2, 20, 17, 1024, 16, 256, 64, 1, 1),             # the width and head count of the "big" model
 }
 
