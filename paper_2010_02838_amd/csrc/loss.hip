@@ -92,9 +92,11 @@ __global__ void __launch_bounds__((TPR > 256 ? TPR : 256)) loss_row_kernel(LossA
   const int64_t row = (int64_t)blockIdx.x * RPB + g;
   if (RPB > 1 && row >= a.rows) return;  // only wave-sized groups can leave early (no barriers)
   const int64_t cols = a.cols;
-  const float* __restrict__ zr = a.z + row * cols;
+  // dz may be the buffer of z (in place): neither pointer is restrict-qualified, and everything the
+  // row needs from z (its elements and z[target]) is loaded before the first store.
+  const float* zr = a.z + row * cols;
   const float* __restrict__ pr = MODE ? a.zp[0] + row * cols : nullptr;
-  float* __restrict__ outr = a.dz + row * cols;
+  float* outr = a.dz + row * cols;
   // The row's loads are issued before anything that depends on the target (whose own load would
   // otherwise sit in front of them as a full memory latency).
   float4 x[V], y[V];
