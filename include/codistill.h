@@ -222,6 +222,22 @@ int codistill_loss_grad(const float* z_local, const float* const* z_peers, const
                         void* stream);
 
 /*
+ * codistill_loss_grad for callers that cannot allocate device memory or hand over a scratch buffer: code under
+ * HIP graph capture, tight serving or training loops, harnesses that forbid hipMalloc.  Same arguments, results and
+ * errors as codistill_loss_grad, minus scratch / scratch_bytes: the per-row terms and the row counter go to a
+ * device array inside the library (16 + 8 * CD_LOSS_STATIC_MAX_ROWS bytes = 512 KiB + 16 B on every GPU the library
+ * runs on, held until the process ends).  The call allocates and frees nothing, on the device or through any
+ * library.  rows above CD_LOSS_STATIC_MAX_ROWS -> CD_ERR_INVALID_ARG, nothing launched.  All calls on one GPU share
+ * the one array: calls that may overlap on a GPU (different streams, different host threads) race on it and must
+ * be ordered by the caller; calls in stream order need nothing (each call writes what it later reads, nothing has
+ * to be cleared in between).
+ */
+#define CD_LOSS_STATIC_MAX_ROWS 65536
+int codistill_loss_grad_static(const float* z_local, const float* const* z_peers, const int32_t* targets,
+                               int64_t rows, int64_t cols, const cd_loss_cfg* cfg,
+                               float* loss_out, float* dz_out, void* stream);
+
+/*
  * Backward pass of the local model (Section 3: only with respect to the local parameters).
  * Consumes the workspace written by codistill_forward(..., save_for_backward = 1, ...) with the
  * same model, params, x and batch.

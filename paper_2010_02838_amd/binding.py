@@ -80,6 +80,7 @@ _SIGS = {
     "codistill_forward": [_vp, _vp, _vp, _i64, _i32, _i32, _vp, _vp, _sz, _vp, _vp],
     "codistill_loss_scratch_bytes": [_i64, _i64, ctypes.POINTER(_sz)],
     "codistill_loss_grad": [_vp, ctypes.POINTER(_vp), _vp, _i64, _i64, ctypes.POINTER(LossCfg), _vp, _vp, _vp, _sz, _vp],
+    "codistill_loss_grad_static": [_vp, ctypes.POINTER(_vp), _vp, _i64, _i64, ctypes.POINTER(LossCfg), _vp, _vp, _vp],
     "codistill_backward": [_vp, _vp, _vp, _i64, _vp, _sz, _vp, _vp, _vp],
     "codistill_sgd_step": [_vp, _vp, _vp, _vp, _i64, _f32, _f32, _f32, _i32, _vp],
     "codistill_adam_step": [_vp, _vp, _vp, _vp, _vp, _i64, _f32, _f32, _f32, _f32, _f32, _i64, _vp],
@@ -217,6 +218,17 @@ def codistill_loss_grad(z_local, z_peers, targets, loss_out, dz_out, scratch, al
     _check(lib.codistill_loss_grad(_ptr(z_local), arr if peers else None, _ptr(targets), rows, cols,
                                    ctypes.byref(cfg), _ptr(loss_out), _ptr(dz_out), _ptr(scratch),
                                    scratch.numel() * scratch.element_size(), _stream()))
+
+
+def codistill_loss_grad_static(z_local, z_peers, targets, loss_out, dz_out, alpha, label_smoothing=0.0,
+                               dist_kind=CD_DIST_MSE_LOGITS, mse_reduction=CD_MEAN_ALL, ignore_index=-1, temperature=1.0):
+    """codistill_loss_grad without a scratch argument (the library's own fixed device array; rows <= 65536)."""
+    rows, cols = z_local.shape
+    peers = list(z_peers) if z_peers is not None else []
+    cfg = LossCfg(alpha, label_smoothing, dist_kind, mse_reduction, ignore_index, len(peers), temperature)
+    arr = (_vp * max(len(peers), 1))(*[p.data_ptr() for p in peers])
+    _check(lib.codistill_loss_grad_static(_ptr(z_local), arr if peers else None, _ptr(targets), rows, cols,
+                                          ctypes.byref(cfg), _ptr(loss_out), _ptr(dz_out), _stream()))
 
 
 def codistill_backward(model, params, x, workspace, dlogits, grads_out):

@@ -11,6 +11,7 @@
 // one group of TPR threads owns one row, every thread holds V float4 of z and V float4 of z'.
 #include "common.h"
 #include <math.h>
+#include <mutex>
 
 namespace cd {
 
@@ -399,9 +400,11 @@ extern "C" int codistill_loss_scratch_bytes(int64_t rows, int64_t cols, size_t* 
   return CD_OK;
 }
 
-extern "C" int codistill_loss_grad(const float* z_local, const float* const* z_peers, const int32_t* targets,
-                                   int64_t rows, int64_t cols, const cd_loss_cfg* cfg, float* loss_out,
-                                   float* dz_out, void* scratch, size_t scratch_bytes, void* stream) {
+// Validation and launches shared by the two entry points; `scratch` is device memory of at least
+// loss_scratch_need(rows) bytes (the caller's, or this library's static array).
+static int loss_grad_run(const float* z_local, const float* const* z_peers, const int32_t* targets,
+                         int64_t rows, int64_t cols, const cd_loss_cfg* cfg, float* loss_out,
+                         float* dz_out, void* scratch, size_t scratch_bytes, void* stream) {
   CD_REQUIRE(z_local && targets && cfg && loss_out && dz_out && scratch, "loss_grad: NULL pointer argument");
   CD_REQUIRE(rows >= 1 && rows <= 2147483647LL, "loss_grad: rows=%lld out of range [1, 2^31-1]", (long long)rows);
   CD_REQUIRE(cols >= 1 && cols <= (1LL << 24), "loss_grad: cols=%lld out of range [1, 2^24]", (long long)cols);
@@ -467,4 +470,55 @@ extern "C" int codistill_loss_grad(const float* z_local, const float* const* z_p
   else launch_rows<1024, 8>(a, mode, s);
   hipLaunchKernelGGL(loss_finalize_kernel, dim3(1), dim3(256), 0, s, a, loss_out);
   return check_launch("loss_grad");
+}
+
+extern "C" int codistill_loss_grad(const float* z_local, const float* const* z_peers, const int32_t* targets,
+                                   int64_t rows, int64_t cols, const cd_loss_cfg* cfg, float* loss_out,
+                                   float* dz_out, void* scratch, size_t scratch_bytes, void* stream) {
+  return loss_grad_run(z_local, z_peers, targets, rows, cols, cfg, loss_out, dz_out, scratch, scratch_bytes, stream);
+}
+
+// ---- the same call for callers that cannot allocate ---------------------------------------------
+// The per-row terms and the row counter live in a device array that is part of the loaded code object
+// (one copy per GPU, held until the process ends).  The array's name is only a host-side handle: its
+// device address is looked up once per device and that address is what the kernels receive.
+static constexpr size_t kStaticScratchBytes = 16 + 2 * (size_t)CD_LOSS_STATIC_MAX_ROWS * 4;
+static __device__ __align__(256) unsigned char g_loss_static_scratch[kStaticScratchBytes];
+
+static constexpr int kMaxDevices = 64;
+static std::mutex g_static_mu;
+static void* g_static_ptr[kMaxDevices] = {};
+
+static int loss_static_scratch_ptr(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    (void)hipGetLastError();
+    return set_error(CD_ERR_HIP, "loss_grad_static: no current device (or device index above %d)", kMaxDevices - 1);
+  }
+  std::lock_guard<std::mutex> lk(g_static_mu);
+  if (!g_static_ptr[dev]) {
+    void* p = nullptr;
+    hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_loss_static_scratch));
+    if (e != hipSuccess || !p) {
+      (void)hipGetLastError();
+      return set_error(CD_ERR_HIP, "loss_grad_static: hipGetSymbolAddress: %s", hipGetErrorString(e));
+    }
+    g_static_ptr[dev] = p;
+  }
+  *out = g_static_ptr[dev];
+  return CD_OK;
+}
+
+extern "C" int codistill_loss_grad_static(const float* z_local, const float* const* z_peers, const int32_t* targets,
+                                          int64_t rows, int64_t cols, const cd_loss_cfg* cfg, float* loss_out,
+                                          float* dz_out, void* stream) {
+  CD_REQUIRE(rows >= 1 && rows <= CD_LOSS_STATIC_MAX_ROWS,
+             "loss_grad_static: rows=%lld outside [1, %d] (use codistill_loss_grad with a caller scratch for more rows)",
+             (long long)rows, CD_LOSS_STATIC_MAX_ROWS);
+  void* scratch = nullptr;
+  int rc = loss_static_scratch_ptr(&scratch);
+  if (rc != CD_OK) return rc;
+  // Every word of the scratch that a call reads (the row counter, status bits and the first `rows` per-row terms)
+  // is written earlier in the same call, so what the previous call left behind needs no clearing.
+  return loss_grad_run(z_local, z_peers, targets, rows, cols, cfg, loss_out, dz_out, scratch, kStaticScratchBytes, stream);
 }

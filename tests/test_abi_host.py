@@ -139,6 +139,11 @@ def test_loss_rejects_bad_arguments_before_launch():
     assert b"scratch" in B.lib.codistill_last_error()
     b = ctypes.c_size_t()
     assert B.lib.codistill_loss_scratch_bytes(0, 5, ctypes.byref(b)) == B.CD_ERR_INVALID_ARG
+    # the variant without a scratch argument: its row limit is checked before anything touches a device
+    gs = B.lib.codistill_loss_grad_static
+    assert gs(fake, peers, fake, 65537, 32, cfg(), fake, fake, None) == B.CD_ERR_INVALID_ARG
+    assert b"65536" in B.lib.codistill_last_error()
+    assert gs(fake, peers, fake, 0, 32, cfg(), fake, fake, None) == B.CD_ERR_INVALID_ARG
 
 
 def test_sgd_rejects_bad_arguments_before_launch():
