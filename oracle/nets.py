@@ -40,16 +40,11 @@ An architecture is (param_table, ops).  param_table is an ordered list of
 (name, shape, kind, fan_in); ops is a list of dicts over integer tensor ids
 (tensor 0 is the input image batch, the last op writes the logits).
 
-Reduced-precision storage.  The workloads run "bf16 compute with fp32 master
-weights": arithmetic is exact here (float64), but `forward` takes an optional
-`store` function that is applied to every tensor such a pipeline writes to
-memory - the output of each convolution, of each BatchNorm group (BatchNorm,
-then the residual add and ReLU that follow it, if any), and of the pools; ops
-carry a `stored` flag saying whether their output is such a tensor.  With
-store = round-to-bf16 the result is what an exact-arithmetic bf16-storage
-pipeline computes; the tests use it to measure how much of a deviation from the
-float64 result is due to storage rounding alone.  store=None (the default) is
-the plain float64 definition.
+Sensitivity studies.  `forward` takes an optional `perturb` map {tensor id: function}: the tensor
+is replaced by function(tensor) as soon as it has been computed, before any op reads it.  Tests use
+it to measure how far a small perturbation of chosen intermediate tensors (for instance rounding
+them to a shorter floating-point format) moves the float64 result.  perturb=None (the default) is
+the plain float64 definition; nothing in this package decides which tensors to perturb.
 """
 import numpy as np
 from . import layers as L
@@ -74,55 +69,55 @@ class Arch:
         w = self._p(name + ".w", (cout, k, k, cin // groups), "conv_w", cin // groups * k * k)
         b = self._p(name + ".b", (cout,), "bias") if bias else None
         y = self._t()
-        self.ops.append(dict(op="conv", x=x, y=y, w=w, b=b, stride=stride, pad=pad, stored=True))
+        self.ops.append(dict(op="conv", x=x, y=y, w=w, b=b, stride=stride, pad=pad))
         return y
 
-    def bn(self, x, name, c, stored=False):
+    def bn(self, x, name, c):
         g = self._p(name + ".gamma", (c,), "bn_gamma")
         b = self._p(name + ".beta", (c,), "bn_beta")
         y = self._t()
-        self.ops.append(dict(op="bn", x=x, y=y, gamma=g, beta=b, stored=stored))
+        self.ops.append(dict(op="bn", x=x, y=y, gamma=g, beta=b))
         return y
 
     def relu(self, x):
         y = self._t()
-        self.ops.append(dict(op="relu", x=x, y=y, stored=True))
+        self.ops.append(dict(op="relu", x=x, y=y))
         return y
 
     def add(self, a, b):
         y = self._t()
-        self.ops.append(dict(op="add", a=a, b=b, y=y, stored=False))
+        self.ops.append(dict(op="add", a=a, b=b, y=y))
         return y
 
     def maxpool(self, x, k, stride, pad):
         y = self._t()
-        self.ops.append(dict(op="maxpool", x=x, y=y, k=k, stride=stride, pad=pad, stored=True))
+        self.ops.append(dict(op="maxpool", x=x, y=y, k=k, stride=stride, pad=pad))
         return y
 
     def gap(self, x):
         y = self._t()
-        self.ops.append(dict(op="gap", x=x, y=y, stored=True))
+        self.ops.append(dict(op="gap", x=x, y=y))
         return y
 
     def layernorm(self, x, name, c):
         g = self._p(name + ".gamma", (c,), "bn_gamma")
         b = self._p(name + ".beta", (c,), "bn_beta")
         y = self._t()
-        self.ops.append(dict(op="layernorm", x=x, y=y, gamma=g, beta=b, stored=True))
+        self.ops.append(dict(op="layernorm", x=x, y=y, gamma=g, beta=b))
         return y
 
     def linear(self, x, name, fin, fout, bias=True):
         w = self._p(name + ".w", (fout, fin), "linear_w", fin)
         b = self._p(name + ".b", (fout,), "bias") if bias else None
         y = self._t()
-        self.ops.append(dict(op="linear", x=x, y=y, w=w, b=b, stored=False))
+        self.ops.append(dict(op="linear", x=x, y=y, w=w, b=b))
         return y
 
     def embed(self, name, vocab, d, col0, T, table=None):
         """Rows of the embedding table for the tokens in columns col0 .. col0+T of the input."""
         w = table if table is not None else self._p(name + ".w", (vocab, d), "embed_w", d)
         y = self._t()
-        self.ops.append(dict(op="embed", x=0, y=y, w=w, col0=col0, T=T, stored=True))
+        self.ops.append(dict(op="embed", x=0, y=y, w=w, col0=col0, T=T))
         return y, w
 
     def attention(self, q, q_col, kv, k_col, v_col, d, heads, S, causal, key_tokens):
@@ -131,13 +126,13 @@ class Arch:
         (padding excluded) limit the keys each sentence attends to."""
         y = self._t()
         self.ops.append(dict(op="attn", x=q, kv=kv, y=y, q_col=q_col, k_col=k_col, v_col=v_col, d=d, heads=heads,
-                             S=S, causal=causal, key_tokens=key_tokens, stored=True))
+                             S=S, causal=causal, key_tokens=key_tokens))
         return y
 
     def tied_linear(self, x, w):
         """Logits against an existing [vocab, d] table (no bias)."""
         y = self._t()
-        self.ops.append(dict(op="linear", x=x, y=y, w=w, b=None, stored=False))
+        self.ops.append(dict(op="linear", x=x, y=y, w=w, b=None))
         return y
 
     def n_params(self):
@@ -170,7 +165,7 @@ def resnet20(classes=10, widths=(16, 32, 64), blocks=(3, 3, 3)):
             u = a.bn(u, p + ".bn2", wd)
             if stride != 1 or cin != wd:
                 sc = a.conv(t, p + ".down.conv", cin, wd, 1, stride, 0, bias=False)
-                sc = a.bn(sc, p + ".down.bn", wd, stored=True)
+                sc = a.bn(sc, p + ".down.bn", wd)
             else:
                 sc = t
             t = a.relu(a.add(u, sc))
@@ -198,7 +193,7 @@ def resnet18(classes=1000, widths=(64, 128, 256, 512), blocks=(2, 2, 2, 2), stem
             u = a.bn(u, p + ".bn2", wd)
             if stride != 1 or cin != wd:
                 sc = a.conv(t, p + ".down.conv", cin, wd, 1, stride, 0, bias=False)
-                sc = a.bn(sc, p + ".down.bn", wd, stored=True)
+                sc = a.bn(sc, p + ".down.bn", wd)
             else:
                 sc = t
             t = a.relu(a.add(u, sc))
@@ -231,7 +226,7 @@ def resnext(classes=1000, widths=(256, 512, 1024, 2048), outs=(256, 512, 1024, 2
             u = a.bn(u, p + ".bn3", out)
             if bi == 0:
                 sc = a.conv(t, p + ".down.conv", cin, out, 1, stride, 0, bias=False)
-                sc = a.bn(sc, p + ".down.bn", out, stored=True)
+                sc = a.bn(sc, p + ".down.bn", out)
             else:
                 sc = t
             t = a.relu(a.add(u, sc))
@@ -259,7 +254,7 @@ def resnet50(classes=1000, widths=(64, 128, 256, 512), blocks=(3, 4, 6, 3), stem
             u = a.bn(u, p + ".bn3", 4 * wd)
             if bi == 0:
                 sc = a.conv(t, p + ".down.conv", cin, 4 * wd, 1, stride, 0, bias=False)
-                sc = a.bn(sc, p + ".down.bn", 4 * wd, stored=True)
+                sc = a.bn(sc, p + ".down.bn", 4 * wd)
             else:
                 sc = t
             t = a.relu(a.add(u, sc))
@@ -314,9 +309,9 @@ def transformer(S, Ts, Tt, d=512, heads=8, d_ff=2048, vocab=32768, enc_layers=6,
     return a
 
 
-def forward(arch, params, x, store=None, running=None, bn_eval=False):
+def forward(arch, params, x, running=None, bn_eval=False, perturb=None):
     """Training-mode forward.  params: dict name -> float64 array.  Returns (logits, tape).
-    store: optional function applied to the tensors a reduced-precision pipeline keeps in memory.
+    perturb: optional {tensor id: function}; see the module docstring.
     running: list with one [mean, var] pair per BatchNorm op, in graph order.  With bn_eval the BatchNorms
     normalise with these averages (evaluation mode; the tape then cannot be used for a backward pass);
     otherwise they use the batch's statistics and, if running is given, update it in place."""
@@ -324,8 +319,6 @@ def forward(arch, params, x, store=None, running=None, bn_eval=False):
     cache = {}
     bn_index = 0
     for i, o in enumerate(arch.ops):
-        if i > 0 and store is not None and arch.ops[i - 1]["stored"]:
-            T[arch.ops[i - 1]["y"]] = store(T[arch.ops[i - 1]["y"]])
         k = o["op"]
         if k == "conv":
             b = params[o["b"]] if o["b"] else None
@@ -366,6 +359,8 @@ def forward(arch, params, x, store=None, running=None, bn_eval=False):
                                          params[o["b"]] if o["b"] else None)
         else:
             raise ValueError(k)
+        if perturb is not None and o["y"] in perturb:
+            T[o["y"]] = perturb[o["y"]](T[o["y"]])
     return T[arch.ops[-1]["y"]], (T, cache)
 
 

@@ -30,16 +30,17 @@ def flatten(arch, d):
 def codistill_step(arch, theta, theta_peers, x, y, alpha, lr, momentum, v=None,
                    weight_decay=0.0, label_smoothing=0.0, dist="mse",
                    mse_reduction="mean_all", ignore_index=-1, nesterov=False,
-                   peer_archs=None, store=None):
+                   peer_archs=None, perturb=None, perturb_peers=None):
     """theta, theta_peers[j], v: flat vectors.  Returns a dict with logits, peer
     logits, losses, dlogits, flat gradient, updated flat parameters and momentum.
-    store: see nets.forward (None = plain float64)."""
+    perturb, perturb_peers[j]: see nets.forward (None = the plain float64 step)."""
     p_local = unflatten(arch, theta)
-    z, tape = nets.forward(arch, p_local, x, store)                # local forward
+    z, tape = nets.forward(arch, p_local, x, perturb=perturb)                # local forward
     z_peers = []
     for j, th in enumerate(theta_peers):                           # peer forwards: constants
         pa = arch if peer_archs is None else peer_archs[j]
-        zp, _ = nets.forward(pa, unflatten(pa, th), x, store)
+        zp, _ = nets.forward(pa, unflatten(pa, th), x,
+                             perturb=None if perturb_peers is None else perturb_peers[j])
         z_peers.append(zp)
     losses, dz = codistill_loss_grad(z, z_peers, y, alpha, label_smoothing, dist,
                                      mse_reduction, ignore_index)

@@ -16,6 +16,28 @@ def norm_err(a, b):
     return float(abs(np.linalg.norm(np.asarray(a, dtype=np.float64)) - nb) / nb) if nb > 0 else float(np.linalg.norm(a))
 
 
+def bf16_storage_points(arch):
+    """Which tensors of the oracle's op list the GPU pipeline keeps in memory as bf16, as a `perturb` map of
+    oracle.nets.forward (tensor id -> round to bf16): the outputs of convolutions / dense layers of the body,
+    of the pools, of LayerNorm, embedding and attention, of every ReLU, and of a BatchNorm that is read as the
+    shortcut operand of a residual add.  A BatchNorm followed by its ReLU (or by the add and the ReLU) is one
+    kernel on the GPU, which stores only the last of those tensors; the logits stay fp32.  This is knowledge of
+    the GPU pipeline and lives with the tests: the oracle only applies the map it is given."""
+    readers = {}
+    for o in arch.ops:
+        for key in ("x", "a", "b", "kv"):
+            if key in o:
+                readers.setdefault(o[key], []).append((o["op"], key))
+    points = {}
+    for o in arch.ops:
+        kind, y = o["op"], o["y"]
+        if kind in ("conv", "relu", "maxpool", "gap", "layernorm", "embed", "attn"):
+            points[y] = synth.round_bf16_f64
+        elif kind == "bn" and all(r == ("add", "b") for r in readers.get(y, [])):
+            points[y] = synth.round_bf16_f64
+    return points
+
+
 class Case:
     """Inputs of one codistillation step for an architecture (library preset kwargs + oracle arch)."""
 
@@ -70,12 +92,17 @@ class Case:
         if v_scale:
             self.v0 = (np.random.default_rng(5).standard_normal(self.th.size) * v_scale).astype(np.float32)
 
-    def oracle(self, alpha=1.0, lr=0.1, mu=0.9, wd=0.0, dist="mse", store=None, label_smoothing=0.0):
+    def oracle(self, alpha=1.0, lr=0.1, mu=0.9, wd=0.0, dist="mse", bf16_storage=False, label_smoothing=0.0):
+        """The float64 step.  bf16_storage: the same exact arithmetic with the tensors of bf16_storage_points rounded
+        to bf16 as they are produced (how far storage rounding alone moves the result on this workload)."""
+        pa = self.ref_arch if self.peer_ref is None else self.peer_ref
         return codistill_step(self.ref_arch, self.th.astype(np.float64), [self.thp.astype(np.float64)],
                               self.x.astype(np.float64), self.y, alpha, lr, mu,
                               v=None if self.v0 is None else self.v0.astype(np.float64), weight_decay=wd, dist=dist,
-                              store=store, label_smoothing=label_smoothing,
-                              peer_archs=None if self.peer_ref is None else [self.peer_ref])
+                              label_smoothing=label_smoothing,
+                              peer_archs=None if self.peer_ref is None else [self.peer_ref],
+                              perturb=bf16_storage_points(self.ref_arch) if bf16_storage else None,
+                              perturb_peers=[bf16_storage_points(pa)] if bf16_storage else None)
 
     def gpu(self, alpha=1.0, lr=0.1, mu=0.9, wd=0.0, dist="mse", label_smoothing=0.0):
         from paper_2010_02838_amd.runner import StepRunner, pack_flat, unpack_flat, to_device

@@ -8,14 +8,19 @@ fp32 models are held to tight end-to-end tolerances.  For bf16 models two things
     workspace) and must reproduce the tensor the kernel wrote, to bf16 rounding (forward
     activations, activation gradients) or to fp32 accumulation error (parameter gradients,
     BatchNorm statistics);
-  * end to end against the float64 oracle, to the stated 2e-2 - or, where rounding the stored
-    activations to bf16 alone (exact arithmetic, measured here with the oracle's `store` hook)
-    already moves the float64 result further than that, to twice that storage-noise floor.
-    At random initialisation on N(0,1) images all samples of a batch look alike, the
-    informative part of every activation and gradient is a small difference of large common
-    terms, and BatchNorm with batch statistics removes the common part, so storage rounding is
-    amplified layer after layer; the deviation is a property of the workload, not of a kernel.
+  * end to end against the float64 oracle, quantity by quantity (logits, loss terms, the norm of
+    every parameter-gradient tensor) to the stated 2e-2 - or, for a quantity that rounding the
+    stored activations to bf16 alone (float64 arithmetic, the oracle's `perturb` map filled in by
+    gpu_util.bf16_storage_points) already moves further than 1e-2, to twice that quantity's own
+    measured sensitivity; see compare_bf16.  At random initialisation on N(0,1) images all
+    samples of a batch look alike, the informative part of every activation and gradient is a
+    small difference of large common terms, and BatchNorm with batch statistics removes the
+    common part, so storage rounding is amplified layer after layer; that deviation is a
+    property of the workload, not of a kernel, and the first check is what pins the kernels.
 """
+import json
+import os
+
 import numpy as np
 import pytest
 
@@ -285,41 +290,90 @@ def check_layers(c, got):
     return worst
 
 
-def compare_bf16(c, ref, floor, got):
-    """End to end against float64: 2e-2, or twice the bf16-storage noise floor where that is larger."""
-    rows = []
-    e, f = rel(got["logits"], ref["logits"]), rel(floor["logits"], ref["logits"])
-    rows.append(("logits", e, f))
-    e2, f2 = rel(got["peer_logits"], ref["peer_logits"][0]), rel(floor["peer_logits"][0], ref["peer_logits"][0])
-    rows.append(("peer logits", e2, f2))
+STATED_TOL = 2e-2     # the stated tolerance of the bf16 step: relative, on logits, loss and per-tensor gradient norms
+L2_LIMIT = 0.5        # a tensor that storage rounding alone moves by more than this (L2) has no meaningful end-to-end gate
+
+
+def compare_bf16(c, ref, floor, got, plain=(), label=None):
+    """End to end against the float64 step, quantity by quantity.  e = distance of the GPU's value from the float64
+    one; f = distance, for the same quantity, of the float64-arithmetic step whose stored tensors are rounded to
+    bf16 (gpu_util.bf16_storage_points): what bf16 storage alone does to this quantity on this input.
+
+      logits, loss terms      e <= max(2e-2, 2 f)
+      every gradient tensor   L2:   ||g - g_ref|| / ||g_ref||     <= max(2e-2, 2 lf_i),  lf_i = the same distance of the
+                                                                                         storage-rounded step (<= 0.5)
+                              norm: | ||g|| - ||g_ref|| | / ||g_ref|| <= max(2e-2, lf_i)   (the stated quantity)
+      all gradient tensors    median norm error <= max(2e-2, 2 x the storage-rounded step's median)
+
+    Where f << 2e-2 these are the stated tolerance.  Where rounding the stored activations alone moves a quantity by
+    more than 1e-2, no bf16-storage pipeline can be held to 2e-2 on this input, and the gate is that quantity's own
+    measured sensitivity (never a bound borrowed from another tensor).  The per-tensor scale is the L2 distance lf_i:
+    it sums over all elements and is stable from one realisation of the rounding noise to the next (measured: GPU
+    L2 error / lf_i between 0.9 and 1.3 on every tensor of every workload here), while a norm error is one signed
+    number per tensor that can be near zero by chance; a norm error never exceeds the L2 distance, so the norm
+    gate is tighter than what the L2 gate already implies.  Tensors with lf_i > 0.5 (1 for the norm) are not gated here
+    (a bound near 1 would pass a zero tensor): they are listed, and their evidence is the teacher-forced per-op
+    test (check_layers).  The report also counts the tensors that meet the plain 2e-2.
+    plain: names in {"logits", "peer logits", "loss", "task", "distill", "median"} that must meet the plain 2e-2.
+    Returns the table as a dict (also written as JSON into $CODISTILL_TEST_REPORT_DIR when that is set)."""
+    rows = [("logits", rel(got["logits"], ref["logits"]), rel(floor["logits"], ref["logits"])),
+            ("peer logits", rel(got["peer_logits"], ref["peer_logits"][0]),
+             rel(floor["peer_logits"][0], ref["peer_logits"][0]))]
     for i, n in enumerate(("loss", "task", "distill")):
         rows.append((n, abs(got["loss"][i] - ref["loss"][i]) / abs(ref["loss"][i]),
                      abs(floor["loss"][i] - ref["loss"][i]) / abs(ref["loss"][i])))
-    rows[0] += (rel(got["logits"], floor["logits"]),)
-    rows[1] += (rel(got["peer_logits"], floor["peer_logits"][0]),)
-    for i in range(3):
-        rows[2 + i] += (abs(got["loss"][i] - floor["loss"][i]) / abs(floor["loss"][i]),)
-    for name, e, f, d in rows:
-        print("%-12s gpu-vs-f64 %.3e   bf16-storage floor %.3e   gpu-vs-bf16-storage-oracle %.3e" % (name, e, f, d))
-        assert e <= max(2e-2, 2 * f), (name, e, f)
+    report = {"scalars": {}, "tensors": {}, "ungated": []}
+    bad = []   # violations are collected and asserted after the table is printed and written
+    for name, e, f in rows:
+        print("%-12s gpu-vs-f64 %.3e   bf16-storage sensitivity %.3e" % (name, e, f))
+        report["scalars"][name] = (e, f)
+        if f > L2_LIMIT:
+            report["ungated"].append(name)
+            continue
+        if e > max(STATED_TOL, 2 * f) or (name in plain and e > STATED_TOL):
+            bad.append((name, e, f))
     Gg, Gr, Gf = c.per_tensor(got["grad"]), c.per_tensor(ref["grad"]), c.per_tensor(floor["grad"])
-    eg = np.array([norm_err(Gg[n], Gr[n]) for n in Gr])
-    ef = np.array([norm_err(Gf[n], Gr[n]) for n in Gr])
-    lg = np.array([rel(Gg[n], Gr[n]) for n in Gr])
-    lf = np.array([rel(Gf[n], Gr[n]) for n in Gr])
-    print("per-tensor gradient norm error: gpu median %.3e max %.3e | floor median %.3e max %.3e"
-          % (np.median(eg), eg.max(), np.median(ef), ef.max()))
-    print("per-tensor gradient L2 error:   gpu median %.3e max %.3e | floor median %.3e max %.3e"
-          % (np.median(lg), lg.max(), np.median(lf), lf.max()))
-    assert np.median(eg) <= max(2e-2, 2 * np.median(ef))
-    assert eg.max() <= max(2e-2, 2 * ef.max())
-    assert np.median(lg) <= max(2e-2, 2 * np.median(lf))
-    assert lg.max() <= max(2e-2, 2 * lf.max())
-    dn = np.array([norm_err(Gg[n], Gf[n]) for n in Gr])
-    dl = np.array([rel(Gg[n], Gf[n]) for n in Gr])
-    print("gpu vs bf16-storage oracle, per-tensor gradient: norm error median %.3e max %.3e | L2 median %.3e max %.3e"
-          % (np.median(dn), dn.max(), np.median(dl), dl.max()))
-    assert rel(got["theta"], ref["theta"]) <= max(2e-2, 2 * rel(floor["theta"], ref["theta"]))
+    eg, fg, over = [], [], []
+    for n in Gr:
+        e, f = norm_err(Gg[n], Gr[n]), norm_err(Gf[n], Gr[n])
+        le, lf = rel(Gg[n], Gr[n]), rel(Gf[n], Gr[n])
+        report["tensors"][n] = dict(norm=(e, f), l2=(le, lf))
+        eg.append(e)
+        fg.append(f)
+        if e > STATED_TOL:
+            over.append((e, f, lf, n))
+        if lf > L2_LIMIT:
+            report["ungated"].append(n + (" (L2)" if lf <= 1.0 else " (L2, norm)"))
+        elif le > max(STATED_TOL, 2 * lf):
+            bad.append(("gradient of " + n, le, lf))
+        if lf <= 1.0 and e > max(STATED_TOL, lf):
+            bad.append(("gradient norm of " + n, e, lf))
+    eg = np.array(eg)
+    report["grad_norm_median"], report["grad_norm_max"] = float(np.median(eg)), float(eg.max())
+    report["within_stated"] = int((eg <= STATED_TOL).sum())
+    l2 = np.array([v["l2"][0] for v in report["tensors"].values()])
+    l2f = np.array([v["l2"][1] for v in report["tensors"].values()])
+    print("per-tensor gradient norms: %d of %d within 2e-2; median %.3e, max %.3e" % (report["within_stated"], len(eg),
+                                                                                     np.median(eg), eg.max()))
+    print("per-tensor gradient L2:    gpu median %.3e max %.3e | storage sensitivity median %.3e max %.3e"
+          % (np.median(l2), l2.max(), np.median(l2f), l2f.max()))
+    for e, f, lf, n in sorted(over, reverse=True)[:12]:
+        print("   norm above 2e-2: %-28s gpu %.3e   storage-rounded step %.3e   its L2 distance %.3e" % (n, e, f, lf))
+    if report["ungated"]:
+        print("   not gated end to end (L2 storage sensitivity above %.1f): %d tensors, e.g. %s"
+              % (L2_LIMIT, len(report["ungated"]), ", ".join(report["ungated"][:6])))
+    if np.median(eg) > max(STATED_TOL, 2 * np.median(fg)):
+        bad.append(("median gradient norm error", float(np.median(eg)), float(np.median(fg))))
+    report["violations"] = bad
+    out = os.environ.get("CODISTILL_TEST_REPORT_DIR")
+    if out and label:
+        with open(os.path.join(out, "bf16_e2e_%s.json" % label), "w") as fh:
+            json.dump(report, fh)
+    assert not bad, bad
+    if "median" in plain:
+        assert np.median(eg) <= STATED_TOL
+    assert rel(got["theta"], ref["theta"]) <= STATED_TOL
+    return report
 
 
 def test_tall_tile_convolutions_bf16_layers():
@@ -393,7 +447,7 @@ def test_small_resnet_fp32_layers(name):
 def test_small_resnet_bf16_step(name):
     kw, mk, batch, res, classes = SMALL[name]
     c = Case(kw, mk(), "bf16", batch, res, classes)
-    compare_bf16(c, c.oracle(), c.oracle(store=synth.round_bf16_f64), c.gpu())
+    compare_bf16(c, c.oracle(), c.oracle(bf16_storage=True), c.gpu(), label="small_" + name)
 
 
 @pytest.mark.parametrize("peer", ["basic_imagenet_mfma", "resnext"])
@@ -404,7 +458,7 @@ def test_peer_of_another_architecture_bf16_step(peer):
     pkw, pmk, _, _, _ = SMALL[peer]
     c = Case(kw, mk(), "bf16", batch, res, classes, peer=(pkw, pmk()))
     assert c.peer.n_elements != c.model.n_elements
-    compare_bf16(c, c.oracle(), c.oracle(store=synth.round_bf16_f64), c.gpu())
+    compare_bf16(c, c.oracle(), c.oracle(bf16_storage=True), c.gpu(), label="mixed_pair_" + peer)
 
 
 def test_resnet20_bf16_layers():
@@ -413,15 +467,34 @@ def test_resnet20_bf16_layers():
     check_layers(c, c.gpu())
 
 
-def test_resnet20_bf16_step():
+@pytest.fixture(scope="module")
+def resnet20_step():
     c = Case(dict(kind=1), nets.resnet20(), "bf16", 128, 32, 10, jitter=0.0)
-    compare_bf16(c, c.oracle(), c.oracle(store=synth.round_bf16_f64), c.gpu())
+    return c, c.oracle(), c.oracle(bf16_storage=True), c.gpu()
+
+
+def test_resnet20_bf16_step(resnet20_step):
+    """Logits, loss terms and the median gradient norm meet the stated 2e-2 outright on this workload."""
+    c, ref, floor, got = resnet20_step
+    compare_bf16(c, ref, floor, got, plain=("logits", "peer logits", "loss", "task", "distill", "median"),
+                 label="resnet20_b128")
+
+
+@pytest.mark.xfail(strict=True, reason="the plain 2e-2 on EVERY per-tensor gradient norm is not met on this workload: "
+                   "measured 42 of 65 tensors within 2e-2, largest 1.6e-1 (a BatchNorm scale of the first stage); the "
+                   "float64-arithmetic step with bf16-rounded stored tensors gives 44 of 65 and 1.2e-1, i.e. bf16 "
+                   "storage itself, not a kernel, sets this; see compare_bf16 for what is asserted instead")
+def test_resnet20_bf16_every_gradient_norm_within_stated_tolerance(resnet20_step):
+    c, ref, floor, got = resnet20_step
+    Gg, Gr = c.per_tensor(got["grad"]), c.per_tensor(ref["grad"])
+    assert max(norm_err(Gg[n], Gr[n]) for n in Gr) <= STATED_TOL
 
 
 def test_resnet50_bf16_layers_reduced_batch():
-    """ResNet-50 at full 224x224 resolution and 1000 classes; batch 4 so that the float64 oracle
-    (which keeps every activation) finishes in about a minute."""
-    c = Case(dict(kind=2), nets.resnet50(), "bf16", 4, 224, 1000, jitter=0.0)
+    """ResNet-50 at full 224x224 resolution and 1000 classes, batch 32: the largest batch whose activations the
+    float64 oracle holds.  Same kernels, same N and K as the benchmarked batch of 256, M an eighth of it: the
+    last stage's convolutions have M = 1568 rows, several row tiles with a ragged last one."""
+    c = Case(dict(kind=2), nets.resnet50(), "bf16", 32, 224, 1000, jitter=0.0)
     check_layers(c, c.gpu())
 
 
@@ -429,7 +502,7 @@ def test_resnet50_bf16_step_reduced_batch():
     c = Case(dict(kind=2), nets.resnet50(), "bf16", 4, 224, 1000, jitter=0.0)
     ref = c.oracle()
     got = c.gpu()
-    compare_bf16(c, ref, c.oracle(store=synth.round_bf16_f64), got)
+    compare_bf16(c, ref, c.oracle(bf16_storage=True), got, label="resnet50_b4")
 
 
 @pytest.mark.parametrize("name,dtype_name", [("basic", "f32"), ("bottleneck_mfma", "bf16")])

@@ -48,20 +48,20 @@ def test_transformer_padded_sentences_bf16_layers(name):
 def test_transformer_padded_sentences_bf16_step():
     c = make("small", ragged=True)
     kw = dict(alpha=0.5, label_smoothing=0.1)
-    compare_bf16(c, c.oracle(**kw), c.oracle(store=synth.round_bf16_f64, **kw), c.gpu(**kw))
+    compare_bf16(c, c.oracle(**kw), c.oracle(bf16_storage=True, **kw), c.gpu(**kw), label="transformer_small_padded")
 
 
 @pytest.mark.parametrize("name", ["small", "ragged_vocab"])
 def test_transformer_bf16_step(name):
     c = make(name)
     kw = dict(alpha=0.5, label_smoothing=0.1)
-    compare_bf16(c, c.oracle(**kw), c.oracle(store=synth.round_bf16_f64, **kw), c.gpu(**kw))
+    compare_bf16(c, c.oracle(**kw), c.oracle(bf16_storage=True, **kw), c.gpu(**kw), label="transformer_" + name)
 
 
 def test_transformer_kl_step_and_base_shape_metadata():
     c = make("small")
     kw = dict(alpha=1.0, label_smoothing=0.1, dist="kl")
-    compare_bf16(c, c.oracle(**kw), c.oracle(store=synth.round_bf16_f64, **kw), c.gpu(**kw))
+    compare_bf16(c, c.oracle(**kw), c.oracle(bf16_storage=True, **kw), c.gpu(**kw), label="transformer_small_kl")
     B = c.B
     base = B.Model(B.arch_preset(B.CD_ARCH_TRANSFORMER), B.CD_BF16)
     assert sum(p["size"] for p in base.params) == 60915712

@@ -9,7 +9,7 @@ import torch
 from oracle import nets
 from paper_2010_02838_amd import synth
 
-from gpu_util import Case, rel
+from gpu_util import Case, bf16_storage_points, rel
 from test_gpu_step import check_layers, compare_bf16, compare_f32
 
 pytestmark = pytest.mark.gpu
@@ -45,8 +45,8 @@ def test_head_bf16_layers(shape):
 
 def test_head_bf16_step():
     c = head_case("bf16", 300, 136, 264, 1000)
-    compare_bf16(c, c.oracle(label_smoothing=0.1), c.oracle(label_smoothing=0.1, store=synth.round_bf16_f64),
-                 c.gpu(label_smoothing=0.1))
+    compare_bf16(c, c.oracle(label_smoothing=0.1), c.oracle(label_smoothing=0.1, bf16_storage=True),
+                 c.gpu(label_smoothing=0.1), label="transformer_head")
 
 
 def test_head_bf16_layers_base_widths():
@@ -66,8 +66,9 @@ def test_head_bf16_full_size_sampled():
     pick = np.random.default_rng(0).choice(rows, size=48, replace=False)
     P = c.per_tensor(c.th.astype(np.float64))
     Pp = c.per_tensor(c.thp.astype(np.float64))
-    z, _ = nets.forward(c.ref_arch, P, c.x[pick].astype(np.float64), store=synth.round_bf16_f64)
-    zp, _ = nets.forward(c.ref_arch, Pp, c.x[pick].astype(np.float64), store=synth.round_bf16_f64)
+    points = bf16_storage_points(c.ref_arch)
+    z, _ = nets.forward(c.ref_arch, P, c.x[pick].astype(np.float64), perturb=points)
+    zp, _ = nets.forward(c.ref_arch, Pp, c.x[pick].astype(np.float64), perturb=points)
     assert rel(got["logits"][pick], z) <= 5e-3
     assert rel(got["peer_logits"][pick], zp) <= 5e-3
     # gradient rows: the loss kernel's result for these rows from the GPU's own logits (mean over all rows)
