@@ -17,10 +17,31 @@
  *   - Unless marked "host", every data pointer is a DEVICE pointer owned by the
  *     caller, 16-byte aligned.  The library does not allocate, free or retain
  *     device memory; all temporary storage is the caller's workspace / scratch.
- *   - Calls only enqueue kernels on the caller's stream (`stream` is a
- *     hipStream_t passed as void*; NULL is the default stream) and never
- *     synchronise.  Arguments are validated on the host before any launch; a
- *     call that returns an error has launched nothing.
+ *   - Calls only enqueue work (`stream` is a hipStream_t passed as void*; NULL is
+ *     the default stream) and never synchronise the host.  Everything is enqueued
+ *     on the caller's stream, with one exception: codistill_backward forks the
+ *     weight gradients of the convolutions onto a second stream that the library
+ *     creates on first use (default priority, one per process) and joins it back
+ *     with an event before it returns, so the caller's stream still orders the
+ *     whole call.  CODISTILL_SERIAL=1 in the environment, or the built-in timer,
+ *     keeps every launch on the caller's stream.
+ *   - Arguments, and whether every op of the model has a kernel for them, are
+ *     checked on the host before any launch: a call that returns
+ *     CD_ERR_INVALID_ARG, CD_ERR_UNSUPPORTED or CD_ERR_WORKSPACE_TOO_SMALL has
+ *     launched nothing.  CD_ERR_HIP reports a failure of the runtime during or
+ *     after the launches: the outputs are then undefined and the device should
+ *     be synchronised before its buffers are reused.
+ *   - Threads: the entry points may be called from several host threads on
+ *     different streams.  codistill_backward calls are serialised among
+ *     themselves by a lock (they share the second stream); calls that share a
+ *     workspace, scratch or output buffer must be ordered by the caller.  One
+ *     device per process: the second stream lives on the device that was
+ *     current at the first codistill_backward.
+ *   - Environment switches read at call time, for comparing code paths (the
+ *     results agree; see the tests): CODISTILL_SERIAL, CODISTILL_FORCE_SIMPLE
+ *     (plain one-thread-per-output kernels instead of the MFMA ones),
+ *     CODISTILL_NO_POOL_FUSION, CODISTILL_WRITE_RESIDUAL_GRADS,
+ *     CODISTILL_SEPARATE_RELU_MASK, CODISTILL_PLAIN_ATTENTION.
  *   - Layouts: activations NHWC, filters [Cout][kh][kw][Cin], linear weights
  *     [out][in], logits row-major [rows][cols].  bf16 is the upper half of an
  *     IEEE float32, round-to-nearest-even.
@@ -57,7 +78,8 @@ enum { CD_DIST_MSE_LOGITS = 0, CD_DIST_KL = 1, CD_DIST_MSE_CENTERED = 2 };
 /* normaliser of the squared error: all rows*cols elements, or rows only */
 enum { CD_MEAN_ALL = 0, CD_MEAN_ROWS = 1 };
 
-/* BatchNorm mode of a forward pass.  Only batch statistics are implemented. */
+/* BatchNorm mode of a forward pass: the statistics of the batch (training, and the stale peer's pass), or the
+ * running averages (evaluation; forward only).  See codistill_forward. */
 enum { CD_BN_BATCH_STATS = 0, CD_BN_RUNNING = 1 };
 
 /* architecture families (the paper names ResNet50, Section 3; the others are
@@ -79,7 +101,8 @@ enum {
                                     (self-attention, feed-forward), decoder layers (causal self-attention, attention over
                                     the encoder output, feed-forward), every sublayer followed by its residual connection
                                     and LayerNorm; logits against the tied embedding table.  No dropout; every sentence
-                                    has in_h source and in_w target tokens (no padding).  CD_BF16 only */
+                                    has room for in_h source and in_w target tokens, shorter ones are padded with
+                                    negative ids (see cd_arch_desc).  CD_BF16 only */
   CD_ARCH_TRANSFORMER_HEAD = 3   /* the last position-wise sublayers of a Transformer decoder (Section 4 trains the
                                     Transformer of Vaswani et al.): h + W2 relu(W1 h + b1) + b2, LayerNorm, projection
                                     onto the vocabulary without bias.  The input is the hidden state of every

@@ -731,7 +731,8 @@ __global__ void __launch_bounds__(256) embed_bwd_k(const int32_t* __restrict__ t
 // The matrix-core kernels read 16-byte vectors: head dimension 64 or 32 and row pitches that keep every row aligned.
 // CODISTILL_PLAIN_ATTENTION=1 keeps the plain kernels (for comparing the two).
 static bool use_mfma(int dh, int64_t ldq, int64_t ldkv, int64_t ldo) {
-  static const bool plain = [] { const char* e = getenv("CODISTILL_PLAIN_ATTENTION"); return e && e[0] == '1'; }();
+  const char* e = getenv("CODISTILL_PLAIN_ATTENTION");
+  const bool plain = e && e[0] == '1';
   return !plain && (dh == 64 || dh == 32) && ldq % 8 == 0 && ldkv % 8 == 0 && ldo % 8 == 0;
 }
 

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stddef.h>
+#include <mutex>
 #include "codistill.h"
 
 namespace cd {
@@ -34,7 +35,8 @@ struct ProfScope {
 // events; nullptr if the runtime refuses.  timer_enabled(): the per-launch timer is on, callers then
 // keep everything on one stream so that a launch's duration is its own.
 hipStream_t side_stream();
-hipEvent_t side_event(int i);
+hipEvent_t side_event(int i);      // creates events 0..i on first use; nullptr if the runtime refuses
+std::mutex& side_mutex();          // held by a call from its first fork onto the side stream to its join
 bool timer_enabled();
 
 // ---- bf16 ---------------------------------------------------------------------------------

@@ -111,7 +111,9 @@ __device__ inline void load_lds16(rsrc_words_t w, uint32_t lds_addr, uint32_t by
   asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                :
                : "s"(lds_addr), "v"(byte_off), "s"(w)
-               : "memory");  // M0 is reserved: the compiler keeps nothing in it, and nothing else here uses it
+               : "memory");  // M0 cannot be named as a clobber: the compiler treats it as a reserved register (it rejects
+                             // "m0" in a clobber list as such), i.e. it never keeps a value in M0 from one statement to
+                             // the next and writes M0 itself right before each of its own uses
 }
 // wait until at most N of this wave's vector memory loads are outstanding
 template <int N>

@@ -5,6 +5,7 @@
 // peer's, keeping nothing) and one backward pass, with respect to its own parameters only.
 // The executors below enqueue exactly that on the caller's stream.
 #include "model.h"
+#include <mutex>
 #include "kernels.h"
 #include <cstdio>
 #include <cstdlib>
@@ -676,6 +677,28 @@ double conv_bytes(const cd_model* m, const ConvGeom& g) {
 
 }  // namespace
 
+// What the op loops of forward and backward cannot run, found before the first launch (a call that returns an
+// error has launched nothing): grouped convolutions outside the kernels' limits, attention inputs with other readers.
+static int check_supported(const char* fn, const cd_model* m, const Plan& plan, int64_t batch, bool backward) {
+  const int dt = m->dtype;
+  for (size_t i = 0; i < m->ops.size(); i++) {
+    const Op& o = m->ops[i];
+    if (o.kind == OP_CONV && o.groups > 1) {
+      const ConvGeom g = conv_geom(m, o, batch);
+      if (dt != CD_BF16 || force_simple() || o.pb >= 0 || o.relu || g.Cin != g.Cout || (backward && (!plan.gx[i] || o.x == 0)))
+        return set_error(CD_ERR_UNSUPPORTED, "%s: this grouped convolution has no kernel (bf16, no bias, Cin = Cout, not on the input batch)", fn);
+    }
+    if (backward && o.kind == OP_ATTN) {
+      for (size_t j = i + 1; j < m->ops.size(); j++) {
+        const Op& q = m->ops[j];
+        if (q.x == o.x || q.res == o.x || (o.res != o.x && (q.x == o.res || q.res == o.res)))
+          return set_error(CD_ERR_UNSUPPORTED, "%s: the inputs of an attention op must have no other reader", fn);
+      }
+    }
+  }
+  return CD_OK;
+}
+
 extern "C" int codistill_forward(const cd_model* m, const void* params, const void* x, int64_t batch, int save,
                                  int bn_mode, float* bn_running, void* workspace, size_t workspace_bytes,
                                  float* logits_out, void* stream) {
@@ -692,6 +715,8 @@ extern "C" int codistill_forward(const cd_model* m, const void* params, const vo
   c.plan = make_plan(m, batch, save != 0);
   if (workspace_bytes < c.plan.total)
     return set_error(CD_ERR_WORKSPACE_TOO_SMALL, "forward: workspace %zu < %zu bytes", workspace_bytes, c.plan.total);
+  rc = check_supported("forward", m, c.plan, batch, false);
+  if (rc) return rc;
   c.ws = static_cast<char*>(workspace);
   c.params = static_cast<const char*>(params);
   c.x = x;
@@ -712,8 +737,6 @@ extern "C" int codistill_forward(const cd_model* m, const void* params, const vo
         if (o.groups > 1) {
           // grouped: slice-major copy of the input, dense per-slice filters, one dense convolution per slice of
           // channels, copy back (conv_grouped.hip); the BatchNorm behind it takes its statistics from the tensor
-          if (dt != CD_BF16 || force_simple() || o.pb >= 0 || o.relu || g.Cin != g.Cout)
-            return set_error(CD_ERR_UNSUPPORTED, "forward: this grouped convolution has no kernel (bf16, no bias, Cin = Cout)");
           const int C = g.Cin, sw = grouped_slice_width(C), ns = C / sw;
           const int64_t Min = batch * g.H * g.W, Mout = g.M();
           bf16_t* tmp0 = reinterpret_cast<bf16_t*>(c.ws + c.plan.gtmp);
@@ -870,6 +893,8 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
   c.plan = make_plan(m, batch, true);
   if (workspace_bytes < c.plan.total)
     return set_error(CD_ERR_WORKSPACE_TOO_SMALL, "backward: workspace %zu < %zu bytes", workspace_bytes, c.plan.total);
+  rc = check_supported("backward", m, c.plan, batch, true);
+  if (rc) return rc;
   c.ws = static_cast<char*>(workspace);
   c.params = static_cast<const char*>(params);
   c.x = x;
@@ -890,8 +915,22 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
   // but the optimizer needs its result: these launches fork onto a second stream (with their own
   // split-K partials) and run beside the data gradients and BatchNorm passes that follow; the
   // caller's stream waits for them at the end.  One stream when the per-launch timer is on.
-  hipStream_t side = (timer_enabled() || force_serial()) ? nullptr : side_stream();
+  // The side stream and its events belong to the library and are shared by every caller of this process: the lock
+  // is held from here to the join, so that two host threads never interleave forks on it.  Everything the forks
+  // need (the stream, one event per convolution and one for the join) exists before the first launch; if the
+  // runtime refuses any of it the call runs on the caller's stream alone.
+  std::unique_lock<std::mutex> side_lock(side_mutex(), std::defer_lock);
+  hipStream_t side = nullptr;
+  if (!timer_enabled() && !force_serial()) {
+    side_lock.lock();
+    int convs = 0;
+    for (const Op& o : m->ops) convs += o.kind == OP_CONV ? 1 : 0;
+    side = side_stream();
+    if (side && !side_event(convs)) side = nullptr;
+    if (!side) side_lock.unlock();
+  }
   int forks = 0;
+  int late_rc = CD_OK;   // a launch-time failure of the fork / join machinery: reported after the join was attempted
   std::vector<char> written(m->tensors.size(), 0);
   // gradients of residual inputs that are handed on as "dy and a bit mask" instead of being written
   // (see residual_grad_route)
@@ -962,8 +1001,7 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
         const TensorDesc& tkv = m->tensors[o.res];
         const TensorDesc& ty = m->tensors[o.y];
         const int d = ty.c, dh = d / o.heads, Tq = tx.h, Tk = tkv.h;
-        if (written[o.x] || written[o.res])
-          return set_error(CD_ERR_UNSUPPORTED, "backward: the inputs of an attention op must have no other reader");
+        // (inputs with another reader were rejected by check_supported before the first launch)
         const bf16_t* kvp = static_cast<const bf16_t*>(c.act(o.res));
         bf16_t* dkv = static_cast<bf16_t*>(c.grad(o.res));
         float* lse = reinterpret_cast<float*>(c.ws + c.plan.aux[i]);
@@ -1038,8 +1076,6 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
       case OP_CONV: {
         ConvGeom g = conv_geom(m, o, batch);
         if (o.groups > 1) {
-          if (dt != CD_BF16 || force_simple() || !c.plan.gx[i] || o.x == 0)
-            return set_error(CD_ERR_UNSUPPORTED, "backward: this grouped convolution has no kernel");
           const int C = g.Cin, sw = grouped_slice_width(C), ns = C / sw, taps = g.kh * g.kw;
           const int64_t Min = batch * g.H * g.W, Mout = g.M();
           bf16_t* dys = reinterpret_cast<bf16_t*>(c.ws + c.plan.gtmp);
@@ -1134,8 +1170,11 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
   if (forks > 0) {  // join: the caller's stream continues after the last weight gradient
     hipEvent_t ev = side_event(forks);
     if (!ev || hipEventRecord(ev, side) != hipSuccess || hipStreamWaitEvent(c.s, ev, 0) != hipSuccess) {
-      (void)hipStreamSynchronize(side);  // no event to wait on: fall back to a host-side join
+      (void)hipGetLastError();
+      late_rc = set_error(CD_ERR_HIP, "backward: could not join the weight-gradient stream (event record / wait failed); "
+                                      "synchronise the device before reading or freeing the buffers of this call");
     }
   }
+  if (late_rc) return late_rc;
   return check_launch("backward");
 }

@@ -94,6 +94,11 @@ hipStream_t side_stream() {
   return g_side_stream;
 }
 
+std::mutex& side_mutex() {
+  static std::mutex mu;
+  return mu;
+}
+
 hipEvent_t side_event(int i) {
   std::lock_guard<std::mutex> lk(g_side_mu);
   while ((int)g_side_events.size() <= i) {

@@ -115,6 +115,7 @@ class Case:
         r.step(xd, yd, alpha, lr, mu, weight_decay=wd, label_smoothing=label_smoothing,
                dist_kind={"kl": B.CD_DIST_KL, "mse": B.CD_DIST_MSE_LOGITS, "mse_centered": B.CD_DIST_MSE_CENTERED}[dist])
         torch.cuda.synchronize()
+        self.last_step = dict(lr=lr, mu=mu, wd=wd)
         got = dict(logits=r.logits.cpu().numpy(), peer_logits=r.peer_logits[0].cpu().numpy(),
                    loss=r.loss.cpu().numpy()[:3].astype(np.float64), dz=r.dz.cpu().numpy(),
                    grad=unpack_flat(model, r.grads.cpu().numpy()), theta=unpack_flat(model, r.master.cpu().numpy()),

@@ -116,3 +116,12 @@ def test_transformer_adam_updates_through_the_runner():
         bits = r.lowp.view(torch.int16).cpu().numpy().view(np.uint16)
         np.testing.assert_array_equal(bits, synth.bf16_bits(got))
     assert r.updates == 2
+
+
+@pytest.mark.parametrize("name", ["mid", "long"])
+def test_plain_attention_switch_bf16_layers(monkeypatch, name):
+    """CODISTILL_PLAIN_ATTENTION=1 runs head dimensions 32 and 64 on the plain fp32 attention kernels instead of the
+    matrix-core ones: same per-layer tolerances against the oracle, padded sentences included."""
+    monkeypatch.setenv("CODISTILL_PLAIN_ATTENTION", "1")
+    c = make(name, ragged=True)
+    check_layers(c, c.gpu(alpha=0.5, label_smoothing=0.1))

@@ -76,3 +76,15 @@ def test_head_bf16_full_size_sampled():
                                            c.y[pick], 1.0, label_smoothing=0.1)
     assert rel(got["dz"][pick] * (rows / len(pick)), dz) <= 1e-5
     assert np.isfinite(got["grad"]).all() and np.isfinite(got["loss"]).all()
+
+
+def test_separate_relu_mask_switch_agrees(monkeypatch):
+    """CODISTILL_SEPARATE_RELU_MASK=1 runs the backward pass of the feed-forward layer's fused ReLU as a kernel of its
+    own instead of in the epilogue of the data-gradient kernel: masking is exact, so the gradients agree."""
+    a = head_case("bf16", 300, 136, 264, 1000).gpu(label_smoothing=0.1)
+    monkeypatch.setenv("CODISTILL_SEPARATE_RELU_MASK", "1")
+    c = head_case("bf16", 300, 136, 264, 1000)
+    b = c.gpu(label_smoothing=0.1)
+    check_layers(c, b)
+    np.testing.assert_array_equal(a["logits"], b["logits"])
+    assert rel(b["grad"], a["grad"].astype(np.float64)) <= 1e-6
