@@ -33,6 +33,7 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch of the two roofline kernels from hardware counters (two rocprofv3 --pmc passes of
 # this script, FETCH_SIZE then WRITE_SIZE, each scaled by what the same counter read for the 1 GiB copy of
 # --copy-calibration).  Valid only for the kernels the counters were taken on: set to None when one changes.
+TRAFFIC_SOURCE = "profiles/resnet50_bs256_step_hbm_counters.md"
 ROOFLINE_TRAFFIC_BYTES = 260.2e6        # bn_apply_k<bf16,8,true>: FETCH_SIZE 76161.8 KiB x 2.000 + WRITE_SIZE 101798.1 KiB x 1.000
 ROOFLINE_CONV_TRAFFIC_BYTES = 221.5e6   # igemm_kernel<0,128,256,...>: FETCH_SIZE 41240.6 KiB x 2.000 + WRITE_SIZE 133859.5 KiB x 1.000
 
@@ -52,7 +53,7 @@ def roofline_of(flops, nbytes, ms, launches, kernel, traffic, event_overhead_us=
             "peak": PEAK_HBM_GBS if hbm_bound else PEAK_BF16_TFLOPS,
             "unit": "GB/s" if hbm_bound else "TFLOP/s",
             "frac": gbs / PEAK_HBM_GBS if hbm_bound else tflops / PEAK_BF16_TFLOPS,
-            "traffic": traffic,
+            "traffic": traffic, "traffic_source": TRAFFIC_SOURCE if traffic is not None else None,
             "algorithmic_bytes_per_launch": nbytes / max(launches, 1),
             "flop_per_launch": flops / max(launches, 1),
             "intensity_flop_per_byte": intensity, "ridge_flop_per_byte": ridge,
@@ -63,17 +64,16 @@ def roofline_of(flops, nbytes, ms, launches, kernel, traffic, event_overhead_us=
             "event_pair_overhead_us": event_overhead_us}
 
 
-def cpu_baseline(seconds_hint=20.0):
-    """Oracle step (ResNet-50, 224x224, batch 2) on the host cores: a baseline, not a target."""
+def cpu_baseline(seconds_hint=24.0):
+    """Oracle step (ResNet-50, 224x224, small batch) on the host cores, with the BLAS thread pool at all cores and at
+    one thread: a baseline, not a target.  Each setting: one calibration step at batch 2, then repeated steps at a batch
+    sized so that the setting takes about seconds_hint / 2 seconds; the median step time is reported."""
     import numpy as np
     from oracle import nets
     from oracle.step import codistill_step
     from paper_2010_02838_amd import synth
-    try:
-        from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-    except Exception:
-        cores = os.cpu_count() or 1
+    from threadpoolctl import threadpool_info, threadpool_limits
+    all_cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     arch = nets.resnet50()
     th = synth.round_bf16(synth.he_init(arch.params, 1)).astype(np.float64)
     thp = synth.round_bf16(synth.he_init(arch.params, 2)).astype(np.float64)
@@ -85,13 +85,24 @@ def cpu_baseline(seconds_hint=20.0):
         codistill_step(arch, th, [thp], x, y, 1.0, 0.1, 0.9)
         return time.time() - t0
 
-    batch = 2
-    dt = run(batch)                       # calibration; on a many-core host this takes about a second
-    if dt < seconds_hint / 3:             # bounded sample of about seconds_hint seconds of CPU work
-        batch = int(max(2, min(24, batch * seconds_hint / dt)))
-        dt = run(batch)
-    return {"value": batch / dt, "unit": "samples/s", "cores": int(cores), "kind": "oracle",
-            "sample": "one float64 NumPy oracle step, ResNet-50 224x224, batch %d (%.1f s)" % (batch, dt)}
+    def measure(threads, budget):
+        with threadpool_limits(limits=threads):
+            per_sample = run(2) / 2                        # calibration
+            reps = 3
+            batch = int(max(1, min(24, budget / reps / per_sample)))
+            times = sorted(run(batch) for _ in range(reps))
+        med = times[len(times) // 2]
+        return {"value": batch / med, "cores": int(threads), "batch": batch, "steps": reps, "median_step_s": med,
+                "step_s": times}
+
+    full = measure(all_cores, seconds_hint * 0.5)
+    one = measure(1, seconds_hint * 0.5)
+    return {"value": full["value"], "unit": "samples/s", "cores": full["cores"], "kind": "oracle",
+            "sample": "float64 NumPy oracle step, ResNet-50 224x224: median of %d steps at batch %d with %d BLAS threads "
+                      "(%.1f s per step); one thread: median of %d steps at batch %d (%.1f s per step)"
+                      % (full["steps"], full["batch"], full["cores"], full["median_step_s"], one["steps"], one["batch"],
+                         one["median_step_s"]),
+            "all_threads": full, "one_thread": one}
 
 
 def loss_kernel_cfg5(B, torch, dev, iters=20):
@@ -183,25 +194,36 @@ def transformer_head(args, B, synth, StepRunner, pack_flat, to_device, torch, de
 
 def transformer(args, B, synth, StepRunner, pack_flat, torch, dev):
     """One codistillation step of the base encoder-decoder Transformer (two models: 6 + 6 layers, d_model 512,
-    8 heads, d_ff 2048, shared vocabulary 32768, bf16) on 64 sentence pairs of 128 + 128 tokens = 8192 target
-    tokens: token ids uniform, label smoothing 0.1, alpha 1, KL distillation term.  roofline: the kernel class
-    that takes the most time of the step."""
-    S, Ts, Tt, vocab = 64, 128, 128, 32768
+    8 heads, d_ff 2048, shared vocabulary 32768, bf16): label smoothing 0.1, alpha 1, KL distillation term, Adam.
+    Default batch: sentence pairs with source and target lengths uniform in [16, 128], drawn until they hold at
+    least 8192 target tokens (about 114 pairs), padded to 128 + 128 positions with negative ids (padding is masked
+    as a key, embeds as zero, takes no gradient; its target rows carry ignore_index); tokens/s counts the valid
+    target tokens.  --sentences uniform: 64 pairs of full length 128 + 128 (8192 target tokens, no padding).
+    roofline: the kernel class that takes the most time of the step."""
+    Ts, Tt, vocab = 128, 128, 32768
     arch = B.arch_preset(B.CD_ARCH_TRANSFORMER)
     big = args.transformer_size == "big"
+    budget = 8192
     if big:   # the model Section 4 trains: d_model 1024, 16 heads, d_ff 4096; about the 3.8 k tokens per GPU of its recipe
-        S = 30
+        budget = 3840
         arch = B.arch_preset(B.CD_ARCH_TRANSFORMER, widths=[1024, 4096, 16])
+    if args.sentences == "uniform":
+        S = budget // Tt
+        xh, yh = synth.tokens(S, Ts + Tt, vocab, seed=100), synth.labels(S * Tt, vocab, seed=3)
+        valid, src_tokens = S * Tt, S * Ts
+    else:
+        xh, yh, sl, tl = synth.sentence_pairs(budget, 16, 128, vocab, seed=100)
+        S, valid, src_tokens = xh.shape[0], int(tl.sum()), int(sl.sum())
     model, peer = B.Model(arch, B.CD_BF16), B.Model(arch, B.CD_BF16)
     table = model.param_table()
     r = StepRunner(model, [peer], S, dev)
     r.load(pack_flat(model, synth.he_init(table, 1)), [pack_flat(peer, synth.he_init(table, 2))])
-    x = torch.from_numpy(synth.tokens(S, Ts + Tt, vocab, seed=100)).to(dev)
-    y = torch.from_numpy(synth.labels(S * Tt, vocab, seed=3)).to(dev)
+    x = torch.from_numpy(xh).to(dev)
+    y = torch.from_numpy(yh).to(dev)
 
     def step():
         # Adam with the constants of the translation recipe the paper follows (Section 4)
-        r.step(x, y, 1.0, 5e-4, 0.0, label_smoothing=0.1, dist_kind=B.CD_DIST_KL, adam=(0.9, 0.98, 1e-8))
+        r.step(x, y, 1.0, 5e-4, 0.0, label_smoothing=0.1, dist_kind=B.CD_DIST_KL, ignore_index=-1, adam=(0.9, 0.98, 1e-8))
 
     for _ in range(args.warmup):
         step()
@@ -226,16 +248,19 @@ def transformer(args, B, synth, StepRunner, pack_flat, torch, dev):
     p = prof[top]
     roof = roofline_of(p["flops"], p["bytes"], p["ms"], p["launches"], "kernel class '%s' of the library's timer" % top, None)
     roof["launches_per_step"] = p["launches"] / psteps
+    name = "big" if big else "base"
     return {
-        "metric": "codistill-step target tokens/sec on 1 MI355X (Transformer-%s, %d x (128 + 128) tokens, vocab 32768)"
-                  % ("big" if big else "base", S),
-        "value": S * Tt / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "metric": "codistill-step target tokens/sec on 1 MI355X (Transformer-%s, %d sentence pairs, %d valid target tokens, "
+                  "vocab 32768)" % (name, S, valid),
+        "value": valid / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": "transformer_%s_codistill_step" % ("big" if big else "base"), "sentences": S,
-                   "source_tokens": Ts, "target_tokens": Tt, "d_model": arch.widths[0], "heads": arch.widths[2],
+        "config": {"workload": "transformer_%s_codistill_step%s" % (name, "" if args.sentences == "ragged" else "_uniform_lengths"),
+                   "sentences": S, "lengths": "uniform in [16, 128], padded to 128 + 128" if args.sentences == "ragged" else "128 + 128",
+                   "valid_target_tokens": valid, "valid_source_tokens": src_tokens, "padded_target_positions": S * Tt,
+                   "d_model": arch.widths[0], "heads": arch.widths[2],
                    "d_ff": arch.widths[1], "layers": "6+6", "vocab": vocab,
-                   "models": "2 x Transformer-%s (local fwd+bwd+Adam, peer fwd)" % ("big" if big else "base"), "alpha": 1.0,
+                   "models": "2 x Transformer-%s (local fwd+bwd+Adam, peer fwd)" % name, "alpha": 1.0,
                    "label_smoothing": 0.1,
                    "distillation": "kl", "optimizer": "adam(0.9, 0.98, 1e-8), lr 5e-4"},
         "loss": [float(v) for v in loss[:3]],
@@ -258,6 +283,9 @@ def main():
                          "tokens, a separate JSON line with its own metric")
     ap.add_argument("--transformer-size", default="base", choices=["base", "big"],
                     help="--workload transformer: base (64 sentences) or big (d_model 1024, 16 heads, d_ff 4096; 30 sentences)")
+    ap.add_argument("--sentences", default="ragged", choices=["ragged", "uniform"],
+                    help="--workload transformer: ragged (default) = lengths uniform in [16, 128] until the batch holds 8192 "
+                         "target tokens, padded; uniform = 64 pairs of 128 + 128 tokens")
     ap.add_argument("--peer", default="resnet50", choices=["resnet50", "resnet18", "resnext101"],
                     help="architecture of the stale peer of the ResNet-50 workload (Section 5 pairs different "
                          "architectures); the default line is the two-ResNet-50 step")
@@ -329,12 +357,17 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]   # step boundaries on the caller's stream
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for i in range(args.steps):
+        marks[i].record()
         step()
+    marks[-1].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
+    ms_median = per_step[len(per_step) // 2]
     loss = r.loss.cpu().numpy()
 
     # second pass: per-launch HIP events on the launch stream, per kernel class; the peer forward runs
@@ -370,7 +403,8 @@ def main():
     out = {
         "metric": "codistill-step samples/sec on 1 MI355X (%s, 224^2, bs%d)" % ("ResNet-50" if args.local == "resnet50" else args.local, batch),
         "value": batch / (ms_per_step * 1e-3), "unit": "samples/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "ms_per_step_median": ms_median,
+        "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "resnet50_codistill_step", "batch": batch, "resolution": res, "classes": classes,
                    "models": "2 x ResNet-50 (local fwd+bwd+SGD, peer fwd)" if default_pair else

@@ -14,6 +14,8 @@ classes, 32K-symbol vocabulary):
            BatchNorm shift and biases 0; `jitter` perturbs the scale/shift/bias
            tensors so that tests exercise them
   logits   N(0, sigma^2) float32
+  sentence pairs  lengths uniform in [16, 128], token ids uniform, drawn until a
+           batch holds about 8192 target tokens, padded with a negative id
 """
 import numpy as np
 
@@ -68,6 +70,27 @@ def images(batch, h, w, c, seed):
 def tokens(sentences, length, vocab, seed):
     """Uniform token ids, int32 [sentences, length] (stand-in for byte-pair encoded text)."""
     return _rng(seed).integers(0, vocab, size=(sentences, length)).astype(np.int32)
+
+
+def sentence_pairs(min_target_tokens, lo, hi, vocab, seed, pad=-1):
+    """A translation batch "of about min_target_tokens target tokens": sentence pairs with independent source and
+    target lengths uniform in [lo, hi] are drawn until the target lengths add up to at least min_target_tokens, then
+    padded to hi + hi columns with `pad` (a negative id).  Returns (x, y, src_len, tgt_len): x int32
+    [sentences, 2 * hi] token ids (source part, then target part, each padded at its end), y int32
+    [sentences * hi] one label per target position, `pad` on the padded ones."""
+    rng = _rng(seed)
+    src, tgt = [], []
+    while sum(tgt) < min_target_tokens:
+        src.append(int(rng.integers(lo, hi + 1)))
+        tgt.append(int(rng.integers(lo, hi + 1)))
+    S = len(src)
+    x = rng.integers(0, vocab, size=(S, 2 * hi)).astype(np.int32)
+    y = rng.integers(0, vocab, size=(S, hi)).astype(np.int32)
+    for i in range(S):
+        x[i, src[i]:hi] = pad
+        x[i, hi + tgt[i]:] = pad
+        y[i, tgt[i]:] = pad
+    return x, y.reshape(-1), np.array(src), np.array(tgt)
 
 
 def labels(n, classes, seed):
