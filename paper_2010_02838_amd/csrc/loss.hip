@@ -15,6 +15,28 @@
 
 namespace cd {
 
+// Streaming accesses for wide rows: every logit is read once and every gradient element written once, so the
+// loads and stores of the register-resident kernel carry the non-temporal hint (measured at 8192 x 32768:
+// 5.1 -> 5.5 TB/s; a plain two-reads-one-write copy goes from 6.0 to 6.4 TB/s with it).
+typedef float f32x4_nt __attribute__((ext_vector_type(4)));
+template <bool NT>
+__device__ inline float4 load4(const float* p) {
+  if (NT) {
+    const f32x4_nt v = __builtin_nontemporal_load(reinterpret_cast<const f32x4_nt*>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+  }
+  return *reinterpret_cast<const float4*>(p);
+}
+template <bool NT>
+__device__ inline void store4(float* p, float4 v) {
+  if (NT) {
+    const f32x4_nt q = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(q, reinterpret_cast<f32x4_nt*>(p));
+  } else {
+    *reinterpret_cast<float4*>(p) = v;
+  }
+}
+
 struct LossArgs {
   const float* z;
   const float* zp[CD_LOSS_MAX_PEERS];
@@ -86,6 +108,7 @@ __device__ inline bool row_target(const LossArgs& a, int64_t row, int& t) {
 template <int TPR, int V, int MODE>
 __global__ void __launch_bounds__((TPR > 256 ? TPR : 256)) loss_row_kernel(LossArgs a) {
   constexpr int BLOCK = TPR > 256 ? TPR : 256;
+  constexpr bool NT = TPR * V * 4 > 8192;   // rows of more than 32 KiB stream past the caches
   constexpr int RPB = BLOCK / TPR;
   __shared__ float smem[5 * 16];
   const int g = threadIdx.x / TPR;      // row group inside the block
@@ -105,8 +128,8 @@ __global__ void __launch_bounds__((TPR > 256 ? TPR : 256)) loss_row_kernel(LossA
   for (int i = 0; i < V; i++) {
     int64_t c = ((int64_t)i * TPR + lane) * 4;
     if (c < cols) {
-      x[i] = *reinterpret_cast<const float4*>(zr + c);
-      if (MODE) y[i] = *reinterpret_cast<const float4*>(pr + c);
+      x[i] = load4<NT>(zr + c);
+      if (MODE) y[i] = load4<NT>(pr + c);
     } else {
       x[i] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
       if (MODE) y[i] = x[i];
@@ -132,7 +155,7 @@ __global__ void __launch_bounds__((TPR > 256 ? TPR : 256)) loss_row_kernel(LossA
       for (int i = 0; i < V; i++) {
         int64_t c = ((int64_t)i * TPR + lane) * 4;
         if (c < cols) {
-          const float4 t = *reinterpret_cast<const float4*>(pj + c);
+          const float4 t = load4<NT>(pj + c);
           const float d0 = x[i].x - t.x, d1 = x[i].y - t.y, d2 = x[i].z - t.z, d3 = x[i].w - t.w;
           sq_extra += d0 * d0 + d1 * d1 + d2 * d2 + d3 * d3;
           y[i].x += t.x; y[i].y += t.y; y[i].z += t.z; y[i].w += t.w;
@@ -152,7 +175,7 @@ __global__ void __launch_bounds__((TPR > 256 ? TPR : 256)) loss_row_kernel(LossA
 #pragma unroll
     for (int i = 0; i < V; i++) {
       int64_t c = ((int64_t)i * TPR + lane) * 4;
-      if (c < cols) *reinterpret_cast<float4*>(outr + c) = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (c < cols) store4<NT>(outr + c, make_float4(0.f, 0.f, 0.f, 0.f));
     }
     if (lane == 0) { a.row_task[row] = 0.f; a.row_dist[row] = 0.f; }
     return;
@@ -245,7 +268,7 @@ __global__ void __launch_bounds__((TPR > 256 ? TPR : 256)) loss_row_kernel(LossA
         if (c + k == t) gk -= onehot;
         o[k] = gk;
       }
-      *reinterpret_cast<float4*>(outr + c) = make_float4(o[0], o[1], o[2], o[3]);
+      store4<NT>(outr + c, make_float4(o[0], o[1], o[2], o[3]));
     }
   }
 }
@@ -345,14 +368,21 @@ __global__ void __launch_bounds__(256) loss_row_generic_kernel(LossArgs a) {
 }
 
 // ---- step 3: deterministic sum of the per-row terms ------------------------------------------
-__global__ void __launch_bounds__(256) loss_finalize_kernel(LossArgs a, float* loss_out) {
-  __shared__ double s_t[256], s_d[256];
-  double st = 0.0, sd = 0.0;
-  for (int64_t r = threadIdx.x; r < a.rows; r += 256) { st += (double)a.row_task[r]; sd += (double)a.row_dist[r]; }
-  s_t[threadIdx.x] = st;
-  s_d[threadIdx.x] = sd;
+__global__ void __launch_bounds__(1024) loss_finalize_kernel(LossArgs a, float* loss_out) {
+  __shared__ double s_t[1024], s_d[1024];
+  // every thread adds its rows in a fixed order, four independent loads in flight at a time
+  double st[4] = {0.0, 0.0, 0.0, 0.0}, sd[4] = {0.0, 0.0, 0.0, 0.0};
+  for (int64_t r0 = threadIdx.x; r0 < a.rows; r0 += 4096) {
+#pragma unroll
+    for (int u = 0; u < 4; u++) {
+      const int64_t r = r0 + 1024 * u;
+      if (r < a.rows) { st[u] += (double)a.row_task[r]; sd[u] += (double)a.row_dist[r]; }
+    }
+  }
+  s_t[threadIdx.x] = (st[0] + st[1]) + (st[2] + st[3]);
+  s_d[threadIdx.x] = (sd[0] + sd[1]) + (sd[2] + sd[3]);
   __syncthreads();
-  for (int o = 128; o > 0; o >>= 1) {
+  for (int o = 512; o > 0; o >>= 1) {
     if ((int)threadIdx.x < o) { s_t[threadIdx.x] += s_t[threadIdx.x + o]; s_d[threadIdx.x] += s_d[threadIdx.x + o]; }
     __syncthreads();
   }
@@ -467,8 +497,8 @@ static int loss_grad_run(const float* z_local, const float* const* z_peers, cons
   else if (cols <= 4096) launch_rows<256, 4>(a, mode, s);
   else if (cols <= 8192) launch_rows<1024, 2>(a, mode, s);
   else if (cols <= 16384) launch_rows<1024, 4>(a, mode, s);
-  else launch_rows<1024, 8>(a, mode, s);
-  hipLaunchKernelGGL(loss_finalize_kernel, dim3(1), dim3(256), 0, s, a, loss_out);
+  else launch_rows<512, 16>(a, mode, s);   // fewer, fatter threads than 1024 x 8: fewer waves to synchronise per reduction
+  hipLaunchKernelGGL(loss_finalize_kernel, dim3(1), dim3(1024), 0, s, a, loss_out);
   return check_launch("loss_grad");
 }
 
