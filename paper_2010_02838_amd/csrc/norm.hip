@@ -11,12 +11,16 @@
 
 namespace cd {
 
+typedef float f32x4_ext __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4_ext __attribute__((ext_vector_type(4)));
+
 template <typename T, int VEC> struct Vec;
 // ld / st convert to and from fp32; ldraw + unpack split the load from the conversion, so that a kernel
 // can hold several loads in flight in their packed form (a quarter of the registers for bf16).
 template <> struct Vec<float, 1> {
   typedef float Raw;
   __device__ static Raw ldraw(const float* p) { return *p; }
+  __device__ static Raw ldraw_nt(const float* p) { return __builtin_nontemporal_load(p); }
   __device__ static void unpack(const Raw& r, float (&v)[1]) { v[0] = r; }
   __device__ static void ld(const float* p, float (&v)[1]) { v[0] = *p; }
   __device__ static void st(float* p, const float (&v)[1]) { *p = v[0]; }
@@ -24,6 +28,10 @@ template <> struct Vec<float, 1> {
 template <> struct Vec<float, 4> {
   typedef float4 Raw;
   __device__ static Raw ldraw(const float* p) { return *reinterpret_cast<const float4*>(p); }
+  __device__ static Raw ldraw_nt(const float* p) {
+    const f32x4_ext v = __builtin_nontemporal_load(reinterpret_cast<const f32x4_ext*>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+  }
   __device__ static void unpack(const Raw& t, float (&v)[4]) { v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w; }
   __device__ static void ld(const float* p, float (&v)[4]) {
     float4 t = *reinterpret_cast<const float4*>(p);
@@ -36,6 +44,7 @@ template <> struct Vec<float, 4> {
 template <> struct Vec<bf16_t, 1> {
   typedef bf16_t Raw;
   __device__ static Raw ldraw(const bf16_t* p) { return *p; }
+  __device__ static Raw ldraw_nt(const bf16_t* p) { return __builtin_nontemporal_load(p); }
   __device__ static void unpack(const Raw& r, float (&v)[1]) { v[0] = bf16_to_f32(r); }
   __device__ static void ld(const bf16_t* p, float (&v)[1]) { v[0] = bf16_to_f32(*p); }
   __device__ static void st(bf16_t* p, const float (&v)[1]) { *p = f32_to_bf16(v[0]); }
@@ -43,6 +52,11 @@ template <> struct Vec<bf16_t, 1> {
 template <> struct Vec<bf16_t, 8> {
   typedef uint4 Raw;
   __device__ static Raw ldraw(const bf16_t* p) { return *reinterpret_cast<const uint4*>(p); }
+  // read-once data: the non-temporal hint keeps it from displacing what later kernels re-read from the caches
+  __device__ static Raw ldraw_nt(const bf16_t* p) {
+    const u32x4_ext v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_ext*>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+  }
   __device__ static void unpack(const Raw& t, float (&v)[8]) {
     const uint32_t u[4] = {t.x, t.y, t.z, t.w};
 #pragma unroll
@@ -274,8 +288,8 @@ __global__ void __launch_bounds__(256) bn_apply_k(const T* __restrict__ x, const
     for (int u = 0; u < kEltUnroll; u++) {
       const int64_t i = ib + u * stride;
       if (i < nvec) {
-        ra[u] = Vec<T, VEC>::ldraw(x + i * VEC);
-        if (res) rr[u] = Vec<T, VEC>::ldraw(res + i * VEC);
+        ra[u] = Vec<T, VEC>::ldraw_nt(x + i * VEC);
+        if (res) rr[u] = Vec<T, VEC>::ldraw_nt(res + i * VEC);
       }
     }
 #pragma unroll
