@@ -96,6 +96,14 @@ enum {
                                     transformations; the largest model of the pairs of different architectures in
                                     Section 5).  CD_BF16 only; the grouped convolution's channel count must be a
                                     multiple of 8 and, above 128, of 128, with whole groups per 128 channels */
+  CD_ARCH_WIDE_RESNET_SPLIT = 7,  /* the modified Wide-ResNet of the multi-view experiment (Section 5): CD_ARCH_RESNET_BASIC
+                                    (3x3 stem, basic blocks; 28x10: three stages of four blocks, widths 160/320/640,
+                                    stem 16) whose first block is a frozen front end.  The front end's output channels
+                                    (widths[0] = 160) are cut into n_splits equal parts and the rest of the network
+                                    receives part `split` only (20 channels for 8 parts).  Frozen: codistill_backward
+                                    stops at the cut, the gradients of the stem and of the first block are written as
+                                    zeros (their parameters stay as loaded, "pre-trained").  Its BatchNorms use
+                                    the batch's statistics like every other */
   CD_ARCH_TRANSFORMER = 4,       /* the encoder-decoder Transformer of Section 4 (Vaswani et al.): embedding of the shared
                                     vocabulary times sqrt(d_model) plus the sinusoidal position signal; encoder layers
                                     (self-attention, feed-forward), decoder layers (causal self-attention, attention over
@@ -133,6 +141,8 @@ typedef struct {
   int32_t groups;                 /* CD_ARCH_RESNEXT: groups of the 3x3 convolution        */
   int32_t out_widths[CD_MAX_STAGES]; /* CD_ARCH_RESNEXT: output channels of a stage's blocks
                                         (widths[] are those of its grouped convolution)    */
+  int32_t n_splits, split;        /* CD_ARCH_WIDE_RESNET_SPLIT: parts the front end's output channels are
+                                     cut into (widths[0] % n_splits == 0), and the part this model receives */
 } cd_arch_desc;
 
 /* kind of a parameter tensor */
@@ -148,6 +158,9 @@ typedef struct {
   int64_t offset;    /* element offset in the flat parameter / gradient buffers     */
   int64_t size;      /* number of elements                                          */
   int64_t fan_in;    /* Cin*kh*kw or in_features; 0 for scale / shift / bias        */
+  int32_t frozen;    /* 1: the tensor belongs to a frozen front end (CD_ARCH_WIDE_RESNET_SPLIT):
+                        codistill_backward writes zeros as its gradient and the caller leaves it out of
+                        the update.  Frozen tensors come first in declaration order                  */
 } cd_tensor_info;
 
 typedef struct cd_model cd_model; /* opaque host object */
@@ -159,7 +172,8 @@ typedef struct cd_model cd_model; /* opaque host object */
  * CD_ARCH_RESNEXT (the 101-layer 32x8d model: blocks 3,4,23,3, grouped widths 256..2048 in 32 groups),
  * CD_ARCH_RESNET_BASIC_IMAGENET (ResNet-18: blocks 2,2,2,2, widths 64..512, 224x224, 1000 classes),
  * CD_ARCH_TRANSFORMER (the base model: 6 + 6 layers, d_model 512, 8 heads, d_ff 2048, vocabulary 32768,
- * 128 source and 128 target tokens per sentence). host. */
+ * 128 source and 128 target tokens per sentence), CD_ARCH_WIDE_RESNET_SPLIT (28x10 on 32x32 images, 10 classes,
+ * 8 parts of 20 channels, part 0). host. */
 int codistill_arch_preset(int kind, cd_arch_desc* out);
 
 /* Build the host-side description (op list, parameter table) of a model.
@@ -304,7 +318,8 @@ int codistill_adam_step(float* master_w, float* exp_avg, float* exp_avg_sq, cons
  * tools and tests can read intermediate activations and activation gradients after a forward /
  * backward pair.  Tensor 0 is the input batch; the last op writes the logits (not in the workspace). */
 enum { CD_OP_CONV = 0, CD_OP_BN = 1, CD_OP_MAXPOOL = 2, CD_OP_GAP = 3, CD_OP_LINEAR = 4, CD_OP_LN = 5,
-       CD_OP_EMBED = 6, CD_OP_ATTN = 7 };
+       CD_OP_EMBED = 6, CD_OP_ATTN = 7,
+       CD_OP_SLICE = 8 /* y = channels k .. k + width(y) of x; no gradient passes it (the ops in front of it are frozen) */ };
 typedef struct {
   int32_t kind;            /* CD_OP_*                                                           */
   int32_t x, y;            /* input / output tensor ids                                         */

@@ -16,6 +16,8 @@ gives as 8e8 bits) without defining them; these are the standard definitions:
              shortcut in the first block of every stage, global average pool,
              linear(2048->classes)+bias.
 
+  wide_resnet_split  the modified Wide-ResNet 28x10 of the multi-view experiment (Section 5); see the builder.
+
   transformer_head  the last position-wise sublayers of a Transformer decoder (Section 4 trains the
              Transformer of Vaswani et al.; base size: d_model 512, d_ff 2048, vocabulary 32768): the
              feed-forward sublayer W2 relu(W1 h + b1) + b2 with its residual connection and
@@ -50,11 +52,19 @@ import numpy as np
 from . import layers as L
 
 
+def op_params(o):
+    """Names of the parameters an op uses."""
+    keys = {"conv": ("w", "b"), "linear": ("w", "b"), "embed": ("w",), "bn": ("gamma", "beta"),
+            "layernorm": ("gamma", "beta")}.get(o["op"], ())
+    return [o[k] for k in keys if o.get(k)]
+
+
 class Arch:
     def __init__(self, name):
         self.name = name
         self.params = []      # (name, shape, kind, fan_in)
         self.ops = []
+        self.frozen = set()   # names of parameters in front of a frozen cut (never updated)
         self.n_tensors = 1    # tensor 0 = input
 
     def _t(self):
@@ -97,6 +107,13 @@ class Arch:
     def gap(self, x):
         y = self._t()
         self.ops.append(dict(op="gap", x=x, y=y))
+        return y
+
+    def frozen_slice(self, x, c0, n):
+        """Channels c0 .. c0+n of x.  Everything in front of it is frozen: no gradient passes it."""
+        y = self._t()
+        self.ops.append(dict(op="slice", x=x, y=y, c0=c0, n=n))
+        self.frozen = {name for o in self.ops for name in op_params(o)}
         return y
 
     def layernorm(self, x, name, c):
@@ -170,6 +187,40 @@ def resnet20(classes=10, widths=(16, 32, 64), blocks=(3, 3, 3)):
                 sc = t
             t = a.relu(a.add(u, sc))
             cin = wd
+    t = a.gap(t)
+    a.linear(t, "fc", cin, classes)
+    return a
+
+
+def wide_resnet_split(split=0, n_splits=8, classes=10, widths=(160, 320, 640), blocks=(4, 4, 4), stem=16):
+    """The modified Wide-ResNet of the paper's multi-view experiment (Section 5): a Wide-ResNet 28x10 (three stages of
+    four blocks, widths 160 / 320 / 640 behind a 16-channel 3x3 stem) whose first block is kept frozen; the 160
+    channels it produces are cut into n_splits = 8 parts of 20 and the rest of the network receives part `split`
+    only.  The paper gives no more than this; the block is the basic block of resnet20 above (the reading taken: the
+    experiment is about which channels the trainable part sees, not about the order of BatchNorm and convolution
+    inside a block).  Frozen: the backward pass stops at the cut and the front end's gradients are zero."""
+    a = Arch("wide_resnet_split")
+    t = a.conv(0, "stem.conv", 3, stem, 3, 1, 1, bias=False)
+    t = a.relu(a.bn(t, "stem.bn", stem))
+    cin = stem
+    for si, (wd, nb) in enumerate(zip(widths, blocks)):
+        for bi in range(nb):
+            stride = 2 if (si > 0 and bi == 0) else 1
+            p = "s%d.b%d" % (si + 1, bi)
+            u = a.conv(t, p + ".conv1", cin, wd, 3, stride, 1, bias=False)
+            u = a.relu(a.bn(u, p + ".bn1", wd))
+            u = a.conv(u, p + ".conv2", wd, wd, 3, 1, 1, bias=False)
+            u = a.bn(u, p + ".bn2", wd)
+            if stride != 1 or cin != wd:
+                sc = a.conv(t, p + ".down.conv", cin, wd, 1, stride, 0, bias=False)
+                sc = a.bn(sc, p + ".down.bn", wd)
+            else:
+                sc = t
+            t = a.relu(a.add(u, sc))
+            cin = wd
+            if si == 0 and bi == 0:
+                cin = wd // n_splits
+                t = a.frozen_slice(t, split * cin, cin)
     t = a.gap(t)
     a.linear(t, "fc", cin, classes)
     return a
@@ -340,6 +391,8 @@ def forward(arch, params, x, running=None, bn_eval=False, perturb=None):
             T[o["y"]], cache[i] = L.maxpool_forward(T[o["x"]], o["k"], o["stride"], o["pad"])
         elif k == "gap":
             T[o["y"]] = L.gap_forward(T[o["x"]])
+        elif k == "slice":
+            T[o["y"]] = T[o["x"]][..., o["c0"]:o["c0"] + o["n"]].copy()
         elif k == "layernorm":
             T[o["y"]], cache[i] = L.layernorm_forward(T[o["x"]], params[o["gamma"]], params[o["beta"]])
         elif k == "embed":
@@ -381,6 +434,10 @@ def backward(arch, params, tape, dlogits):
     for i in reversed(range(len(arch.ops))):
         o = arch.ops[i]
         k = o["op"]
+        if o["y"] not in G:     # in front of a frozen cut: no gradient arrives, the parameters' gradients are zero
+            for name in op_params(o):
+                grads.setdefault(name, np.zeros_like(params[name]))
+            continue
         dy = G.pop(o["y"])
         if k == "conv":
             dx, dw, db = L.conv2d_backward(T[o["x"]], params[o["w"]], dy, o["stride"], o["pad"],
@@ -402,6 +459,8 @@ def backward(arch, params, tape, dlogits):
             acc(o["x"], L.maxpool_backward(T[o["x"]].shape, cache[i], dy, o["k"], o["stride"], o["pad"]))
         elif k == "gap":
             acc(o["x"], L.gap_backward(T[o["x"]].shape, dy))
+        elif k == "slice":
+            pass                 # frozen cut: the gradient stops here
         elif k == "layernorm":
             dx, dg, db = L.layernorm_backward(dy, params[o["gamma"]], cache[i])
             grads[o["gamma"]], grads[o["beta"]] = dg, db

@@ -49,5 +49,13 @@ def codistill_step(arch, theta, theta_peers, x, y, alpha, lr, momentum, v=None,
     v0 = np.zeros_like(g) if v is None else np.asarray(v, dtype=np.float64)
     w_new, v_new = sgd.sgd_step(np.asarray(theta, dtype=np.float64), v0, g, lr, momentum,
                                 weight_decay, nesterov)
+    if arch.frozen:                                                # frozen parameters are left out of the update
+        off = 0
+        for name, shape, _, _ in arch.params:
+            n = int(np.prod(shape))
+            if name in arch.frozen:
+                w_new[off:off + n] = np.asarray(theta, dtype=np.float64)[off:off + n]
+                v_new[off:off + n] = v0[off:off + n]
+            off += n
     return dict(logits=z, peer_logits=z_peers, loss=losses, dlogits=dz, grad=g,
                 grads=grads, theta=w_new, v=v_new)

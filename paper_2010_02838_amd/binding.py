@@ -22,6 +22,7 @@ CD_ARCH_TINY_CNN, CD_ARCH_RESNET_BASIC, CD_ARCH_RESNET_BOTTLENECK, CD_ARCH_TRANS
 CD_ARCH_TRANSFORMER = 4
 CD_ARCH_RESNET_BASIC_IMAGENET = 5
 CD_ARCH_RESNEXT = 6
+CD_ARCH_WIDE_RESNET_SPLIT = 7
 CD_MAX_STAGES, CD_NAME_LEN, CD_LOSS_MAX_PEERS = 4, 48, 8
 KERNEL_CLASSES = ["conv_fprop", "conv_dgrad", "conv_wgrad", "norm", "glue", "linear", "loss", "sgd", "conv_fprop_narrow",
                   "bn_apply", "conv_fprop_wide", "attention"]
@@ -33,13 +34,13 @@ class ArchDesc(ctypes.Structure):
                 ("in_w", ctypes.c_int32), ("n_stages", ctypes.c_int32),
                 ("widths", ctypes.c_int32 * CD_MAX_STAGES), ("blocks", ctypes.c_int32 * CD_MAX_STAGES),
                 ("stem_width", ctypes.c_int32), ("groups", ctypes.c_int32),
-                ("out_widths", ctypes.c_int32 * CD_MAX_STAGES)]
+                ("out_widths", ctypes.c_int32 * CD_MAX_STAGES), ("n_splits", ctypes.c_int32), ("split", ctypes.c_int32)]
 
 
 class TensorInfo(ctypes.Structure):
     _fields_ = [("name", ctypes.c_char * CD_NAME_LEN), ("kind", ctypes.c_int32), ("ndim", ctypes.c_int32),
                 ("shape", ctypes.c_int64 * 4), ("offset", ctypes.c_int64), ("size", ctypes.c_int64),
-                ("fan_in", ctypes.c_int64)]
+                ("fan_in", ctypes.c_int64), ("frozen", ctypes.c_int32)]
 
 
 class OpInfo(ctypes.Structure):
@@ -149,7 +150,9 @@ class Model:
             ti = TensorInfo()
             _check(lib.codistill_param_info(self._h, i, ctypes.byref(ti)))
             self.params.append(dict(name=ti.name.decode(), kind=PARAM_KINDS[ti.kind], shape=tuple(ti.shape[:ti.ndim]),
-                                    offset=ti.offset, size=ti.size, fan_in=ti.fan_in))
+                                    offset=ti.offset, size=ti.size, fan_in=ti.fan_in, frozen=bool(ti.frozen)))
+        # frozen tensors (a frozen front end) come first: the update covers the flat buffers from here on
+        self.trainable_offset = min([p["offset"] for p in self.params if not p["frozen"]] + [self.n_elements])
         self.classes = arch.classes
         # rows of logits per element of the batch: target tokens per sentence for the Transformer, else 1
         self.rows_per_sample = arch.in_w if arch.kind == CD_ARCH_TRANSFORMER else 1
@@ -169,7 +172,7 @@ class Model:
         no, nt = _i64(), _i64()
         _check(lib.codistill_graph_size(self._h, ctypes.byref(no), ctypes.byref(nt)))
         ops, tensors = [], []
-        kinds = ["conv", "bn", "maxpool", "gap", "linear", "layernorm", "embed", "attn"]
+        kinds = ["conv", "bn", "maxpool", "gap", "linear", "layernorm", "embed", "attn", "slice"]
         for i in range(no.value):
             o = OpInfo()
             _check(lib.codistill_op_info(self._h, batch, i, ctypes.byref(o)))

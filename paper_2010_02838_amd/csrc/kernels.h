@@ -88,6 +88,10 @@ void linear_fwd(int dtype, const void* x, const void* w, const void* b, float* y
 void linear_bwd(int dtype, const void* x, const void* w, const float* dy, void* dx, bool accumulate, float* dw,
                 float* db, int64_t B, int F, int C, hipStream_t s);
 
+// y[m][j] = x[m][c0 + j], j < Cy (a range of channels of every pixel)
+void channel_slice(int dtype, const void* x, void* y, int64_t M, int Cx, int c0, int Cy, hipStream_t s);
+void fill_zero_f32(float* p, int64_t n, hipStream_t s);
+
 struct Gap { int64_t off; int32_t len; };
 void zero_gaps(float* base, const Gap* gaps, int n, hipStream_t s);
 

@@ -121,6 +121,30 @@ __global__ void __launch_bounds__(256) relu_bwd_k(T* __restrict__ dy, const T* _
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (i < n && !(Cvt<T>::ld(y[i]) > 0.f)) dy[i] = Cvt<T>::st(0.f);
 }
+template <typename T>
+__global__ void __launch_bounds__(256) channel_slice_k(const T* __restrict__ x, T* __restrict__ y, int64_t n, int Cx, int c0,
+                                                       int Cy) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  const int64_t m = i / Cy;
+  y[i] = x[m * Cx + c0 + (int)(i - m * Cy)];
+}
+void channel_slice(int dtype, const void* x, void* y, int64_t M, int Cx, int c0, int Cy, hipStream_t s) {
+  const int64_t n = M * Cy;
+  const dim3 grid((unsigned)cdiv(n, 256));
+  if (dtype == CD_BF16)
+    hipLaunchKernelGGL(channel_slice_k<bf16_t>, grid, dim3(256), 0, s, static_cast<const bf16_t*>(x), static_cast<bf16_t*>(y), n, Cx, c0, Cy);
+  else
+    hipLaunchKernelGGL(channel_slice_k<float>, grid, dim3(256), 0, s, static_cast<const float*>(x), static_cast<float*>(y), n, Cx, c0, Cy);
+}
+__global__ void __launch_bounds__(256) fill_zero_f32_k(float* p, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = 0.f;
+}
+void fill_zero_f32(float* p, int64_t n, hipStream_t s) {
+  if (n > 0) hipLaunchKernelGGL(fill_zero_f32_k, dim3((unsigned)cdiv(n, 256)), dim3(256), 0, s, p, n);
+}
+
 void relu_bwd_inplace(int dtype, void* dy, const void* y, int64_t n, hipStream_t s) {
   CD_DISPATCH_T(dtype, hipLaunchKernelGGL(relu_bwd_k<T>, grid1d(n), dim3(256), 0, s, (T*)dy, (const T*)y, n));
 }

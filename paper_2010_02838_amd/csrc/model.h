@@ -6,7 +6,7 @@
 
 namespace cd {
 
-enum OpKind { OP_CONV, OP_BN, OP_MAXPOOL, OP_GAP, OP_LINEAR, OP_LN, OP_EMBED, OP_ATTN };
+enum OpKind { OP_CONV, OP_BN, OP_MAXPOOL, OP_GAP, OP_LINEAR, OP_LN, OP_EMBED, OP_ATTN, OP_SLICE };
 
 struct TensorDesc {
   int h = 1, w = 1, c = 1;  // per-sample shape; a [B, F] tensor has h = w = 1
@@ -23,6 +23,7 @@ struct Op {
   int pw = -1, pb = -1;  // parameter indices: conv/linear weight + bias, BN gamma + beta
   int k = 1, stride = 1, pad = 0;
   int bn_slot = -1;    // OP_BN: index into the per-BN statistics area
+  // OP_SLICE: a0 = first channel of x that y receives (y is narrower than x); the ops in front of it are frozen.
   // OP_EMBED: a0 = first token column of the input, a1 = tokens per sentence.
   // OP_ATTN: a0, a1, a2 = first column of the queries in x, of the keys and of the values in res;
   //          heads, causal; the width of each column range is the width of y.
@@ -81,6 +82,7 @@ struct cd_model {
   int64_t bn_c_total = 0;  // sum of BN channel counts
   std::vector<int64_t> bn_off;  // per BN slot: channel offset into the statistics area
   int max_c = 1;
+  int first_trainable_op = 0;   // ops before it are frozen: the backward pass stops there (index behind an OP_SLICE)
   size_t esize() const { return dtype == CD_BF16 ? 2 : 4; }
 };
 

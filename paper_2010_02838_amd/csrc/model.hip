@@ -71,6 +71,15 @@ struct Builder {
     m->ops.push_back(o);
     return o.y;
   }
+  int slice(int x, int c0, int n) {
+    const TensorDesc tx = m->tensors[x];
+    Op o;
+    o.kind = OP_SLICE; o.x = x; o.a0 = c0;
+    o.y = add_tensor(tx.h, tx.w, n);
+    m->ops.push_back(o);
+    m->first_trainable_op = (int)m->ops.size();
+    return o.y;
+  }
   int gap(int x) {
     const TensorDesc tx = m->tensors[x];
     Op o;
@@ -262,6 +271,11 @@ void build_resnet(Builder& b, const cd_arch_desc& a) {
         t = b.bn(u, p2.g, p2.b, sc, true);
       }
       cin = cout;
+      if (a.kind == CD_ARCH_WIDE_RESNET_SPLIT && si == 0 && bi == 0) {
+        // the frozen front end ends here: the rest of the network receives one part of its output channels
+        cin = cout / a.n_splits;
+        t = b.slice(t, a.split * cin, cin);
+      }
     }
   }
   t = b.gap(t);
@@ -482,6 +496,10 @@ extern "C" int codistill_arch_preset(int kind, cd_arch_desc* out) {
     out->classes = 1000; out->in_h = out->in_w = 224; out->n_stages = 4; out->stem_width = 64;
     const int w[4] = {64, 128, 256, 512};
     for (int i = 0; i < 4; i++) { out->widths[i] = w[i]; out->blocks[i] = 2; }
+  } else if (kind == CD_ARCH_WIDE_RESNET_SPLIT) {
+    out->classes = 10; out->in_h = out->in_w = 32; out->n_stages = 3; out->stem_width = 16; out->n_splits = 8; out->split = 0;
+    const int w[3] = {160, 320, 640};
+    for (int i = 0; i < 3; i++) { out->widths[i] = w[i]; out->blocks[i] = 4; }
   } else if (kind == CD_ARCH_TRANSFORMER_HEAD) {
     out->classes = 32768; out->in_h = out->in_w = 1; out->n_stages = 0;
     out->widths[0] = 512; out->widths[1] = 2048;
@@ -500,7 +518,7 @@ extern "C" int codistill_model_create(const cd_arch_desc* a, int dtype, cd_model
   CD_REQUIRE(dtype == CD_F32 || dtype == CD_BF16, "model_create: unknown dtype %d", dtype);
   CD_REQUIRE(a->kind == CD_ARCH_TINY_CNN || a->kind == CD_ARCH_RESNET_BASIC || a->kind == CD_ARCH_RESNET_BOTTLENECK ||
                  a->kind == CD_ARCH_RESNET_BASIC_IMAGENET || a->kind == CD_ARCH_RESNEXT ||
-                 a->kind == CD_ARCH_TRANSFORMER_HEAD || a->kind == CD_ARCH_TRANSFORMER,
+                 a->kind == CD_ARCH_TRANSFORMER_HEAD || a->kind == CD_ARCH_TRANSFORMER || a->kind == CD_ARCH_WIDE_RESNET_SPLIT,
              "model_create: unknown architecture kind %d", a->kind);
   CD_REQUIRE(a->classes >= 1 && a->classes <= (1 << 24), "model_create: classes=%d out of range", a->classes);
   CD_REQUIRE(a->in_h >= 1 && a->in_w >= 1 && a->in_h <= 4096 && a->in_w <= 4096,
@@ -527,6 +545,12 @@ extern "C" int codistill_model_create(const cd_arch_desc* a, int dtype, cd_model
     for (int i = 0; i < a->n_stages; i++)
       CD_REQUIRE(a->widths[i] >= 1 && a->widths[i] <= 4096 && a->blocks[i] >= 1 && a->blocks[i] <= 64,
                  "model_create: stage %d width/blocks out of range", i);
+    if (a->kind == CD_ARCH_WIDE_RESNET_SPLIT) {
+      CD_REQUIRE(a->n_splits >= 1 && a->widths[0] % a->n_splits == 0 && a->split >= 0 && a->split < a->n_splits,
+                 "model_create: n_splits=%d must divide widths[0]=%d, and 0 <= split=%d < n_splits", a->n_splits, a->widths[0],
+                 a->split);
+      CD_REQUIRE(a->blocks[0] >= 2, "model_create: the first stage needs a block behind the frozen one");
+    }
     if (a->kind == CD_ARCH_RESNEXT) {
       if (dtype != CD_BF16) return set_error(CD_ERR_UNSUPPORTED, "model_create: grouped convolutions are implemented for CD_BF16 only");
       for (int i = 0; i < a->n_stages; i++) {
@@ -587,6 +611,8 @@ extern "C" int codistill_param_info(const cd_model* m, int64_t idx, cd_tensor_in
   out->kind = p.kind; out->ndim = p.ndim;
   for (int i = 0; i < 4; i++) out->shape[i] = p.shape[i];
   out->offset = p.offset; out->size = p.size; out->fan_in = p.fan_in;
+  for (int i = 0; i < m->first_trainable_op; i++)
+    if (m->ops[i].pw == idx || m->ops[i].pb == idx) out->frozen = 1;
   return CD_OK;
 }
 
@@ -619,6 +645,7 @@ extern "C" int codistill_op_info(const cd_model* m, int64_t batch, int64_t idx, 
   if (o.kind == OP_LN) out->stats_offset = (int64_t)make_plan(m, batch, true).aux[idx];
   out->k_col = out->v_col = 0;
   if (o.kind == OP_EMBED) { out->k = o.a0; out->stride = o.a1; }
+  if (o.kind == OP_SLICE) out->k = o.a0;
   if (o.kind == OP_ATTN) {
     out->k = o.heads; out->stride = o.causal ? 1 : 0; out->pad = o.a0; out->k_col = o.a1; out->v_col = o.a2;
     out->key_tok0 = o.key_tok0;
@@ -844,6 +871,12 @@ extern "C" int codistill_forward(const cd_model* m, const void* params, const vo
         gap_fwd(dt, in, out, batch, tx.h * tx.w, tx.c, c.s);
         break;
       }
+      case OP_SLICE: {
+        const TensorDesc& ty = m->tensors[o.y];
+        ProfScope pr(CD_K_GLUE, c.s, 0, 2.0 * batch * ty.per_sample() * m->esize());
+        channel_slice(dt, in, out, batch * tx.h * tx.w, tx.c, o.a0, ty.c, c.s);
+        break;
+      }
       case OP_LINEAR: {
         const int F = tx.c, C = m->tensors[o.y].c;
         const int64_t rows = batch * tx.h * tx.w;
@@ -953,7 +986,13 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
     if (m->ops[j].res >= 0 && m->ops[j].res != m->ops[j].x) readers[m->ops[j].res]++;
   }
   std::vector<char> relu_done(m->tensors.size(), 0);
-  for (int i = (int)m->ops.size() - 1; i >= 0; i--) {
+  // frozen front end (the ops before first_trainable_op): no gradient reaches it; its parameters' gradients are zeros
+  for (int i = 0; i < m->first_trainable_op; i++) {
+    const Op& o = m->ops[i];
+    for (int pi : {o.pw, o.pb})
+      if (pi >= 0) fill_zero_f32(G(pi), m->params[pi].size, c.s);
+  }
+  for (int i = (int)m->ops.size() - 1; i >= m->first_trainable_op; i--) {
     const Op& o = m->ops[i];
     const TensorDesc& tx = m->tensors[o.x];
     const void* in = o.x == 0 ? x : c.act(o.x);
@@ -1019,6 +1058,7 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
         gap_bwd(dt, dy, dx, acc, batch, tx.h * tx.w, tx.c, c.s);
         break;
       }
+      case OP_SLICE: break;   // never reached: the loop stops behind it
       case OP_MAXPOOL: {
         if (pool_fused_bwd(i - 1)) continue;   // gathered by the BatchNorm's backward pass instead (nothing written)
         ProfScope pr(CD_K_GLUE, c.s, 0, (double)batch * tx.per_sample() * m->esize() * 2.25);

@@ -92,14 +92,17 @@ class StepRunner:
         B.codistill_loss_grad(self.logits, peer_logits, y, self.loss, self.dz, self.scratch, alpha,
                               label_smoothing, dist_kind, mse_reduction, ignore_index, temperature)
         B.codistill_backward(self.model, self.params(), x, self.ws, self.dz, self.grads)
+        t0 = self.model.trainable_offset      # a frozen front end (first in the flat buffers) is left out of the update
+        lowp = None if self.lowp is None else self.lowp[t0:]
         if adam is None:
-            B.codistill_sgd_step(self.master, self.momentum, self.grads, self.lowp, lr, momentum, weight_decay, nesterov)
+            B.codistill_sgd_step(self.master[t0:], self.momentum[t0:], self.grads[t0:], lowp, lr, momentum, weight_decay,
+                                 nesterov)
         else:   # the momentum buffer holds Adam's first moment
             if self.second_moment is None:
                 self.second_moment = torch.zeros_like(self.momentum)
             self.updates += 1
-            B.codistill_adam_step(self.master, self.momentum, self.second_moment, self.grads, self.lowp, lr, self.updates,
-                                  adam[0], adam[1], adam[2], weight_decay)
+            B.codistill_adam_step(self.master[t0:], self.momentum[t0:], self.second_moment[t0:], self.grads[t0:], lowp, lr,
+                                  self.updates, adam[0], adam[1], adam[2], weight_decay)
 
     def step(self, x, y, alpha, lr, momentum, weight_decay=0.0, label_smoothing=0.0,
              dist_kind=B.CD_DIST_MSE_LOGITS, mse_reduction=B.CD_MEAN_ALL, ignore_index=-1, nesterov=False, adam=None,

@@ -46,6 +46,8 @@ def test_param_tables_match_oracle(dtype):
         (B.arch_preset(B.CD_ARCH_RESNEXT), nets.resnext()),
         (B.arch_preset(B.CD_ARCH_RESNEXT, widths=[128, 256, 512, 1024], blocks=[3, 4, 6, 3]),
          nets.resnext(widths=(128, 256, 512, 1024), blocks=(3, 4, 6, 3))),
+        (B.arch_preset(B.CD_ARCH_WIDE_RESNET_SPLIT), nets.wide_resnet_split()),
+        (B.arch_preset(B.CD_ARCH_WIDE_RESNET_SPLIT, split=5), nets.wide_resnet_split(split=5)),
         (B.arch_preset(B.CD_ARCH_RESNET_BASIC, widths=[4, 8, 16], blocks=[2, 1, 1], stem_width=4),
          nets.resnet20(widths=(4, 8, 16), blocks=(2, 1, 1))),
         (B.arch_preset(B.CD_ARCH_RESNET_BOTTLENECK, widths=[4, 8, 8, 16], blocks=[2, 1, 1, 1], stem_width=8, classes=7),
@@ -57,6 +59,8 @@ def test_param_tables_match_oracle(dtype):
         m = B.Model(arch, dtype)
         assert _table(m) == [(n, tuple(s), k, f) for n, s, k, f in ref.params]
         assert sum(p["size"] for p in m.params) == ref.n_params()
+        assert {p["name"] for p in m.params if p["frozen"]} == ref.frozen
+        assert all(p["offset"] < m.trainable_offset for p in m.params if p["frozen"])
         for p in m.params:
             assert p["offset"] % 8 == 0
         assert m.n_elements >= ref.n_params()
@@ -88,6 +92,9 @@ def test_model_create_rejects_bad_arguments():
     assert B.lib.codistill_model_create(ctypes.byref(bad), B.CD_F32, ctypes.byref(h)) == B.CD_ERR_INVALID_ARG
     a2 = B.ArchDesc()
     assert B.lib.codistill_arch_preset(42, ctypes.byref(a2)) == B.CD_ERR_INVALID_ARG
+    for kw in (dict(n_splits=7), dict(split=8), dict(split=-1), dict(n_splits=0)):     # 160 channels in 8 parts
+        bad = B.arch_preset(B.CD_ARCH_WIDE_RESNET_SPLIT, **kw)
+        assert B.lib.codistill_model_create(ctypes.byref(bad), B.CD_BF16, ctypes.byref(h)) == B.CD_ERR_INVALID_ARG, kw
 
 
 def test_forward_backward_reject_bad_arguments_before_launch():

@@ -89,6 +89,15 @@ SMALL = {
     "resnext_slices": (dict(kind=6, widths=[256, 256], out_widths=[64, 64], groups=8, blocks=[1, 1], stem_width=32),
                        lambda: nets.resnext(classes=10, widths=(256, 256), outs=(64, 64), groups=8, blocks=(1, 1), stem=32),
                        3, 40, 10),
+    # the multi-view network (Section 5): a frozen first block, the rest sees one part of its output channels: 4 of 16
+    # (plain kernels for the convolutions that read them) ...
+    "wide_split": (dict(kind=7, widths=[16, 24, 32], blocks=[2, 1, 2], stem_width=8, n_splits=4, split=1),
+                   lambda: nets.wide_resnet_split(split=1, n_splits=4, classes=10, widths=(16, 24, 32), blocks=(2, 1, 2), stem=8),
+                   6, 16, 10),
+    # ... and 16 of 32 (matrix-core kernels throughout)
+    "wide_split_mfma": (dict(kind=7, widths=[32, 32, 48], blocks=[2, 1, 1], stem_width=16, n_splits=2, split=1),
+                        lambda: nets.wide_resnet_split(split=1, n_splits=2, classes=10, widths=(32, 32, 48), blocks=(2, 1, 1),
+                                                       stem=16), 5, 20, 10),
     # basic blocks behind the 7x7 stem and the max-pool (the ResNet-18 family)
     "basic_imagenet_mfma": (dict(kind=5, widths=[16, 24, 32, 40], blocks=[1, 2, 1, 1], stem_width=16),
                             lambda: nets.resnet18(classes=10, widths=(16, 24, 32, 40), blocks=(1, 2, 1, 1), stem=16),
@@ -170,8 +179,17 @@ def check_layers(c, got):
         else:
             note("pgrad", rel(G[name], g), tag + ".w", tol)
 
+    # ops in front of a frozen cut (the multi-view network): forward only; their parameter gradients are exact zeros
+    cut = max([j for j, o in enumerate(ops) if o["kind"] == "slice"] + [-1])
     for i, o in enumerate(ops):
         x = act(o["x"])
+        frozen = i < cut
+        if frozen:
+            for pi in (o["param_w"], o["param_b"]):
+                assert pi < 0 or not G[names[pi]].any(), names[pi]
+        if o["kind"] == "slice":
+            np.testing.assert_array_equal(act(o["y"]), x[..., o["k"]:o["k"] + tensors[o["y"]]["c"]])
+            continue
         fused_pool = o["kind"] == "bn" and o["fused_pool"]
         y = got["logits"].astype(np.float64) if o["y"] == logits_t else (None if fused_pool else act(o["y"]))
         dy = got["dz"].astype(np.float64) if o["y"] == logits_t else (None if fused_pool else grad_in(o["y"]))
@@ -184,6 +202,8 @@ def check_layers(c, got):
                 yr = L.relu_forward(yr)
                 dy = L.relu_backward(y, dy)
             note("act", rel(y, yr), tag, tol_t)
+            if frozen:
+                continue
             dx, dw, db = L.conv2d_backward(x, w, dy, o["stride"], o["pad"], b is not None, o["x"] != 0)
             pgrad(o, dw, tag, TOL_F32_TENSOR)
             if b is not None:
@@ -230,6 +250,8 @@ def check_layers(c, got):
                 unwritten[o["y"]] = yr
             else:
                 note("act", rel(y, yr), tag, tol_t)
+            if frozen:
+                continue
             dx, dg, db = L.batchnorm_backward(dy, w, cache)
             note("pgrad", rel(G[names[o["param_w"]]], dg), tag + ".gamma", TOL_F32_TENSOR)
             note("pgrad", rel(G[names[o["param_b"]]], db), tag + ".beta", TOL_F32_TENSOR)
@@ -378,6 +400,12 @@ def compare_bf16(c, ref, floor, got, plain=(), label=None):
     h = c.last_step
     v0 = np.zeros(c.th.size) if c.v0 is None else c.v0.astype(np.float64)
     w_new, v_new = sgd_step(c.th.astype(np.float64), v0, got["grad"].astype(np.float64), h["lr"], h["mu"], h["wd"], False)
+    off = 0
+    for n, shape, _, _ in c.ref_arch.params:      # a frozen front end is left out of the update
+        k = int(np.prod(shape))
+        if n in c.ref_arch.frozen:
+            w_new[off:off + k], v_new[off:off + k] = c.th[off:off + k], v0[off:off + k]
+        off += k
     assert rel(got["theta"], w_new) <= 1e-6 and rel(got["v"], v_new) <= 1e-6
     return report
 
@@ -494,6 +522,18 @@ def test_resnet20_bf16_every_gradient_norm_within_stated_tolerance(resnet20_step
     c, ref, floor, got = resnet20_step
     Gg, Gr = c.per_tensor(got["grad"]), c.per_tensor(ref["grad"])
     assert max(norm_err(Gg[n], Gr[n]) for n in Gr) <= STATED_TOL
+
+
+def test_wide_resnet_28x10_split_bf16_layers():
+    """The multi-view network at its real widths (Section 5: Wide-ResNet 28x10 on 32x32 images, 160 channels cut into
+    8 parts of 20, this model sees part 5), batch 32: every op teacher forced; the stem and the first block are
+    frozen (gradients exactly zero, weights not moved by the update)."""
+    c = Case(dict(kind=7, split=5), nets.wide_resnet_split(split=5), "bf16", 32, 32, 10, jitter=0.0)
+    got = c.gpu()
+    check_layers(c, got)
+    th, new = c.per_tensor(c.th), c.per_tensor(got["theta"])
+    for n in th:
+        assert (n in c.ref_arch.frozen) == bool(np.array_equal(th[n], new[n])), n
 
 
 def test_resnet50_bf16_layers_reduced_batch():

@@ -161,6 +161,30 @@ def test_parameter_counts():
     assert sum(1 for o in r18.ops if o["op"] == "conv") == 20
 
 
+def test_wide_resnet_split_structure():
+    """The multi-view network of Section 5: 160 channels behind the first block, 8 parts of 20; the part a model
+    receives is exactly that range of the front end's output; cutting changes the parameter count by the first
+    trainable block alone (its 3x3 filter shrinks to 20 input channels and it gains a projection shortcut)."""
+    full = nets.wide_resnet_split(split=0, n_splits=1)         # one part = all 160 channels: the unmodified network
+    assert round(full.n_params() / 1e5) == 365                 # the 36.5 M parameters Wide-ResNet 28x10 is known to have
+    cut = nets.wide_resnet_split(split=3)
+    assert cut.n_params() == full.n_params() - 9 * 160 * 160 + 9 * 20 * 160 + (20 * 160 + 2 * 160)
+    sl = [o for o in cut.ops if o["op"] == "slice"]
+    assert len(sl) == 1 and (sl[0]["c0"], sl[0]["n"]) == (60, 20)
+    assert cut.frozen == {n for n, _, _, _ in cut.params if n.startswith("stem.") or n.startswith("s1.b0.")}
+    small = [nets.wide_resnet_split(split=k, n_splits=4, classes=7, widths=(12, 16, 24), blocks=(2, 1, 1), stem=4) for k in range(4)]
+    th = synth.he_init(small[0].params, 1, jitter=0.1).astype(np.float64)
+    x = synth.images(3, 8, 8, 3, seed=0).astype(np.float64)
+    parts = []
+    for k, a in enumerate(small):
+        z, (T, _) = nets.forward(a, unflatten(a, th), x)
+        o = [q for q in a.ops if q["op"] == "slice"][0]
+        np.testing.assert_array_equal(T[o["y"]], T[o["x"]][..., 3 * k:3 * k + 3])
+        parts.append(T[o["y"]])
+        front = T[o["x"]]
+    np.testing.assert_array_equal(np.concatenate(parts, axis=-1), front)     # the parts tile the front end's output
+
+
 def _torch_forward(arch, params, x):
     T = {0: x.permute(0, 3, 1, 2)}
     for o in arch.ops:
@@ -179,6 +203,8 @@ def _torch_forward(arch, params, x):
             T[o["y"]] = F.max_pool2d(T[o["x"]], o["k"], o["stride"], o["pad"])
         elif k == "gap":
             T[o["y"]] = T[o["x"]].mean(dim=(2, 3))
+        elif k == "slice":          # frozen cut: a range of channels, detached from what produced it
+            T[o["y"]] = T[o["x"]][:, o["c0"]:o["c0"] + o["n"]].detach()
         elif k == "layernorm":      # over the channel axis (axis 1 in this NCHW view)
             t = T[o["x"]].permute(0, 2, 3, 1)
             t = F.layer_norm(t, t.shape[-1:], params[o["gamma"]], params[o["beta"]], 1e-5)
@@ -197,6 +223,9 @@ ARCHS = {
     "resnext_small": (lambda: nets.resnext(classes=7, widths=(8, 16, 16, 24), outs=(12, 16, 24, 32), groups=4,
                                            blocks=(2, 1, 1, 1), stem=8), (3, 40, 40, 3), 7),
     "resnet18_small": (lambda: nets.resnet18(classes=7, widths=(8, 8, 16, 16), blocks=(1, 2, 1, 1), stem=8), (3, 40, 40, 3), 7),
+    # the multi-view network: a frozen first block whose 12 output channels are cut into 4 parts, this model sees part 2
+    "wide_split_small": (lambda: nets.wide_resnet_split(split=2, n_splits=4, classes=7, widths=(12, 16, 24), blocks=(2, 1, 2),
+                                                       stem=4), (5, 16, 16, 3), 7),
 }
 
 
@@ -230,11 +259,13 @@ def test_step_matches_library_autograd(name, dist):
     leaves = [tp[n] for n, _, _, _ in arch.params]
     opt = torch.optim.SGD(leaves, lr=lr, momentum=mu, weight_decay=lam)
     loss.backward()
+    frozen = [p.grad is None for p in leaves]          # parameters in front of a frozen cut: the optimiser skips them
+    assert [n in arch.frozen for n, _, _, _ in arch.params] == frozen
     off = 0
     for p in leaves:                       # preload the momentum buffers with v0
         opt.state[p]["momentum_buffer"] = torch.tensor(v0[off:off + p.numel()]).reshape(p.shape).clone()
         off += p.numel()
-    g_ref = np.concatenate([p.grad.numpy().ravel() for p in leaves])
+    g_ref = np.concatenate([(torch.zeros_like(p) if p.grad is None else p.grad).numpy().ravel() for p in leaves])
     opt.step()
     w_ref = np.concatenate([p.detach().numpy().ravel() for p in leaves])
 
@@ -247,7 +278,7 @@ def test_step_matches_library_autograd(name, dist):
     np.testing.assert_allclose(out["theta"], w_ref, atol=1e-11)
 
 
-@pytest.mark.parametrize("name", ["tiny_cnn", "resnet20_small", "resnet50_small", "transformer_head_small"])
+@pytest.mark.parametrize("name", ["tiny_cnn", "resnet20_small", "resnet50_small", "transformer_head_small", "wide_split_small"])
 def test_step_gradient_by_finite_differences(name):
     mk, xs, classes = ARCHS[name]
     arch = mk()
@@ -266,15 +297,21 @@ def test_step_gradient_by_finite_differences(name):
     h = 1e-5
     # every tensor gets probed: one random coordinate each, plus a random direction
     off = 0
-    for _, shape, _, _ in arch.params:
+    trainable = np.ones(th.size)
+    for pname, shape, _, _ in arch.params:
         n = int(np.prod(shape))
+        if pname in arch.frozen:     # frozen parameters: the step's gradient is zero by definition, not the derivative
+            assert not g[off:off + n].any()
+            trainable[off:off + n] = 0.0
+            off += n
+            continue
         i = off + int(rng.integers(0, n))
         e = np.zeros_like(th)
         e[i] = h
         fd = (loss_at(th + e) - loss_at(th - e)) / (2 * h)
         assert abs(fd - g[i]) <= 2e-6 * max(1.0, abs(g[i])), (shape, fd, g[i])
         off += n
-    d = rng.standard_normal(th.size)
+    d = rng.standard_normal(th.size) * trainable
     d /= np.linalg.norm(d)
     fd = (loss_at(th + h * d) - loss_at(th - h * d)) / (2 * h)
     assert fd == pytest.approx(float(g.dot(d)), rel=1e-6, abs=1e-8)
