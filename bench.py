@@ -34,8 +34,12 @@ PEAK_HBM_GBS = 8000.0
 # this script, FETCH_SIZE then WRITE_SIZE, each scaled by what the same counter read for the 1 GiB copy of
 # --copy-calibration).  Valid only for the kernels the counters were taken on: set to None when one changes.
 TRAFFIC_SOURCE = "profiles/resnet50_bs256_step_hbm_counters.md"
-ROOFLINE_TRAFFIC_BYTES = 260.2e6        # bn_apply_k<bf16,8,true>: FETCH_SIZE 76161.8 KiB x 2.000 + WRITE_SIZE 101798.1 KiB x 1.000
-ROOFLINE_CONV_TRAFFIC_BYTES = 221.5e6   # igemm_kernel<0,128,256,...>: FETCH_SIZE 41240.6 KiB x 2.000 + WRITE_SIZE 133859.5 KiB x 1.000
+ROOFLINE_TRAFFIC_BYTES = 260.2e6        # bn_apply_k<bf16,8,true>: FETCH_SIZE 76166.7 KiB x 2.000 + WRITE_SIZE 101792.6 KiB x 1.000
+ROOFLINE_CONV_TRAFFIC_BYTES = 221.4e6   # igemm_kernel<0,128,256,...>: FETCH_SIZE 41159.5 KiB x 2.000 + WRITE_SIZE 133859.5 KiB x 1.000
+# Matrix-pipe busy share of that convolution kernel from hardware counters (SQ_VALU_MFMA_BUSY_CYCLES over
+# GRBM_GUI_ACTIVE x 1024 SIMDs, mean over its dispatches); None when the kernel changes.
+MFMA_COUNTER_SOURCE = "profiles/resnet50_bs256_step_mfma_counters.md"
+ROOFLINE_CONV_MFMA_BUSY = 0.217
 
 
 def roofline_of(flops, nbytes, ms, launches, kernel, traffic, event_overhead_us=None):
@@ -270,6 +274,46 @@ def transformer(args, B, synth, StepRunner, pack_flat, torch, dev):
     }
 
 
+def library_gemm_reference(torch, dev):
+    """The vendor GEMM (torch.matmul in bf16) on the matrix shapes of ResNet-50's convolutions at batch 256: 1x1
+    convolutions are plain [pixels x Cin] x [Cin x Cout] products, 3x3 convolutions are timed as the product an explicit
+    im2col would feed it ([pixels x 9 Cin], the gather itself not included), weight gradients as the transposed product over
+    the pixels.  A reference point for what the machine's tuned library reaches on these shapes; not part of the step."""
+    fwd = [("s1.c3 64>256 1x1", 802816, 256, 64), ("s2.c3 128>512 1x1", 200704, 512, 128), ("s3.c3 256>1024 1x1", 50176, 1024, 256),
+           ("s3.c1 1024>256 1x1", 50176, 256, 1024), ("s4.c3 512>2048 1x1", 12544, 2048, 512), ("s4.c1 2048>512 1x1", 12544, 512, 2048),
+           ("s3.c2 3x3 256 as GEMM", 50176, 256, 2304), ("s4.c2 3x3 512 as GEMM", 12544, 512, 4608), ("8192^3", 8192, 8192, 8192)]
+    wg = [("s1.c2 3x3 64", 802816, 64, 576), ("s1.c3 64>256", 802816, 256, 64), ("s2.c2 3x3 128", 200704, 128, 1152),
+          ("s3.c2 3x3 256", 50176, 256, 2304), ("s3.c3 256>1024", 50176, 1024, 256), ("s4.c2 3x3 512", 12544, 512, 4608),
+          ("s4.c3 512>2048", 12544, 2048, 512)]
+
+    def timed(fn):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / 10 * 1e3
+
+    rows = []
+    for name, M, N, K in fwd:
+        a = torch.randn(M, K, device=dev, dtype=torch.bfloat16)
+        w = torch.randn(N, K, device=dev, dtype=torch.bfloat16)
+        us = timed(lambda: a @ w.t())
+        rows.append({"product": "forward", "layer": name, "M": M, "N": N, "K": K, "us": us, "TFLOP/s": 2.0 * M * N * K / us / 1e6})
+    for name, M, N, K in wg:
+        dy = torch.randn(M, N, device=dev, dtype=torch.bfloat16)
+        x = torch.randn(M, K, device=dev, dtype=torch.bfloat16)
+        us = timed(lambda: dy.t() @ x)
+        rows.append({"product": "weight gradient", "layer": name, "M": M, "N": N, "K": K, "us": us,
+                     "TFLOP/s": 2.0 * M * N * K / us / 1e6})
+    return {"metric": "vendor-library bf16 GEMM time on ResNet-50 (batch 256) convolution shapes", "unit": "us", "n_gpus": 1,
+            "data": "synthetic", "dtype": "bf16", "config": {"workload": "library_gemm_reference"}, "rows": rows}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -277,7 +321,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--batch", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", default="resnet50", choices=["resnet50", "transformer_head", "transformer"],
+    ap.add_argument("--workload", default="resnet50",
+                    choices=["resnet50", "transformer_head", "transformer", "library_gemm_reference"],
                     help="resnet50 (default): the headline metric.  transformer_head: the output block of the base "
                          "Transformer (feed-forward sublayer, residual, LayerNorm, vocabulary projection) on 8192 target "
                          "tokens, a separate JSON line with its own metric")
@@ -311,6 +356,9 @@ def main():
     from paper_2010_02838_amd.runner import StepRunner, pack_flat, to_device
 
     dev = "cuda:0"
+    if args.workload == "library_gemm_reference":
+        print(json.dumps(library_gemm_reference(torch, dev)))
+        return
     if args.workload == "transformer_head":
         print(json.dumps(transformer_head(args, B, synth, StepRunner, pack_flat, to_device, torch, dev)))
         return
@@ -393,6 +441,8 @@ def main():
                                 "128x256 tiles, BatchNorm column sums in the epilogue)", ROOFLINE_CONV_TRAFFIC_BYTES if default_pair else None,
                                 ev_us)
     roofline_conv["launches_per_step"] = cw["launches"] / psteps
+    roofline_conv["mfma_busy_frac_counters"] = ROOFLINE_CONV_MFMA_BUSY if default_pair else None
+    roofline_conv["mfma_counter_source"] = MFMA_COUNTER_SOURCE if default_pair else None
     classes_ms = {k: round(v["ms"] / psteps, 4) for k, v in prof.items()}
     hbm = {}
     for k in ("bn_apply", "norm", "loss", "sgd"):

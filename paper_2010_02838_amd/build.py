@@ -42,5 +42,17 @@ def build(verbose=True, jobs=8):
     return LIB
 
 
+def build_layer_bench():
+    """The per-layer convolution timing program (bench_src/conv_layer_bench.hip), linked against libcodistill.so."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    exe = os.path.join(HERE, "conv_layer_bench")
+    subprocess.check_call([hipcc, "-O2", "-std=c++17", "--offload-arch=gfx950", "-w", "-I", os.path.join(ROOT, "include"),
+                           "-I", CSRC, "-o", exe, os.path.join(HERE, "bench_src", "conv_layer_bench.hip"), "-L", HERE,
+                           "-lcodistill", "-Wl,-rpath,$ORIGIN"])
+    return exe
+
+
 if __name__ == "__main__":
     print(build())
+    if "--layer-bench" in sys.argv:
+        print(build_layer_bench())
