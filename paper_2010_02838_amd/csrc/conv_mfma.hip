@@ -41,6 +41,11 @@ struct IgemmArgs {
   // (nullable) a tensor [M][N] of which the output is the gradient behind a ReLU: output elements whose element
   // of relu_out is not positive are written as zero (the ReLU's backward pass, without a pass of its own)
   const bf16_t* relu_out = nullptr;
+  // Grouped convolutions (sliced launches): the gathered tensor has src_pitch channels per pixel, of which column tile
+  // tn reads the Cs = BN channels [tn * BN, (tn + 1) * BN): the slice of channels whose groups the tile's output
+  // channels belong to.  The filter rows then hold kh * kw * Cs elements, zero outside a row's own group.
+  int src_pitch = 0;   // 0: Cs (an ordinary convolution)
+  int sliced = 0;
   int pointwise;  // kh = kw = 1, stride 1, no padding (set by the launcher)
   int group_m;    // GROUP kernels: tile order in groups of this many row tiles
   int ntiles;
@@ -192,7 +197,9 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
   // slot ^ ((row >> 2) & 3) of the tile (see lds_off), the same for all of the thread's rows.
   const int lrow = tid >> 2;
   const int kvec = (tid & 3) ^ ((tid >> 4) & 3);
-  int rowoff[AV];                 // element offset of (image, h0, w0, channel 0); may be negative
+  const int P = a.src_pitch ? a.src_pitch : a.Cs;   // channels per pixel of the gathered tensor
+  const int cs0 = a.sliced ? n0 : 0;                // first channel this tile gathers (sliced launches)
+  int rowoff[AV];                 // element offset of (image, h0, w0, first gathered channel); may be negative
   uint32_t hmask[AV], wmask[AV];  // bit r / s set: tap row r / column s reads inside the image
 #pragma unroll
   for (int j = 0; j < AV; j++) {
@@ -201,7 +208,7 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
     if (a.pointwise) {  // 1x1 filter, stride 1, no padding: row m of the gathered tensor, every tap inside
       hmask[j] = rowok ? 1u : 0u;
       wmask[j] = 1u;
-      rowoff[j] = m * a.Cs;
+      rowoff[j] = m * P + cs0;
       continue;
     }
     const unsigned mm = rowok ? (unsigned)m : 0u;
@@ -222,7 +229,7 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
     }
     hmask[j] = rowok ? hm : 0u;
     wmask[j] = wm;
-    rowoff[j] = ((b * a.Hs + hh) * a.Ws + ww) * a.Cs;
+    rowoff[j] = ((b * a.Hs + hh) * a.Ws + ww) * P + cs0;
   }
   uint32_t woff[BV];  // byte offset of this thread's filter row (+ its 16-byte column), ~0 if masked
 #pragma unroll
@@ -249,7 +256,7 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
   // zeros), so that the number of loads in flight is the same at every step, and is straight-line code.
   auto gload = [&](uint32_t stage_b, int kt) {
     const uint32_t kokb = kr < a.kh ? 1u : 0u;
-    const int koff = tapdir * (kr * a.Ws + ks) * a.Cs + kc;
+    const int koff = tapdir * (kr * a.Ws + ks) * P + kc;
     const uint32_t krs = (uint32_t)kr & 31u, kss = (uint32_t)ks & 31u;
 #pragma unroll
     for (int j = 0; j < AV; j++) {
@@ -543,7 +550,7 @@ static int launch_igemm_w(IgemmArgs a, hipStream_t s) {
   a.pointwise = (a.kh == 1 && a.kw == 1 && a.stride == 1 && a.pad == 0 && a.pad_w == 0 && a.Hs == a.Hd &&
                  a.Ws == a.Wd) ? 1 : 0;
   a.group_m = 1;
-  const int tile = (NWRAP == 1 && !REMAP && EPI == 0) ? igemm_tile(a.M, a.N, a.K) : TILE_SQUARE;
+  const int tile = (NWRAP == 1 && !REMAP && EPI == 0 && !a.sliced) ? igemm_tile(a.M, a.N, a.K) : TILE_SQUARE;
   if (tile == TILE_TALL) {
     a.ntiles = (int)cdiv(a.N, 128);
     const int mt = (int)cdiv(a.M, 256);
@@ -558,11 +565,19 @@ static int launch_igemm_w(IgemmArgs a, hipStream_t s) {
                        dim3((unsigned)((int64_t)mt * a.ntiles)), dim3(256), 0, s, a);
     return mt;
   }
-  if (a.N > 64 && g_tune_tile != 1) {
+  if (a.N > 64 && g_tune_tile != 1 && !a.sliced) {
     a.ntiles = (int)cdiv(a.N, 128);
     const int mt = (int)cdiv(a.M, 128);
     hipLaunchKernelGGL((igemm_kernel<MODE, 128, 128, 2, 2, false, STATS, NWRAP, REMAP, EPI>),
                        dim3((unsigned)((int64_t)mt * a.ntiles)), dim3(256), 0, s, a);
+    return mt;
+  }
+  if (a.sliced) {   // grouped convolution: one column tile per slice of Cs = 32 or 64 channels
+    a.ntiles = a.N / a.Cs;
+    const int mt = (int)cdiv(a.M, 256);
+    const dim3 grid((unsigned)((int64_t)mt * a.ntiles));
+    if (a.Cs == 64) hipLaunchKernelGGL((igemm_kernel<MODE, 256, 64, 4, 1, false, STATS, NWRAP, REMAP, EPI>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((igemm_kernel<MODE, 256, 32, 4, 1, false, STATS, NWRAP, REMAP, EPI>), grid, dim3(256), 0, s, a);
     return mt;
   }
   a.ntiles = (int)cdiv(a.N, 64);
@@ -718,6 +733,123 @@ void conv_dgrad_mfma(const bf16_t* dy, const bf16_t* w, bf16_t* wt, bf16_t* dx, 
     }
 }
 
+// ---- grouped convolutions (Cin = Cout = C, groups of cg = C / groups channels) as sliced launches ----------------
+// The channels are cut into slices of SW = 32 or 64 (whole groups).  Column tile s of a launch computes the SW output
+// channels of slice s from the SW input channels of the same slice, read in place from the row-major tensor (pitch C),
+// with a filter whose rows hold kh * kw * SW elements, zero outside the row's own group: for cg = SW the contraction
+// runs over the group's channels only, for smaller groups it spends SW / cg times the grouped arithmetic on zeros.
+int grouped_mfma_slice(int C, int groups) {
+  if (groups < 1 || C % groups) return 0;
+  const int cg = C / groups;
+  const int sw = cg > 32 ? 64 : 32;
+  return (C % sw == 0 && sw % cg == 0) ? sw : 0;
+}
+
+// w [C][taps][cg] -> wd [C][th * tw][SW]: row o, tap (jh, jw), column i holds w[o][r][t][i - its group's first channel
+// in the slice] if input channel i of o's slice belongs to o's group, else 0; r = r0 + rstep * jh, t = s0 + rstep * jw.
+// TRANSPOSED: wd [C][th * tw][SW] indexed [input channel c][tap][output channel of c's slice] (data gradients).
+template <bool TRANSPOSED>
+__global__ void __launch_bounds__(256) expand_sliced_weights_k(const bf16_t* __restrict__ w, bf16_t* __restrict__ wd, int C,
+                                                               int kh, int kw, int cg, int SW, int th, int tw, int r0, int s0,
+                                                               int rstep) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (int64_t)C * th * tw * SW) return;
+  const int col = (int)(idx % SW);
+  const int t = (int)((idx / SW) % (th * tw));
+  const int row = (int)(idx / ((int64_t)SW * th * tw));
+  const int slice0 = row / SW * SW;
+  const int o = TRANSPOSED ? slice0 + col : row;      // output channel
+  const int ci = TRANSPOSED ? row : slice0 + col;     // input channel
+  const int r = r0 + rstep * (t / tw), q = s0 + rstep * (t % tw);
+  const bool ok = o / cg == ci / cg && r >= 0 && r < kh && q >= 0 && q < kw;
+  wd[idx] = ok ? w[(((int64_t)o * kh + r) * kw + q) * cg + ci % cg] : (bf16_t)0;
+}
+
+static void fill_sliced(IgemmArgs& a, int C, int SW) {
+  a.N = C; a.Cs = SW; a.src_pitch = C; a.sliced = 1;
+  a.bias = nullptr; a.addend = nullptr; a.addend_gate = nullptr; a.relu_out = nullptr;
+  a.omul = 0; a.ooff_h = a.ooff_w = 0;
+  a.accumulate = 0; a.ntiles = 1;
+}
+
+int conv_grouped_fprop_mfma(const bf16_t* x, const bf16_t* w, bf16_t* wd, bf16_t* y, const ConvGeom& g, int groups,
+                            float* stat_partials, hipStream_t s) {
+  const int C = g.Cin, cg = C / groups, SW = grouped_mfma_slice(C, groups), taps = g.kh * g.kw;
+  const int64_t nw = (int64_t)C * taps * SW;
+  hipLaunchKernelGGL(expand_sliced_weights_k<false>, dim3((unsigned)cdiv(nw, 256)), dim3(256), 0, s, w, wd, C, g.kh, g.kw, cg, SW,
+                     g.kh, g.kw, 0, 0, 1);
+  IgemmArgs a;
+  fill_sliced(a, C, SW);
+  a.stat_partials = stat_partials;
+  a.src = x; a.wt = wd; a.dst = y;
+  a.M = g.M(); a.K = taps * SW;
+  a.Hs = g.H; a.Ws = g.W; a.Hd = g.Ho; a.Wd = g.Wo;
+  a.kh = g.kh; a.kw = g.kw; a.stride = g.stride; a.pad = g.pad; a.pad_w = g.pad;
+  a.Ho = g.Ho; a.Wo = g.Wo;
+  a.src_bytes = (uint32_t)(g.B * g.H * g.W * (int64_t)C * 2);
+  a.wt_bytes = (uint32_t)(nw * 2);
+  return stat_partials ? launch_igemm_w<0, true, 1, false, 0>(a, s) : launch_igemm_w<0, false, 1, false, 0>(a, s);
+}
+
+void conv_grouped_dgrad_mfma(const bf16_t* dy, const bf16_t* w, bf16_t* wd, bf16_t* dx, const ConvGeom& g, int groups,
+                             bool accumulate, hipStream_t s) {
+  const int C = g.Cin, cg = C / groups, SW = grouped_mfma_slice(C, groups);
+  IgemmArgs a;
+  fill_sliced(a, C, SW);
+  a.stat_partials = nullptr;
+  a.src = dy; a.dst = dx;
+  a.Hs = g.Ho; a.Ws = g.Wo;
+  a.src_bytes = (uint32_t)(g.M() * (int64_t)C * 2);
+  a.Ho = g.H; a.Wo = g.W;
+  if (g.stride == 1) {
+    const int64_t nw = (int64_t)C * g.kh * g.kw * SW;
+    hipLaunchKernelGGL(expand_sliced_weights_k<true>, dim3((unsigned)cdiv(nw, 256)), dim3(256), 0, s, w, wd, C, g.kh, g.kw, cg,
+                       SW, g.kh, g.kw, 0, 0, 1);
+    a.wt = wd;
+    a.M = g.B * g.H * g.W; a.K = g.kh * g.kw * SW;
+    a.Hd = g.H; a.Wd = g.W;
+    a.kh = g.kh; a.kw = g.kw; a.stride = 1; a.pad = g.pad; a.pad_w = g.pad;
+    a.accumulate = accumulate ? 1 : 0;
+    a.wt_bytes = (uint32_t)(nw * 2);
+    launch_igemm_w<1, false, 1, false, 0>(a, s);
+    return;
+  }
+  // stride 2: one stride-1 problem per parity class of the input pixel, as in conv_dgrad_mfma
+  bool covered_all = true;
+  for (int ph = 0; ph < 2; ph++) {
+    const int tmax = (ph + g.pad) >> 1, lo = ph + g.pad - g.kh + 1;
+    if (tmax < (lo <= 0 ? -((-lo) >> 1) : (lo + 1) >> 1)) covered_all = false;
+  }
+  if (!accumulate && !covered_all) {
+    const int64_t n16 = g.B * g.H * g.W * (int64_t)C / 8;
+    hipLaunchKernelGGL(fill_zero16_k, dim3((unsigned)cdiv(n16, 256)), dim3(256), 0, s, reinterpret_cast<uint4*>(dx), n16);
+    accumulate = true;
+  }
+  int64_t woff = 0;
+  for (int ph = 0; ph < 2; ph++)
+    for (int pw = 0; pw < 2; pw++) {
+      const int loh = ph + g.pad - g.kh + 1, low = pw + g.pad - g.kw + 1;
+      const int tminh = loh <= 0 ? -((-loh) >> 1) : (loh + 1) >> 1, tmaxh = (ph + g.pad) >> 1;
+      const int tminw = low <= 0 ? -((-low) >> 1) : (low + 1) >> 1, tmaxw = (pw + g.pad) >> 1;
+      const int th = tmaxh - tminh + 1, tw = tmaxw - tminw + 1;
+      const int hd = (g.H - ph + 1) / 2, wdd = (g.W - pw + 1) / 2;
+      if (th <= 0 || tw <= 0 || hd <= 0 || wdd <= 0) continue;
+      bf16_t* wc = wd + woff;
+      const int64_t wn = (int64_t)C * th * tw * SW;
+      hipLaunchKernelGGL(expand_sliced_weights_k<true>, dim3((unsigned)cdiv(wn, 256)), dim3(256), 0, s, w, wc, C, g.kh, g.kw, cg,
+                         SW, th, tw, ph + g.pad - 2 * tminh, pw + g.pad - 2 * tminw, -2);
+      woff += (wn + 7) / 8 * 8;
+      a.wt = wc;
+      a.M = g.B * hd * wdd; a.K = th * tw * SW;
+      a.Hd = hd; a.Wd = wdd;
+      a.kh = th; a.kw = tw; a.stride = 1; a.pad = -tminh; a.pad_w = -tminw;
+      a.omul = 2; a.ooff_h = ph; a.ooff_w = pw;
+      a.accumulate = accumulate ? 1 : 0;
+      a.wt_bytes = (uint32_t)(wn * 2);
+      launch_igemm_w<0, false, 1, true, 0>(a, s);
+    }
+}
+
 // ---- wgrad ------------------------------------------------------------------------------------------
 // dw[n][k] = sum_m dy[m][n] * im2col(x)[m][k].  The contraction runs over pixels, which is the slow
 // axis of both operands in memory.  Tiles are staged in LDS as they lie in memory ([pixel][channel],
@@ -736,6 +868,10 @@ struct WgradArgs {
   int H, W, Cin, Ho, Wo, kh, kw, stride, pad;
   int ktiles, tiles;  // tiles along K; tiles of dw in all
   uint32_t x_bytes, dy_bytes;
+  // Grouped convolutions (sliced launches): `slices` independent problems, slice s taking channels [s * N, (s + 1) * N) of
+  // dy and [s * Cin, (s + 1) * Cin) of x, both row-major with `pitch` channels per pixel (N = Cin = the slice width);
+  // out is [splits][slices][N][K].  An ordinary convolution: slices = 1, x_pitch = Cin, dy_pitch = N.
+  int slices = 1, tiles_per_slice = 0, x_pitch = 0, dy_pitch = 0;
 };
 
 constexpr int WG_MS = 32;  // pixels per main-loop step
@@ -757,8 +893,10 @@ __global__ void __launch_bounds__(256) wgrad_kernel(WgradArgs a) {
   // read the same rows of dy, and the same rows of x up to the filter's reach) run side by side on
   // one XCD and share those rows in its L2 instead of each fetching them from memory.
   const unsigned wg = xcd_remap(blockIdx.x, gridDim.x);
-  const unsigned split = wg / (unsigned)a.tiles, tile = wg - split * (unsigned)a.tiles;
+  const unsigned split = wg / (unsigned)a.tiles, tile_all = wg - split * (unsigned)a.tiles;
+  const unsigned sl = tile_all / (unsigned)a.tiles_per_slice, tile = tile_all - sl * (unsigned)a.tiles_per_slice;
   const int n0 = (int)(tile / (unsigned)a.ktiles) * BN, k0 = (int)(tile % (unsigned)a.ktiles) * BKK;
+  const int dyc0 = (int)sl * a.N, xc0 = (int)sl * a.Cin;   // first channel of this slice in dy and in x
   // pixel and element indices fit 32 bits: every operand is smaller than 2 GiB (conv_mfma_supported)
   const int M = (int)a.M;
   const int mbeg = (int)split * (int)a.m_per_split;
@@ -774,9 +912,9 @@ __global__ void __launch_bounds__(256) wgrad_kernel(WgradArgs a) {
 #pragma unroll
   for (int j = 0; j < DV; j++) {
     dm[j] = mbeg + drow + DROWS * j;
-    doff[j] = ((uint32_t)dm[j] * (uint32_t)a.N + (uint32_t)(n0 + dnv * 8)) * 2u;
+    doff[j] = ((uint32_t)dm[j] * (uint32_t)a.dy_pitch + (uint32_t)(dyc0 + n0 + dnv * 8)) * 2u;
   }
-  const uint32_t dstep = (uint32_t)WG_MS * (uint32_t)a.N * 2u;
+  const uint32_t dstep = (uint32_t)WG_MS * (uint32_t)a.dy_pitch * 2u;
   // x loader: fixed (tap, channel) vector, XV rows, pixel coordinates advanced incrementally
   const int xkv = tid % KVR, xrow = tid / KVR;
   const int k = k0 + xkv * 8;
@@ -811,7 +949,7 @@ __global__ void __launch_bounds__(256) wgrad_kernel(WgradArgs a) {
     for (int j = 0; j < XV; j++) {
       const int hi = ph[j] * a.stride - a.pad + kr, wi = pw[j] * a.stride - a.pad + ks;
       const bool ok = kok && xm[j] < mend && (unsigned)hi < (unsigned)a.H && (unsigned)wi < (unsigned)a.W;
-      rx[j] = buf_load16(rx_src, ok ? (uint32_t)(((pb[j] * a.H + hi) * a.W + wi) * a.Cin + kc) * 2u : 0xffffffffu);
+      rx[j] = buf_load16(rx_src, ok ? (uint32_t)(((pb[j] * a.H + hi) * a.W + wi) * a.x_pitch + xc0 + kc) * 2u : 0xffffffffu);
       xm[j] += WG_MS;
       pw[j] += adv_w;
       const int cw = pw[j] >= a.Wo ? 1 : 0;
@@ -911,7 +1049,7 @@ __global__ void __launch_bounds__(256) wgrad_kernel(WgradArgs a) {
     read_frags(df[0], xf[0], 0);
   }
 
-  float* out = a.out + (int64_t)split * a.N * a.K;   // N*K*4 bytes < 2^33: 32-bit element offsets inside
+  float* out = a.out + ((int64_t)split * a.slices + sl) * a.N * a.K;   // N*K*4 bytes < 2^33: 32-bit element offsets inside
 #pragma unroll
   for (int i = 0; i < TN; i++)
 #pragma unroll
@@ -941,20 +1079,26 @@ __global__ void __launch_bounds__(256) wgrad_reduce_kernel(const float* __restri
   if (lane == 0 && i < n) out[i] = (sm[0][ol] + sm[1][ol]) + (sm[2][ol] + sm[3][ol]);
 }
 
-void conv_wgrad_mfma(const bf16_t* x, const bf16_t* dy, float* dw, const ConvGeom& g, float* partials,
-                     size_t partials_bytes, hipStream_t s) {
+// slices > 1: a grouped convolution cut into `slices` slices of g.Cin = g.Cout = SW channels; x and dy are the whole
+// row-major tensors with `pitch` channels per pixel and dw receives the dense per-slice gradients [slices][SW][K].
+static void wgrad_launch(const bf16_t* x, const bf16_t* dy, float* dw, const ConvGeom& g, int slices, int pitch, float* partials,
+                         size_t partials_bytes, hipStream_t s) {
   WgradArgs a;
   a.x = x; a.dy = dy;
   a.M = g.M(); a.N = g.Cout; a.K = g.K();
   a.H = g.H; a.W = g.W; a.Cin = g.Cin; a.Ho = g.Ho; a.Wo = g.Wo;
   a.kh = g.kh; a.kw = g.kw; a.stride = g.stride; a.pad = g.pad;
-  a.x_bytes = (uint32_t)(g.B * g.H * g.W * (int64_t)g.Cin * 2);
-  a.dy_bytes = (uint32_t)(g.M() * (int64_t)g.Cout * 2);
+  a.slices = slices;
+  a.x_pitch = slices > 1 ? pitch : g.Cin;
+  a.dy_pitch = slices > 1 ? pitch : g.Cout;
+  a.x_bytes = (uint32_t)(g.B * g.H * g.W * (int64_t)a.x_pitch * 2);
+  a.dy_bytes = (uint32_t)(g.M() * (int64_t)a.dy_pitch * 2);
   const int bn = a.N > 64 ? 128 : 64, bk = a.K > 64 ? 128 : 64;
   const int ntiles = (int)cdiv(a.N, bn);
   a.ktiles = (int)cdiv(a.K, bk);
-  const int64_t tiles = (int64_t)ntiles * a.ktiles;
-  const int64_t nk = (int64_t)a.N * a.K;
+  a.tiles_per_slice = ntiles * a.ktiles;
+  const int64_t tiles = (int64_t)a.tiles_per_slice * slices;
+  const int64_t nk = (int64_t)a.N * a.K * slices;
   // Workgroups to aim for (measured on the layer shapes of ResNet-50 at batch 256).  Every split writes
   // an fp32 copy of dw, so 1x1 filters with small N*K/(N+K) (few flops per byte of dy and x: the launch
   // is bound by memory traffic whatever the split) run one long workgroup per compute unit; the other
@@ -980,6 +1124,33 @@ void conv_wgrad_mfma(const bf16_t* x, const bf16_t* dy, float* dw, const ConvGeo
   if (splits > 1)
     hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)cdiv(nk, 64)), dim3(256), 0, s, partials, dw, nk,
                        (int)splits);
+}
+
+void conv_wgrad_mfma(const bf16_t* x, const bf16_t* dy, float* dw, const ConvGeom& g, float* partials,
+                     size_t partials_bytes, hipStream_t s) {
+  wgrad_launch(x, dy, dw, g, 1, 0, partials, partials_bytes, s);
+}
+
+// dw [C][taps][cg] fp32 of a grouped convolution: dense per-slice gradients dwd [C / SW][SW][taps][SW] (scratch) by the
+// sliced launch, then the diagonal blocks.
+__global__ void __launch_bounds__(256) extract_sliced_dw_k(const float* __restrict__ dwd, float* __restrict__ dw, int C,
+                                                           int taps, int cg, int SW) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (int64_t)C * taps * cg) return;
+  const int j = (int)(idx % cg);
+  const int t = (int)((idx / cg) % taps);
+  const int o = (int)(idx / ((int64_t)cg * taps));
+  dw[idx] = dwd[((int64_t)o * taps + t) * SW + (o % SW) / cg * cg + j];
+}
+
+void conv_grouped_wgrad_mfma(const bf16_t* x, const bf16_t* dy, float* dwd, float* dw, const ConvGeom& g, int groups,
+                             float* partials, size_t partials_bytes, hipStream_t s) {
+  const int C = g.Cin, cg = C / groups, SW = grouped_mfma_slice(C, groups), taps = g.kh * g.kw;
+  ConvGeom gs = g;
+  gs.Cin = gs.Cout = SW;
+  wgrad_launch(x, dy, dwd, gs, C / SW, C, partials, partials_bytes, s);
+  const int64_t n = (int64_t)C * taps * cg;
+  hipLaunchKernelGGL(extract_sliced_dw_k, dim3((unsigned)cdiv(n, 256)), dim3(256), 0, s, dwd, dw, C, taps, cg, SW);
 }
 
 // eight elements per thread (two 16-byte loads, one 16-byte store); the ragged tail element by element

@@ -121,6 +121,17 @@ void conv_dgrad_mfma(const bf16_t* dy, const bf16_t* w, bf16_t* wt, bf16_t* dx, 
 // dw[Cout][K] = dy[M][Cout]^T * im2col(x)[M][K], split over M with fp32 partials reduced in fixed order
 void conv_wgrad_mfma(const bf16_t* x, const bf16_t* dy, float* dw, const ConvGeom& g, float* partials,
                      size_t partials_bytes, hipStream_t s);
+// Grouped convolutions (Cin = Cout = C, groups of C / groups channels) on the same kernels, reading and writing the
+// row-major tensors in place: slices of grouped_mfma_slice(C, groups) = 32 or 64 channels (0: this shape is not taken;
+// the slice must hold whole groups and divide C).  w is the grouped filter [C][kh][kw][C / groups]; wd is scratch for
+// its per-slice form, at least C * kh * kw * 64 + 64 elements (fp32 elements for the weight gradient's dwd).
+int grouped_mfma_slice(int C, int groups);
+int conv_grouped_fprop_mfma(const bf16_t* x, const bf16_t* w, bf16_t* wd, bf16_t* y, const ConvGeom& g, int groups,
+                            float* stat_partials, hipStream_t s);   // returns the number of statistics chunks
+void conv_grouped_dgrad_mfma(const bf16_t* dy, const bf16_t* w, bf16_t* wd, bf16_t* dx, const ConvGeom& g, int groups,
+                             bool accumulate, hipStream_t s);
+void conv_grouped_wgrad_mfma(const bf16_t* x, const bf16_t* dy, float* dwd, float* dw, const ConvGeom& g, int groups,
+                             float* partials, size_t partials_bytes, hipStream_t s);
 // dense layer on the same kernel: y[B][C] (fp32) = x[B][F] * w[C][F]^T + bias; needs F % 8 == 0
 void linear_fwd_mfma(const bf16_t* x, const bf16_t* w, const bf16_t* bias, float* y, int64_t B, int F, int C,
                      hipStream_t s);

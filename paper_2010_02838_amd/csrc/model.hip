@@ -345,6 +345,16 @@ bool use_mfma(const cd_model* m, const ConvGeom& g) {
   return conv_mfma_supported(packed_geom(g));
 }
 
+// Whether a grouped convolution runs as sliced launches on the row-major tensors (conv_grouped_*_mfma): bf16, slices of
+// whole groups, 32-bit offsets; otherwise as dense convolutions on slice-major copies (conv_grouped.hip).
+bool grouped_sliced(const cd_model* m, const Op& o, int64_t batch) {
+  if (m->dtype != CD_BF16 || force_simple() || o.kind != OP_CONV || o.groups <= 1) return false;
+  const TensorDesc& tx = m->tensors[o.x];
+  const TensorDesc& ty = m->tensors[o.y];
+  if (tx.c != ty.c || grouped_mfma_slice(tx.c, o.groups) == 0) return false;
+  return batch * tx.per_sample() * 2 < (1LL << 31) && batch * ty.per_sample() * 2 < (1LL << 31);
+}
+
 // How the backward pass of BatchNorm op i hands the gradient of its residual input on (that gradient
 // is the op's own dy, gated by its ReLU).  Where the branch's next reader can take "dy and the ReLU
 // bit mask" in place of a tensor, the gradient is never written out:
@@ -439,15 +449,18 @@ Plan make_plan(const cd_model* m, int64_t B, bool save) {
       const Op& o = m->ops[i];
       if (o.kind != OP_CONV || o.groups <= 1) continue;
       const size_t in_b = (size_t)B * m->tensors[o.x].per_sample() * 2, out_b = (size_t)B * m->tensors[o.y].per_sample() * 2;
+      const size_t wd = (size_t)m->tensors[o.x].c * o.k * o.k * grouped_slice_width(m->tensors[o.x].c) + 64;
+      if (wd > wdmax) wdmax = wd;
+      if (grouped_sliced(m, o, B)) continue;   // reads and writes the row-major tensors in place: no copies
       if (in_b > tmax) tmax = in_b;
       if (out_b > tmax) tmax = out_b;
-      const size_t wd = (size_t)m->tensors[o.x].c * o.k * o.k * grouped_slice_width(m->tensors[o.x].c);
-      if (wd > wdmax) wdmax = wd;
       if (save) p.gx[i] = alloc(in_b);
     }
     if (tmax) {
       p.gtmp_bytes = align_up(tmax, 256);
       p.gtmp = alloc(2 * p.gtmp_bytes);
+    }
+    if (wdmax) {
       p.gw = alloc(wdmax * 2);
       if (save) p.gdw = alloc(wdmax * 4);
     }
@@ -712,7 +725,7 @@ static int check_supported(const char* fn, const cd_model* m, const Plan& plan, 
     const Op& o = m->ops[i];
     if (o.kind == OP_CONV && o.groups > 1) {
       const ConvGeom g = conv_geom(m, o, batch);
-      if (dt != CD_BF16 || force_simple() || o.pb >= 0 || o.relu || g.Cin != g.Cout || (backward && (!plan.gx[i] || o.x == 0)))
+      if (dt != CD_BF16 || force_simple() || o.pb >= 0 || o.relu || g.Cin != g.Cout || (backward && ((!plan.gx[i] && !grouped_sliced(m, o, batch)) || o.x == 0)))
         return set_error(CD_ERR_UNSUPPORTED, "%s: this grouped convolution has no kernel (bf16, no bias, Cin = Cout, not on the input batch)", fn);
     }
     if (backward && o.kind == OP_ATTN) {
@@ -761,6 +774,20 @@ extern "C" int codistill_forward(const cd_model* m, const void* params, const vo
     switch (o.kind) {
       case OP_CONV: {
         ConvGeom g = conv_geom(m, o, batch);
+        if (grouped_sliced(m, o, batch)) {
+          // grouped, in place on the row-major tensors: one launch whose column tiles are slices of whole groups; the
+          // BatchNorm that follows gets its column sums from the epilogue like behind a dense convolution
+          const bool fuse = bn_mode == CD_BN_BATCH_STATS && oi + 1 < m->ops.size() && m->ops[oi + 1].kind == OP_BN &&
+                            m->ops[oi + 1].x == o.y &&
+                            (size_t)(g.M() / 128 + 1 + 32) * stat_pitch(g.Cout) * sizeof(float) <= c.plan.partials_bytes;
+          ProfScope pr(CD_K_CONV_FPROP_NARROW, c.s, 2.0 * g.M() * g.Cout * (double)g.kh * g.kw * grouped_mfma_slice(g.Cin, o.groups),
+                       conv_bytes(m, g));
+          stat_chunks = conv_grouped_fprop_mfma(static_cast<const bf16_t*>(in), static_cast<const bf16_t*>(c.P(o.pw)),
+                                                reinterpret_cast<bf16_t*>(c.ws + c.plan.gw), static_cast<bf16_t*>(out), g, o.groups,
+                                                fuse ? c.partials() : nullptr, c.s);
+          stat_tensor = fuse ? o.y : -1;
+          break;
+        }
         if (o.groups > 1) {
           // grouped: slice-major copy of the input, dense per-slice filters, one dense convolution per slice of
           // channels, copy back (conv_grouped.hip); the BatchNorm behind it takes its statistics from the tensor
@@ -1115,6 +1142,21 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
       }
       case OP_CONV: {
         ConvGeom g = conv_geom(m, o, batch);
+        if (grouped_sliced(m, o, batch)) {
+          const double fl = 2.0 * g.M() * g.Cout * (double)g.kh * g.kw * grouped_mfma_slice(g.Cin, o.groups);
+          {
+            ProfScope pr(CD_K_CONV_WGRAD, c.s, fl, conv_bytes(m, g));
+            conv_grouped_wgrad_mfma(static_cast<const bf16_t*>(in), static_cast<const bf16_t*>(dy),
+                                    reinterpret_cast<float*>(c.ws + c.plan.gdw), G(o.pw), g, o.groups, c.partials(),
+                                    c.plan.partials_bytes, c.s);
+          }
+          {
+            ProfScope pr(CD_K_CONV_DGRAD, c.s, fl, conv_bytes(m, g));
+            conv_grouped_dgrad_mfma(static_cast<const bf16_t*>(dy), static_cast<const bf16_t*>(c.P(o.pw)),
+                                    reinterpret_cast<bf16_t*>(c.ws + c.plan.gw), static_cast<bf16_t*>(dx), g, o.groups, acc, c.s);
+          }
+          break;
+        }
         if (o.groups > 1) {
           const int C = g.Cin, sw = grouped_slice_width(C), ns = C / sw, taps = g.kh * g.kw;
           const int64_t Min = batch * g.H * g.W, Mout = g.M();

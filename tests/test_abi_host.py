@@ -195,8 +195,8 @@ def test_unsupported_ops_are_reported_before_any_launch(monkeypatch):
     m = B.Model(B.arch_preset(B.CD_ARCH_RESNEXT, widths=[128, 256], out_widths=[64, 64], groups=8, blocks=[1, 1],
                               stem_width=32, in_h=32, in_w=32, classes=10), B.CD_BF16)
     fake = ctypes.c_void_p(0x1000)
-    need = m.workspace_bytes(2, True)
     monkeypatch.setenv("CODISTILL_FORCE_SIMPLE", "1")
+    need = m.workspace_bytes(2, True)
     assert B.lib.codistill_forward(m._h, fake, fake, 2, 1, 0, None, fake, need, fake, None) == B.CD_ERR_UNSUPPORTED
     assert b"grouped" in B.lib.codistill_last_error()
     assert B.lib.codistill_backward(m._h, fake, fake, 2, fake, need, fake, fake, None) == B.CD_ERR_UNSUPPORTED

@@ -89,6 +89,14 @@ SMALL = {
     "resnext_slices": (dict(kind=6, widths=[256, 256], out_widths=[64, 64], groups=8, blocks=[1, 1], stem_width=32),
                        lambda: nets.resnext(classes=10, widths=(256, 256), outs=(64, 64), groups=8, blocks=(1, 1), stem=32),
                        3, 40, 10),
+    # groups of 64 channels (slices of 64, the contraction runs over the group's channels only) and of 16 (two groups
+    # per 32-channel slice), stride 1 and stride 2
+    "resnext_cg64": (dict(kind=6, widths=[128, 128], out_widths=[32, 32], groups=2, blocks=[1, 1], stem_width=16),
+                     lambda: nets.resnext(classes=10, widths=(128, 128), outs=(32, 32), groups=2, blocks=(1, 1), stem=16),
+                     3, 40, 10),
+    "resnext_cg16": (dict(kind=6, widths=[64, 64], out_widths=[32, 32], groups=4, blocks=[1, 1], stem_width=16),
+                     lambda: nets.resnext(classes=10, widths=(64, 64), outs=(32, 32), groups=4, blocks=(1, 1), stem=16),
+                     3, 40, 10),
     # the multi-view network (Section 5): a frozen first block, the rest sees one part of its output channels: 4 of 16
     # (plain kernels for the convolutions that read them) ...
     "wide_split": (dict(kind=7, widths=[16, 24, 32], blocks=[2, 1, 2], stem_width=8, n_splits=4, split=1),
