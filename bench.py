@@ -200,7 +200,7 @@ def transformer(args, B, synth, StepRunner, pack_flat, torch, dev):
     """One codistillation step of the base encoder-decoder Transformer (two models: 6 + 6 layers, d_model 512,
     8 heads, d_ff 2048, shared vocabulary 32768, bf16): label smoothing 0.1, alpha 1, KL distillation term, Adam.
     Default batch: sentence pairs with source and target lengths uniform in [16, 128], drawn until they hold at
-    least 8192 target tokens (about 114 pairs), padded to 128 + 128 positions with negative ids (padding is masked
+    least 8192 target tokens (109 pairs with this seed), padded to 128 + 128 positions with negative ids (padding is masked
     as a key, embeds as zero, takes no gradient; its target rows carry ignore_index); tokens/s counts the valid
     target tokens.  --sentences uniform: 64 pairs of full length 128 + 128 (8192 target tokens, no padding).
     roofline: the kernel class that takes the most time of the step."""
