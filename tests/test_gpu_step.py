@@ -200,7 +200,8 @@ def check_layers(c, got):
             continue
         fused_pool = o["kind"] == "bn" and o["fused_pool"]
         y = got["logits"].astype(np.float64) if o["y"] == logits_t else (None if fused_pool else act(o["y"]))
-        dy = got["dz"].astype(np.float64) if o["y"] == logits_t else (None if fused_pool else grad_in(o["y"]))
+        # nothing flows back through the frozen front end: its gradient slots are never written, and never read here
+        dy = got["dz"].astype(np.float64) if o["y"] == logits_t else (None if fused_pool or frozen else grad_in(o["y"]))
         w = P[names[o["param_w"]]] if o["param_w"] >= 0 else None
         b = P[names[o["param_b"]]] if o["param_b"] >= 0 else None
         tag = "op%d:%s" % (i, o["kind"])
@@ -208,10 +209,11 @@ def check_layers(c, got):
             yr = L.conv2d_forward(x, w, b, o["stride"], o["pad"])
             if o["relu"]:
                 yr = L.relu_forward(yr)
-                dy = L.relu_backward(y, dy)
             note("act", rel(y, yr), tag, tol_t)
             if frozen:
                 continue
+            if o["relu"]:
+                dy = L.relu_backward(y, dy)
             dx, dw, db = L.conv2d_backward(x, w, dy, o["stride"], o["pad"], b is not None, o["x"] != 0)
             pgrad(o, dw, tag, TOL_F32_TENSOR)
             if b is not None:
@@ -249,11 +251,12 @@ def check_layers(c, got):
                 yr = yr + act(o["res"])
             if o["relu"]:
                 yr = L.relu_forward(yr)
-                if fused_pool:   # neither this op's output nor its gradient is written: both come from the pool's side
+                if fused_pool and not frozen:   # neither this op's output nor its gradient is written: both come from the pool's side
                     q = ops[i + 1]
                     _, arg = L.maxpool_forward(yr, q["k"], q["stride"], q["pad"])
                     dy = L.maxpool_backward(yr.shape, arg, grad(q["y"]), q["k"], q["stride"], q["pad"])
-                dy = L.relu_backward(yr if fused_pool else y, dy)
+                if not frozen:
+                    dy = L.relu_backward(yr if fused_pool else y, dy)
             if fused_pool:
                 unwritten[o["y"]] = yr
             else:
