@@ -200,9 +200,12 @@ def transformer(args, B, synth, StepRunner, pack_flat, torch, dev):
     """One codistillation step of the base encoder-decoder Transformer (two models: 6 + 6 layers, d_model 512,
     8 heads, d_ff 2048, shared vocabulary 32768, bf16): label smoothing 0.1, alpha 1, KL distillation term, Adam.
     Default batch: sentence pairs with source and target lengths uniform in [16, 128], drawn until they hold at
-    least 8192 target tokens (109 pairs with this seed), padded to 128 + 128 positions with negative ids (padding is masked
-    as a key, embeds as zero, takes no gradient; its target rows carry ignore_index); tokens/s counts the valid
-    target tokens.  --sentences uniform: 64 pairs of full length 128 + 128 (8192 target tokens, no padding).
+    least 8192 target tokens (109 pairs with this seed), handed to the library in packed form: the tokens of all
+    sentences one after the other, each stream's rows rounded up to a multiple of 128 (the rows behind the last sentence
+    hold negative ids and ignored labels).  --sentences padded: the same pairs, every sentence padded to 128 + 128 positions
+    with negative ids (padding is masked as a key, embeds as zero, takes no gradient; its target rows carry
+    ignore_index).  tokens/s counts the valid target tokens in both.  --sentences uniform: 64 pairs of full length
+    128 + 128 (8192 target tokens, no padding).
     roofline: the kernel class that takes the most time of the step."""
     Ts, Tt, vocab = 128, 128, 32768
     arch = B.arch_preset(B.CD_ARCH_TRANSFORMER)
@@ -218,9 +221,16 @@ def transformer(args, B, synth, StepRunner, pack_flat, torch, dev):
     else:
         xh, yh, sl, tl = synth.sentence_pairs(budget, 16, 128, vocab, seed=100)
         S, valid, src_tokens = xh.shape[0], int(tl.sum()), int(sl.sum())
+    elements, target_rows = S, S * Tt
+    if args.sentences == "ragged":   # packed: one batch element whose streams hold all sentences
+        xh, yh, _, _ = synth.pack_sentences(xh, yh, Ts, multiple=128)
+        target_rows = len(yh)
+        kw = dict(in_h=xh.shape[1] - target_rows, in_w=target_rows, max_sentences=S, max_sentence_len=max(Ts, Tt))
+        arch = B.arch_preset(B.CD_ARCH_TRANSFORMER, widths=[1024, 4096, 16], **kw) if big else B.arch_preset(B.CD_ARCH_TRANSFORMER, **kw)
+        xh, elements = xh[None], 1
     model, peer = B.Model(arch, B.CD_BF16), B.Model(arch, B.CD_BF16)
     table = model.param_table()
-    r = StepRunner(model, [peer], S, dev)
+    r = StepRunner(model, [peer], elements, dev)
     r.load(pack_flat(model, synth.he_init(table, 1)), [pack_flat(peer, synth.he_init(table, 2))])
     x = torch.from_numpy(xh).to(dev)
     y = torch.from_numpy(yh).to(dev)
@@ -259,9 +269,12 @@ def transformer(args, B, synth, StepRunner, pack_flat, torch, dev):
         "value": valid / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": "transformer_%s_codistill_step%s" % (name, "" if args.sentences == "ragged" else "_uniform_lengths"),
-                   "sentences": S, "lengths": "uniform in [16, 128], padded to 128 + 128" if args.sentences == "ragged" else "128 + 128",
-                   "valid_target_tokens": valid, "valid_source_tokens": src_tokens, "padded_target_positions": S * Tt,
+        "config": {"workload": "transformer_%s_codistill_step%s" % (name, {"ragged": "", "padded": "_padded_sentences",
+                                                                        "uniform": "_uniform_lengths"}[args.sentences]),
+                   "sentences": S, "lengths": {"ragged": "uniform in [16, 128], packed (no padding rows)",
+                                               "padded": "uniform in [16, 128], padded to 128 + 128",
+                                               "uniform": "128 + 128"}[args.sentences],
+                   "valid_target_tokens": valid, "valid_source_tokens": src_tokens, "target_rows": target_rows,
                    "d_model": arch.widths[0], "heads": arch.widths[2],
                    "d_ff": arch.widths[1], "layers": "6+6", "vocab": vocab,
                    "models": "2 x Transformer-%s (local fwd+bwd+Adam, peer fwd)" % name, "alpha": 1.0,
@@ -328,9 +341,10 @@ def main():
                          "tokens, a separate JSON line with its own metric")
     ap.add_argument("--transformer-size", default="base", choices=["base", "big"],
                     help="--workload transformer: base (64 sentences) or big (d_model 1024, 16 heads, d_ff 4096; 30 sentences)")
-    ap.add_argument("--sentences", default="ragged", choices=["ragged", "uniform"],
+    ap.add_argument("--sentences", default="ragged", choices=["ragged", "padded", "uniform"],
                     help="--workload transformer: ragged (default) = lengths uniform in [16, 128] until the batch holds 8192 "
-                         "target tokens, padded; uniform = 64 pairs of 128 + 128 tokens")
+                         "target tokens, given in packed form (no padding rows); padded = the same sentences padded to "
+                         "128 + 128; uniform = 64 pairs of 128 + 128 tokens")
     ap.add_argument("--peer", default="resnet50", choices=["resnet50", "resnet18", "resnext101"],
                     help="architecture of the stale peer of the ResNet-50 workload (Section 5 pairs different "
                          "architectures); the default line is the two-ResNet-50 step")

@@ -128,7 +128,17 @@ enum {
  * int32 [batch][in_h + in_w] token ids (batch = sentences) and it produces batch * in_w rows of logits.  Shorter
  * sentences are padded at the end of their source / target part with negative ids: padding embeds as a zero row,
  * is masked as a key in every attention and takes no gradient; give its rows of the targets ignore_index.  Every
- * part needs at least one real token. */
+ * part needs at least one real token.
+ * Packed sentences (max_sentences > 0): a batch of sentences of different lengths without the padding.  The
+ * sentences' tokens lie one after the other; in_h and in_w are the rows the source and the target stream have room
+ * for (up to 65536 each), batch is 1, and x is int32 [2][in_h + in_w]: row 0 the token ids (source stream, then
+ * target stream; the rows of a stream behind its last sentence hold negative ids), row 1 the position of every
+ * token inside its own sentence (0 starts a sentence).  Both streams hold the same sentences in the same order, every
+ * sentence has at least one token in each, at most max_sentence_len, and there are at most max_sentences of them
+ * (what exceeds either bound is left out of the attention; nothing is read or written out of bounds).  The
+ * model produces in_w rows of logits, one per target row; the rows behind the last sentence are not defined: give
+ * them ignore_index in the targets.  Everything else (parameters, losses, gradients) is as for padded sentences, and
+ * equal to it up to rounding order when the same sentences are given in both forms. */
 typedef struct {
   int32_t kind;                   /* CD_ARCH_*                                             */
   int32_t classes;                /* width of the logits                                   */
@@ -143,6 +153,8 @@ typedef struct {
                                         (widths[] are those of its grouped convolution)    */
   int32_t n_splits, split;        /* CD_ARCH_WIDE_RESNET_SPLIT: parts the front end's output channels are
                                      cut into (widths[0] % n_splits == 0), and the part this model receives */
+  int32_t max_sentences;          /* CD_ARCH_TRANSFORMER: 0 = padded sentences (above); > 0 = packed sentences (below): */
+  int32_t max_sentence_len;       /*   the most sentences a batch may hold, and the most tokens one sentence may have   */
 } cd_arch_desc;
 
 /* kind of a parameter tensor */

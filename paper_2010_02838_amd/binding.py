@@ -34,7 +34,8 @@ class ArchDesc(ctypes.Structure):
                 ("in_w", ctypes.c_int32), ("n_stages", ctypes.c_int32),
                 ("widths", ctypes.c_int32 * CD_MAX_STAGES), ("blocks", ctypes.c_int32 * CD_MAX_STAGES),
                 ("stem_width", ctypes.c_int32), ("groups", ctypes.c_int32),
-                ("out_widths", ctypes.c_int32 * CD_MAX_STAGES), ("n_splits", ctypes.c_int32), ("split", ctypes.c_int32)]
+                ("out_widths", ctypes.c_int32 * CD_MAX_STAGES), ("n_splits", ctypes.c_int32), ("split", ctypes.c_int32),
+                ("max_sentences", ctypes.c_int32), ("max_sentence_len", ctypes.c_int32)]
 
 
 class TensorInfo(ctypes.Structure):

@@ -66,6 +66,13 @@ struct AttArgs {
   // Padding (nullable): token ids [S][tok_pitch]; the keys of sentence s come from columns ktok0 .. ktok0 + Tk,
   // and only those before the first negative id are real.
   const int32_t* ktok; int64_t tok_pitch; int ktok0;
+  // Packed sentences (nullable, both or neither): tables of max_sent + 2 entries, [i] = first row of sentence i of the
+  // query / key tensor, [n] = one past the last row of the last sentence, [max_sent + 1] = n, the number of sentences.
+  // S is then max_sent, Tq and Tk the longest sentence the launch covers, and lse / dsum are [heads][lse_rows],
+  // indexed by the query's row in its tensor.
+  // The workgroups of "sentence" n (the grid has max_sent + 1 of them) clear the rows behind the last sentence in what
+  // the kernel writes, so that no tensor holds rows that were never written (k_rows: rows of the key tensor).
+  const int32_t* q_tab; const int32_t* k_tab; int max_sent; int lse_rows; int k_rows;
 };
 
 // Number of real keys of sentence s (at least 1), the same value in every thread of the workgroup.
@@ -80,6 +87,39 @@ __device__ inline int key_count(const AttArgs& a, int s) {
   return max(n, 1);
 }
 
+// Where sentence s lives: first row and number of rows of its queries and of its keys, number of real keys, and the
+// first element of its rows in lse / dsum (head h).  Padded batches: every sentence has Tq and Tk rows.  Packed
+// batches: rows and lengths come from the tables.  Returns SEG_ROWS for a sentence, SEG_TAIL for the index right
+// behind the last sentence (qrow / krow are then the first rows that belong to no sentence), SEG_NONE beyond that:
+// in the last two cases the whole workgroup leaves.  Contains barriers (key_count): every thread of the workgroup calls it.
+struct Seg { int qrow, Tq, krow, Tk, nk; int64_t lrow; };
+enum { SEG_NONE = 0, SEG_ROWS = 1, SEG_TAIL = 2 };
+__device__ inline int segment(const AttArgs& a, int s, int h, Seg& g) {
+  if (!a.q_tab) {
+    g.qrow = s * a.Tq; g.Tq = a.Tq; g.krow = s * a.Tk; g.Tk = a.Tk;
+    g.nk = key_count(a, s);
+    g.lrow = ((int64_t)s * a.heads + h) * a.Tq;
+    return SEG_ROWS;
+  }
+  const int n = min(min(a.q_tab[a.max_sent + 1], a.k_tab[a.max_sent + 1]), a.max_sent);
+  if (s > n) return SEG_NONE;
+  g.qrow = a.q_tab[s];
+  g.krow = a.k_tab[s];
+  if (s == n) return SEG_TAIL;
+  g.Tq = min(a.q_tab[s + 1] - g.qrow, a.Tq);
+  g.Tk = min(a.k_tab[s + 1] - g.krow, a.Tk);
+  g.nk = g.Tk;
+  g.lrow = (int64_t)h * a.lse_rows + g.qrow;
+  return g.Tq > 0 && g.Tk > 0 ? SEG_ROWS : SEG_NONE;
+}
+// zeros in columns h*DH .. (h+1)*DH of rows first .. rows of a bf16 tensor with row pitch ld (the whole workgroup)
+template <int DH>
+__device__ inline void clear_rows(bf16_t* __restrict__ p, int64_t ld, int first, int rows, int h) {
+  constexpr int VPR = DH / 8;
+  for (int v = threadIdx.x; v < (rows - first) * VPR; v += 256)
+    *reinterpret_cast<uint4*>(p + (int64_t)(first + v / VPR) * ld + h * DH + (v % VPR) * 8) = make_uint4(0, 0, 0, 0);
+}
+
 // blockIdx.x = (sentence * heads + head) * tiles + tile of ATT_ROWS queries
 template <int DH>
 __global__ void __launch_bounds__(256) attn_fwd_k(AttArgs a) {
@@ -88,24 +128,31 @@ __global__ void __launch_bounds__(256) attn_fwd_k(AttArgs a) {
   const int tiles = (a.Tq + ATT_ROWS - 1) / ATT_ROWS;
   const int tile = blockIdx.x % tiles, sh = blockIdx.x / tiles;
   const int h = sh % a.heads, s = sh / a.heads;
+  Seg sg;
+  const int seg = segment(a, s, h, sg);
+  if (seg != SEG_ROWS) {   // (packed batches) no such sentence; the first index behind the last one clears the unused rows
+    if (seg == SEG_TAIL && tile == 0) clear_rows<DH>(a.out, a.ldo, sg.qrow, a.lse_rows, h);
+    return;
+  }
+  if (tile * ATT_ROWS >= sg.Tq) return;   // (packed batches) the sentence ends before this tile
   const int i = tile * ATT_ROWS + (threadIdx.x >> 1), hf = threadIdx.x & 1;
-  const bool live = i < a.Tq;
+  const bool live = i < sg.Tq;
   float q[HALF], o[HALF];
 #pragma unroll
   for (int c = 0; c < HALF; c++) { q[c] = 0.f; o[c] = 0.f; }
   if (live) {
-    const bf16_t* qp = a.q + ((int64_t)s * a.Tq + i) * a.ldq + h * DH + hf * HALF;
+    const bf16_t* qp = a.q + ((int64_t)sg.qrow + i) * a.ldq + h * DH + hf * HALF;
 #pragma unroll
     for (int c = 0; c < HALF; c++) q[c] = bf16_to_f32(qp[c]) * a.scale;
   }
   float m = -INFINITY, l = 0.f;
-  const int nk = key_count(a, s);
+  const int nk = sg.nk;
   const int last = a.causal ? min(nk, tile * ATT_ROWS + ATT_ROWS) : nk;   // keys any query of the tile sees
   for (int j0 = 0; j0 < last; j0 += ATT_KC) {
     const int n = min(ATT_KC, nk - j0);
     __syncthreads();
-    stage_chunk<DH>(a.k + ((int64_t)s * a.Tk + j0) * a.ldkv + h * DH, a.ldkv, n, Ks);
-    stage_chunk<DH>(a.v + ((int64_t)s * a.Tk + j0) * a.ldkv + h * DH, a.ldkv, n, Vs);
+    stage_chunk<DH>(a.k + ((int64_t)sg.krow + j0) * a.ldkv + h * DH, a.ldkv, n, Ks);
+    stage_chunk<DH>(a.v + ((int64_t)sg.krow + j0) * a.ldkv + h * DH, a.ldkv, n, Vs);
     __syncthreads();
     for (int j = 0; j < n; j++) {
       float part = 0.f;
@@ -128,10 +175,10 @@ __global__ void __launch_bounds__(256) attn_fwd_k(AttArgs a) {
   }
   if (!live) return;
   const float inv = 1.f / l;
-  bf16_t* op = a.out + ((int64_t)s * a.Tq + i) * a.ldo + h * DH + hf * HALF;
+  bf16_t* op = a.out + ((int64_t)sg.qrow + i) * a.ldo + h * DH + hf * HALF;
 #pragma unroll
   for (int c = 0; c < HALF; c++) op[c] = f32_to_bf16(o[c] * inv);
-  if (hf == 0 && a.lse) a.lse[((int64_t)s * a.heads + h) * a.Tq + i] = m + __logf(l);
+  if (hf == 0 && a.lse) a.lse[sg.lrow + i] = m + __logf(l);
 }
 
 // dq: one pair of threads per query.  p_ij = exp(s_ij - lse_i); D_i = dO_i . O_i = sum_j p_ij dP_ij;
@@ -144,20 +191,27 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_k(AttArgs a) {
   const int tiles = (a.Tq + ATT_ROWS - 1) / ATT_ROWS;
   const int tile = blockIdx.x % tiles, sh = blockIdx.x / tiles;
   const int h = sh % a.heads, s = sh / a.heads;
+  Seg sg;
+  const int seg = segment(a, s, h, sg);
+  if (seg != SEG_ROWS) {   // (packed batches) no such sentence; the first index behind the last one clears the unused rows
+    if (seg == SEG_TAIL && tile == 0) clear_rows<DH>(a.dq, a.ldq, sg.qrow, a.lse_rows, h);
+    return;
+  }
+  if (tile * ATT_ROWS >= sg.Tq) return;   // (packed batches) the sentence ends before this tile
   const int i = tile * ATT_ROWS + (threadIdx.x >> 1), hf = threadIdx.x & 1;
-  const bool live = i < a.Tq;
+  const bool live = i < sg.Tq;
   float q[HALF], go[HALF], dq[HALF];
 #pragma unroll
   for (int c = 0; c < HALF; c++) { q[c] = 0.f; go[c] = 0.f; dq[c] = 0.f; }
   float lse = 0.f;
   if (live) {
-    const bf16_t* qp = a.q + ((int64_t)s * a.Tq + i) * a.ldq + h * DH + hf * HALF;
-    const bf16_t* gp = a.dout + ((int64_t)s * a.Tq + i) * a.ldo + h * DH + hf * HALF;
+    const bf16_t* qp = a.q + ((int64_t)sg.qrow + i) * a.ldq + h * DH + hf * HALF;
+    const bf16_t* gp = a.dout + ((int64_t)sg.qrow + i) * a.ldo + h * DH + hf * HALF;
 #pragma unroll
     for (int c = 0; c < HALF; c++) { q[c] = bf16_to_f32(qp[c]) * a.scale; go[c] = bf16_to_f32(gp[c]); }
-    lse = a.lse[((int64_t)s * a.heads + h) * a.Tq + i];
+    lse = a.lse[sg.lrow + i];
   }
-  const int nk = key_count(a, s);
+  const int nk = sg.nk;
   const int last = a.causal ? min(nk, tile * ATT_ROWS + ATT_ROWS) : nk;
   // Where the weights are nearly uniform dq is a small difference of large terms (10^4 times smaller at the base
   // model's initialisation), so relative errors of 1e-7 in the recomputed probabilities matter.  Two measures:
@@ -175,8 +229,8 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_k(AttArgs a) {
     for (int j0 = 0; j0 < last; j0 += ATT_KC) {
       const int n = min(ATT_KC, nk - j0);
       __syncthreads();
-      stage_chunk<DH>(a.k + ((int64_t)s * a.Tk + j0) * a.ldkv + h * DH, a.ldkv, n, Ks);
-      stage_chunk<DH>(a.v + ((int64_t)s * a.Tk + j0) * a.ldkv + h * DH, a.ldkv, n, Vs);
+      stage_chunk<DH>(a.k + ((int64_t)sg.krow + j0) * a.ldkv + h * DH, a.ldkv, n, Ks);
+      stage_chunk<DH>(a.v + ((int64_t)sg.krow + j0) * a.ldkv + h * DH, a.ldkv, n, Vs);
       __syncthreads();
       for (int j = 0; j < n; j++) {
         float ps = 0.f, pd = 0.f;
@@ -203,11 +257,11 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_k(AttArgs a) {
     }
   }
   if (!live) return;
-  bf16_t* dp_ = a.dq + ((int64_t)s * a.Tq + i) * a.ldq + h * DH + hf * HALF;
+  bf16_t* dp_ = a.dq + ((int64_t)sg.qrow + i) * a.ldq + h * DH + hf * HALF;
   const float fin = Z > 0.f ? a.scale / Z : 0.f;
 #pragma unroll
   for (int c = 0; c < HALF; c++) dp_[c] = f32_to_bf16(dq[c] * fin);
-  if (hf == 0) a.dsum[((int64_t)s * a.heads + h) * a.Tq + i] = D + dp0;
+  if (hf == 0) a.dsum[sg.lrow + i] = D + dp0;
 }
 
 // dk, dv: one pair of threads per key; the queries (scaled), their output gradients, log-sum-exps and
@@ -219,28 +273,35 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_k(AttArgs a) {
   const int tiles = (a.Tk + ATT_ROWS - 1) / ATT_ROWS;
   const int tile = blockIdx.x % tiles, sh = blockIdx.x / tiles;
   const int h = sh % a.heads, s = sh / a.heads;
+  Seg sg;
+  const int seg = segment(a, s, h, sg);
+  if (seg != SEG_ROWS) {   // (packed batches) no such sentence; the first index behind the last one clears the unused rows
+    if (seg == SEG_TAIL && tile == 0) { clear_rows<DH>(a.dk, a.ldkv, sg.krow, a.k_rows, h); clear_rows<DH>(a.dv, a.ldkv, sg.krow, a.k_rows, h); }
+    return;
+  }
+  if (tile * ATT_ROWS >= sg.Tk) return;   // (packed batches) the sentence ends before this tile
   const int j = tile * ATT_ROWS + (threadIdx.x >> 1), hf = threadIdx.x & 1;
-  const bool live = j < a.Tk;
+  const bool live = j < sg.Tk;
   float k[HALF], v[HALF], dk[HALF], dv[HALF];
 #pragma unroll
   for (int c = 0; c < HALF; c++) { k[c] = 0.f; v[c] = 0.f; dk[c] = 0.f; dv[c] = 0.f; }
   if (live) {
-    const bf16_t* kp = a.k + ((int64_t)s * a.Tk + j) * a.ldkv + h * DH + hf * HALF;
-    const bf16_t* vp = a.v + ((int64_t)s * a.Tk + j) * a.ldkv + h * DH + hf * HALF;
+    const bf16_t* kp = a.k + ((int64_t)sg.krow + j) * a.ldkv + h * DH + hf * HALF;
+    const bf16_t* vp = a.v + ((int64_t)sg.krow + j) * a.ldkv + h * DH + hf * HALF;
 #pragma unroll
     for (int c = 0; c < HALF; c++) { k[c] = bf16_to_f32(kp[c]); v[c] = bf16_to_f32(vp[c]); }
   }
-  const bool real = j < key_count(a, s);   // a padded key gets no weight from any query: its dk, dv stay zero
+  const bool real = j < sg.nk;   // a padded key gets no weight from any query: its dk, dv stay zero
   const int first = a.causal ? tile * ATT_ROWS / ATT_KC * ATT_KC : 0;   // queries before the tile's first key see none of it
-  for (int i0 = first; i0 < a.Tq; i0 += ATT_KC) {
-    const int n = min(ATT_KC, a.Tq - i0);
+  for (int i0 = first; i0 < sg.Tq; i0 += ATT_KC) {
+    const int n = min(ATT_KC, sg.Tq - i0);
     __syncthreads();
-    stage_chunk<DH>(a.q + ((int64_t)s * a.Tq + i0) * a.ldq + h * DH, a.ldq, n, Qs);
-    stage_chunk<DH>(a.dout + ((int64_t)s * a.Tq + i0) * a.ldo + h * DH, a.ldo, n, Gs);
+    stage_chunk<DH>(a.q + ((int64_t)sg.qrow + i0) * a.ldq + h * DH, a.ldq, n, Qs);
+    stage_chunk<DH>(a.dout + ((int64_t)sg.qrow + i0) * a.ldo + h * DH, a.ldo, n, Gs);
     if ((int)threadIdx.x < ATT_KC) {
       const bool in = (int)threadIdx.x < n;
-      Ls[threadIdx.x] = in ? a.lse[((int64_t)s * a.heads + h) * a.Tq + i0 + threadIdx.x] : 0.f;
-      Ds[threadIdx.x] = in ? a.dsum[((int64_t)s * a.heads + h) * a.Tq + i0 + threadIdx.x] : 0.f;
+      Ls[threadIdx.x] = in ? a.lse[sg.lrow + i0 + threadIdx.x] : 0.f;
+      Ds[threadIdx.x] = in ? a.dsum[sg.lrow + i0 + threadIdx.x] : 0.f;
     }
     __syncthreads();
     for (int i = 0; i < n; i++) {
@@ -262,8 +323,8 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_k(AttArgs a) {
     }
   }
   if (!live) return;
-  bf16_t* dkp = a.dk + ((int64_t)s * a.Tk + j) * a.ldkv + h * DH + hf * HALF;
-  bf16_t* dvp = a.dv + ((int64_t)s * a.Tk + j) * a.ldkv + h * DH + hf * HALF;
+  bf16_t* dkp = a.dk + ((int64_t)sg.krow + j) * a.ldkv + h * DH + hf * HALF;
+  bf16_t* dvp = a.dv + ((int64_t)sg.krow + j) * a.ldkv + h * DH + hf * HALF;
 #pragma unroll
   for (int c = 0; c < HALF; c++) { dkp[c] = f32_to_bf16(dk[c] * a.scale); dvp[c] = f32_to_bf16(dv[c]); }
 }
@@ -358,15 +419,22 @@ __global__ void __launch_bounds__(256) attn_fwd_mfma_k(AttArgs a) {
   const int tiles = (a.Tq + ATT_ROWS - 1) / ATT_ROWS;
   const int tile = blockIdx.x % tiles, sh = blockIdx.x / tiles;
   const int h = sh % a.heads, s = sh / a.heads;
+  Seg sg;
+  const int seg = segment(a, s, h, sg);
+  if (seg != SEG_ROWS) {   // (packed batches) no such sentence; the first index behind the last one clears the unused rows
+    if (seg == SEG_TAIL && tile == 0) clear_rows<DH>(a.out, a.ldo, sg.qrow, a.lse_rows, h);
+    return;
+  }
+  if (tile * ATT_ROWS >= sg.Tq) return;   // (packed batches) the sentence ends before this tile
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int c = lane & 31, hh = lane >> 5;
   const int qi = tile * ATT_ROWS + wave * 32 + c;
-  const bool live = qi < a.Tq;
+  const bool live = qi < sg.Tq;
   bf16x8_t qf[KS];
 #pragma unroll
   for (int t = 0; t < KS; t++) {
     uint4 u = make_uint4(0, 0, 0, 0);
-    if (live) u = *reinterpret_cast<const uint4*>(a.q + ((int64_t)s * a.Tq + qi) * a.ldq + h * DH + 16 * t + 8 * hh);
+    if (live) u = *reinterpret_cast<const uint4*>(a.q + ((int64_t)sg.qrow + qi) * a.ldq + h * DH + 16 * t + 8 * hh);
     qf[t] = frag_from(u);
   }
   f32x16_t o[DT];
@@ -375,13 +443,13 @@ __global__ void __launch_bounds__(256) attn_fwd_mfma_k(AttArgs a) {
 #pragma unroll
     for (int v = 0; v < 16; v++) o[dt][v] = 0.f;
   float m = -INFINITY, lsum = 0.f;
-  const int nk = key_count(a, s);
+  const int nk = sg.nk;
   const int last = a.causal ? min(nk, tile * ATT_ROWS + ATT_ROWS) : nk;
   for (int j0 = 0; j0 < last; j0 += MF_KC) {
     const int n = min(MF_KC, nk - j0);
     __syncthreads();
-    stage_rows<DH>(a.k + ((int64_t)s * a.Tk + j0) * a.ldkv + h * DH, a.ldkv, n, Ks);
-    stage_transposed<DH, false>(a.v + ((int64_t)s * a.Tk + j0) * a.ldkv + h * DH, a.ldkv, n, Vt, nullptr);
+    stage_rows<DH>(a.k + ((int64_t)sg.krow + j0) * a.ldkv + h * DH, a.ldkv, n, Ks);
+    stage_transposed<DH, false>(a.v + ((int64_t)sg.krow + j0) * a.ldkv + h * DH, a.ldkv, n, Vt, nullptr);
     __syncthreads();
     f32x16_t sc[2];
     float mx = -INFINITY;
@@ -430,7 +498,7 @@ __global__ void __launch_bounds__(256) attn_fwd_mfma_k(AttArgs a) {
   const float lt = lsum + __shfl_xor(lsum, 32, 64);
   if (!live) return;
   const float inv = 1.f / lt;
-  bf16_t* op = a.out + ((int64_t)s * a.Tq + qi) * a.ldo + h * DH + 4 * hh;
+  bf16_t* op = a.out + ((int64_t)sg.qrow + qi) * a.ldo + h * DH + 4 * hh;
 #pragma unroll
   for (int dt = 0; dt < DT; dt++)
 #pragma unroll
@@ -438,7 +506,7 @@ __global__ void __launch_bounds__(256) attn_fwd_mfma_k(AttArgs a) {
       *reinterpret_cast<uint2*>(op + 32 * dt + 8 * g) =
           make_uint2(pack_bf16_pair(o[dt][4 * g] * inv, o[dt][4 * g + 1] * inv),
                      pack_bf16_pair(o[dt][4 * g + 2] * inv, o[dt][4 * g + 3] * inv));
-  if (hh == 0 && a.lse) a.lse[((int64_t)s * a.heads + h) * a.Tq + qi] = m + __logf(lt);
+  if (hh == 0 && a.lse) a.lse[sg.lrow + qi] = m + __logf(lt);
 }
 
 // dq on the matrix cores: 32 queries of a wave on the lanes, two passes over the keys as in the plain kernel
@@ -456,26 +524,33 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_mfma_k(AttArgs a) {
   const int tiles = (a.Tq + ATT_ROWS - 1) / ATT_ROWS;
   const int tile = blockIdx.x % tiles, sh = blockIdx.x / tiles;
   const int h = sh % a.heads, s = sh / a.heads;
+  Seg sg;
+  const int seg = segment(a, s, h, sg);
+  if (seg != SEG_ROWS) {   // (packed batches) no such sentence; the first index behind the last one clears the unused rows
+    if (seg == SEG_TAIL && tile == 0) clear_rows<DH>(a.dq, a.ldq, sg.qrow, a.lse_rows, h);
+    return;
+  }
+  if (tile * ATT_ROWS >= sg.Tq) return;   // (packed batches) the sentence ends before this tile
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int c = lane & 31, hh = lane >> 5;
   const int qi = tile * ATT_ROWS + wave * 32 + c;
-  const bool live = qi < a.Tq;
+  const bool live = qi < sg.Tq;
   bf16x8_t qf[KS], gf[KS];
 #pragma unroll
   for (int t = 0; t < KS; t++) {
     uint4 u = make_uint4(0, 0, 0, 0), g = make_uint4(0, 0, 0, 0);
     if (live) {
-      u = *reinterpret_cast<const uint4*>(a.q + ((int64_t)s * a.Tq + qi) * a.ldq + h * DH + 16 * t + 8 * hh);
-      g = *reinterpret_cast<const uint4*>(a.dout + ((int64_t)s * a.Tq + qi) * a.ldo + h * DH + 16 * t + 8 * hh);
+      u = *reinterpret_cast<const uint4*>(a.q + ((int64_t)sg.qrow + qi) * a.ldq + h * DH + 16 * t + 8 * hh);
+      g = *reinterpret_cast<const uint4*>(a.dout + ((int64_t)sg.qrow + qi) * a.ldo + h * DH + 16 * t + 8 * hh);
     }
     qf[t] = frag_from(u);
     gf[t] = frag_from(g);
   }
-  const float lse = live ? a.lse[((int64_t)s * a.heads + h) * a.Tq + qi] : 0.f;
-  const int nk = key_count(a, s);
+  const float lse = live ? a.lse[sg.lrow + qi] : 0.f;
+  const int nk = sg.nk;
   const int visible = a.causal ? min(qi + 1, nk) : nk;
   const float ref = lse - __logf((float)max(visible, 1));
-  if ((int)threadIdx.x < DH) K0[threadIdx.x] = bf16_to_f32(a.k[(int64_t)s * a.Tk * a.ldkv + h * DH + threadIdx.x]);
+  if ((int)threadIdx.x < DH) K0[threadIdx.x] = bf16_to_f32(a.k[(int64_t)sg.krow * a.ldkv + h * DH + threadIdx.x]);
   f32x16_t dq[DT];
 #pragma unroll
   for (int dt = 0; dt < DT; dt++)
@@ -491,10 +566,10 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_mfma_k(AttArgs a) {
     }
     for (int j0 = 0; j0 < last; j0 += MF_KC) {
       const int n = min(MF_KC, nk - j0);
-      const bf16_t* kb = a.k + ((int64_t)s * a.Tk + j0) * a.ldkv + h * DH;
+      const bf16_t* kb = a.k + ((int64_t)sg.krow + j0) * a.ldkv + h * DH;
       __syncthreads();
       stage_rows<DH>(kb, a.ldkv, n, Ks);
-      stage_rows<DH>(a.v + ((int64_t)s * a.Tk + j0) * a.ldkv + h * DH, a.ldkv, n, Vs);
+      stage_rows<DH>(a.v + ((int64_t)sg.krow + j0) * a.ldkv + h * DH, a.ldkv, n, Vs);
       if (pass == 1) stage_transposed<DH, true>(kb, a.ldkv, n, Kc, K0);
       __syncthreads();
       f32x16_t sc[2], dp[2];
@@ -538,7 +613,7 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_mfma_k(AttArgs a) {
   }
   if (!live) return;
   const float fin = Z > 0.f ? a.scale / Z : 0.f;
-  bf16_t* op = a.dq + ((int64_t)s * a.Tq + qi) * a.ldq + h * DH + 4 * hh;
+  bf16_t* op = a.dq + ((int64_t)sg.qrow + qi) * a.ldq + h * DH + 4 * hh;
 #pragma unroll
   for (int dt = 0; dt < DT; dt++)
 #pragma unroll
@@ -546,7 +621,7 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_mfma_k(AttArgs a) {
       *reinterpret_cast<uint2*>(op + 32 * dt + 8 * g) =
           make_uint2(pack_bf16_pair(dq[dt][4 * g] * fin, dq[dt][4 * g + 1] * fin),
                      pack_bf16_pair(dq[dt][4 * g + 2] * fin, dq[dt][4 * g + 3] * fin));
-  if (hh == 0) a.dsum[((int64_t)s * a.heads + h) * a.Tq + qi] = D + dp0;
+  if (hh == 0) a.dsum[sg.lrow + qi] = D + dp0;
 }
 
 // dk, dv on the matrix cores: 32 keys of a wave on the lanes; per chunk of 64 queries S = Q K^T and
@@ -563,17 +638,24 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_mfma_k(AttArgs a) {
   const int tiles = (a.Tk + ATT_ROWS - 1) / ATT_ROWS;
   const int tile = blockIdx.x % tiles, sh = blockIdx.x / tiles;
   const int h = sh % a.heads, s = sh / a.heads;
+  Seg sg;
+  const int seg = segment(a, s, h, sg);
+  if (seg != SEG_ROWS) {   // (packed batches) no such sentence; the first index behind the last one clears the unused rows
+    if (seg == SEG_TAIL && tile == 0) { clear_rows<DH>(a.dk, a.ldkv, sg.krow, a.k_rows, h); clear_rows<DH>(a.dv, a.ldkv, sg.krow, a.k_rows, h); }
+    return;
+  }
+  if (tile * ATT_ROWS >= sg.Tk) return;   // (packed batches) the sentence ends before this tile
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int c = lane & 31, hh = lane >> 5;
   const int kj = tile * ATT_ROWS + wave * 32 + c;
-  const bool live = kj < a.Tk;
+  const bool live = kj < sg.Tk;
   bf16x8_t kf[KS], vf[KS];
 #pragma unroll
   for (int t = 0; t < KS; t++) {
     uint4 u = make_uint4(0, 0, 0, 0), w = make_uint4(0, 0, 0, 0);
     if (live) {
-      u = *reinterpret_cast<const uint4*>(a.k + ((int64_t)s * a.Tk + kj) * a.ldkv + h * DH + 16 * t + 8 * hh);
-      w = *reinterpret_cast<const uint4*>(a.v + ((int64_t)s * a.Tk + kj) * a.ldkv + h * DH + 16 * t + 8 * hh);
+      u = *reinterpret_cast<const uint4*>(a.k + ((int64_t)sg.krow + kj) * a.ldkv + h * DH + 16 * t + 8 * hh);
+      w = *reinterpret_cast<const uint4*>(a.v + ((int64_t)sg.krow + kj) * a.ldkv + h * DH + 16 * t + 8 * hh);
     }
     kf[t] = frag_from(u);
     vf[t] = frag_from(w);
@@ -583,12 +665,12 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_mfma_k(AttArgs a) {
   for (int dt = 0; dt < DT; dt++)
 #pragma unroll
     for (int v = 0; v < 16; v++) { dk[dt][v] = 0.f; dv[dt][v] = 0.f; }
-  const bool real = kj < key_count(a, s);   // a padded key gets no weight from any query: its dk, dv stay zero
+  const bool real = kj < sg.nk;   // a padded key gets no weight from any query: its dk, dv stay zero
   const int first = a.causal ? tile * ATT_ROWS / MF_KC * MF_KC : 0;   // earlier queries see none of the tile's keys
-  for (int i0 = first; i0 < a.Tq; i0 += MF_KC) {
-    const int n = min(MF_KC, a.Tq - i0);
-    const bf16_t* qb = a.q + ((int64_t)s * a.Tq + i0) * a.ldq + h * DH;
-    const bf16_t* gb = a.dout + ((int64_t)s * a.Tq + i0) * a.ldo + h * DH;
+  for (int i0 = first; i0 < sg.Tq; i0 += MF_KC) {
+    const int n = min(MF_KC, sg.Tq - i0);
+    const bf16_t* qb = a.q + ((int64_t)sg.qrow + i0) * a.ldq + h * DH;
+    const bf16_t* gb = a.dout + ((int64_t)sg.qrow + i0) * a.ldo + h * DH;
     __syncthreads();
     stage_rows<DH>(qb, a.ldq, n, Qs);
     stage_rows<DH>(gb, a.ldo, n, Gs);
@@ -596,8 +678,8 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_mfma_k(AttArgs a) {
     stage_transposed<DH, false>(gb, a.ldo, n, Gt, nullptr);
     if ((int)threadIdx.x < MF_KC) {
       const bool in = (int)threadIdx.x < n;
-      Ls[threadIdx.x] = in ? a.lse[((int64_t)s * a.heads + h) * a.Tq + i0 + threadIdx.x] : 0.f;
-      Ds[threadIdx.x] = in ? a.dsum[((int64_t)s * a.heads + h) * a.Tq + i0 + threadIdx.x] : 0.f;
+      Ls[threadIdx.x] = in ? a.lse[sg.lrow + i0 + threadIdx.x] : 0.f;
+      Ds[threadIdx.x] = in ? a.dsum[sg.lrow + i0 + threadIdx.x] : 0.f;
     }
     __syncthreads();
     f32x16_t sc[2], dp[2];
@@ -616,7 +698,7 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_mfma_k(AttArgs a) {
         const int r = 32 * qt + 8 * (v >> 2) + 4 * hh + (v & 3);
         const int qi = i0 + r;
         float p = __expf(sc[qt][v] * a.scale - Ls[r]);
-        if (qi >= a.Tq || !real || (a.causal && kj > qi)) p = 0.f;
+        if (qi >= sg.Tq || !real || (a.causal && kj > qi)) p = 0.f;
         dp[qt][v] = p * (dp[qt][v] - Ds[r]);
         sc[qt][v] = p;
       }
@@ -632,8 +714,8 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_mfma_k(AttArgs a) {
     }
   }
   if (!live) return;
-  bf16_t* dkp = a.dk + ((int64_t)s * a.Tk + kj) * a.ldkv + h * DH + 4 * hh;
-  bf16_t* dvp = a.dv + ((int64_t)s * a.Tk + kj) * a.ldkv + h * DH + 4 * hh;
+  bf16_t* dkp = a.dk + ((int64_t)sg.krow + kj) * a.ldkv + h * DH + 4 * hh;
+  bf16_t* dvp = a.dv + ((int64_t)sg.krow + kj) * a.ldkv + h * DH + 4 * hh;
 #pragma unroll
   for (int dt = 0; dt < DT; dt++)
 #pragma unroll
@@ -652,15 +734,16 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_mfma_k(AttArgs a) {
 template <typename T>
 __global__ void __launch_bounds__(256) embed_fwd_k(const int32_t* __restrict__ tok, int64_t tok_pitch, int col0, int T_,
                                                    const T* __restrict__ table, int vocab, int d, T* __restrict__ y,
-                                                   int64_t rows) {
+                                                   int64_t rows, const int32_t* __restrict__ pos) {
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int half = d / 2;
   if (idx >= rows * half) return;
   const int i = (int)(idx % half);
   const int64_t row = idx / half;
-  const int t = (int)(row % T_);
+  int t = (int)(row % T_);
   const int64_t s = row / T_;
   int id = tok[s * tok_pitch + col0 + t];
+  if (pos) t = pos[s * tok_pitch + col0 + t];   // packed batches: the position inside the token's own sentence
   const float keep = id < 0 ? 0.f : 1.f;      // a negative id is padding: a zero row (plus the position signal)
   id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);   // ids are validated by the caller; clamp keeps the access in bounds
   const float ang = (float)t * __expf(-(float)(2 * i) / (float)d * 9.210340371976184f);   // ln 10000
@@ -726,6 +809,44 @@ __global__ void __launch_bounds__(256) embed_bwd_k(const int32_t* __restrict__ t
   }
 }
 
+// ---- sentence tables of a packed batch -------------------------------------------------------------
+// One workgroup walks the rows 1024 at a time.  A row with a non-negative id and position 0 starts a sentence: its
+// rank among the starts (a prefix count over the workgroup) is the sentence's number.  table[i] = first row of
+// sentence i (i < max_sent), table[n] = the first row that belongs to no sentence kept (the start of sentence
+// max_sent, if there are more, else the number of rows with non-negative ids), table[max_sent + 1] = n.
+__global__ void __launch_bounds__(1024) sentence_tables_k(const int32_t* __restrict__ tok, const int32_t* __restrict__ pos,
+                                                          int rows, int max_sent, int32_t* __restrict__ table) {
+  __shared__ int wave_cnt[16], wave_val[16];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int starts = 0, valid = 0;   // running totals, the same in every thread
+  for (int r0 = 0; r0 < rows; r0 += 1024) {
+    const int r = r0 + (int)threadIdx.x;
+    const bool ok = r < rows && tok[r] >= 0;
+    const bool st = ok && pos[r] == 0;
+    const unsigned long long bs = __ballot(st), bv = __ballot(ok);
+    __syncthreads();   // the previous chunk's counts have been read
+    if (lane == 0) { wave_cnt[wave] = __popcll(bs); wave_val[wave] = __popcll(bv); }
+    __syncthreads();
+    int before = 0, chunk_starts = 0, chunk_valid = 0;
+    for (int w = 0; w < 16; w++) {
+      before += w < wave ? wave_cnt[w] : 0;
+      chunk_starts += wave_cnt[w];
+      chunk_valid += wave_val[w];
+    }
+    if (st) {
+      const int rank = starts + before + __popcll(bs & ((1ull << lane) - 1ull));
+      if (rank <= max_sent) table[rank] = r;   // rank == max_sent: the end of the last sentence kept
+    }
+    starts += chunk_starts;
+    valid += chunk_valid;
+  }
+  if (threadIdx.x == 0) {
+    const int n = starts < max_sent ? starts : max_sent;
+    if (starts <= max_sent) table[n] = valid;
+    table[max_sent + 1] = n;
+  }
+}
+
 }  // namespace
 
 // The matrix-core kernels read 16-byte vectors: head dimension 64 or 32 and row pitches that keep every row aligned.
@@ -748,9 +869,14 @@ bool attention_supported(int dh) { return dh == 8 || dh == 16 || dh == 32 || dh 
 
 void attention_forward(const bf16_t* q, int64_t ldq, const bf16_t* k, const bf16_t* v, int64_t ldkv, bf16_t* out, int64_t ldo,
                        float* lse, int S, int heads, int Tq, int Tk, int dh, bool causal, const int32_t* key_tokens,
-                       int64_t tok_pitch, int key_col0, hipStream_t s) {
+                       int64_t tok_pitch, int key_col0, const SentenceTables* tab, hipStream_t s) {
   AttArgs a = {};
   a.ktok = key_tokens; a.tok_pitch = tok_pitch; a.ktok0 = key_col0;
+  if (tab) {
+    a.q_tab = tab->q; a.k_tab = tab->k; a.max_sent = tab->max_sent; a.lse_rows = tab->q_rows; a.k_rows = tab->k_rows;
+    a.ktok = nullptr;
+    S = tab->max_sent + 1;   // one more row of workgroups: it clears the rows behind the last sentence
+  }
   a.q = q; a.k = k; a.v = v; a.ldq = ldq; a.ldkv = ldkv; a.out = out; a.ldo = ldo; a.lse = lse;
   a.S = S; a.heads = heads; a.Tq = Tq; a.Tk = Tk; a.causal = causal ? 1 : 0;
   a.scale = 1.f / sqrtf((float)dh);
@@ -766,9 +892,14 @@ void attention_forward(const bf16_t* q, int64_t ldq, const bf16_t* k, const bf16
 void attention_backward(const bf16_t* q, int64_t ldq, const bf16_t* k, const bf16_t* v, int64_t ldkv, const bf16_t* dout,
                         int64_t ldo, const float* lse, float* dsum, bf16_t* dq, bf16_t* dk, bf16_t* dv, int S, int heads,
                         int Tq, int Tk, int dh, bool causal, const int32_t* key_tokens, int64_t tok_pitch, int key_col0,
-                        hipStream_t s) {
+                        const SentenceTables* tab, hipStream_t s) {
   AttArgs a = {};
   a.ktok = key_tokens; a.tok_pitch = tok_pitch; a.ktok0 = key_col0;
+  if (tab) {
+    a.q_tab = tab->q; a.k_tab = tab->k; a.max_sent = tab->max_sent; a.lse_rows = tab->q_rows; a.k_rows = tab->k_rows;
+    a.ktok = nullptr;
+    S = tab->max_sent + 1;   // one more row of workgroups: it clears the rows behind the last sentence
+  }
   a.q = q; a.k = k; a.v = v; a.ldq = ldq; a.ldkv = ldkv; a.dout = dout; a.ldo = ldo;
   a.lse = const_cast<float*>(lse); a.dsum = dsum; a.dq = dq; a.dk = dk; a.dv = dv;
   a.S = S; a.heads = heads; a.Tq = Tq; a.Tk = Tk; a.causal = causal ? 1 : 0;
@@ -790,14 +921,18 @@ void attention_backward(const bf16_t* q, int64_t ldq, const bf16_t* k, const bf1
 }
 
 void embed_forward(int dtype, const int32_t* tok, int64_t tok_pitch, int col0, int len, const void* table, int vocab, int d,
-                   void* y, int64_t rows, hipStream_t s) {
+                   void* y, int64_t rows, const int32_t* pos, hipStream_t s) {
   const unsigned grid = (unsigned)cdiv(rows * (d / 2), 256);
   if (dtype == CD_BF16)
     hipLaunchKernelGGL(embed_fwd_k<bf16_t>, dim3(grid), dim3(256), 0, s, tok, tok_pitch, col0, len, (const bf16_t*)table,
-                       vocab, d, (bf16_t*)y, rows);
+                       vocab, d, (bf16_t*)y, rows, pos);
   else
     hipLaunchKernelGGL(embed_fwd_k<float>, dim3(grid), dim3(256), 0, s, tok, tok_pitch, col0, len, (const float*)table,
-                       vocab, d, (float*)y, rows);
+                       vocab, d, (float*)y, rows, pos);
+}
+
+void sentence_tables(const int32_t* tok, const int32_t* pos, int rows, int max_sent, int32_t* table, hipStream_t s) {
+  hipLaunchKernelGGL(sentence_tables_k, dim3(1), dim3(1024), 0, s, tok, pos, rows, max_sent, table);
 }
 
 void embed_backward(int dtype, const int32_t* tok, int64_t tok_pitch, int col0, int len, const void* dy, int vocab, int d,

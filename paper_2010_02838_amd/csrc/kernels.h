@@ -168,19 +168,30 @@ void extract_group_dw(const float* dwd, float* dw, int C, int taps, int groups, 
 // scores.  dh in {8, 16, 32, 64} (attention_supported).  key_tokens (nullable): int32 token ids [S][tok_pitch]; the keys
 // of sentence s belong to columns key_col0 .. key_col0 + Tk, and only those before the first negative id (padding)
 // take part; padded keys get zero dk, dv.
+// Packed batches (tab != nullptr): the sentences lie one after the other in the query and key tensors.  q and k are
+// device tables of max_sent + 2 entries (sentence_tables): [i] = first row of sentence i, [n] = the row after the last
+// sentence, [max_sent + 1] = n.  S is then max_sent, Tq / Tk the longest sentence the launch covers, lse and dsum are
+// [heads][q_rows] indexed by the query's row, and key_tokens is not used.  q_rows / k_rows: rows of the query / key
+// tensors; the rows behind the last sentence are written as zeros in out, dq, dk and dv.
+struct SentenceTables { const int32_t* q; const int32_t* k; int max_sent; int q_rows; int k_rows; };
+// table (max_sent + 2 entries) from the rows' token ids and positions inside their sentences: a row with a
+// non-negative id and position 0 starts a sentence; the rows after the last sentence have negative ids.
+// Sentences beyond max_sent are left out.
+void sentence_tables(const int32_t* tok, const int32_t* pos, int rows, int max_sent, int32_t* table, hipStream_t s);
 bool attention_supported(int dh);
 void attention_forward(const bf16_t* q, int64_t ldq, const bf16_t* k, const bf16_t* v, int64_t ldkv, bf16_t* out, int64_t ldo,
                        float* lse, int S, int heads, int Tq, int Tk, int dh, bool causal, const int32_t* key_tokens,
-                       int64_t tok_pitch, int key_col0, hipStream_t s);
+                       int64_t tok_pitch, int key_col0, const SentenceTables* tab, hipStream_t s);
 // dq, dk, dv are written (not accumulated), with the pitches of q and k / v; dsum: [S][heads][Tq] fp32 scratch.
 void attention_backward(const bf16_t* q, int64_t ldq, const bf16_t* k, const bf16_t* v, int64_t ldkv, const bf16_t* dout,
                         int64_t ldo, const float* lse, float* dsum, bf16_t* dq, bf16_t* dk, bf16_t* dv, int S, int heads,
                         int Tq, int Tk, int dh, bool causal, const int32_t* key_tokens, int64_t tok_pitch, int key_col0,
-                        hipStream_t s);
+                        const SentenceTables* tab, hipStream_t s);
 // y[s*len + t][:] = table[tok[s*tok_pitch + col0 + t]][:] * sqrt(d) + the sinusoidal position signal of t (d even);
-// a negative id (padding) gives the position signal alone and takes no gradient
+// a negative id (padding) gives the position signal alone and takes no gradient.  pos (nullable, packed batches):
+// the position of every token inside its sentence, laid out like tok; t is then read from it.
 void embed_forward(int dtype, const int32_t* tok, int64_t tok_pitch, int col0, int len, const void* table, int vocab, int d,
-                   void* y, int64_t rows, hipStream_t s);
+                   void* y, int64_t rows, const int32_t* pos, hipStream_t s);
 // dtable[tok] += sqrt(d) * dy[row], added onto a gradient that already holds the other uses of the table; one writer per
 // table row, additions in position order (bit-reproducible)
 void embed_backward(int dtype, const int32_t* tok, int64_t tok_pitch, int col0, int len, const void* dy, int vocab, int d,

@@ -29,6 +29,7 @@ struct Op {
   //          heads, causal; the width of each column range is the width of y.
   int a0 = 0, a1 = 0, a2 = 0, heads = 0;
   int key_tok0 = 0;    // OP_ATTN: first token column of the sentences the keys come from (their padding is masked)
+  int q_stream = 0, k_stream = 0;   // OP_ATTN: which token stream (0 source, 1 target) the queries and the keys belong to
   bool causal = false;
   bool tied = false;   // OP_LINEAR: the weight is another op's parameter (the embedding table)
   int groups = 1;      // OP_CONV: groups of a grouped convolution (input and output channels are then equal)
@@ -66,6 +67,8 @@ struct Plan {
   size_t gtmp_bytes = 0;
   size_t gw = 0;              // the dense per-slice filters of the op at hand
   size_t gdw = 0;             // save only: the dense per-slice filter gradients of the op at hand (fp32)
+  size_t seq_tab = 0;         // packed Transformer batches: the sentence tables of the source and of the target stream,
+                              // max_sentences + 2 int32 each (kernels.h, sentence_tables)
   size_t total = 0;
 };
 

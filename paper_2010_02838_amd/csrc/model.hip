@@ -123,11 +123,12 @@ struct Builder {
     m->ops.push_back(o);
     return o.y;
   }
-  int attention(int q, int q_col, int kv, int k_col, int v_col, int d, int heads, bool causal, int key_tok0) {
+  int attention(int q, int q_col, int kv, int k_col, int v_col, int d, int heads, bool causal, int key_tok0, int q_stream,
+                int k_stream) {
     const TensorDesc tq = m->tensors[q];
     Op o;
     o.kind = OP_ATTN; o.x = q; o.res = kv; o.a0 = q_col; o.a1 = k_col; o.a2 = v_col; o.heads = heads; o.causal = causal;
-    o.key_tok0 = key_tok0;
+    o.key_tok0 = key_tok0; o.q_stream = q_stream; o.k_stream = k_stream;
     o.y = add_tensor(tq.h, tq.w, d);
     m->ops.push_back(o);
     return o.y;
@@ -163,7 +164,7 @@ void build_transformer_head(Builder& b, const cd_arch_desc& a) {
 // followed by its residual connection and LayerNorm; logits against the (tied) embedding table.  The
 // input projections of an attention sublayer are one dense layer (d -> 3d, or d -> d for the queries and
 // d -> 2d for keys and values of the encoder output); dense layers are 1x1 convolutions over
-// [sentences][tokens][1][d] tensors.  No dropout, no padding (all sentences have the same lengths).
+// [sentences][tokens][1][d] tensors ([1][rows of the stream][1][d] for packed sentences).  No dropout.
 void build_transformer(Builder& b, const cd_arch_desc& a) {
   const int d = a.widths[0], ff = a.widths[1], heads = a.widths[2];
   const int Ts = a.in_h, Tt = a.in_w;
@@ -182,7 +183,7 @@ void build_transformer(Builder& b, const cd_arch_desc& a) {
   };
   auto self_attention = [&](int x, const std::string& p, bool causal) {
     int qkv = dense(x, p + ".qkv", d, 3 * d, false);
-    int o = b.attention(qkv, 0, qkv, d, 2 * d, d, heads, causal, causal ? Ts : 0);   // decoder keys: target sentences
+    int o = b.attention(qkv, 0, qkv, d, 2 * d, d, heads, causal, causal ? Ts : 0, causal, causal);   // decoder keys: target sentences
     return add_norm(x, dense(o, p + ".out", d, d, false), p + ".ln");
   };
   int64_t sh[2] = {a.classes, d};
@@ -201,7 +202,7 @@ void build_transformer(Builder& b, const cd_arch_desc& a) {
     y = self_attention(y, p + ".self", true);
     int q = dense(y, p + ".cross.q", d, d, false);
     int kv = dense(memory, p + ".cross.kv", d, 2 * d, false);
-    int o = b.attention(q, 0, kv, 0, d, d, heads, false, 0);
+    int o = b.attention(q, 0, kv, 0, d, d, heads, false, 0, 1, 0);
     y = add_norm(y, dense(o, p + ".cross.out", d, d, false), p + ".cross.ln");
     y = ffn(y, p);
   }
@@ -423,7 +424,9 @@ Plan make_plan(const cd_model* m, int64_t B, bool save) {
   p.partials_bytes = kPartialsBytes;
   p.partials = alloc(p.partials_bytes);
   if (m->dtype == CD_BF16) {
-    p.xpack = alloc((size_t)B * m->arch.in_h * m->arch.in_w * 8 * 2);
+    if (m->arch.kind != CD_ARCH_TRANSFORMER) p.xpack = alloc((size_t)B * m->arch.in_h * m->arch.in_w * 8 * 2);
+    if (m->arch.kind == CD_ARCH_TRANSFORMER && m->arch.max_sentences > 0)
+      p.seq_tab = alloc((size_t)2 * (m->arch.max_sentences + 2) * sizeof(int32_t));
     size_t wmax = 0;
     for (const ParamDesc& q : m->params) {
       if (q.kind == CD_P_CONV_W) {
@@ -534,8 +537,12 @@ extern "C" int codistill_model_create(const cd_arch_desc* a, int dtype, cd_model
                  a->kind == CD_ARCH_TRANSFORMER_HEAD || a->kind == CD_ARCH_TRANSFORMER || a->kind == CD_ARCH_WIDE_RESNET_SPLIT,
              "model_create: unknown architecture kind %d", a->kind);
   CD_REQUIRE(a->classes >= 1 && a->classes <= (1 << 24), "model_create: classes=%d out of range", a->classes);
-  CD_REQUIRE(a->in_h >= 1 && a->in_w >= 1 && a->in_h <= 4096 && a->in_w <= 4096,
+  const bool packed = a->kind == CD_ARCH_TRANSFORMER && a->max_sentences != 0;
+  const int res_max = packed ? 65536 : 4096;
+  CD_REQUIRE(a->in_h >= 1 && a->in_w >= 1 && a->in_h <= res_max && a->in_w <= res_max,
              "model_create: input resolution %dx%d out of range", a->in_h, a->in_w);
+  CD_REQUIRE(a->kind == CD_ARCH_TRANSFORMER || (a->max_sentences == 0 && a->max_sentence_len == 0),
+             "model_create: max_sentences / max_sentence_len belong to CD_ARCH_TRANSFORMER");
   if (a->kind == CD_ARCH_TINY_CNN) {
     CD_REQUIRE(a->widths[0] >= 1 && a->widths[1] >= 1 && a->widths[0] <= 4096 && a->widths[1] <= 4096,
                "model_create: tiny CNN widths out of range");
@@ -547,6 +554,12 @@ extern "C" int codistill_model_create(const cd_arch_desc* a, int dtype, cd_model
                "model_create: d_model / heads must be 8, 16, 32 or 64");
     CD_REQUIRE(a->blocks[0] >= 1 && a->blocks[0] <= 64 && a->blocks[1] >= 1 && a->blocks[1] <= 64,
                "model_create: encoder / decoder layer counts out of range");
+    if (packed)
+      CD_REQUIRE(a->max_sentences >= 1 && a->max_sentences <= 65536 && a->max_sentence_len >= 1 && a->max_sentence_len <= 65536,
+                 "model_create: packed sentences need 1 <= max_sentences, max_sentence_len <= 65536 (got %d, %d)",
+                 a->max_sentences, a->max_sentence_len);
+    else
+      CD_REQUIRE(a->max_sentence_len == 0, "model_create: max_sentence_len without max_sentences");
     if (dtype != CD_BF16) return set_error(CD_ERR_UNSUPPORTED, "model_create: the Transformer is implemented for CD_BF16 only");
   } else if (a->kind == CD_ARCH_TRANSFORMER_HEAD) {
     CD_REQUIRE(a->widths[0] >= 1 && a->widths[1] >= 1 && a->widths[0] <= 16384 && a->widths[1] <= 65536,
@@ -701,11 +714,21 @@ struct Ctx {
   float* coef() const { return reinterpret_cast<float*>(ws + plan.bn_coef); }
   bf16_t* xpack() const { return reinterpret_cast<bf16_t*>(ws + plan.xpack); }
   bf16_t* wpack() const { return reinterpret_cast<bf16_t*>(ws + plan.wpack); }
+  // packed Transformer batches: x is [2][rows] (ids, then positions); one sentence table per token stream
+  bool packed() const { return m->arch.kind == CD_ARCH_TRANSFORMER && m->arch.max_sentences > 0; }
+  const int32_t* positions() const { return packed() ? static_cast<const int32_t*>(x) + m->tensors[0].w : nullptr; }
+  int32_t* table(int stream) const { return reinterpret_cast<int32_t*>(ws + plan.seq_tab) + stream * (m->arch.max_sentences + 2); }
+  // the tables an attention op reads, and the sentence count / length its launch covers (padded: batch and the tensors' rows)
+  SentenceTables tables(const Op& o, int q_rows, int k_rows) const {
+    return SentenceTables{table(o.q_stream), table(o.k_stream), m->arch.max_sentences, q_rows, k_rows};
+  }
 };
 
 int check_common(const char* fn, const cd_model* m, const void* params, const void* x, int64_t batch, void* ws) {
   CD_REQUIRE(m && params && x && ws, "%s: NULL pointer argument", fn);
   CD_REQUIRE(batch >= 1 && batch <= (1 << 20), "%s: batch=%lld out of range", fn, (long long)batch);
+  CD_REQUIRE(!(m->arch.kind == CD_ARCH_TRANSFORMER && m->arch.max_sentences > 0) || batch == 1,
+             "%s: a packed batch of sentences is one batch element (batch=%lld)", fn, (long long)batch);
   CD_REQUIRE(aligned16(params) && aligned16(x) && (reinterpret_cast<uintptr_t>(ws) & 255) == 0,
              "%s: params and x must be 16-byte aligned, the workspace 256-byte aligned", fn);
   return CD_OK;
@@ -765,6 +788,12 @@ extern "C" int codistill_forward(const cd_model* m, const void* params, const vo
   const int dt = m->dtype;
   const int logits_t = m->ops.back().y;
 
+  if (c.packed()) {   // where the sentences of this batch begin, per stream (the backward pass reads the same tables)
+    const int32_t* tok = static_cast<const int32_t*>(x);
+    ProfScope pr(CD_K_GLUE, c.s, 0, 8.0 * (m->arch.in_h + m->arch.in_w));
+    sentence_tables(tok, c.positions(), m->arch.in_h, m->arch.max_sentences, c.table(0), c.s);
+    sentence_tables(tok + m->arch.in_h, c.positions() + m->arch.in_h, m->arch.in_w, m->arch.max_sentences, c.table(1), c.s);
+  }
   int stat_chunks = 0, stat_tensor = -1;  // statistics a convolution left in the partials area for its BatchNorm
   for (size_t oi = 0; oi < m->ops.size(); oi++) {
     const Op& o = m->ops[oi];
@@ -920,20 +949,26 @@ extern "C" int codistill_forward(const cd_model* m, const void* params, const vo
         const TensorDesc& ty = m->tensors[o.y];
         ProfScope pr(CD_K_GLUE, c.s, 0, (double)batch * ty.per_sample() * m->esize() * 2);
         embed_forward(dt, static_cast<const int32_t*>(x), m->tensors[0].w, o.a0, o.a1, c.P(o.pw), m->arch.classes, ty.c, out,
-                      batch * ty.h, c.s);
+                      batch * ty.h, c.positions(), c.s);
         break;
       }
       case OP_ATTN: {
         const TensorDesc& tkv = m->tensors[o.res];
         const TensorDesc& ty = m->tensors[o.y];
-        const int d = ty.c, dh = d / o.heads, Tq = tx.h, Tk = tkv.h;
+        const int d = ty.c, dh = d / o.heads;
+        // packed sentences: one workgroup row per possible sentence, the tables say where each one lies
+        const bool pk = c.packed();
+        const int S = pk ? m->arch.max_sentences : (int)batch;
+        const int Tq = pk ? std::min(m->arch.max_sentence_len, tx.h) : tx.h, Tk = pk ? std::min(m->arch.max_sentence_len, tkv.h) : tkv.h;
+        const SentenceTables tab = c.tables(o, tx.h, tkv.h);
         const bf16_t* kvp = static_cast<const bf16_t*>(c.act(o.res));
-        ProfScope pr(CD_K_ATTN, c.s, 4.0 * batch * o.heads * Tq * (double)Tk * dh * (o.causal ? 0.5 : 1.0),
-                     2.0 * batch * ((double)Tq * 2 + (double)Tk * 2) * d);
+        // (work figures of a packed batch: as if every row attended to a full-length sentence, an upper bound)
+        ProfScope pr(CD_K_ATTN, c.s, 4.0 * batch * o.heads * tx.h * (double)Tk * dh * (o.causal ? 0.5 : 1.0),
+                     2.0 * batch * ((double)tx.h * 2 + (double)tkv.h * 2) * d);
         attention_forward(static_cast<const bf16_t*>(in) + o.a0, tx.c, kvp + o.a1, kvp + o.a2, tkv.c,
                           static_cast<bf16_t*>(out), d, c.plan.aux[oi] ? reinterpret_cast<float*>(c.ws + c.plan.aux[oi]) : nullptr,
-                          (int)batch, o.heads, Tq, Tk, dh, o.causal, static_cast<const int32_t*>(x), m->tensors[0].w, o.key_tok0,
-                          c.s);
+                          S, o.heads, Tq, Tk, dh, o.causal, static_cast<const int32_t*>(x), m->tensors[0].w, o.key_tok0,
+                          pk ? &tab : nullptr, c.s);
         break;
       }
     }
@@ -1066,17 +1101,21 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
       case OP_ATTN: {
         const TensorDesc& tkv = m->tensors[o.res];
         const TensorDesc& ty = m->tensors[o.y];
-        const int d = ty.c, dh = d / o.heads, Tq = tx.h, Tk = tkv.h;
+        const int d = ty.c, dh = d / o.heads;
+        const bool pk = c.packed();
+        const int S = pk ? m->arch.max_sentences : (int)batch;
+        const int Tq = pk ? std::min(m->arch.max_sentence_len, tx.h) : tx.h, Tk = pk ? std::min(m->arch.max_sentence_len, tkv.h) : tkv.h;
+        const SentenceTables tab = c.tables(o, tx.h, tkv.h);
         // (inputs with another reader were rejected by check_supported before the first launch)
         const bf16_t* kvp = static_cast<const bf16_t*>(c.act(o.res));
         bf16_t* dkv = static_cast<bf16_t*>(c.grad(o.res));
         float* lse = reinterpret_cast<float*>(c.ws + c.plan.aux[i]);
-        ProfScope pr(CD_K_ATTN, c.s, 14.0 * batch * o.heads * Tq * (double)Tk * dh * (o.causal ? 0.5 : 1.0),
-                     2.0 * batch * ((double)Tq * 3 + (double)Tk * 4) * d);
+        ProfScope pr(CD_K_ATTN, c.s, 14.0 * batch * o.heads * tx.h * (double)Tk * dh * (o.causal ? 0.5 : 1.0),
+                     2.0 * batch * ((double)tx.h * 3 + (double)tkv.h * 4) * d);
         attention_backward(static_cast<const bf16_t*>(in) + o.a0, tx.c, kvp + o.a1, kvp + o.a2, tkv.c,
-                           static_cast<const bf16_t*>(dy), d, lse, lse + (size_t)batch * o.heads * Tq,
-                           static_cast<bf16_t*>(dx) + o.a0, dkv + o.a1, dkv + o.a2, (int)batch, o.heads, Tq, Tk, dh, o.causal,
-                           static_cast<const int32_t*>(x), m->tensors[0].w, o.key_tok0, c.s);
+                           static_cast<const bf16_t*>(dy), d, lse, lse + (size_t)batch * o.heads * tx.h,
+                           static_cast<bf16_t*>(dx) + o.a0, dkv + o.a1, dkv + o.a2, S, o.heads, Tq, Tk, dh, o.causal,
+                           static_cast<const int32_t*>(x), m->tensors[0].w, o.key_tok0, pk ? &tab : nullptr, c.s);
         written[o.res] = 1;
         break;
       }

@@ -93,6 +93,44 @@ def sentence_pairs(min_target_tokens, lo, hi, vocab, seed, pad=-1):
     return x, y.reshape(-1), np.array(src), np.array(tgt)
 
 
+def pack_sentences(x, y, src_len, rows_src=None, rows_tgt=None, multiple=128):
+    """A padded batch of sentence pairs in packed form (layout only, no arithmetic).  x: int32 [S, src_len + T] token
+    ids, every part padded at its end with negative ids; y: int32 [S * T] labels.  Returns (xp, yp, src_map, tgt_map):
+    xp int32 [2, rows_src + rows_tgt]: row 0 the real tokens of all sentences one after the other (source stream,
+    then target stream; negative ids in the rows behind the last sentence), row 1 every token's position inside its
+    sentence; yp int32 [rows_tgt] the labels of the target rows (-1 behind the last sentence); src_map / tgt_map: for every
+    used row of a stream its (sentence, position).  A part's length is the number of ids in front of its first negative
+    one (at least one token).  rows_src / rows_tgt default to the token counts rounded up to `multiple`."""
+    S, T = x.shape[0], x.shape[1] - src_len
+    y = np.asarray(y).reshape(S, T)
+
+    def length(row):
+        neg = np.nonzero(row < 0)[0]
+        return max(1, int(neg[0]) if len(neg) else len(row))
+
+    ls = [length(x[i, :src_len]) for i in range(S)]
+    lt = [length(x[i, src_len:]) for i in range(S)]
+    up = lambda n: -(-n // multiple) * multiple
+    rows_src = up(sum(ls)) if rows_src is None else rows_src
+    rows_tgt = up(sum(lt)) if rows_tgt is None else rows_tgt
+    assert sum(ls) <= rows_src and sum(lt) <= rows_tgt
+    xp = np.full((2, rows_src + rows_tgt), -1, dtype=np.int32)
+    xp[1] = 0
+    yp = np.full(rows_tgt, -1, dtype=np.int32)
+    src_map, tgt_map, rs, rt = [], [], 0, rows_src
+    for i in range(S):
+        xp[0, rs:rs + ls[i]] = x[i, :ls[i]]
+        xp[1, rs:rs + ls[i]] = np.arange(ls[i])
+        src_map += [(i, t) for t in range(ls[i])]
+        rs += ls[i]
+        xp[0, rt:rt + lt[i]] = x[i, src_len:src_len + lt[i]]
+        xp[1, rt:rt + lt[i]] = np.arange(lt[i])
+        yp[rt - rows_src:rt - rows_src + lt[i]] = y[i, :lt[i]]
+        tgt_map += [(i, t) for t in range(lt[i])]
+        rt += lt[i]
+    return xp, yp, np.array(src_map), np.array(tgt_map)
+
+
 def labels(n, classes, seed):
     return _rng(seed).integers(0, classes, size=n).astype(np.int32)
 

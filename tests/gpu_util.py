@@ -143,3 +143,96 @@ class Case:
         else:
             a = synth.bf16_to_f32(ws[offset:offset + 2 * n].view(torch.int16).cpu().numpy().view(np.uint16))
         return a.astype(np.float64).reshape(shape)
+
+
+class PackedCase:
+    """The sentences of a padded Transformer Case, given to the library in packed form (cd_arch_desc.max_sentences > 0:
+    the tokens of all sentences one after the other, no padding rows).  The oracle knows padded batches only: its results
+    on the padded form are the reference, and what the GPU returns per row of a stream is put back at the row's
+    (sentence, position); rows that are padding in the padded form have no counterpart and are left out of every
+    comparison (zeros on both sides)."""
+
+    def __init__(self, c0, arch_kw, Ts, Tt, multiple=128, slack_sentences=3):
+        B = c0.B
+        self.c0, self.B, self.dtype, self.ref_arch, self.batch = c0, B, c0.dtype, c0.ref_arch, c0.batch
+        self.x, self.y, self.th, self.thp, self.v0, self.classes = c0.x, c0.y, c0.th, c0.thp, c0.v0, c0.classes
+        self.Ts, self.Tt = Ts, Tt
+        self.xp, self.yp, self.src_map, self.tgt_map = synth.pack_sentences(c0.x, c0.y, Ts, multiple=multiple)
+        self.rows_src = self.xp.shape[1] - len(self.yp)
+        self.rows_tgt = len(self.yp)
+        kw = dict(arch_kw)
+        arch = B.arch_preset(kw.pop("kind"), in_h=self.rows_src, in_w=self.rows_tgt, classes=c0.classes,
+                             max_sentences=c0.batch + slack_sentences, max_sentence_len=max(Ts, Tt), **kw)
+        self.model, self.peer = B.Model(arch, self.dtype), B.Model(arch, self.dtype)
+        assert self.model.param_table() == c0.model.param_table()
+        self.per_tensor = c0.per_tensor
+
+    def valid_rows(self, stream):
+        """boolean [S, T]: the positions of a stream's padded form that hold a token"""
+        T, mp = (self.Tt, self.tgt_map) if stream else (self.Ts, self.src_map)
+        m = np.zeros((self.batch, T), dtype=bool)
+        m[mp[:, 0], mp[:, 1]] = True
+        return m
+
+    def unpack(self, a, stream):
+        """[rows of the stream, ...] -> [S * T, ...] with zeros where the padded form has padding"""
+        T, mp = (self.Tt, self.tgt_map) if stream else (self.Ts, self.src_map)
+        out = np.zeros((self.batch, T) + a.shape[1:], dtype=a.dtype)
+        out[mp[:, 0], mp[:, 1]] = a[:len(mp)]
+        return out.reshape((self.batch * T,) + a.shape[1:])
+
+    def oracle(self, **kw):
+        """The padded batch through the oracle; logits of padding rows zeroed (no counterpart on the GPU)."""
+        r = dict(self.c0.oracle(**kw))
+        keep = self.valid_rows(1).reshape(-1, 1)
+        r["logits"] = r["logits"] * keep
+        r["peer_logits"] = [z * keep for z in r["peer_logits"]]
+        return r
+
+    def gpu(self, alpha=1.0, lr=0.1, mu=0.9, wd=0.0, dist="mse", label_smoothing=0.0):
+        from paper_2010_02838_amd.runner import StepRunner, pack_flat, unpack_flat
+        B, model = self.B, self.model
+        r = StepRunner(model, [self.peer], 1)
+        r.load(pack_flat(model, self.th), [pack_flat(self.peer, self.thp)],
+               None if self.v0 is None else pack_flat(model, self.v0))
+        xd, yd = torch.from_numpy(self.xp[None]).to("cuda:0"), torch.from_numpy(self.yp).to("cuda:0")   # one batch element
+        r.step(xd, yd, alpha, lr, mu, weight_decay=wd, label_smoothing=label_smoothing,
+               dist_kind={"kl": B.CD_DIST_KL, "mse": B.CD_DIST_MSE_LOGITS, "mse_centered": B.CD_DIST_MSE_CENTERED}[dist])
+        torch.cuda.synchronize()
+        self.last_step = dict(lr=lr, mu=mu, wd=wd)
+        self.runner = r
+        self.raw_logits = r.logits.cpu().numpy()
+        return dict(logits=self.unpack(self.raw_logits, 1), peer_logits=self.unpack(r.peer_logits[0].cpu().numpy(), 1),
+                    loss=r.loss.cpu().numpy()[:3].astype(np.float64), dz=self.unpack(r.dz.cpu().numpy(), 1),
+                    grad=unpack_flat(model, r.grads.cpu().numpy()), theta=unpack_flat(model, r.master.cpu().numpy()),
+                    v=unpack_flat(model, r.momentum.cpu().numpy()))
+
+    read = Case.read
+
+    def graph(self):
+        """The op list and tensor table of the packed model, re-expressed for the padded form: tensors get the padded
+        sentence length as their height and the stream they belong to; token columns refer to the padded ids."""
+        ops, tensors = self.model.graph(1)
+        stream = {0: 0}
+        for o in ops:
+            if o["kind"] == "embed":
+                stream[o["y"]] = 0 if o["k"] == 0 else 1
+                o["k"], o["stride"] = (0, self.Ts) if o["k"] == 0 else (self.Ts, self.Tt)
+            else:
+                stream[o["y"]] = stream[o["x"]]
+            if o["kind"] == "attn" and o["key_tok0"]:
+                o["key_tok0"] = self.Ts
+        for t, td in enumerate(tensors):
+            td["stream"] = stream.get(t, 0)
+            td["rows"] = td["h"]
+            td["h"] = self.Tt if td["stream"] else self.Ts
+        return ops, tensors
+
+    def read_tensor(self, td, key, shape, f32=False):
+        """A tensor of the packed model out of the workspace, in the padded form's shape."""
+        a = self.read(td[key], (td["rows"],) + tuple(shape[2:]), f32)
+        return self.unpack(a, td["stream"]).reshape(shape)
+
+    def read_rows(self, td, offset, width):
+        """per-row fp32 side data of a tensor's rows ([rows][width]) -> [S * T][width]"""
+        return self.unpack(self.read(offset, (td["rows"], width), f32=True), td["stream"])

@@ -4,6 +4,7 @@ import ctypes
 import os
 import re
 
+import numpy as np
 import pytest
 
 from oracle import nets
@@ -95,6 +96,42 @@ def test_model_create_rejects_bad_arguments():
     for kw in (dict(n_splits=7), dict(split=8), dict(split=-1), dict(n_splits=0)):     # 160 channels in 8 parts
         bad = B.arch_preset(B.CD_ARCH_WIDE_RESNET_SPLIT, **kw)
         assert B.lib.codistill_model_create(ctypes.byref(bad), B.CD_BF16, ctypes.byref(h)) == B.CD_ERR_INVALID_ARG, kw
+
+
+def test_packed_sentences_arguments():
+    """Packed batches of sentences (max_sentences > 0): bounds checked at creation, one batch element per call, the same
+    parameters as the padded model, and a packing helper that loses nothing."""
+    h = ctypes.c_void_p()
+    ok = dict(in_h=8192, in_w=8320, max_sentences=512, max_sentence_len=128)
+    for kw in (dict(ok, max_sentences=-1), dict(ok, max_sentence_len=0), dict(ok, max_sentences=0), dict(ok, in_h=70000),
+               dict(ok, max_sentences=70000)):
+        bad = B.arch_preset(B.CD_ARCH_TRANSFORMER, **kw)
+        assert B.lib.codistill_model_create(ctypes.byref(bad), B.CD_BF16, ctypes.byref(h)) == B.CD_ERR_INVALID_ARG, kw
+    bad = B.arch_preset(B.CD_ARCH_RESNET_BOTTLENECK, max_sentences=4, max_sentence_len=4)
+    assert B.lib.codistill_model_create(ctypes.byref(bad), B.CD_BF16, ctypes.byref(h)) == B.CD_ERR_INVALID_ARG
+    padded = B.arch_preset(B.CD_ARCH_TRANSFORMER, in_h=8192)       # more than 4096 rows only in packed form
+    assert B.lib.codistill_model_create(ctypes.byref(padded), B.CD_BF16, ctypes.byref(h)) == B.CD_ERR_INVALID_ARG
+    m = B.Model(B.arch_preset(B.CD_ARCH_TRANSFORMER, **ok), B.CD_BF16)
+    assert m.param_table() == B.Model(B.arch_preset(B.CD_ARCH_TRANSFORMER), B.CD_BF16).param_table()
+    assert m.rows_per_sample == 8320
+    fake = ctypes.c_void_p(0x1000)       # never dereferenced: validation fails first
+    need = m.workspace_bytes(1, True)
+    assert B.lib.codistill_forward(m._h, fake, fake, 2, 1, 0, None, fake, need, fake, None) == B.CD_ERR_INVALID_ARG
+    assert b"one batch element" in B.lib.codistill_last_error()
+    assert B.lib.codistill_backward(m._h, fake, fake, 3, fake, need, fake, fake, None) == B.CD_ERR_INVALID_ARG
+    # the packing helper: every real token and label once, in order, positions restart with every sentence
+    from paper_2010_02838_amd import synth
+    x, y, sl, tl = synth.sentence_pairs(300, 3, 20, 50, seed=1)
+    xp, yp, smap, tmap = synth.pack_sentences(x, y, 20, multiple=16)
+    rows_src = xp.shape[1] - len(yp)
+    assert rows_src % 16 == 0 and len(yp) % 16 == 0 and len(smap) == sl.sum() and len(tmap) == tl.sum()
+    np.testing.assert_array_equal(xp[0, :len(smap)], x[smap[:, 0], smap[:, 1]])
+    np.testing.assert_array_equal(xp[0, rows_src:rows_src + len(tmap)], x[tmap[:, 0], 20 + tmap[:, 1]])
+    np.testing.assert_array_equal(xp[1, :len(smap)], smap[:, 1])
+    np.testing.assert_array_equal(xp[1, rows_src:rows_src + len(tmap)], tmap[:, 1])
+    np.testing.assert_array_equal(yp[:len(tmap)], y.reshape(-1, 20)[tmap[:, 0], tmap[:, 1]])
+    assert (xp[0, len(smap):rows_src] < 0).all() and (xp[0, rows_src + len(tmap):] < 0).all() and (yp[len(tmap):] == -1).all()
+    assert (np.diff(smap[:, 0]) >= 0).all() and (x[x >= 0].size == len(smap) + len(tmap))
 
 
 def test_forward_backward_reject_bad_arguments_before_launch():

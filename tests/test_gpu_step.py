@@ -127,12 +127,21 @@ TOL_F32_TENSOR = 1e-3    # fp32 results of fp32 accumulation over up to ~1e6 bf1
 
 def check_layers(c, got):
     """Teacher-forced parity of every op of the local model, forward and backward."""
-    ops, tensors = c.model.graph(c.batch)
+    packed = hasattr(c, "read_tensor")   # gpu_util.PackedCase: tensors come back in the padded form, padding rows zero
+    ops, tensors = c.graph() if packed else c.model.graph(c.batch)
     P = c.per_tensor(c.th.astype(np.float64))
     G = c.per_tensor(got["grad"])
     names = [n for n, _, _, _ in c.ref_arch.params]
     f32 = c.dtype == c.B.CD_F32
     tol_t = 2e-5 if f32 else TOL_BF16_TENSOR
+
+    def rel_rows(t, a, b):
+        """rel(a, b) over the rows of tensor t that exist (a packed batch has no padding rows: the oracle's values there
+        have no counterpart)"""
+        if not packed:
+            return rel(a, b)
+        keep = c.valid_rows(tensors[t]["stream"]).reshape(-1)
+        return rel(np.asarray(a).reshape(keep.size, -1)[keep], np.asarray(b).reshape(keep.size, -1)[keep])
 
     def shape(t):
         return (c.batch, tensors[t]["h"], tensors[t]["w"], tensors[t]["c"])
@@ -144,9 +153,15 @@ def check_layers(c, got):
     def act(t):
         if t in unwritten:
             return unwritten[t]
-        return c.x.astype(np.float64) if t == 0 else c.read(tensors[t]["act_offset"], shape(t))
+        if t == 0:
+            return c.x.astype(np.float64)
+        if packed:
+            return c.read_tensor(tensors[t], "act_offset", shape(t))
+        return c.read(tensors[t]["act_offset"], shape(t))
 
     def grad(t):
+        if packed:
+            return c.read_tensor(tensors[t], "grad_offset", shape(t))
         return c.read(tensors[t]["grad_offset"], shape(t))
 
     logits_t = ops[-1]["y"]
@@ -209,7 +224,7 @@ def check_layers(c, got):
             yr = L.conv2d_forward(x, w, b, o["stride"], o["pad"])
             if o["relu"]:
                 yr = L.relu_forward(yr)
-            note("act", rel(y, yr), tag, tol_t)
+            note("act", rel_rows(o["y"], y, yr), tag, tol_t)
             if frozen:
                 continue
             if o["relu"]:
@@ -222,7 +237,7 @@ def check_layers(c, got):
         elif o["kind"] == "embed":
             tok = c.x[:, o["k"]:o["k"] + o["stride"]]
             yr = L.embed_forward(tok, w).reshape(y.shape)
-            note("act", rel(y, yr), tag, tol_t)
+            note("act", rel_rows(o["y"], y, yr), tag, tol_t)
             pgrad(o, L.embed_backward(tok, w.shape, dy), tag, TOL_F32_TENSOR)
         elif o["kind"] == "attn":
             d = y.shape[-1]
@@ -232,7 +247,7 @@ def check_layers(c, got):
             q, kk, v = x2[:, qc:qc + d], kv2[:, kc:kc + d], kv2[:, vc:vc + d]
             klen = L.sentence_lengths(c.x[:, o["key_tok0"]:o["key_tok0"] + kv.shape[1]])
             yr, Pm = L.attention_forward(q, kk, v, c.batch, o["k"], bool(o["stride"]), klen)
-            note("act", rel(y.reshape(-1, d), yr), tag, tol_t)
+            note("act", rel_rows(o["y"], y.reshape(-1, d), yr), tag, tol_t)
             dq, dk, dv = L.attention_backward(q, kk, v, Pm, dy.reshape(-1, d), c.batch, o["k"])
             gx, gkv = np.zeros_like(x2), np.zeros_like(kv2)
             gx[:, qc:qc + d] = dq
@@ -280,11 +295,16 @@ def check_layers(c, got):
         elif o["kind"] == "layernorm":
             s = x + act(o["res"]) if o["res"] >= 0 else x
             yr, cache = L.layernorm_forward(s, w, b)
-            stats = c.read(o["stats_offset"], (c.batch * x.shape[1] * x.shape[2], 2), f32=True)
-            mean = s.mean(axis=-1).reshape(-1)
+            mean, rstd = s.mean(axis=-1).reshape(-1), cache[1].reshape(-1)
+            if packed:   # the rows that exist
+                stats = c.read_rows(tensors[o["x"]], o["stats_offset"], 2)
+                keep = c.valid_rows(tensors[o["x"]]["stream"]).reshape(-1)
+                stats, mean, rstd = stats[keep], mean[keep], rstd[keep]
+            else:
+                stats = c.read(o["stats_offset"], (c.batch * x.shape[1] * x.shape[2], 2), f32=True)
             note("stats", float(np.abs(stats[:, 0] - mean).max() / np.sqrt((s ** 2).mean())), tag + ".mean", 1e-5)
-            note("stats", rel(stats[:, 1], cache[1].reshape(-1)), tag + ".rstd", 1e-4)
-            note("act", rel(y, yr), tag, tol_t)
+            note("stats", rel(stats[:, 1], rstd), tag + ".rstd", 1e-4)
+            note("act", rel_rows(o["y"], y, yr), tag, tol_t)
             dx, dg, db = L.layernorm_backward(dy, w, cache)
             note("pgrad", rel(G[names[o["param_w"]]], dg), tag + ".gamma", TOL_F32_TENSOR)
             note("pgrad", rel(G[names[o["param_b"]]], db), tag + ".beta", TOL_F32_TENSOR)
@@ -293,7 +313,7 @@ def check_layers(c, got):
                 contribute(o["res"], dx)
         elif o["kind"] == "linear":
             x2 = x.reshape(-1, x.shape[-1]) if x.shape[1] * x.shape[2] > 1 else x.reshape(c.batch, -1)
-            note("act", rel(y, L.linear_forward(x2, w, b)), tag, 2e-5 if f32 else 1e-4)
+            note("act", rel_rows(o["y"], y, L.linear_forward(x2, w, b)), tag, 2e-5 if f32 else 1e-4)
             dx, dw, db = L.linear_backward(x2, w, dy, b is not None)
             # the bf16 model's dense-layer backward runs on the MFMA kernels from a bf16 copy of d loss / d logits
             pgrad(o, dw, tag, TOL_F32_TENSOR if f32 else TOL_BF16_TENSOR)

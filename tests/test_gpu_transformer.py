@@ -5,7 +5,7 @@ import pytest
 
 from oracle import nets
 from paper_2010_02838_amd import synth
-from gpu_util import Case, rel
+from gpu_util import Case, PackedCase, rel
 from test_gpu_step import check_layers, compare_bf16
 
 pytestmark = pytest.mark.gpu
@@ -45,6 +45,45 @@ def test_transformer_padded_sentences_bf16_layers(name):
     assert np.all(got["dz"][c.y < 0] == 0)
 
 
+def make_packed(name, multiple=16, slack_sentences=3):
+    """The ragged batch of make(name, ragged=True), handed to the library without its padding."""
+    S, Ts, Tt, d, heads, ff, vocab, ne, nd = CASES[name]
+    return PackedCase(make(name, ragged=True), dict(kind=4, widths=[d, ff, heads], blocks=[ne, nd]), Ts, Tt,
+                      multiple=multiple, slack_sentences=slack_sentences)
+
+
+@pytest.mark.parametrize("name,multiple,slack", [("small", 16, 3), ("long", 128, 0), ("mid", 1, 1), ("wide", 8, 2)])
+def test_transformer_packed_sentences_bf16_layers(name, multiple, slack):
+    """Sentences of different lengths one after the other, no padding rows (cd_arch_desc.max_sentences): every op against
+    the oracle's layer functions on the padded form of the same batch, forward and backward, on the rows that exist.
+    Stream capacities with unused rows behind the last sentence (a multiple of 16 / 128), without any (multiple 1), as
+    many sentences as the model allows (slack 0), sentences longer than one 128-row attention tile ("long")."""
+    c = make_packed(name, multiple, slack)
+    got = c.gpu(alpha=0.5, label_smoothing=0.1)
+    check_layers(c, got)
+    # the rows behind the last sentence take no loss gradient, and what the attention kernels leave there is zero
+    assert np.all(c.runner.dz.cpu().numpy()[len(c.tgt_map):] == 0)
+
+
+def test_transformer_packed_sentences_bf16_step():
+    c = make_packed("small")
+    kw = dict(alpha=0.5, label_smoothing=0.1)
+    compare_bf16(c, c.oracle(**kw), c.oracle(bf16_storage=True, **kw), c.gpu(**kw), label="transformer_small_packed")
+
+
+def test_packed_and_padded_forms_agree():
+    """The same sentences in both forms: equal losses and gradients up to the rounding order of the sums over rows."""
+    c = make_packed("mid")
+    kw = dict(alpha=0.5, label_smoothing=0.1)
+    a, b = c.gpu(**kw), c.c0.gpu(**kw)
+    np.testing.assert_allclose(a["loss"], b["loss"], rtol=1e-4)
+    keep = c.valid_rows(1).reshape(-1)
+    assert rel(a["logits"][keep], b["logits"][keep].astype(np.float64)) <= 1e-5
+    Ga, Gb = c.per_tensor(a["grad"]), c.per_tensor(b["grad"])
+    for n in Gb:
+        assert rel(Ga[n], Gb[n].astype(np.float64)) <= 2e-3, n
+
+
 def test_transformer_padded_sentences_bf16_step():
     c = make("small", ragged=True)
     kw = dict(alpha=0.5, label_smoothing=0.1)
@@ -75,6 +114,23 @@ def test_transformer_base_size_layers():
     S, Ts, Tt = 64, 128, 128
     ref = nets.transformer(S, Ts, Tt)
     c = Case(dict(kind=4), ref, "bf16", S, 0, 32768, jitter=0.1, tokens=(Ts, Tt))
+    got = c.gpu(alpha=1.0, label_smoothing=0.1)
+    assert np.isfinite(got["loss"]).all() and got["loss"][2] > 0
+    check_layers(c, got)
+
+
+@pytest.mark.timeout(1500)
+def test_transformer_base_size_packed_layers():
+    """The default benchmark batch (base model, sentence pairs with lengths uniform in [16, 128] up to 8192 target
+    tokens, packed, rows of each stream a multiple of 128, as many sentences as the model allows, the two-stream launch
+    configuration): every op of the 12 layers teacher-forced against the oracle on the padded form, all rows that exist."""
+    Ts = Tt = 128
+    x, y, sl, tl = synth.sentence_pairs(8192, 16, 128, 32768, seed=100)
+    S = x.shape[0]
+    c0 = Case(dict(kind=4), nets.transformer(S, Ts, Tt), "bf16", S, 0, 32768, jitter=0.1, tokens=(Ts, Tt))
+    c0.x, c0.y = x, y
+    c = PackedCase(c0, dict(kind=4), Ts, Tt, multiple=128, slack_sentences=0)
+    assert len(c.tgt_map) == tl.sum() >= 8192 and c.rows_tgt < S * Tt * 0.65
     got = c.gpu(alpha=1.0, label_smoothing=0.1)
     assert np.isfinite(got["loss"]).all() and got["loss"][2] > 0
     check_layers(c, got)
