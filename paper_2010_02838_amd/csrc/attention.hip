@@ -515,7 +515,7 @@ __global__ void __launch_bounds__(256) attn_fwd_mfma_k(AttArgs a) {
 // key of the sentence (exactly what a vanishing sum allows), so that the rounding errors multiply the keys'
 // differences and not their common part.
 template <int DH>
-__global__ void __launch_bounds__(256) attn_bwd_dq_mfma_k(AttArgs a) {
+__global__ void __launch_bounds__(256, 2) attn_bwd_dq_mfma_k(AttArgs a) {
   constexpr int KS = DH / 16, DT = DH / 32;
   __shared__ __attribute__((aligned(16))) bf16_t Ks[MF_KC * MF_PITCH];
   __shared__ __attribute__((aligned(16))) bf16_t Vs[MF_KC * MF_PITCH];
@@ -628,7 +628,7 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_mfma_k(AttArgs a) {
 // dP = dO V^T (queries on the registers), then dV^T += dO^T P and dK^T += Q^T dS with P, dS rounded to bf16
 // and Q, dO read from transposed LDS copies.
 template <int DH>
-__global__ void __launch_bounds__(256) attn_bwd_dkv_mfma_k(AttArgs a) {
+__global__ void __launch_bounds__(256, 2) attn_bwd_dkv_mfma_k(AttArgs a) {
   constexpr int KS = DH / 16, DT = DH / 32;
   __shared__ __attribute__((aligned(16))) bf16_t Qs[MF_KC * MF_PITCH];
   __shared__ __attribute__((aligned(16))) bf16_t Gs[MF_KC * MF_PITCH];
