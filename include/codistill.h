@@ -41,7 +41,8 @@
  *     results agree; see the tests): CODISTILL_SERIAL, CODISTILL_FORCE_SIMPLE
  *     (plain one-thread-per-output kernels instead of the MFMA ones),
  *     CODISTILL_NO_POOL_FUSION, CODISTILL_WRITE_RESIDUAL_GRADS,
- *     CODISTILL_SEPARATE_RELU_MASK, CODISTILL_PLAIN_ATTENTION.
+ *     CODISTILL_SEPARATE_RELU_MASK, CODISTILL_SEPARATE_BN_REDUCTION,
+ *     CODISTILL_PLAIN_ATTENTION.
  *   - Layouts: activations NHWC, filters [Cout][kh][kw][Cin], linear weights
  *     [out][in], logits row-major [rows][cols].  bf16 is the upper half of an
  *     IEEE float32, round-to-nearest-even.

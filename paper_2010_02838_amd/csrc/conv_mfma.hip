@@ -52,6 +52,13 @@ struct IgemmArgs {
   uint32_t src_bytes, wt_bytes;
   const bf16_t* bias;  // per-column bias added to the output (kernels with EPI >= 1)
   float* stat_partials;  // STATS kernels: [m-tiles][stat_pitch(N)] per-tile column sums and sums of squares
+  // STATS == 2 (a data gradient that completes the gradient of a BatchNorm's output): the sums that BatchNorm's
+  // backward pass reduces over the rows, taken from the values as they are stored: dz = the output, gated by the
+  // BatchNorm's ReLU bit mask (bn_mask, nullable: no ReLU), and dz * xhat with xhat = (bn_x - mean) * invstd,
+  // bn_x [M][N] the BatchNorm's input, bn_stats = [mean[N] | invstd[N]].  Written to stat_partials like the forward sums.
+  const bf16_t* bn_x = nullptr;
+  const uint8_t* bn_mask = nullptr;
+  const float* bn_stats = nullptr;
 };
 
 int g_tune_tile = 0, g_tune_co = -1;  // tuning knobs of the microbenchmark
@@ -143,17 +150,21 @@ __device__ inline int lds_off(int row, int cv) { return row * BK + ((cv ^ ((row 
 // compiler does not track them, so it cannot serialise them against the LDS reads.
 // F32OUT: the output is fp32 [M][N] (dense layers that produce logits); like the bf16 output it is
 // transposed through LDS so that a store instruction writes whole 256-byte row segments.
-// STATS: the epilogue also emits, per m-tile, the column sums and sums of squares of the bf16 values
+// STATS 1: the epilogue also emits, per m-tile, the column sums and sums of squares of the bf16 values
 // it writes (taken from the staged rows with transposing LDS reads and two MFMAs per fragment): the
 // BatchNorm that follows a convolution gets its batch statistics without re-reading the tensor.
+// STATS 2 (data gradients): per m-tile, the column sums of dz and dz * xhat that the backward pass of the BatchNorm
+// whose output gradient this launch completes would otherwise reduce from memory (see IgemmArgs::bn_x).
 // NWRAP: 1 when the gathered tensor has at least 32 channels (a 32-element step crosses at most one
 // tap boundary), 4 for 8..31 channels.
 // REMAP: output rows are placed with the strided row map of IgemmArgs (parity class of a stride-2 dgrad).
 // EPI: 0 plain output, 1 per-column bias added, 2 bias and ReLU.  GROUP: grouped tile order (wide outputs).
 // Both are compile-time: the plain kernels pay nothing for them.
-template <int MODE, int BM, int BN, int WAVES_M, int WAVES_N, bool F32OUT = false, bool STATS = false, int NWRAP = 1,
+template <int MODE, int BM, int BN, int WAVES_M, int WAVES_N, bool F32OUT = false, int STATS = 0, int NWRAP = 1,
           bool REMAP = false, int EPI = 0, bool GROUP = false>
-__global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
+__global__ void __launch_bounds__(256, ((BM / WAVES_M / 32) * (BN / WAVES_N / 32) >= 8 ? 2 : 1)) igemm_kernel(IgemmArgs a) {
+  // (tiles whose accumulators take 128 registers: two waves per SIMD, i.e. two workgroups per compute unit, is what their
+  // LDS allows; the bound keeps the other registers within the 128 that leaves)
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   constexpr int TM = WM / 32, TN = WN / 32;
   constexpr int AV = BM / 64;                  // activation vectors per thread per step
@@ -284,6 +295,28 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
     }
   };
 
+  // STATS 2: what the epilogue reads besides the tile itself (the BatchNorm's input and its ReLU bits at this lane's
+  // output vectors) is requested now and arrives during the main loop.  (Vector memory operations retire in order:
+  // the main loop's first wait also waits for these, and the compiler's own waits for them can only be too strict.)
+  constexpr int BS_LPR = WN / 8, BS_RPP = 64 / BS_LPR, BS_EROWS = WM < 64 ? WM : 64;
+  constexpr int BS_NV = STATS == 2 ? (WM / BS_EROWS) * (BS_EROWS / BS_RPP) : 1;
+  uint4 bs_x[BS_NV];
+  uint32_t bs_bits[BS_NV];
+  if (STATS == 2) {
+    const int er_ = lane / BS_LPR, n = n0 + wn0 + (lane % BS_LPR) * 8;
+#pragma unroll
+    for (int v = 0; v < BS_NV; v++) {
+      const int pass = v / (BS_EROWS / BS_RPP), pp = v % (BS_EROWS / BS_RPP);
+      const int m = m0 + wm0 + pass * BS_EROWS + pp * BS_RPP + er_;
+      bs_x[v] = make_uint4(0, 0, 0, 0);
+      bs_bits[v] = 0u;
+      if (m < M && n < a.N) {
+        const unsigned idx = (unsigned)m * (unsigned)a.N + (unsigned)n;
+        bs_x[v] = *reinterpret_cast<const uint4*>(a.bn_x + idx);
+        bs_bits[v] = a.bn_mask ? a.bn_mask[idx >> 3] : 0xffu;
+      }
+    }
+  }
   f32x16_t acc[TN][TM];
 #pragma unroll
   for (int i = 0; i < TN; i++)
@@ -402,7 +435,15 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
   constexpr int TPG = EROWS / 32;    // 32-row tiles per staging pass
   const int er = lane / LPR, ec = (lane % LPR) * 8;
   // STATS: per-wave column sums [WAVES_M][2][BN], behind the staging rows
-  static_assert(!STATS || EPI_BYTES + WAVES_M * 2 * BN * 4 <= SMEM, "no room for the column sums behind the staging rows");
+  static_assert(STATS == 0 || EPI_BYTES + WAVES_M * 2 * BN * 4 <= SMEM, "no room for the column sums behind the staging rows");
+  static_assert(STATS != 2 || !REMAP, "the backward sums are taken where the rows are stored in order");
+  // STATS 2: running sums of dz and of dz * x over this lane's 8 channels (the same in every pass); the mean and the
+  // scale of xhat = (x - mean) * invstd are applied to the tile's sums at the end (the sums are linear in x)
+  float bs0[8], bs1[8];
+  if (STATS == 2) {
+#pragma unroll
+    for (int k = 0; k < 8; k++) { bs0[k] = 0.f; bs1[k] = 0.f; }
+  }
   float* red = reinterpret_cast<float*>(smem + EPI_BYTES);
   __syncthreads();  // the main loop's tiles are no longer read: the staging rows alias them
 #pragma unroll
@@ -422,7 +463,7 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
           *reinterpret_cast<uint2*>(stage + (j * 32 + frow) * EPITCH + i * 32 + 8 * g + 4 * (lane >> 5)) = p;
         }
     __builtin_amdgcn_wave_barrier();
-    if (STATS) {
+    if (STATS == 1) {
       // Column sums and sums of squares of the staged (rounded) rows on the matrix cores, which idle in
       // the epilogue: the transposing LDS read hands a lane 8 pixels of its column (16 pixels x 32
       // columns per fragment, the operand layout of wgrad_kernel); ones^T Y gives the sums in every row
@@ -499,7 +540,40 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
             vv[q] &= ((int16_t)(yy[q] & 0xffffu) > 0 ? 0x0000ffffu : 0u) | ((int16_t)(yy[q] >> 16) > 0 ? 0xffff0000u : 0u);
           v = make_uint4(vv[0], vv[1], vv[2], vv[3]);
         }
+        if (STATS == 2) {   // the stored values feed the sums of the BatchNorm's backward pass
+          const uint4 xr = bs_x[(g0 / TPG) * (EROWS / RPP) + p];
+          const uint32_t bits = bs_bits[(g0 / TPG) * (EROWS / RPP) + p];
+          const uint32_t gv[4] = {v.x, v.y, v.z, v.w}, xv[4] = {xr.x, xr.y, xr.z, xr.w};
+#pragma unroll
+          for (int q = 0; q < 4; q++) {
+            const float d0 = (bits >> (2 * q)) & 1u ? __uint_as_float(gv[q] << 16) : 0.f;
+            const float d1 = (bits >> (2 * q + 1)) & 1u ? __uint_as_float(gv[q] & 0xffff0000u) : 0.f;
+            bs0[2 * q] += d0;
+            bs0[2 * q + 1] += d1;
+            bs1[2 * q] += d0 * __uint_as_float(xv[q] << 16);
+            bs1[2 * q + 1] += d1 * __uint_as_float(xv[q] & 0xffff0000u);
+          }
+        }
         *reinterpret_cast<uint4*>(dp) = v;
+      }
+    }
+  }
+  if (STATS == 2) {
+    // lanes that share their 8 channels (one per row of a pass) add up, the first of them hands the wave's sums over
+#pragma unroll
+    for (int k = 0; k < 8; k++) {
+#pragma unroll
+      for (int off = LPR; off < 64; off <<= 1) {
+        bs0[k] += __shfl_xor(bs0[k], off, 64);
+        bs1[k] += __shfl_xor(bs1[k], off, 64);
+      }
+    }
+    if (lane < LPR) {
+      const int wmi = wave % WAVES_M;
+#pragma unroll
+      for (int k = 0; k < 8; k++) {
+        red[(wmi * 2 + 0) * BN + wn0 + ec + k] = bs0[k];
+        red[(wmi * 2 + 1) * BN + wn0 + ec + k] = bs1[k];
       }
     }
   }
@@ -510,6 +584,7 @@ __global__ void __launch_bounds__(256) igemm_kernel(IgemmArgs a) {
       float s0 = 0.f, s1 = 0.f;
 #pragma unroll
       for (int w = 0; w < WAVES_M; w++) { s0 += red[(w * 2 + 0) * BN + tid]; s1 += red[(w * 2 + 1) * BN + tid]; }
+      if (STATS == 2) s1 = (s1 - a.bn_stats[n0 + tid] * s0) * a.bn_stats[a.N + n0 + tid];   // sum dz x -> sum dz xhat
       const int64_t mt = tm;
       a.stat_partials[mt * stat_pitch(a.N) + n0 + tid] = s0;
       a.stat_partials[mt * stat_pitch(a.N) + a.N + n0 + tid] = s1;
@@ -545,7 +620,7 @@ int conv_fprop_tile_class(const ConvGeom& g, bool bias) {
 }
 
 // returns the number of m-tiles (= statistics chunks when STATS)
-template <int MODE, bool STATS, int NWRAP, bool REMAP, int EPI>
+template <int MODE, int STATS, int NWRAP, bool REMAP, int EPI>
 static int launch_igemm_w(IgemmArgs a, hipStream_t s) {
   a.pointwise = (a.kh == 1 && a.kw == 1 && a.stride == 1 && a.pad == 0 && a.pad_w == 0 && a.Hs == a.Hd &&
                  a.Ws == a.Wd) ? 1 : 0;
@@ -590,7 +665,7 @@ static int launch_igemm_w(IgemmArgs a, hipStream_t s) {
                        0, s, a);
   return mt;
 }
-template <int MODE, bool STATS, bool REMAP = false, int EPI = 0>
+template <int MODE, int STATS, bool REMAP = false, int EPI = 0>
 static int launch_igemm(IgemmArgs a, hipStream_t s) {
   return a.Cs >= BK ? launch_igemm_w<MODE, STATS, 1, REMAP, EPI>(a, s) : launch_igemm_w<MODE, STATS, 4, REMAP, EPI>(a, s);
 }
@@ -668,8 +743,9 @@ __global__ void __launch_bounds__(256) fill_zero16_k(uint4* p, int64_t n) {
   if (i < n) p[i] = make_uint4(0, 0, 0, 0);
 }
 
-void conv_dgrad_mfma(const bf16_t* dy, const bf16_t* w, bf16_t* wt, bf16_t* dx, const ConvGeom& g, bool accumulate,
-                     hipStream_t s, const bf16_t* addend, const uint8_t* addend_gate, const bf16_t* relu_out) {
+int conv_dgrad_mfma(const bf16_t* dy, const bf16_t* w, bf16_t* wt, bf16_t* dx, const ConvGeom& g, bool accumulate,
+                    hipStream_t s, const bf16_t* addend, const uint8_t* addend_gate, const bf16_t* relu_out,
+                    const BnBackwardSums* bn) {
   IgemmArgs a;
   a.bias = nullptr;
   a.stat_partials = nullptr;
@@ -691,8 +767,12 @@ void conv_dgrad_mfma(const bf16_t* dy, const bf16_t* w, bf16_t* wt, bf16_t* dx, 
     a.addend_gate = addend_gate;
     a.relu_out = relu_out;      // stride 1 only, like the addend
     a.wt_bytes = (uint32_t)((int64_t)g.Cout * g.K() * 2);
-    launch_igemm<1, false>(a, s);
-    return;
+    if (bn) {
+      a.bn_x = bn->x; a.bn_mask = bn->mask; a.bn_stats = bn->stats; a.stat_partials = bn->partials;
+      return launch_igemm<1, 2>(a, s);
+    }
+    launch_igemm<1, 0>(a, s);
+    return 0;
   }
   // Stride 2: input pixel (h, w) receives dy[(h + pad - r)/2, (w + pad - s)/2] * w[., r, s, .] for the taps
   // of matching parity only.  Per parity class (h%2, w%2) that is a stride-1 gather over the half
@@ -729,8 +809,9 @@ void conv_dgrad_mfma(const bf16_t* dy, const bf16_t* w, bf16_t* wt, bf16_t* dx, 
       a.omul = 2; a.ooff_h = ph; a.ooff_w = pw;
       a.accumulate = accumulate ? 1 : 0;
       a.wt_bytes = (uint32_t)(wn * 2);
-      launch_igemm<0, false, true>(a, s);
+      launch_igemm<0, 0, true>(a, s);
     }
+  return 0;
 }
 
 // ---- grouped convolutions (Cin = Cout = C, groups of cg = C / groups channels) as sliced launches ----------------

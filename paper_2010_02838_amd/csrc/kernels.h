@@ -60,9 +60,12 @@ void bn_relu_pool_backward(const bf16_t* dpool, const uint8_t* argmax, const bf1
                            const uint8_t* relu_mask, int64_t B, int H, int W, int C, hipStream_t s);
 // dz = dy * (relu ? y > 0 : 1); dgamma = sum dz*xhat; dbeta = sum dz;
 // dx = gamma*invstd*(dz - dbeta/M - xhat*dgamma/M); dres = dz.  coef: [3][C] fp32 scratch.
+// pre_chunks > 0: the sums over the rows are already in partials, in pre_chunks chunks of stat_pitch(C) floats (left by
+// the data gradient that wrote dy: conv_dgrad_mfma with bn); the reduction pass over dy and x is then left out.
 void bn_backward(int dtype, const void* dy, const void* y, const void* x, const void* gamma, const float* stats,
                  bool relu, void* dx, bool acc_dx, void* dres, bool acc_dres, float* dgamma, float* dbeta,
-                 float* coef, float* partials, const uint8_t* relu_mask, int64_t M, int C, hipStream_t s);
+                 float* coef, float* partials, const uint8_t* relu_mask, int64_t M, int C, hipStream_t s,
+                 int pre_chunks = 0);
 
 // LayerNorm over the last axis of [rows][d] (biased variance, eps 1e-5) of a + r (r nullable):
 // y = gamma * xhat + beta.  stats: [rows][2] fp32 = mean, rstd (kept for the backward pass).
@@ -115,9 +118,14 @@ int conv_fprop_tile_class(const ConvGeom& g, bool bias);
 // with addend_gate (nullable, one bit per element of addend) dropping the elements whose bit is clear.
 // relu_out (nullable; stride 1 only): dx is the gradient behind a ReLU whose result is relu_out [B*H*W][Cin]; its
 // elements where relu_out is not positive are written as zero.
-void conv_dgrad_mfma(const bf16_t* dy, const bf16_t* w, bf16_t* wt, bf16_t* dx, const ConvGeom& g, bool accumulate,
-                     hipStream_t s, const bf16_t* addend = nullptr, const uint8_t* addend_gate = nullptr,
-                     const bf16_t* relu_out = nullptr);
+// bn (nullable; stride 1 only): dx completes the gradient of the output of a BatchNorm (input bn->x [B*H*W][Cin], batch
+// statistics bn->stats = [mean | invstd], ReLU bit mask bn->mask or NULL): the launch also leaves, per row tile, the
+// column sums of dz = dx gated by the mask and of dz * xhat in bn->partials, for bn_backward's pre_chunks.  Returns the
+// number of row tiles (the chunks of those sums), 0 without bn.
+struct BnBackwardSums { const bf16_t* x; const uint8_t* mask; const float* stats; float* partials; };
+int conv_dgrad_mfma(const bf16_t* dy, const bf16_t* w, bf16_t* wt, bf16_t* dx, const ConvGeom& g, bool accumulate,
+                    hipStream_t s, const bf16_t* addend = nullptr, const uint8_t* addend_gate = nullptr,
+                    const bf16_t* relu_out = nullptr, const BnBackwardSums* bn = nullptr);
 // dw[Cout][K] = dy[M][Cout]^T * im2col(x)[M][K], split over M with fp32 partials reduced in fixed order
 void conv_wgrad_mfma(const bf16_t* x, const bf16_t* dy, float* dw, const ConvGeom& g, float* partials,
                      size_t partials_bytes, hipStream_t s);

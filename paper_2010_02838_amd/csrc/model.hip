@@ -309,6 +309,14 @@ bool fuse_off() {
   return e && e[0] == '1';
 }
 
+// CODISTILL_SEPARATE_BN_REDUCTION=1 keeps the reduction pass of every BatchNorm's backward pass (debugging aid): without
+// it, the data-gradient kernel that completes the gradient of a BatchNorm's output also takes that BatchNorm's column
+// sums (dz and dz * xhat) from the values it stores
+bool separate_bn_reduction() {
+  const char* e = getenv("CODISTILL_SEPARATE_BN_REDUCTION");
+  return e && e[0] == '1';
+}
+
 // CODISTILL_SERIAL=1 keeps every launch of a call on the caller's stream (debugging aid)
 bool force_serial() {
   const char* e = getenv("CODISTILL_SERIAL");
@@ -1041,6 +1049,9 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
   // Tensors that are the ReLU'd output of a convolution and have one reader, itself a stride-1 convolution on the
   // matrix-core path: that reader's data-gradient kernel applies the ReLU mask as it writes the tensor's gradient,
   // and the producing convolution's own masking pass is dropped.
+  // tensor -> chunks of BatchNorm backward sums that the data gradient which completed its gradient left in the partials
+  // area (0: none): the BatchNorm that produced the tensor, the op right in front of that convolution, skips its reduction
+  std::vector<int> bn_sums(m->tensors.size(), 0);
   std::vector<int> producer(m->tensors.size(), -1), readers(m->tensors.size(), 0);
   for (size_t j = 0; j < m->ops.size(); j++) {
     producer[m->ops[j].y] = (int)j;
@@ -1163,8 +1174,10 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
         }
         const double per_elt = m->esize() * (5 + (dres ? 1 : 0)) + (gated ? (mask ? 0.25 : 2.0 * m->esize()) : 0.0);
         ProfScope pr(CD_K_NORM, c.s, 0, (double)M * tx.c * per_elt);
+        // (sums left by the data gradient that wrote dy: only ever set for this op's own, ungated-route dy)
+        const int pre = dy_in == dy ? bn_sums[o.y] : 0;
         bn_backward(dt, dy_in, c.act(o.y), in, c.P(o.pw), c.stats(o), gated, dx, acc, dres, acc_res, G(o.pw), G(o.pb),
-                    c.coef(), c.partials(), mask, M, tx.c, c.s);
+                    c.coef(), c.partials(), mask, M, tx.c, c.s, pre);
         if (o.res >= 0 && !defer) written[o.res] = 1;
         break;
       }
@@ -1275,9 +1288,27 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
             const int pi = producer[o.x];
             const bool gate = g.stride == 1 && !acc && readers[o.x] == 1 && pi >= 0 && m->ops[pi].kind == OP_CONV &&
                               m->ops[pi].relu && use_mfma(m, conv_geom(m, m->ops[pi], batch)) && !fuse_off();
-            conv_dgrad_mfma(static_cast<const bf16_t*>(dy), static_cast<const bf16_t*>(c.P(o.pw)), c.wpack(),
-                            static_cast<bf16_t*>(dx), g, acc, c.s, static_cast<const bf16_t*>(df.src), df.gate,
-                            gate ? static_cast<const bf16_t*>(c.act(o.x)) : nullptr);
+            // The op right in front of this convolution is the BatchNorm that produced its input: every other reader of
+            // that tensor comes later in the graph and has added its share already, so this launch completes the
+            // tensor's gradient and can hand the BatchNorm the column sums of its backward pass (stride 1: one launch
+            // writes every row; the BatchNorm's next op in this pass is its own backward, which consumes them).
+            BnBackwardSums sums = {};
+            bool with_sums = false;
+            if (pi == (int)i - 1 && m->ops[pi].kind == OP_BN && g.stride == 1 && !separate_bn_reduction() &&
+                !pool_fused(m, pi) && m->ops[pi].x != 0 && (!m->ops[pi].relu || c.plan.aux[pi] != 0) &&
+                (size_t)(batch * g.H * g.W / 128 + 1 + 32) * stat_pitch(g.Cin) * sizeof(float) <= c.plan.partials_bytes) {
+              const Op& b = m->ops[pi];
+              sums.x = static_cast<const bf16_t*>(c.act(b.x));
+              sums.mask = b.relu ? reinterpret_cast<const uint8_t*>(c.ws + c.plan.aux[pi]) : nullptr;
+              sums.stats = c.stats(b);
+              sums.partials = c.partials();
+              with_sums = true;
+            }
+            const int chunks = conv_dgrad_mfma(static_cast<const bf16_t*>(dy), static_cast<const bf16_t*>(c.P(o.pw)), c.wpack(),
+                                               static_cast<bf16_t*>(dx), g, acc, c.s, static_cast<const bf16_t*>(df.src), df.gate,
+                                               gate ? static_cast<const bf16_t*>(c.act(o.x)) : nullptr,
+                                               with_sums ? &sums : nullptr);
+            if (with_sums) bn_sums[o.x] = chunks;
             if (gate) relu_done[o.x] = 1;
           } else {
             conv_dgrad_simple(dt, dy, c.P(o.pw), dx, g, acc, c.s);

@@ -656,13 +656,23 @@ static void bn_apply_t(const T* x, const T* res, bool relu, T* y, int64_t M, int
 template <typename T>
 static void bn_backward_t(const T* dy, const T* y, const T* x, const T* gamma, const float* stats, bool relu, T* dx,
                           bool acc_dx, T* dres, bool acc_dres, float* dgamma, float* dbeta, float* coef,
-                          float* partials, const uint8_t* mask, int64_t M, int C, hipStream_t s) {
+                          float* partials, const uint8_t* mask, int64_t M, int C, hipStream_t s, int pre_chunks) {
   int vec = pick_vec<T>(C, dy, y, x, dx);
   if (!aligned16(dres)) vec = 1;
   constexpr int V = sizeof(T) == 2 ? 8 : 4;
-  ReducePlan p = vec > 1 ? launch_reduce<T, V, 1>(dy, y, x, stats, relu, M, C, partials, s, mask)
-                         : launch_reduce<T, 1, 1>(dy, y, x, stats, relu, M, C, partials, s);
-  hipLaunchKernelGGL((col_finalize_k<T, 1>), dim3((unsigned)cdiv(C, 64)), dim3(1024), 0, s, partials, p.chunks, M, C,
+  int chunks = pre_chunks;
+  const float* src = partials;
+  if (pre_chunks == 0) {
+    ReducePlan p = vec > 1 ? launch_reduce<T, V, 1>(dy, y, x, stats, relu, M, C, partials, s, mask)
+                           : launch_reduce<T, 1, 1>(dy, y, x, stats, relu, M, C, partials, s);
+    chunks = p.chunks;
+  } else if (pre_chunks > 256) {   // the sums came per row tile of the data gradient that wrote dy: fold them first
+    float* scratch = partials + (size_t)pre_chunks * stat_pitch(C);
+    hipLaunchKernelGGL(col_fold_k, dim3((unsigned)cdiv(C, 64), 32), dim3(1024), 0, s, partials, pre_chunks, C, scratch);
+    chunks = 32;
+    src = scratch;
+  }
+  hipLaunchKernelGGL((col_finalize_k<T, 1>), dim3((unsigned)cdiv(C, 64)), dim3(1024), 0, s, src, chunks, M, C,
                      gamma, (const T*)nullptr, const_cast<float*>(stats), dgamma, dbeta, coef);
   const int64_t nvec = M * C / vec;
   bool fixc;
@@ -766,13 +776,14 @@ void bn_apply(int dtype, const void* x, const void* res, bool relu, void* y, int
 }
 void bn_backward(int dtype, const void* dy, const void* y, const void* x, const void* gamma, const float* stats,
                  bool relu, void* dx, bool acc_dx, void* dres, bool acc_dres, float* dgamma, float* dbeta, float* coef,
-                 float* partials, const uint8_t* relu_mask, int64_t M, int C, hipStream_t s) {
+                 float* partials, const uint8_t* relu_mask, int64_t M, int C, hipStream_t s, int pre_chunks) {
   if (dtype == CD_BF16)
     bn_backward_t<bf16_t>((const bf16_t*)dy, (const bf16_t*)y, (const bf16_t*)x, (const bf16_t*)gamma, stats, relu,
-                          (bf16_t*)dx, acc_dx, (bf16_t*)dres, acc_dres, dgamma, dbeta, coef, partials, relu_mask, M, C, s);
+                          (bf16_t*)dx, acc_dx, (bf16_t*)dres, acc_dres, dgamma, dbeta, coef, partials, relu_mask, M, C, s,
+                          pre_chunks);
   else
     bn_backward_t<float>((const float*)dy, (const float*)y, (const float*)x, (const float*)gamma, stats, relu,
-                         (float*)dx, acc_dx, (float*)dres, acc_dres, dgamma, dbeta, coef, partials, nullptr, M, C, s);
+                         (float*)dx, acc_dx, (float*)dres, acc_dres, dgamma, dbeta, coef, partials, nullptr, M, C, s, 0);
 }
 void colsum(int dtype, const void* a, int64_t M, int C, float* out, float* partials, hipStream_t s) {
   if (dtype == CD_BF16) colsum_t<bf16_t>((const bf16_t*)a, M, C, out, partials, s);

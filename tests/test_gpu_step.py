@@ -643,6 +643,24 @@ def test_serial_switch_is_bit_identical(monkeypatch):
         np.testing.assert_array_equal(a[k], b[k])
 
 
+def test_separate_bn_reduction_switch_agrees(monkeypatch):
+    """By default the data-gradient kernel that completes the gradient of a BatchNorm's output also takes the column sums
+    of that BatchNorm's backward pass from the values it stores; CODISTILL_SEPARATE_BN_REDUCTION=1 keeps the reduction
+    pass over dy and x instead.  Same stored tensors, same sums up to the order of the additions: the logits are
+    identical, the gradients agree to fp32 rounding, and both forms meet the per-layer tolerances against the oracle."""
+    kw, mk, batch, res, classes = SMALL["bottleneck_mfma"]
+    a = Case(kw, mk(), "bf16", batch, res, classes).gpu()
+    monkeypatch.setenv("CODISTILL_SEPARATE_BN_REDUCTION", "1")
+    c = Case(kw, mk(), "bf16", batch, res, classes)
+    b = c.gpu()
+    check_layers(c, b)
+    np.testing.assert_array_equal(a["logits"], b["logits"])
+    assert not np.array_equal(a["grad"], b["grad"])        # the switch does select another path
+    Ga, Gb = c.per_tensor(a["grad"]), c.per_tensor(b["grad"])
+    for n in Gb:
+        assert rel(Ga[n], Gb[n].astype(np.float64)) <= 5e-3, n   # bf16 activation gradients differ by single roundings
+
+
 def test_plain_kernels_switch_bf16_layers(monkeypatch):
     """CODISTILL_FORCE_SIMPLE=1 routes every convolution of a bf16 model to the plain one-thread-per-output kernels:
     they meet the same per-layer tolerances against the oracle as the MFMA kernels they stand in for."""
