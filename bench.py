@@ -10,7 +10,7 @@ Prints ONE JSON line.  `roofline` is for the kernel that takes the most time of 
 bn_apply_k<bf16,8,true> (the elementwise pass of every BatchNorm forward, both models):
 HBM-bound, algorithmic bytes (input, residual, output and ReLU bit mask, each once) over
 the HIP-event time of its launches.  `roofline_conv` is the same for the convolution kernel
-that takes the most time, igemm_kernel<0,128,256,2,2,false,true,1,false,0,false> (bf16 MFMA
+that takes the most time, igemm_kernel<0,128,256,2,2,false,1,1,false,0,false> (bf16 MFMA
 implicit GEMM, forward, 128x256 tiles): its arithmetic intensity decides which roof bounds
 it, and its fraction of the MFMA peak is given either way.  Both are measured in a second
 pass of the same steps with the library's per-launch event timer (events on the launch
@@ -35,11 +35,11 @@ PEAK_HBM_GBS = 8000.0
 # --copy-calibration).  Valid only for the kernels the counters were taken on: set to None when one changes.
 TRAFFIC_SOURCE = "profiles/resnet50_bs256_step_hbm_counters.md"
 ROOFLINE_TRAFFIC_BYTES = 260.2e6        # bn_apply_k<bf16,8,true>: FETCH_SIZE 76166.7 KiB x 2.000 + WRITE_SIZE 101792.6 KiB x 1.000
-ROOFLINE_CONV_TRAFFIC_BYTES = 221.4e6   # igemm_kernel<0,128,256,...>: FETCH_SIZE 41159.5 KiB x 2.000 + WRITE_SIZE 133859.5 KiB x 1.000
+ROOFLINE_CONV_TRAFFIC_BYTES = 220.9e6   # igemm_kernel<0,128,256,...>: FETCH_SIZE 40945.3 KiB x 2.000 + WRITE_SIZE 133859.5 KiB x 1.000
 # Matrix-pipe busy share of that convolution kernel from hardware counters (SQ_VALU_MFMA_BUSY_CYCLES over
 # GRBM_GUI_ACTIVE x 1024 SIMDs, mean over its dispatches); None when the kernel changes.
 MFMA_COUNTER_SOURCE = "profiles/resnet50_bs256_step_mfma_counters.md"
-ROOFLINE_CONV_MFMA_BUSY = 0.217
+ROOFLINE_CONV_MFMA_BUSY = 0.231
 
 
 def roofline_of(flops, nbytes, ms, launches, kernel, traffic, event_overhead_us=None):
@@ -188,7 +188,7 @@ def transformer_head(args, B, synth, StepRunner, pack_flat, to_device, torch, de
                    "distillation": "mse_logits"},
         "loss": [float(v) for v in loss[:3]],
         "roofline": dict(roofline_of(lin["flops"], lin["bytes"], lin["ms"], lin["launches"],
-                                     "igemm_kernel<0,128,128,2,2,true,false,1,false> (vocabulary projection, fp32 logits)",
+                                     "igemm_kernel<0,128,128,2,2,true,0,1,false> (vocabulary projection, fp32 logits)",
                                      None), launches_per_step=lin["launches"] / psteps),
         "kernel_class_ms_per_step": {k: round(v["ms"] / psteps, 4) for k, v in prof.items()},
         "hbm_kernels": hbm,
@@ -451,7 +451,7 @@ def main():
     roofline["launches_per_step"] = bn["launches"] / psteps
     cw = prof["conv_fprop_wide"]
     roofline_conv = roofline_of(cw["flops"], cw["bytes"], cw["ms"], cw["launches"],
-                                "igemm_kernel<0,128,256,2,2,false,true,1,false,0,false> (bf16 implicit-GEMM conv fprop on "
+                                "igemm_kernel<0,128,256,2,2,false,1,1,false,0,false> (bf16 implicit-GEMM conv fprop on "
                                 "128x256 tiles, BatchNorm column sums in the epilogue)", ROOFLINE_CONV_TRAFFIC_BYTES if default_pair else None,
                                 ev_us)
     roofline_conv["launches_per_step"] = cw["launches"] / psteps
