@@ -98,6 +98,25 @@ def test_model_create_rejects_bad_arguments():
         assert B.lib.codistill_model_create(ctypes.byref(bad), B.CD_BF16, ctypes.byref(h)) == B.CD_ERR_INVALID_ARG, kw
 
 
+def test_every_environment_switch_is_documented_and_tested():
+    """The switches the sources read (getenv) are the ones the header lists, and each has a test that names it."""
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    read = set()
+    src = os.path.join(root, "paper_2010_02838_amd", "csrc")
+    for f in os.listdir(src):
+        read |= set(re.findall(r'getenv\("(CODISTILL_[A-Z_]+)"\)', open(os.path.join(src, f)).read()))
+    header = open(os.path.join(root, "include", "codistill.h")).read()
+    tests = "".join(open(os.path.join(root, "tests", f)).read() for f in os.listdir(os.path.join(root, "tests"))
+                    if f.startswith("test_gpu") and f.endswith(".py"))
+    assert read, "no switch found: the pattern no longer matches the sources"
+    for name in sorted(read):
+        assert name in header, name + " is read by the library but not listed in include/codistill.h"
+        assert '"%s"' % name in tests, name + " has no GPU test that sets it"
+    for name in set(re.findall(r"CODISTILL_[A-Z]+_[A-Z_]+", header)) - {"CODISTILL_H"}:
+        if name.startswith("CODISTILL_") and name not in read and not name.startswith("CODISTILL_H"):
+            assert False, name + " is listed in the header but read nowhere"
+
+
 def test_packed_sentences_arguments():
     """Packed batches of sentences (max_sentences > 0): bounds checked at creation, one batch element per call, the same
     parameters as the padded model, and a packing helper that loses nothing."""
