@@ -13,6 +13,7 @@
 // full 16-byte vectors along the channels.  The MFMA "A" operand is the filter tile and "B" the
 // activation tile, so that a lane's 16 accumulators run along the output channels of one pixel.
 #include "kernels.h"
+#include <algorithm>
 
 namespace cd {
 
@@ -743,9 +744,75 @@ __global__ void __launch_bounds__(256) fill_zero16_k(uint4* p, int64_t n) {
   if (i < n) p[i] = make_uint4(0, 0, 0, 0);
 }
 
+// ---- filter re-layouts of many data gradients in one launch ------------------------------------------------------
+constexpr int kLayoutJobs = 48;   // jobs per launch: the table travels in the kernel arguments
+struct LayoutBatch { WeightLayoutJob j[kLayoutJobs]; int n; int64_t total; };
+__global__ void __launch_bounds__(256) relayout_weights_k(LayoutBatch b) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= b.total) return;
+  int k = 0;
+  while (k + 1 < b.n && b.j[k + 1].first <= i) k++;
+  const WeightLayoutJob& q = b.j[k];
+  const int64_t e = i - q.first;
+  const int n = (int)(e % q.cout);
+  int64_t t = e / q.cout;
+  const int jw = (int)(t % q.tw); t /= q.tw;
+  const int jh = (int)(t % q.th);
+  const int c = (int)(t / q.th);
+  q.wt[e] = q.w[(((int64_t)n * q.kh + (q.r0 + q.rstep * jh)) * q.kw + (q.s0 + q.rstep * jw)) * q.cin + c];
+}
+void relayout_weights_batch(std::vector<WeightLayoutJob>& jobs, hipStream_t s) {
+  for (size_t j0 = 0; j0 < jobs.size(); j0 += kLayoutJobs) {
+    LayoutBatch b;
+    b.n = (int)std::min<size_t>(kLayoutJobs, jobs.size() - j0);
+    b.total = 0;
+    for (int k = 0; k < b.n; k++) {
+      WeightLayoutJob& q = jobs[j0 + k];
+      q.first = b.total;
+      b.j[k] = q;
+      b.total += (int64_t)q.cin * q.th * q.tw * q.cout;
+    }
+    if (b.total > 0)
+      hipLaunchKernelGGL(relayout_weights_k, dim3((unsigned)cdiv(b.total, 256)), dim3(256), 0, s, b);
+  }
+}
+// The parity classes of a stride-2 data gradient (see conv_dgrad_mfma): calls f(ph, pw, th, tw, tminh, tminw) for every
+// class that has taps and pixels.
+template <typename F>
+static void for_each_parity_class(const ConvGeom& g, F f) {
+  for (int ph = 0; ph < 2; ph++)
+    for (int pw = 0; pw < 2; pw++) {
+      const int loh = ph + g.pad - g.kh + 1, low = pw + g.pad - g.kw + 1;
+      const int tminh = loh <= 0 ? -((-loh) >> 1) : (loh + 1) >> 1, tmaxh = (ph + g.pad) >> 1;
+      const int tminw = low <= 0 ? -((-low) >> 1) : (low + 1) >> 1, tmaxw = (pw + g.pad) >> 1;
+      const int th = tmaxh - tminh + 1, tw = tmaxw - tminw + 1;
+      const int hd = (g.H - ph + 1) / 2, wd = (g.W - pw + 1) / 2;
+      if (th <= 0 || tw <= 0 || hd <= 0 || wd <= 0) continue;
+      f(ph, pw, th, tw, tminh, tminw);
+    }
+}
+int64_t conv_dgrad_layout_elems(const ConvGeom& g) {
+  if (g.stride == 1) return (int64_t)g.Cout * g.K();
+  int64_t n = 0;
+  for_each_parity_class(g, [&](int, int, int th, int tw, int, int) { n += ((int64_t)g.Cin * th * tw * g.Cout + 7) / 8 * 8; });
+  return n;
+}
+void conv_dgrad_layout_jobs(const bf16_t* w, bf16_t* wt, const ConvGeom& g, std::vector<WeightLayoutJob>& jobs) {
+  if (g.stride == 1) {   // wt[Cin][kh][kw][Cout] = w[Cout][kh][kw][Cin]
+    jobs.push_back(WeightLayoutJob{w, wt, g.Cout, g.kh, g.kw, g.Cin, g.kh, g.kw, 0, 0, 1, 0});
+    return;
+  }
+  int64_t woff = 0;
+  for_each_parity_class(g, [&](int ph, int pw, int th, int tw, int tminh, int tminw) {
+    jobs.push_back(WeightLayoutJob{w, wt + woff, g.Cout, g.kh, g.kw, g.Cin, th, tw, ph + g.pad - 2 * tminh, pw + g.pad - 2 * tminw,
+                                   -2, 0});
+    woff += ((int64_t)g.Cin * th * tw * g.Cout + 7) / 8 * 8;
+  });
+}
+
 int conv_dgrad_mfma(const bf16_t* dy, const bf16_t* w, bf16_t* wt, bf16_t* dx, const ConvGeom& g, bool accumulate,
                     hipStream_t s, const bf16_t* addend, const uint8_t* addend_gate, const bf16_t* relu_out,
-                    const BnBackwardSums* bn) {
+                    const BnBackwardSums* bn, bool wt_ready) {
   IgemmArgs a;
   a.bias = nullptr;
   a.stat_partials = nullptr;
@@ -756,7 +823,7 @@ int conv_dgrad_mfma(const bf16_t* dy, const bf16_t* w, bf16_t* wt, bf16_t* dx, c
   a.src_bytes = (uint32_t)(g.M() * (int64_t)g.Cout * 2);
   a.Ho = g.H; a.Wo = g.W;
   if (g.stride == 1) {
-    transpose_weight(w, wt, g.Cout, g.kh * g.kw, g.Cin, s);
+    if (!wt_ready) transpose_weight(w, wt, g.Cout, g.kh * g.kw, g.Cin, s);
     a.wt = wt;
     a.M = g.B * g.H * g.W; a.K = g.kh * g.kw * g.Cout;
     a.Hd = g.H; a.Wd = g.W;
@@ -799,8 +866,9 @@ int conv_dgrad_mfma(const bf16_t* dy, const bf16_t* w, bf16_t* wt, bf16_t* dx, c
       if (th <= 0 || tw <= 0 || hd <= 0 || wd <= 0) continue;
       bf16_t* wc = wt + woff;
       const int64_t wn = (int64_t)g.Cin * th * tw * g.Cout;
-      hipLaunchKernelGGL(gather_weight_class_k, dim3((unsigned)cdiv(wn, 256)), dim3(256), 0, s, w, wc, g.Cout, g.kh,
-                         g.kw, g.Cin, th, tw, ph + g.pad - 2 * tminh, pw + g.pad - 2 * tminw);
+      if (!wt_ready)
+        hipLaunchKernelGGL(gather_weight_class_k, dim3((unsigned)cdiv(wn, 256)), dim3(256), 0, s, w, wc, g.Cout, g.kh,
+                           g.kw, g.Cin, th, tw, ph + g.pad - 2 * tminh, pw + g.pad - 2 * tminw);
       woff += (wn + 7) / 8 * 8;
       a.wt = wc;
       a.M = g.B * hd * wd; a.K = th * tw * g.Cout;

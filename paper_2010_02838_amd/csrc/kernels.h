@@ -3,6 +3,7 @@
 // are always fp32.  Nothing here allocates or synchronises.
 #pragma once
 #include "common.h"
+#include <vector>
 
 namespace cd {
 
@@ -123,9 +124,20 @@ int conv_fprop_tile_class(const ConvGeom& g, bool bias);
 // column sums of dz = dx gated by the mask and of dz * xhat in bn->partials, for bn_backward's pre_chunks.  Returns the
 // number of row tiles (the chunks of those sums), 0 without bn.
 struct BnBackwardSums { const bf16_t* x; const uint8_t* mask; const float* stats; float* partials; };
+// wt_ready: wt already holds the re-laid-out filter (conv_dgrad_layout_jobs + relayout_weights_batch): the launch's own
+// re-layout kernels are left out.
 int conv_dgrad_mfma(const bf16_t* dy, const bf16_t* w, bf16_t* wt, bf16_t* dx, const ConvGeom& g, bool accumulate,
                     hipStream_t s, const bf16_t* addend = nullptr, const uint8_t* addend_gate = nullptr,
-                    const bf16_t* relu_out = nullptr, const BnBackwardSums* bn = nullptr);
+                    const bf16_t* relu_out = nullptr, const BnBackwardSums* bn = nullptr, bool wt_ready = false);
+// The filter re-layouts of many data gradients in one launch (a backward pass needs one per convolution, each a few
+// microseconds of work behind a launch of its own otherwise).  A job writes wt[c][jh][jw][n] = w[n][r0 + rstep jh][s0 + rstep jw][c]
+// for c < cin, jh < th, jw < tw, n < cout; first = the number of elements of the jobs in front of it.
+struct WeightLayoutJob { const bf16_t* w; bf16_t* wt; int cout, kh, kw, cin, th, tw, r0, s0, rstep; int64_t first; };
+// appends the jobs that conv_dgrad_mfma's own re-layout of this convolution consists of (same places inside wt)
+void conv_dgrad_layout_jobs(const bf16_t* w, bf16_t* wt, const ConvGeom& g, std::vector<WeightLayoutJob>& jobs);
+// elements of wt that conv_dgrad_mfma uses for this convolution
+int64_t conv_dgrad_layout_elems(const ConvGeom& g);
+void relayout_weights_batch(std::vector<WeightLayoutJob>& jobs, hipStream_t s);   // sets every job's `first`
 // dw[Cout][K] = dy[M][Cout]^T * im2col(x)[M][K], split over M with fp32 partials reduced in fixed order
 void conv_wgrad_mfma(const bf16_t* x, const bf16_t* dy, float* dw, const ConvGeom& g, float* partials,
                      size_t partials_bytes, hipStream_t s);

@@ -67,6 +67,8 @@ struct Plan {
   size_t gtmp_bytes = 0;
   size_t gw = 0;              // the dense per-slice filters of the op at hand
   size_t gdw = 0;             // save only: the dense per-slice filter gradients of the op at hand (fp32)
+  std::vector<size_t> wt_op;  // per op (save only): where the backward pass keeps the convolution's filter as its data gradient
+                              // reads it (all of them are re-laid-out by one launch at the start of the pass); 0 = none
   size_t seq_tab = 0;         // packed Transformer batches: the sentence tables of the source and of the target stream,
                               // max_sentences + 2 int32 each (kernels.h, sentence_tables)
   size_t total = 0;

@@ -476,6 +476,15 @@ Plan make_plan(const cd_model* m, int64_t B, bool save) {
       if (save) p.gdw = alloc(wdmax * 4);
     }
   }
+  p.wt_op.assign(m->ops.size(), 0);
+  if (save && m->dtype == CD_BF16) {
+    for (size_t i = (size_t)m->first_trainable_op; i < m->ops.size(); i++) {
+      const Op& o = m->ops[i];
+      if (o.kind != OP_CONV || o.groups > 1 || o.x == 0) continue;
+      const ConvGeom g = conv_geom(m, o, B);
+      if (use_mfma(m, g)) p.wt_op[i] = alloc((size_t)(conv_dgrad_layout_elems(g) + 32) * 2);
+    }
+  }
   if (save) {
     p.partials_side = alloc(p.partials_bytes);
     for (int t = 1; t < nt; t++)
@@ -1032,6 +1041,20 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
     if (side && !side_event(convs)) side = nullptr;
     if (!side) side_lock.unlock();
   }
+  {   // the filters of all matrix-core data gradients, in the layouts those read them, by one launch (per 48 filters)
+    std::vector<WeightLayoutJob> jobs;
+    double bytes = 0;
+    for (size_t i = (size_t)m->first_trainable_op; i < m->ops.size(); i++)
+      if (c.plan.wt_op[i]) {
+        const ConvGeom g = conv_geom(m, m->ops[i], batch);
+        conv_dgrad_layout_jobs(static_cast<const bf16_t*>(c.P(m->ops[i].pw)), reinterpret_cast<bf16_t*>(c.ws + c.plan.wt_op[i]), g, jobs);
+        bytes += 4.0 * g.Cout * g.K();
+      }
+    if (!jobs.empty()) {
+      ProfScope pr(CD_K_GLUE, c.s, 0, bytes);
+      relayout_weights_batch(jobs, c.s);
+    }
+  }
   int forks = 0;
   int late_rc = CD_OK;   // a launch-time failure of the fork / join machinery: reported after the join was attempted
   std::vector<char> written(m->tensors.size(), 0);
@@ -1304,10 +1327,12 @@ extern "C" int codistill_backward(const cd_model* m, const void* params, const v
               sums.partials = c.partials();
               with_sums = true;
             }
-            const int chunks = conv_dgrad_mfma(static_cast<const bf16_t*>(dy), static_cast<const bf16_t*>(c.P(o.pw)), c.wpack(),
+            const bool ready = c.plan.wt_op[i] != 0;   // re-laid-out at the start of the pass
+            const int chunks = conv_dgrad_mfma(static_cast<const bf16_t*>(dy), static_cast<const bf16_t*>(c.P(o.pw)),
+                                               ready ? reinterpret_cast<bf16_t*>(c.ws + c.plan.wt_op[i]) : c.wpack(),
                                                static_cast<bf16_t*>(dx), g, acc, c.s, static_cast<const bf16_t*>(df.src), df.gate,
                                                gate ? static_cast<const bf16_t*>(c.act(o.x)) : nullptr,
-                                               with_sums ? &sums : nullptr);
+                                               with_sums ? &sums : nullptr, ready);
             if (with_sums) bn_sums[o.x] = chunks;
             if (gate) relu_done[o.x] = 1;
           } else {
