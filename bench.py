@@ -35,7 +35,7 @@ PEAK_HBM_GBS = 8000.0
 # --copy-calibration).  Valid only for the kernels the counters were taken on: set to None when one changes.
 TRAFFIC_SOURCE = "profiles/resnet50_bs256_step_hbm_counters.md"
 ROOFLINE_TRAFFIC_BYTES = 260.2e6        # bn_apply_k<bf16,8,true>: FETCH_SIZE 76166.7 KiB x 2.000 + WRITE_SIZE 101792.6 KiB x 1.000
-ROOFLINE_CONV_TRAFFIC_BYTES = 220.9e6   # igemm_kernel<0,128,256,...>: FETCH_SIZE 40945.3 KiB x 2.000 + WRITE_SIZE 133859.5 KiB x 1.000
+ROOFLINE_CONV_TRAFFIC_BYTES = 221.0e6   # igemm_kernel<0,128,256,...>: FETCH_SIZE 40974.9 KiB x 2.000 + WRITE_SIZE 133859.5 KiB x 1.000
 # Matrix-pipe busy share of that convolution kernel from hardware counters (SQ_VALU_MFMA_BUSY_CYCLES over
 # GRBM_GUI_ACTIVE x 1024 SIMDs, mean over its dispatches); None when the kernel changes.
 MFMA_COUNTER_SOURCE = "profiles/resnet50_bs256_step_mfma_counters.md"
